@@ -1,0 +1,150 @@
+"""ctypes front end of the CPU checker in ``dl_oracle.c``.
+
+TEST INFRASTRUCTURE: used by the tests, the smoke check and the benchmark's
+CPU-baseline leg only.  Nothing here touches the GPU or the HIP library.
+
+All buffers are ``numpy.uint8`` arrays.  The functions marshal pointers and
+sizes; every byte is moved by the C code.
+"""
+
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+SRC = os.path.join(_HERE, "dl_oracle.c")
+LIB = os.path.join(_HERE, "libdl_oracle.so")
+
+
+class RefCopy(ctypes.Structure):
+    _fields_ = [("src", ctypes.c_void_p), ("dst", ctypes.c_void_p), ("bytes", ctypes.c_size_t)]
+
+
+def build(src: str = SRC, out: str = LIB, force: bool = False) -> str:
+    """Compile the checker with gcc (plain C, no GPU toolchain)."""
+    if force or not os.path.exists(out) or os.path.getmtime(out) < os.path.getmtime(src):
+        subprocess.run(["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-fPIC", "-shared", src, "-o", out],
+                       check=True)
+    return out
+
+
+def load(path: str | None = None) -> ctypes.CDLL:
+    lib = ctypes.CDLL(path or build())
+    VPP = ctypes.POINTER(ctypes.c_void_p)
+    lib.ref_first_hazard.restype = ctypes.c_long
+    lib.ref_first_hazard.argtypes = [ctypes.POINTER(RefCopy), ctypes.c_size_t]
+    lib.ref_batch_copy.restype = ctypes.c_int
+    lib.ref_batch_copy.argtypes = [ctypes.POINTER(RefCopy), ctypes.c_size_t]
+    lib.ref_broadcast.restype = ctypes.c_int
+    lib.ref_broadcast.argtypes = [ctypes.c_void_p, VPP, ctypes.c_int, ctypes.c_size_t]
+    lib.ref_allgather.restype = ctypes.c_int
+    lib.ref_allgather.argtypes = [VPP, VPP, ctypes.c_int, ctypes.c_size_t]
+    lib.ref_alltoall.restype = ctypes.c_int
+    lib.ref_alltoall.argtypes = [VPP, VPP, ctypes.c_int, ctypes.POINTER(ctypes.c_size_t)]
+    return lib
+
+
+_lib = None
+
+
+def _get():
+    global _lib
+    if _lib is None:
+        _lib = load()
+    return _lib
+
+
+def _check_buf(a: np.ndarray) -> np.ndarray:
+    if a.dtype != np.uint8 or not a.flags["C_CONTIGUOUS"]:
+        raise TypeError("buffers must be contiguous uint8 arrays")
+    return a
+
+
+def _ptrs(arrs):
+    return (ctypes.c_void_p * len(arrs))(*[a.ctypes.data if a.size else None for a in arrs])
+
+
+def allgather(ins, lib=None):
+    """W send buffers of equal size B -> W receive buffers of W*B bytes."""
+    lib = lib or _get()
+    ins = [_check_buf(a) for a in ins]
+    W = len(ins)
+    B = ins[0].size
+    if any(a.size != B for a in ins):
+        raise ValueError("all-gather needs equal per-rank sizes")
+    outs = [np.zeros(W * B, dtype=np.uint8) for _ in range(W)]
+    rc = lib.ref_allgather(_ptrs(ins), _ptrs(outs), W, B)
+    if rc:
+        raise RuntimeError(f"ref_allgather failed: {rc}")
+    return outs
+
+
+def alltoall(ins, C, lib=None):
+    """ins[i] has sum_j C[i][j] bytes; returns outs[j] with sum_i C[i][j] bytes."""
+    lib = lib or _get()
+    ins = [_check_buf(a) for a in ins]
+    W = len(ins)
+    C = np.ascontiguousarray(np.asarray(C, dtype=np.uint64))
+    if C.shape != (W, W):
+        raise ValueError("chunk matrix must be W x W")
+    for i in range(W):
+        if ins[i].size != int(C[i].sum()):
+            raise ValueError("send buffer size does not match its row of the chunk matrix")
+    outs = [np.zeros(int(C[:, j].sum()), dtype=np.uint8) for j in range(W)]
+    Cc = C.astype(np.uintp)
+    rc = lib.ref_alltoall(_ptrs(ins), _ptrs(outs), W, Cc.ctypes.data_as(ctypes.POINTER(ctypes.c_size_t)))
+    if rc:
+        raise RuntimeError(f"ref_alltoall failed: {rc}")
+    return outs
+
+
+def broadcast(src, k, lib=None):
+    """k fresh destination buffers, each receiving ``src``."""
+    lib = lib or _get()
+    src = _check_buf(src)
+    dsts = [np.zeros(src.size, dtype=np.uint8) for _ in range(k)]
+    rc = lib.ref_broadcast(src.ctypes.data if src.size else None, _ptrs(dsts), k, src.size)
+    if rc:
+        raise RuntimeError(f"ref_broadcast failed: {rc}")
+    return dsts
+
+
+def _descs(buffers, descs):
+    arr = (RefCopy * max(len(descs), 1))()
+    for n, (sb, so, db, do, nb) in enumerate(descs):
+        sbuf, dbuf = _check_buf(buffers[sb]), _check_buf(buffers[db])
+        so, do, nb = int(so), int(do), int(nb)
+        if so + nb > sbuf.size or do + nb > dbuf.size:
+            raise ValueError("descriptor outside its buffer")
+        arr[n].src = sbuf.ctypes.data + so
+        arr[n].dst = dbuf.ctypes.data + do
+        arr[n].bytes = nb
+    return arr
+
+
+def batch_copy(buffers, descs, lib=None):
+    """Run a hazard-free batch in place on ``buffers``.
+
+    descs: iterable of (src_buffer_index, src_offset, dst_buffer_index,
+    dst_offset, bytes).  Raises ValueError if the batch has a hazard.
+    """
+    lib = lib or _get()
+    descs = list(descs)
+    arr = _descs(buffers, descs)
+    rc = lib.ref_batch_copy(arr, len(descs))
+    if rc == -2:
+        raise ValueError("batch has a data-dependence hazard")
+    if rc:
+        raise RuntimeError(f"ref_batch_copy failed: {rc}")
+    return buffers
+
+
+def first_hazard(buffers, descs, lib=None) -> int:
+    """Index of the first copy whose destination collides, or -1."""
+    lib = lib or _get()
+    descs = list(descs)
+    return int(lib.ref_first_hazard(_descs(buffers, descs), len(descs)))

@@ -1,0 +1,246 @@
+"""Pins of the CPU checker to things other than itself.
+
+Each pin is independent of ``oracle/dl_oracle.c``:
+  * per-byte index formulas evaluated by pure-Python loops (brute force),
+  * reductions to numpy library routines (tile/concatenate, reshape+transpose,
+    broadcast_to),
+  * the invariants of the collectives (identical all-gather outputs,
+    all-to-all twice with the transposed chunk matrix is the identity,
+    broadcast destinations equal the source, byte-multiset conservation),
+  * W = 1, where every operation is a plain copy,
+  * the hazard rule of back-to-back copies (Sec. IV-D) on hand-built cases.
+The paper prints no worked numeric example for these operations, so there is
+no golden fixture of printed values; tests/golden holds only the copy counts
+the paper states.
+"""
+
+import itertools
+
+import numpy as np
+import pytest
+
+from paper_2511_06605_amd import inputs
+
+SIZES = [0, 1, 2, 15, 16, 17, 255, 256, 4097]
+WS = [1, 2, 3, 5, 8]
+
+
+# ---------------------------------------------------------------- brute force
+
+def brute_allgather(ins):
+    W, B = len(ins), len(ins[0])
+    outs = []
+    for r in range(W):
+        o = bytearray(W * B)
+        for p in range(W * B):
+            o[p] = ins[p // B][p % B]
+        outs.append(np.frombuffer(bytes(o), dtype=np.uint8))
+    return outs
+
+
+def brute_alltoall(ins, C):
+    """For each receiver j walk its buffer byte by byte; find which sender's
+    chunk the byte falls in by scanning column j; locate it in the sender's
+    buffer by scanning row i.  No prefix arrays."""
+    W = len(ins)
+    outs = []
+    for j in range(W):
+        total = sum(int(C[i][j]) for i in range(W))
+        o = bytearray(total)
+        for p in range(total):
+            i, q = 0, p
+            while q >= int(C[i][j]):
+                q -= int(C[i][j])
+                i += 1
+            s = q
+            for jj in range(j):
+                s += int(C[i][jj])
+            o[p] = ins[i][s]
+        outs.append(np.frombuffer(bytes(o), dtype=np.uint8))
+    return outs
+
+
+@pytest.mark.parametrize("W", WS)
+@pytest.mark.parametrize("B", [0, 1, 2, 15, 16, 17, 255, 256])
+def test_allgather_bruteforce(ref, W, B):
+    ins = inputs.allgather_inputs(W, B, seed=W * 1000 + B)
+    got = ref.allgather(ins)
+    want = brute_allgather(ins)
+    for r in range(W):
+        assert got[r].tobytes() == want[r].tobytes()
+
+
+@pytest.mark.parametrize("W", WS)
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_alltoall_bruteforce_nonsymmetric(ref, W, seed):
+    C = inputs.random_chunks(W, 300, seed=seed * 17 + W, zero_frac=0.25)
+    if W > 1:
+        assert not np.array_equal(C, C.T)  # a symmetric C cannot tell i from j
+    ins = inputs.alltoall_inputs(C, seed=seed)
+    got = ref.alltoall(ins, C)
+    want = brute_alltoall(ins, C)
+    for j in range(W):
+        assert got[j].tobytes() == want[j].tobytes()
+
+
+@pytest.mark.parametrize("W", [2, 3, 8])
+@pytest.mark.parametrize("c", [1, 15, 16, 17, 256])
+def test_alltoall_bruteforce_uniform(ref, W, c):
+    C = inputs.uniform_chunks(W, c)
+    ins = inputs.alltoall_inputs(C, seed=c)
+    got = ref.alltoall(ins, C)
+    want = brute_alltoall(ins, C)
+    for j in range(W):
+        assert got[j].tobytes() == want[j].tobytes()
+
+
+# ------------------------------------------------- reductions to numpy routines
+
+@pytest.mark.parametrize("W", WS)
+@pytest.mark.parametrize("B", SIZES)
+def test_allgather_is_tile_of_concatenation(ref, W, B):
+    ins = inputs.allgather_inputs(W, B, seed=B + 7 * W, kind="bf16" if B % 2 == 0 else "u8")
+    got = ref.allgather(ins)
+    want = np.tile(np.concatenate(ins), (W, 1))
+    assert np.array_equal(np.stack(got), want)
+
+
+@pytest.mark.parametrize("W", WS)
+@pytest.mark.parametrize("c", SIZES)
+def test_uniform_alltoall_is_transpose(ref, W, c):
+    C = inputs.uniform_chunks(W, c)
+    ins = inputs.alltoall_inputs(C, seed=c + W, kind="fp16" if c % 2 == 0 else "u8")
+    got = ref.alltoall(ins, C)
+    x = np.stack(ins).reshape(W, W, c)           # [sender i][chunk j][t]
+    want = x.transpose(1, 0, 2).reshape(W, W * c)  # [receiver j][chunk i][t]
+    assert np.array_equal(np.stack(got), want)
+
+
+@pytest.mark.parametrize("k", [1, 2, 7, 8, 13])
+@pytest.mark.parametrize("n", SIZES)
+def test_broadcast_is_broadcast_to(ref, k, n):
+    src = inputs.payload(np.random.default_rng(n * 31 + k), n)
+    got = ref.broadcast(src, k)
+    assert np.array_equal(np.stack(got), np.broadcast_to(src, (k, n)))
+
+
+@pytest.mark.parametrize("n", SIZES)
+def test_W1_everything_is_a_plain_copy(ref, n):
+    x = inputs.payload(np.random.default_rng(n), n)
+    assert ref.allgather([x])[0].tobytes() == x.tobytes()
+    assert ref.alltoall([x], np.array([[n]]))[0].tobytes() == x.tobytes()
+    assert ref.broadcast(x, 1)[0].tobytes() == x.tobytes()
+    bufs = [x.copy(), np.zeros(n, dtype=np.uint8)]
+    ref.batch_copy(bufs, [(0, 0, 1, 0, n)])
+    assert bufs[1].tobytes() == x.tobytes()
+
+
+# ------------------------------------------------------------------ invariants
+
+@pytest.mark.parametrize("W,B", [(8, 64 * 1024), (8, 4096), (5, 12345), (3, 1)])
+def test_allgather_invariants(ref, W, B):
+    ins = inputs.allgather_inputs(W, B, seed=0)
+    outs = ref.allgather(ins)
+    for r in range(1, W):
+        assert np.array_equal(outs[r], outs[0])
+    assert outs[0].tobytes() == b"".join(a.tobytes() for a in ins)
+    # conservation: every input byte value appears W times as often in the outputs
+    hin = np.bincount(np.concatenate(ins), minlength=256)
+    hout = np.bincount(np.concatenate(outs), minlength=256)
+    assert np.array_equal(hout, W * hin)
+
+
+@pytest.mark.parametrize("W", [2, 3, 8])
+@pytest.mark.parametrize("seed", [3, 4])
+def test_alltoall_twice_with_transposed_chunks_is_identity(ref, W, seed):
+    C = inputs.random_chunks(W, 5000, seed=seed, zero_frac=0.2)
+    assert not np.array_equal(C, C.T)
+    ins = inputs.alltoall_inputs(C, seed=seed + 100)
+    mid = ref.alltoall(ins, C)
+    back = ref.alltoall(mid, C.T)
+    for i in range(W):
+        assert back[i].tobytes() == ins[i].tobytes()
+    hin = np.bincount(np.concatenate(ins), minlength=256)
+    hmid = np.bincount(np.concatenate(mid), minlength=256)
+    assert np.array_equal(hin, hmid)
+
+
+def test_alltoall_moe_shape_matches_index_formula(ref):
+    """MoE-dispatch chunk sizes (whole token rows, some zero chunks): check
+    sampled output bytes against the closed-form source location."""
+    W = 8
+    C = inputs.moe_dispatch_chunks(W, tokens_per_rank=16, seed=5, hidden=64)
+    assert (C % 128 == 0).all() and int(C.sum()) == W * 8 * 16 * 128
+    ins = inputs.alltoall_inputs(C, seed=6, kind="bf16")
+    outs = ref.alltoall(ins, C)
+    rng = np.random.default_rng(0)
+    for _ in range(2000):
+        i, j = int(rng.integers(W)), int(rng.integers(W))
+        if C[i, j] == 0:
+            continue
+        t = int(rng.integers(int(C[i, j])))
+        assert outs[j][int(C[:i, j].sum()) + t] == ins[i][int(C[i, :j].sum()) + t]
+
+
+def test_broadcast_destinations_equal_source(ref):
+    src = inputs.payload(np.random.default_rng(1), 2 * 1024 * 1024, "bf16")
+    for d in ref.broadcast(src, 7):
+        assert np.array_equal(d, src)
+
+
+# ------------------------------------------------------------- batched copies
+
+def test_batch_copy_matches_slice_assignment(ref):
+    arena, descs = inputs.b2b_batch(64, 16 * 1024, 4 * 1024 * 1024, seed=2)
+    want = arena.copy()
+    before = arena.copy()
+    for s, d, n in descs.astype(np.int64):
+        want[d:d + n] = before[s:s + n]
+    got = ref.batch_copy([arena], [(0, s, 0, d, n) for s, d, n in descs])[0]
+    assert np.array_equal(got, want)
+    # bytes outside every destination are untouched
+    mask = np.ones(arena.size, dtype=bool)
+    for _, d, n in descs.astype(np.int64):
+        mask[d:d + n] = False
+    assert np.array_equal(got[mask], before[mask])
+
+
+@pytest.mark.parametrize("perm_seed", [0, 1, 2])
+def test_batch_copy_order_does_not_matter(ref, perm_seed):
+    arena, descs = inputs.b2b_batch(32, 1000, 256 * 1024, seed=9, align=8)
+    a = ref.batch_copy([arena.copy()], [(0, s, 0, d, n) for s, d, n in descs])[0]
+    p = np.random.default_rng(perm_seed).permutation(len(descs))
+    b = ref.batch_copy([arena.copy()], [(0, s, 0, d, n) for s, d, n in descs[p]])[0]
+    assert np.array_equal(a, b)
+
+
+def test_hazard_rule(ref):
+    buf = np.arange(256, dtype=np.uint8)
+    ok = [(0, 0, 0, 100, 50), (0, 10, 0, 160, 40)]            # overlapping sources are fine
+    assert ref.first_hazard([buf], ok) == -1
+    assert ref.first_hazard([buf], [(0, 0, 0, 100, 50), (0, 60, 0, 149, 10)]) == 0   # dst-dst, 1 byte
+    assert ref.first_hazard([buf], [(0, 0, 0, 100, 50), (0, 60, 0, 150, 10)]) == -1  # touching, disjoint
+    assert ref.first_hazard([buf], [(0, 0, 0, 100, 50), (0, 120, 0, 200, 10)]) == 0  # dst of 0 hits src of 1
+    assert ref.first_hazard([buf], [(0, 0, 0, 10, 50)]) == 0                         # src-dst of one copy
+    assert ref.first_hazard([buf], [(0, 5, 0, 5, 50)]) == -1                         # identical range: no-op
+    assert ref.first_hazard([buf], [(0, 0, 0, 100, 0), (0, 0, 0, 100, 10)]) == -1    # empty copies never collide
+    with pytest.raises(ValueError):
+        ref.batch_copy([buf.copy()], [(0, 0, 0, 100, 50), (0, 60, 0, 149, 10)])
+    same = buf.copy()
+    ref.batch_copy([same], [(0, 5, 0, 5, 50)])
+    assert np.array_equal(same, buf)
+
+
+def test_generated_batches_are_hazard_free(ref):
+    for seed in range(5):
+        arena, descs = inputs.b2b_batch(64, 16 * 1024, 8 * 1024 * 1024, seed=seed)
+        d = [(0, s, 0, t, n) for s, t, n in descs]
+        assert ref.first_hazard([arena], d) == -1
+        # and every pair is checked independently of the C validator
+        iv = [(int(t), int(t + n)) for _, t, n in descs]
+        sv = [(int(s), int(s + n)) for s, _, n in descs]
+        for (a0, a1), (b0, b1) in itertools.combinations(iv, 2):
+            assert a1 <= b0 or b1 <= a0
+        for (a0, a1) in iv:
+            for (b0, b1) in sv:
+                assert a1 <= b0 or b1 <= a0
