@@ -1,0 +1,203 @@
+/*
+ * dmalatte.h - C boundary of the MI355X copy-collective library.
+ *
+ * The library executes the data movement behind DMA-offloaded collectives
+ * (all-gather, all-to-all, broadcast, batched back-to-back copies) on the
+ * compute units of one GPU.  W "virtual ranks" are W send buffers and W receive
+ * buffers that all live in that GPU's memory.
+ *
+ * Conventions for every entry point
+ *  - Data pointers (src, dst, in[r], out[r], dsts[d]) are DEVICE pointers owned
+ *    by the caller.  The library never allocates, frees or keeps them.
+ *  - Pointer arrays, descriptor arrays and chunk_bytes are HOST arrays.  They
+ *    are fully consumed before the call returns.
+ *  - Any byte count and any alignment gives the result memcpy would give;
+ *    buffers whose addresses agree modulo 16 take the 16-byte vector path.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *  - Calls only enqueue work.  In one-shot mode the result is complete when
+ *    the stream reaches the end of the enqueued kernel.  In prelaunch mode the
+ *    request is handed to a resident kernel through a doorbell, `stream` is
+ *    not used, inputs must already be complete when the call is made, and
+ *    completion is observed with dl_wait() on the ticket of the call.
+ *  - Return value: DL_OK (0) or a negative dl_status.  No exceptions, no
+ *    aborts.  On DL_ERR_HIP, dl_last_hip_error() gives the hipError_t.
+ *  - Not thread-safe: one host thread drives the library at a time.
+ */
+#ifndef DMALATTE_H
+#define DMALATTE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum dl_status {
+    DL_OK = 0,
+    DL_ERR_INVALID = -1,  /* null pointer with non-zero bytes, W < 1, k < 1, k > DL_MAX_FANOUT, bad config */
+    DL_ERR_OVERLAP = -2,  /* a destination overlaps another destination or a source (validation on) */
+    DL_ERR_HIP = -3,      /* a HIP call failed; see dl_last_hip_error() */
+    DL_ERR_TIMEOUT = -4,  /* dl_wait() gave up, or the resident kernel did not come up or go down in time */
+    DL_ERR_STATE = -5     /* not initialised; prelaunch mode without a resident kernel; started twice */
+} dl_status;
+
+/* Largest number of destinations of one dl_broadcast call / ranks of a collective. */
+#define DL_MAX_FANOUT 64
+
+typedef enum dl_mode {
+    DL_MODE_ONESHOT = 0,   /* one kernel launch per call, ordered on `stream` */
+    DL_MODE_PRELAUNCH = 1  /* request handed to the resident doorbell-polling kernel */
+} dl_mode;
+
+/* One copy of a batch: `bytes` bytes from device pointer src to device pointer dst. */
+typedef struct dl_copy_desc {
+    const void *src;
+    void *dst;
+    size_t bytes;
+} dl_copy_desc;
+
+/* ------------------------------------------------------------------ lifecycle */
+
+/* Bind the library to HIP device `device` and create its staging ring.  Calling
+ * it again for the same device is a no-op; another device needs dl_shutdown()
+ * first (DL_ERR_STATE). */
+int dl_init(int device);
+
+/* Stop the resident kernel if one runs, release the staging memory. */
+int dl_shutdown(void);
+
+/* Select how the four operations are executed.  DL_MODE_PRELAUNCH requires a
+ * running resident kernel at call time (DL_ERR_STATE otherwise). */
+int dl_set_mode(int mode);
+int dl_get_mode(void);
+
+/* Validation of the hazard rule (see dl_batch_copy).  Off by default: it costs
+ * O(n log n) on the host.  on = 0 / 1. */
+int dl_set_validate(int on);
+
+const char *dl_strerror(int status);
+int dl_last_hip_error(void);
+
+/* ----------------------------------------------------------------- operations */
+
+/*
+ * Batched back-to-back copies (paper Sec. IV-D; the batched-copy runtime call
+ * of Sec. VI).  n independent copies, no ordering among them, one completion
+ * for the whole batch; all of them are packed into one grid.
+ * Precondition (hazard rule of Sec. IV-D): no destination range overlaps
+ * another destination range or any source range.  Sources may overlap each
+ * other.  A descriptor with src == dst is a no-op.  With validation on, a
+ * violated precondition returns DL_ERR_OVERLAP and nothing is enqueued; with
+ * validation off the result of such a batch is undefined.
+ * desc: host array of n descriptors.  n == 0 or all bytes == 0: DL_OK, no work.
+ */
+int dl_batch_copy(const dl_copy_desc *desc, size_t n, void *stream);
+
+/*
+ * Broadcast (paper Sec. IV-B, generalised from 2 to k destinations): every
+ * dsts[d][0..bytes) becomes src[0..bytes).  The source is read once per group
+ * of up to 8 destinations and written to each of them from registers.
+ * dsts: host array of k device pointers, 1 <= k <= DL_MAX_FANOUT, pairwise
+ * disjoint and disjoint from src.
+ */
+int dl_broadcast(const void *src, void *const *dsts, int k, size_t bytes, void *stream);
+
+/*
+ * All-gather over W virtual ranks (paper Sec. II-A1, Fig. 2 left):
+ *   out[r][j*B + t] = in[j][t]   for all r, j in [0,W), t in [0,B), B = bytes_per_rank.
+ * in, out: host arrays of W device pointers; in[j] has B bytes, out[r] has W*B.
+ * Lowered to W read-once/write-W copies.  The in-place layout of the paper is
+ * accepted: if in[j] == out[j] + j*B that self-copy is skipped.  Any other
+ * overlap between inputs and outputs is a hazard.
+ */
+int dl_allgather(const void *const *in, void *const *out, int W, size_t bytes_per_rank, void *stream);
+
+/*
+ * All-to-all over W virtual ranks (paper Sec. II-A1, Fig. 2 right: the ranks
+ * collectively transpose).  chunk_bytes is a host W x W row-major matrix,
+ * C[i][j] = chunk_bytes[i*W + j] = bytes rank i sends to rank j (zero allowed).
+ * in[i] is packed in destination order and out[j] in source order:
+ *   out[j][roff(i,j) + t] = in[i][soff(i,j) + t],  0 <= t < C[i][j],
+ *   soff(i,j) = sum of C[i][j'] for j' < j,  roff(i,j) = sum of C[i'][j] for i' < i.
+ * Out of place only.
+ */
+int dl_alltoall(const void *const *in, void *const *out, int W, const size_t *chunk_bytes, void *stream);
+
+/* ------------------------------------------------------------- prelaunch mode */
+
+/*
+ * Launch the resident kernel (the analogue of a pre-enqueued poll command,
+ * paper Sec. IV-E).  It occupies a fixed number of workgroups on a private
+ * non-blocking stream and spins on a doorbell word in host-coherent memory.
+ * While it runs, hipDeviceSynchronize() (and anything that implies it) blocks
+ * until dl_prelaunch_stop().  The kernel also leaves by itself after
+ * `idle_timeout_ms` without a doorbell (see dl_config); the next call in
+ * prelaunch mode then returns DL_ERR_STATE.
+ */
+int dl_prelaunch_start(void);
+int dl_prelaunch_stop(void);
+
+/* Ticket of the most recent request issued in prelaunch mode (0 = none yet). */
+uint64_t dl_last_ticket(void);
+
+/* Spin on the host until the request `ticket` and all earlier ones are complete.
+ * timeout_ns == 0 polls once.  DL_OK, DL_ERR_TIMEOUT, or DL_ERR_STATE if the
+ * resident kernel is gone and the ticket can no longer complete. */
+int dl_wait(uint64_t ticket, uint64_t timeout_ns);
+
+/* -------------------------------------------------------------------- tunables */
+
+typedef struct dl_config {
+    uint32_t tile_bytes;         /* bytes of one workgroup tile; 0 = choose from the request size; power of two >= 1024 */
+    uint32_t block_threads;      /* workgroup size of the one-shot kernel: 64, 128, 256, 512 or 1024; 0 = choose */
+    uint64_t nontemporal_min_bytes; /* requests moving at least this many bytes use streaming loads/stores */
+    uint32_t resident_blocks;    /* workgroups of the resident kernel; 0 = one per compute unit */
+    uint32_t idle_timeout_ms;    /* the resident kernel exits after this long without a doorbell */
+    uint32_t fuse_broadcast;     /* 1: all-gather reads each source once (W fused copies); 0: W*W plain copies */
+    uint32_t reserved;
+} dl_config;
+
+int dl_get_config(dl_config *cfg);
+int dl_set_config(const dl_config *cfg);
+
+/* -------------------------------------------------- lowering, for inspection */
+
+/* One lowered copy: read `bytes` at src once, write them to k destinations. */
+#define DL_PLAN_FANOUT 8
+typedef struct dl_plan_item {
+    const void *src;
+    size_t bytes;
+    uint32_t k;
+    uint32_t reserved;
+    void *dst[DL_PLAN_FANOUT];
+} dl_plan_item;
+
+/*
+ * Host-only: lower a collective to the list of copies the device executes
+ * (the analogue of building the command list, paper Sec. III-B2 "control").
+ * Pointers are treated as opaque addresses and never dereferenced, so these
+ * work without a GPU.  Writes at most `cap` items to `items` (may be NULL when
+ * cap == 0) and returns the number of items the request lowers to, or a
+ * negative dl_status.
+ */
+long dl_plan_allgather(const void *const *in, void *const *out, int W, size_t bytes_per_rank,
+                       int fuse_broadcast, dl_plan_item *items, size_t cap);
+long dl_plan_alltoall(const void *const *in, void *const *out, int W, const size_t *chunk_bytes,
+                      dl_plan_item *items, size_t cap);
+long dl_plan_broadcast(const void *src, void *const *dsts, int k, size_t bytes,
+                       dl_plan_item *items, size_t cap);
+long dl_plan_batch(const dl_copy_desc *desc, size_t n, dl_plan_item *items, size_t cap);
+
+/* Host-only: index of the first item whose destination overlaps another
+ * destination or any source (the hazard rule), or -1 if there is none. */
+long dl_plan_first_hazard(const dl_plan_item *items, size_t n);
+
+/* Host-only: number of workgroup tiles the item list is cut into for a given
+ * tile size (the grid of the one-shot launch). */
+uint64_t dl_plan_tiles(const dl_plan_item *items, size_t n, uint32_t tile_bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DMALATTE_H */

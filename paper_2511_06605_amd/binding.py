@@ -1,0 +1,311 @@
+"""ctypes binding of the C boundary in ``include/dmalatte.h``.
+
+Argument marshalling only: every byte is moved by the HIP kernels behind the
+``dl_*`` entry points.  There is no CPU fallback: if the built library is
+missing, loading fails with an error.
+
+Device buffers may be given as integer addresses or as objects with a
+``data_ptr()`` method (torch tensors); streams as ``None`` (default stream),
+integer handles, or objects with a ``cuda_stream`` attribute.
+"""
+
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdmalatte.so")
+
+DL_OK = 0
+DL_ERR_INVALID = -1
+DL_ERR_OVERLAP = -2
+DL_ERR_HIP = -3
+DL_ERR_TIMEOUT = -4
+DL_ERR_STATE = -5
+DL_MAX_FANOUT = 64
+DL_PLAN_FANOUT = 8
+DL_MODE_ONESHOT = 0
+DL_MODE_PRELAUNCH = 1
+
+# every symbol include/dmalatte.h declares
+EXPORTS = [
+    "dl_init", "dl_shutdown", "dl_set_mode", "dl_get_mode", "dl_set_validate", "dl_strerror",
+    "dl_last_hip_error", "dl_batch_copy", "dl_broadcast", "dl_allgather", "dl_alltoall",
+    "dl_prelaunch_start", "dl_prelaunch_stop", "dl_last_ticket", "dl_wait", "dl_get_config",
+    "dl_set_config", "dl_plan_allgather", "dl_plan_alltoall", "dl_plan_broadcast", "dl_plan_batch",
+    "dl_plan_first_hazard", "dl_plan_tiles",
+]
+
+
+class DlError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: {strerror(status)} (status {status}, hip error {last_hip_error()})")
+
+
+class CopyDesc(ctypes.Structure):
+    _fields_ = [("src", ctypes.c_void_p), ("dst", ctypes.c_void_p), ("bytes", ctypes.c_size_t)]
+
+
+class Config(ctypes.Structure):
+    _fields_ = [
+        ("tile_bytes", ctypes.c_uint32),
+        ("block_threads", ctypes.c_uint32),
+        ("nontemporal_min_bytes", ctypes.c_uint64),
+        ("resident_blocks", ctypes.c_uint32),
+        ("idle_timeout_ms", ctypes.c_uint32),
+        ("fuse_broadcast", ctypes.c_uint32),
+        ("reserved", ctypes.c_uint32),
+    ]
+
+
+class PlanItem(ctypes.Structure):
+    _fields_ = [
+        ("src", ctypes.c_void_p),
+        ("bytes", ctypes.c_size_t),
+        ("k", ctypes.c_uint32),
+        ("reserved", ctypes.c_uint32),
+        ("dst", ctypes.c_void_p * DL_PLAN_FANOUT),
+    ]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2511_06605_amd.build` "
+            "(there is no fallback path)")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, vpp = ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p)
+    szp = ctypes.POINTER(ctypes.c_size_t)
+    sig = {
+        "dl_init": (ctypes.c_int, [ctypes.c_int]),
+        "dl_shutdown": (ctypes.c_int, []),
+        "dl_set_mode": (ctypes.c_int, [ctypes.c_int]),
+        "dl_get_mode": (ctypes.c_int, []),
+        "dl_set_validate": (ctypes.c_int, [ctypes.c_int]),
+        "dl_strerror": (ctypes.c_char_p, [ctypes.c_int]),
+        "dl_last_hip_error": (ctypes.c_int, []),
+        "dl_batch_copy": (ctypes.c_int, [ctypes.POINTER(CopyDesc), ctypes.c_size_t, vp]),
+        "dl_broadcast": (ctypes.c_int, [vp, vpp, ctypes.c_int, ctypes.c_size_t, vp]),
+        "dl_allgather": (ctypes.c_int, [vpp, vpp, ctypes.c_int, ctypes.c_size_t, vp]),
+        "dl_alltoall": (ctypes.c_int, [vpp, vpp, ctypes.c_int, szp, vp]),
+        "dl_prelaunch_start": (ctypes.c_int, []),
+        "dl_prelaunch_stop": (ctypes.c_int, []),
+        "dl_last_ticket": (ctypes.c_uint64, []),
+        "dl_wait": (ctypes.c_int, [ctypes.c_uint64, ctypes.c_uint64]),
+        "dl_get_config": (ctypes.c_int, [ctypes.POINTER(Config)]),
+        "dl_set_config": (ctypes.c_int, [ctypes.POINTER(Config)]),
+        "dl_plan_allgather": (ctypes.c_long, [vpp, vpp, ctypes.c_int, ctypes.c_size_t, ctypes.c_int,
+                                              ctypes.POINTER(PlanItem), ctypes.c_size_t]),
+        "dl_plan_alltoall": (ctypes.c_long, [vpp, vpp, ctypes.c_int, szp, ctypes.POINTER(PlanItem), ctypes.c_size_t]),
+        "dl_plan_broadcast": (ctypes.c_long, [vp, vpp, ctypes.c_int, ctypes.c_size_t, ctypes.POINTER(PlanItem),
+                                              ctypes.c_size_t]),
+        "dl_plan_batch": (ctypes.c_long, [ctypes.POINTER(CopyDesc), ctypes.c_size_t, ctypes.POINTER(PlanItem),
+                                          ctypes.c_size_t]),
+        "dl_plan_first_hazard": (ctypes.c_long, [ctypes.POINTER(PlanItem), ctypes.c_size_t]),
+        "dl_plan_tiles": (ctypes.c_uint64, [ctypes.POINTER(PlanItem), ctypes.c_size_t, ctypes.c_uint32]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(L, name)
+        fn.restype = res
+        fn.argtypes = args
+    _lib = L
+    return L
+
+
+# ------------------------------------------------------------------ marshalling
+
+def _addr(x) -> int | None:
+    if x is None:
+        return None
+    if hasattr(x, "data_ptr"):
+        return int(x.data_ptr()) or None
+    return int(x) or None
+
+
+def _stream(s) -> int | None:
+    if s is None:
+        return None
+    if hasattr(s, "cuda_stream"):
+        return int(s.cuda_stream) or None
+    return int(s) or None
+
+
+def _ptr_array(xs):
+    return (ctypes.c_void_p * max(len(xs), 1))(*[_addr(x) for x in xs])
+
+
+def _chunk_array(chunk_bytes, W):
+    flat = [int(v) for row in chunk_bytes for v in (row if hasattr(row, "__len__") else [row])]
+    if len(flat) != W * W:
+        raise ValueError("chunk_bytes must have W*W entries")
+    return (ctypes.c_size_t * (W * W))(*flat)
+
+
+def _desc_array(descs):
+    arr = (CopyDesc * max(len(descs), 1))()
+    for i, (s, d, n) in enumerate(descs):
+        arr[i].src, arr[i].dst, arr[i].bytes = _addr(s), _addr(d), int(n)
+    return arr
+
+
+def _check(status: int, what: str) -> None:
+    if status != DL_OK:
+        raise DlError(status, what)
+
+
+# ------------------------------------------------------------------- lifecycle
+
+def strerror(status: int) -> str:
+    return lib().dl_strerror(status).decode()
+
+
+def last_hip_error() -> int:
+    return lib().dl_last_hip_error()
+
+
+def dl_init(device: int = 0) -> None:
+    _check(lib().dl_init(device), "dl_init")
+
+
+def dl_shutdown() -> None:
+    _check(lib().dl_shutdown(), "dl_shutdown")
+
+
+def dl_set_mode(mode: int) -> None:
+    _check(lib().dl_set_mode(mode), "dl_set_mode")
+
+
+def dl_get_mode() -> int:
+    return lib().dl_get_mode()
+
+
+def dl_set_validate(on: bool) -> None:
+    _check(lib().dl_set_validate(1 if on else 0), "dl_set_validate")
+
+
+def dl_get_config() -> Config:
+    c = Config()
+    _check(lib().dl_get_config(ctypes.byref(c)), "dl_get_config")
+    return c
+
+
+def dl_set_config(cfg: Config | None = None, **fields) -> None:
+    c = cfg or dl_get_config()
+    for k, v in fields.items():
+        if not hasattr(c, k):
+            raise AttributeError(k)
+        setattr(c, k, v)
+    _check(lib().dl_set_config(ctypes.byref(c)), "dl_set_config")
+
+
+# ------------------------------------------------------------------ operations
+
+def dl_batch_copy(descs, stream=None) -> None:
+    """descs: sequence of (src, dst, bytes)."""
+    descs = list(descs)
+    _check(lib().dl_batch_copy(_desc_array(descs), len(descs), _stream(stream)), "dl_batch_copy")
+
+
+def dl_broadcast(src, dsts, nbytes: int, stream=None) -> None:
+    dsts = list(dsts)
+    _check(lib().dl_broadcast(_addr(src), _ptr_array(dsts), len(dsts), int(nbytes), _stream(stream)), "dl_broadcast")
+
+
+def dl_allgather(ins, outs, bytes_per_rank: int, stream=None) -> None:
+    ins, outs = list(ins), list(outs)
+    if len(ins) != len(outs):
+        raise ValueError("need as many receive buffers as send buffers")
+    _check(lib().dl_allgather(_ptr_array(ins), _ptr_array(outs), len(ins), int(bytes_per_rank), _stream(stream)),
+           "dl_allgather")
+
+
+def dl_alltoall(ins, outs, chunk_bytes, stream=None) -> None:
+    ins, outs = list(ins), list(outs)
+    W = len(ins)
+    if len(outs) != W:
+        raise ValueError("need as many receive buffers as send buffers")
+    _check(lib().dl_alltoall(_ptr_array(ins), _ptr_array(outs), W, _chunk_array(chunk_bytes, W), _stream(stream)),
+           "dl_alltoall")
+
+
+# -------------------------------------------------------------------- prelaunch
+
+def dl_prelaunch_start() -> None:
+    _check(lib().dl_prelaunch_start(), "dl_prelaunch_start")
+
+
+def dl_prelaunch_stop() -> None:
+    _check(lib().dl_prelaunch_stop(), "dl_prelaunch_stop")
+
+
+def dl_last_ticket() -> int:
+    return int(lib().dl_last_ticket())
+
+
+def dl_wait(ticket: int | None = None, timeout_ns: int = 5_000_000_000) -> None:
+    t = dl_last_ticket() if ticket is None else ticket
+    _check(lib().dl_wait(t, timeout_ns), "dl_wait")
+
+
+# --------------------------------------------------------------------- lowering
+
+def _items_out(call):
+    n = call(None, 0)
+    if n < 0:
+        raise DlError(int(n), "dl_plan")
+    arr = (PlanItem * max(n, 1))()
+    m = call(arr, n)
+    assert m == n
+    return [dict(src=arr[i].src or 0, bytes=arr[i].bytes, k=arr[i].k,
+                 dst=[arr[i].dst[j] or 0 for j in range(arr[i].k)]) for i in range(n)]
+
+
+def dl_plan_allgather(ins, outs, bytes_per_rank: int, fuse_broadcast: bool = True):
+    ins, outs = list(ins), list(outs)
+    a, b = _ptr_array(ins), _ptr_array(outs)
+    return _items_out(lambda arr, cap: lib().dl_plan_allgather(a, b, len(ins), int(bytes_per_rank),
+                                                               1 if fuse_broadcast else 0, arr, cap))
+
+
+def dl_plan_alltoall(ins, outs, chunk_bytes):
+    ins, outs = list(ins), list(outs)
+    a, b, c = _ptr_array(ins), _ptr_array(outs), _chunk_array(chunk_bytes, len(ins))
+    return _items_out(lambda arr, cap: lib().dl_plan_alltoall(a, b, len(ins), c, arr, cap))
+
+
+def dl_plan_broadcast(src, dsts, nbytes: int):
+    dsts = list(dsts)
+    d = _ptr_array(dsts)
+    return _items_out(lambda arr, cap: lib().dl_plan_broadcast(_addr(src), d, len(dsts), int(nbytes), arr, cap))
+
+
+def dl_plan_batch(descs):
+    descs = list(descs)
+    d = _desc_array(descs)
+    return _items_out(lambda arr, cap: lib().dl_plan_batch(d, len(descs), arr, cap))
+
+
+def _items_in(items):
+    arr = (PlanItem * max(len(items), 1))()
+    for i, it in enumerate(items):
+        arr[i].src, arr[i].bytes, arr[i].k = it["src"] or None, it["bytes"], len(it["dst"])
+        for j, d in enumerate(it["dst"]):
+            arr[i].dst[j] = d or None
+    return arr
+
+
+def dl_plan_first_hazard(items) -> int:
+    return int(lib().dl_plan_first_hazard(_items_in(items), len(items)))
+
+
+def dl_plan_tiles(items, tile_bytes: int) -> int:
+    return int(lib().dl_plan_tiles(_items_in(items), len(items), tile_bytes))

@@ -1,0 +1,335 @@
+// The C boundary: argument checks, lowering of the collectives to copy lists
+// (the "control" phase of Sec. III-B2), the optional hazard check of Sec. IV-D,
+// and dispatch to the one-shot launcher or the resident kernel.
+#include "dl_internal.h"
+
+#include <string.h>
+
+#include <algorithm>
+#include <vector>
+
+dl_state g_dl;
+
+static_assert(sizeof(dl_plan_item) == sizeof(dl_fused_item), "public and device item must share a layout");
+static_assert(offsetof(dl_plan_item, dst) == offsetof(dl_fused_item, dst), "public and device item must share a layout");
+static_assert(DL_PLAN_FANOUT == DL_FAN, "public and device fan-out must agree");
+
+namespace {
+
+// Collects lowered items into caller storage, counting past its capacity.
+struct sink {
+    dl_plan_item *items;
+    size_t cap;
+    size_t n = 0;
+    void put(const void *src, size_t bytes, void *const *dst, uint32_t k)
+    {
+        if (n < cap) {
+            dl_plan_item &it = items[n];
+            it.src = src;
+            it.bytes = bytes;
+            it.k = k;
+            it.reserved = 0;
+            for (uint32_t j = 0; j < (uint32_t)DL_PLAN_FANOUT; ++j) it.dst[j] = j < k ? dst[j] : nullptr;
+        }
+        ++n;
+    }
+};
+
+// One source to many destinations, in groups of DL_PLAN_FANOUT.
+void put_fanout(sink &s, const void *src, size_t bytes, void *const *dst, size_t k)
+{
+    for (size_t g = 0; g < k; g += DL_PLAN_FANOUT)
+        s.put(src, bytes, dst + g, (uint32_t)std::min<size_t>(DL_PLAN_FANOUT, k - g));
+}
+
+long lower_allgather(const void *const *in, void *const *out, int W, size_t B, int fuse, sink &s)
+{
+    if (W < 1 || W > DL_MAX_FANOUT || !in || !out) return DL_ERR_INVALID;
+    if (B == 0) return 0;
+    for (int r = 0; r < W; ++r)
+        if (!in[r] || !out[r]) return DL_ERR_INVALID;
+    void *dst[DL_MAX_FANOUT];
+    for (int j = 0; j < W; ++j) {  // source rank j goes to slot j of every receive buffer
+        size_t k = 0;
+        for (int r = 0; r < W; ++r) {
+            void *d = (char *)out[r] + (size_t)j * B;
+            if (d == in[j]) continue;  // in-place layout: rank j's own slot already holds its data
+            dst[k++] = d;
+        }
+        if (fuse)
+            put_fanout(s, in[j], B, dst, k);
+        else
+            for (size_t q = 0; q < k; ++q) s.put(in[j], B, &dst[q], 1);
+    }
+    return (long)s.n;
+}
+
+long lower_alltoall(const void *const *in, void *const *out, int W, const size_t *C, sink &s)
+{
+    if (W < 1 || W > DL_MAX_FANOUT || !in || !out || !C) return DL_ERR_INVALID;
+    size_t recv_off[DL_MAX_FANOUT] = {0};  // running offset into each receive buffer
+    for (int i = 0; i < W; ++i) {
+        size_t send_off = 0;
+        for (int j = 0; j < W; ++j) {
+            const size_t c = C[(size_t)i * W + j];
+            if (c) {
+                if (!in[i] || !out[j]) return DL_ERR_INVALID;
+                void *d = (char *)out[j] + recv_off[j];
+                s.put((const char *)in[i] + send_off, c, &d, 1);
+            }
+            send_off += c;
+            recv_off[j] += c;
+        }
+    }
+    return (long)s.n;
+}
+
+long lower_broadcast(const void *src, void *const *dsts, int k, size_t bytes, sink &s)
+{
+    if (k < 1 || k > DL_MAX_FANOUT || !dsts) return DL_ERR_INVALID;
+    if (bytes == 0) return 0;
+    if (!src) return DL_ERR_INVALID;
+    for (int d = 0; d < k; ++d)
+        if (!dsts[d]) return DL_ERR_INVALID;
+    put_fanout(s, src, bytes, dsts, (size_t)k);
+    return (long)s.n;
+}
+
+long lower_batch(const dl_copy_desc *desc, size_t n, sink &s)
+{
+    if (n && !desc) return DL_ERR_INVALID;
+    for (size_t i = 0; i < n; ++i) {
+        if (desc[i].bytes == 0) continue;
+        if (!desc[i].src || !desc[i].dst) return DL_ERR_INVALID;
+        if (desc[i].src == desc[i].dst) continue;  // identical range: nothing to move
+        void *d = desc[i].dst;
+        s.put(desc[i].src, desc[i].bytes, &d, 1);
+    }
+    return (long)s.n;
+}
+
+struct interval {
+    uint64_t lo, hi;
+    size_t item;
+};
+
+long first_hazard(const dl_plan_item *items, size_t n)
+{
+    std::vector<interval> dst;
+    for (size_t i = 0; i < n; ++i) {
+        if (items[i].bytes == 0) continue;
+        for (uint32_t j = 0; j < items[i].k; ++j)
+            dst.push_back({(uint64_t)items[i].dst[j], (uint64_t)items[i].dst[j] + items[i].bytes, i});
+    }
+    std::sort(dst.begin(), dst.end(), [](const interval &a, const interval &b) { return a.lo < b.lo; });
+    long worst = -1;
+    auto flag = [&](size_t i) {
+        if (worst < 0 || (long)i < worst) worst = (long)i;
+    };
+    // destination against destination: sweep by start, remember the furthest end so far
+    size_t owner = 0;
+    for (size_t q = 1; q < dst.size(); ++q) {
+        if (dst[q].lo < dst[owner].hi) {
+            flag(dst[q].item);
+            flag(dst[owner].item);
+        }
+        if (dst[q].hi > dst[owner].hi) owner = q;
+    }
+    if (worst >= 0) return worst;
+    // destinations are now known disjoint, so sorted by start is sorted by end:
+    // binary search the first destination ending after the source starts
+    for (size_t i = 0; i < n; ++i) {
+        if (items[i].bytes == 0) continue;
+        const uint64_t lo = (uint64_t)items[i].src, hi = lo + items[i].bytes;
+        auto it = std::partition_point(dst.begin(), dst.end(), [&](const interval &d) { return d.hi <= lo; });
+        if (it != dst.end() && it->lo < hi) flag(it->item);
+    }
+    return worst;
+}
+
+std::vector<dl_plan_item> g_items;      // reused between calls: no allocation once warm
+std::vector<dl_plain_item> g_plain;
+
+int execute(const dl_plan_item *items, size_t n, void *stream)
+{
+    if (!g_dl.inited) return DL_ERR_STATE;
+    if (n == 0) return DL_OK;
+    if (g_dl.validate && first_hazard(items, n) >= 0) return DL_ERR_OVERLAP;
+    bool all_plain = true;
+    for (size_t i = 0; i < n; ++i) all_plain &= items[i].k == 1;
+    const dl_fused_item *fused = reinterpret_cast<const dl_fused_item *>(items);
+    if (all_plain) {
+        g_plain.resize(n);
+        for (size_t i = 0; i < n; ++i) g_plain[i] = {(const char *)items[i].src, (char *)items[i].dst[0], items[i].bytes};
+        if (g_dl.mode == DL_MODE_PRELAUNCH) return dl_resident_submit_plain(g_plain.data(), n);
+        return dl_exec_plain(g_plain.data(), n, (hipStream_t)stream);
+    }
+    if (g_dl.mode == DL_MODE_PRELAUNCH) return dl_resident_submit_fused(fused, n);
+    return dl_exec_fused(fused, n, (hipStream_t)stream);
+}
+
+// Lower with `fn` into the reusable buffer, growing it when the first pass
+// reports more items than fit.
+template <class Fn>
+int lower_and_execute(Fn fn, void *stream)
+{
+    if (g_items.size() < 64) g_items.resize(64);
+    for (int pass = 0; pass < 2; ++pass) {
+        sink s{g_items.data(), g_items.size()};
+        const long r = fn(s);
+        if (r < 0) return (int)r;
+        if ((size_t)r <= g_items.size()) return execute(g_items.data(), (size_t)r, stream);
+        g_items.resize((size_t)r);
+    }
+    return DL_ERR_INVALID;
+}
+
+}  // namespace
+
+extern "C" {
+
+int dl_init(int device)
+{
+    if (g_dl.inited) return g_dl.device == device ? DL_OK : DL_ERR_STATE;
+    DL_HIP(hipSetDevice(device));
+    int cus = 0;
+    DL_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device));
+    g_dl.device = device;
+    g_dl.num_cu = cus;
+    g_dl.mode = DL_MODE_ONESHOT;
+    g_dl.validate = 0;
+    g_dl.cfg = dl_config{};
+    g_dl.cfg.nontemporal_min_bytes = 64ull << 20;
+    g_dl.cfg.idle_timeout_ms = 10000;
+    g_dl.cfg.fuse_broadcast = 1;
+    const int rc = dl_exec_init();
+    if (rc != DL_OK) return rc;
+    g_dl.inited = true;
+    return DL_OK;
+}
+
+int dl_shutdown(void)
+{
+    if (!g_dl.inited) return DL_OK;
+    int rc = DL_OK;
+    if (dl_resident_running()) rc = dl_prelaunch_stop();
+    dl_exec_shutdown();
+    g_dl.inited = false;
+    g_dl.device = -1;
+    g_dl.mode = DL_MODE_ONESHOT;
+    return rc;
+}
+
+int dl_set_mode(int mode)
+{
+    if (mode != DL_MODE_ONESHOT && mode != DL_MODE_PRELAUNCH) return DL_ERR_INVALID;
+    if (mode == DL_MODE_PRELAUNCH && !dl_resident_running()) return DL_ERR_STATE;
+    g_dl.mode = mode;
+    return DL_OK;
+}
+
+int dl_get_mode(void) { return g_dl.mode; }
+
+int dl_set_validate(int on)
+{
+    g_dl.validate = on ? 1 : 0;
+    return DL_OK;
+}
+
+const char *dl_strerror(int status)
+{
+    switch (status) {
+    case DL_OK: return "ok";
+    case DL_ERR_INVALID: return "invalid argument";
+    case DL_ERR_OVERLAP: return "a destination overlaps another destination or a source";
+    case DL_ERR_HIP: return "HIP call failed";
+    case DL_ERR_TIMEOUT: return "timed out";
+    case DL_ERR_STATE: return "library or resident kernel not in the required state";
+    default: return "unknown status";
+    }
+}
+
+int dl_last_hip_error(void) { return g_dl.last_hip; }
+
+int dl_get_config(dl_config *cfg)
+{
+    if (!cfg) return DL_ERR_INVALID;
+    *cfg = g_dl.cfg;
+    return DL_OK;
+}
+
+int dl_set_config(const dl_config *cfg)
+{
+    if (!cfg) return DL_ERR_INVALID;
+    const uint32_t t = cfg->tile_bytes, b = cfg->block_threads;
+    if (t && (t < 1024 || (t & (t - 1)) || t > (1u << 24))) return DL_ERR_INVALID;
+    if (b && b != 64 && b != 128 && b != 256 && b != 512) return DL_ERR_INVALID;
+    if (dl_resident_running() &&
+        (cfg->resident_blocks != g_dl.cfg.resident_blocks || cfg->idle_timeout_ms != g_dl.cfg.idle_timeout_ms))
+        return DL_ERR_STATE;
+    g_dl.cfg = *cfg;
+    return DL_OK;
+}
+
+int dl_batch_copy(const dl_copy_desc *desc, size_t n, void *stream)
+{
+    return lower_and_execute([&](sink &s) { return lower_batch(desc, n, s); }, stream);
+}
+
+int dl_broadcast(const void *src, void *const *dsts, int k, size_t bytes, void *stream)
+{
+    return lower_and_execute([&](sink &s) { return lower_broadcast(src, dsts, k, bytes, s); }, stream);
+}
+
+int dl_allgather(const void *const *in, void *const *out, int W, size_t bytes_per_rank, void *stream)
+{
+    const int fuse = (int)g_dl.cfg.fuse_broadcast;
+    return lower_and_execute([&](sink &s) { return lower_allgather(in, out, W, bytes_per_rank, fuse, s); }, stream);
+}
+
+int dl_alltoall(const void *const *in, void *const *out, int W, const size_t *chunk_bytes, void *stream)
+{
+    return lower_and_execute([&](sink &s) { return lower_alltoall(in, out, W, chunk_bytes, s); }, stream);
+}
+
+long dl_plan_allgather(const void *const *in, void *const *out, int W, size_t bytes_per_rank, int fuse_broadcast,
+                       dl_plan_item *items, size_t cap)
+{
+    sink s{items, items ? cap : 0};
+    return lower_allgather(in, out, W, bytes_per_rank, fuse_broadcast, s);
+}
+
+long dl_plan_alltoall(const void *const *in, void *const *out, int W, const size_t *chunk_bytes, dl_plan_item *items,
+                      size_t cap)
+{
+    sink s{items, items ? cap : 0};
+    return lower_alltoall(in, out, W, chunk_bytes, s);
+}
+
+long dl_plan_broadcast(const void *src, void *const *dsts, int k, size_t bytes, dl_plan_item *items, size_t cap)
+{
+    sink s{items, items ? cap : 0};
+    return lower_broadcast(src, dsts, k, bytes, s);
+}
+
+long dl_plan_batch(const dl_copy_desc *desc, size_t n, dl_plan_item *items, size_t cap)
+{
+    sink s{items, items ? cap : 0};
+    return lower_batch(desc, n, s);
+}
+
+long dl_plan_first_hazard(const dl_plan_item *items, size_t n)
+{
+    if (!items) return -1;
+    return first_hazard(items, n);
+}
+
+uint64_t dl_plan_tiles(const dl_plan_item *items, size_t n, uint32_t tile_bytes)
+{
+    if (!items || tile_bytes < 16) return 0;
+    uint64_t t = 0;
+    for (size_t i = 0; i < n; ++i) t += dl_item_tiles(*reinterpret_cast<const dl_fused_item *>(&items[i]), tile_bytes);
+    return t;
+}
+
+}  // extern "C"

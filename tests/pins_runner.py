@@ -1,0 +1,54 @@
+"""A condensed pass over the pins of test_oracle_pins.py against one build of
+the CPU checker.  Run as a script with the library path as its argument so
+that a build with a planted mistake (which may write out of bounds) cannot
+damage the test process: exit status 0 = all pins hold."""
+
+import os
+import sys
+
+import numpy as np
+
+sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+
+from oracle import ref  # noqa: E402
+from paper_2511_06605_amd import inputs  # noqa: E402
+
+
+def run_pins(lib):
+    W = 3
+    ins = inputs.allgather_inputs(W, 17, seed=1)
+    got = ref.allgather(ins, lib=lib)
+    assert np.array_equal(np.stack(got), np.tile(np.concatenate(ins), (W, 1)))
+
+    C = inputs.random_chunks(W, 40, seed=5, zero_frac=0.2)
+    assert not np.array_equal(C, C.T)
+    ins = inputs.alltoall_inputs(C, seed=2)
+    mid = ref.alltoall(ins, C, lib=lib)
+    for j in range(W):
+        for i in range(W):
+            a = mid[j][int(C[:i, j].sum()): int(C[:i + 1, j].sum())]
+            b = ins[i][int(C[i, :j].sum()): int(C[i, :j + 1].sum())]
+            assert np.array_equal(a, b)
+    back = ref.alltoall(mid, C.T, lib=lib)
+    for i in range(W):
+        assert np.array_equal(back[i], ins[i])
+
+    src = inputs.payload(np.random.default_rng(3), 100)
+    for d in ref.broadcast(src, 4, lib=lib):
+        assert np.array_equal(d, src)
+
+    arena, descs = inputs.b2b_batch(8, 64, 4096, seed=4, align=8)
+    want = arena.copy()
+    for s, d, n in descs.astype(np.int64):
+        want[d:d + n] = arena[s:s + n]
+    got = ref.batch_copy([arena.copy()], [(0, s, 0, d, n) for s, d, n in descs], lib=lib)[0]
+    assert np.array_equal(got, want)
+
+    buf = np.arange(256, dtype=np.uint8)
+    assert ref.first_hazard([buf], [(0, 0, 0, 100, 50), (0, 60, 0, 150, 10)], lib=lib) == -1
+    assert ref.first_hazard([buf], [(0, 0, 0, 100, 50), (0, 120, 0, 200, 10)], lib=lib) == 0
+
+
+
+if __name__ == "__main__":
+    run_pins(ref.load(sys.argv[1]))

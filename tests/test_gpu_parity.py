@@ -1,0 +1,274 @@
+"""GPU parity: every operation, through the C boundary, byte for byte against
+the CPU checker on the same seeded inputs.  The bar is bit-exact (pure data
+movement), and bytes outside every destination must stay untouched."""
+
+import numpy as np
+import pytest
+
+import paper_2511_06605_amd as dl
+from paper_2511_06605_amd import inputs
+from paper_2511_06605_amd.inputs import KiB, MiB
+
+from gpu_util import DevBuf, stream, sync
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def library():
+    import torch
+    assert torch.cuda.is_available()
+    torch.cuda.set_device(0)
+    dl.dl_init(0)
+    base = dl.dl_get_config()
+    yield
+    dl.dl_set_config(base)
+    dl.dl_set_validate(False)
+    dl.dl_shutdown()
+
+
+@pytest.fixture()
+def cfg():
+    """Set tunables for one test and restore the defaults afterwards."""
+    base = dl.dl_get_config()
+    saved = {f[0]: getattr(base, f[0]) for f in base._fields_}
+
+    def set_(**kw):
+        dl.dl_set_config(**kw)
+    yield set_
+    dl.dl_set_config(**saved)
+
+
+def run_allgather(ref, W, B, seed, kind="u8", shifts=None, in_place=False):
+    ins = inputs.allgather_inputs(W, B, seed, kind)
+    want = ref.allgather(ins)
+    shifts = shifts or [0] * (2 * W)
+    d_out = [DevBuf(W * B, shift=shifts[W + r]) for r in range(W)]
+    if in_place:
+        for r in range(W):
+            d_out[r].view()[r * B:(r + 1) * B].copy_(__import__("torch").from_numpy(ins[r]))
+        in_ptrs = [d_out[r].ptr(r * B) for r in range(W)]
+        d_in = []
+    else:
+        d_in = [DevBuf(B, fill=ins[r], shift=shifts[r]) for r in range(W)]
+        in_ptrs = [b.ptr() for b in d_in]
+    dl.dl_allgather(in_ptrs, [b.ptr() for b in d_out], B, stream())
+    sync()
+    for r in range(W):
+        assert np.array_equal(d_out[r].host(), want[r]), f"rank {r} differs (W={W}, B={B})"
+        assert d_out[r].guards_intact()
+    for r, b in enumerate(d_in):
+        assert np.array_equal(b.host(), ins[r]) and b.guards_intact()
+
+
+def run_alltoall(ref, C, seed, kind="u8"):
+    W = C.shape[0]
+    ins = inputs.alltoall_inputs(C, seed, kind)
+    want = ref.alltoall(ins, C)
+    d_in = [DevBuf(ins[i].size, fill=ins[i]) for i in range(W)]
+    d_out = [DevBuf(want[j].size) for j in range(W)]
+    dl.dl_alltoall([b.ptr() for b in d_in], [b.ptr() for b in d_out], C, stream())
+    sync()
+    for j in range(W):
+        assert np.array_equal(d_out[j].host(), want[j]), f"receiver {j} differs"
+        assert d_out[j].guards_intact()
+    return d_out, ins
+
+
+# ------------------------------------------------------------------ all-gather
+
+def test_allgather_config0_uint8_64KiB(ref):
+    """W = 8, 64 KiB per rank of uniform bytes, seed 0: every bit pattern moves unchanged."""
+    run_allgather(ref, 8, 64 * KiB, seed=0)
+
+
+@pytest.mark.parametrize("B", [1, 15, 16, 17, 255, 4096, 4097, 64 * KiB + 1, 1 * MiB + 3, 3 * MiB])
+def test_allgather_sizes_ragged(ref, B):
+    run_allgather(ref, 8, B, seed=B, kind="bf16" if B % 2 == 0 else "u8")
+
+
+@pytest.mark.parametrize("W", [1, 2, 3, 5, 13, 64])
+def test_allgather_rank_counts(ref, W):
+    run_allgather(ref, W, 5000, seed=W)
+
+
+@pytest.mark.parametrize("B", [4 * KiB, 256 * KiB, 16 * MiB])
+def test_allgather_sweep_points_bf16(ref, B):
+    run_allgather(ref, 8, B, seed=B.bit_length() - 1, kind="bf16")
+
+
+@pytest.mark.parametrize("tokens", [1, 8, 32, 128, 256])
+def test_allgather_tp_decode(ref, tokens):
+    run_allgather(ref, 8, inputs.tp_decode_bytes_per_rank(tokens), seed=tokens, kind="bf16")
+
+
+def test_allgather_in_place(ref):
+    run_allgather(ref, 8, 70001, seed=3, in_place=True)
+
+
+@pytest.mark.parametrize("case", ["coaligned_odd", "mod4", "mod1"])
+def test_allgather_misaligned(ref, case):
+    W = 4
+    if case == "coaligned_odd":
+        shifts = [5] * (2 * W)                       # all equal modulo 16, none aligned
+    elif case == "mod4":
+        shifts = [0, 4, 8, 12, 0, 4, 8, 12]          # agree modulo 4 only
+    else:
+        shifts = [0, 1, 2, 3, 7, 9, 11, 13]          # agree modulo 1 only
+    # W*B a multiple of 16 keeps slot offsets from changing the residues
+    run_allgather(ref, W, 40000, seed=11, shifts=shifts)
+    run_allgather(ref, W, 16 * 77, seed=12, shifts=shifts)
+
+
+def test_allgather_unfused_plain_copies(ref, cfg):
+    cfg(fuse_broadcast=0)
+    run_allgather(ref, 8, 100000, seed=5)
+
+
+@pytest.mark.parametrize("tile,block", [(1024, 64), (4096, 256), (65536, 512), (1 << 20, 128)])
+def test_allgather_forced_tiles(ref, cfg, tile, block):
+    cfg(tile_bytes=tile, block_threads=block)
+    run_allgather(ref, 8, 3 * tile + 16 * 5 + 7, seed=tile)
+    run_allgather(ref, 3, tile - 16, seed=tile + 1)
+
+
+def test_allgather_nontemporal_path(ref, cfg):
+    cfg(nontemporal_min_bytes=0)
+    run_allgather(ref, 8, 300001, seed=8)
+    cfg(nontemporal_min_bytes=1 << 62)
+    run_allgather(ref, 8, 300001, seed=8)
+
+
+def test_allgather_full_size_64MiB(ref):
+    """Largest sweep point, default launch configuration: 0.5 GiB in, 4 GiB out."""
+    import torch
+    W, B = 8, 64 * MiB
+    ins = inputs.allgather_inputs(W, B, seed=26, kind="bf16")
+    d_in = [torch.from_numpy(a).cuda() for a in ins]
+    d_out = [torch.full((W * B,), 0xA5, dtype=torch.uint8, device="cuda") for _ in range(W)]
+    dl.dl_allgather(d_in, d_out, B, stream())
+    sync()
+    want = ref.allgather(ins)
+    for r in range(W):
+        assert np.array_equal(d_out[r].cpu().numpy(), want[r]), f"rank {r}"
+
+
+# ------------------------------------------------------------------ all-to-all
+
+@pytest.mark.parametrize("c", [1 * KiB, 64 * KiB, 4 * MiB])
+def test_alltoall_uniform_fp16(ref, c):
+    run_alltoall(ref, inputs.uniform_chunks(8, c), seed=c, kind="fp16")
+
+
+@pytest.mark.parametrize("W,seed", [(2, 0), (3, 1), (8, 2), (8, 3), (13, 4)])
+def test_alltoall_nonsymmetric_with_zero_chunks(ref, W, seed):
+    C = inputs.random_chunks(W, 50000, seed=seed, zero_frac=0.25)
+    assert W == 1 or not np.array_equal(C, C.T)
+    run_alltoall(ref, C, seed=seed + 50)
+
+
+def test_alltoall_twice_is_identity_on_gpu(ref):
+    C = inputs.random_chunks(8, 30000, seed=9, zero_frac=0.2, multiple_of=16)
+    d_mid, ins = run_alltoall(ref, C, seed=10)
+    d_back = [DevBuf(ins[i].size) for i in range(8)]
+    dl.dl_alltoall([b.ptr() for b in d_mid], [b.ptr() for b in d_back], C.T, stream())
+    sync()
+    for i in range(8):
+        assert np.array_equal(d_back[i].host(), ins[i])
+
+
+@pytest.mark.parametrize("T", [16, 128, 512])
+def test_alltoall_moe_dispatch(ref, T):
+    C = inputs.moe_dispatch_chunks(8, T, seed=T)
+    assert int(C.sum()) == 8 * 8 * T * 14336
+    run_alltoall(ref, C, seed=T + 1, kind="bf16")
+
+
+def test_alltoall_moe_dispatch_skewed(ref):
+    run_alltoall(ref, inputs.moe_dispatch_chunks(8, 128, seed=7, skew_alpha=0.5), seed=8, kind="bf16")
+
+
+def test_alltoall_many_ranks_long_list(ref):
+    """W = 16 gives 256 copies: more than the kernel-argument list holds."""
+    C = inputs.random_chunks(16, 200000, seed=21, zero_frac=0.1)
+    run_alltoall(ref, C, seed=22)
+
+
+# ------------------------------------------------------------------- broadcast
+
+@pytest.mark.parametrize("k,n,kind", [(7, 2 * MiB, "bf16"), (1, 12345, "u8"), (8, 4096, "u8"), (9, 100001, "u8"),
+                                      (20, 77777, "u8"), (64, 1000, "u8")])
+def test_broadcast(ref, k, n, kind):
+    src = inputs.payload(np.random.default_rng(k * 7 + n), n, kind)
+    want = ref.broadcast(src, k)
+    d_src = DevBuf(n, fill=src)
+    d_dst = [DevBuf(n) for _ in range(k)]
+    dl.dl_broadcast(d_src.ptr(), [b.ptr() for b in d_dst], n, stream())
+    sync()
+    for b, w in zip(d_dst, want):
+        assert np.array_equal(b.host(), w) and b.guards_intact()
+    assert np.array_equal(d_src.host(), src)
+
+
+# --------------------------------------------------------------- batched copies
+
+def run_batch(ref, n, copy_bytes, arena_bytes, seed, align=256):
+    arena, descs = inputs.b2b_batch(n, copy_bytes, arena_bytes, seed, align)
+    want = ref.batch_copy([arena.copy()], [(0, s, 0, d, nb) for s, d, nb in descs])[0]
+    d = DevBuf(arena_bytes, fill=arena)
+    dl.dl_batch_copy([(d.ptr(int(s)), d.ptr(int(t)), int(nb)) for s, t, nb in descs], stream())
+    sync()
+    assert np.array_equal(d.host(), want)
+    assert d.guards_intact()
+
+
+def test_batch_config3_64_copies_of_16KiB(ref):
+    run_batch(ref, 64, 16 * KiB, 64 * MiB, seed=3)
+
+
+@pytest.mark.parametrize("n,nb,arena,align", [(1, 100, 4096, 1), (5, 1000, 64 * KiB, 8), (65, 5000, 4 * MiB, 16),
+                                              (1000, 4096, 32 * MiB, 256), (300, 70001, 128 * MiB, 1)])
+def test_batch_shapes(ref, n, nb, arena, align):
+    run_batch(ref, n, nb, arena, seed=n, align=align)
+
+
+def test_batch_long_list_with_large_items(ref, cfg):
+    """More copies than the argument list holds, each several tiles long."""
+    cfg(tile_bytes=4096)
+    run_batch(ref, 200, 50000, 64 * MiB, seed=77, align=16)
+
+
+def test_batch_kv_fetch_shape(ref):
+    """256 dispersed block copies in one batch, as a paged KV-cache fetch issues them."""
+    run_batch(ref, 256, 128 * KiB, 256 * MiB, seed=5)
+
+
+def test_empty_requests_are_no_ops():
+    d = DevBuf(1024)
+    dl.dl_batch_copy([], stream())
+    dl.dl_batch_copy([(d.ptr(), d.ptr(512), 0), (d.ptr(5), d.ptr(5), 100)], stream())
+    dl.dl_allgather([d.ptr()], [d.ptr(512)], 0, stream())
+    dl.dl_broadcast(d.ptr(), [d.ptr(512)], 0, stream())
+    dl.dl_alltoall([d.ptr(), d.ptr(8)], [d.ptr(512), d.ptr(600)], np.zeros((2, 2), dtype=np.uint64), stream())
+    sync()
+    assert (d.host() == 0xA5).all()
+
+
+def test_validation_rejects_hazards_and_enqueues_nothing():
+    d = DevBuf(4096)
+    before = d.host().copy()
+    dl.dl_set_validate(True)
+    try:
+        with pytest.raises(dl.DlError) as e:
+            dl.dl_batch_copy([(d.ptr(0), d.ptr(1000), 500), (d.ptr(2000), d.ptr(1400), 500)], stream())
+        assert e.value.status == dl.DL_ERR_OVERLAP
+        with pytest.raises(dl.DlError) as e:
+            dl.dl_broadcast(d.ptr(0), [d.ptr(1000), d.ptr(50)], 100, stream())
+        assert e.value.status == dl.DL_ERR_OVERLAP
+        dl.dl_batch_copy([(d.ptr(0), d.ptr(1000), 500), (d.ptr(100), d.ptr(1500), 500)], stream())
+    finally:
+        dl.dl_set_validate(False)
+    sync()
+    after = d.host()
+    assert np.array_equal(after[:1000], before[:1000]) and np.array_equal(after[2000:], before[2000:])
+    assert np.array_equal(after[1000:1500], before[0:500]) and np.array_equal(after[1500:2000], before[100:600])

@@ -4,11 +4,10 @@ at least one pin.  This guards the pins, not the checker: a mutant that
 survives means the pins could not tell a wrong checker from a right one."""
 
 import os
+import subprocess
+import sys
 
-import numpy as np
 import pytest
-
-from paper_2511_06605_amd import inputs
 
 MUTANTS = {
     # all-gather: wrong source rank, wrong slot, dropped last rank
@@ -40,44 +39,15 @@ MUTANTS = {
 }
 
 
-def run_pins(ref, lib):
-    """A condensed pass over the pins of test_oracle_pins.py against ``lib``."""
-    W = 3
-    ins = inputs.allgather_inputs(W, 17, seed=1)
-    got = ref.allgather(ins, lib=lib)
-    assert np.array_equal(np.stack(got), np.tile(np.concatenate(ins), (W, 1)))
+RUNNER = os.path.join(os.path.dirname(os.path.abspath(__file__)), "pins_runner.py")
 
-    C = inputs.random_chunks(W, 40, seed=5, zero_frac=0.2)
-    assert not np.array_equal(C, C.T)
-    ins = inputs.alltoall_inputs(C, seed=2)
-    mid = ref.alltoall(ins, C, lib=lib)
-    for j in range(W):
-        for i in range(W):
-            a = mid[j][int(C[:i, j].sum()): int(C[:i + 1, j].sum())]
-            b = ins[i][int(C[i, :j].sum()): int(C[i, :j + 1].sum())]
-            assert np.array_equal(a, b)
-    back = ref.alltoall(mid, C.T, lib=lib)
-    for i in range(W):
-        assert np.array_equal(back[i], ins[i])
 
-    src = inputs.payload(np.random.default_rng(3), 100)
-    for d in ref.broadcast(src, 4, lib=lib):
-        assert np.array_equal(d, src)
-
-    arena, descs = inputs.b2b_batch(8, 64, 4096, seed=4, align=8)
-    want = arena.copy()
-    for s, d, n in descs.astype(np.int64):
-        want[d:d + n] = arena[s:s + n]
-    got = ref.batch_copy([arena.copy()], [(0, s, 0, d, n) for s, d, n in descs], lib=lib)[0]
-    assert np.array_equal(got, want)
-
-    buf = np.arange(256, dtype=np.uint8)
-    assert ref.first_hazard([buf], [(0, 0, 0, 100, 50), (0, 60, 0, 150, 10)], lib=lib) == -1
-    assert ref.first_hazard([buf], [(0, 0, 0, 100, 50), (0, 120, 0, 200, 10)], lib=lib) == 0
+def pins_hold(lib_path) -> bool:
+    return subprocess.run([sys.executable, RUNNER, lib_path], capture_output=True).returncode == 0
 
 
 def test_unpatched_checker_passes(ref):
-    run_pins(ref, ref.load())
+    assert pins_hold(ref.build())
 
 
 @pytest.mark.parametrize("name", sorted(MUTANTS))
@@ -89,6 +59,4 @@ def test_mutant_is_caught(ref, tmp_path, name):
     src.write_text(text.replace(old, new))
     out = str(tmp_path / f"libmutant_{name}.so")
     ref.build(str(src), out, force=True)
-    lib = ref.load(out)
-    with pytest.raises((AssertionError, ValueError, RuntimeError)):
-        run_pins(ref, lib)
+    assert not pins_hold(out)
