@@ -1,0 +1,113 @@
+"""ctypes front end of the measurement aid (``libdl_benchaid.so``): timing loops
+around the public ``dl_*`` calls and the runtime copy paths timed beside them.
+Used by ``bench.py`` only."""
+
+from __future__ import annotations
+
+import ctypes
+import os
+
+from . import binding
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+AID_PATH = os.path.join(_HERE, "libdl_benchaid.so")
+
+OP_BATCH, OP_BROADCAST, OP_ALLGATHER, OP_ALLTOALL, OP_MEMCPY_ASYNC, OP_MEMCPY_BATCH = range(6)
+WAIT_STREAM, WAIT_TICKET = 0, 1
+
+
+class Request(ctypes.Structure):
+    _fields_ = [
+        ("op", ctypes.c_int), ("k", ctypes.c_int), ("W", ctypes.c_int), ("pad", ctypes.c_int),
+        ("desc", ctypes.POINTER(binding.CopyDesc)), ("n", ctypes.c_size_t),
+        ("src", ctypes.c_void_p), ("dsts", ctypes.POINTER(ctypes.c_void_p)), ("bytes", ctypes.c_size_t),
+        ("in_", ctypes.POINTER(ctypes.c_void_p)), ("out", ctypes.POINTER(ctypes.c_void_p)),
+        ("C", ctypes.POINTER(ctypes.c_size_t)),
+    ]
+
+
+_aid = None
+
+
+def aid() -> ctypes.CDLL:
+    global _aid
+    if _aid is None:
+        binding.lib()  # the aid links against the library
+        if not os.path.exists(AID_PATH):
+            raise ImportError(f"{AID_PATH} is missing: run `python -m paper_2511_06605_amd.build`")
+        L = ctypes.CDLL(AID_PATH)
+        rp, dp = ctypes.POINTER(Request), ctypes.POINTER(ctypes.c_double)
+        L.dlb_issue.restype = ctypes.c_int
+        L.dlb_issue.argtypes = [rp, ctypes.c_void_p]
+        L.dlb_time_host.restype = ctypes.c_int
+        L.dlb_time_host.argtypes = [rp, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, dp]
+        L.dlb_time_device.restype = ctypes.c_int
+        L.dlb_time_device.argtypes = [rp, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, dp]
+        _aid = L
+    return _aid
+
+
+class Prepared:
+    """A request with its marshalled arrays kept alive."""
+
+    def __init__(self, req, keep):
+        self.req, self._keep = req, keep
+
+
+def allgather_request(ins, outs, bytes_per_rank) -> Prepared:
+    a, b = binding._ptr_array(list(ins)), binding._ptr_array(list(outs))
+    r = Request(op=OP_ALLGATHER, W=len(ins), bytes=int(bytes_per_rank))
+    r.in_ = ctypes.cast(a, ctypes.POINTER(ctypes.c_void_p))
+    r.out = ctypes.cast(b, ctypes.POINTER(ctypes.c_void_p))
+    return Prepared(r, (a, b))
+
+
+def alltoall_request(ins, outs, C) -> Prepared:
+    W = len(ins)
+    a, b, c = binding._ptr_array(list(ins)), binding._ptr_array(list(outs)), binding._chunk_array(C, W)
+    r = Request(op=OP_ALLTOALL, W=W)
+    r.in_ = ctypes.cast(a, ctypes.POINTER(ctypes.c_void_p))
+    r.out = ctypes.cast(b, ctypes.POINTER(ctypes.c_void_p))
+    r.C = ctypes.cast(c, ctypes.POINTER(ctypes.c_size_t))
+    return Prepared(r, (a, b, c))
+
+
+def broadcast_request(src, dsts, nbytes) -> Prepared:
+    d = binding._ptr_array(list(dsts))
+    r = Request(op=OP_BROADCAST, k=len(dsts), bytes=int(nbytes), src=binding._addr(src))
+    r.dsts = ctypes.cast(d, ctypes.POINTER(ctypes.c_void_p))
+    return Prepared(r, (d,))
+
+
+def copy_list_request(descs, op=OP_BATCH) -> Prepared:
+    descs = list(descs)
+    d = binding._desc_array(descs)
+    r = Request(op=op, n=len(descs))
+    r.desc = ctypes.cast(d, ctypes.POINTER(binding.CopyDesc))
+    return Prepared(r, (d,))
+
+
+def _rc(rc, what):
+    if rc >= 1000:
+        raise RuntimeError(f"{what}: hipError {rc - 1000}")
+    if rc:
+        raise binding.DlError(rc, what)
+
+
+def issue(p: Prepared, stream=None) -> None:
+    _rc(aid().dlb_issue(ctypes.byref(p.req), binding._stream(stream)), "dlb_issue")
+
+
+def time_host(p: Prepared, stream=None, wait=WAIT_STREAM, warmup=50, iters=1000):
+    """Per-call host-observed latencies in microseconds."""
+    out = (ctypes.c_double * iters)()
+    _rc(aid().dlb_time_host(ctypes.byref(p.req), binding._stream(stream), wait, warmup, iters, out), "dlb_time_host")
+    return list(out)
+
+
+def time_device(p: Prepared, stream=None, warmup=5, calls=20) -> float:
+    """Microseconds per call from HIP events around ``calls`` back-to-back issues."""
+    out = ctypes.c_double(0)
+    _rc(aid().dlb_time_device(ctypes.byref(p.req), binding._stream(stream), warmup, calls, ctypes.byref(out)),
+        "dlb_time_device")
+    return out.value

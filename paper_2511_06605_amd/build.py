@@ -19,9 +19,10 @@ HIPCC_FLAGS = [
 ]
 
 
-def build(verbose: bool = False) -> str:
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB]
+AID_LIB = os.path.join(HERE, "libdl_benchaid.so")
+
+
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     r = subprocess.run(cmd, stderr=subprocess.PIPE, text=True)
@@ -32,6 +33,14 @@ def build(verbose: bool = False) -> str:
         print(err, file=sys.stderr, flush=True)
     if r.returncode:
         raise subprocess.CalledProcessError(r.returncode, cmd)
+
+
+def build(verbose: bool = False) -> str:
+    """The library, then the measurement aid that links against it."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    _run([hipcc, *HIPCC_FLAGS, *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB], verbose)
+    _run([hipcc, *HIPCC_FLAGS, os.path.join(CSRC, "dl_benchaid.hip"), "-L" + HERE, "-ldmalatte",
+          "-Wl,-rpath,$ORIGIN", "-ldl", "-o", AID_LIB], verbose)
     return LIB
 
 

@@ -1,0 +1,123 @@
+// Measurement aid, separate from the library: timing loops around the public
+// dl_* calls (host-observed latency per call, device time per call from HIP
+// events on the launch stream) and the two runtime copy paths timed beside
+// them: one hipMemcpyAsync per chunk, and one hipMemcpyBatchAsync.
+// Links against libdmalatte.so; moves no bytes itself.
+#include <dlfcn.h>
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <time.h>
+
+#include <vector>
+
+#include "../../include/dmalatte.h"
+
+extern "C" {
+
+typedef struct dlb_request {
+    int op;  // 0 batch, 1 broadcast, 2 all-gather, 3 all-to-all, 4 hipMemcpyAsync per desc, 5 hipMemcpyBatchAsync
+    int k;
+    int W;
+    int pad;
+    const dl_copy_desc *desc;
+    size_t n;
+    const void *src;
+    void *const *dsts;
+    size_t bytes;
+    const void *const *in;
+    void *const *out;
+    const size_t *C;
+} dlb_request;
+
+static double now_us()
+{
+    timespec ts;
+    clock_gettime(CLOCK_MONOTONIC, &ts);
+    return ts.tv_sec * 1e6 + ts.tv_nsec * 1e-3;
+}
+
+// Issue the request once.  Returns a dl_status, or 1000 + hipError_t for the runtime paths.
+int dlb_issue(const dlb_request *r, void *stream)
+{
+    switch (r->op) {
+    case 0: return dl_batch_copy(r->desc, r->n, stream);
+    case 1: return dl_broadcast(r->src, r->dsts, r->k, r->bytes, stream);
+    case 2: return dl_allgather(r->in, r->out, r->W, r->bytes, stream);
+    case 3: return dl_alltoall(r->in, r->out, r->W, r->C, stream);
+    case 4:
+        for (size_t i = 0; i < r->n; ++i) {
+            hipError_t e = hipMemcpyAsync(r->desc[i].dst, r->desc[i].src, r->desc[i].bytes, hipMemcpyDeviceToDevice,
+                                          (hipStream_t)stream);
+            if (e != hipSuccess) return 1000 + (int)e;
+        }
+        return 0;
+    case 5: {
+        static std::vector<void *> d, s;
+        static std::vector<size_t> z;
+        d.resize(r->n), s.resize(r->n), z.resize(r->n);
+        for (size_t i = 0; i < r->n; ++i) {
+            d[i] = r->desc[i].dst;
+            s[i] = (void *)r->desc[i].src;
+            z[i] = r->desc[i].bytes;
+        }
+        // The batched runtime copy exists only in newer HIP runtimes; take whatever the
+        // runtime already loaded in this process offers, and report its absence.
+        typedef hipError_t (*batch_fn)(void **, void **, size_t *, size_t, hipMemcpyAttributes *, size_t *, size_t,
+                                       size_t *, hipStream_t);
+        static batch_fn fn = (batch_fn)dlsym(RTLD_DEFAULT, "hipMemcpyBatchAsync");
+        if (!fn) return 1000 + (int)hipErrorNotSupported;
+        size_t fail = 0;
+        hipError_t e = fn(d.data(), s.data(), z.data(), r->n, nullptr, nullptr, 0, &fail, (hipStream_t)stream);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            return 1000 + (int)e;
+        }
+        return 0;
+    }
+    default: return DL_ERR_INVALID;
+    }
+}
+
+// Host-observed latency: clock before the call to completion seen on the host.
+// wait_mode 0: hipStreamSynchronize(stream); 1: dl_wait(dl_last_ticket()).
+int dlb_time_host(const dlb_request *r, void *stream, int wait_mode, int warmup, int iters, double *us)
+{
+    for (int i = -warmup; i < iters; ++i) {
+        const double t0 = now_us();
+        int rc = dlb_issue(r, stream);
+        if (rc) return rc;
+        if (wait_mode == 1) {
+            rc = dl_wait(dl_last_ticket(), 2000000000ull);
+            if (rc) return rc;
+        } else {
+            hipError_t e = hipStreamSynchronize((hipStream_t)stream);
+            if (e != hipSuccess) return 1000 + (int)e;
+        }
+        const double t1 = now_us();
+        if (i >= 0) us[i] = t1 - t0;
+    }
+    return 0;
+}
+
+// Device time per call: HIP events on `stream` around `calls` back-to-back issues.
+int dlb_time_device(const dlb_request *r, void *stream, int warmup, int calls, double *us_per_call)
+{
+    hipEvent_t a, b;
+    if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return 1000;
+    int rc = 0;
+    for (int i = 0; i < warmup && !rc; ++i) rc = dlb_issue(r, stream);
+    if (!rc && hipStreamSynchronize((hipStream_t)stream) != hipSuccess) rc = 1000;
+    if (!rc) {
+        (void)hipEventRecord(a, (hipStream_t)stream);
+        for (int i = 0; i < calls && !rc; ++i) rc = dlb_issue(r, stream);
+        (void)hipEventRecord(b, (hipStream_t)stream);
+        if (hipEventSynchronize(b) != hipSuccess) rc = rc ? rc : 1000;
+        float ms = 0;
+        if (!rc && hipEventElapsedTime(&ms, a, b) == hipSuccess) *us_per_call = ms * 1e3 / calls;
+    }
+    (void)hipEventDestroy(a);
+    (void)hipEventDestroy(b);
+    return rc;
+}
+
+}  // extern "C"
