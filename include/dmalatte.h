@@ -151,11 +151,11 @@ int dl_wait(uint64_t ticket, uint64_t timeout_ns);
 typedef struct dl_config {
     uint32_t tile_bytes;         /* bytes of one workgroup tile; 0 = choose from the request size; power of two >= 1024 */
     uint32_t block_threads;      /* workgroup size of the one-shot kernel: 64, 128, 256, 512 or 1024; 0 = choose */
-    uint64_t nontemporal_min_bytes; /* requests moving at least this many bytes use streaming loads/stores */
+    uint64_t nontemporal_min_bytes; /* requests moving at least this many bytes use streaming loads/stores; default: never */
     uint32_t resident_blocks;    /* workgroups of the resident kernel; 0 = one per compute unit */
     uint32_t idle_timeout_ms;    /* the resident kernel exits after this long without a doorbell */
     uint32_t fuse_broadcast;     /* 1: all-gather reads each source once (W fused copies); 0: W*W plain copies */
-    uint32_t reserved;
+    uint32_t max_blocks;         /* cap on the one-shot grid; workgroups then stride over the tiles; 0 = one workgroup per tile */
 } dl_config;
 
 int dl_get_config(dl_config *cfg);

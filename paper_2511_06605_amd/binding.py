@@ -56,7 +56,7 @@ class Config(ctypes.Structure):
         ("resident_blocks", ctypes.c_uint32),
         ("idle_timeout_ms", ctypes.c_uint32),
         ("fuse_broadcast", ctypes.c_uint32),
-        ("reserved", ctypes.c_uint32),
+        ("max_blocks", ctypes.c_uint32),
     ]
 
 

@@ -199,7 +199,7 @@ int dl_init(int device)
     g_dl.mode = DL_MODE_ONESHOT;
     g_dl.validate = 0;
     g_dl.cfg = dl_config{};
-    g_dl.cfg.nontemporal_min_bytes = 64ull << 20;
+    g_dl.cfg.nontemporal_min_bytes = ~0ull;  // streaming hints measured slower: off unless asked for
     g_dl.cfg.idle_timeout_ms = 10000;
     g_dl.cfg.fuse_broadcast = 1;
     const int rc = dl_exec_init();

@@ -34,6 +34,7 @@ extern dl_state g_dl;
 struct dl_launch_shape {
     uint32_t tile_bytes;
     uint32_t block_threads;
+    uint32_t max_blocks;  // 0 = one workgroup per tile
     bool nontemporal;
 };
 
