@@ -16,9 +16,9 @@
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *  - Calls only enqueue work.  In one-shot mode the result is complete when
  *    the stream reaches the end of the enqueued kernel.  In prelaunch mode the
- *    request is handed to a resident kernel through a doorbell, `stream` is
- *    not used, inputs must already be complete when the call is made, and
- *    completion is observed with dl_wait() on the ticket of the call.
+ *    call enqueues an "armed" kernel that waits for dl_trigger() before it
+ *    copies (see "prelaunch mode" below); completion is observed with
+ *    dl_wait() on the ticket of the call.
  *  - Return value: DL_OK (0) or a negative dl_status.  No exceptions, no
  *    aborts.  On DL_ERR_HIP, dl_last_hip_error() gives the hipError_t.
  *  - Not thread-safe: one host thread drives the library at a time.
@@ -38,8 +38,9 @@ typedef enum dl_status {
     DL_ERR_INVALID = -1,  /* null pointer with non-zero bytes, W < 1, k < 1, k > DL_MAX_FANOUT, bad config */
     DL_ERR_OVERLAP = -2,  /* a destination overlaps another destination or a source (validation on) */
     DL_ERR_HIP = -3,      /* a HIP call failed; see dl_last_hip_error() */
-    DL_ERR_TIMEOUT = -4,  /* dl_wait() gave up, or the resident kernel did not come up or go down in time */
-    DL_ERR_STATE = -5     /* not initialised; prelaunch mode without a resident kernel; started twice */
+    DL_ERR_TIMEOUT = -4,  /* a host-side wait gave up */
+    DL_ERR_STATE = -5,    /* not initialised; prelaunch mode not started; started twice */
+    DL_ERR_EXPIRED = -6   /* an armed request was cancelled or not triggered within its arm limit: nothing was copied */
 } dl_status;
 
 /* Largest number of destinations of one dl_broadcast call / ranks of a collective. */
@@ -47,7 +48,7 @@ typedef enum dl_status {
 
 typedef enum dl_mode {
     DL_MODE_ONESHOT = 0,   /* one kernel launch per call, ordered on `stream` */
-    DL_MODE_PRELAUNCH = 1  /* request handed to the resident doorbell-polling kernel */
+    DL_MODE_PRELAUNCH = 1  /* one armed kernel per call, started by dl_trigger() */
 } dl_mode;
 
 /* One copy of a batch: `bytes` bytes from device pointer src to device pointer dst. */
@@ -64,11 +65,11 @@ typedef struct dl_copy_desc {
  * first (DL_ERR_STATE). */
 int dl_init(int device);
 
-/* Stop the resident kernel if one runs, release the staging memory. */
+/* Leave prelaunch mode if it was started, release the staging memory. */
 int dl_shutdown(void);
 
-/* Select how the four operations are executed.  DL_MODE_PRELAUNCH requires a
- * running resident kernel at call time (DL_ERR_STATE otherwise). */
+/* Select how the four operations are executed.  DL_MODE_PRELAUNCH requires
+ * dl_prelaunch_start() first (DL_ERR_STATE otherwise). */
 int dl_set_mode(int mode);
 int dl_get_mode(void);
 
@@ -127,24 +128,38 @@ int dl_alltoall(const void *const *in, void *const *out, int W, const size_t *ch
 /* ------------------------------------------------------------- prelaunch mode */
 
 /*
- * Launch the resident kernel (the analogue of a pre-enqueued poll command,
- * paper Sec. IV-E).  It occupies a fixed number of workgroups on a private
- * non-blocking stream and spins on a doorbell word in host-coherent memory.
- * While it runs, hipDeviceSynchronize() (and anything that implies it) blocks
- * until dl_prelaunch_stop().  The kernel also leaves by itself after
- * `idle_timeout_ms` without a doorbell (see dl_config); the next call in
- * prelaunch mode then returns DL_ERR_STATE.
+ * Prelaunch (paper Sec. IV-E: copies pre-enqueued behind a poll command and
+ * triggered later by a memory write, which takes the launch off the critical
+ * path).  In DL_MODE_PRELAUNCH each of the four operations enqueues ONE kernel
+ * immediately, on `stream` (NULL = a non-blocking stream owned by the library),
+ * and returns; dl_last_ticket() then names the request.  The kernel's
+ * workgroups become resident and poll a doorbell word in host-coherent memory.
+ *   dl_trigger(t)  rings the doorbell for every ticket <= t: one 8-byte store.
+ *                  Everything the request reads must be complete before it.
+ *   dl_wait(t, ns) spins on the host until request t has finished: DL_OK,
+ *                  DL_ERR_EXPIRED (the request gave up without copying a byte,
+ *                  or copied only part, because it was cancelled or waited
+ *                  longer than dl_config.arm_timeout_us), or DL_ERR_TIMEOUT
+ *                  (the host gave up waiting; ns == 0 polls once).
+ *   dl_wait_armed(t, ns) returns once request t's kernel is resident and
+ *                  polling (used to time trigger -> completion).
+ * Requests on one stream run in ticket order.  The armed kernel occupies its
+ * stream until it is triggered, cancelled or expires; later work on that
+ * stream waits for it.  At most 64 requests may be armed and unfinished.
+ * Lists too long for one kernel (hundreds of thousands of tiles) are refused
+ * with DL_ERR_INVALID in this mode.  An empty request enqueues nothing and
+ * takes no ticket.
+ *
+ * dl_prelaunch_start() allocates the doorbell and completion words and the
+ * library's stream; dl_prelaunch_stop() cancels whatever is still armed, waits
+ * for it to leave the device and releases them.
  */
 int dl_prelaunch_start(void);
 int dl_prelaunch_stop(void);
-
-/* Ticket of the most recent request issued in prelaunch mode (0 = none yet). */
-uint64_t dl_last_ticket(void);
-
-/* Spin on the host until the request `ticket` and all earlier ones are complete.
- * timeout_ns == 0 polls once.  DL_OK, DL_ERR_TIMEOUT, or DL_ERR_STATE if the
- * resident kernel is gone and the ticket can no longer complete. */
+uint64_t dl_last_ticket(void); /* ticket of the most recent request issued in prelaunch mode (0 = none yet) */
+int dl_trigger(uint64_t ticket);
 int dl_wait(uint64_t ticket, uint64_t timeout_ns);
+int dl_wait_armed(uint64_t ticket, uint64_t timeout_ns);
 
 /* -------------------------------------------------------------------- tunables */
 
@@ -152,8 +167,8 @@ typedef struct dl_config {
     uint32_t tile_bytes;         /* bytes of one workgroup tile; 0 = choose from the request size; power of two >= 1024 */
     uint32_t block_threads;      /* workgroup size of the one-shot kernel: 64, 128, 256, 512 or 1024; 0 = choose */
     uint64_t nontemporal_min_bytes; /* requests moving at least this many bytes use streaming loads/stores; default: never */
-    uint32_t resident_blocks;    /* workgroups of the resident kernel; 0 = one per compute unit */
-    uint32_t idle_timeout_ms;    /* the resident kernel exits after this long without a doorbell */
+    uint32_t armed_blocks;       /* cap on the grid of an armed kernel (its workgroups stride over the tiles); 0 = 4 per compute unit */
+    uint32_t arm_timeout_us;     /* an armed kernel gives up this long after becoming resident; 1 .. 1000000, default 20000 */
     uint32_t fuse_broadcast;     /* 1: all-gather reads each source once (W fused copies); 0: W*W plain copies */
     uint32_t max_blocks;         /* cap on the one-shot grid; workgroups then stride over the tiles; 0 = one workgroup per tile */
 } dl_config;

@@ -23,6 +23,7 @@ DL_ERR_OVERLAP = -2
 DL_ERR_HIP = -3
 DL_ERR_TIMEOUT = -4
 DL_ERR_STATE = -5
+DL_ERR_EXPIRED = -6
 DL_MAX_FANOUT = 64
 DL_PLAN_FANOUT = 8
 DL_MODE_ONESHOT = 0
@@ -32,7 +33,8 @@ DL_MODE_PRELAUNCH = 1
 EXPORTS = [
     "dl_init", "dl_shutdown", "dl_set_mode", "dl_get_mode", "dl_set_validate", "dl_strerror",
     "dl_last_hip_error", "dl_batch_copy", "dl_broadcast", "dl_allgather", "dl_alltoall",
-    "dl_prelaunch_start", "dl_prelaunch_stop", "dl_last_ticket", "dl_wait", "dl_get_config",
+    "dl_prelaunch_start", "dl_prelaunch_stop", "dl_last_ticket", "dl_trigger", "dl_wait", "dl_wait_armed",
+    "dl_get_config",
     "dl_set_config", "dl_plan_allgather", "dl_plan_alltoall", "dl_plan_broadcast", "dl_plan_batch",
     "dl_plan_first_hazard", "dl_plan_tiles",
 ]
@@ -53,8 +55,8 @@ class Config(ctypes.Structure):
         ("tile_bytes", ctypes.c_uint32),
         ("block_threads", ctypes.c_uint32),
         ("nontemporal_min_bytes", ctypes.c_uint64),
-        ("resident_blocks", ctypes.c_uint32),
-        ("idle_timeout_ms", ctypes.c_uint32),
+        ("armed_blocks", ctypes.c_uint32),
+        ("arm_timeout_us", ctypes.c_uint32),
         ("fuse_broadcast", ctypes.c_uint32),
         ("max_blocks", ctypes.c_uint32),
     ]
@@ -100,7 +102,9 @@ def lib() -> ctypes.CDLL:
         "dl_prelaunch_start": (ctypes.c_int, []),
         "dl_prelaunch_stop": (ctypes.c_int, []),
         "dl_last_ticket": (ctypes.c_uint64, []),
+        "dl_trigger": (ctypes.c_int, [ctypes.c_uint64]),
         "dl_wait": (ctypes.c_int, [ctypes.c_uint64, ctypes.c_uint64]),
+        "dl_wait_armed": (ctypes.c_int, [ctypes.c_uint64, ctypes.c_uint64]),
         "dl_get_config": (ctypes.c_int, [ctypes.POINTER(Config)]),
         "dl_set_config": (ctypes.c_int, [ctypes.POINTER(Config)]),
         "dl_plan_allgather": (ctypes.c_long, [vpp, vpp, ctypes.c_int, ctypes.c_size_t, ctypes.c_int,
@@ -251,9 +255,19 @@ def dl_last_ticket() -> int:
     return int(lib().dl_last_ticket())
 
 
+def dl_trigger(ticket: int | None = None) -> None:
+    t = dl_last_ticket() if ticket is None else ticket
+    _check(lib().dl_trigger(t), "dl_trigger")
+
+
 def dl_wait(ticket: int | None = None, timeout_ns: int = 5_000_000_000) -> None:
     t = dl_last_ticket() if ticket is None else ticket
     _check(lib().dl_wait(t, timeout_ns), "dl_wait")
+
+
+def dl_wait_armed(ticket: int | None = None, timeout_ns: int = 5_000_000_000) -> None:
+    t = dl_last_ticket() if ticket is None else ticket
+    _check(lib().dl_wait_armed(t, timeout_ns), "dl_wait_armed")
 
 
 # --------------------------------------------------------------------- lowering

@@ -1,6 +1,6 @@
 // The C boundary: argument checks, lowering of the collectives to copy lists
 // (the "control" phase of Sec. III-B2), the optional hazard check of Sec. IV-D,
-// and dispatch to the one-shot launcher or the resident kernel.
+// and dispatch to the one-shot or the armed (prelaunched) launcher.
 #include "dl_internal.h"
 
 #include <string.h>
@@ -155,17 +155,27 @@ int execute(const dl_plan_item *items, size_t n, void *stream)
     if (!g_dl.inited) return DL_ERR_STATE;
     if (n == 0) return DL_OK;
     if (g_dl.validate && first_hazard(items, n) >= 0) return DL_ERR_OVERLAP;
+    hipStream_t hs = (hipStream_t)stream;
+    dl_arm arm;
+    const dl_arm *armp = nullptr;
+    if (g_dl.mode == DL_MODE_PRELAUNCH) {
+        const int rc = dl_armed_begin(&arm, &hs);
+        if (rc != DL_OK) return rc;
+        armp = &arm;
+    }
     bool all_plain = true;
     for (size_t i = 0; i < n; ++i) all_plain &= items[i].k == 1;
-    const dl_fused_item *fused = reinterpret_cast<const dl_fused_item *>(items);
+    bool launched = false;
+    int rc;
     if (all_plain) {
         g_plain.resize(n);
         for (size_t i = 0; i < n; ++i) g_plain[i] = {(const char *)items[i].src, (char *)items[i].dst[0], items[i].bytes};
-        if (g_dl.mode == DL_MODE_PRELAUNCH) return dl_resident_submit_plain(g_plain.data(), n);
-        return dl_exec_plain(g_plain.data(), n, (hipStream_t)stream);
+        rc = dl_exec_plain(g_plain.data(), n, hs, armp, &launched);
+    } else {
+        rc = dl_exec_fused(reinterpret_cast<const dl_fused_item *>(items), n, hs, armp, &launched);
     }
-    if (g_dl.mode == DL_MODE_PRELAUNCH) return dl_resident_submit_fused(fused, n);
-    return dl_exec_fused(fused, n, (hipStream_t)stream);
+    if (armp && rc == DL_OK && launched) dl_armed_commit();
+    return rc;
 }
 
 // Lower with `fn` into the reusable buffer, growing it when the first pass
@@ -200,7 +210,7 @@ int dl_init(int device)
     g_dl.validate = 0;
     g_dl.cfg = dl_config{};
     g_dl.cfg.nontemporal_min_bytes = ~0ull;  // streaming hints measured slower: off unless asked for
-    g_dl.cfg.idle_timeout_ms = 10000;
+    g_dl.cfg.arm_timeout_us = 20000;
     g_dl.cfg.fuse_broadcast = 1;
     const int rc = dl_exec_init();
     if (rc != DL_OK) return rc;
@@ -212,7 +222,7 @@ int dl_shutdown(void)
 {
     if (!g_dl.inited) return DL_OK;
     int rc = DL_OK;
-    if (dl_resident_running()) rc = dl_prelaunch_stop();
+    if (dl_armed_ready()) rc = dl_prelaunch_stop();
     dl_exec_shutdown();
     g_dl.inited = false;
     g_dl.device = -1;
@@ -223,7 +233,7 @@ int dl_shutdown(void)
 int dl_set_mode(int mode)
 {
     if (mode != DL_MODE_ONESHOT && mode != DL_MODE_PRELAUNCH) return DL_ERR_INVALID;
-    if (mode == DL_MODE_PRELAUNCH && !dl_resident_running()) return DL_ERR_STATE;
+    if (mode == DL_MODE_PRELAUNCH && !dl_armed_ready()) return DL_ERR_STATE;
     g_dl.mode = mode;
     return DL_OK;
 }
@@ -244,7 +254,8 @@ const char *dl_strerror(int status)
     case DL_ERR_OVERLAP: return "a destination overlaps another destination or a source";
     case DL_ERR_HIP: return "HIP call failed";
     case DL_ERR_TIMEOUT: return "timed out";
-    case DL_ERR_STATE: return "library or resident kernel not in the required state";
+    case DL_ERR_STATE: return "library or prelaunch mode not in the required state";
+    case DL_ERR_EXPIRED: return "armed request cancelled or not triggered in time; nothing or only part was copied";
     default: return "unknown status";
     }
 }
@@ -264,9 +275,7 @@ int dl_set_config(const dl_config *cfg)
     const uint32_t t = cfg->tile_bytes, b = cfg->block_threads;
     if (t && (t < 1024 || (t & (t - 1)) || t > (1u << 24))) return DL_ERR_INVALID;
     if (b && b != 64 && b != 128 && b != 256 && b != 512) return DL_ERR_INVALID;
-    if (dl_resident_running() &&
-        (cfg->resident_blocks != g_dl.cfg.resident_blocks || cfg->idle_timeout_ms != g_dl.cfg.idle_timeout_ms))
-        return DL_ERR_STATE;
+    if (cfg->arm_timeout_us < 1 || cfg->arm_timeout_us > 1000000) return DL_ERR_INVALID;
     g_dl.cfg = *cfg;
     return DL_OK;
 }

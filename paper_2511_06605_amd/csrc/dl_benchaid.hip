@@ -78,20 +78,31 @@ int dlb_issue(const dlb_request *r, void *stream)
     }
 }
 
-// Host-observed latency: clock before the call to completion seen on the host.
-// wait_mode 0: hipStreamSynchronize(stream); 1: dl_wait(dl_last_ticket()).
+// Host-observed latency per call, in microseconds.
+// wait_mode 0 (one-shot): clock before the call -> hipStreamSynchronize(stream) returns.
+// wait_mode 1 (prelaunch): the request is armed and seen resident first (untimed);
+//             clock before dl_trigger() -> dl_wait() returns.
+// wait_mode 2 (prelaunch): clock before the arming call -> dl_trigger() -> dl_wait() returns.
 int dlb_time_host(const dlb_request *r, void *stream, int wait_mode, int warmup, int iters, double *us)
 {
     for (int i = -warmup; i < iters; ++i) {
-        const double t0 = now_us();
+        double t0 = now_us();
         int rc = dlb_issue(r, stream);
         if (rc) return rc;
-        if (wait_mode == 1) {
-            rc = dl_wait(dl_last_ticket(), 2000000000ull);
-            if (rc) return rc;
-        } else {
+        if (wait_mode == 0) {
             hipError_t e = hipStreamSynchronize((hipStream_t)stream);
             if (e != hipSuccess) return 1000 + (int)e;
+        } else {
+            const uint64_t t = dl_last_ticket();
+            if (wait_mode == 1) {
+                rc = dl_wait_armed(t, 2000000000ull);
+                if (rc) return rc;
+                t0 = now_us();
+            }
+            rc = dl_trigger(t);
+            if (rc) return rc;
+            rc = dl_wait(t, 2000000000ull);
+            if (rc) return rc;
         }
         const double t1 = now_us();
         if (i >= 0) us[i] = t1 - t0;

@@ -1,5 +1,5 @@
 // Internal: the device-side copy loop (the "copy" phase of Sec. III-B2 executed
-// by compute units) used by both the one-shot and the resident kernel.
+// by compute units) used by both the one-shot and the armed kernels.
 //
 // One tile = a contiguous run of the item's body, read once with 16-byte
 // vector loads (lane l of a wavefront reads bytes 16*l .. 16*l+15 of each
@@ -146,4 +146,59 @@ __device__ __forceinline__ void dl_move_tile(const char *src, char *const (&dsts
     } else {
         dl_copy_narrow<uint8_t, FAN>(src, dsts, k, off, n, tid, nthr);
     }
+}
+
+// ------------------------------------------------ items and lists on the device
+
+__device__ __forceinline__ uint64_t dl_uniform64(uint64_t v)
+{
+    uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return ((uint64_t)hi << 32) | lo;
+}
+
+template <bool NT>
+__device__ __forceinline__ void dl_run_item(const dl_plain_item &it, uint64_t tile, uint32_t tile_bytes)
+{
+    char *d[1] = {(char *)dl_uniform64((uint64_t)it.dst)};
+    dl_move_tile<1, NT>((const char *)dl_uniform64((uint64_t)it.src), d, 1u, dl_uniform64(it.bytes), tile, tile_bytes,
+                        threadIdx.x, blockDim.x);
+}
+
+template <bool NT>
+__device__ __forceinline__ void dl_run_item(const dl_fused_item &it, uint64_t tile, uint32_t tile_bytes)
+{
+    char *d[DL_FAN];
+#pragma unroll
+    for (int j = 0; j < DL_FAN; ++j) d[j] = (char *)dl_uniform64((uint64_t)it.dst[j]);
+    dl_move_tile<DL_FAN, NT>((const char *)dl_uniform64((uint64_t)it.src), d, __builtin_amdgcn_readfirstlane(it.k),
+                             dl_uniform64(it.bytes), tile, tile_bytes, threadIdx.x, blockDim.x);
+}
+
+template <class Item, int NMAX>
+struct dl_klist {
+    uint32_t n;
+    uint32_t tile_bytes;
+    uint32_t tile_end[NMAX];  // inclusive prefix sum of tiles per item
+    Item item[NMAX];
+};
+
+// Global tile b of a list: find its item with one wavefront ballot over the
+// prefix sums (item index = number of items whose last tile lies before b),
+// then move that tile.  b must be uniform across the workgroup.
+template <bool NT, class Item, int NMAX>
+__device__ __forceinline__ void dl_run_tile(const dl_klist<Item, NMAX> &p, uint32_t b)
+{
+    const uint32_t lane = threadIdx.x & 63u;
+    uint32_t d = 0;
+#pragma unroll
+    for (int base = 0; base < NMAX; base += 64) {
+        const uint32_t idx = base + lane;
+        const uint32_t e = (idx < p.n) ? p.tile_end[idx < NMAX ? idx : 0] : 0xFFFFFFFFu;
+        d += (uint32_t)__popcll(__ballot(e <= b));
+    }
+    d = __builtin_amdgcn_readfirstlane(d);
+    if (d >= p.n) return;
+    const uint32_t first = d ? p.tile_end[d - 1] : 0u;
+    dl_run_item<NT>(p.item[d], (uint64_t)(b - first), p.tile_bytes);
 }

@@ -17,77 +17,18 @@
 
 // ------------------------------------------------------------------- kernels
 
-__device__ __forceinline__ uint64_t dl_uniform64(uint64_t v)
-{
-    uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
-    uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
-    return ((uint64_t)hi << 32) | lo;
-}
-
-template <bool NT>
-__device__ __forceinline__ void dl_run_item(const dl_plain_item &it, uint64_t tile, uint32_t tile_bytes)
-{
-    char *d[1] = {(char *)dl_uniform64((uint64_t)it.dst)};
-    dl_move_tile<1, NT>((const char *)dl_uniform64((uint64_t)it.src), d, 1u, dl_uniform64(it.bytes), tile, tile_bytes,
-                        threadIdx.x, blockDim.x);
-}
-
-template <bool NT>
-__device__ __forceinline__ void dl_run_item(const dl_fused_item &it, uint64_t tile, uint32_t tile_bytes)
-{
-    char *d[DL_FAN];
-#pragma unroll
-    for (int j = 0; j < DL_FAN; ++j) d[j] = (char *)dl_uniform64((uint64_t)it.dst[j]);
-    dl_move_tile<DL_FAN, NT>((const char *)dl_uniform64((uint64_t)it.src), d, __builtin_amdgcn_readfirstlane(it.k),
-                             dl_uniform64(it.bytes), tile, tile_bytes, threadIdx.x, blockDim.x);
-}
-
-template <class Item, int NMAX>
-struct dl_klist {
-    uint32_t n;
-    uint32_t tile_bytes;
-    uint32_t tile_end[NMAX];  // inclusive prefix sum of tiles per item
-    Item item[NMAX];
-};
-
 template <class Item, int NMAX, bool NT>
 __global__ void __launch_bounds__(512) dl_exec_list_kernel(const dl_klist<Item, NMAX> p)
 {
-    const uint32_t b = blockIdx.x;
-    const uint32_t lane = threadIdx.x & 63u;
-    // item index = number of items whose last tile lies before b
-    uint32_t d = 0;
-#pragma unroll
-    for (int base = 0; base < NMAX; base += 64) {
-        const uint32_t idx = base + lane;
-        const uint32_t e = (idx < p.n) ? p.tile_end[idx < NMAX ? idx : 0] : 0xFFFFFFFFu;
-        d += (uint32_t)__popcll(__ballot(e <= b));
-    }
-    d = __builtin_amdgcn_readfirstlane(d);
-    if (d >= p.n) return;
-    const uint32_t first = d ? p.tile_end[d - 1] : 0u;
-    dl_run_item<NT>(p.item[d], (uint64_t)(b - first), p.tile_bytes);
+    dl_run_tile<NT>(p, blockIdx.x);
 }
 
 // Same, with a capped grid: workgroup b takes tiles b, b + grid, b + 2 grid, ...
 template <class Item, int NMAX, bool NT>
 __global__ void __launch_bounds__(512) dl_exec_list_strided_kernel(const dl_klist<Item, NMAX> p)
 {
-    const uint32_t lane = threadIdx.x & 63u;
     const uint32_t total = p.tile_end[p.n - 1];
-    for (uint32_t b = blockIdx.x; b < total; b += gridDim.x) {
-        uint32_t d = 0;
-#pragma unroll
-        for (int base = 0; base < NMAX; base += 64) {
-            const uint32_t idx = base + lane;
-            const uint32_t e = (idx < p.n) ? p.tile_end[idx < NMAX ? idx : 0] : 0xFFFFFFFFu;
-            d += (uint32_t)__popcll(__ballot(e <= b));
-        }
-        d = __builtin_amdgcn_readfirstlane(d);
-        if (d >= p.n) return;
-        const uint32_t first = d ? p.tile_end[d - 1] : 0u;
-        dl_run_item<NT>(p.item[d], (uint64_t)(b - first), p.tile_bytes);
-    }
+    for (uint32_t b = blockIdx.x; b < total; b += gridDim.x) dl_run_tile<NT>(p, b);
 }
 
 template <class Item, bool NT>
@@ -98,6 +39,113 @@ __global__ void __launch_bounds__(512) dl_exec_table_kernel(const Item *__restri
     if (b >= n) return;
     const Item it = items[b];
     dl_run_item<NT>(it, 0, tile_bytes);
+}
+
+// ------------------------------------------------------------ armed kernels
+//
+// The compute-unit analogue of a poll command queued in front of the copies
+// (Sec. IV-E): the kernel is enqueued ahead of time, its workgroups wait until
+// the doorbell word in host-coherent memory reaches their ticket, then copy.
+// No workgroup ever waits for another one to make progress, and every wait is
+// bounded by a wall-clock limit, so every wave leaves the kernel.
+
+enum : uint32_t { DL_GO_WAIT = 0, DL_GO_RUN = 1, DL_GO_SKIP = 2 };
+
+template <typename T>
+__device__ __forceinline__ T dl_ld_sys(const T *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
+// Returns DL_GO_RUN once the doorbell has been rung for this ticket, DL_GO_SKIP
+// if the request was cancelled or the limit ran out.  Uniform over the workgroup.
+__device__ __forceinline__ uint32_t dl_arm_wait(const dl_arm &a)
+{
+    __shared__ uint32_t s_go;
+    if (threadIdx.x == 0) {
+        uint32_t go = DL_GO_SKIP;
+        const uint64_t t0 = wall_clock64();
+        if (blockIdx.x == 0)
+            __hip_atomic_store(a.armed, a.ticket, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        if (a.direct || blockIdx.x == 0) {
+            // poll the host doorbell (uncached system-scope loads over the host link)
+            for (uint32_t spins = 1;; ++spins) {
+                const uint64_t cancel = dl_ld_sys(a.bell + 1);
+                const uint64_t bell = dl_ld_sys(a.bell);
+                if (cancel >= a.ticket) break;
+                if (bell >= a.ticket) {
+                    go = DL_GO_RUN;
+                    break;
+                }
+                if ((spins & 3u) == 0 && (uint64_t)wall_clock64() - t0 > a.limit_ticks) break;
+                if (spins >= a.max_spins) break;
+                if (blockIdx.x) __builtin_amdgcn_s_sleep(8);
+            }
+            if (!a.direct)
+                __hip_atomic_store(a.go, (a.ticket << 2) | go, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        } else {
+            // wait for workgroup 0 to pass the word on through device memory
+            for (uint32_t spins = 1;; ++spins) {
+                const uint64_t g = __hip_atomic_load(a.go, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if ((g >> 2) == a.ticket) {
+                    go = (uint32_t)(g & 3u);
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(4);
+                if ((spins & 15u) == 0 && (uint64_t)wall_clock64() - t0 > a.limit_ticks + a.margin_ticks) break;
+                if (spins >= a.max_spins) break;
+            }
+        }
+        s_go = go;
+    }
+    __syncthreads();
+    const uint32_t go = s_go;
+    // everything written before the doorbell was rung (the sources) is visible from here on
+    if (go == DL_GO_RUN) __atomic_thread_fence(__ATOMIC_ACQUIRE);
+    return go;
+}
+
+// Count this workgroup in; the last one to arrive publishes the completion word.
+__device__ __forceinline__ void dl_arm_finish(const dl_arm &a, uint32_t go)
+{
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        __atomic_thread_fence(__ATOMIC_RELEASE);  // system scope: this workgroup's stores
+        const uint32_t add = 1u + (go == DL_GO_RUN ? 0u : 0x10000u);
+        const uint32_t old = __hip_atomic_fetch_add(a.arrive, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if ((old & 0xFFFFu) == gridDim.x - 1u) {
+            const uint32_t skipped = (old >> 16) + (add >> 16);
+            __hip_atomic_store(a.arrive, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __atomic_thread_fence(__ATOMIC_ACQUIRE);
+            __hip_atomic_store(a.done, a.ticket | (skipped ? DL_DONE_SKIPPED : 0ull), __ATOMIC_RELEASE,
+                               __HIP_MEMORY_SCOPE_SYSTEM);
+        }
+    }
+}
+
+template <class Item, int NMAX>
+__global__ void __launch_bounds__(512) dl_armed_list_kernel(const dl_klist<Item, NMAX> p, const dl_arm a)
+{
+    const uint32_t go = dl_arm_wait(a);
+    if (go == DL_GO_RUN) {
+        const uint32_t total = p.tile_end[p.n - 1];
+        for (uint32_t b = blockIdx.x; b < total; b += gridDim.x) dl_run_tile<false>(p, b);
+    }
+    dl_arm_finish(a, go);
+}
+
+template <class Item>
+__global__ void __launch_bounds__(512) dl_armed_table_kernel(const Item *__restrict__ items, uint32_t n,
+                                                             uint32_t tile_bytes, const dl_arm a)
+{
+    const uint32_t go = dl_arm_wait(a);
+    if (go == DL_GO_RUN) {
+        for (uint32_t b = blockIdx.x; b < n; b += gridDim.x) {
+            const Item it = items[b];
+            dl_run_item<false>(it, 0, tile_bytes);
+        }
+    }
+    dl_arm_finish(a, go);
 }
 
 // ---------------------------------------------------------------- host side
@@ -122,8 +170,18 @@ struct ring_t {
 inline uint32_t item_k(const dl_plain_item &) { return 1; }
 inline uint32_t item_k(const dl_fused_item &it) { return it.k; }
 
+constexpr uint32_t ARMED_DIRECT_MAX = 32;  // up to this many workgroups all poll the host doorbell themselves
+
+uint32_t armed_grid(uint64_t tiles)
+{
+    uint32_t cap = g_dl.cfg.armed_blocks ? g_dl.cfg.armed_blocks : 4u * (uint32_t)(g_dl.num_cu > 0 ? g_dl.num_cu : 256);
+    if (cap > 32768u) cap = 32768u;  // the arrival counter keeps 16 bits for the count
+    return (uint32_t)(tiles < cap ? tiles : cap);
+}
+
 template <class Item, int NMAX>
-int launch_klist(const Item *items, size_t n, const uint64_t *tile_end, const dl_launch_shape &sh, hipStream_t stream)
+int launch_klist(const Item *items, size_t n, const uint64_t *tile_end, const dl_launch_shape &sh, hipStream_t stream,
+                 const dl_arm *arm)
 {
     dl_klist<Item, NMAX> p;
     p.n = (uint32_t)n;
@@ -133,7 +191,12 @@ int launch_klist(const Item *items, size_t n, const uint64_t *tile_end, const dl
         p.item[i] = items[i];
     }
     const uint32_t grid = (uint32_t)tile_end[n - 1];
-    if (sh.max_blocks && grid > sh.max_blocks) {
+    if (arm) {
+        dl_arm a = *arm;
+        const uint32_t g = armed_grid(grid);
+        a.direct = g <= ARMED_DIRECT_MAX ? 1u : 0u;
+        hipLaunchKernelGGL((dl_armed_list_kernel<Item, NMAX>), dim3(g), dim3(sh.block_threads), 0, stream, p, a);
+    } else if (sh.max_blocks && grid > sh.max_blocks) {
         if (sh.nontemporal)
             hipLaunchKernelGGL((dl_exec_list_strided_kernel<Item, NMAX, true>), dim3(sh.max_blocks),
                                dim3(sh.block_threads), 0, stream, p);
@@ -160,10 +223,20 @@ inline void advance(dl_fused_item &it, uint64_t off)
 }
 
 template <class Item>
-int launch_table(const Item *items, size_t n, const dl_launch_shape &sh, hipStream_t stream)
+int launch_table(const Item *items, size_t n, dl_launch_shape sh, hipStream_t stream, const dl_arm *arm)
 {
     if (!g_ring.base) return DL_ERR_STATE;
     const size_t cap = RING_SLOT_BYTES / sizeof(Item);
+    if (arm) {
+        // an armed request is exactly one kernel: grow the tile until the cut list fits one ring slot
+        for (;;) {
+            uint64_t m = 0;
+            for (size_t i = 0; i < n; ++i) m += (items[i].bytes + sh.tile_bytes - 1) / sh.tile_bytes;
+            if (m <= cap) break;
+            if (sh.tile_bytes >= (1u << 30)) return DL_ERR_INVALID;
+            sh.tile_bytes *= 2;
+        }
+    }
     size_t i = 0;
     uint64_t off = 0;  // progress inside items[i]
     while (i < n) {
@@ -185,7 +258,13 @@ int launch_table(const Item *items, size_t n, const dl_launch_shape &sh, hipStre
             off += it.bytes;
         }
         if (m == 0) break;
-        if (sh.nontemporal)
+        if (arm) {
+            dl_arm a = *arm;
+            const uint32_t g = armed_grid(m);
+            a.direct = g <= ARMED_DIRECT_MAX ? 1u : 0u;
+            hipLaunchKernelGGL((dl_armed_table_kernel<Item>), dim3(g), dim3(sh.block_threads), 0, stream, slot,
+                               (uint32_t)m, sh.tile_bytes, a);
+        } else if (sh.nontemporal)
             hipLaunchKernelGGL((dl_exec_table_kernel<Item, true>), dim3((uint32_t)m), dim3(sh.block_threads), 0,
                                stream, slot, (uint32_t)m, sh.tile_bytes);
         else
@@ -199,8 +278,9 @@ int launch_table(const Item *items, size_t n, const dl_launch_shape &sh, hipStre
 }
 
 template <class Item>
-int exec_list(const Item *items, size_t n, hipStream_t stream)
+int exec_list(const Item *items, size_t n, hipStream_t stream, const dl_arm *arm, bool *launched)
 {
+    *launched = false;
     if (n == 0) return DL_OK;
     uint64_t total = 0, biggest = 0;
     uint32_t kmax = 1;
@@ -224,10 +304,12 @@ int exec_list(const Item *items, size_t n, hipStream_t stream)
             if (acc < (1ull << 30)) break;
             sh.tile_bytes *= 2;  // keep the grid inside the launch limit
         }
-        if (n <= (size_t)NMAX_SMALL) return launch_klist<Item, NMAX_SMALL>(items, n, tile_end, sh, stream);
-        return launch_klist<Item, NBIG>(items, n, tile_end, sh, stream);
+        *launched = true;
+        if (n <= (size_t)NMAX_SMALL) return launch_klist<Item, NMAX_SMALL>(items, n, tile_end, sh, stream, arm);
+        return launch_klist<Item, NBIG>(items, n, tile_end, sh, stream, arm);
     }
-    return launch_table(items, n, sh, stream);
+    *launched = true;
+    return launch_table(items, n, sh, stream, arm);
 }
 
 uint32_t floor_pow2(uint64_t v)
@@ -264,8 +346,14 @@ dl_launch_shape dl_choose_shape(uint64_t src_bytes, uint64_t max_item_bytes, uin
     return sh;
 }
 
-int dl_exec_plain(const dl_plain_item *items, size_t n, hipStream_t stream) { return exec_list(items, n, stream); }
-int dl_exec_fused(const dl_fused_item *items, size_t n, hipStream_t stream) { return exec_list(items, n, stream); }
+int dl_exec_plain(const dl_plain_item *items, size_t n, hipStream_t stream, const dl_arm *arm, bool *launched)
+{
+    return exec_list(items, n, stream, arm, launched);
+}
+int dl_exec_fused(const dl_fused_item *items, size_t n, hipStream_t stream, const dl_arm *arm, bool *launched)
+{
+    return exec_list(items, n, stream, arm, launched);
+}
 
 int dl_exec_init()
 {

@@ -38,14 +38,33 @@ struct dl_launch_shape {
     bool nontemporal;
 };
 
-// dl_exec.hip: one-shot execution of a lowered list on a stream.
-int dl_exec_plain(const dl_plain_item *items, size_t n, hipStream_t stream);
-int dl_exec_fused(const dl_fused_item *items, size_t n, hipStream_t stream);
+// What an armed (prelaunched) kernel needs to wait for its doorbell and to
+// report completion.  Passed by value in the kernel arguments.
+struct dl_arm {
+    const uint64_t *bell;  // host-coherent: bell[0] = doorbell, bell[1] = cancel; both only ever grow
+    uint64_t *done;        // host-coherent: completion word of this ticket's slot
+    uint64_t *armed;       // host-coherent: "resident and polling" word of this ticket's slot
+    uint64_t *go;          // device: fan-out flag of this ticket's slot
+    uint32_t *arrive;      // device: arrival counter of this ticket's slot
+    uint64_t ticket;
+    uint64_t limit_ticks;   // give up this long after becoming resident
+    uint64_t margin_ticks;  // extra time a non-polling workgroup grants the polling one
+    uint32_t direct;        // 1: every workgroup polls the host doorbell itself
+    uint32_t max_spins;     // backstop that does not depend on the clock: give up after this many polls
+};
+constexpr uint64_t DL_DONE_SKIPPED = 1ull << 63;  // set in the completion word when nothing was copied
+
+// dl_exec.hip: execution of a lowered list on a stream.  With arm == nullptr one
+// kernel launch per call (more for very long lists).  With arm != nullptr the
+// launch is an armed kernel: its workgroups first wait for the doorbell.
+// *launched tells whether a kernel was enqueued (empty requests enqueue none).
+int dl_exec_plain(const dl_plain_item *items, size_t n, hipStream_t stream, const dl_arm *arm, bool *launched);
+int dl_exec_fused(const dl_fused_item *items, size_t n, hipStream_t stream, const dl_arm *arm, bool *launched);
 int dl_exec_init();
 int dl_exec_shutdown();
 dl_launch_shape dl_choose_shape(uint64_t src_bytes, uint64_t max_item_bytes, uint32_t max_k);
 
-// dl_prelaunch.hip: the resident kernel and its doorbell.
-int dl_resident_submit_plain(const dl_plain_item *items, size_t n);
-int dl_resident_submit_fused(const dl_fused_item *items, size_t n);
-bool dl_resident_running();
+// dl_prelaunch.hip: tickets, doorbell and completion words of armed requests.
+bool dl_armed_ready();
+int dl_armed_begin(dl_arm *arm, hipStream_t *stream);  // next ticket's words; picks the library stream if *stream is null
+void dl_armed_commit();                                // the ticket of the last dl_armed_begin was launched

@@ -1,26 +1,17 @@
-// The resident ("prelaunched") executor: the compute-unit analogue of
-// pre-enqueueing a poll command in front of the copies (Sec. IV-E).  One kernel
-// is launched ahead of time and stays resident; a request is then triggered by a
-// single 8-byte write into host-coherent memory, so no launch sits on the
-// critical path.
+// Prelaunched ("armed") requests: tickets, the doorbell and the completion
+// words (Sec. IV-E: copies pre-enqueued behind a poll, triggered later by a
+// plain memory write, so that the launch is off the critical path).
 //
-// Protocol
-//   host   : writes the command into ring slot seq % SLOTS, then release-stores
-//            the slot's `ready` word = (seq << 16) | command length.  That store
-//            is the doorbell.
-//   leader : workgroup 0 polls the ready word of the slot it expects next
-//            (system-scope loads from uncached host memory), copies the command
-//            into device memory and publishes (seq, active workgroups) through an
-//            agent-scope flag.
-//   workers: thread 0 of every other workgroup polls that flag; the first
-//            `active` workgroups stride over the command's tiles.
-//   finish : each active workgroup release-fences and bumps an arrival counter;
-//            the leader waits for all arrivals and release-stores seq into the
-//            completion word in host memory, which dl_wait() spins on.
-// Requests are executed one at a time in ticket order.  Every spin is bounded by
-// a wall-clock limit, so every wave leaves the kernel: on the quit flag, after
-// the idle limit without a doorbell, or after the hard limit.
-#include "dl_device.h"
+// Each request issued in prelaunch mode is its own kernel, enqueued at once on
+// the caller's stream (or the library's non-blocking stream).  Its workgroups
+// poll the doorbell in host-coherent memory until it reaches the request's
+// ticket, copy, and the last workgroup to finish writes the ticket into the
+// request's completion word, again in host-coherent memory.  dl_trigger() is
+// one 8-byte store; dl_wait() spins on the completion word.
+//
+// A wave never lives longer than the arm limit (plus the copy itself): a
+// request that is not triggered in time gives up without copying and reports
+// that.  Nothing stays resident between requests.
 #include "dl_internal.h"
 
 #include <immintrin.h>
@@ -29,278 +20,29 @@
 
 namespace {
 
-constexpr uint32_t SLOTS = 8;
-constexpr uint32_t SLOT_BYTES = 3072;
-constexpr uint32_t HDR_BYTES = 64;
-constexpr uint32_t RES_THREADS = 256;
-constexpr uint32_t MAX_PLAIN = 64, MAX_FUSED = 32;
-constexpr size_t TABLE_BYTES = 1u << 20;  // per slot, for lists longer than a slot holds
+constexpr uint32_t SLOTS = 64;  // requests that may be armed and not yet completed
 
-enum : uint32_t { KIND_PLAIN_LIST = 0, KIND_FUSED_LIST = 1, KIND_PLAIN_TABLE = 2, KIND_FUSED_TABLE = 3 };
-enum : uint32_t { ST_NONE = 0, ST_RUNNING = 1, ST_EXITED = 2, ST_EXITED_IDLE = 3, ST_EXITED_STUCK = 4 };
-
-constexpr uint64_t GO_EXIT = ~0ull;
-
-// Command header; followed by tile_end[n] (padded to 16 bytes) and item[n], or by nothing for tables.
-struct res_hdr {
-    uint64_t ready;  // host slot only: (seq << 16) | 16-byte vectors to copy
-    uint32_t kind;
-    uint32_t n;
-    uint32_t tile_bytes;
-    uint32_t total_tiles;
-    uint32_t nontemporal;
-    uint32_t active;
-    uint64_t table;  // items of a table command (pinned host memory)
-    uint32_t vecs;
-    uint32_t pad[5];
-};
-static_assert(sizeof(res_hdr) == HDR_BYTES, "header is one 64-byte line");
-
-struct res_host {  // pinned, host-coherent
-    uint64_t done;   // device -> host: last completed ticket
-    uint32_t state;  // device -> host
-    uint32_t quit;   // host -> device
-    uint8_t pad[64 - 16];
-    uint8_t slot[SLOTS][SLOT_BYTES];
+struct arm_host {  // pinned, host-coherent
+    uint64_t bell;    // host -> device: every ticket <= bell may run
+    uint64_t cancel;  // host -> device: every ticket <= cancel gives up
+    uint64_t pad[6];
+    uint64_t done[SLOTS];   // device -> host: ticket (| DL_DONE_SKIPPED) of the last request finished in the slot
+    uint64_t armed[SLOTS];  // device -> host: ticket of the last request seen resident in the slot
 };
 
-struct res_dev {  // device memory
-    uint64_t go;  // (seq << 20) | active, or GO_EXIT
-    uint32_t arrive;
-    uint32_t pad[13];
-    uint8_t cmd[SLOT_BYTES];
+struct arm_dev {  // device memory
+    uint64_t go[SLOTS];
+    uint32_t arrive[SLOTS];
 };
 
-__host__ __device__ inline uint32_t items_offset(uint32_t n) { return HDR_BYTES + ((n * 4u + 15u) & ~15u); }
-
-// ------------------------------------------------------------------ device
-
-template <typename T>
-__device__ __forceinline__ T ld_sys(const T *p)
-{
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-}
-template <typename T>
-__device__ __forceinline__ T ld_agent(const T *p)
-{
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-template <bool NT>
-__device__ __forceinline__ void res_run_tile(const uint8_t *cmd, uint32_t kind, uint32_t n, uint32_t tile_bytes,
-                                             uint32_t tile, uint32_t tid)
-{
-    // cmd is the workgroup's LDS copy of the command
-    const uint32_t *tile_end = (const uint32_t *)(cmd + HDR_BYTES);
-    const uint32_t lane = tid & 63u;
-    uint32_t d = 0;
-    for (uint32_t base = 0; base < n; base += 64) {
-        const uint32_t idx = base + lane;
-        const uint32_t e = idx < n ? tile_end[idx] : 0xFFFFFFFFu;
-        d += (uint32_t)__popcll(__ballot(e <= tile));
-    }
-    d = __builtin_amdgcn_readfirstlane(d);
-    if (d >= n) return;
-    const uint32_t first = d ? tile_end[d - 1] : 0u;
-    const uint64_t t = tile - first;
-    if (kind == KIND_PLAIN_LIST) {
-        const dl_plain_item *it = (const dl_plain_item *)(cmd + items_offset(n)) + d;
-        char *dst[1] = {it->dst};
-        dl_move_tile<1, NT>(it->src, dst, 1u, it->bytes, t, tile_bytes, tid, RES_THREADS);
-    } else {
-        const dl_fused_item *it = (const dl_fused_item *)(cmd + items_offset(n)) + d;
-        char *dst[DL_FAN];
-#pragma unroll
-        for (int j = 0; j < DL_FAN; ++j) dst[j] = it->dst[j];
-        dl_move_tile<DL_FAN, NT>(it->src, dst, it->k, it->bytes, t, tile_bytes, tid, RES_THREADS);
-    }
-}
-
-__device__ __forceinline__ uint64_t uni64(uint64_t v)
-{
-    return ((uint64_t)__builtin_amdgcn_readfirstlane((uint32_t)(v >> 32)) << 32) |
-           __builtin_amdgcn_readfirstlane((uint32_t)v);
-}
-
-template <bool NT>
-__device__ __forceinline__ void res_run_table_item(const res_hdr *h, uint32_t idx, uint32_t tid)
-{
-    // one pre-cut item per step, read straight from the pinned table
-    if (h->kind == KIND_PLAIN_TABLE) {
-        const dl_plain_item it = ((const dl_plain_item *)h->table)[idx];
-        char *dst[1] = {(char *)uni64((uint64_t)it.dst)};
-        dl_move_tile<1, NT>((const char *)uni64((uint64_t)it.src), dst, 1u, uni64(it.bytes), 0, h->tile_bytes, tid,
-                            RES_THREADS);
-    } else {
-        const dl_fused_item it = ((const dl_fused_item *)h->table)[idx];
-        char *dst[DL_FAN];
-#pragma unroll
-        for (int j = 0; j < DL_FAN; ++j) dst[j] = (char *)uni64((uint64_t)it.dst[j]);
-        dl_move_tile<DL_FAN, NT>((const char *)uni64((uint64_t)it.src), dst, __builtin_amdgcn_readfirstlane(it.k),
-                                 uni64(it.bytes), 0, h->tile_bytes, tid, RES_THREADS);
-    }
-}
-
-// Execute this workgroup's share of the command held in LDS.
-__device__ __forceinline__ void res_execute(const uint8_t *cmd, uint32_t block, uint32_t active, uint32_t tid)
-{
-    const res_hdr *h = (const res_hdr *)cmd;
-    const uint32_t kind = h->kind, n = h->n, tile_bytes = h->tile_bytes, total = h->total_tiles;
-    const bool nt = h->nontemporal != 0;
-    if (kind == KIND_PLAIN_LIST || kind == KIND_FUSED_LIST) {
-        for (uint32_t t = block; t < total; t += active) {
-            if (nt)
-                res_run_tile<true>(cmd, kind, n, tile_bytes, t, tid);
-            else
-                res_run_tile<false>(cmd, kind, n, tile_bytes, t, tid);
-        }
-    } else {
-        for (uint32_t t = block; t < n; t += active) {
-            if (nt)
-                res_run_table_item<true>(h, t, tid);
-            else
-                res_run_table_item<false>(h, t, tid);
-        }
-    }
-}
-
-__global__ void __launch_bounds__(RES_THREADS) dl_resident_kernel(res_host *host, res_dev *dev, uint64_t idle_ticks,
-                                                                   uint64_t hard_ticks)
-{
-    __shared__ __attribute__((aligned(16))) uint8_t s_cmd[SLOT_BYTES];
-    __shared__ uint64_t s_word;
-    const uint32_t tid = threadIdx.x;
-    const uint32_t block = blockIdx.x;
-
-    if (block == 0) {
-        // ------------------------------------------------------------ leader
-        if (tid == 0) __hip_atomic_store(&host->state, (uint32_t)ST_RUNNING, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
-        for (uint64_t seq = 1;; ++seq) {
-            const res_hdr *slot = (const res_hdr *)host->slot[seq % SLOTS];
-            if (tid == 0) {
-                const uint64_t t0 = wall_clock64();
-                uint64_t word;
-                uint32_t spins = 0;
-                for (;;) {
-                    const uint64_t w = ld_sys(&slot->ready);
-                    if ((w >> 16) == seq) {
-                        word = w & 0xFFFFu;
-                        break;
-                    }
-                    if (ld_sys(&host->quit)) {
-                        word = GO_EXIT;
-                        break;
-                    }
-                    if ((++spins & 15u) == 0 && wall_clock64() - t0 > idle_ticks) {
-                        word = GO_EXIT - 1;
-                        break;
-                    }
-                }
-                s_word = word;
-            }
-            __syncthreads();
-            const uint64_t word = s_word;
-            if (word >= GO_EXIT - 1) {
-                if (tid == 0) {
-                    __hip_atomic_store(&dev->go, GO_EXIT, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-                    __hip_atomic_store(&host->state, word == GO_EXIT ? (uint32_t)ST_EXITED : (uint32_t)ST_EXITED_IDLE,
-                                       __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
-                }
-                return;
-            }
-            // everything written before the doorbell (command and source data) is visible from here on
-            __atomic_thread_fence(__ATOMIC_ACQUIRE);  // system scope
-            const uint32_t vecs = (uint32_t)word;
-            if (tid < vecs) {
-                const dl_u32x4 v = ((const DL_GLOBAL dl_u32x4 *)(uint64_t)slot)[tid];
-                ((dl_u32x4 *)s_cmd)[tid] = v;
-                ((DL_GLOBAL dl_u32x4 *)(uint64_t)dev->cmd)[tid] = v;
-            }
-            __syncthreads();
-            const uint32_t active = ((const res_hdr *)s_cmd)->active;
-            if (tid == 0)
-                __hip_atomic_store(&dev->go, (seq << 20) | active, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-            res_execute(s_cmd, 0, active, tid);
-            __syncthreads();
-            if (tid == 0) {
-                __atomic_thread_fence(__ATOMIC_RELEASE);  // system scope: this workgroup's stores
-                __hip_atomic_fetch_add(&dev->arrive, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                const uint64_t t0 = wall_clock64();
-                uint32_t spins = 0;
-                bool stuck = false;
-                while (ld_agent(&dev->arrive) != active) {
-                    if ((++spins & 1023u) == 0 && wall_clock64() - t0 > hard_ticks) {
-                        stuck = true;
-                        break;
-                    }
-                }
-                __hip_atomic_store(&dev->arrive, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __atomic_thread_fence(__ATOMIC_ACQUIRE);
-                s_word = stuck ? 1 : 0;
-                if (!stuck) __hip_atomic_store(&host->done, seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
-            }
-            __syncthreads();
-            if (s_word) {  // a workgroup never arrived: give up rather than spin for ever
-                if (tid == 0) {
-                    __hip_atomic_store(&dev->go, GO_EXIT, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-                    __hip_atomic_store(&host->state, (uint32_t)ST_EXITED_STUCK, __ATOMIC_RELEASE,
-                                       __HIP_MEMORY_SCOPE_SYSTEM);
-                }
-                return;
-            }
-            __syncthreads();
-        }
-    }
-
-    // ---------------------------------------------------------------- workers
-    uint64_t seen = 0;  // last sequence number this workgroup has dealt with
-    for (;;) {
-        if (tid == 0) {
-            const uint64_t t0 = wall_clock64();
-            uint64_t g;
-            uint32_t spins = 0;
-            for (;;) {
-                g = ld_agent(&dev->go);
-                if (g == GO_EXIT || (g >> 20) > seen) break;
-                __builtin_amdgcn_s_sleep(2);
-                if ((++spins & 255u) == 0 && wall_clock64() - t0 > idle_ticks + hard_ticks) {
-                    g = GO_EXIT;  // the leader is gone or stuck
-                    break;
-                }
-            }
-            s_word = g;
-        }
-        __syncthreads();
-        const uint64_t g = s_word;
-        __syncthreads();
-        if (g == GO_EXIT) return;
-        seen = g >> 20;
-        const uint32_t active = (uint32_t)(g & 0xFFFFFu);
-        if (block >= active) continue;
-        __atomic_thread_fence(__ATOMIC_ACQUIRE);  // system scope: command and source data
-        const uint32_t vecs = ((const DL_GLOBAL res_hdr *)(uint64_t)dev->cmd)->vecs;
-        if (tid < vecs) ((dl_u32x4 *)s_cmd)[tid] = ((const DL_GLOBAL dl_u32x4 *)(uint64_t)dev->cmd)[tid];
-        __syncthreads();
-        res_execute(s_cmd, block, active, tid);
-        __syncthreads();
-        if (tid == 0) {
-            __atomic_thread_fence(__ATOMIC_RELEASE);  // system scope: this workgroup's stores
-            __hip_atomic_fetch_add(&dev->arrive, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-    }
-}
-
-// -------------------------------------------------------------------- host
-
-struct res_state {
+struct arm_state {
     bool started = false;
-    res_host *host = nullptr;  // pinned
-    res_dev *dev = nullptr;
-    char *tables = nullptr;  // pinned, SLOTS x TABLE_BYTES
+    arm_host *host = nullptr;
+    arm_dev *dev = nullptr;
     hipStream_t stream = nullptr;
-    uint32_t blocks = 0;
     uint64_t seq = 0;  // last ticket issued
-} g_res;
+    uint64_t clock_khz = 100000;
+} g_arm;
 
 uint64_t now_ns()
 {
@@ -309,235 +51,132 @@ uint64_t now_ns()
     return (uint64_t)ts.tv_sec * 1000000000ull + (uint64_t)ts.tv_nsec;
 }
 
-uint32_t host_state() { return __atomic_load_n(&g_res.host->state, __ATOMIC_ACQUIRE); }
-uint64_t host_done() { return __atomic_load_n(&g_res.host->done, __ATOMIC_ACQUIRE); }
+inline uint64_t load_word(const uint64_t *p) { return __atomic_load_n(p, __ATOMIC_ACQUIRE); }
 
-int wait_done(uint64_t ticket, uint64_t timeout_ns)
+// Spin until `word` holds `ticket` or a later one (slots are reused in ticket order).
+int wait_word(const uint64_t *word, uint64_t ticket, uint64_t timeout_ns, uint64_t *seen)
 {
-    if (host_done() >= ticket) return DL_OK;
     const uint64_t t0 = now_ns();
     for (uint32_t spins = 1;; ++spins) {
-        if (host_done() >= ticket) return DL_OK;
-        _mm_pause();
-        if ((spins & 255u) == 0) {
-            const uint32_t st = host_state();
-            if (st != ST_RUNNING && host_done() < ticket) return DL_ERR_STATE;
-            if (now_ns() - t0 >= timeout_ns) return DL_ERR_TIMEOUT;
+        const uint64_t v = load_word(word);
+        if ((v & ~DL_DONE_SKIPPED) >= ticket) {
+            if (seen) *seen = v;
+            return DL_OK;
         }
         if (timeout_ns == 0) return DL_ERR_TIMEOUT;
+        _mm_pause();
+        if ((spins & 63u) == 0 && now_ns() - t0 >= timeout_ns) return DL_ERR_TIMEOUT;
     }
 }
 
-void release_resources()
-{
-    if (g_res.stream) {
-        (void)hipStreamSynchronize(g_res.stream);
-        (void)hipStreamDestroy(g_res.stream);
-    }
-    if (g_res.dev) (void)hipFree(g_res.dev);
-    if (g_res.host) (void)hipHostFree(g_res.host);
-    if (g_res.tables) (void)hipHostFree(g_res.tables);
-    g_res = res_state{};
-}
-
-inline uint32_t item_k(const dl_plain_item &) { return 1; }
-inline uint32_t item_k(const dl_fused_item &it) { return it.k; }
-inline void advance(dl_plain_item &it, uint64_t off)
-{
-    it.src += off;
-    it.dst += off;
-}
-inline void advance(dl_fused_item &it, uint64_t off)
-{
-    it.src += off;
-    for (uint32_t j = 0; j < it.k; ++j) it.dst[j] += off;
-}
-
-// Wait for ring slot `seq % SLOTS` to be free, fill it through `fill`, ring the doorbell.
-template <class Fill>
-int post(Fill fill)
-{
-    const uint64_t seq = g_res.seq + 1;
-    if (seq > SLOTS) {
-        const int rc = wait_done(seq - SLOTS, 10000000000ull);
-        if (rc != DL_OK) return rc;
-    }
-    uint8_t *slot = g_res.host->slot[seq % SLOTS];
-    res_hdr *h = (res_hdr *)slot;
-    const uint32_t bytes = fill(h, slot, g_res.tables + (seq % SLOTS) * TABLE_BYTES);
-    h->vecs = (bytes + 15u) / 16u;
-    __atomic_store_n(&h->ready, (seq << 16) | h->vecs, __ATOMIC_RELEASE);  // the doorbell
-    g_res.seq = seq;
-    return DL_OK;
-}
-
-template <class Item>
-int submit(const Item *items, size_t n)
-{
-    if (!g_res.started) return DL_ERR_STATE;
-    if (host_state() != ST_RUNNING) return DL_ERR_STATE;
-    constexpr bool fused = sizeof(Item) == sizeof(dl_fused_item);
-    constexpr uint32_t cap = fused ? MAX_FUSED : MAX_PLAIN;
-    uint64_t total = 0, biggest = 0;
-    uint32_t kmax = 1;
-    for (size_t i = 0; i < n; ++i) {
-        total += items[i].bytes;
-        if (items[i].bytes > biggest) biggest = items[i].bytes;
-        if (item_k(items[i]) > kmax) kmax = item_k(items[i]);
-    }
-    if (total == 0) return DL_OK;
-    dl_launch_shape sh = dl_choose_shape(total, biggest, kmax);
-
-    if (n <= cap) {
-        return post([&](res_hdr *h, uint8_t *slot, char *) -> uint32_t {
-            uint32_t *tile_end = (uint32_t *)(slot + HDR_BYTES);
-            uint64_t acc;
-            for (;;) {
-                acc = 0;
-                for (size_t i = 0; i < n; ++i) {
-                    acc += dl_item_tiles(items[i], sh.tile_bytes);
-                    tile_end[i] = (uint32_t)acc;
-                }
-                if (acc < (1ull << 30)) break;
-                sh.tile_bytes *= 2;
-            }
-            memcpy(slot + items_offset((uint32_t)n), items, n * sizeof(Item));
-            h->kind = fused ? KIND_FUSED_LIST : KIND_PLAIN_LIST;
-            h->n = (uint32_t)n;
-            h->tile_bytes = sh.tile_bytes;
-            h->total_tiles = (uint32_t)acc;
-            h->nontemporal = sh.nontemporal ? 1u : 0u;
-            h->active = (uint32_t)(acc < g_res.blocks ? acc : g_res.blocks);
-            h->table = 0;
-            return items_offset((uint32_t)n) + (uint32_t)(n * sizeof(Item));
-        });
-    }
-
-    // long list: cut into one-tile items in the slot's pinned table, one command per table-full
-    const size_t tcap = TABLE_BYTES / sizeof(Item);
-    size_t i = 0;
-    uint64_t off = 0;
-    while (i < n) {
-        int rc = post([&](res_hdr *h, uint8_t *, char *table) -> uint32_t {
-            Item *out = (Item *)table;
-            size_t m = 0;
-            while (i < n && m < tcap) {
-                const uint64_t left = items[i].bytes - off;
-                if (left == 0) {
-                    ++i;
-                    off = 0;
-                    continue;
-                }
-                Item it = items[i];
-                advance(it, off);
-                it.bytes = left < sh.tile_bytes ? left : sh.tile_bytes;
-                out[m++] = it;
-                off += it.bytes;
-            }
-            h->kind = fused ? KIND_FUSED_TABLE : KIND_PLAIN_TABLE;
-            h->n = (uint32_t)m;
-            h->tile_bytes = sh.tile_bytes;
-            h->total_tiles = (uint32_t)m;
-            h->nontemporal = sh.nontemporal ? 1u : 0u;
-            h->active = (uint32_t)(m < g_res.blocks ? (m ? m : 1) : g_res.blocks);
-            h->table = (uint64_t)table;
-            return HDR_BYTES;
-        });
-        if (rc != DL_OK) return rc;
-    }
-    return DL_OK;
-}
+// Upper bound, in ns, on how long an armed kernel can still be on the device
+// once it has started: arm limit + margin + slack for the copy.
+uint64_t drain_ns() { return ((uint64_t)g_dl.cfg.arm_timeout_us + 5000ull) * 1000ull + 2000000000ull; }
 
 }  // namespace
 
-bool dl_resident_running() { return g_res.started && host_state() == ST_RUNNING; }
-int dl_resident_submit_plain(const dl_plain_item *items, size_t n) { return submit(items, n); }
-int dl_resident_submit_fused(const dl_fused_item *items, size_t n) { return submit(items, n); }
+bool dl_armed_ready() { return g_arm.started; }
+
+int dl_armed_begin(dl_arm *arm, hipStream_t *stream)
+{
+    if (!g_arm.started) return DL_ERR_STATE;
+    const uint64_t ticket = g_arm.seq + 1;
+    const uint32_t slot = (uint32_t)(ticket % SLOTS);
+    if (ticket > SLOTS) {
+        // the slot's previous request must have left the device before its words are reused
+        const int rc = wait_word(&g_arm.host->done[slot], ticket - SLOTS, drain_ns(), nullptr);
+        if (rc != DL_OK) return rc;
+    }
+    arm->bell = &g_arm.host->bell;
+    arm->done = &g_arm.host->done[slot];
+    arm->armed = &g_arm.host->armed[slot];
+    arm->go = &g_arm.dev->go[slot];
+    arm->arrive = &g_arm.dev->arrive[slot];
+    arm->ticket = ticket;
+    arm->limit_ticks = (uint64_t)g_dl.cfg.arm_timeout_us * g_arm.clock_khz / 1000ull;
+    arm->margin_ticks = 5000ull * g_arm.clock_khz / 1000ull;  // 5 ms
+    arm->direct = 0;
+    // a poll takes well over 100 ns (a host-link round trip, or a sleep plus a device-memory load)
+    arm->max_spins = (g_dl.cfg.arm_timeout_us + 5000u) * 10u;
+    if (!*stream) *stream = g_arm.stream;
+    return DL_OK;
+}
+
+void dl_armed_commit() { ++g_arm.seq; }
 
 extern "C" {
 
 int dl_prelaunch_start(void)
 {
     if (!g_dl.inited) return DL_ERR_STATE;
-    if (g_res.started) {
-        if (host_state() == ST_RUNNING) return DL_ERR_STATE;  // already running
-        release_resources();                                   // it left by itself: start afresh
-    }
-    uint32_t blocks = g_dl.cfg.resident_blocks ? g_dl.cfg.resident_blocks : (uint32_t)g_dl.num_cu;
-    int per_cu = 0;
-    DL_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, dl_resident_kernel, RES_THREADS, 0));
-    if (blocks < 1 || per_cu < 1 || blocks > (uint32_t)per_cu * (uint32_t)g_dl.num_cu || blocks >= (1u << 20))
-        return DL_ERR_INVALID;  // every workgroup must be resident at once
+    if (g_arm.started) return DL_ERR_STATE;
     int clock_khz = 0;
     DL_HIP(hipDeviceGetAttribute(&clock_khz, hipDeviceAttributeWallClockRate, g_dl.device));
-    if (clock_khz <= 0) clock_khz = 100000;
-
-    DL_HIP(hipHostMalloc((void **)&g_res.host, sizeof(res_host), hipHostMallocCoherent | hipHostMallocMapped));
-    memset(g_res.host, 0, sizeof(res_host));
-    int rc = DL_OK;
-    auto fail = [&](int code) {
-        release_resources();
-        return code;
-    };
-    if (hipHostMalloc((void **)&g_res.tables, SLOTS * TABLE_BYTES, hipHostMallocCoherent | hipHostMallocMapped) !=
-        hipSuccess)
-        return fail(DL_ERR_HIP);
-    if (hipMalloc((void **)&g_res.dev, sizeof(res_dev)) != hipSuccess) return fail(DL_ERR_HIP);
-    if (hipStreamCreateWithFlags(&g_res.stream, hipStreamNonBlocking) != hipSuccess) return fail(DL_ERR_HIP);
-    if (hipMemsetAsync(g_res.dev, 0, sizeof(res_dev), g_res.stream) != hipSuccess) return fail(DL_ERR_HIP);
-    g_res.blocks = blocks;
-    g_res.seq = 0;
-    const uint64_t idle_ticks = (uint64_t)g_dl.cfg.idle_timeout_ms * (uint64_t)clock_khz;
-    const uint64_t hard_ticks = 10000ull * (uint64_t)clock_khz;  // 10 s
-    hipLaunchKernelGGL(dl_resident_kernel, dim3(blocks), dim3(RES_THREADS), 0, g_res.stream, g_res.host, g_res.dev,
-                       idle_ticks, hard_ticks);
-    if (hipGetLastError() != hipSuccess) return fail(DL_ERR_HIP);
-    g_res.started = true;
-    // wait until the leader reports in
-    const uint64_t t0 = now_ns();
-    while (host_state() == ST_NONE) {
-        _mm_pause();
-        if (now_ns() - t0 > 10000000000ull) {
-            rc = DL_ERR_TIMEOUT;
-            break;
-        }
+    g_arm.clock_khz = clock_khz > 0 ? (uint64_t)clock_khz : 100000ull;
+    DL_HIP(hipHostMalloc((void **)&g_arm.host, sizeof(arm_host), hipHostMallocCoherent | hipHostMallocMapped));
+    memset(g_arm.host, 0, sizeof(arm_host));
+    hipError_t e = hipMalloc((void **)&g_arm.dev, sizeof(arm_dev));
+    if (e == hipSuccess) e = hipMemset(g_arm.dev, 0, sizeof(arm_dev));
+    if (e == hipSuccess) e = hipStreamCreateWithFlags(&g_arm.stream, hipStreamNonBlocking);
+    if (e != hipSuccess) {
+        g_dl.last_hip = (int)e;
+        (void)hipGetLastError();
+        if (g_arm.dev) (void)hipFree(g_arm.dev);
+        (void)hipHostFree(g_arm.host);
+        g_arm = arm_state{};
+        return DL_ERR_HIP;
     }
-    if (rc != DL_OK) {
-        __atomic_store_n(&g_res.host->quit, 1u, __ATOMIC_RELEASE);
-        return fail(rc);
-    }
+    g_arm.seq = 0;
+    g_arm.started = true;
     return DL_OK;
 }
 
 int dl_prelaunch_stop(void)
 {
-    if (!g_res.started) return DL_ERR_STATE;
+    if (!g_arm.started) return DL_ERR_STATE;
+    // every request still armed gives up; then wait until all of them have left the device
+    __atomic_store_n(&g_arm.host->cancel, g_arm.seq, __ATOMIC_RELEASE);
     int rc = DL_OK;
-    if (host_state() == ST_RUNNING && g_res.seq) rc = wait_done(g_res.seq, 10000000000ull);
-    __atomic_store_n(&g_res.host->quit, 1u, __ATOMIC_RELEASE);
-    const uint64_t t0 = now_ns();
-    while (host_state() == ST_RUNNING) {
-        _mm_pause();
-        if (now_ns() - t0 > 15000000000ull) {
-            rc = DL_ERR_TIMEOUT;
-            break;
-        }
-    }
-    if (rc != DL_ERR_TIMEOUT) {
-        release_resources();  // the stream drains: the kernel has left
-        if (g_dl.mode == DL_MODE_PRELAUNCH) g_dl.mode = DL_MODE_ONESHOT;
-    }
-    return rc;
+    const uint64_t first = g_arm.seq > SLOTS ? g_arm.seq - SLOTS + 1 : 1;
+    for (uint64_t t = first; t <= g_arm.seq && rc == DL_OK; ++t)
+        rc = wait_word(&g_arm.host->done[t % SLOTS], t, drain_ns(), nullptr);
+    if (rc != DL_OK) return rc;  // words stay allocated: a kernel may still use them
+    (void)hipStreamSynchronize(g_arm.stream);
+    (void)hipStreamDestroy(g_arm.stream);
+    (void)hipFree(g_arm.dev);
+    (void)hipHostFree(g_arm.host);
+    g_arm = arm_state{};
+    if (g_dl.mode == DL_MODE_PRELAUNCH) g_dl.mode = DL_MODE_ONESHOT;
+    return DL_OK;
 }
 
-uint64_t dl_last_ticket(void) { return g_res.seq; }
+uint64_t dl_last_ticket(void) { return g_arm.seq; }
+
+int dl_trigger(uint64_t ticket)
+{
+    if (!g_arm.started) return DL_ERR_STATE;
+    if (ticket == 0 || ticket > g_arm.seq) return DL_ERR_INVALID;
+    if (ticket > g_arm.host->bell) __atomic_store_n(&g_arm.host->bell, ticket, __ATOMIC_RELEASE);  // the doorbell
+    return DL_OK;
+}
+
+int dl_wait_armed(uint64_t ticket, uint64_t timeout_ns)
+{
+    if (!g_arm.started) return DL_ERR_STATE;
+    if (ticket == 0 || ticket > g_arm.seq) return DL_ERR_INVALID;
+    return wait_word(&g_arm.host->armed[ticket % SLOTS], ticket, timeout_ns, nullptr);
+}
 
 int dl_wait(uint64_t ticket, uint64_t timeout_ns)
 {
-    if (!g_res.started) return DL_ERR_STATE;
+    if (!g_arm.started) return DL_ERR_STATE;
     if (ticket == 0) return DL_OK;
-    if (ticket > g_res.seq) return DL_ERR_INVALID;
-    return wait_done(ticket, timeout_ns);
+    if (ticket > g_arm.seq) return DL_ERR_INVALID;
+    uint64_t seen = 0;
+    const int rc = wait_word(&g_arm.host->done[ticket % SLOTS], ticket, timeout_ns, &seen);
+    if (rc != DL_OK) return rc;
+    if ((seen & ~DL_DONE_SKIPPED) == ticket && (seen & DL_DONE_SKIPPED)) return DL_ERR_EXPIRED;
+    return DL_OK;
 }
 
 }  // extern "C"
