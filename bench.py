@@ -163,12 +163,30 @@ def main() -> int:
             row["GBps"] = ag_bytes(B) / row["device_us"] / 1e3
             if B <= MiB:
                 lat = benchaid.time_host(reqs[B], stream, benchaid.WAIT_STREAM, warmup=50, iters=500)
-                row["host_us_p50"], row["host_us_p10"], row["host_us_p90"] = pct(lat, .5), pct(lat, .1), pct(lat, .9)
+                row["oneshot_host_us"] = {"p50": pct(lat, .5), "p10": pct(lat, .1), "p90": pct(lat, .9)}
             detail["allgather"].append(row)
+        # prelaunch mode: the request is armed ahead of time; timed from the doorbell write to the
+        # completion word seen on the host, and from the arming call for comparison
+        dl.dl_prelaunch_start()
+        dl.dl_set_mode(dl.DL_MODE_PRELAUNCH)
+        for row in detail["allgather"]:
+            B = row["bytes_per_rank"]
+            if B > MiB:
+                continue
+            lat = benchaid.time_host(reqs[B], None, benchaid.WAIT_TRIGGER, warmup=50, iters=500)
+            row["prelaunch_trigger_to_done_us"] = {"p50": pct(lat, .5), "p10": pct(lat, .1), "p90": pct(lat, .9)}
+            lat = benchaid.time_host(reqs[B], None, benchaid.WAIT_ARM_AND_TRIGGER, warmup=50, iters=500)
+            row["prelaunch_arm_to_done_us"] = {"p50": pct(lat, .5), "p10": pct(lat, .1), "p90": pct(lat, .9)}
+        dl.dl_set_mode(dl.DL_MODE_ONESHOT)
+        dl.dl_prelaunch_stop()
         out["detail"] = detail
         small = detail["allgather"][0]
-        out["latency_us_4KiB_allgather"] = {"oneshot_host_p50": small.get("host_us_p50"),
-                                            "oneshot_device": small["device_us"]}
+        out["latency_us_4KiB_allgather"] = {
+            "oneshot_call_to_stream_sync_p50": small["oneshot_host_us"]["p50"],
+            "oneshot_device": small["device_us"],
+            "prelaunch_trigger_to_done_p50": small["prelaunch_trigger_to_done_us"]["p50"],
+            "prelaunch_arm_to_done_p50": small["prelaunch_arm_to_done_us"]["p50"],
+        }
 
     dl.dl_shutdown()
     if not args.no_cpu:

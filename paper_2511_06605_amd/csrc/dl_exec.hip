@@ -81,17 +81,24 @@ __device__ __forceinline__ uint32_t dl_arm_wait(const dl_arm &a)
                 if (spins >= a.max_spins) break;
                 if (blockIdx.x) __builtin_amdgcn_s_sleep(8);
             }
-            if (!a.direct)
-                __hip_atomic_store(a.go, (a.ticket << 2) | go, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+            if (!a.direct) {
+                // pass the word on: one flag per group of workgroups, each in its own cache line
+                __atomic_thread_fence(__ATOMIC_RELEASE);
+                const uint32_t groups = gridDim.x < DL_ARM_GROUPS ? gridDim.x : DL_ARM_GROUPS;
+                for (uint32_t g = 0; g < groups; ++g)
+                    __hip_atomic_store((uint64_t *)((char *)a.go + g * DL_ARM_STRIDE), (a.ticket << 2) | go,
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
         } else {
             // wait for workgroup 0 to pass the word on through device memory
+            const uint64_t *flag = (const uint64_t *)((const char *)a.go + (blockIdx.x % DL_ARM_GROUPS) * DL_ARM_STRIDE);
             for (uint32_t spins = 1;; ++spins) {
-                const uint64_t g = __hip_atomic_load(a.go, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const uint64_t g = __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 if ((g >> 2) == a.ticket) {
                     go = (uint32_t)(g & 3u);
                     break;
                 }
-                __builtin_amdgcn_s_sleep(4);
+                __builtin_amdgcn_s_sleep(8);
                 if ((spins & 15u) == 0 && (uint64_t)wall_clock64() - t0 > a.limit_ticks + a.margin_ticks) break;
                 if (spins >= a.max_spins) break;
             }
@@ -106,20 +113,36 @@ __device__ __forceinline__ uint32_t dl_arm_wait(const dl_arm &a)
 }
 
 // Count this workgroup in; the last one to arrive publishes the completion word.
+// Arrivals are counted per group first (a counter per cache line), and the last
+// of each group is counted at the top, so no counter sees more than
+// grid / DL_ARM_GROUPS + DL_ARM_GROUPS updates.  The low 16 bits of a counter
+// count arrivals, the high bits count workgroups that skipped the copy.
 __device__ __forceinline__ void dl_arm_finish(const dl_arm &a, uint32_t go)
 {
     __syncthreads();
     if (threadIdx.x == 0) {
+        const uint32_t grid = gridDim.x;
+        const uint32_t groups = grid < DL_ARM_GROUPS ? grid : DL_ARM_GROUPS;
+        const uint32_t g = blockIdx.x % DL_ARM_GROUPS;
+        const uint32_t gsize = (grid - g + DL_ARM_GROUPS - 1) / DL_ARM_GROUPS;
+        uint32_t *gcount = (uint32_t *)((char *)a.arrive + g * DL_ARM_STRIDE);
+        uint32_t *top = (uint32_t *)((char *)a.arrive + DL_ARM_GROUPS * DL_ARM_STRIDE);
         __atomic_thread_fence(__ATOMIC_RELEASE);  // system scope: this workgroup's stores
-        const uint32_t add = 1u + (go == DL_GO_RUN ? 0u : 0x10000u);
-        const uint32_t old = __hip_atomic_fetch_add(a.arrive, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if ((old & 0xFFFFu) == gridDim.x - 1u) {
-            const uint32_t skipped = (old >> 16) + (add >> 16);
-            __hip_atomic_store(a.arrive, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __atomic_thread_fence(__ATOMIC_ACQUIRE);
-            __hip_atomic_store(a.done, a.ticket | (skipped ? DL_DONE_SKIPPED : 0ull), __ATOMIC_RELEASE,
-                               __HIP_MEMORY_SCOPE_SYSTEM);
-        }
+        uint32_t add = 1u + (go == DL_GO_RUN ? 0u : 0x10000u);
+        uint32_t old = __hip_atomic_fetch_add(gcount, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if ((old & 0xFFFFu) != gsize - 1u) return;
+        // last of the group: carry the group's result to the top counter
+        __hip_atomic_store(gcount, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __atomic_thread_fence(__ATOMIC_ACQ_REL);
+        add = 1u + (((old >> 16) + (add >> 16)) << 16);
+        old = __hip_atomic_fetch_add(top, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if ((old & 0xFFFFu) != groups - 1u) return;
+        // last of all
+        const uint32_t skipped = (old >> 16) + (add >> 16);
+        __hip_atomic_store(top, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __atomic_thread_fence(__ATOMIC_ACQUIRE);
+        __hip_atomic_store(a.done, a.ticket | (skipped ? DL_DONE_SKIPPED : 0ull), __ATOMIC_RELEASE,
+                           __HIP_MEMORY_SCOPE_SYSTEM);
     }
 }
 
@@ -170,7 +193,7 @@ struct ring_t {
 inline uint32_t item_k(const dl_plain_item &) { return 1; }
 inline uint32_t item_k(const dl_fused_item &it) { return it.k; }
 
-constexpr uint32_t ARMED_DIRECT_MAX = 32;  // up to this many workgroups all poll the host doorbell themselves
+constexpr uint32_t ARMED_DIRECT_MAX = 16;  // up to this many workgroups all poll the host doorbell themselves
 
 uint32_t armed_grid(uint64_t tiles)
 {
@@ -291,6 +314,12 @@ int exec_list(const Item *items, size_t n, hipStream_t stream, const dl_arm *arm
     }
     if (total == 0) return DL_OK;
     dl_launch_shape sh = dl_choose_shape(total, biggest, kmax);
+    if (arm && g_dl.cfg.tile_bytes == 0 && g_dl.cfg.block_threads == 0) {
+        // armed kernels pay per workgroup for the doorbell fan-out and the arrival count:
+        // four wavefronts per workgroup, each still moving 1 KiB rows
+        sh.tile_bytes = 4096;
+        sh.block_threads = biggest >= 4096 ? 256u : sh.block_threads;
+    }
 
     constexpr int NBIG = list_cap<Item>::big;
     if (n <= (size_t)NBIG) {

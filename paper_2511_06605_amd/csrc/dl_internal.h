@@ -44,14 +44,16 @@ struct dl_arm {
     const uint64_t *bell;  // host-coherent: bell[0] = doorbell, bell[1] = cancel; both only ever grow
     uint64_t *done;        // host-coherent: completion word of this ticket's slot
     uint64_t *armed;       // host-coherent: "resident and polling" word of this ticket's slot
-    uint64_t *go;          // device: fan-out flag of this ticket's slot
-    uint32_t *arrive;      // device: arrival counter of this ticket's slot
+    uint64_t *go;          // device: fan-out flags of this ticket's slot, one per group, DL_ARM_STRIDE bytes apart
+    uint32_t *arrive;      // device: arrival counters of this slot: one per group, then the top one, same spacing
     uint64_t ticket;
     uint64_t limit_ticks;   // give up this long after becoming resident
     uint64_t margin_ticks;  // extra time a non-polling workgroup grants the polling one
     uint32_t direct;        // 1: every workgroup polls the host doorbell itself
     uint32_t max_spins;     // backstop that does not depend on the clock: give up after this many polls
 };
+constexpr uint32_t DL_ARM_GROUPS = 16;  // workgroup b belongs to group b % DL_ARM_GROUPS
+constexpr uint32_t DL_ARM_STRIDE = 64;  // every flag and counter sits in a cache line of its own
 constexpr uint64_t DL_DONE_SKIPPED = 1ull << 63;  // set in the completion word when nothing was copied
 
 // dl_exec.hip: execution of a lowered list on a stream.  With arm == nullptr one

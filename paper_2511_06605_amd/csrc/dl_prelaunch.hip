@@ -30,9 +30,9 @@ struct arm_host {  // pinned, host-coherent
     uint64_t armed[SLOTS];  // device -> host: ticket of the last request seen resident in the slot
 };
 
-struct arm_dev {  // device memory
-    uint64_t go[SLOTS];
-    uint32_t arrive[SLOTS];
+struct arm_dev {  // device memory; every flag and counter in a cache line of its own
+    uint8_t go[SLOTS][DL_ARM_GROUPS * DL_ARM_STRIDE];
+    uint8_t arrive[SLOTS][(DL_ARM_GROUPS + 1) * DL_ARM_STRIDE];
 };
 
 struct arm_state {
@@ -90,8 +90,8 @@ int dl_armed_begin(dl_arm *arm, hipStream_t *stream)
     arm->bell = &g_arm.host->bell;
     arm->done = &g_arm.host->done[slot];
     arm->armed = &g_arm.host->armed[slot];
-    arm->go = &g_arm.dev->go[slot];
-    arm->arrive = &g_arm.dev->arrive[slot];
+    arm->go = (uint64_t *)g_arm.dev->go[slot];
+    arm->arrive = (uint32_t *)g_arm.dev->arrive[slot];
     arm->ticket = ticket;
     arm->limit_ticks = (uint64_t)g_dl.cfg.arm_timeout_us * g_arm.clock_khz / 1000ull;
     arm->margin_ticks = 5000ull * g_arm.clock_khz / 1000ull;  // 5 ms
