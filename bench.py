@@ -28,6 +28,23 @@ KiB, MiB = 1024, 1024 * 1024
 HBM_PEAK_GBS = 8000.0
 
 
+# HBM bytes per launch of the dominant kernel (all-gather, 64 MiB per rank) from hardware counters:
+# FETCH_SIZE and WRITE_SIZE of two rocprofv3 --pmc runs, each scaled by the same counter's reading
+# for a plain copy of known size.  Valid only for the kernel sources whose digest is given; with
+# any other sources the figure is reported as null until the counters are taken again.
+KERNEL_SOURCES = ["dl_work.h", "dl_device.h", "dl_exec.hip"]
+MEASURED_TRAFFIC = {"sources_sha256": "2f0ccd5abd3d18bac4833c6b996d346fca6ede7618581f85483bf9d3434871d0", "bytes_per_rank": 64 * MiB, "bytes_per_launch": 4831955968}
+
+
+def kernel_sources_digest() -> str:
+    import hashlib
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2511_06605_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
 def ag_bytes(B: int) -> int:
     return W * B + W * W * B
 
@@ -72,6 +89,136 @@ def cpu_baseline(sizes, budget_s=10.0):
     }
 
 
+def lat_stats(lat):
+    return {"p50": pct(lat, .5), "p10": pct(lat, .1), "p90": pct(lat, .9)}
+
+
+def other_operations(dl, benchaid, inputs, torch, stream, ag_reqs, ag_bufs, ag_sizes):
+    """The other operations of the library and the runtime's own copy paths, timed
+    beside the all-gather sweep (context, not part of `value`)."""
+    import numpy as np
+
+    res = {}
+
+    def dev(t):
+        return torch.from_numpy(t).cuda()
+
+    def timed(req, nbytes, small, calls=None):
+        us = benchaid.time_device(req, stream, warmup=3, calls=calls or (50 if small else 10))
+        row = {"device_us": us, "GBps": nbytes / us / 1e3}
+        if small:
+            row["oneshot_host_us"] = lat_stats(benchaid.time_host(req, stream, benchaid.WAIT_STREAM, 30, 300))
+        return row
+
+    # runtime copy engines / blit path: one hipMemcpyAsync per chunk (W*W calls + one sync), and the batched call
+    rows = []
+    for B, (d_in, d_out) in zip(ag_sizes, ag_bufs):
+        if B not in (4 * KiB, 64 * KiB, MiB, 16 * MiB):
+            continue
+        descs = [(d_in[j].data_ptr(), d_out[r].data_ptr() + j * B, B) for r in range(W) for j in range(W)]
+        row = {"bytes_per_rank": B}
+        req = benchaid.copy_list_request(descs, benchaid.OP_MEMCPY_ASYNC)
+        row["memcpy_async_per_chunk_host_us"] = lat_stats(benchaid.time_host(req, stream, benchaid.WAIT_STREAM, 5, 50))
+        row["memcpy_async_per_chunk_device_us"] = benchaid.time_device(req, stream, warmup=2, calls=5)
+        try:
+            req = benchaid.copy_list_request(descs, benchaid.OP_MEMCPY_BATCH)
+            row["memcpy_batch_host_us"] = lat_stats(benchaid.time_host(req, stream, benchaid.WAIT_STREAM, 5, 50))
+        except RuntimeError as e:
+            row["memcpy_batch_host_us"] = f"unavailable in the loaded HIP runtime ({e})"
+        req = benchaid.copy_list_request(descs, benchaid.OP_BATCH)   # same 64 plain copies through dl_batch_copy
+        row["dl_batch_copy_unfused"] = timed(req, 2 * W * W * B, B <= MiB)
+        rows.append(row)
+    res["allgather_vs_runtime_copies"] = rows
+
+    # all-to-all, uniform per-pair chunk, fp16 ~N(0,1)
+    rows = []
+    for c in [KiB << i for i in range(13)]:
+        C = inputs.uniform_chunks(W, c)
+        ins = inputs.alltoall_inputs(C, seed=c.bit_length(), kind="fp16")
+        d_in = [dev(a) for a in ins]
+        d_out = [torch.empty(W * c, dtype=torch.uint8, device="cuda") for _ in range(W)]
+        req = benchaid.alltoall_request(d_in, d_out, C)
+        row = {"chunk_bytes": c}
+        row.update(timed(req, 2 * W * W * c, c <= 128 * KiB))
+        rows.append(row)
+    res["alltoall_uniform"] = rows
+
+    # MoE dispatch all-to-all: hidden 7168 bf16, 256 experts over 8 ranks, top-8
+    rows = []
+    for T in (16, 128, 512):
+        C = inputs.moe_dispatch_chunks(W, T, seed=T)
+        ins = inputs.alltoall_inputs(C, seed=T + 1, kind="bf16")
+        d_in = [dev(a) for a in ins]
+        d_out = [torch.empty(int(C[:, j].sum()), dtype=torch.uint8, device="cuda") for j in range(W)]
+        req = benchaid.alltoall_request(d_in, d_out, C)
+        row = {"tokens_per_rank": T, "total_bytes": int(C.sum()), "zero_chunks": int((C == 0).sum())}
+        row.update(timed(req, 2 * int(C.sum()), T <= 16))
+        rows.append(row)
+    res["alltoall_moe_dispatch"] = rows
+
+    # tensor-parallel decode all-gather: hidden 8192 bf16
+    rows = []
+    for tokens in (1, 8, 32, 128, 256):
+        B = inputs.tp_decode_bytes_per_rank(tokens)
+        ins = inputs.allgather_inputs(W, B, seed=tokens, kind="bf16")
+        d_in = [dev(a) for a in ins]
+        d_out = [torch.empty(W * B, dtype=torch.uint8, device="cuda") for _ in range(W)]
+        req = benchaid.allgather_request(d_in, d_out, B)
+        row = {"tokens": tokens, "bytes_per_rank": B}
+        row.update(timed(req, ag_bytes(B), True))
+        rows.append(row)
+    res["allgather_tp_decode"] = rows
+
+    # broadcast 2 MiB -> 7 destinations; 64 back-to-back copies of 16 KiB in a 64 MiB arena
+    n = 2 * MiB
+    src = dev(inputs.payload(np.random.default_rng(7), n, "bf16"))
+    dsts = [torch.empty(n, dtype=torch.uint8, device="cuda") for _ in range(7)]
+    row = {"bytes": n, "k": 7}
+    row.update(timed(benchaid.broadcast_request(src, dsts, n), 8 * n, True))
+    res["broadcast"] = row
+    arena_h, descs = inputs.b2b_batch(64, 16 * KiB, 64 * MiB, seed=3)
+    arena = dev(arena_h)
+    p = arena.data_ptr()
+    dlist = [(p + int(a), p + int(b), int(m)) for a, b, m in descs]
+    row = {"copies": 64, "copy_bytes": 16 * KiB}
+    row.update(timed(benchaid.copy_list_request(dlist, benchaid.OP_BATCH), 2 * 64 * 16 * KiB, True))
+    req = benchaid.copy_list_request(dlist, benchaid.OP_MEMCPY_ASYNC)
+    row["memcpy_async_per_copy_host_us"] = lat_stats(benchaid.time_host(req, stream, benchaid.WAIT_STREAM, 5, 50))
+    dl.dl_prelaunch_start()
+    dl.dl_set_mode(dl.DL_MODE_PRELAUNCH)
+    req = benchaid.copy_list_request(dlist, benchaid.OP_BATCH)
+    row["prelaunch_trigger_to_done_us"] = lat_stats(benchaid.time_host(req, None, benchaid.WAIT_TRIGGER, 30, 300))
+    dl.dl_set_mode(dl.DL_MODE_ONESHOT)
+    dl.dl_prelaunch_stop()
+    res["batch_b2b"] = row
+    return res
+
+
+def pmc_case(args, dl, benchaid, torch, stream) -> int:
+    """A few launches of the dominant kernel (all-gather at the largest sweep
+    point: dl_exec_list_kernel<dl_fused_item,...>) and of a plain copy of known
+    size (dl_exec_list_kernel<dl_plain_item,...>: reads 1 GiB, writes 1 GiB) so
+    that counter readings of the first can be scaled by those of the second."""
+    B = args.max_bytes
+    d_in = [torch.randint(0, 256, (B,), dtype=torch.uint8, device="cuda") for _ in range(W)]
+    d_out = [torch.empty(W * B, dtype=torch.uint8, device="cuda") for _ in range(W)]
+    ag = benchaid.allgather_request(d_in, d_out, B)
+    n = 1 << 30
+    a = torch.randint(0, 256, (n,), dtype=torch.uint8, device="cuda")
+    b = torch.empty(n, dtype=torch.uint8, device="cuda")
+    cp = benchaid.copy_list_request([(a.data_ptr(), b.data_ptr(), n)], benchaid.OP_BATCH)
+    stream.synchronize()
+    for _ in range(args.warmup + args.steps):
+        benchaid.issue(ag, stream)
+        benchaid.issue(cp, stream)
+    stream.synchronize()
+    dl.dl_shutdown()
+    print(json.dumps({"case": "pmc", "launches_each": args.warmup + args.steps,
+                      "allgather": {"bytes_per_rank": B, "algorithmic_read": W * B, "algorithmic_write": W * W * B},
+                      "copy": {"read": n, "write": n}}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -80,6 +227,9 @@ def main() -> int:
     ap.add_argument("--max-bytes", type=int, default=64 * MiB, help="largest per-rank payload of the sweep")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline leg")
     ap.add_argument("--no-detail", action="store_true", help="skip per-size latency and comparison legs")
+    ap.add_argument("--case", choices=["sweep", "pmc"], default="sweep",
+                    help="pmc: only --steps launches of the largest all-gather and of a plain 1 GiB copy "
+                         "(the calibration kernel), for hardware-counter runs")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU (W virtual ranks share its HBM); --gpus must be 1",
@@ -96,6 +246,9 @@ def main() -> int:
     torch.cuda.set_device(0)
     dl.dl_init(0)
     stream = torch.cuda.current_stream()
+
+    if args.case == "pmc":
+        return pmc_case(args, dl, benchaid, torch, stream)
 
     sizes = [B for B in (4 * KiB << i for i in range(15)) if B <= args.max_bytes]
     reqs, keep, check = {}, [], None
@@ -139,6 +292,9 @@ def main() -> int:
     value = step_bytes * args.steps / dt / 1e9
     big_ms = sum(a.elapsed_time(b) for a, b in events) / len(events)
     achieved = ag_bytes(big) / (big_ms * 1e-3) / 1e9
+    traffic = None
+    if MEASURED_TRAFFIC["bytes_per_rank"] == big and MEASURED_TRAFFIC["sources_sha256"] == kernel_sources_digest():
+        traffic = MEASURED_TRAFFIC["bytes_per_launch"]
 
     out = {
         "metric": "all-gather sweep (W=8, 4 KiB..64 MiB per rank) algorithmic read+write throughput",
@@ -149,8 +305,8 @@ def main() -> int:
                                f"{sizes[0] // KiB} KiB..{big // MiB} MiB in powers of 2, bf16 ~N(0,1) seeded",
                    "W": W, "calls_per_step": len(sizes), "bytes_per_step": step_bytes, "mode": "oneshot"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": "dl_exec_list_kernel<dl_fused_item, 8, nontemporal>",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "kernel": "dl_exec_list_kernel<dl_fused_item, 8, false>",
                      "launch": f"all-gather {big // MiB} MiB per rank: {ag_bytes(big)} algorithmic bytes, "
                                f"{big_ms * 1e3:.1f} us average over {len(events)} launches (HIP events)"},
     }
@@ -163,7 +319,7 @@ def main() -> int:
             row["GBps"] = ag_bytes(B) / row["device_us"] / 1e3
             if B <= MiB:
                 lat = benchaid.time_host(reqs[B], stream, benchaid.WAIT_STREAM, warmup=50, iters=500)
-                row["oneshot_host_us"] = {"p50": pct(lat, .5), "p10": pct(lat, .1), "p90": pct(lat, .9)}
+                row["oneshot_host_us"] = lat_stats(lat)
             detail["allgather"].append(row)
         # prelaunch mode: the request is armed ahead of time; timed from the doorbell write to the
         # completion word seen on the host, and from the arming call for comparison
@@ -174,11 +330,12 @@ def main() -> int:
             if B > MiB:
                 continue
             lat = benchaid.time_host(reqs[B], None, benchaid.WAIT_TRIGGER, warmup=50, iters=500)
-            row["prelaunch_trigger_to_done_us"] = {"p50": pct(lat, .5), "p10": pct(lat, .1), "p90": pct(lat, .9)}
+            row["prelaunch_trigger_to_done_us"] = lat_stats(lat)
             lat = benchaid.time_host(reqs[B], None, benchaid.WAIT_ARM_AND_TRIGGER, warmup=50, iters=500)
-            row["prelaunch_arm_to_done_us"] = {"p50": pct(lat, .5), "p10": pct(lat, .1), "p90": pct(lat, .9)}
+            row["prelaunch_arm_to_done_us"] = lat_stats(lat)
         dl.dl_set_mode(dl.DL_MODE_ONESHOT)
         dl.dl_prelaunch_stop()
+        detail.update(other_operations(dl, benchaid, inputs, torch, stream, reqs, keep, sizes))
         out["detail"] = detail
         small = detail["allgather"][0]
         out["latency_us_4KiB_allgather"] = {
