@@ -196,8 +196,8 @@ def other_operations(dl, benchaid, inputs, torch, stream, ag_reqs, ag_bufs, ag_s
 
 def pmc_case(args, dl, benchaid, torch, stream) -> int:
     """A few launches of the dominant kernel (all-gather at the largest sweep
-    point: dl_exec_list_kernel<dl_fused_item,...>) and of a plain copy of known
-    size (dl_exec_list_kernel<dl_plain_item,...>: reads 1 GiB, writes 1 GiB) so
+    point: dl_exec_rows_kernel<dl_fused_item,...>) and of a plain copy of known
+    size (dl_exec_rows_kernel<dl_plain_item,...>: reads 1 GiB, writes 1 GiB) so
     that counter readings of the first can be scaled by those of the second."""
     B = args.max_bytes
     d_in = [torch.randint(0, 256, (B,), dtype=torch.uint8, device="cuda") for _ in range(W)]
@@ -306,7 +306,7 @@ def main() -> int:
                    "W": W, "calls_per_step": len(sizes), "bytes_per_step": step_bytes, "mode": "oneshot"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "kernel": "dl_exec_list_kernel<dl_fused_item, 8, false>",
+                     "kernel": "dl_exec_rows_kernel<dl_fused_item, 8, false>",
                      "launch": f"all-gather {big // MiB} MiB per rank: {ag_bytes(big)} algorithmic bytes, "
                                f"{big_ms * 1e3:.1f} us average over {len(events)} launches (HIP events)"},
     }

@@ -59,6 +59,7 @@ class Config(ctypes.Structure):
         ("arm_timeout_us", ctypes.c_uint32),
         ("fuse_broadcast", ctypes.c_uint32),
         ("max_blocks", ctypes.c_uint32),
+        ("fan_split", ctypes.c_uint32),
     ]
 
 

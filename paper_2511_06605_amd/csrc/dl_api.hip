@@ -276,6 +276,8 @@ int dl_set_config(const dl_config *cfg)
     if (t && (t < 1024 || (t & (t - 1)) || t > (1u << 24))) return DL_ERR_INVALID;
     if (b && b != 64 && b != 128 && b != 256 && b != 512) return DL_ERR_INVALID;
     if (cfg->arm_timeout_us < 1 || cfg->arm_timeout_us > 1000000) return DL_ERR_INVALID;
+    const uint32_t fs = cfg->fan_split;
+    if (fs != 0 && fs != 1 && fs != 2 && fs != 4) return DL_ERR_INVALID;
     g_dl.cfg = *cfg;
     return DL_OK;
 }

@@ -23,6 +23,14 @@ __global__ void __launch_bounds__(512) dl_exec_list_kernel(const dl_klist<Item, 
     dl_run_tile<NT>(p, blockIdx.x);
 }
 
+// Row path only (see dl_run_rows).  A kernel of its own: sharing one kernel with
+// the general path cost 5 % of the all-gather rate through its register count.
+template <class Item, int NMAX, bool NT>
+__global__ void __launch_bounds__(512) dl_exec_rows_kernel(const dl_klist<Item, NMAX> p)
+{
+    dl_run_rows<NT>(p, blockIdx.x);
+}
+
 // Same, with a capped grid: workgroup b takes tiles b, b + grid, b + 2 grid, ...
 template <class Item, int NMAX, bool NT>
 __global__ void __launch_bounds__(512) dl_exec_list_strided_kernel(const dl_klist<Item, NMAX> p)
@@ -33,12 +41,12 @@ __global__ void __launch_bounds__(512) dl_exec_list_strided_kernel(const dl_klis
 
 template <class Item, bool NT>
 __global__ void __launch_bounds__(512) dl_exec_table_kernel(const Item *__restrict__ items, uint32_t n,
-                                                            uint32_t tile_bytes)
+                                                            uint32_t tile_bytes, uint32_t split)
 {
     const uint32_t b = blockIdx.x;
     if (b >= n) return;
     const Item it = items[b];
-    dl_run_item<NT>(it, 0, tile_bytes);
+    dl_run_item<NT>(it, 0, tile_bytes, split);
 }
 
 // ------------------------------------------------------------ armed kernels
@@ -146,26 +154,31 @@ __device__ __forceinline__ void dl_arm_finish(const dl_arm &a, uint32_t go)
     }
 }
 
-template <class Item, int NMAX>
+template <class Item, int NMAX, bool ROWS>
 __global__ void __launch_bounds__(512) dl_armed_list_kernel(const dl_klist<Item, NMAX> p, const dl_arm a)
 {
     const uint32_t go = dl_arm_wait(a);
     if (go == DL_GO_RUN) {
         const uint32_t total = p.tile_end[p.n - 1];
-        for (uint32_t b = blockIdx.x; b < total; b += gridDim.x) dl_run_tile<false>(p, b);
+        for (uint32_t b = blockIdx.x; b < total; b += gridDim.x) {
+            if constexpr (ROWS)
+                dl_run_rows<false>(p, b);
+            else
+                dl_run_tile<false>(p, b);
+        }
     }
     dl_arm_finish(a, go);
 }
 
 template <class Item>
 __global__ void __launch_bounds__(512) dl_armed_table_kernel(const Item *__restrict__ items, uint32_t n,
-                                                             uint32_t tile_bytes, const dl_arm a)
+                                                             uint32_t tile_bytes, uint32_t split, const dl_arm a)
 {
     const uint32_t go = dl_arm_wait(a);
     if (go == DL_GO_RUN) {
         for (uint32_t b = blockIdx.x; b < n; b += gridDim.x) {
             const Item it = items[b];
-            dl_run_item<false>(it, 0, tile_bytes);
+            dl_run_item<false>(it, 0, tile_bytes, split);
         }
     }
     dl_arm_finish(a, go);
@@ -190,6 +203,39 @@ struct ring_t {
     size_t next = 0;
 } g_ring;
 
+inline uint32_t log2u(uint32_t v)
+{
+    uint32_t l = 0;
+    while ((2u << l) <= v) ++l;
+    return l;
+}
+
+// Every address and the byte count of the item are multiples of 16.
+inline bool item_aligned16(const dl_plain_item &it)
+{
+    return (((uint64_t)it.src | (uint64_t)it.dst | it.bytes) & 15u) == 0;
+}
+inline bool item_aligned16(const dl_fused_item &it)
+{
+    uint64_t m = (uint64_t)it.src | it.bytes;
+    for (uint32_t j = 0; j < it.k; ++j) m |= (uint64_t)it.dst[j];
+    return (m & 15u) == 0;
+}
+
+// Row path layout of a fused item's destinations: sub-group g of `split` owns
+// slots g * (DL_FAN / split) onwards and gets destinations g * per ..
+// g * per + per - 1 (per = ceil(k / split)), filled from the front; unused
+// slots are null, which is what ends a sub-group's store loop on the device.
+inline void slots_by_subgroup(dl_plain_item &, uint32_t) {}
+inline void slots_by_subgroup(dl_fused_item &it, uint32_t split)
+{
+    char *by_group[DL_FAN] = {};
+    const uint32_t slots = (uint32_t)DL_FAN / split, per = (it.k + split - 1) / split;
+    for (uint32_t g = 0; g < split; ++g)
+        for (uint32_t q = 0; q < per && g * per + q < it.k; ++q) by_group[g * slots + q] = it.dst[g * per + q];
+    for (int j = 0; j < DL_FAN; ++j) it.dst[j] = by_group[j];
+}
+
 inline uint32_t item_k(const dl_plain_item &) { return 1; }
 inline uint32_t item_k(const dl_fused_item &it) { return it.k; }
 
@@ -209,16 +255,30 @@ int launch_klist(const Item *items, size_t n, const uint64_t *tile_end, const dl
     dl_klist<Item, NMAX> p;
     p.n = (uint32_t)n;
     p.tile_bytes = sh.tile_bytes;
+    p.split = sh.split;
+    p.split_log2 = log2u(sh.split);
+    p.wpg_log2 = log2u(sh.block_threads / 64u / sh.split);
     for (size_t i = 0; i < n; ++i) {
         p.tile_end[i] = (uint32_t)tile_end[i];
         p.item[i] = items[i];
     }
+    for (size_t i = n; i < (size_t)NMAX; ++i) p.tile_end[i] = 0xFFFFFFFFu;  // the device compares without looking at n
+    if (sh.rows)
+        for (size_t i = 0; i < n; ++i) slots_by_subgroup(p.item[i], sh.split);
     const uint32_t grid = (uint32_t)tile_end[n - 1];
     if (arm) {
         dl_arm a = *arm;
         const uint32_t g = armed_grid(grid);
         a.direct = g <= ARMED_DIRECT_MAX ? 1u : 0u;
-        hipLaunchKernelGGL((dl_armed_list_kernel<Item, NMAX>), dim3(g), dim3(sh.block_threads), 0, stream, p, a);
+        if (sh.rows)
+            hipLaunchKernelGGL((dl_armed_list_kernel<Item, NMAX, true>), dim3(g), dim3(sh.block_threads), 0, stream, p, a);
+        else
+            hipLaunchKernelGGL((dl_armed_list_kernel<Item, NMAX, false>), dim3(g), dim3(sh.block_threads), 0, stream, p, a);
+    } else if (sh.rows) {
+        if (sh.nontemporal)
+            hipLaunchKernelGGL((dl_exec_rows_kernel<Item, NMAX, true>), dim3(grid), dim3(sh.block_threads), 0, stream, p);
+        else
+            hipLaunchKernelGGL((dl_exec_rows_kernel<Item, NMAX, false>), dim3(grid), dim3(sh.block_threads), 0, stream, p);
     } else if (sh.max_blocks && grid > sh.max_blocks) {
         if (sh.nontemporal)
             hipLaunchKernelGGL((dl_exec_list_strided_kernel<Item, NMAX, true>), dim3(sh.max_blocks),
@@ -286,13 +346,13 @@ int launch_table(const Item *items, size_t n, dl_launch_shape sh, hipStream_t st
             const uint32_t g = armed_grid(m);
             a.direct = g <= ARMED_DIRECT_MAX ? 1u : 0u;
             hipLaunchKernelGGL((dl_armed_table_kernel<Item>), dim3(g), dim3(sh.block_threads), 0, stream, slot,
-                               (uint32_t)m, sh.tile_bytes, a);
+                               (uint32_t)m, sh.tile_bytes, sh.split, a);
         } else if (sh.nontemporal)
             hipLaunchKernelGGL((dl_exec_table_kernel<Item, true>), dim3((uint32_t)m), dim3(sh.block_threads), 0,
-                               stream, slot, (uint32_t)m, sh.tile_bytes);
+                               stream, slot, (uint32_t)m, sh.tile_bytes, sh.split);
         else
             hipLaunchKernelGGL((dl_exec_table_kernel<Item, false>), dim3((uint32_t)m), dim3(sh.block_threads), 0,
-                               stream, slot, (uint32_t)m, sh.tile_bytes);
+                               stream, slot, (uint32_t)m, sh.tile_bytes, sh.split);
         DL_HIP(hipGetLastError());
         DL_HIP(hipEventRecord(g_ring.ev[s], stream));
         g_ring.used[s] = true;
@@ -319,6 +379,7 @@ int exec_list(const Item *items, size_t n, hipStream_t stream, const dl_arm *arm
         // four wavefronts per workgroup, each still moving 1 KiB rows
         sh.tile_bytes = 4096;
         sh.block_threads = biggest >= 4096 ? 256u : sh.block_threads;
+        sh.split = 1;
     }
 
     constexpr int NBIG = list_cap<Item>::big;
@@ -333,6 +394,12 @@ int exec_list(const Item *items, size_t n, hipStream_t stream, const dl_arm *arm
             if (acc < (1ull << 30)) break;
             sh.tile_bytes *= 2;  // keep the grid inside the launch limit
         }
+        // row path: a short list (found by a few scalar compares; bisecting a long one per wavefront
+        // measured slower than the general path), aligned items, and a tile that is exactly one
+        // 1 KiB row per wavefront of a sub-group
+        sh.rows = n <= (size_t)NMAX_SMALL && sh.tile_bytes == 16u * (sh.block_threads / sh.split) &&
+                  !(sh.max_blocks && !arm);
+        for (size_t i = 0; i < n && sh.rows; ++i) sh.rows = item_aligned16(items[i]);
         *launched = true;
         if (n <= (size_t)NMAX_SMALL) return launch_klist<Item, NMAX_SMALL>(items, n, tile_end, sh, stream, arm);
         return launch_klist<Item, NBIG>(items, n, tile_end, sh, stream, arm);
@@ -350,26 +417,35 @@ uint32_t floor_pow2(uint64_t v)
 
 }  // namespace
 
-// Tile and workgroup size for a request.  Measured on MI355X (all-gather of
-// 64 MiB per rank, 1:1 copies of 2 GiB): the finest cut wins.  For fused
-// fan-out, one wavefront per workgroup moving one 1 KiB row (one 16-byte load
-// and k stores per lane) beat every larger tile; for 1:1 copies 4 KiB tiles of
-// 256 threads did.  Larger tiles, capped grids and streaming hints were slower.
+// Tile, workgroup size and fan split for a request.  Measured on MI355X
+// (all-gather of 8 .. 64 MiB per rank, 1:1 copies of 2 GiB): the finest cut
+// wins, with 256-thread workgroups in which every wavefront moves one 1 KiB row
+// with one 16-byte load and at most two stores per lane.  So a fan-out of 5..8
+// takes 1 KiB tiles shared out over four wavefronts, 3..4 takes 2 KiB tiles and
+// two sub-groups, 1:1 and 1:2 copies take 4 KiB tiles.  Larger tiles, larger or
+// smaller workgroups, capped grids and streaming hints were all slower.
 dl_launch_shape dl_choose_shape(uint64_t src_bytes, uint64_t max_item_bytes, uint32_t max_k)
 {
     const dl_config &c = g_dl.cfg;
     dl_launch_shape sh;
+    uint32_t split = c.fan_split;
+    if (split == 0) split = max_k > 4 ? 4u : max_k > 2 ? 2u : 1u;
+    if (max_k == 1) split = 1;
     uint32_t tile = c.tile_bytes;
-    if (tile == 0) tile = max_k > 2 ? 1024u : 4096u;
+    if (tile == 0) tile = 4096u / split;
     sh.tile_bytes = tile;
     uint32_t bt = c.block_threads;
     if (bt == 0) {
+        // threads of one sub-group: enough for the tile (or the largest item if that is smaller)
         const uint64_t span = max_item_bytes < tile ? max_item_bytes : tile;
-        bt = floor_pow2(span / 16 ? span / 16 : 1);
-        if (bt > 256) bt = 256;
-        if (bt < 64) bt = 64;
+        uint32_t sub = floor_pow2(span / 16 ? span / 16 : 1);
+        if (sub > 256u / split) sub = 256u / split;
+        if (sub < 64) sub = 64;
+        bt = sub * split;
     }
+    while (split > 1 && bt / split < 64) split /= 2;  // sub-groups are whole wavefronts
     sh.block_threads = bt;
+    sh.split = split;
     sh.max_blocks = c.max_blocks;
     sh.nontemporal = src_bytes * (1ull + max_k) >= c.nontemporal_min_bytes;
     return sh;

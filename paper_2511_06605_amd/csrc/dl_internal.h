@@ -34,8 +34,10 @@ extern dl_state g_dl;
 struct dl_launch_shape {
     uint32_t tile_bytes;
     uint32_t block_threads;
+    uint32_t split;       // sub-groups of a workgroup sharing out the destinations of a fused item: 1, 2 or 4
     uint32_t max_blocks;  // 0 = one workgroup per tile
     bool nontemporal;
+    bool rows = false;    // the list qualifies for the row path of the list kernels
 };
 
 // What an armed (prelaunched) kernel needs to wait for its doorbell and to
@@ -53,7 +55,7 @@ struct dl_arm {
     uint32_t max_spins;     // backstop that does not depend on the clock: give up after this many polls
 };
 constexpr uint32_t DL_ARM_GROUPS = 16;  // workgroup b belongs to group b % DL_ARM_GROUPS
-constexpr uint32_t DL_ARM_STRIDE = 64;  // every flag and counter sits in a cache line of its own
+constexpr uint32_t DL_ARM_STRIDE = 4352;  // flags and counters sit 4 KiB + 256 B apart: separate lines and memory channels
 constexpr uint64_t DL_DONE_SKIPPED = 1ull << 63;  // set in the completion word when nothing was copied
 
 // dl_exec.hip: execution of a lowered list on a stream.  With arm == nullptr one

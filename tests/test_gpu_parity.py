@@ -132,6 +132,32 @@ def test_allgather_forced_tiles(ref, cfg, tile, block):
     run_allgather(ref, 3, tile - 16, seed=tile + 1)
 
 
+@pytest.mark.parametrize("split,block,tile", [(1, 64, 1024), (1, 256, 4096), (2, 128, 1024), (2, 256, 2048),
+                                              (4, 256, 1024), (4, 512, 4096), (4, 64, 1024), (2, 512, 65536)])
+def test_allgather_forced_fan_split(ref, cfg, split, block, tile):
+    """Destinations shared out over sub-groups of a workgroup: every fan-out 1..8 (W ranks, and the
+    in-place layout that drops one), ragged sizes, for every split / workgroup / tile combination.
+    A workgroup too small for the split (4 over 64 threads) falls back to fewer sub-groups."""
+    cfg(fan_split=split, block_threads=block, tile_bytes=tile)
+    for W in (1, 2, 3, 4, 5, 6, 7, 8):
+        run_allgather(ref, W, 3 * tile + 16 * 3 + 5, seed=100 * split + W)
+    run_allgather(ref, 8, 900, seed=split)
+    run_allgather(ref, 8, 70001, seed=split + 1, in_place=True)
+    run_allgather(ref, 13, 5000, seed=split + 2)
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 5, 6, 7, 8, 9, 15])
+def test_broadcast_default_split_every_fanout(ref, k):
+    n = 300 * KiB + 48
+    src = inputs.payload(np.random.default_rng(k), n, "bf16")
+    d_src = DevBuf(n, fill=src)
+    d_dst = [DevBuf(n) for _ in range(k)]
+    dl.dl_broadcast(d_src.ptr(), [b.ptr() for b in d_dst], n, stream())
+    sync()
+    for b, w in zip(d_dst, ref.broadcast(src, k)):
+        assert np.array_equal(b.host(), w) and b.guards_intact()
+
+
 def test_allgather_nontemporal_path(ref, cfg):
     cfg(nontemporal_min_bytes=0)
     run_allgather(ref, 8, 300001, seed=8)
