@@ -60,6 +60,8 @@ class Config(ctypes.Structure):
         ("fuse_broadcast", ctypes.c_uint32),
         ("max_blocks", ctypes.c_uint32),
         ("fan_split", ctypes.c_uint32),
+        ("reserved", ctypes.c_uint32),
+        ("write_through_max_bytes", ctypes.c_uint64),
     ]
 
 

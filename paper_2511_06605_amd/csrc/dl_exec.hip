@@ -13,40 +13,41 @@
 
 #include <string.h>
 
+#include <type_traits>
 #include <vector>
 
 // ------------------------------------------------------------------- kernels
 
-template <class Item, int NMAX, bool NT>
+template <class Item, int NMAX, int POL>
 __global__ void __launch_bounds__(512) dl_exec_list_kernel(const dl_klist<Item, NMAX> p)
 {
-    dl_run_tile<NT>(p, blockIdx.x);
+    dl_run_tile<POL>(p, blockIdx.x);
 }
 
 // Row path only (see dl_run_rows).  A kernel of its own: sharing one kernel with
 // the general path cost 5 % of the all-gather rate through its register count.
-template <class Item, int NMAX, bool NT>
+template <class Item, int NMAX, int POL>
 __global__ void __launch_bounds__(512) dl_exec_rows_kernel(const dl_klist<Item, NMAX> p)
 {
-    dl_run_rows<NT>(p, blockIdx.x);
+    dl_run_rows<POL>(p, blockIdx.x);
 }
 
 // Same, with a capped grid: workgroup b takes tiles b, b + grid, b + 2 grid, ...
-template <class Item, int NMAX, bool NT>
+template <class Item, int NMAX, int POL>
 __global__ void __launch_bounds__(512) dl_exec_list_strided_kernel(const dl_klist<Item, NMAX> p)
 {
     const uint32_t total = p.tile_end[p.n - 1];
-    for (uint32_t b = blockIdx.x; b < total; b += gridDim.x) dl_run_tile<NT>(p, b);
+    for (uint32_t b = blockIdx.x; b < total; b += gridDim.x) dl_run_tile<POL>(p, b);
 }
 
-template <class Item, bool NT>
+template <class Item, int POL>
 __global__ void __launch_bounds__(512) dl_exec_table_kernel(const Item *__restrict__ items, uint32_t n,
                                                             uint32_t tile_bytes, uint32_t split)
 {
     const uint32_t b = blockIdx.x;
     if (b >= n) return;
     const Item it = items[b];
-    dl_run_item<NT>(it, 0, tile_bytes, split);
+    dl_run_item<POL>(it, 0, tile_bytes, split);
 }
 
 // ------------------------------------------------------------ armed kernels
@@ -162,9 +163,9 @@ __global__ void __launch_bounds__(512) dl_armed_list_kernel(const dl_klist<Item,
         const uint32_t total = p.tile_end[p.n - 1];
         for (uint32_t b = blockIdx.x; b < total; b += gridDim.x) {
             if constexpr (ROWS)
-                dl_run_rows<false>(p, b);
+                dl_run_rows<DL_POL_PLAIN>(p, b);
             else
-                dl_run_tile<false>(p, b);
+                dl_run_tile<DL_POL_PLAIN>(p, b);
         }
     }
     dl_arm_finish(a, go);
@@ -178,7 +179,7 @@ __global__ void __launch_bounds__(512) dl_armed_table_kernel(const Item *__restr
     if (go == DL_GO_RUN) {
         for (uint32_t b = blockIdx.x; b < n; b += gridDim.x) {
             const Item it = items[b];
-            dl_run_item<false>(it, 0, tile_bytes, split);
+            dl_run_item<DL_POL_PLAIN>(it, 0, tile_bytes, split);
         }
     }
     dl_arm_finish(a, go);
@@ -202,6 +203,17 @@ struct ring_t {
     bool used[RING_SLOTS]{};
     size_t next = 0;
 } g_ring;
+
+// Calls f with the cache policy as a compile-time constant.
+template <class F>
+inline void with_policy(int policy, F f)
+{
+    switch (policy) {
+    case DL_POL_STREAM: f(std::integral_constant<int, DL_POL_STREAM>{}); break;
+    case DL_POL_WT: f(std::integral_constant<int, DL_POL_WT>{}); break;
+    default: f(std::integral_constant<int, DL_POL_PLAIN>{}); break;
+    }
+}
 
 inline uint32_t log2u(uint32_t v)
 {
@@ -275,21 +287,21 @@ int launch_klist(const Item *items, size_t n, const uint64_t *tile_end, const dl
         else
             hipLaunchKernelGGL((dl_armed_list_kernel<Item, NMAX, false>), dim3(g), dim3(sh.block_threads), 0, stream, p, a);
     } else if (sh.rows) {
-        if (sh.nontemporal)
-            hipLaunchKernelGGL((dl_exec_rows_kernel<Item, NMAX, true>), dim3(grid), dim3(sh.block_threads), 0, stream, p);
-        else
-            hipLaunchKernelGGL((dl_exec_rows_kernel<Item, NMAX, false>), dim3(grid), dim3(sh.block_threads), 0, stream, p);
+        with_policy(sh.policy, [&](auto pol) {
+            hipLaunchKernelGGL((dl_exec_rows_kernel<Item, NMAX, decltype(pol)::value>), dim3(grid),
+                               dim3(sh.block_threads), 0, stream, p);
+        });
     } else if (sh.max_blocks && grid > sh.max_blocks) {
-        if (sh.nontemporal)
-            hipLaunchKernelGGL((dl_exec_list_strided_kernel<Item, NMAX, true>), dim3(sh.max_blocks),
+        with_policy(sh.policy, [&](auto pol) {
+            hipLaunchKernelGGL((dl_exec_list_strided_kernel<Item, NMAX, decltype(pol)::value>), dim3(sh.max_blocks),
                                dim3(sh.block_threads), 0, stream, p);
-        else
-            hipLaunchKernelGGL((dl_exec_list_strided_kernel<Item, NMAX, false>), dim3(sh.max_blocks),
+        });
+    } else {
+        with_policy(sh.policy, [&](auto pol) {
+            hipLaunchKernelGGL((dl_exec_list_kernel<Item, NMAX, decltype(pol)::value>), dim3(grid),
                                dim3(sh.block_threads), 0, stream, p);
-    } else if (sh.nontemporal)
-        hipLaunchKernelGGL((dl_exec_list_kernel<Item, NMAX, true>), dim3(grid), dim3(sh.block_threads), 0, stream, p);
-    else
-        hipLaunchKernelGGL((dl_exec_list_kernel<Item, NMAX, false>), dim3(grid), dim3(sh.block_threads), 0, stream, p);
+        });
+    }
     DL_HIP(hipGetLastError());
     return DL_OK;
 }
@@ -347,12 +359,12 @@ int launch_table(const Item *items, size_t n, dl_launch_shape sh, hipStream_t st
             a.direct = g <= ARMED_DIRECT_MAX ? 1u : 0u;
             hipLaunchKernelGGL((dl_armed_table_kernel<Item>), dim3(g), dim3(sh.block_threads), 0, stream, slot,
                                (uint32_t)m, sh.tile_bytes, sh.split, a);
-        } else if (sh.nontemporal)
-            hipLaunchKernelGGL((dl_exec_table_kernel<Item, true>), dim3((uint32_t)m), dim3(sh.block_threads), 0,
-                               stream, slot, (uint32_t)m, sh.tile_bytes, sh.split);
-        else
-            hipLaunchKernelGGL((dl_exec_table_kernel<Item, false>), dim3((uint32_t)m), dim3(sh.block_threads), 0,
-                               stream, slot, (uint32_t)m, sh.tile_bytes, sh.split);
+        } else {
+            with_policy(sh.policy, [&](auto pol) {
+                hipLaunchKernelGGL((dl_exec_table_kernel<Item, decltype(pol)::value>), dim3((uint32_t)m),
+                                   dim3(sh.block_threads), 0, stream, slot, (uint32_t)m, sh.tile_bytes, sh.split);
+            });
+        }
         DL_HIP(hipGetLastError());
         DL_HIP(hipEventRecord(g_ring.ev[s], stream));
         g_ring.used[s] = true;
@@ -447,7 +459,10 @@ dl_launch_shape dl_choose_shape(uint64_t src_bytes, uint64_t max_item_bytes, uin
     sh.block_threads = bt;
     sh.split = split;
     sh.max_blocks = c.max_blocks;
-    sh.nontemporal = src_bytes * (1ull + max_k) >= c.nontemporal_min_bytes;
+    const uint64_t moved = src_bytes * (1ull + max_k);  // upper bound on bytes read + written
+    sh.policy = moved >= c.nontemporal_min_bytes ? DL_POL_STREAM
+                : moved <= c.write_through_max_bytes ? DL_POL_WT
+                                                     : DL_POL_PLAIN;
     return sh;
 }
 

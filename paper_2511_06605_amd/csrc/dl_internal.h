@@ -36,7 +36,7 @@ struct dl_launch_shape {
     uint32_t block_threads;
     uint32_t split;       // sub-groups of a workgroup sharing out the destinations of a fused item: 1, 2 or 4
     uint32_t max_blocks;  // 0 = one workgroup per tile
-    bool nontemporal;
+    int policy;           // cache policy of the copy loop (DL_POL_*)
     bool rows = false;    // the list qualifies for the row path of the list kernels
 };
 

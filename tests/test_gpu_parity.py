@@ -165,6 +165,19 @@ def test_allgather_nontemporal_path(ref, cfg):
     run_allgather(ref, 8, 300001, seed=8)
 
 
+@pytest.mark.parametrize("wt_max", [0, 1 << 62])
+def test_store_policy_write_through_on_and_off(ref, cfg, wt_max):
+    """Write-through stores forced on / off for every path: row kernels, general path with heads and
+    tails, misaligned (narrow elements), long lists (table kernel), 1:1 and fused."""
+    cfg(write_through_max_bytes=wt_max)
+    run_allgather(ref, 8, 256 * KiB, seed=31, kind="bf16")
+    run_allgather(ref, 8, 300001, seed=32)
+    run_allgather(ref, 4, 40000, seed=33, shifts=[0, 1, 2, 3, 7, 9, 11, 13])
+    run_alltoall(ref, inputs.uniform_chunks(8, 64 * KiB), seed=34, kind="fp16")
+    run_alltoall(ref, inputs.random_chunks(16, 100000, seed=35, zero_frac=0.1), seed=36)
+    run_batch(ref, 200, 50000, 64 * MiB, seed=37, align=16)
+
+
 def test_allgather_full_size_64MiB(ref):
     """Largest sweep point, default launch configuration: 0.5 GiB in, 4 GiB out."""
     import torch
