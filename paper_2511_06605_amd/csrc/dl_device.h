@@ -34,15 +34,29 @@ constexpr int DL_UNROLL = 4;
 //           L2 for the end of the kernel to write back, which shortens small and
 //           medium requests by 10-15 % and costs nothing until the output outgrows
 //           the on-die caches.
-enum : int { DL_POL_PLAIN = 0, DL_POL_STREAM = 1, DL_POL_WT = 2 };
+//  COHERENT every load and store at system scope: loads never hit a stale cache
+//           line, stores are written through and are visible to the whole system once
+//           the wavefront's memory counter has drained.  Used by the armed kernels,
+//           which therefore need no cache invalidate after the doorbell and no cache
+//           write-back before the completion word.  A wavefront that used this policy
+//           must execute dl_drain_stores() before it signals anything: the compiler
+//           does not count the stores issued from inline assembly.
+enum : int { DL_POL_PLAIN = 0, DL_POL_STREAM = 1, DL_POL_WT = 2, DL_POL_COHERENT = 3 };
 
 template <int POL, typename V>
 __device__ __forceinline__ V dl_ld(const DL_GLOBAL V *p)
 {
-    if constexpr (POL == DL_POL_STREAM)
+    if constexpr (POL == DL_POL_STREAM) {
         return __builtin_nontemporal_load(p);
-    else
+    } else if constexpr (POL == DL_POL_COHERENT && sizeof(V) == 16) {
+        V v;
+        asm volatile("global_load_dwordx4 %0, %1, off sc0 sc1\n\ts_waitcnt vmcnt(0)" : "=v"(v) : "v"(p) : "memory");
+        return v;
+    } else if constexpr (POL == DL_POL_COHERENT) {
+        return __hip_atomic_load((const V *)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    } else {
         return *p;
+    }
 }
 
 template <int POL, typename V>
@@ -52,8 +66,18 @@ __device__ __forceinline__ void dl_st(DL_GLOBAL V *p, V v)
         __builtin_nontemporal_store(v, p);
     else if constexpr (POL == DL_POL_WT && sizeof(V) == 16)
         asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(v) : "memory");
+    else if constexpr (POL == DL_POL_COHERENT && sizeof(V) == 16)
+        asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" : : "v"(p), "v"(v) : "memory");
+    else if constexpr (POL == DL_POL_COHERENT)
+        __hip_atomic_store((V *)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     else
         *p = v;
+}
+
+// Wait until every vector memory operation of this wavefront has completed.
+__device__ __forceinline__ void dl_drain_stores()
+{
+    asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
 }
 
 // n 16-byte vectors from s to the first K of the destinations, by nthr threads.
@@ -85,16 +109,16 @@ __device__ __forceinline__ void dl_copy_vec16(const DL_GLOBAL dl_u32x4 *__restri
 }
 
 // Narrow elements (addresses that do not agree modulo 16): correctness path.
-template <typename V, int FAN>
+template <typename V, int FAN, int POL>
 __device__ __forceinline__ void dl_copy_narrow(const char *src, char *const (&dsts)[FAN], uint32_t k,
                                                uint64_t byte_off, uint32_t n, uint32_t tid, uint32_t nthr)
 {
     const DL_GLOBAL V *s = dl_global<V>(src + byte_off);
     for (uint32_t i = tid; i < n; i += nthr) {
-        V v = s[i];
+        V v = dl_ld<POL>(s + i);
 #pragma unroll
         for (int j = 0; j < FAN; ++j)
-            if ((uint32_t)j < k) dl_global<V>(dsts[j] + byte_off)[i] = v;
+            if ((uint32_t)j < k) dl_st<POL>(dl_global<V>(dsts[j] + byte_off) + i, v);
     }
 }
 
@@ -122,17 +146,17 @@ __device__ __forceinline__ void dl_move_tile(const char *src, char *const (&dsts
     if (tile == 0) {
         // head bytes by threads 0..15, tail bytes by threads 32..47
         if (tid < g.head) {
-            uint8_t v = dl_global<uint8_t>(src)[tid];
+            uint8_t v = dl_ld<POL>(dl_global<uint8_t>(src) + tid);
 #pragma unroll
             for (int j = 0; j < FAN; ++j)
-                if ((uint32_t)j < k) dl_global<uint8_t>(dsts[j])[tid] = v;
+                if ((uint32_t)j < k) dl_st<POL>(dl_global<uint8_t>(dsts[j]) + tid, v);
         }
         if (tid >= 32 && tid - 32 < g.tail) {
             uint64_t off = (uint64_t)g.head + g.body * g.esize + (tid - 32);
-            uint8_t v = dl_global<uint8_t>(src)[off];
+            uint8_t v = dl_ld<POL>(dl_global<uint8_t>(src) + off);
 #pragma unroll
             for (int j = 0; j < FAN; ++j)
-                if ((uint32_t)j < k) dl_global<uint8_t>(dsts[j])[off] = v;
+                if ((uint32_t)j < k) dl_st<POL>(dl_global<uint8_t>(dsts[j]) + off, v);
         }
     }
 
@@ -182,9 +206,9 @@ __device__ __forceinline__ void dl_move_tile(const char *src, char *const (&dsts
             }
         }
     } else if (g.esize == 4) {
-        dl_copy_narrow<uint32_t, FAN>(src, dsts, k, off, n, tid, nthr);
+        dl_copy_narrow<uint32_t, FAN, POL>(src, dsts, k, off, n, tid, nthr);
     } else {
-        dl_copy_narrow<uint8_t, FAN>(src, dsts, k, off, n, tid, nthr);
+        dl_copy_narrow<uint8_t, FAN, POL>(src, dsts, k, off, n, tid, nthr);
     }
 }
 

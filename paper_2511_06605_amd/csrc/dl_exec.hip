@@ -92,7 +92,7 @@ __device__ __forceinline__ uint32_t dl_arm_wait(const dl_arm &a)
             }
             if (!a.direct) {
                 // pass the word on: one flag per group of workgroups, each in its own cache line
-                __atomic_thread_fence(__ATOMIC_RELEASE);
+                // (the flag carries everything the others need, so it is not ordered against anything)
                 const uint32_t groups = gridDim.x < DL_ARM_GROUPS ? gridDim.x : DL_ARM_GROUPS;
                 for (uint32_t g = 0; g < groups; ++g)
                     __hip_atomic_store((uint64_t *)((char *)a.go + g * DL_ARM_STRIDE), (a.ticket << 2) | go,
@@ -115,10 +115,9 @@ __device__ __forceinline__ uint32_t dl_arm_wait(const dl_arm &a)
         s_go = go;
     }
     __syncthreads();
-    const uint32_t go = s_go;
-    // everything written before the doorbell was rung (the sources) is visible from here on
-    if (go == DL_GO_RUN) __atomic_thread_fence(__ATOMIC_ACQUIRE);
-    return go;
+    // No cache invalidate here: the copy that follows loads at system scope (DL_POL_COHERENT), so
+    // it sees everything that was written before the doorbell was rung.
+    return s_go;
 }
 
 // Count this workgroup in; the last one to arrive publishes the completion word.
@@ -126,8 +125,15 @@ __device__ __forceinline__ uint32_t dl_arm_wait(const dl_arm &a)
 // of each group is counted at the top, so no counter sees more than
 // grid / DL_ARM_GROUPS + DL_ARM_GROUPS updates.  The low 16 bits of a counter
 // count arrivals, the high bits count workgroups that skipped the copy.
+//
+// No cache write-back anywhere: the copy stored at system scope, so once every
+// wavefront has drained its memory counter the workgroup's bytes are visible to
+// the host and to every later kernel, and relaxed counters suffice.  (With
+// ordinary stores each workgroup had to write the L2 back before counting
+// itself in; that serialised per XCD and cost ~0.5 us per workgroup.)
 __device__ __forceinline__ void dl_arm_finish(const dl_arm &a, uint32_t go)
 {
+    dl_drain_stores();
     __syncthreads();
     if (threadIdx.x == 0) {
         const uint32_t grid = gridDim.x;
@@ -136,21 +142,21 @@ __device__ __forceinline__ void dl_arm_finish(const dl_arm &a, uint32_t go)
         const uint32_t gsize = (grid - g + DL_ARM_GROUPS - 1) / DL_ARM_GROUPS;
         uint32_t *gcount = (uint32_t *)((char *)a.arrive + g * DL_ARM_STRIDE);
         uint32_t *top = (uint32_t *)((char *)a.arrive + DL_ARM_GROUPS * DL_ARM_STRIDE);
-        __atomic_thread_fence(__ATOMIC_RELEASE);  // system scope: this workgroup's stores
         uint32_t add = 1u + (go == DL_GO_RUN ? 0u : 0x10000u);
         uint32_t old = __hip_atomic_fetch_add(gcount, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if ((old & 0xFFFFu) != gsize - 1u) return;
-        // last of the group: carry the group's result to the top counter
+        // last of the group: leave the counter at zero for the slot's next request (the reset has
+        // completed before anything that can let that request start), carry the result to the top
         __hip_atomic_store(gcount, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __atomic_thread_fence(__ATOMIC_ACQ_REL);
+        dl_drain_stores();
         add = 1u + (((old >> 16) + (add >> 16)) << 16);
         old = __hip_atomic_fetch_add(top, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if ((old & 0xFFFFu) != groups - 1u) return;
         // last of all
         const uint32_t skipped = (old >> 16) + (add >> 16);
         __hip_atomic_store(top, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __atomic_thread_fence(__ATOMIC_ACQUIRE);
-        __hip_atomic_store(a.done, a.ticket | (skipped ? DL_DONE_SKIPPED : 0ull), __ATOMIC_RELEASE,
+        dl_drain_stores();
+        __hip_atomic_store(a.done, a.ticket | (skipped ? DL_DONE_SKIPPED : 0ull), __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_SYSTEM);
     }
 }
@@ -163,9 +169,9 @@ __global__ void __launch_bounds__(512) dl_armed_list_kernel(const dl_klist<Item,
         const uint32_t total = p.tile_end[p.n - 1];
         for (uint32_t b = blockIdx.x; b < total; b += gridDim.x) {
             if constexpr (ROWS)
-                dl_run_rows<DL_POL_PLAIN>(p, b);
+                dl_run_rows<DL_POL_COHERENT>(p, b);
             else
-                dl_run_tile<DL_POL_PLAIN>(p, b);
+                dl_run_tile<DL_POL_COHERENT>(p, b);
         }
     }
     dl_arm_finish(a, go);
@@ -179,7 +185,7 @@ __global__ void __launch_bounds__(512) dl_armed_table_kernel(const Item *__restr
     if (go == DL_GO_RUN) {
         for (uint32_t b = blockIdx.x; b < n; b += gridDim.x) {
             const Item it = items[b];
-            dl_run_item<DL_POL_PLAIN>(it, 0, tile_bytes, split);
+            dl_run_item<DL_POL_COHERENT>(it, 0, tile_bytes, split);
         }
     }
     dl_arm_finish(a, go);
