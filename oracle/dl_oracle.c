@@ -8,15 +8,16 @@
  * called by it; only the tests, the smoke check and the benchmark's CPU
  * baseline use it.
  *
- * All four results are pinned by the CPU tests (per-byte index formulas on
- * tiny inputs, reductions to numpy library routines, and the invariants of
- * the collectives), so no function here is "parity unpinned".
+ * Every result is pinned by the CPU tests (per-byte index formulas on tiny
+ * inputs, reductions to numpy library routines, and the invariants of the
+ * collectives), so no function here is "parity unpinned".
  *
  * Every function returns 0 on success and a negative value on a malformed
  * request.  Buffers are host memory owned by the caller.
  */
 #include <stddef.h>
 #include <stdint.h>
+#include <stdlib.h>
 #include <string.h>
 
 typedef struct {
@@ -142,5 +143,83 @@ int ref_alltoall(const void *const *in, void *const *out, int W, const size_t *C
             memcpy((char *)out[j] + recv, (const char *)in[i] + send, n);
         }
     }
+    return 0;
+}
+
+typedef struct {
+    void *a;
+    void *b;
+    size_t bytes;
+} ref_swap;
+
+/*
+ * Batch of swaps (Sec. IV-C): swap k exchanges the contents of the two memory
+ * locations a_k and b_k.  Written as what the swap command replaces: three
+ * copies, to and from a temporary buffer.  The swaps of a batch are independent
+ * and unordered, so every range that any of them touches must be disjoint from
+ * every other one (the hazard rule of Sec. IV-D applied to ranges that are
+ * both read and written); -2 otherwise.  A swap whose two locations are the
+ * identical range is a no-op.
+ */
+int ref_batch_swap(const ref_swap *d, size_t n)
+{
+    if (n && !d)
+        return -1;
+    for (size_t k = 0; k < n; ++k)
+        if (d[k].bytes && (!d[k].a || !d[k].b))
+            return -1;
+    for (size_t k = 0; k < n; ++k) {
+        if (d[k].a != d[k].b && ranges_overlap(d[k].a, d[k].bytes, d[k].b, d[k].bytes))
+            return -2;
+        for (size_t m = k + 1; m < n; ++m) {
+            if (ranges_overlap(d[k].a, d[k].bytes, d[m].a, d[m].bytes) ||
+                ranges_overlap(d[k].a, d[k].bytes, d[m].b, d[m].bytes) ||
+                ranges_overlap(d[k].b, d[k].bytes, d[m].a, d[m].bytes) ||
+                ranges_overlap(d[k].b, d[k].bytes, d[m].b, d[m].bytes))
+                return -2;
+        }
+    }
+    for (size_t k = 0; k < n; ++k) {
+        if (d[k].bytes == 0 || d[k].a == d[k].b)
+            continue;
+        void *tmp = malloc(d[k].bytes);
+        if (!tmp)
+            return -3;
+        memcpy(tmp, d[k].a, d[k].bytes);
+        memcpy(d[k].a, d[k].b, d[k].bytes);
+        memcpy(d[k].b, tmp, d[k].bytes);
+        free(tmp);
+    }
+    return 0;
+}
+
+/*
+ * In-place all-to-all with equal chunks (Sec. IV-C; Fig. 2 right): buf[i]
+ * holds W chunks of c bytes, chunk j being what rank i sends to rank j.
+ * Afterwards buf[j] chunk i holds what buf[i] chunk j held before:
+ *   new buf[j][i*c + t] = old buf[i][j*c + t].
+ * Written as the definition: every buffer is copied aside first, then every
+ * chunk is placed from the copies.  (That the same result is a series of swaps
+ * between the buffers, as the paper realises it, is checked by the tests.)
+ */
+int ref_alltoall_inplace(void *const *buf, int W, size_t c)
+{
+    if (W < 1 || !buf)
+        return -1;
+    if (c == 0)
+        return 0;
+    for (int i = 0; i < W; ++i)
+        if (!buf[i])
+            return -1;
+    const size_t row = (size_t)W * c;
+    char *old = malloc((size_t)W * row);
+    if (!old)
+        return -3;
+    for (int i = 0; i < W; ++i)
+        memcpy(old + (size_t)i * row, buf[i], row);
+    for (int i = 0; i < W; ++i)
+        for (int j = 0; j < W; ++j)
+            memcpy((char *)buf[j] + (size_t)i * c, old + (size_t)i * row + (size_t)j * c, c);
+    free(old);
     return 0;
 }

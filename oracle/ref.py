@@ -24,6 +24,10 @@ class RefCopy(ctypes.Structure):
     _fields_ = [("src", ctypes.c_void_p), ("dst", ctypes.c_void_p), ("bytes", ctypes.c_size_t)]
 
 
+class RefSwap(ctypes.Structure):
+    _fields_ = [("a", ctypes.c_void_p), ("b", ctypes.c_void_p), ("bytes", ctypes.c_size_t)]
+
+
 def build(src: str = SRC, out: str = LIB, force: bool = False) -> str:
     """Compile the checker with gcc (plain C, no GPU toolchain)."""
     if force or not os.path.exists(out) or os.path.getmtime(out) < os.path.getmtime(src):
@@ -45,6 +49,10 @@ def load(path: str | None = None) -> ctypes.CDLL:
     lib.ref_allgather.argtypes = [VPP, VPP, ctypes.c_int, ctypes.c_size_t]
     lib.ref_alltoall.restype = ctypes.c_int
     lib.ref_alltoall.argtypes = [VPP, VPP, ctypes.c_int, ctypes.POINTER(ctypes.c_size_t)]
+    lib.ref_batch_swap.restype = ctypes.c_int
+    lib.ref_batch_swap.argtypes = [ctypes.POINTER(RefSwap), ctypes.c_size_t]
+    lib.ref_alltoall_inplace.restype = ctypes.c_int
+    lib.ref_alltoall_inplace.argtypes = [VPP, ctypes.c_int, ctypes.c_size_t]
     return lib
 
 
@@ -148,3 +156,42 @@ def first_hazard(buffers, descs, lib=None) -> int:
     lib = lib or _get()
     descs = list(descs)
     return int(lib.ref_first_hazard(_descs(buffers, descs), len(descs)))
+
+
+def batch_swap(buffers, descs, lib=None):
+    """Run a batch of swaps in place on ``buffers``.
+
+    descs: iterable of (a_buffer_index, a_offset, b_buffer_index, b_offset,
+    bytes).  Raises ValueError if two ranges of the batch overlap.
+    """
+    lib = lib or _get()
+    descs = list(descs)
+    arr = (RefSwap * max(len(descs), 1))()
+    for n, (ab, ao, bb, bo, nb) in enumerate(descs):
+        abuf, bbuf = _check_buf(buffers[ab]), _check_buf(buffers[bb])
+        ao, bo, nb = int(ao), int(bo), int(nb)
+        if ao + nb > abuf.size or bo + nb > bbuf.size:
+            raise ValueError("descriptor outside its buffer")
+        arr[n].a = abuf.ctypes.data + ao
+        arr[n].b = bbuf.ctypes.data + bo
+        arr[n].bytes = nb
+    rc = lib.ref_batch_swap(arr, len(descs))
+    if rc == -2:
+        raise ValueError("two ranges of the batch overlap")
+    if rc:
+        raise RuntimeError(f"ref_batch_swap failed: {rc}")
+    return buffers
+
+
+def alltoall_inplace(bufs, chunk_bytes, lib=None):
+    """In-place all-to-all with equal chunks on copies of ``bufs`` (W buffers
+    of W * chunk_bytes bytes); returns the new buffers."""
+    lib = lib or _get()
+    W, c = len(bufs), int(chunk_bytes)
+    outs = [_check_buf(a).copy() for a in bufs]
+    if any(a.size != W * c for a in outs):
+        raise ValueError("every buffer must hold W chunks")
+    rc = lib.ref_alltoall_inplace(_ptrs(outs), W, c)
+    if rc:
+        raise RuntimeError(f"ref_alltoall_inplace failed: {rc}")
+    return outs

@@ -136,3 +136,29 @@ def b2b_batch(n: int, copy_bytes: int, arena_bytes: int, seed: int, align: int =
         out[i] = (s, d, copy_bytes)
         i += 1
     return arena, out
+
+
+def swap_batch(n: int, swap_bytes: int, arena_bytes: int, seed: int, align: int = 256):
+    """n independent swaps inside one arena.
+
+    Returns (arena, descs) with descs an (n, 3) uint64 array of
+    (a_offset, b_offset, bytes); all 2n ranges are pairwise disjoint.
+    """
+    rng = np.random.default_rng(seed)
+    arena = rng.integers(0, 256, arena_bytes, dtype=np.uint8)
+    slots = (arena_bytes - swap_bytes) // align + 1
+    taken: list[tuple[int, int]] = []
+    out = np.zeros((n, 3), dtype=np.uint64)
+    i = 0
+    while i < n:
+        a = int(rng.integers(0, slots)) * align
+        b = int(rng.integers(0, slots)) * align
+        ra, rb = (a, a + swap_bytes), (b, b + swap_bytes)
+        if ra[0] < rb[1] and rb[0] < ra[1]:
+            continue
+        if any(x0 < y1 and y0 < x1 for x0, x1 in (ra, rb) for y0, y1 in taken):
+            continue
+        taken += [ra, rb]
+        out[i] = (a, b, swap_bytes)
+        i += 1
+    return arena, out

@@ -48,6 +48,26 @@ def run_pins(lib):
     assert ref.first_hazard([buf], [(0, 0, 0, 100, 50), (0, 60, 0, 150, 10)], lib=lib) == -1
     assert ref.first_hazard([buf], [(0, 0, 0, 100, 50), (0, 120, 0, 200, 10)], lib=lib) == 0
 
+    arena, descs = inputs.swap_batch(5, 30, 2048, seed=6, align=2)
+    want = arena.copy()
+    for a, b, n in descs.astype(np.int64):
+        want[a:a + n], want[b:b + n] = arena[b:b + n].copy(), arena[a:a + n].copy()
+    got = ref.batch_swap([arena.copy()], [(0, a, 0, b, n) for a, b, n in descs], lib=lib)[0]
+    assert np.array_equal(got, want)
+    for bad in ([(0, 0, 0, 100, 20), (0, 110, 0, 200, 20)], [(0, 0, 0, 100, 20), (0, 200, 0, 19, 20)],
+                [(0, 0, 0, 10, 20)]):
+        try:
+            ref.batch_swap([buf.copy()], bad, lib=lib)
+        except ValueError:
+            pass
+        else:
+            raise AssertionError("overlapping swap ranges accepted")
+    ref.batch_swap([buf.copy()], [(0, 0, 0, 20, 20), (0, 40, 0, 60, 20)], lib=lib)   # touching ranges are fine
+
+    c = 7
+    bufs = inputs.alltoall_inputs(inputs.uniform_chunks(W, c), seed=8)
+    got = ref.alltoall_inplace(bufs, c, lib=lib)
+    assert np.array_equal(np.stack(got), np.stack(bufs).reshape(W, W, c).transpose(1, 0, 2).reshape(W, W * c))
 
 
 if __name__ == "__main__":

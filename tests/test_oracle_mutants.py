@@ -36,6 +36,18 @@ MUTANTS = {
                            "if (0)\n                return (long)a;"),
     "hz_closed_interval": ("return (uintptr_t)a < (uintptr_t)b + bn && (uintptr_t)b < (uintptr_t)a + an;",
                            "return (uintptr_t)a <= (uintptr_t)b + bn && (uintptr_t)b <= (uintptr_t)a + an;"),
+    # swap: one copy of the three dropped, exchange in one direction only, hazard check between swaps incomplete
+    "sw_no_restore": ("memcpy(d[k].b, tmp, d[k].bytes);", "memcpy(d[k].b, d[k].a, d[k].bytes);"),
+    "sw_one_way": ("memcpy(d[k].a, d[k].b, d[k].bytes);\n", "\n"),
+    "sw_hazard_ab_only": ("ranges_overlap(d[k].b, d[k].bytes, d[m].a, d[m].bytes) ||", "0 ||"),
+    "sw_hazard_self": ("if (d[k].a != d[k].b && ranges_overlap(d[k].a, d[k].bytes, d[k].b, d[k].bytes))", "if (0)"),
+    # in-place all-to-all: not transposed, chunk index and rank exchanged on one side only, wrong stride
+    "ip_not_transposed": ("memcpy((char *)buf[j] + (size_t)i * c, old + (size_t)i * row + (size_t)j * c, c);",
+                          "memcpy((char *)buf[i] + (size_t)j * c, old + (size_t)i * row + (size_t)j * c, c);"),
+    "ip_wrong_slot": ("memcpy((char *)buf[j] + (size_t)i * c, old + (size_t)i * row + (size_t)j * c, c);",
+                      "memcpy((char *)buf[j] + (size_t)j * c, old + (size_t)i * row + (size_t)j * c, c);"),
+    "ip_reads_new": ("memcpy((char *)buf[j] + (size_t)i * c, old + (size_t)i * row + (size_t)j * c, c);",
+                     "memcpy((char *)buf[j] + (size_t)i * c, (char *)buf[i] + (size_t)j * c, c);"),
 }
 
 

@@ -8,7 +8,10 @@ Each pin is independent of ``oracle/dl_oracle.c``:
     all-to-all twice with the transposed chunk matrix is the identity,
     broadcast destinations equal the source, byte-multiset conservation),
   * W = 1, where every operation is a plain copy,
-  * the hazard rule of back-to-back copies (Sec. IV-D) on hand-built cases.
+  * the hazard rule of back-to-back copies (Sec. IV-D) on hand-built cases,
+  * swap and the in-place all-to-all (Sec. IV-C): slice exchange, the three
+    copies through a temporary that a swap replaces, reshape+transpose, the
+    out-of-place all-to-all, the series of pairwise swaps, involution.
 The paper prints no worked numeric example for these operations, so there is
 no golden fixture of printed values; tests/golden holds only the copy counts
 the paper states.
@@ -244,3 +247,88 @@ def test_generated_batches_are_hazard_free(ref):
         for (a0, a1) in iv:
             for (b0, b1) in sv:
                 assert a1 <= b0 or b1 <= a0
+
+
+# ------------------------------------------- swap and in-place all-to-all (Sec. IV-C)
+
+def test_swap_is_slice_exchange(ref):
+    arena, descs = inputs.swap_batch(9, 70, 8192, seed=1, align=2)
+    want = arena.copy()
+    for a, b, n in descs.astype(np.int64):
+        want[a:a + n], want[b:b + n] = arena[b:b + n].copy(), arena[a:a + n].copy()
+    got = ref.batch_swap([arena.copy()], [(0, a, 0, b, n) for a, b, n in descs])[0]
+    assert np.array_equal(got, want)
+    assert not np.array_equal(got, arena)
+
+
+@pytest.mark.parametrize("n", [0, 1, 15, 16, 17, 4097])
+def test_swap_equals_three_copies_through_a_temporary(ref, n):
+    """What the swap command replaces (Sec. IV-C): copy a to a temporary, b to a, the temporary to b."""
+    rng = np.random.default_rng(n)
+    a, b = inputs.payload(rng, n), inputs.payload(rng, n)
+    x, y, tmp = a.copy(), b.copy(), np.zeros(n, dtype=np.uint8)
+    ref.batch_copy([x, y, tmp], [(0, 0, 2, 0, n)])
+    ref.batch_copy([x, y, tmp], [(1, 0, 0, 0, n)])
+    ref.batch_copy([x, y, tmp], [(2, 0, 1, 0, n)])
+    p, q = a.copy(), b.copy()
+    ref.batch_swap([p, q], [(0, 0, 1, 0, n)])
+    assert np.array_equal(p, x) and np.array_equal(q, y)
+    assert np.array_equal(p, b) and np.array_equal(q, a)
+
+
+def test_swap_twice_is_identity_and_order_is_free(ref):
+    arena, descs = inputs.swap_batch(12, 100, 16384, seed=2, align=4)
+    d = [(0, a, 0, b, n) for a, b, n in descs]
+    once = ref.batch_swap([arena.copy()], d)[0]
+    assert np.array_equal(ref.batch_swap([once.copy()], d)[0], arena)
+    assert np.array_equal(ref.batch_swap([arena.copy()], d[::-1])[0], once)
+    # exchanging the two locations of a descriptor changes nothing
+    assert np.array_equal(ref.batch_swap([arena.copy()], [(0, b, 0, a, n) for a, b, n in descs])[0], once)
+
+
+def test_swap_rejects_overlapping_ranges(ref):
+    buf = np.arange(256, dtype=np.uint8)
+    with pytest.raises(ValueError):
+        ref.batch_swap([buf.copy()], [(0, 0, 0, 10, 20)])                      # its own two ranges overlap
+    with pytest.raises(ValueError):
+        ref.batch_swap([buf.copy()], [(0, 0, 0, 100, 20), (0, 110, 0, 200, 20)])  # b of one, a of the other
+    with pytest.raises(ValueError):
+        ref.batch_swap([buf.copy()], [(0, 0, 0, 100, 20), (0, 200, 0, 19, 20)])   # a of one, b of the other
+    ok = ref.batch_swap([buf.copy()], [(0, 0, 0, 20, 20), (0, 40, 0, 60, 20), (0, 90, 0, 90, 10)])[0]  # touching; identical
+    assert np.array_equal(ok[:20], buf[20:40]) and np.array_equal(ok[40:60], buf[60:80]) and np.array_equal(ok[90:100], buf[90:100])
+
+
+@pytest.mark.parametrize("W", WS)
+@pytest.mark.parametrize("c", [0, 1, 16, 17, 255])
+def test_alltoall_inplace_is_transpose_and_matches_out_of_place(ref, W, c):
+    bufs = inputs.alltoall_inputs(inputs.uniform_chunks(W, c), seed=W + c)
+    got = ref.alltoall_inplace(bufs, c)
+    want = np.stack(bufs).reshape(W, W, c).transpose(1, 0, 2).reshape(W, W * c)
+    assert np.array_equal(np.stack(got), want)
+    for g, o in zip(got, ref.alltoall(bufs, inputs.uniform_chunks(W, c))):
+        assert np.array_equal(g, o)
+    back = ref.alltoall_inplace(got, c)
+    for x, y in zip(back, bufs):
+        assert np.array_equal(x, y)
+
+
+@pytest.mark.parametrize("W,c", [(2, 3), (3, 5), (5, 2)])
+def test_alltoall_inplace_bruteforce(ref, W, c):
+    bufs = inputs.alltoall_inputs(inputs.uniform_chunks(W, c), seed=7 * W + c)
+    got = ref.alltoall_inplace(bufs, c)
+    for j in range(W):
+        for p in range(W * c):
+            assert got[j][p] == bufs[p // c][j * c + p % c]
+
+
+@pytest.mark.parametrize("W", [2, 3, 8])
+def test_alltoall_inplace_is_a_series_of_swaps(ref, W):
+    """The paper's realisation (Sec. IV-C): one swap per pair of ranks, W(W-1)/2 in all, nothing on the diagonal."""
+    c = 48
+    bufs = inputs.alltoall_inputs(inputs.uniform_chunks(W, c), seed=W)
+    work = [b.copy() for b in bufs]
+    swaps = [(i, j * c, j, i * c, c) for i in range(W) for j in range(i + 1, W)]
+    assert len(swaps) == W * (W - 1) // 2
+    ref.batch_swap(work, swaps)
+    for x, y in zip(work, ref.alltoall_inplace(bufs, c)):
+        assert np.array_equal(x, y)
