@@ -143,6 +143,17 @@ def other_operations(dl, benchaid, inputs, torch, stream, ag_reqs, ag_bufs, ag_s
         rows.append(row)
     res["alltoall_uniform"] = rows
 
+    # in-place all-to-all (one swap per pair of ranks): every off-diagonal chunk is read once and written once
+    rows = []
+    for c in [KiB << i for i in range(13)]:
+        bufs = inputs.alltoall_inputs(inputs.uniform_chunks(W, c), seed=c.bit_length(), kind="fp16")
+        d_buf = [dev(a) for a in bufs]
+        req = benchaid.alltoall_inplace_request(d_buf, c)
+        row = {"chunk_bytes": c}
+        row.update(timed(req, 2 * W * (W - 1) * c, c <= 128 * KiB, calls=(50 if c <= 128 * KiB else 10)))
+        rows.append(row)
+    res["alltoall_inplace_uniform"] = rows
+
     # MoE dispatch all-to-all: hidden 7168 bf16, 256 experts over 8 ranks, top-8
     rows = []
     for T in (16, 128, 512):

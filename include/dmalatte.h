@@ -125,6 +125,38 @@ int dl_allgather(const void *const *in, void *const *out, int W, size_t bytes_pe
  */
 int dl_alltoall(const void *const *in, void *const *out, int W, const size_t *chunk_bytes, void *stream);
 
+/* One swap of a batch: the `bytes` bytes at device pointer a and the `bytes` bytes at b change places. */
+typedef struct dl_swap_desc {
+    void *a;
+    void *b;
+    size_t bytes;
+} dl_swap_desc;
+
+/*
+ * Batch of swaps (paper Sec. IV-C: the swap command exchanges the contents of
+ * two memory locations, which otherwise takes a temporary buffer and three
+ * copies).  n independent swaps, no ordering among them, one completion; every
+ * 16-byte piece is read from both ranges into registers and written back
+ * crossed, so there is no temporary.
+ * Precondition: all 2n ranges are pairwise disjoint (each is both read and
+ * written).  A descriptor with a == b is a no-op.  With validation on, a
+ * violated precondition returns DL_ERR_OVERLAP and nothing is enqueued.
+ * desc: host array.  n == 0 or all bytes == 0: DL_OK, no work.
+ */
+int dl_batch_swap(const dl_swap_desc *desc, size_t n, void *stream);
+
+/*
+ * In-place all-to-all with equal chunks (paper Sec. IV-C, Fig. 2 right): buf[i]
+ * (device, W * chunk_bytes bytes) holds W chunks, chunk j being what rank i
+ * sends to rank j.  Afterwards
+ *   buf[j][i*c + t] = old buf[i][j*c + t],  c = chunk_bytes,
+ * i.e. the result of dl_alltoall with a uniform chunk matrix, written over the
+ * inputs.  Lowered to one swap per pair of ranks, W(W-1)/2 in all; the diagonal
+ * chunks stay where they are.  buf: host array of W device pointers to
+ * pairwise disjoint buffers, 1 <= W <= DL_MAX_FANOUT.
+ */
+int dl_alltoall_inplace(void *const *buf, int W, size_t chunk_bytes, void *stream);
+
 /* ------------------------------------------------------------- prelaunch mode */
 
 /*
@@ -210,6 +242,14 @@ long dl_plan_batch(const dl_copy_desc *desc, size_t n, dl_plan_item *items, size
 /* Host-only: index of the first item whose destination overlaps another
  * destination or any source (the hazard rule), or -1 if there is none. */
 long dl_plan_first_hazard(const dl_plan_item *items, size_t n);
+
+/* Host-only: the swaps an in-place all-to-all lowers to (at most `cap` written;
+ * returns their number, or a negative dl_status). */
+long dl_plan_alltoall_inplace(void *const *buf, int W, size_t chunk_bytes, dl_swap_desc *swaps, size_t cap);
+
+/* Host-only: index of the first swap one of whose ranges overlaps another range
+ * of the batch (its own other range included), or -1 if there is none. */
+long dl_plan_swap_first_hazard(const dl_swap_desc *swaps, size_t n);
 
 /* Host-only: number of workgroup tiles the item list is cut into for a given
  * tile size (the grid of the one-shot launch). */

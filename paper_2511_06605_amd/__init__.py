@@ -12,4 +12,5 @@ from .binding import (  # noqa: F401
     dl_alltoall, dl_batch_copy, dl_broadcast, dl_get_config, dl_get_mode, dl_init, dl_last_ticket,
     dl_plan_allgather, dl_plan_alltoall, dl_plan_batch, dl_plan_broadcast, dl_plan_first_hazard,
     dl_plan_tiles, dl_prelaunch_start, dl_prelaunch_stop, dl_set_config, dl_set_mode,
-    dl_set_validate, dl_shutdown, dl_trigger, dl_wait, dl_wait_armed)
+    dl_set_validate, dl_shutdown, dl_trigger, dl_wait, dl_wait_armed, dl_batch_swap, dl_alltoall_inplace,
+    dl_plan_alltoall_inplace, dl_plan_swap_first_hazard)

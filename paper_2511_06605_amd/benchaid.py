@@ -12,7 +12,7 @@ from . import binding
 _HERE = os.path.dirname(os.path.abspath(__file__))
 AID_PATH = os.path.join(_HERE, "libdl_benchaid.so")
 
-OP_BATCH, OP_BROADCAST, OP_ALLGATHER, OP_ALLTOALL, OP_MEMCPY_ASYNC, OP_MEMCPY_BATCH = range(6)
+OP_BATCH, OP_BROADCAST, OP_ALLGATHER, OP_ALLTOALL, OP_MEMCPY_ASYNC, OP_MEMCPY_BATCH, OP_SWAP, OP_ALLTOALL_INPLACE = range(8)
 WAIT_STREAM, WAIT_TRIGGER, WAIT_ARM_AND_TRIGGER = 0, 1, 2
 
 
@@ -85,6 +85,13 @@ def copy_list_request(descs, op=OP_BATCH) -> Prepared:
     r = Request(op=op, n=len(descs))
     r.desc = ctypes.cast(d, ctypes.POINTER(binding.CopyDesc))
     return Prepared(r, (d,))
+
+
+def alltoall_inplace_request(bufs, chunk_bytes) -> Prepared:
+    b = binding._ptr_array(list(bufs))
+    r = Request(op=OP_ALLTOALL_INPLACE, W=len(bufs), bytes=int(chunk_bytes))
+    r.out = ctypes.cast(b, ctypes.POINTER(ctypes.c_void_p))
+    return Prepared(r, (b,))
 
 
 def _rc(rc, what):

@@ -36,7 +36,8 @@ EXPORTS = [
     "dl_prelaunch_start", "dl_prelaunch_stop", "dl_last_ticket", "dl_trigger", "dl_wait", "dl_wait_armed",
     "dl_get_config",
     "dl_set_config", "dl_plan_allgather", "dl_plan_alltoall", "dl_plan_broadcast", "dl_plan_batch",
-    "dl_plan_first_hazard", "dl_plan_tiles",
+    "dl_plan_first_hazard", "dl_plan_tiles", "dl_batch_swap", "dl_alltoall_inplace", "dl_plan_alltoall_inplace",
+    "dl_plan_swap_first_hazard",
 ]
 
 
@@ -48,6 +49,10 @@ class DlError(RuntimeError):
 
 class CopyDesc(ctypes.Structure):
     _fields_ = [("src", ctypes.c_void_p), ("dst", ctypes.c_void_p), ("bytes", ctypes.c_size_t)]
+
+
+class SwapDesc(ctypes.Structure):
+    _fields_ = [("a", ctypes.c_void_p), ("b", ctypes.c_void_p), ("bytes", ctypes.c_size_t)]
 
 
 class Config(ctypes.Structure):
@@ -87,6 +92,12 @@ def lib() -> ctypes.CDLL:
         raise ImportError(
             f"{LIB_PATH} is missing: build it with `python -m paper_2511_06605_amd.build` "
             "(there is no fallback path)")
+    try:
+        # One HIP runtime per process: PyTorch ships its own, and device memory and streams come
+        # from it, so it has to be loaded first for the library to bind to that same runtime.
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     L = ctypes.CDLL(LIB_PATH)
     vp, vpp = ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p)
     szp = ctypes.POINTER(ctypes.c_size_t)
@@ -119,6 +130,11 @@ def lib() -> ctypes.CDLL:
                                           ctypes.c_size_t]),
         "dl_plan_first_hazard": (ctypes.c_long, [ctypes.POINTER(PlanItem), ctypes.c_size_t]),
         "dl_plan_tiles": (ctypes.c_uint64, [ctypes.POINTER(PlanItem), ctypes.c_size_t, ctypes.c_uint32]),
+        "dl_batch_swap": (ctypes.c_int, [ctypes.POINTER(SwapDesc), ctypes.c_size_t, vp]),
+        "dl_alltoall_inplace": (ctypes.c_int, [vpp, ctypes.c_int, ctypes.c_size_t, vp]),
+        "dl_plan_alltoall_inplace": (ctypes.c_long, [vpp, ctypes.c_int, ctypes.c_size_t, ctypes.POINTER(SwapDesc),
+                                                     ctypes.c_size_t]),
+        "dl_plan_swap_first_hazard": (ctypes.c_long, [ctypes.POINTER(SwapDesc), ctypes.c_size_t]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -161,6 +177,13 @@ def _desc_array(descs):
     arr = (CopyDesc * max(len(descs), 1))()
     for i, (s, d, n) in enumerate(descs):
         arr[i].src, arr[i].dst, arr[i].bytes = _addr(s), _addr(d), int(n)
+    return arr
+
+
+def _swap_array(descs):
+    arr = (SwapDesc * max(len(descs), 1))()
+    for i, (a, b, n) in enumerate(descs):
+        arr[i].a, arr[i].b, arr[i].bytes = _addr(a), _addr(b), int(n)
     return arr
 
 
@@ -244,6 +267,18 @@ def dl_alltoall(ins, outs, chunk_bytes, stream=None) -> None:
            "dl_alltoall")
 
 
+def dl_batch_swap(descs, stream=None) -> None:
+    """descs: sequence of (a, b, bytes)."""
+    descs = list(descs)
+    _check(lib().dl_batch_swap(_swap_array(descs), len(descs), _stream(stream)), "dl_batch_swap")
+
+
+def dl_alltoall_inplace(bufs, chunk_bytes: int, stream=None) -> None:
+    bufs = list(bufs)
+    _check(lib().dl_alltoall_inplace(_ptr_array(bufs), len(bufs), int(chunk_bytes), _stream(stream)),
+           "dl_alltoall_inplace")
+
+
 # -------------------------------------------------------------------- prelaunch
 
 def dl_prelaunch_start() -> None:
@@ -309,6 +344,23 @@ def dl_plan_batch(descs):
     descs = list(descs)
     d = _desc_array(descs)
     return _items_out(lambda arr, cap: lib().dl_plan_batch(d, len(descs), arr, cap))
+
+
+def dl_plan_alltoall_inplace(bufs, chunk_bytes: int):
+    """The (a, b, bytes) swaps an in-place all-to-all lowers to."""
+    bufs = list(bufs)
+    p = _ptr_array(bufs)
+    n = lib().dl_plan_alltoall_inplace(p, len(bufs), int(chunk_bytes), None, 0)
+    if n < 0:
+        raise DlError(int(n), "dl_plan_alltoall_inplace")
+    arr = (SwapDesc * max(n, 1))()
+    assert lib().dl_plan_alltoall_inplace(p, len(bufs), int(chunk_bytes), arr, n) == n
+    return [(arr[i].a or 0, arr[i].b or 0, arr[i].bytes) for i in range(n)]
+
+
+def dl_plan_swap_first_hazard(descs) -> int:
+    descs = list(descs)
+    return int(lib().dl_plan_swap_first_hazard(_swap_array(descs), len(descs)))
 
 
 def _items_in(items):

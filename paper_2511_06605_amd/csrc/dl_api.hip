@@ -147,14 +147,56 @@ long first_hazard(const dl_plan_item *items, size_t n)
     return worst;
 }
 
+// Swaps of an in-place all-to-all with equal chunks: rank i's chunk j and rank
+// j's chunk i change places, once per pair i < j.
+long lower_alltoall_inplace(void *const *buf, int W, size_t c, dl_swap_desc *out, size_t cap)
+{
+    if (W < 1 || W > DL_MAX_FANOUT || !buf) return DL_ERR_INVALID;
+    if (c == 0) return 0;
+    for (int i = 0; i < W; ++i)
+        if (!buf[i]) return DL_ERR_INVALID;
+    size_t n = 0;
+    for (int i = 0; i < W; ++i)
+        for (int j = i + 1; j < W; ++j) {
+            if (n < cap) out[n] = {(char *)buf[i] + (size_t)j * c, (char *)buf[j] + (size_t)i * c, c};
+            ++n;
+        }
+    return (long)n;
+}
+
+// First swap with a range that overlaps any other range of the batch.
+long swap_first_hazard(const dl_swap_desc *d, size_t n)
+{
+    std::vector<interval> r;
+    for (size_t i = 0; i < n; ++i) {
+        if (d[i].bytes == 0) continue;
+        r.push_back({(uint64_t)d[i].a, (uint64_t)d[i].a + d[i].bytes, i});
+        // a swap of a range with itself changes nothing, but the range still belongs to it
+        if (d[i].a != d[i].b) r.push_back({(uint64_t)d[i].b, (uint64_t)d[i].b + d[i].bytes, i});
+    }
+    std::sort(r.begin(), r.end(), [](const interval &x, const interval &y) { return x.lo < y.lo; });
+    long worst = -1;
+    size_t owner = 0;  // the range that reaches furthest so far
+    for (size_t q = 1; q < r.size(); ++q) {
+        if (r[q].lo < r[owner].hi) {
+            const long w = (long)std::min(r[q].item, r[owner].item);
+            if (worst < 0 || w < worst) worst = w;
+        }
+        if (r[q].hi > r[owner].hi) owner = q;
+    }
+    return worst;
+}
+
 std::vector<dl_plan_item> g_items;      // reused between calls: no allocation once warm
 std::vector<dl_plain_item> g_plain;
+std::vector<dl_swap_item> g_swaps;
+std::vector<dl_swap_desc> g_swap_descs;
 
-int execute(const dl_plan_item *items, size_t n, void *stream)
+// Runs `launch(stream, arm, &launched)` in the current mode: in prelaunch mode it
+// gets the next ticket's words and the ticket is committed if a kernel went out.
+template <class Launch>
+int run_in_mode(void *stream, Launch launch)
 {
-    if (!g_dl.inited) return DL_ERR_STATE;
-    if (n == 0) return DL_OK;
-    if (g_dl.validate && first_hazard(items, n) >= 0) return DL_ERR_OVERLAP;
     hipStream_t hs = (hipStream_t)stream;
     dl_arm arm;
     const dl_arm *armp = nullptr;
@@ -163,19 +205,50 @@ int execute(const dl_plan_item *items, size_t n, void *stream)
         if (rc != DL_OK) return rc;
         armp = &arm;
     }
-    bool all_plain = true;
-    for (size_t i = 0; i < n; ++i) all_plain &= items[i].k == 1;
     bool launched = false;
-    int rc;
-    if (all_plain) {
-        g_plain.resize(n);
-        for (size_t i = 0; i < n; ++i) g_plain[i] = {(const char *)items[i].src, (char *)items[i].dst[0], items[i].bytes};
-        rc = dl_exec_plain(g_plain.data(), n, hs, armp, &launched);
-    } else {
-        rc = dl_exec_fused(reinterpret_cast<const dl_fused_item *>(items), n, hs, armp, &launched);
-    }
+    const int rc = launch(hs, armp, &launched);
     if (armp && rc == DL_OK && launched) dl_armed_commit();
     return rc;
+}
+
+int execute(const dl_plan_item *items, size_t n, void *stream)
+{
+    if (!g_dl.inited) return DL_ERR_STATE;
+    if (n == 0) return DL_OK;
+    if (g_dl.validate && first_hazard(items, n) >= 0) return DL_ERR_OVERLAP;
+    bool all_plain = true;
+    for (size_t i = 0; i < n; ++i) all_plain &= items[i].k == 1;
+    return run_in_mode(stream, [&](hipStream_t hs, const dl_arm *armp, bool *launched) {
+        if (all_plain) {
+            g_plain.resize(n);
+            for (size_t i = 0; i < n; ++i)
+                g_plain[i] = {(const char *)items[i].src, (char *)items[i].dst[0], items[i].bytes};
+            return dl_exec_plain(g_plain.data(), n, hs, armp, launched);
+        }
+        return dl_exec_fused(reinterpret_cast<const dl_fused_item *>(items), n, hs, armp, launched);
+    });
+}
+
+int execute_swaps(const dl_swap_desc *d, size_t n, void *stream)
+{
+    if (!g_dl.inited) return DL_ERR_STATE;
+    if (n && !d) return DL_ERR_INVALID;
+    g_swaps.clear();
+    for (size_t i = 0; i < n; ++i) {
+        if (d[i].bytes == 0) continue;
+        if (!d[i].a || !d[i].b) return DL_ERR_INVALID;
+        if (d[i].a == d[i].b) continue;  // identical range: nothing changes
+        dl_swap_item it;
+        it.src = (const char *)d[i].a;
+        it.dst = (char *)d[i].b;
+        it.bytes = d[i].bytes;
+        g_swaps.push_back(it);
+    }
+    if (g_swaps.empty()) return DL_OK;
+    if (g_dl.validate && swap_first_hazard(d, n) >= 0) return DL_ERR_OVERLAP;
+    return run_in_mode(stream, [&](hipStream_t hs, const dl_arm *armp, bool *launched) {
+        return dl_exec_swap(g_swaps.data(), g_swaps.size(), hs, armp, launched);
+    });
 }
 
 // Lower with `fn` into the reusable buffer, growing it when the first pass
@@ -302,6 +375,28 @@ int dl_allgather(const void *const *in, void *const *out, int W, size_t bytes_pe
 int dl_alltoall(const void *const *in, void *const *out, int W, const size_t *chunk_bytes, void *stream)
 {
     return lower_and_execute([&](sink &s) { return lower_alltoall(in, out, W, chunk_bytes, s); }, stream);
+}
+
+int dl_batch_swap(const dl_swap_desc *desc, size_t n, void *stream) { return execute_swaps(desc, n, stream); }
+
+int dl_alltoall_inplace(void *const *buf, int W, size_t chunk_bytes, void *stream)
+{
+    const long n = lower_alltoall_inplace(buf, W, chunk_bytes, nullptr, 0);
+    if (n < 0) return (int)n;
+    g_swap_descs.resize((size_t)n);
+    lower_alltoall_inplace(buf, W, chunk_bytes, g_swap_descs.data(), g_swap_descs.size());
+    return execute_swaps(g_swap_descs.data(), g_swap_descs.size(), stream);
+}
+
+long dl_plan_alltoall_inplace(void *const *buf, int W, size_t chunk_bytes, dl_swap_desc *swaps, size_t cap)
+{
+    return lower_alltoall_inplace(buf, W, chunk_bytes, swaps, swaps ? cap : 0);
+}
+
+long dl_plan_swap_first_hazard(const dl_swap_desc *swaps, size_t n)
+{
+    if (!swaps) return -1;
+    return swap_first_hazard(swaps, n);
 }
 
 long dl_plan_allgather(const void *const *in, void *const *out, int W, size_t bytes_per_rank, int fuse_broadcast,

@@ -15,7 +15,8 @@
 extern "C" {
 
 typedef struct dlb_request {
-    int op;  // 0 batch, 1 broadcast, 2 all-gather, 3 all-to-all, 4 hipMemcpyAsync per desc, 5 hipMemcpyBatchAsync
+    int op;  // 0 batch, 1 broadcast, 2 all-gather, 3 all-to-all, 4 hipMemcpyAsync per desc, 5 hipMemcpyBatchAsync,
+             // 6 batch of swaps (desc as {a, b, bytes}), 7 in-place all-to-all (out = buffers, bytes = chunk)
     int k;
     int W;
     int pad;
@@ -74,6 +75,8 @@ int dlb_issue(const dlb_request *r, void *stream)
         }
         return 0;
     }
+    case 6: return dl_batch_swap((const dl_swap_desc *)r->desc, r->n, stream);
+    case 7: return dl_alltoall_inplace(r->out, r->W, r->bytes, stream);
     default: return DL_ERR_INVALID;
     }
 }

@@ -12,6 +12,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "dl_work.h"
 
 typedef uint32_t dl_u32x4 __attribute__((ext_vector_type(4)));
@@ -212,6 +214,49 @@ __device__ __forceinline__ void dl_move_tile(const char *src, char *const (&dsts
     }
 }
 
+// Exchange n elements of type V between a and b (disjoint ranges).
+template <typename V, int POL>
+__device__ __forceinline__ void dl_swap_elems(char *a, char *b, uint64_t byte_off, uint32_t n, uint32_t tid,
+                                              uint32_t nthr)
+{
+    DL_GLOBAL V *pa = dl_global<V>(a + byte_off);
+    DL_GLOBAL V *pb = dl_global<V>(b + byte_off);
+    for (uint32_t i = tid; i < n; i += nthr) {
+        const V x = dl_ld<POL>(pa + i);
+        const V y = dl_ld<POL>(pb + i);
+        dl_st<POL>(pa + i, y);
+        dl_st<POL>(pb + i, x);
+    }
+}
+
+// Tile `tile` of a swap, any alignment: same cut as dl_move_tile (element size
+// from the two addresses, head and tail bytes with tile 0).  Every byte of
+// either range is read and written by exactly one lane, so no lane depends on
+// another.
+template <int POL>
+__device__ __forceinline__ void dl_swap_tile(char *a, char *b, uint64_t bytes, uint64_t tile, uint32_t tile_bytes,
+                                             uint32_t tid, uint32_t nthr)
+{
+    const dl_geom g = dl_make_geom((uint64_t)a, (uint64_t)a ^ (uint64_t)b, bytes);
+    if (tile == 0) {
+        if (tid < g.head) dl_swap_elems<uint8_t, POL>(a, b, tid, 1u, 0u, 1u);
+        if (tid >= 32 && tid - 32 < g.tail)
+            dl_swap_elems<uint8_t, POL>(a, b, (uint64_t)g.head + g.body * g.esize + (tid - 32), 1u, 0u, 1u);
+    }
+    const uint64_t per_tile = tile_bytes / g.esize;
+    const uint64_t first = tile * per_tile;
+    if (first >= g.body) return;
+    const uint64_t left = g.body - first;
+    const uint32_t n = (uint32_t)(left < per_tile ? left : per_tile);
+    const uint64_t off = (uint64_t)g.head + first * g.esize;
+    if (g.esize == 16)
+        dl_swap_elems<dl_u32x4, POL>(a, b, off, n, tid, nthr);
+    else if (g.esize == 4)
+        dl_swap_elems<uint32_t, POL>(a, b, off, n, tid, nthr);
+    else
+        dl_swap_elems<uint8_t, POL>(a, b, off, n, tid, nthr);
+}
+
 // ------------------------------------------------ items and lists on the device
 
 __device__ __forceinline__ uint64_t dl_uniform64(uint64_t v)
@@ -227,6 +272,13 @@ __device__ __forceinline__ void dl_run_item(const dl_plain_item &it, uint64_t ti
     char *d[1] = {(char *)dl_uniform64((uint64_t)it.dst)};
     dl_move_tile<1, POL>((const char *)dl_uniform64((uint64_t)it.src), d, 1u, dl_uniform64(it.bytes), tile, tile_bytes,
                         1u, threadIdx.x, blockDim.x);
+}
+
+template <int POL>
+__device__ __forceinline__ void dl_run_item(const dl_swap_item &it, uint64_t tile, uint32_t tile_bytes, uint32_t)
+{
+    dl_swap_tile<POL>((char *)dl_uniform64((uint64_t)it.src), (char *)dl_uniform64((uint64_t)it.dst),
+                      dl_uniform64(it.bytes), tile, tile_bytes, threadIdx.x, blockDim.x);
 }
 
 template <int POL>
@@ -307,7 +359,15 @@ __device__ __forceinline__ void dl_run_rows(const dl_klist<Item, NMAX> &p, uint3
     const uint32_t wl = p.wpg_log2;
     const uint64_t row = ((uint64_t)(b - first_tile) << wl) + (wave & ((1u << wl) - 1u));
     const uint64_t byte = (row << 10) + (lane << 4);
-    if constexpr (sizeof(Item) == sizeof(dl_plain_item)) {
+    if constexpr (std::is_same<Item, dl_swap_item>::value) {
+        const char *a = it.src;
+        const char *b = it.dst;
+        if (byte >= it.bytes) return;
+        const dl_u32x4 x = dl_ld<POL>(dl_global<dl_u32x4>(a + byte));
+        const dl_u32x4 y = dl_ld<POL>(dl_global<dl_u32x4>(b + byte));
+        dl_st<POL>(dl_global<dl_u32x4>(a + byte), y);
+        dl_st<POL>(dl_global<dl_u32x4>(b + byte), x);
+    } else if constexpr (std::is_same<Item, dl_plain_item>::value) {
         const char *src = it.src;
         const char *dst = dl_item_dst(it, 0);
         if (byte >= it.bytes) return;

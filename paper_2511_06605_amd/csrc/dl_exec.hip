@@ -198,6 +198,7 @@ namespace {
 constexpr int NMAX_SMALL = 8;
 template <class Item> struct list_cap;
 template <> struct list_cap<dl_plain_item> { static constexpr int big = 64; };
+template <> struct list_cap<dl_swap_item> { static constexpr int big = 64; };
 template <> struct list_cap<dl_fused_item> { static constexpr int big = 32; };
 
 constexpr size_t RING_SLOTS = 4;
@@ -477,6 +478,10 @@ int dl_exec_plain(const dl_plain_item *items, size_t n, hipStream_t stream, cons
     return exec_list(items, n, stream, arm, launched);
 }
 int dl_exec_fused(const dl_fused_item *items, size_t n, hipStream_t stream, const dl_arm *arm, bool *launched)
+{
+    return exec_list(items, n, stream, arm, launched);
+}
+int dl_exec_swap(const dl_swap_item *items, size_t n, hipStream_t stream, const dl_arm *arm, bool *launched)
 {
     return exec_list(items, n, stream, arm, launched);
 }

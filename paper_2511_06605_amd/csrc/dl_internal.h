@@ -64,6 +64,7 @@ constexpr uint64_t DL_DONE_SKIPPED = 1ull << 63;  // set in the completion word 
 // *launched tells whether a kernel was enqueued (empty requests enqueue none).
 int dl_exec_plain(const dl_plain_item *items, size_t n, hipStream_t stream, const dl_arm *arm, bool *launched);
 int dl_exec_fused(const dl_fused_item *items, size_t n, hipStream_t stream, const dl_arm *arm, bool *launched);
+int dl_exec_swap(const dl_swap_item *items, size_t n, hipStream_t stream, const dl_arm *arm, bool *launched);
 int dl_exec_init();
 int dl_exec_shutdown();
 dl_launch_shape dl_choose_shape(uint64_t src_bytes, uint64_t max_item_bytes, uint32_t max_k);

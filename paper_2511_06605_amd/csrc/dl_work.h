@@ -20,6 +20,11 @@ struct dl_plain_item {
     uint64_t bytes;
 };
 
+// Swap (Sec. IV-C): the ranges [src, src + bytes) and [dst, dst + bytes), which
+// do not overlap, exchange their contents.  Same layout and geometry as a plain
+// copy; only what the device does with a tile differs.
+struct dl_swap_item : dl_plain_item {};
+
 // Fused broadcast copy: one source read once, k <= DL_FAN destinations.
 struct dl_fused_item {
     const char *src;

@@ -282,6 +282,79 @@ def test_batch_kv_fetch_shape(ref):
     run_batch(ref, 256, 128 * KiB, 256 * MiB, seed=5)
 
 
+# ------------------------------------------------- swap / in-place all-to-all
+
+def run_swaps(ref, n, nb, arena_bytes, seed, align=256):
+    arena, descs = inputs.swap_batch(n, nb, arena_bytes, seed, align)
+    want = ref.batch_swap([arena.copy()], [(0, a, 0, b, m) for a, b, m in descs])[0]
+    d = DevBuf(arena_bytes, fill=arena)
+    dl.dl_batch_swap([(d.ptr(int(a)), d.ptr(int(b)), int(m)) for a, b, m in descs], stream())
+    sync()
+    assert np.array_equal(d.host(), want)
+    assert d.guards_intact()
+
+
+@pytest.mark.parametrize("n,nb,arena,align", [(1, 100, 4096, 1), (4, 16 * KiB, 1 * MiB, 256), (7, 5000, 256 * KiB, 16),
+                                              (8, 1 * MiB + 48, 32 * MiB, 256), (40, 70001, 16 * MiB, 1),
+                                              (40, 4096, 4 * MiB, 4), (300, 3000, 8 * MiB, 8)])
+def test_batch_swap_shapes(ref, n, nb, arena, align):
+    """Row path (aligned, short list), general path (ragged, modulo 4, modulo 1), long lists (table kernel)."""
+    run_swaps(ref, n, nb, arena, seed=n + nb, align=align)
+
+
+def run_alltoall_inplace(ref, W, c, seed, kind="u8"):
+    bufs = inputs.alltoall_inputs(inputs.uniform_chunks(W, c), seed=seed, kind=kind)
+    want = ref.alltoall_inplace(bufs, c)
+    d = [DevBuf(W * c, fill=bufs[i]) for i in range(W)]
+    dl.dl_alltoall_inplace([b.ptr() for b in d], c, stream())
+    sync()
+    for i in range(W):
+        assert np.array_equal(d[i].host(), want[i]), f"rank {i} differs (W={W}, c={c})"
+        assert d[i].guards_intact()
+    return d, bufs
+
+
+@pytest.mark.parametrize("c", [1 * KiB, 64 * KiB, 4 * MiB])
+def test_alltoall_inplace_uniform_fp16(ref, c):
+    run_alltoall_inplace(ref, 8, c, seed=c, kind="fp16")
+
+
+@pytest.mark.parametrize("W,c", [(1, 1000), (2, 17), (3, 4097), (5, 16), (8, 1), (8, 100001), (13, 5000)])
+def test_alltoall_inplace_ranks_and_ragged_chunks(ref, W, c):
+    run_alltoall_inplace(ref, W, c, seed=W * 1000 + c)
+
+
+def test_alltoall_inplace_twice_is_identity_and_matches_out_of_place(ref):
+    W, c = 8, 48 * KiB
+    d, bufs = run_alltoall_inplace(ref, W, c, seed=77, kind="bf16")
+    # the out-of-place operation on the same inputs gives the same buffers
+    d_in = [DevBuf(W * c, fill=bufs[i]) for i in range(W)]
+    d_out = [DevBuf(W * c) for _ in range(W)]
+    dl.dl_alltoall([b.ptr() for b in d_in], [b.ptr() for b in d_out], inputs.uniform_chunks(W, c), stream())
+    dl.dl_alltoall_inplace([b.ptr() for b in d], c, stream())
+    sync()
+    for i in range(W):
+        assert np.array_equal(d_out[i].host(), ref.alltoall_inplace(bufs, c)[i])
+        assert np.array_equal(d[i].host(), bufs[i])
+
+
+def test_swap_validation_rejects_overlap_and_enqueues_nothing():
+    d = DevBuf(4096)
+    before = d.host().copy()
+    dl.dl_set_validate(True)
+    try:
+        with pytest.raises(dl.DlError) as e:
+            dl.dl_batch_swap([(d.ptr(0), d.ptr(1000), 500), (d.ptr(1400), d.ptr(2000), 500)], stream())
+        assert e.value.status == dl.DL_ERR_OVERLAP
+        with pytest.raises(dl.DlError) as e:
+            dl.dl_batch_swap([(d.ptr(0), d.ptr(100), 500)], stream())
+        assert e.value.status == dl.DL_ERR_OVERLAP
+    finally:
+        dl.dl_set_validate(False)
+    sync()
+    assert np.array_equal(d.host(), before)
+
+
 def test_empty_requests_are_no_ops():
     d = DevBuf(1024)
     dl.dl_batch_copy([], stream())
@@ -289,6 +362,9 @@ def test_empty_requests_are_no_ops():
     dl.dl_allgather([d.ptr()], [d.ptr(512)], 0, stream())
     dl.dl_broadcast(d.ptr(), [d.ptr(512)], 0, stream())
     dl.dl_alltoall([d.ptr(), d.ptr(8)], [d.ptr(512), d.ptr(600)], np.zeros((2, 2), dtype=np.uint64), stream())
+    dl.dl_batch_swap([], stream())
+    dl.dl_batch_swap([(d.ptr(), d.ptr(512), 0), (d.ptr(7), d.ptr(7), 100)], stream())
+    dl.dl_alltoall_inplace([d.ptr(), d.ptr(512)], 0, stream())
     sync()
     assert (d.host() == 0xA5).all()
 

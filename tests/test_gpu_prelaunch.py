@@ -150,6 +150,32 @@ def test_batch(ref, armed, n, nb, arena, align):
     assert np.array_equal(d.host(), want) and d.guards_intact()
 
 
+@pytest.mark.parametrize("W,c", [(8, 64 * KiB), (8, 1000), (3, 300 * KiB + 16), (13, 5001)])
+def test_alltoall_inplace_armed(ref, armed, W, c):
+    bufs = inputs.alltoall_inputs(inputs.uniform_chunks(W, c), seed=W + c, kind="fp16" if c % 2 == 0 else "u8")
+    d = [DevBuf(W * c, fill=bufs[i]) for i in range(W)]
+    sync()
+    dl.dl_alltoall_inplace([b.ptr() for b in d], c)
+    fire()
+    want = ref.alltoall_inplace(bufs, c)
+    for i in range(W):
+        assert np.array_equal(d[i].host(), want[i]) and d[i].guards_intact()
+
+
+def test_batch_swap_armed_twice_restores(ref, armed):
+    arena, descs = inputs.swap_batch(30, 20000, 8 * MiB, seed=9, align=16)
+    d = DevBuf(8 * MiB, fill=arena)
+    sw = [(d.ptr(int(a)), d.ptr(int(b)), int(m)) for a, b, m in descs]
+    sync()
+    dl.dl_batch_swap(sw)
+    fire()
+    want = ref.batch_swap([arena.copy()], [(0, a, 0, b, m) for a, b, m in descs])[0]
+    assert np.array_equal(d.host(), want)
+    dl.dl_batch_swap(sw)
+    fire()
+    assert np.array_equal(d.host(), arena) and d.guards_intact()
+
+
 def test_sources_written_after_arming_are_seen(ref, armed):
     """The point of prelaunch: the request is armed first, its inputs are
     produced afterwards, and only then is the doorbell rung.  The same device

@@ -223,3 +223,65 @@ def test_tile_count():
     outs = [(1 << 40) + r * 8 * B for r in range(8)]
     items = dl.dl_plan_allgather(ins, outs, B)
     assert dl.dl_plan_tiles(items, 16384) == 8 * B // 16384
+
+
+# ------------------------------------------------- swap / in-place all-to-all (Sec. IV-C)
+
+@pytest.mark.parametrize("W", [1, 2, 3, 8, 13])
+def test_inplace_alltoall_lowers_to_one_swap_per_pair_and_replays_to_the_checker(ref, W):
+    """W(W-1)/2 swaps, i.e. half the n(n-1) copies of the out-of-place form (for the paper's n = 8:
+    28 instead of 56), nothing on the diagonal; replayed on the CPU through a temporary and three
+    moves each (what a swap replaces), the list gives the checker's result."""
+    c = 40
+    g = golden_counts()
+    bufs = inputs.alltoall_inputs(inputs.uniform_chunks(W, c), seed=W)
+    work = [b.copy() for b in bufs]
+    swaps = dl.dl_plan_alltoall_inplace([addr(b) for b in work], c)
+    assert len(swaps) == W * (W - 1) // 2
+    if W == g["n_devices"]:
+        assert 2 * len(swaps) == g["copies_per_collective"]
+    assert dl.dl_plan_swap_first_hazard(swaps) == -1
+    moves = 0
+    for a, b, n in swaps:
+        tmp = (ctypes.c_char * n)()
+        ctypes.memmove(tmp, a, n)
+        ctypes.memmove(a, b, n)
+        ctypes.memmove(b, tmp, n)
+        moves += 3
+    assert moves == g["swap_copies_replaced"] * len(swaps)
+    for x, y in zip(work, ref.alltoall_inplace(bufs, c)):
+        assert np.array_equal(x, y)
+    assert dl.dl_plan_alltoall_inplace([addr(b) for b in work], 0) == []
+
+
+def test_swap_hazard_validator_agrees_with_the_checker(ref):
+    buf = np.zeros(4096, dtype=np.uint8)
+    base = addr(buf)
+    cases = {
+        "disjoint": [(0, 100, 50), (200, 300, 50)],
+        "touching": [(0, 50, 50), (100, 150, 50)],
+        "own ranges overlap": [(0, 30, 50)],
+        "a hits other b": [(0, 100, 50), (500, 40, 50)],
+        "b hits other a": [(0, 100, 50), (120, 600, 50)],
+        "contained": [(0, 1000, 500), (100, 2000, 10)],
+        "identical range is a no-op": [(10, 10, 100), (20, 300, 50)],
+        "empty ranges never collide": [(0, 10, 0), (0, 100, 50)],
+    }
+    for name, sw in cases.items():
+        got = dl.dl_plan_swap_first_hazard([(base + a, base + b, n) for a, b, n in sw])
+        try:
+            ref.batch_swap([buf.copy()], [(0, a, 0, b, n) for a, b, n in sw])
+            want_ok = True
+        except ValueError:
+            want_ok = False
+        assert (got == -1) == want_ok, name
+    rng = np.random.default_rng(5)
+    for _ in range(200):
+        sw = [(int(rng.integers(0, 900)), int(rng.integers(0, 900)), int(rng.integers(0, 60))) for _ in range(3)]
+        got = dl.dl_plan_swap_first_hazard([(base + a, base + b, n) for a, b, n in sw])
+        try:
+            ref.batch_swap([buf.copy()], [(0, a, 0, b, n) for a, b, n in sw])
+            want_ok = True
+        except ValueError:
+            want_ok = False
+        assert (got == -1) == want_ok, sw
