@@ -180,6 +180,32 @@ def other_operations(dl, benchaid, inputs, torch, stream, ag_reqs, ag_bufs, ag_s
         rows.append(row)
     res["allgather_tp_decode"] = rows
 
+    # KV-cache fetch: 256 dispersed blocks per request, pinned host pool -> device pool (over the host link),
+    # and the paged device -> device variant; one dl_batch_copy against one hipMemcpyAsync per block
+    rows = []
+    n_blk = 256
+    for blk in (16 * KiB, 64 * KiB, 256 * KiB, MiB, 4 * MiB):
+        pairs = inputs.kv_fetch_blocks(n_blk, 320, 320, seed=blk.bit_length())
+        host_pool = torch.empty(320 * blk, dtype=torch.uint8, pin_memory=True)
+        host_pool.random_(0, 256)
+        dev_pool = torch.empty(320 * blk, dtype=torch.uint8, device="cuda")
+        dev_src = torch.randint(0, 256, (320 * blk,), dtype=torch.uint8, device="cuda")
+        row = {"blocks": n_blk, "block_bytes": blk}
+        for name, base in (("host_to_device", host_pool.data_ptr()), ("device_to_device", dev_src.data_ptr())):
+            dlist = [(base + int(a) * blk, dev_pool.data_ptr() + int(b) * blk, blk) for a, b in pairs]
+            nbytes = n_blk * blk * (1 if name == "host_to_device" else 2)   # host link: bytes delivered; HBM: read + write
+            req = benchaid.copy_list_request(dlist, benchaid.OP_BATCH)
+            us = benchaid.time_device(req, stream, warmup=2, calls=5)
+            sub = {"dl_batch_copy_device_us": us, "dl_batch_copy_GBps": nbytes / us / 1e3,
+                   "dl_batch_copy_host_us": lat_stats(benchaid.time_host(req, stream, benchaid.WAIT_STREAM, 3, 20))}
+            req = benchaid.copy_list_request(dlist, benchaid.OP_MEMCPY_ASYNC)
+            sub["memcpy_async_per_block_host_us"] = lat_stats(benchaid.time_host(req, stream, benchaid.WAIT_STREAM, 2, 10))
+            sub["memcpy_async_per_block_GBps"] = nbytes / sub["memcpy_async_per_block_host_us"]["p50"] / 1e3
+            row[name] = sub
+        rows.append(row)
+        del host_pool, dev_pool, dev_src
+    res["kv_fetch"] = rows
+
     # broadcast 2 MiB -> 7 destinations; 64 back-to-back copies of 16 KiB in a 64 MiB arena
     n = 2 * MiB
     src = dev(inputs.payload(np.random.default_rng(7), n, "bf16"))

@@ -162,3 +162,14 @@ def swap_batch(n: int, swap_bytes: int, arena_bytes: int, seed: int, align: int 
         out[i] = (a, b, swap_bytes)
         i += 1
     return arena, out
+
+
+def kv_fetch_blocks(n_blocks: int, host_pool_blocks: int, device_pool_blocks: int, seed: int) -> np.ndarray:
+    """Which blocks a paged KV-cache fetch moves: an (n_blocks, 2) array of
+    (host pool block index, device pool block index), each column without
+    repeats, drawn uniformly (the blocks of one request are dispersed in both
+    pools)."""
+    rng = np.random.default_rng(seed)
+    src = rng.choice(host_pool_blocks, n_blocks, replace=False)
+    dst = rng.choice(device_pool_blocks, n_blocks, replace=False)
+    return np.stack([src, dst], axis=1).astype(np.int64)

@@ -282,6 +282,39 @@ def test_batch_kv_fetch_shape(ref):
     run_batch(ref, 256, 128 * KiB, 256 * MiB, seed=5)
 
 
+# ------------------------------------------- KV-cache fetch / save (Sec. V-C)
+
+@pytest.mark.parametrize("block_bytes", [16 * KiB, 160 * KiB, 1 * MiB + 4096])
+def test_kv_fetch_from_pinned_host_memory_and_save_back(ref, block_bytes):
+    """256 dispersed blocks per request, host-pinned pool -> device pool in one batch (fetch), then
+    a different set device -> host (save).  The checker sees the same two pools as host arrays."""
+    import torch
+    n, host_blocks, dev_blocks = 256, 300, 280
+    rng = np.random.default_rng(block_bytes)
+    host_pool = rng.integers(0, 256, host_blocks * block_bytes, dtype=np.uint8)
+    dev_pool = rng.integers(0, 256, dev_blocks * block_bytes, dtype=np.uint8)
+    pinned = torch.empty(host_pool.size, dtype=torch.uint8, pin_memory=True)
+    pinned.copy_(torch.from_numpy(host_pool))
+    d = DevBuf(dev_pool.size, fill=dev_pool)
+    hp = pinned.data_ptr()
+
+    pairs = inputs.kv_fetch_blocks(n, host_blocks, dev_blocks, seed=1)
+    want_h, want_d = ref.batch_copy([host_pool.copy(), dev_pool.copy()],
+                                    [(0, int(s) * block_bytes, 1, int(t) * block_bytes, block_bytes) for s, t in pairs])
+    dl.dl_batch_copy([(hp + int(s) * block_bytes, d.ptr(int(t) * block_bytes), block_bytes) for s, t in pairs], stream())
+    sync()
+    assert np.array_equal(d.host(), want_d) and d.guards_intact()
+    assert np.array_equal(pinned.numpy(), want_h)
+
+    pairs = inputs.kv_fetch_blocks(n, host_blocks, dev_blocks, seed=2)
+    want_h, want_d = ref.batch_copy([want_h, want_d],
+                                    [(1, int(t) * block_bytes, 0, int(s) * block_bytes, block_bytes) for s, t in pairs])
+    dl.dl_batch_copy([(d.ptr(int(t) * block_bytes), hp + int(s) * block_bytes, block_bytes) for s, t in pairs], stream())
+    sync()
+    assert np.array_equal(pinned.numpy(), want_h)
+    assert np.array_equal(d.host(), want_d) and d.guards_intact()
+
+
 # ------------------------------------------------- swap / in-place all-to-all
 
 def run_swaps(ref, n, nb, arena_bytes, seed, align=256):
