@@ -223,3 +223,39 @@ int ref_alltoall_inplace(void *const *buf, int W, size_t c)
     free(old);
     return 0;
 }
+
+/*
+ * Token dispatch of an expert-parallel mixture-of-experts layer (Sec. II-A1:
+ * tokens are exchanged between ranks by expert preference; Sec. IV-B: a token
+ * that goes to several experts is one source with several destinations).
+ * in[i] holds tokens[i] rows of row_bytes bytes.  dest has one byte per (token,
+ * rank), tokens numbered over all ranks in rank order: dest[g*W + j] != 0 means
+ * token g goes to rank j.  out[j] receives its rows packed in token order
+ * (source rank first, then row index):
+ *   out[j] row (number of tokens g' < g with dest[g'*W + j] != 0) = row of token g.
+ */
+int ref_token_dispatch(const void *const *in, void *const *out, int W, const uint32_t *tokens, size_t row_bytes,
+                       const uint8_t *dest)
+{
+    if (W < 1 || !in || !out || !tokens)
+        return -1;
+    for (int j = 0; j < W; ++j) {
+        size_t placed = 0; /* rows already written to out[j] */
+        size_t g = 0;      /* global token number */
+        for (int i = 0; i < W; ++i) {
+            for (uint32_t t = 0; t < tokens[i]; ++t, ++g) {
+                if (!dest)
+                    return -1;
+                if (!dest[g * (size_t)W + (size_t)j])
+                    continue;
+                if (row_bytes) {
+                    if (!in[i] || !out[j])
+                        return -1;
+                    memcpy((char *)out[j] + placed * row_bytes, (const char *)in[i] + (size_t)t * row_bytes, row_bytes);
+                }
+                ++placed;
+            }
+        }
+    }
+    return 0;
+}

@@ -53,6 +53,9 @@ def load(path: str | None = None) -> ctypes.CDLL:
     lib.ref_batch_swap.argtypes = [ctypes.POINTER(RefSwap), ctypes.c_size_t]
     lib.ref_alltoall_inplace.restype = ctypes.c_int
     lib.ref_alltoall_inplace.argtypes = [VPP, ctypes.c_int, ctypes.c_size_t]
+    lib.ref_token_dispatch.restype = ctypes.c_int
+    lib.ref_token_dispatch.argtypes = [VPP, VPP, ctypes.c_int, ctypes.POINTER(ctypes.c_uint32), ctypes.c_size_t,
+                                       ctypes.POINTER(ctypes.c_uint8)]
     return lib
 
 
@@ -194,4 +197,25 @@ def alltoall_inplace(bufs, chunk_bytes, lib=None):
     rc = lib.ref_alltoall_inplace(_ptrs(outs), W, c)
     if rc:
         raise RuntimeError(f"ref_alltoall_inplace failed: {rc}")
+    return outs
+
+
+def token_dispatch(ins, row_bytes, dest, lib=None):
+    """ins[i]: tokens_i rows of ``row_bytes`` bytes.  dest: (total tokens, W)
+    array, non-zero where a token goes to a rank.  Returns the W receive
+    buffers, rows packed in token order."""
+    lib = lib or _get()
+    ins = [_check_buf(a) for a in ins]
+    W, row_bytes = len(ins), int(row_bytes)
+    tokens = np.array([a.size // row_bytes if row_bytes else 0 for a in ins], dtype=np.uint32)
+    if any(a.size != int(t) * row_bytes for a, t in zip(ins, tokens)):
+        raise ValueError("send buffers must hold whole rows")
+    dest = np.ascontiguousarray(np.asarray(dest, dtype=np.uint8))
+    if dest.shape != (int(tokens.sum()), W):
+        raise ValueError("dest must be (total tokens, W)")
+    outs = [np.zeros(int((dest[:, j] != 0).sum()) * row_bytes, dtype=np.uint8) for j in range(W)]
+    rc = lib.ref_token_dispatch(_ptrs(ins), _ptrs(outs), W, tokens.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32)),
+                                row_bytes, dest.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)))
+    if rc:
+        raise RuntimeError(f"ref_token_dispatch failed: {rc}")
     return outs

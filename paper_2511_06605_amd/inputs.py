@@ -173,3 +173,35 @@ def kv_fetch_blocks(n_blocks: int, host_pool_blocks: int, device_pool_blocks: in
     src = rng.choice(host_pool_blocks, n_blocks, replace=False)
     dst = rng.choice(device_pool_blocks, n_blocks, replace=False)
     return np.stack([src, dst], axis=1).astype(np.int64)
+
+
+def moe_token_destinations(W: int, tokens_per_rank, seed: int, n_experts: int = 256, top_k: int = 8,
+                           skew_alpha: float | None = None) -> np.ndarray:
+    """Which ranks each token of an expert-parallel MoE layer goes to.
+
+    Every token picks ``top_k`` distinct experts (uniformly, or by Dirichlet
+    (skew_alpha) weights); the experts are split evenly over the W ranks; a
+    token goes once to every rank that owns at least one of its experts.
+    ``tokens_per_rank`` is one number or a list of W.  Returns a
+    (total tokens, W) uint8 array with 1 where the token goes to the rank.
+    """
+    rng = np.random.default_rng(seed)
+    counts = [int(tokens_per_rank)] * W if np.isscalar(tokens_per_rank) else [int(t) for t in tokens_per_rank]
+    total = sum(counts)
+    if skew_alpha is None:
+        keys = rng.random((total, n_experts))
+    else:
+        p = rng.dirichlet(np.full(n_experts, skew_alpha))
+        keys = rng.random((total, n_experts)) ** (1.0 / np.maximum(p, 1e-12))   # weighted sampling without replacement
+    experts = np.argsort(-keys, axis=1)[:, :top_k]
+    per_rank = n_experts // W
+    dest = np.zeros((total, W), dtype=np.uint8)
+    np.put_along_axis(dest, np.minimum(experts // per_rank, W - 1), 1, axis=1)
+    return dest
+
+
+def token_rows(W: int, tokens_per_rank, row_bytes: int, seed: int, kind: str = "u8"):
+    """W send buffers of tokens_i rows of ``row_bytes`` bytes."""
+    rng = np.random.default_rng(seed)
+    counts = [int(tokens_per_rank)] * W if np.isscalar(tokens_per_rank) else [int(t) for t in tokens_per_rank]
+    return [payload(rng, c * row_bytes, kind) for c in counts]

@@ -69,6 +69,15 @@ def run_pins(lib):
     got = ref.alltoall_inplace(bufs, c, lib=lib)
     assert np.array_equal(np.stack(got), np.stack(bufs).reshape(W, W, c).transpose(1, 0, 2).reshape(W, W * c))
 
+    counts, row = [3, 0, 4], 6
+    tin = inputs.token_rows(W, counts, row, seed=9)
+    dest = inputs.moe_token_destinations(W, counts, seed=10, n_experts=12, top_k=2)
+    dest[2] = 0
+    rows = np.concatenate(tin).reshape(sum(counts), row)
+    got = ref.token_dispatch(tin, row, dest, lib=lib)
+    for j in range(W):
+        assert np.array_equal(got[j].reshape(-1, row), rows[dest[:, j] != 0])
+
 
 if __name__ == "__main__":
     run_pins(ref.load(sys.argv[1]))

@@ -48,6 +48,14 @@ MUTANTS = {
                       "memcpy((char *)buf[j] + (size_t)j * c, old + (size_t)i * row + (size_t)j * c, c);"),
     "ip_reads_new": ("memcpy((char *)buf[j] + (size_t)i * c, old + (size_t)i * row + (size_t)j * c, c);",
                      "memcpy((char *)buf[j] + (size_t)i * c, (char *)buf[i] + (size_t)j * c, c);"),
+    # token dispatch: mask read transposed, rows placed by token number instead of packed, row index of the wrong rank
+    "td_mask_transposed": ("if (!dest[g * (size_t)W + (size_t)j])", "if (!dest[(size_t)j * (size_t)W + g % (size_t)W])"),
+    "td_not_packed": ("memcpy((char *)out[j] + placed * row_bytes, (const char *)in[i] + (size_t)t * row_bytes, row_bytes);",
+                      "memcpy((char *)out[j] + (placed ? placed - 1 : 0) * row_bytes, (const char *)in[i] + (size_t)t * row_bytes, row_bytes);"),
+    "td_global_row": ("(const char *)in[i] + (size_t)t * row_bytes, row_bytes);\n                }\n                ++placed;",
+                      "(const char *)in[i] + (size_t)(t ? t - 1 : 0) * row_bytes, row_bytes);\n                }\n                ++placed;"),
+    "td_counts_skipped": ("                if (!dest[g * (size_t)W + (size_t)j])\n                    continue;",
+                          "                if (!dest[g * (size_t)W + (size_t)j]) {\n                    ++placed;\n                    continue;\n                }"),
 }
 
 

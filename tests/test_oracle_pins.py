@@ -332,3 +332,71 @@ def test_alltoall_inplace_is_a_series_of_swaps(ref, W):
     ref.batch_swap(work, swaps)
     for x, y in zip(work, ref.alltoall_inplace(bufs, c)):
         assert np.array_equal(x, y)
+
+
+# ------------------------------------------------- token dispatch (Sec. II-A1, IV-B)
+
+def brute_token_dispatch(ins, row, dest):
+    W = len(ins)
+    outs = []
+    for j in range(W):
+        o = bytearray()
+        g = 0
+        for i in range(W):
+            for t in range(len(ins[i]) // row if row else 0):
+                if dest[g][j]:
+                    for q in range(row):
+                        o.append(int(ins[i][t * row + q]))
+                g += 1
+        outs.append(np.frombuffer(bytes(o), dtype=np.uint8))
+    return outs
+
+
+@pytest.mark.parametrize("W,counts,row", [(1, [3], 5), (2, [2, 3], 1), (3, [4, 0, 2], 7), (5, [1, 2, 3, 2, 1], 16),
+                                          (8, [3] * 8, 17)])
+def test_token_dispatch_bruteforce(ref, W, counts, row):
+    ins = inputs.token_rows(W, counts, row, seed=W)
+    dest = inputs.moe_token_destinations(W, counts, seed=W + 1, n_experts=8 * W, top_k=min(3, W))
+    dest[::5] = 0                      # some tokens go nowhere
+    got = ref.token_dispatch(ins, row, dest)
+    for g, w in zip(got, brute_token_dispatch(ins, row, dest)):
+        assert np.array_equal(g, w)
+
+
+@pytest.mark.parametrize("W,T,row", [(8, 16, 64), (4, 33, 100), (8, 5, 14336)])
+def test_token_dispatch_is_boolean_row_selection(ref, W, T, row):
+    """Receive buffer j is the stacked token rows filtered by column j of the destination mask."""
+    ins = inputs.token_rows(W, T, row, seed=T, kind="bf16")
+    dest = inputs.moe_token_destinations(W, T, seed=T + 1)
+    rows = np.concatenate(ins).reshape(W * T, row)
+    got = ref.token_dispatch(ins, row, dest)
+    for j in range(W):
+        assert np.array_equal(got[j].reshape(-1, row), rows[dest[:, j] != 0])
+    # top-8 over 256 experts: every token reaches between 1 and min(8, W) ranks
+    k = dest.sum(axis=1)
+    assert k.min() >= 1 and k.max() <= min(8, W)
+
+
+def test_token_dispatch_to_every_rank_is_an_allgather(ref):
+    W, T, row = 4, 6, 24
+    ins = inputs.token_rows(W, T, row, seed=3)
+    got = ref.token_dispatch(ins, row, np.ones((W * T, W), dtype=np.uint8))
+    for g, w in zip(got, ref.allgather(ins)):
+        assert np.array_equal(g, w)
+
+
+def test_token_dispatch_with_one_destination_sorted_by_rank_is_the_alltoall(ref):
+    """Tokens that each go to exactly one rank, stored grouped by that rank: the packed all-to-all."""
+    W, row = 5, 12
+    rng = np.random.default_rng(11)
+    counts = rng.integers(0, 4, (W, W))                  # tokens rank i sends to rank j
+    ins = inputs.token_rows(W, [int(c.sum()) for c in counts], row, seed=12)
+    dest = np.zeros((int(counts.sum()), W), dtype=np.uint8)
+    g = 0
+    for i in range(W):
+        for j in range(W):
+            dest[g:g + counts[i, j], j] = 1
+            g += counts[i, j]
+    got = ref.token_dispatch(ins, row, dest)
+    for x, y in zip(got, ref.alltoall(ins, counts * row)):
+        assert np.array_equal(x, y)
