@@ -126,7 +126,10 @@ def other_operations(dl, benchaid, inputs, torch, stream, ag_reqs, ag_bufs, ag_s
         except RuntimeError as e:
             row["memcpy_batch_host_us"] = f"unavailable in the loaded HIP runtime ({e})"
         req = benchaid.copy_list_request(descs, benchaid.OP_BATCH)   # same 64 plain copies through dl_batch_copy
+        dl.dl_set_config(infer_broadcast=0)                          # ... kept as 64 copies (each source re-read 8 times)
         row["dl_batch_copy_unfused"] = timed(req, 2 * W * W * B, B <= MiB)
+        dl.dl_set_config(infer_broadcast=1)                          # ... merged back into 8 read-once/write-8 copies
+        row["dl_batch_copy_inferred_broadcast"] = timed(req, ag_bytes(B), B <= MiB)
         rows.append(row)
     res["allgather_vs_runtime_copies"] = rows
 
@@ -166,6 +169,26 @@ def other_operations(dl, benchaid, inputs, torch, stream, ag_reqs, ag_bufs, ag_s
         row.update(timed(req, 2 * int(C.sum()), T <= 16))
         rows.append(row)
     res["alltoall_moe_dispatch"] = rows
+
+    # token-granular MoE dispatch: every token row (14 KiB) is read once and written to the 1..8 ranks that own
+    # its top-8 experts; bytes = rows read + rows written
+    rows = []
+    for T in (16, 128, 512):
+        row_bytes = 14336
+        dest = inputs.moe_token_destinations(W, T, seed=T)
+        ins = inputs.token_rows(W, T, row_bytes, seed=T + 1, kind="bf16")
+        d_in = [dev(a) for a in ins]
+        d_out = [torch.empty(int(dest[:, j].sum()) * row_bytes, dtype=torch.uint8, device="cuda") for j in range(W)]
+        req = benchaid.token_dispatch_request(d_in, d_out, [T] * W, row_bytes, dest)
+        nbytes = (W * T + int(dest.sum())) * row_bytes
+        row = {"tokens_per_rank": T, "row_bytes": row_bytes, "copies": int(dest.sum()),
+               "mean_fanout": float(dest.sum()) / (W * T)}
+        lowered, row["lowering_host_us"] = benchaid.lowered_token_dispatch(req)
+        row["items"] = lowered.req.n
+        row.update(timed(lowered, nbytes, False, calls=10))            # the lowered list alone: device-bound
+        row["call_to_sync_host_us"] = lat_stats(benchaid.time_host(req, stream, benchaid.WAIT_STREAM, 10, 100))
+        rows.append(row)
+    res["token_dispatch_moe"] = rows
 
     # tensor-parallel decode all-gather: hidden 8192 bf16
     rows = []
@@ -256,6 +279,24 @@ def pmc_case(args, dl, benchaid, torch, stream) -> int:
     return 0
 
 
+def token_case(args, dl, benchaid, inputs, torch, stream) -> int:
+    """Only the token-granular MoE dispatch (W = 8, 14 KiB rows, top-8 of 256 experts), --steps calls per
+    tokens-per-rank point with a synchronisation after each: for kernel traces of the table kernels."""
+    row_bytes = 14336
+    for T in (16, 128, 512):
+        dest = inputs.moe_token_destinations(W, T, seed=T)
+        ins = inputs.token_rows(W, T, row_bytes, seed=T + 1, kind="bf16")
+        d_in = [torch.from_numpy(a).cuda() for a in ins]
+        d_out = [torch.empty(int(dest[:, j].sum()) * row_bytes, dtype=torch.uint8, device="cuda") for j in range(W)]
+        req = benchaid.token_dispatch_request(d_in, d_out, [T] * W, row_bytes, dest)
+        for _ in range(args.warmup + args.steps):
+            benchaid.issue(req, stream)
+            stream.synchronize()
+    dl.dl_shutdown()
+    print(json.dumps({"case": "token_dispatch", "calls_per_point": args.warmup + args.steps}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -264,9 +305,10 @@ def main() -> int:
     ap.add_argument("--max-bytes", type=int, default=64 * MiB, help="largest per-rank payload of the sweep")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline leg")
     ap.add_argument("--no-detail", action="store_true", help="skip per-size latency and comparison legs")
-    ap.add_argument("--case", choices=["sweep", "pmc"], default="sweep",
+    ap.add_argument("--case", choices=["sweep", "pmc", "token_dispatch"], default="sweep",
                     help="pmc: only --steps launches of the largest all-gather and of a plain 1 GiB copy "
-                         "(the calibration kernel), for hardware-counter runs")
+                         "(the calibration kernel), for hardware-counter runs; token_dispatch: only the "
+                         "token-granular MoE dispatch, for kernel traces")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU (W virtual ranks share its HBM); --gpus must be 1",
@@ -286,6 +328,8 @@ def main() -> int:
 
     if args.case == "pmc":
         return pmc_case(args, dl, benchaid, torch, stream)
+    if args.case == "token_dispatch":
+        return token_case(args, dl, benchaid, inputs, torch, stream)
 
     sizes = [B for B in (4 * KiB << i for i in range(15)) if B <= args.max_bytes]
     reqs, keep, check = {}, [], None

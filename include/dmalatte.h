@@ -204,7 +204,7 @@ typedef struct dl_config {
     uint32_t fuse_broadcast;     /* 1: all-gather reads each source once (W fused copies); 0: W*W plain copies */
     uint32_t max_blocks;         /* cap on the one-shot grid; workgroups then stride over the tiles; 0 = one workgroup per tile */
     uint32_t fan_split;          /* sub-groups of a workgroup that share out the destinations of a fused copy: 1, 2 or 4; 0 = choose */
-    uint32_t reserved;
+    uint32_t infer_broadcast;    /* 1: dl_batch_copy merges copies that share source and size into read-once/write-k copies; default 1 */
     uint64_t write_through_max_bytes; /* requests moving at most this many bytes (read + written) use write-through stores; default 144 MiB */
 } dl_config;
 
@@ -224,6 +224,30 @@ typedef struct dl_plan_item {
 } dl_plan_item;
 
 /*
+ * Batch of read-once/write-many copies (paper Sec. IV-B generalised, and the
+ * broadcast form of the batched runtime call of Sec. VI): item i reads
+ * items[i].bytes bytes at items[i].src once and writes them to its
+ * items[i].k destinations, 1 <= k <= DL_PLAN_FANOUT.  Independent and unordered
+ * like dl_batch_copy, same hazard rule, one completion.  items: host array.
+ */
+int dl_batch_fanout(const dl_plan_item *items, size_t n, void *stream);
+
+/*
+ * Token dispatch of an expert-parallel mixture-of-experts layer (paper
+ * Sec. II-A1: ranks exchange tokens by expert preference; Sec. IV-B: a token
+ * sent to several experts is one source with several destinations).
+ * in[i] (device) holds tokens[i] rows of row_bytes bytes.  dest (host) has one
+ * byte per (token, rank), tokens numbered over all ranks in rank order:
+ * dest[g*W + j] != 0 sends token g to rank j.  out[j] (device) receives its
+ * rows packed in token order (source rank first, then row index), so it must
+ * hold row_bytes times the number of non-zero entries in column j of dest.
+ * Lowered to one read-once/write-k copy per token; a token with no destination
+ * moves nothing.  tokens: host array of W counts.  1 <= W <= DL_MAX_FANOUT.
+ */
+int dl_token_dispatch(const void *const *in, void *const *out, int W, const uint32_t *tokens, size_t row_bytes,
+                      const uint8_t *dest, void *stream);
+
+/*
  * Host-only: lower a collective to the list of copies the device executes
  * (the analogue of building the command list, paper Sec. III-B2 "control").
  * Pointers are treated as opaque addresses and never dereferenced, so these
@@ -238,6 +262,15 @@ long dl_plan_alltoall(const void *const *in, void *const *out, int W, const size
 long dl_plan_broadcast(const void *src, void *const *dsts, int k, size_t bytes,
                        dl_plan_item *items, size_t cap);
 long dl_plan_batch(const dl_copy_desc *desc, size_t n, dl_plan_item *items, size_t cap);
+long dl_plan_token_dispatch(const void *const *in, void *const *out, int W, const uint32_t *tokens, size_t row_bytes,
+                            const uint8_t *dest, dl_plan_item *items, size_t cap);
+
+/* Host-only: what dl_batch_copy does with a batch when dl_config.infer_broadcast
+ * is on (paper Sec. VI: the runtime inspects a batch and turns copies with the
+ * same source and the same size into a broadcast): copies that share source
+ * address and byte count are merged into read-once/write-k items, up to
+ * DL_PLAN_FANOUT destinations each, in order of first appearance. */
+long dl_plan_batch_inferred(const dl_copy_desc *desc, size_t n, dl_plan_item *items, size_t cap);
 
 /* Host-only: index of the first item whose destination overlaps another
  * destination or any source (the hazard rule), or -1 if there is none. */

@@ -12,7 +12,7 @@ from . import binding
 _HERE = os.path.dirname(os.path.abspath(__file__))
 AID_PATH = os.path.join(_HERE, "libdl_benchaid.so")
 
-OP_BATCH, OP_BROADCAST, OP_ALLGATHER, OP_ALLTOALL, OP_MEMCPY_ASYNC, OP_MEMCPY_BATCH, OP_SWAP, OP_ALLTOALL_INPLACE = range(8)
+OP_BATCH, OP_BROADCAST, OP_ALLGATHER, OP_ALLTOALL, OP_MEMCPY_ASYNC, OP_MEMCPY_BATCH, OP_SWAP, OP_ALLTOALL_INPLACE, OP_TOKEN_DISPATCH, OP_FANOUT = range(10)
 WAIT_STREAM, WAIT_TRIGGER, WAIT_ARM_AND_TRIGGER = 0, 1, 2
 
 
@@ -23,6 +23,7 @@ class Request(ctypes.Structure):
         ("src", ctypes.c_void_p), ("dsts", ctypes.POINTER(ctypes.c_void_p)), ("bytes", ctypes.c_size_t),
         ("in_", ctypes.POINTER(ctypes.c_void_p)), ("out", ctypes.POINTER(ctypes.c_void_p)),
         ("C", ctypes.POINTER(ctypes.c_size_t)),
+        ("tokens", ctypes.POINTER(ctypes.c_uint32)), ("dest", ctypes.POINTER(ctypes.c_uint8)),
     ]
 
 
@@ -43,6 +44,8 @@ def aid() -> ctypes.CDLL:
         L.dlb_time_host.argtypes = [rp, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, dp]
         L.dlb_time_device.restype = ctypes.c_int
         L.dlb_time_device.argtypes = [rp, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, dp]
+        L.dlb_time_token_lowering.restype = ctypes.c_int
+        L.dlb_time_token_lowering.argtypes = [rp, ctypes.POINTER(binding.PlanItem), ctypes.c_size_t, ctypes.c_int, dp]
         _aid = L
     return _aid
 
@@ -92,6 +95,31 @@ def alltoall_inplace_request(bufs, chunk_bytes) -> Prepared:
     r = Request(op=OP_ALLTOALL_INPLACE, W=len(bufs), bytes=int(chunk_bytes))
     r.out = ctypes.cast(b, ctypes.POINTER(ctypes.c_void_p))
     return Prepared(r, (b,))
+
+
+def token_dispatch_request(ins, outs, tokens, row_bytes, dest) -> Prepared:
+    a, b, W, tok, d = binding._dispatch_args(ins, outs, tokens, dest)
+    r = Request(op=OP_TOKEN_DISPATCH, W=W, bytes=int(row_bytes))
+    r.in_ = ctypes.cast(a, ctypes.POINTER(ctypes.c_void_p))
+    r.out = ctypes.cast(b, ctypes.POINTER(ctypes.c_void_p))
+    r.tokens = ctypes.cast(tok, ctypes.POINTER(ctypes.c_uint32))
+    r.dest = ctypes.cast(d, ctypes.POINTER(ctypes.c_uint8))
+    return Prepared(r, (a, b, tok, d))
+
+
+def lowered_token_dispatch(p: Prepared, iters=20):
+    """Lower a prepared token dispatch on the host: returns (a fan-out batch request that executes
+    the lowered list, microseconds per lowering)."""
+    n = binding.lib().dl_plan_token_dispatch(p.req.in_, p.req.out, p.req.W, p.req.tokens, p.req.bytes, p.req.dest,
+                                             None, 0)
+    if n < 0:
+        raise binding.DlError(int(n), "dl_plan_token_dispatch")
+    items = (binding.PlanItem * max(n, 1))()
+    us = ctypes.c_double(0)
+    _rc(aid().dlb_time_token_lowering(ctypes.byref(p.req), items, n, iters, ctypes.byref(us)), "dlb_time_token_lowering")
+    r = Request(op=OP_FANOUT, n=n)
+    r.desc = ctypes.cast(items, ctypes.POINTER(binding.CopyDesc))
+    return Prepared(r, (items, p)), us.value
 
 
 def _rc(rc, what):

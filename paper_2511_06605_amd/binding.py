@@ -37,7 +37,8 @@ EXPORTS = [
     "dl_get_config",
     "dl_set_config", "dl_plan_allgather", "dl_plan_alltoall", "dl_plan_broadcast", "dl_plan_batch",
     "dl_plan_first_hazard", "dl_plan_tiles", "dl_batch_swap", "dl_alltoall_inplace", "dl_plan_alltoall_inplace",
-    "dl_plan_swap_first_hazard",
+    "dl_plan_swap_first_hazard", "dl_batch_fanout", "dl_token_dispatch", "dl_plan_token_dispatch",
+    "dl_plan_batch_inferred",
 ]
 
 
@@ -65,7 +66,7 @@ class Config(ctypes.Structure):
         ("fuse_broadcast", ctypes.c_uint32),
         ("max_blocks", ctypes.c_uint32),
         ("fan_split", ctypes.c_uint32),
-        ("reserved", ctypes.c_uint32),
+        ("infer_broadcast", ctypes.c_uint32),
         ("write_through_max_bytes", ctypes.c_uint64),
     ]
 
@@ -75,7 +76,7 @@ class PlanItem(ctypes.Structure):
         ("src", ctypes.c_void_p),
         ("bytes", ctypes.c_size_t),
         ("k", ctypes.c_uint32),
-        ("reserved", ctypes.c_uint32),
+        ("infer_broadcast", ctypes.c_uint32),
         ("dst", ctypes.c_void_p * DL_PLAN_FANOUT),
     ]
 
@@ -135,6 +136,14 @@ def lib() -> ctypes.CDLL:
         "dl_plan_alltoall_inplace": (ctypes.c_long, [vpp, ctypes.c_int, ctypes.c_size_t, ctypes.POINTER(SwapDesc),
                                                      ctypes.c_size_t]),
         "dl_plan_swap_first_hazard": (ctypes.c_long, [ctypes.POINTER(SwapDesc), ctypes.c_size_t]),
+        "dl_batch_fanout": (ctypes.c_int, [ctypes.POINTER(PlanItem), ctypes.c_size_t, vp]),
+        "dl_token_dispatch": (ctypes.c_int, [vpp, vpp, ctypes.c_int, ctypes.POINTER(ctypes.c_uint32), ctypes.c_size_t,
+                                             ctypes.POINTER(ctypes.c_uint8), vp]),
+        "dl_plan_token_dispatch": (ctypes.c_long, [vpp, vpp, ctypes.c_int, ctypes.POINTER(ctypes.c_uint32),
+                                                   ctypes.c_size_t, ctypes.POINTER(ctypes.c_uint8),
+                                                   ctypes.POINTER(PlanItem), ctypes.c_size_t]),
+        "dl_plan_batch_inferred": (ctypes.c_long, [ctypes.POINTER(CopyDesc), ctypes.c_size_t, ctypes.POINTER(PlanItem),
+                                                   ctypes.c_size_t]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -279,6 +288,32 @@ def dl_alltoall_inplace(bufs, chunk_bytes: int, stream=None) -> None:
            "dl_alltoall_inplace")
 
 
+def _dispatch_args(ins, outs, tokens, dest):
+    ins, outs = list(ins), list(outs)
+    W = len(ins)
+    if len(outs) != W or len(tokens) != W:
+        raise ValueError("need W send buffers, W receive buffers and W token counts")
+    tok = (ctypes.c_uint32 * W)(*[int(t) for t in tokens])
+    total = sum(int(t) for t in tokens)
+    flat = bytes(bytearray(int(v) != 0 for row in dest for v in row)) if not hasattr(dest, "tobytes") else \
+        (dest != 0).astype("uint8").tobytes()
+    if len(flat) != total * W:
+        raise ValueError("dest must have one entry per (token, rank)")
+    d = (ctypes.c_uint8 * max(len(flat), 1)).from_buffer_copy(flat or b"\0")
+    return _ptr_array(ins), _ptr_array(outs), W, tok, d
+
+
+def dl_batch_fanout(items, stream=None) -> None:
+    """items: sequence of dicts {src, bytes, dst: [..]} (as the dl_plan_* functions return)."""
+    items = list(items)
+    _check(lib().dl_batch_fanout(_items_in(items), len(items), _stream(stream)), "dl_batch_fanout")
+
+
+def dl_token_dispatch(ins, outs, tokens, row_bytes: int, dest, stream=None) -> None:
+    a, b, W, tok, d = _dispatch_args(ins, outs, tokens, dest)
+    _check(lib().dl_token_dispatch(a, b, W, tok, int(row_bytes), d, _stream(stream)), "dl_token_dispatch")
+
+
 # -------------------------------------------------------------------- prelaunch
 
 def dl_prelaunch_start() -> None:
@@ -344,6 +379,17 @@ def dl_plan_batch(descs):
     descs = list(descs)
     d = _desc_array(descs)
     return _items_out(lambda arr, cap: lib().dl_plan_batch(d, len(descs), arr, cap))
+
+
+def dl_plan_token_dispatch(ins, outs, tokens, row_bytes: int, dest):
+    a, b, W, tok, d = _dispatch_args(ins, outs, tokens, dest)
+    return _items_out(lambda arr, cap: lib().dl_plan_token_dispatch(a, b, W, tok, int(row_bytes), d, arr, cap))
+
+
+def dl_plan_batch_inferred(descs):
+    descs = list(descs)
+    d = _desc_array(descs)
+    return _items_out(lambda arr, cap: lib().dl_plan_batch_inferred(d, len(descs), arr, cap))
 
 
 def dl_plan_alltoall_inplace(bufs, chunk_bytes: int):

@@ -108,6 +108,88 @@ long lower_batch(const dl_copy_desc *desc, size_t n, sink &s)
     return (long)s.n;
 }
 
+// dl_batch_copy with broadcast inference (Sec. VI): copies with the same source
+// address and the same byte count become one read-once/write-k item, in order of
+// first appearance, at most DL_PLAN_FANOUT destinations per item.
+long lower_batch_inferred(const dl_copy_desc *desc, size_t n, sink &s)
+{
+    if (n && !desc) return DL_ERR_INVALID;
+    // open[] holds, per distinct (src, bytes), the index in `groups` of the item still taking destinations
+    struct group {
+        const void *src;
+        size_t bytes;
+        uint32_t k;
+        void *dst[DL_PLAN_FANOUT];
+    };
+    static std::vector<group> groups;
+    static std::vector<uint32_t> slots;  // open-addressing table of indices into groups (+1), 0 = empty
+    groups.clear();
+    size_t want = 16;
+    while (want < 2 * n) want *= 2;
+    slots.assign(want, 0);
+    for (size_t i = 0; i < n; ++i) {
+        if (desc[i].bytes == 0) continue;
+        if (!desc[i].src || !desc[i].dst) return DL_ERR_INVALID;
+        if (desc[i].src == desc[i].dst) continue;
+        uint64_t h = ((uint64_t)desc[i].src * 0x9E3779B97F4A7C15ull) ^ ((uint64_t)desc[i].bytes * 0xC2B2AE3D27D4EB4Full);
+        size_t q = (size_t)(h >> 20) & (want - 1);
+        for (;;) {
+            const uint32_t g = slots[q];
+            if (g == 0) {  // first copy from this (src, bytes)
+                groups.push_back({desc[i].src, desc[i].bytes, 1u, {desc[i].dst}});
+                slots[q] = (uint32_t)groups.size();
+                break;
+            }
+            group &gr = groups[g - 1];
+            if (gr.src == desc[i].src && gr.bytes == desc[i].bytes) {
+                if (gr.k < (uint32_t)DL_PLAN_FANOUT) {
+                    gr.dst[gr.k++] = desc[i].dst;
+                } else {  // full: a fresh item takes over this key
+                    groups.push_back({desc[i].src, desc[i].bytes, 1u, {desc[i].dst}});
+                    slots[q] = (uint32_t)groups.size();
+                }
+                break;
+            }
+            q = (q + 1) & (want - 1);
+        }
+    }
+    for (const group &g : groups) s.put(g.src, g.bytes, g.dst, g.k);
+    return (long)s.n;
+}
+
+// One read-once/write-k item per token that has a destination; receive buffers
+// fill up in token order.
+long lower_token_dispatch(const void *const *in, void *const *out, int W, const uint32_t *tokens, size_t row,
+                          const uint8_t *dest, sink &s)
+{
+    if (W < 1 || W > DL_MAX_FANOUT || !in || !out || !tokens) return DL_ERR_INVALID;
+    size_t placed[DL_MAX_FANOUT] = {0};  // rows already assigned in each receive buffer
+    void *dst[DL_MAX_FANOUT + 1];
+    if (tokens && !dest)
+        for (int i = 0; i < W; ++i)
+            if (tokens[i]) return DL_ERR_INVALID;
+    size_t g = 0;
+    for (int i = 0; i < W; ++i) {
+        if (tokens[i] && row && !in[i]) return DL_ERR_INVALID;
+        for (uint32_t t = 0; t < tokens[i]; ++t, ++g) {
+            // thousands of tokens per call: no data-dependent branch per (token, rank)
+            const uint8_t *m = dest + g * (size_t)W;
+            size_t k = 0;
+            for (int j = 0; j < W; ++j) {
+                const size_t go = m[j] != 0;
+                dst[k] = (char *)out[j] + placed[j] * row;
+                k += go;
+                placed[j] += go;
+            }
+            if (k == 0 || row == 0) continue;
+            put_fanout(s, (const char *)in[i] + (size_t)t * row, row, dst, k);
+        }
+    }
+    for (int j = 0; j < W; ++j)
+        if (placed[j] && row && !out[j]) return DL_ERR_INVALID;  // rows were placed at a null buffer: nothing is executed
+    return (long)s.n;
+}
+
 struct interval {
     uint64_t lo, hi;
     size_t item;
@@ -286,6 +368,7 @@ int dl_init(int device)
     g_dl.cfg.write_through_max_bytes = 144ull << 20;  // all-gather of 2 MiB per rank over 8 ranks
     g_dl.cfg.arm_timeout_us = 20000;
     g_dl.cfg.fuse_broadcast = 1;
+    g_dl.cfg.infer_broadcast = 1;
     const int rc = dl_exec_init();
     if (rc != DL_OK) return rc;
     g_dl.inited = true;
@@ -358,7 +441,47 @@ int dl_set_config(const dl_config *cfg)
 
 int dl_batch_copy(const dl_copy_desc *desc, size_t n, void *stream)
 {
+    if (g_dl.cfg.infer_broadcast && n > 1)
+        return lower_and_execute([&](sink &s) { return lower_batch_inferred(desc, n, s); }, stream);
     return lower_and_execute([&](sink &s) { return lower_batch(desc, n, s); }, stream);
+}
+
+int dl_batch_fanout(const dl_plan_item *items, size_t n, void *stream)
+{
+    if (n && !items) return DL_ERR_INVALID;
+    return lower_and_execute(
+        [&](sink &s) -> long {
+            for (size_t i = 0; i < n; ++i) {
+                if (items[i].k < 1 || items[i].k > (uint32_t)DL_PLAN_FANOUT) return DL_ERR_INVALID;
+                if (items[i].bytes == 0) continue;
+                if (!items[i].src) return DL_ERR_INVALID;
+                for (uint32_t j = 0; j < items[i].k; ++j)
+                    if (!items[i].dst[j]) return DL_ERR_INVALID;
+                s.put(items[i].src, items[i].bytes, items[i].dst, items[i].k);
+            }
+            return (long)s.n;
+        },
+        stream);
+}
+
+int dl_token_dispatch(const void *const *in, void *const *out, int W, const uint32_t *tokens, size_t row_bytes,
+                      const uint8_t *dest, void *stream)
+{
+    return lower_and_execute([&](sink &s) { return lower_token_dispatch(in, out, W, tokens, row_bytes, dest, s); },
+                             stream);
+}
+
+long dl_plan_token_dispatch(const void *const *in, void *const *out, int W, const uint32_t *tokens, size_t row_bytes,
+                            const uint8_t *dest, dl_plan_item *items, size_t cap)
+{
+    sink s{items, items ? cap : 0};
+    return lower_token_dispatch(in, out, W, tokens, row_bytes, dest, s);
+}
+
+long dl_plan_batch_inferred(const dl_copy_desc *desc, size_t n, dl_plan_item *items, size_t cap)
+{
+    sink s{items, items ? cap : 0};
+    return lower_batch_inferred(desc, n, s);
 }
 
 int dl_broadcast(const void *src, void *const *dsts, int k, size_t bytes, void *stream)

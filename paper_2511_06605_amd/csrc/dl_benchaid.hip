@@ -16,7 +16,8 @@ extern "C" {
 
 typedef struct dlb_request {
     int op;  // 0 batch, 1 broadcast, 2 all-gather, 3 all-to-all, 4 hipMemcpyAsync per desc, 5 hipMemcpyBatchAsync,
-             // 6 batch of swaps (desc as {a, b, bytes}), 7 in-place all-to-all (out = buffers, bytes = chunk)
+             // 6 batch of swaps (desc as {a, b, bytes}), 7 in-place all-to-all (out = buffers, bytes = chunk),
+             // 8 token dispatch (in, out, W, tokens, bytes = row, dest), 9 fan-out batch (desc = dl_plan_item array)
     int k;
     int W;
     int pad;
@@ -28,6 +29,8 @@ typedef struct dlb_request {
     const void *const *in;
     void *const *out;
     const size_t *C;
+    const uint32_t *tokens;
+    const uint8_t *dest;
 } dlb_request;
 
 static double now_us()
@@ -77,6 +80,8 @@ int dlb_issue(const dlb_request *r, void *stream)
     }
     case 6: return dl_batch_swap((const dl_swap_desc *)r->desc, r->n, stream);
     case 7: return dl_alltoall_inplace(r->out, r->W, r->bytes, stream);
+    case 8: return dl_token_dispatch(r->in, r->out, r->W, r->tokens, r->bytes, r->dest, stream);
+    case 9: return dl_batch_fanout((const dl_plan_item *)r->desc, r->n, stream);
     default: return DL_ERR_INVALID;
     }
 }
@@ -110,6 +115,19 @@ int dlb_time_host(const dlb_request *r, void *stream, int wait_mode, int warmup,
         const double t1 = now_us();
         if (i >= 0) us[i] = t1 - t0;
     }
+    return 0;
+}
+
+// Host time of the lowering alone (no GPU work): microseconds per dl_plan_token_dispatch call.
+int dlb_time_token_lowering(const dlb_request *r, dl_plan_item *items, size_t cap, int iters, double *us_per_call)
+{
+    long n = 0;
+    const double t0 = now_us();
+    for (int i = 0; i < iters; ++i) {
+        n = dl_plan_token_dispatch(r->in, r->out, r->W, r->tokens, r->bytes, r->dest, items, cap);
+        if (n < 0) return (int)n;
+    }
+    *us_per_call = (now_us() - t0) / iters;
     return 0;
 }
 

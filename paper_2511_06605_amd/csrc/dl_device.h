@@ -66,10 +66,14 @@ __device__ __forceinline__ void dl_st(DL_GLOBAL V *p, V v)
 {
     if constexpr (POL == DL_POL_STREAM)
         __builtin_nontemporal_store(v, p);
+    // The s_nop after each store: a store of more than 8 bytes must not be followed directly by a
+    // vector ALU write to its data registers (the hardware reads them a cycle late).  The compiler
+    // pads its own stores for this, but it cannot see that the assembly below is one, and it is free
+    // to reuse v's registers in the very next instruction.
     else if constexpr (POL == DL_POL_WT && sizeof(V) == 16)
-        asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(v) : "memory");
+        asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
     else if constexpr (POL == DL_POL_COHERENT && sizeof(V) == 16)
-        asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" : : "v"(p), "v"(v) : "memory");
+        asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
     else if constexpr (POL == DL_POL_COHERENT)
         __hip_atomic_store((V *)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     else

@@ -202,11 +202,13 @@ template <> struct list_cap<dl_swap_item> { static constexpr int big = 64; };
 template <> struct list_cap<dl_fused_item> { static constexpr int big = 32; };
 
 constexpr uint64_t TABLE_ENTRIES_TARGET = 8192;  // table kernels: aim for at most this many one-tile entries
+constexpr size_t TABLE_STAGE_MIN = 512;          // tables at least this long are staged in device memory first
 constexpr size_t RING_SLOTS = 4;
 constexpr size_t RING_SLOT_BYTES = 1u << 20;
 
 struct ring_t {
-    char *base = nullptr;
+    char *base = nullptr;  // pinned host memory: the host writes tables here
+    char *dev = nullptr;   // device memory of the same shape: long tables are staged here before they are used
     hipEvent_t ev[RING_SLOTS]{};
     bool used[RING_SLOTS]{};
     size_t next = 0;
@@ -377,6 +379,20 @@ int launch_table(const Item *items, size_t n, dl_launch_shape sh, hipStream_t st
             off += it.bytes;
         }
         if (m == 0) break;
+        if (m >= TABLE_STAGE_MIN) {
+            // Stage the table in device memory with a 1:1 copy of our own, enqueued in front of the
+            // kernel that uses it (it does not wait for a doorbell: the table is final now).  The
+            // workgroups then find their entries in HBM instead of each fetching one over the host link.
+            Item *dslot = (Item *)(g_ring.dev + s * RING_SLOT_BYTES);
+            dl_plain_item stage{(const char *)slot, (char *)dslot, (m * sizeof(Item) + 15u) & ~(uint64_t)15u};
+            const dl_launch_shape ssh = dl_choose_shape(stage.bytes, stage.bytes, 1);
+            uint64_t stage_tiles = dl_item_tiles(stage, ssh.tile_bytes);
+            dl_launch_shape rsh = ssh;
+            rsh.rows = true;
+            const int rc = launch_klist<dl_plain_item, NMAX_SMALL>(&stage, 1, &stage_tiles, rsh, stream, nullptr);
+            if (rc != DL_OK) return rc;
+            slot = dslot;
+        }
         if (arm) {
             dl_arm a = *arm;
             const uint32_t g = armed_grid(m);
@@ -507,6 +523,7 @@ int dl_exec_init()
 {
     if (g_ring.base) return DL_OK;
     DL_HIP(hipHostMalloc((void **)&g_ring.base, RING_SLOTS * RING_SLOT_BYTES, hipHostMallocDefault));
+    DL_HIP(hipMalloc((void **)&g_ring.dev, RING_SLOTS * RING_SLOT_BYTES));
     for (size_t s = 0; s < RING_SLOTS; ++s) {
         DL_HIP(hipEventCreateWithFlags(&g_ring.ev[s], hipEventDisableTiming));
         g_ring.used[s] = false;
@@ -523,6 +540,8 @@ int dl_exec_shutdown()
         (void)hipEventDestroy(g_ring.ev[s]);
     }
     (void)hipHostFree(g_ring.base);
+    (void)hipFree(g_ring.dev);
     g_ring.base = nullptr;
+    g_ring.dev = nullptr;
     return DL_OK;
 }

@@ -282,6 +282,81 @@ def test_batch_kv_fetch_shape(ref):
     run_batch(ref, 256, 128 * KiB, 256 * MiB, seed=5)
 
 
+# ------------------------------------------- token dispatch, fan-out batches, broadcast inference
+
+def run_token_dispatch(ref, W, counts, row, seed, kind="u8", drop=None, skew=None, experts=256, top_k=8):
+    ins = inputs.token_rows(W, counts, row, seed=seed, kind=kind)
+    dest = inputs.moe_token_destinations(W, counts, seed=seed + 1, n_experts=experts, top_k=top_k, skew_alpha=skew)
+    if drop:
+        dest[::drop] = 0
+    want = ref.token_dispatch(ins, row, dest)
+    d_in = [DevBuf(a.size, fill=a) for a in ins]
+    d_out = [DevBuf(w.size) for w in want]
+    tok = [counts] * W if np.isscalar(counts) else counts
+    dl.dl_token_dispatch([b.ptr() for b in d_in], [b.ptr() for b in d_out], tok, row, dest, stream())
+    sync()
+    for j in range(W):
+        assert np.array_equal(d_out[j].host(), want[j]), f"receiver {j} differs"
+        assert d_out[j].guards_intact()
+    return int(dest.sum())
+
+
+@pytest.mark.parametrize("T", [16, 128, 512])
+def test_token_dispatch_moe_hidden_7168_bf16_top8(ref, T):
+    """W = 8, 256 experts split 32 per rank, top-8: thousands of 14 KiB rows, each to 1..8 ranks."""
+    copies = run_token_dispatch(ref, 8, T, 14336, seed=T, kind="bf16")
+    assert 8 * T <= copies <= 8 * 8 * T
+
+
+@pytest.mark.parametrize("W,counts,row,drop", [(1, [5], 1000, None), (3, [7, 0, 2], 100, 3), (8, [1] * 8, 17, None),
+                                               (5, [40, 3, 0, 11, 9], 4097, 4), (13, [6] * 13, 5000, 5)])
+def test_token_dispatch_ragged(ref, W, counts, row, drop):
+    run_token_dispatch(ref, W, counts, row, seed=W * 7 + row, drop=drop, experts=16 * W, top_k=min(8, W))
+
+
+def test_token_dispatch_skewed_experts(ref):
+    run_token_dispatch(ref, 8, 128, 14336, seed=21, kind="bf16", skew=0.3)
+
+
+def test_batch_fanout_mixed_items(ref):
+    """Read-once/write-k items with every k in one batch, ragged sizes; checked as the plain copies they stand for."""
+    rng = np.random.default_rng(8)
+    n_items, slot = 24, 20000
+    arena = rng.integers(0, 256, (n_items * 9 + 1) * slot, dtype=np.uint8)
+    d = DevBuf(arena.size, fill=arena)
+    items, copies = [], []
+    for i in range(n_items):
+        k, nb = 1 + i % 8, int(rng.integers(1, slot))
+        s = i * 9 * slot
+        dsts = [s + (q + 1) * slot for q in range(k)]
+        items.append(dict(src=d.ptr(s), bytes=nb, dst=[d.ptr(t) for t in dsts]))
+        copies += [(0, s, 0, t, nb) for t in dsts]
+    want = ref.batch_copy([arena.copy()], copies)[0]
+    dl.dl_batch_fanout(items, stream())
+    sync()
+    assert np.array_equal(d.host(), want) and d.guards_intact()
+
+
+@pytest.mark.parametrize("infer", [0, 1])
+def test_batch_copy_with_and_without_broadcast_inference(ref, cfg, infer):
+    """An all-gather written as 64 plain copies (receiver-major), plus unrelated copies: same bytes either way."""
+    cfg(infer_broadcast=infer)
+    W, B = 8, 50000
+    ins = inputs.allgather_inputs(W, B, seed=6)
+    want = ref.allgather(ins)
+    d_in = [DevBuf(B, fill=a) for a in ins]
+    d_out = [DevBuf(W * B) for _ in range(W)]
+    extra_src = DevBuf(3000, fill=inputs.payload(np.random.default_rng(1), 3000))
+    extra_dst = DevBuf(3000)
+    descs = [(d_in[j].ptr(), d_out[r].ptr(j * B), B) for r in range(W) for j in range(W)]
+    descs += [(extra_src.ptr(0), extra_dst.ptr(0), 1500), (extra_src.ptr(1500), extra_dst.ptr(1500), 1500)]
+    dl.dl_batch_copy(descs, stream())
+    sync()
+    for r in range(W):
+        assert np.array_equal(d_out[r].host(), want[r]) and d_out[r].guards_intact()
+    assert np.array_equal(extra_dst.host(), extra_src.host()) and extra_dst.guards_intact()
+
+
 # ------------------------------------------- KV-cache fetch / save (Sec. V-C)
 
 @pytest.mark.parametrize("block_bytes", [16 * KiB, 160 * KiB, 1 * MiB + 4096])

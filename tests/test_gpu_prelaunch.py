@@ -162,6 +162,21 @@ def test_alltoall_inplace_armed(ref, armed, W, c):
         assert np.array_equal(d[i].host(), want[i]) and d[i].guards_intact()
 
 
+@pytest.mark.parametrize("T", [16, 128])
+def test_token_dispatch_armed(ref, armed, T):
+    W, row = 8, 14336
+    ins = inputs.token_rows(W, T, row, seed=T, kind="bf16")
+    dest = inputs.moe_token_destinations(W, T, seed=T + 1)
+    want = ref.token_dispatch(ins, row, dest)
+    d_in = [DevBuf(a.size, fill=a) for a in ins]
+    d_out = [DevBuf(w.size) for w in want]
+    sync()
+    dl.dl_token_dispatch([b.ptr() for b in d_in], [b.ptr() for b in d_out], [T] * W, row, dest)
+    fire()
+    for j in range(W):
+        assert np.array_equal(d_out[j].host(), want[j]) and d_out[j].guards_intact()
+
+
 def test_batch_swap_armed_twice_restores(ref, armed):
     arena, descs = inputs.swap_batch(30, 20000, 8 * MiB, seed=9, align=16)
     d = DevBuf(8 * MiB, fill=arena)

@@ -285,3 +285,48 @@ def test_swap_hazard_validator_agrees_with_the_checker(ref):
         except ValueError:
             want_ok = False
         assert (got == -1) == want_ok, sw
+
+
+# --------------------------------------- token dispatch and broadcast inference (Sec. IV-B, VI)
+
+@pytest.mark.parametrize("W,counts,row", [(8, [16] * 8, 14336), (3, [5, 0, 7], 100), (13, [3] * 13, 48), (1, [4], 9)])
+def test_token_dispatch_lowers_to_one_fanout_copy_per_token_and_replays_to_the_checker(ref, W, counts, row):
+    ins = inputs.token_rows(W, counts, row, seed=W)
+    dest = inputs.moe_token_destinations(W, counts, seed=W + 1, n_experts=16 * W, top_k=min(8, W))
+    dest[1::7] = 0
+    want = ref.token_dispatch(ins, row, dest)
+    outs = [np.zeros(w.size, dtype=np.uint8) for w in want]
+    items = dl.dl_plan_token_dispatch([addr(a) for a in ins], [addr(o) if o.size else 0 for o in outs], counts, row, dest)
+    k = dest.sum(axis=1)
+    # one item per group of up to 8 destinations of a token; none for a token that goes nowhere
+    assert len(items) == int(np.ceil(k / 8).sum())
+    assert sum(len(it["dst"]) for it in items) == int(dest.sum())
+    assert all(it["bytes"] == row for it in items)
+    assert dl.dl_plan_first_hazard(items) == -1
+    replay(items)
+    for o, w in zip(outs, want):
+        assert np.array_equal(o, w)
+
+
+def test_broadcast_inference_merges_copies_with_same_source_and_size(ref):
+    W, B = 8, 96
+    ins = inputs.allgather_inputs(W, B, seed=4)
+    outs = [np.zeros(W * B, dtype=np.uint8) for _ in range(W)]
+    # an all-gather written as n x n plain copies, receiver-major (so equal sources are not adjacent)
+    descs = [(addr(ins[j]), addr(outs[r], j * B), B) for r in range(W) for j in range(W)]
+    items = dl.dl_plan_batch_inferred(descs)
+    assert len(items) == W and all(len(it["dst"]) == W for it in items)
+    assert [it["src"] for it in items] == [addr(a) for a in ins]        # order of first appearance
+    replay(items)
+    for o, w in zip(outs, ref.allgather(ins)):
+        assert np.array_equal(o, w)
+    # more than 8 destinations: a second item; other size or other source: not merged; empty and identical: dropped
+    buf = np.zeros(4096, dtype=np.uint8)
+    p = addr(buf)
+    descs = [(p, p + 1000 + 100 * d, 50) for d in range(11)] + [(p, p + 3000, 40), (p + 8, p + 3100, 50),
+                                                                 (p, p + 3200, 0), (p + 500, p + 500, 20)]
+    items = dl.dl_plan_batch_inferred(descs)
+    assert [(it["src"] - p, it["bytes"], len(it["dst"])) for it in items] == [(0, 50, 8), (0, 40, 1), (8, 50, 1), (0, 50, 3)] \
+        or [(it["src"] - p, it["bytes"], len(it["dst"])) for it in items] == [(0, 50, 8), (0, 50, 3), (0, 40, 1), (8, 50, 1)]
+    assert sorted(d - p for it in items if it["bytes"] == 50 and it["src"] == p for d in it["dst"]) == \
+        [1000 + 100 * d for d in range(11)]
