@@ -414,8 +414,34 @@ def main() -> int:
             row["prelaunch_trigger_to_done_us"] = lat_stats(lat)
             lat = benchaid.time_host(reqs[B], None, benchaid.WAIT_ARM_AND_TRIGGER, warmup=50, iters=500)
             row["prelaunch_arm_to_done_us"] = lat_stats(lat)
+        # phase breakdown (the form of the paper's Fig. 4: one transfer split into control / schedule / copy / sync,
+        # 4 KB .. 2 MB), medians in microseconds
+        med = lambda xs: pct(xs, .5)
+        rows = []
+        for row in detail["allgather"]:
+            B = row["bytes_per_rank"]
+            if B > 2 * MiB:
+                continue
+            ph = benchaid.phases(reqs[B], warmup=10, iters=100)
+            m = {k: med([p[k] for p in ph]) for k in benchaid.PHASES}
+            rows.append({"bytes_per_rank": B, "prelaunch": {
+                "control_arming_call_off_critical_path": m["arming_call"],
+                "schedule_and_sync_over_host_link": m["doorbell_to_seen"] + m["completion_issued_to_host"],
+                "schedule_fanout_to_workgroups": m["seen_to_first_copy"],
+                "copy": m["copy"],
+                "sync_arrival_count": m["last_copy_to_completion_issued"],
+                "host_link_split_estimate": {"doorbell_to_seen": m["doorbell_to_seen"],
+                                             "completion_issued_to_host": m["completion_issued_to_host"]}}})
         dl.dl_set_mode(dl.DL_MODE_ONESHOT)
         dl.dl_prelaunch_stop()
+        for r_ in rows:
+            B = r_["bytes_per_rank"]
+            call, total = benchaid.time_call(reqs[B], stream, 20, 200)
+            dev_us = next(x["device_us"] for x in detail["allgather"] if x["bytes_per_rank"] == B)
+            r_["oneshot"] = {"control_call": med(call), "copy_device": dev_us,
+                             "schedule_and_sync_launch_and_stream_sync": med(total) - med(call) - dev_us,
+                             "total": med(total)}
+        detail["phase_breakdown_allgather"] = rows
         detail.update(other_operations(dl, benchaid, inputs, torch, stream, reqs, keep, sizes))
         out["detail"] = detail
         small = detail["allgather"][0]

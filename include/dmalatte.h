@@ -193,6 +193,31 @@ int dl_trigger(uint64_t ticket);
 int dl_wait(uint64_t ticket, uint64_t timeout_ns);
 int dl_wait_armed(uint64_t ticket, uint64_t timeout_ns);
 
+/*
+ * Phase stamps of an armed request (the analogue of splitting one copy into
+ * schedule, copy and sync with timestamp commands, paper Sec. III-B1/B2).
+ * With dl_set_trace(1), every request armed afterwards records four readings of
+ * the device's wall clock; dl_get_trace() returns them once dl_wait() has
+ * returned for that ticket (and before 64 later requests reuse its slot):
+ *   doorbell_seen      the polling workgroup saw the doorbell
+ *   copy_begin         the polling workgroup, the first to do so, began to copy
+ *   copy_end           the stores of the workgroup that arrived last had completed
+ *   completion_issued  the last workgroup was about to write the completion word
+ * dl_trace_clock() relates that clock to the host's CLOCK_MONOTONIC by a short
+ * ping-pong through host-coherent memory: device tick t happened at about
+ * host_ns_at_tick0 + t * 1000 / ticks_per_us nanoseconds (good to half a
+ * round trip over the host link, under a microsecond).  Needs prelaunch mode started.
+ */
+typedef struct dl_trace {
+    uint64_t doorbell_seen;
+    uint64_t copy_begin;
+    uint64_t copy_end;
+    uint64_t completion_issued;
+} dl_trace;
+int dl_set_trace(int on);
+int dl_get_trace(uint64_t ticket, dl_trace *out);
+int dl_trace_clock(double *ticks_per_us, double *host_ns_at_tick0);
+
 /* -------------------------------------------------------------------- tunables */
 
 typedef struct dl_config {

@@ -14,4 +14,4 @@ from .binding import (  # noqa: F401
     dl_plan_tiles, dl_prelaunch_start, dl_prelaunch_stop, dl_set_config, dl_set_mode,
     dl_set_validate, dl_shutdown, dl_trigger, dl_wait, dl_wait_armed, dl_batch_swap, dl_alltoall_inplace,
     dl_plan_alltoall_inplace, dl_plan_swap_first_hazard, dl_batch_fanout, dl_token_dispatch,
-    dl_plan_token_dispatch, dl_plan_batch_inferred)
+    dl_plan_token_dispatch, dl_plan_batch_inferred, dl_set_trace, dl_get_trace, dl_trace_clock)

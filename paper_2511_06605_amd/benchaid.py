@@ -44,6 +44,10 @@ def aid() -> ctypes.CDLL:
         L.dlb_time_host.argtypes = [rp, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, dp]
         L.dlb_time_device.restype = ctypes.c_int
         L.dlb_time_device.argtypes = [rp, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, dp]
+        L.dlb_time_call.restype = ctypes.c_int
+        L.dlb_time_call.argtypes = [rp, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, dp, dp]
+        L.dlb_phases.restype = ctypes.c_int
+        L.dlb_phases.argtypes = [rp, ctypes.c_int, ctypes.c_int, dp]
         L.dlb_time_token_lowering.restype = ctypes.c_int
         L.dlb_time_token_lowering.argtypes = [rp, ctypes.POINTER(binding.PlanItem), ctypes.c_size_t, ctypes.c_int, dp]
         _aid = L
@@ -146,3 +150,21 @@ def time_device(p: Prepared, stream=None, warmup=5, calls=20) -> float:
     _rc(aid().dlb_time_device(ctypes.byref(p.req), binding._stream(stream), warmup, calls, ctypes.byref(out)),
         "dlb_time_device")
     return out.value
+
+
+def time_call(p: Prepared, stream=None, warmup=20, iters=200):
+    """One-shot mode: (host durations of the call itself, call -> stream synchronised), microseconds."""
+    a, b = (ctypes.c_double * iters)(), (ctypes.c_double * iters)()
+    _rc(aid().dlb_time_call(ctypes.byref(p.req), binding._stream(stream), warmup, iters, a, b), "dlb_time_call")
+    return list(a), list(b)
+
+
+PHASES = ("arming_call", "doorbell_to_seen", "seen_to_first_copy", "copy", "last_copy_to_completion_issued",
+          "completion_issued_to_host")
+
+
+def phases(p: Prepared, warmup=10, iters=100):
+    """Prelaunch mode with phase stamps: a list of dicts, microseconds per phase (see PHASES)."""
+    out = (ctypes.c_double * (6 * iters))()
+    _rc(aid().dlb_phases(ctypes.byref(p.req), warmup, iters, out), "dlb_phases")
+    return [dict(zip(PHASES, out[6 * i:6 * i + 6])) for i in range(iters)]

@@ -38,7 +38,7 @@ EXPORTS = [
     "dl_set_config", "dl_plan_allgather", "dl_plan_alltoall", "dl_plan_broadcast", "dl_plan_batch",
     "dl_plan_first_hazard", "dl_plan_tiles", "dl_batch_swap", "dl_alltoall_inplace", "dl_plan_alltoall_inplace",
     "dl_plan_swap_first_hazard", "dl_batch_fanout", "dl_token_dispatch", "dl_plan_token_dispatch",
-    "dl_plan_batch_inferred",
+    "dl_plan_batch_inferred", "dl_set_trace", "dl_get_trace", "dl_trace_clock",
 ]
 
 
@@ -54,6 +54,11 @@ class CopyDesc(ctypes.Structure):
 
 class SwapDesc(ctypes.Structure):
     _fields_ = [("a", ctypes.c_void_p), ("b", ctypes.c_void_p), ("bytes", ctypes.c_size_t)]
+
+
+class Trace(ctypes.Structure):
+    _fields_ = [("doorbell_seen", ctypes.c_uint64), ("copy_begin", ctypes.c_uint64), ("copy_end", ctypes.c_uint64),
+                ("completion_issued", ctypes.c_uint64)]
 
 
 class Config(ctypes.Structure):
@@ -136,6 +141,9 @@ def lib() -> ctypes.CDLL:
         "dl_plan_alltoall_inplace": (ctypes.c_long, [vpp, ctypes.c_int, ctypes.c_size_t, ctypes.POINTER(SwapDesc),
                                                      ctypes.c_size_t]),
         "dl_plan_swap_first_hazard": (ctypes.c_long, [ctypes.POINTER(SwapDesc), ctypes.c_size_t]),
+        "dl_set_trace": (ctypes.c_int, [ctypes.c_int]),
+        "dl_get_trace": (ctypes.c_int, [ctypes.c_uint64, ctypes.POINTER(Trace)]),
+        "dl_trace_clock": (ctypes.c_int, [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]),
         "dl_batch_fanout": (ctypes.c_int, [ctypes.POINTER(PlanItem), ctypes.c_size_t, vp]),
         "dl_token_dispatch": (ctypes.c_int, [vpp, vpp, ctypes.c_int, ctypes.POINTER(ctypes.c_uint32), ctypes.c_size_t,
                                              ctypes.POINTER(ctypes.c_uint8), vp]),
@@ -341,6 +349,23 @@ def dl_wait(ticket: int | None = None, timeout_ns: int = 5_000_000_000) -> None:
 def dl_wait_armed(ticket: int | None = None, timeout_ns: int = 5_000_000_000) -> None:
     t = dl_last_ticket() if ticket is None else ticket
     _check(lib().dl_wait_armed(t, timeout_ns), "dl_wait_armed")
+
+
+def dl_set_trace(on: bool) -> None:
+    _check(lib().dl_set_trace(1 if on else 0), "dl_set_trace")
+
+
+def dl_get_trace(ticket: int | None = None) -> dict:
+    t = Trace()
+    _check(lib().dl_get_trace(dl_last_ticket() if ticket is None else ticket, ctypes.byref(t)), "dl_get_trace")
+    return {f[0]: int(getattr(t, f[0])) for f in Trace._fields_}
+
+
+def dl_trace_clock():
+    """(device ticks per microsecond, host CLOCK_MONOTONIC nanoseconds at device tick 0)."""
+    a, b = ctypes.c_double(0), ctypes.c_double(0)
+    _check(lib().dl_trace_clock(ctypes.byref(a), ctypes.byref(b)), "dl_trace_clock")
+    return a.value, b.value
 
 
 # --------------------------------------------------------------------- lowering

@@ -118,6 +118,70 @@ int dlb_time_host(const dlb_request *r, void *stream, int wait_mode, int warmup,
     return 0;
 }
 
+// One-shot mode, per call in microseconds: call_us[i] = how long the dl_* call itself took on the host (lowering
+// and the launch: the "control" phase), total_us[i] = clock before the call -> hipStreamSynchronize returns.
+int dlb_time_call(const dlb_request *r, void *stream, int warmup, int iters, double *call_us, double *total_us)
+{
+    for (int i = -warmup; i < iters; ++i) {
+        const double t0 = now_us();
+        int rc = dlb_issue(r, stream);
+        const double t1 = now_us();
+        if (rc) return rc;
+        if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return 1000;
+        const double t2 = now_us();
+        if (i >= 0) {
+            call_us[i] = t1 - t0;
+            total_us[i] = t2 - t0;
+        }
+    }
+    return 0;
+}
+
+// Prelaunch mode with phase stamps (dl_set_trace(1) is switched on and off here), six numbers per call in
+// microseconds: out[6 i + ..] =
+//   0 arming call on the host (lowering and launch; off the critical path)
+//   1 doorbell written by the host -> seen by the polling workgroup
+//   2 doorbell seen -> first workgroup begins to copy (fan-out over the workgroups)
+//   3 first copy begins -> last workgroup's stores have completed
+//   4 last copy ends -> completion word issued (arrival counting)
+//   5 completion word issued -> dl_wait returns on the host
+// The device clock is related to the host clock anew before every call.
+int dlb_phases(const dlb_request *r, int warmup, int iters, double *out)
+{
+    int rc = dl_set_trace(1);
+    for (int i = -warmup; i < iters && !rc; ++i) {
+        double tpu = 0, h0 = 0;
+        rc = dl_trace_clock(&tpu, &h0);
+        if (rc) break;
+        const double c0 = now_us();
+        rc = dlb_issue(r, nullptr);
+        const double c1 = now_us();
+        if (rc) break;
+        const uint64_t t = dl_last_ticket();
+        rc = dl_wait_armed(t, 2000000000ull);
+        if (rc) break;
+        const double t0 = now_us();
+        rc = dl_trigger(t);
+        if (!rc) rc = dl_wait(t, 2000000000ull);
+        const double t1 = now_us();
+        if (rc) break;
+        dl_trace tr;
+        rc = dl_get_trace(t, &tr);
+        if (rc) break;
+        if (i < 0) continue;
+        const double h0_us = h0 * 1e-3;
+        double *o = out + 6 * (size_t)i;
+        o[0] = c1 - c0;
+        o[1] = h0_us + (double)tr.doorbell_seen / tpu - t0;
+        o[2] = ((double)tr.copy_begin - (double)tr.doorbell_seen) / tpu;
+        o[3] = ((double)tr.copy_end - (double)tr.copy_begin) / tpu;
+        o[4] = ((double)tr.completion_issued - (double)tr.copy_end) / tpu;
+        o[5] = t1 - (h0_us + (double)tr.completion_issued / tpu);
+    }
+    (void)dl_set_trace(0);
+    return rc;
+}
+
 // Host time of the lowering alone (no GPU work): microseconds per dl_plan_token_dispatch call.
 int dlb_time_token_lowering(const dlb_request *r, dl_plan_item *items, size_t cap, int iters, double *us_per_call)
 {

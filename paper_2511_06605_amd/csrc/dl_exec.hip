@@ -84,6 +84,9 @@ __device__ __forceinline__ uint32_t dl_arm_wait(const dl_arm &a)
                 if (cancel >= a.ticket) break;
                 if (bell >= a.ticket) {
                     go = DL_GO_RUN;
+                    if (a.trace_host && blockIdx.x == 0)
+                        __hip_atomic_store(a.trace_host, (uint64_t)wall_clock64(), __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_SYSTEM);
                     break;
                 }
                 if ((spins & 3u) == 0 && (uint64_t)wall_clock64() - t0 > a.limit_ticks) break;
@@ -112,6 +115,8 @@ __device__ __forceinline__ uint32_t dl_arm_wait(const dl_arm &a)
                 if (spins >= a.max_spins) break;
             }
         }
+        if (a.trace_host && blockIdx.x == 0 && go == DL_GO_RUN)  // the polling workgroup is the first to begin its copy
+            __hip_atomic_store(a.trace_host + 1, (uint64_t)wall_clock64(), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
         s_go = go;
     }
     __syncthreads();
@@ -142,6 +147,9 @@ __device__ __forceinline__ void dl_arm_finish(const dl_arm &a, uint32_t go)
         const uint32_t gsize = (grid - g + DL_ARM_GROUPS - 1) / DL_ARM_GROUPS;
         uint32_t *gcount = (uint32_t *)((char *)a.arrive + g * DL_ARM_STRIDE);
         uint32_t *top = (uint32_t *)((char *)a.arrive + DL_ARM_GROUPS * DL_ARM_STRIDE);
+        // this workgroup's stores have drained; the workgroup that turns out to be the last of all reports
+        // its own reading as the end of the last copy (no extra traffic for the others)
+        const uint64_t t_end = a.trace_host ? (uint64_t)wall_clock64() : 0ull;
         uint32_t add = 1u + (go == DL_GO_RUN ? 0u : 0x10000u);
         uint32_t old = __hip_atomic_fetch_add(gcount, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if ((old & 0xFFFFu) != gsize - 1u) return;
@@ -155,6 +163,10 @@ __device__ __forceinline__ void dl_arm_finish(const dl_arm &a, uint32_t go)
         // last of all
         const uint32_t skipped = (old >> 16) + (add >> 16);
         __hip_atomic_store(top, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (a.trace_host) {
+            __hip_atomic_store(a.trace_host + 2, t_end, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            __hip_atomic_store(a.trace_host + 3, (uint64_t)wall_clock64(), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
         dl_drain_stores();
         __hip_atomic_store(a.done, a.ticket | (skipped ? DL_DONE_SKIPPED : 0ull), __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_SYSTEM);

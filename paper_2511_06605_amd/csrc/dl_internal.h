@@ -16,6 +16,7 @@ struct dl_state {
     int mode = DL_MODE_ONESHOT;
     int validate = 0;
     int last_hip = 0;
+    int trace = 0;  // armed kernels record phase stamps
     dl_config cfg{};
 };
 extern dl_state g_dl;
@@ -53,6 +54,9 @@ struct dl_arm {
     uint64_t margin_ticks;  // extra time a non-polling workgroup grants the polling one
     uint32_t direct;        // 1: every workgroup polls the host doorbell itself
     uint32_t max_spins;     // backstop that does not depend on the clock: give up after this many polls
+    // Phase stamps (device wall-clock ticks), null unless tracing is on: host-coherent, 4 words: doorbell seen,
+    // first copy begins (the polling workgroup's), last copy ends (the last arriver's), completion issued
+    uint64_t *trace_host;
 };
 constexpr uint32_t DL_ARM_GROUPS = 16;  // workgroup b belongs to group b % DL_ARM_GROUPS
 constexpr uint32_t DL_ARM_STRIDE = 4352;  // flags and counters sit 4 KiB + 256 B apart: separate lines and memory channels

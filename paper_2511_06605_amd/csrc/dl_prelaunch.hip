@@ -28,6 +28,8 @@ struct arm_host {  // pinned, host-coherent
     uint64_t pad[6];
     uint64_t done[SLOTS];   // device -> host: ticket (| DL_DONE_SKIPPED) of the last request finished in the slot
     uint64_t armed[SLOTS];  // device -> host: ticket of the last request seen resident in the slot
+    uint64_t trace[SLOTS][4];  // device -> host, when tracing: phase stamps of the slot's last request (device ticks)
+    uint64_t ping[2];       // clock calibration: host -> device round number, device -> host its clock at that round
 };
 
 struct arm_dev {  // device memory; every flag and counter in a cache line of its own
@@ -98,6 +100,7 @@ int dl_armed_begin(dl_arm *arm, hipStream_t *stream)
     arm->direct = 0;
     // a poll takes well over 100 ns (a host-link round trip, or a sleep plus a device-memory load)
     arm->max_spins = (g_dl.cfg.arm_timeout_us + 5000u) * 10u;
+    arm->trace_host = g_dl.trace ? g_arm.host->trace[slot] : nullptr;
     if (!*stream) *stream = g_arm.stream;
     return DL_OK;
 }
@@ -151,6 +154,77 @@ int dl_prelaunch_stop(void)
 }
 
 uint64_t dl_last_ticket(void) { return g_arm.seq; }
+
+int dl_set_trace(int on)
+{
+    g_dl.trace = on ? 1 : 0;
+    return DL_OK;
+}
+
+int dl_get_trace(uint64_t ticket, dl_trace *out)
+{
+    if (!g_arm.started) return DL_ERR_STATE;
+    if (!out || ticket == 0 || ticket > g_arm.seq || ticket + SLOTS <= g_arm.seq) return DL_ERR_INVALID;
+    const uint64_t *t = g_arm.host->trace[ticket % SLOTS];
+    out->doorbell_seen = load_word(&t[0]);
+    out->copy_begin = load_word(&t[1]);
+    out->copy_end = load_word(&t[2]);
+    out->completion_issued = load_word(&t[3]);
+    return DL_OK;
+}
+
+// Answers `rounds` pings: waits for ping[0] to reach r, then stores the device clock in ping[1].
+// Every wait is bounded by limit_ticks.
+__global__ void dl_clock_ping_kernel(uint64_t *ping, uint32_t rounds, uint64_t limit_ticks)
+{
+    const uint64_t t0 = wall_clock64();
+    for (uint32_t r = 1; r <= rounds; ++r) {
+        for (;;) {
+            if (__hip_atomic_load(ping, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) >= r) break;
+            if ((uint64_t)wall_clock64() - t0 > limit_ticks) return;
+        }
+        __hip_atomic_store(ping + 1, (uint64_t)wall_clock64(), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+}
+
+int dl_trace_clock(double *ticks_per_us, double *host_ns_at_tick0)
+{
+    if (!g_arm.started) return DL_ERR_STATE;
+    if (!ticks_per_us || !host_ns_at_tick0) return DL_ERR_INVALID;
+    constexpr uint32_t ROUNDS = 32;
+    uint64_t *ping = g_arm.host->ping;
+    __atomic_store_n(&ping[0], 0, __ATOMIC_RELEASE);
+    __atomic_store_n(&ping[1], 0, __ATOMIC_RELEASE);
+    const uint64_t limit = 200000ull * g_arm.clock_khz / 1000ull;  // 200 ms for all rounds
+    hipLaunchKernelGGL(dl_clock_ping_kernel, dim3(1), dim3(1), 0, g_arm.stream, ping, ROUNDS, limit);
+    DL_HIP(hipGetLastError());
+    double best_rtt = 1e30, best_host = 0;
+    uint64_t best_tick = 0, seen = 0;
+    for (uint32_t r = 1; r <= ROUNDS; ++r) {
+        const uint64_t t0 = now_ns();
+        __atomic_store_n(&ping[0], (uint64_t)r, __ATOMIC_RELEASE);
+        uint64_t v;
+        for (;;) {
+            v = load_word(&ping[1]);
+            if (v != seen) break;
+            if (now_ns() - t0 > 250000000ull) {
+                (void)hipStreamSynchronize(g_arm.stream);
+                return DL_ERR_TIMEOUT;
+            }
+        }
+        const uint64_t t1 = now_ns();
+        seen = v;
+        if (r > 4 && (double)(t1 - t0) < best_rtt) {  // the device stamped its clock about half-way through the round trip
+            best_rtt = (double)(t1 - t0);
+            best_host = (double)t0 + 0.5 * (double)(t1 - t0);
+            best_tick = v;
+        }
+    }
+    DL_HIP(hipStreamSynchronize(g_arm.stream));
+    *ticks_per_us = (double)g_arm.clock_khz / 1000.0;
+    *host_ns_at_tick0 = best_host - (double)best_tick * 1e6 / (double)g_arm.clock_khz;
+    return DL_OK;
+}
 
 int dl_trigger(uint64_t ticket)
 {

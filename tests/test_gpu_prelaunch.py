@@ -278,6 +278,38 @@ def test_armed_on_callers_stream_after_its_producer(ref, armed):
         assert np.array_equal(o.cpu().numpy(), want)
 
 
+def test_phase_stamps_are_ordered_and_clock_relates_to_host(ref, armed):
+    import time
+    rate, host_ns_at_tick0 = dl.dl_trace_clock()
+    assert 1.0 <= rate <= 10000.0                       # ticks per microsecond
+    dl.dl_set_trace(True)
+    try:
+        for B in (4 * KiB, 1 * MiB):                    # every workgroup polls / one polls and fans out
+            W = 8
+            ins = inputs.allgather_inputs(W, B, seed=B)
+            d_in = [DevBuf(B, fill=a) for a in ins]
+            d_out = [DevBuf(W * B) for _ in range(W)]
+            sync()
+            dl.dl_allgather([b.ptr() for b in d_in], [b.ptr() for b in d_out], B)
+            dl.dl_wait_armed()
+            t0 = time.clock_gettime_ns(time.CLOCK_MONOTONIC)
+            fire()
+            t1 = time.clock_gettime_ns(time.CLOCK_MONOTONIC)
+            tr = dl.dl_get_trace()
+            assert tr["doorbell_seen"] <= tr["copy_begin"] <= tr["copy_end"] <= tr["completion_issued"]
+            assert (tr["completion_issued"] - tr["doorbell_seen"]) / rate <= (t1 - t0) / 1e3   # inside the host's window
+            for name in ("doorbell_seen", "completion_issued"):
+                at = host_ns_at_tick0 + tr[name] * 1e3 / rate
+                assert t0 - 50_000 <= at <= t1 + 50_000, name                 # within 50 us of the host's window
+            for r, w in zip(d_out, ref.allgather(ins)):
+                assert np.array_equal(r.host(), w)
+    finally:
+        dl.dl_set_trace(False)
+    with pytest.raises(dl.DlError) as e:
+        dl.dl_get_trace(dl.dl_last_ticket() + 1)
+    assert e.value.status == dl.DL_ERR_INVALID
+
+
 def test_untriggered_request_expires_and_copies_nothing(ref):
     dl.dl_set_config(arm_timeout_us=3000)
     try:
