@@ -151,13 +151,17 @@ __device__ __forceinline__ void dl_arm_finish(const dl_arm &a, uint32_t go)
         // its own reading as the end of the last copy (no extra traffic for the others)
         const uint64_t t_end = a.trace_host ? (uint64_t)wall_clock64() : 0ull;
         uint32_t add = 1u + (go == DL_GO_RUN ? 0u : 0x10000u);
-        uint32_t old = __hip_atomic_fetch_add(gcount, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if ((old & 0xFFFFu) != gsize - 1u) return;
-        // last of the group: leave the counter at zero for the slot's next request (the reset has
-        // completed before anything that can let that request start), carry the result to the top
-        __hip_atomic_store(gcount, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        dl_drain_stores();
-        add = 1u + (((old >> 16) + (add >> 16)) << 16);
+        uint32_t old;
+        if (grid > DL_ARM_GROUPS) {
+            old = __hip_atomic_fetch_add(gcount, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if ((old & 0xFFFFu) != gsize - 1u) return;
+            // last of the group: leave the counter at zero for the slot's next request (the reset has
+            // completed before anything that can let that request start), carry the result to the top
+            __hip_atomic_store(gcount, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            dl_drain_stores();
+            add = 1u + (((old >> 16) + (add >> 16)) << 16);
+        }
+        // a grid of at most DL_ARM_GROUPS workgroups has one workgroup per group: counted at the top directly
         old = __hip_atomic_fetch_add(top, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if ((old & 0xFFFFu) != groups - 1u) return;
         // last of all
