@@ -5,9 +5,9 @@
 //
 // Short lists travel by value in the kernel-argument segment, so the device
 // needs no extra memory round trip to find its work: workgroup b finds its
-// (item, tile) from an inclusive prefix sum of tile counts with one wavefront
-// ballot.  Long lists are cut into one-tile items on the host and read by the
-// device straight from a pinned host ring, workgroup b taking item b.
+// (item, tile) from an inclusive prefix sum of tile counts.  Long lists are cut
+// into one-tile entries on the host, written to a pinned host ring (and copied
+// to device memory first when there are many), workgroup b taking entry b.
 #include "dl_device.h"
 #include "dl_internal.h"
 
@@ -18,18 +18,19 @@
 
 // ------------------------------------------------------------------- kernels
 
-template <class Item, int NMAX, int POL>
-__global__ void __launch_bounds__(512) dl_exec_list_kernel(const dl_klist<Item, NMAX> p)
-{
-    dl_run_tile<POL>(p, blockIdx.x);
-}
-
 // Row path only (see dl_run_rows).  A kernel of its own: sharing one kernel with
 // the general path cost 5 % of the all-gather rate through its register count.
 template <class Item, int NMAX, int POL>
 __global__ void __launch_bounds__(512) dl_exec_rows_kernel(const dl_klist<Item, NMAX> p)
 {
     dl_run_rows<POL>(p, blockIdx.x);
+}
+
+// General path: any alignment and tile size, one workgroup per tile.
+template <class Item, int NMAX, int POL>
+__global__ void __launch_bounds__(512) dl_exec_list_kernel(const dl_klist<Item, NMAX> p)
+{
+    dl_run_tile<POL>(p, blockIdx.x);
 }
 
 // Same, with a capped grid: workgroup b takes tiles b, b + grid, b + 2 grid, ...
