@@ -310,6 +310,32 @@ def test_phase_stamps_are_ordered_and_clock_relates_to_host(ref, armed):
     assert e.value.status == dl.DL_ERR_INVALID
 
 
+def test_armed_requests_back_to_back_with_changing_sources(armed):
+    """10000 armed all-gathers in a row over the same buffers, the sources rewritten (by another stream) before
+    every doorbell and the receive buffers checked (by that stream) right after every completion word: a load
+    served from a stale cache line, or a store not yet visible when the completion word is, shows up as a
+    wrong byte.  Sizes cycle through both doorbell schemes (every workgroup polls / one polls and fans out)."""
+    import torch
+    W = 8
+    sizes = [4 * KiB, 48 * KiB, 256 * KiB]
+    d_in = {B: [torch.zeros(B, dtype=torch.uint8, device="cuda") for _ in range(W)] for B in sizes}
+    d_out = {B: [torch.zeros(W * B, dtype=torch.uint8, device="cuda") for _ in range(W)] for B in sizes}
+    bad = torch.zeros(1, dtype=torch.int64, device="cuda")
+    for it in range(10000):
+        B = sizes[it % len(sizes)]
+        dl.dl_allgather(d_in[B], d_out[B], B)              # armed on the library's stream, polling
+        for j in range(W):
+            d_in[B][j].fill_((it * 7 + j * 31) % 251)      # sources written after arming, on torch's stream
+        sync()
+        fire()
+        for r in (it % W, (it + 3) % W):                   # two receive buffers per round, checked on the device
+            got = d_out[B][r].view(W, B)
+            want = torch.tensor([(it * 7 + j * 31) % 251 for j in range(W)], dtype=torch.uint8, device="cuda")
+            bad += (got != want[:, None]).sum()
+    sync()
+    assert int(bad.item()) == 0
+
+
 def test_untriggered_request_expires_and_copies_nothing(ref):
     dl.dl_set_config(arm_timeout_us=3000)
     try:
