@@ -351,33 +351,29 @@ __device__ __forceinline__ const char *dl_item_dst(const dl_fused_item &it, uint
 // destination in its sub-group's slots.  At this granularity (a wavefront lives
 // for one load and one or two stores) the per-wavefront instruction count and
 // the dependent scalar loads in front of the vector load decide the rate.
-template <int POL, class Item, int NMAX>
-__device__ __forceinline__ void dl_run_rows(const dl_klist<Item, NMAX> &p, uint32_t b)
+// `tile` is the tile's index within the item.
+template <int POL, class Item>
+__device__ __forceinline__ void dl_rows_body(const Item &it, uint32_t tile, uint32_t wl, uint32_t sl)
 {
-    uint32_t first_tile;
-    const uint32_t d = dl_find_item(p, b, &first_tile);
-    if (d >= p.n) return;
-    const Item &it = p.item[d];
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t lane = threadIdx.x & 63u;
-    const uint32_t wl = p.wpg_log2;
-    const uint64_t row = ((uint64_t)(b - first_tile) << wl) + (wave & ((1u << wl) - 1u));
+    const uint64_t row = ((uint64_t)tile << wl) + (wave & ((1u << wl) - 1u));
     const uint64_t byte = (row << 10) + (lane << 4);
     if constexpr (std::is_same<Item, dl_swap_item>::value) {
-        const char *a = it.src;
-        const char *b = it.dst;
+        const char *pa = it.src;
+        const char *pb = it.dst;
         if (byte >= it.bytes) return;
-        const dl_u32x4 x = dl_ld<POL>(dl_global<dl_u32x4>(a + byte));
-        const dl_u32x4 y = dl_ld<POL>(dl_global<dl_u32x4>(b + byte));
-        dl_st<POL>(dl_global<dl_u32x4>(a + byte), y);
-        dl_st<POL>(dl_global<dl_u32x4>(b + byte), x);
+        const dl_u32x4 x = dl_ld<POL>(dl_global<dl_u32x4>(pa + byte));
+        const dl_u32x4 y = dl_ld<POL>(dl_global<dl_u32x4>(pb + byte));
+        dl_st<POL>(dl_global<dl_u32x4>(pa + byte), y);
+        dl_st<POL>(dl_global<dl_u32x4>(pb + byte), x);
     } else if constexpr (std::is_same<Item, dl_plain_item>::value) {
         const char *src = it.src;
         const char *dst = dl_item_dst(it, 0);
         if (byte >= it.bytes) return;
         dl_st<POL>(dl_global<dl_u32x4>(dst + byte), dl_ld<POL>(dl_global<dl_u32x4>(src + byte)));
     } else {
-        const uint32_t slots = (uint32_t)DL_FAN >> p.split_log2;
+        const uint32_t slots = (uint32_t)DL_FAN >> sl;
         const uint32_t base = (wave >> wl) * slots;
         // everything the wavefront needs from the item is requested before the first use
         const char *src = it.src;
@@ -397,6 +393,16 @@ __device__ __forceinline__ void dl_run_rows(const dl_klist<Item, NMAX> &p, uint3
             dl_st<POL>(dl_global<dl_u32x4>(dq + byte), v);
         }
     }
+}
+
+// Row path over a list in the kernel arguments: global tile b -> (item, tile).
+template <int POL, class Item, int NMAX>
+__device__ __forceinline__ void dl_run_rows(const dl_klist<Item, NMAX> &p, uint32_t b)
+{
+    uint32_t first_tile;
+    const uint32_t d = dl_find_item(p, b, &first_tile);
+    if (d >= p.n) return;
+    dl_rows_body<POL>(p.item[d], b - first_tile, p.wpg_log2, p.split_log2);
 }
 
 // Global tile b of a list, any alignment and tile size: find its item, then

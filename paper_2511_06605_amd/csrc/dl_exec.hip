@@ -26,6 +26,19 @@ __global__ void __launch_bounds__(512) dl_exec_rows_kernel(const dl_klist<Item, 
     dl_run_rows<POL>(p, blockIdx.x);
 }
 
+// Row path over a table of equally sized items in device memory (long lists: thousands of token
+// rows, hundreds of cache blocks): workgroup b works on item b / tiles_per_item, which every
+// workgroup of that item finds in the scalar cache.
+template <class Item, int POL>
+__global__ void __launch_bounds__(512) dl_exec_urows_kernel(const Item *__restrict__ items, uint32_t n,
+                                                            uint32_t tiles_per_item, uint32_t wpg_log2,
+                                                            uint32_t split_log2)
+{
+    const uint32_t d = blockIdx.x / tiles_per_item;
+    if (d >= n) return;
+    dl_rows_body<POL>(items[d], blockIdx.x - d * tiles_per_item, wpg_log2, split_log2);
+}
+
 // General path: any alignment and tile size, one workgroup per tile.
 template <class Item, int NMAX, int POL>
 __global__ void __launch_bounds__(512) dl_exec_list_kernel(const dl_klist<Item, NMAX> p)
@@ -219,6 +232,7 @@ template <> struct list_cap<dl_swap_item> { static constexpr int big = 64; };
 template <> struct list_cap<dl_fused_item> { static constexpr int big = 32; };
 
 constexpr uint64_t TABLE_ENTRIES_TARGET = 8192;  // table kernels: aim for at most this many one-tile entries
+constexpr uint64_t UNIFORM_ROWS_MIN_BYTES = 4ull << 20;  // source bytes from which a uniform long list takes the row kernel
 constexpr size_t TABLE_STAGE_MIN = 512;          // tables at least this long are staged in device memory first
 constexpr size_t RING_SLOTS = 4;
 constexpr size_t RING_SLOT_BYTES = 1u << 20;
@@ -344,10 +358,82 @@ inline void advance(dl_fused_item &it, uint64_t off)
     for (uint32_t j = 0; j < it.k; ++j) it.dst[j] += off;
 }
 
+// Copy `bytes` (a multiple of 16) from a slot of the pinned ring to the same slot of its device
+// mirror with a 1:1 row kernel of our own, enqueued on `stream` in front of the kernel that reads it.
+int stage_slot(size_t s, uint64_t bytes, hipStream_t stream)
+{
+    dl_plain_item stage{g_ring.base + s * RING_SLOT_BYTES, g_ring.dev + s * RING_SLOT_BYTES, bytes};
+    dl_launch_shape ssh = dl_choose_shape(stage.bytes, stage.bytes, 1);
+    ssh.split = 1;
+    ssh.tile_bytes = 16u * ssh.block_threads;  // the row path's tile: one 1 KiB row per wavefront
+    ssh.rows = true;
+    uint64_t stage_tiles = dl_item_tiles(stage, ssh.tile_bytes);
+    return launch_klist<dl_plain_item, NMAX_SMALL>(&stage, 1, &stage_tiles, ssh, stream, nullptr);
+}
+
+// Long list of equally sized, 16-byte aligned items that moves enough bytes to pay for staging
+// its table: the items themselves (not cut into tiles) go to device memory and the row kernel
+// above works on them.  Returns false if the list does not qualify.  (Lists that still fit the
+// kernel arguments, such as the 64 chunks of a uniform all-to-all, were 5-25 % slower this way than
+// on the general path and do not come here.)
+template <class Item>
+bool launch_uniform_rows(const Item *items, size_t n, const dl_launch_shape &sh, hipStream_t stream, int *rc)
+{
+    const dl_config &c = g_dl.cfg;
+    if (c.tile_bytes || c.block_threads || sh.max_blocks) return false;
+    if (n * sizeof(Item) > RING_SLOT_BYTES) return false;
+    const uint64_t bytes = items[0].bytes;
+    uint32_t kmax = 1;
+    for (size_t i = 0; i < n; ++i) {
+        if (items[i].bytes != bytes || !item_aligned16(items[i])) return false;
+        if (item_k(items[i]) > kmax) kmax = item_k(items[i]);
+    }
+    if (bytes * n < UNIFORM_ROWS_MIN_BYTES) return false;
+    const uint32_t split = sh.split, tile = 4096u / split;  // 256 threads: one 1 KiB row per wavefront of a sub-group
+    const uint64_t tpi = (bytes + tile - 1) / tile;
+    if (tpi * n >= (1ull << 30)) return false;
+
+    const size_t s = g_ring.next++ % RING_SLOTS;
+    *rc = DL_ERR_HIP;
+    if (g_ring.used[s]) {
+        const hipError_t e = hipEventSynchronize(g_ring.ev[s]);
+        if (e != hipSuccess) {
+            g_dl.last_hip = (int)e;
+            return true;
+        }
+    }
+    Item *slot = (Item *)(g_ring.base + s * RING_SLOT_BYTES);
+    for (size_t i = 0; i < n; ++i) {
+        slot[i] = items[i];
+        slots_by_subgroup(slot[i], split);
+    }
+    *rc = stage_slot(s, (n * sizeof(Item) + 15u) & ~(uint64_t)15u, stream);
+    if (*rc != DL_OK) return true;
+    const Item *dslot = (const Item *)(g_ring.dev + s * RING_SLOT_BYTES);
+    with_policy(sh.policy, [&](auto pol) {
+        hipLaunchKernelGGL((dl_exec_urows_kernel<Item, decltype(pol)::value>), dim3((uint32_t)(tpi * n)), dim3(256), 0,
+                           stream, dslot, (uint32_t)n, (uint32_t)tpi, log2u(4u / split), log2u(split));
+    });
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) e = hipEventRecord(g_ring.ev[s], stream);
+    if (e != hipSuccess) {
+        g_dl.last_hip = (int)e;
+        *rc = DL_ERR_HIP;
+        return true;
+    }
+    g_ring.used[s] = true;
+    *rc = DL_OK;
+    return true;
+}
+
 template <class Item>
 int launch_table(const Item *items, size_t n, dl_launch_shape sh, hipStream_t stream, const dl_arm *arm)
 {
     if (!g_ring.base) return DL_ERR_STATE;
+    if (!arm) {
+        int rc = DL_OK;
+        if (launch_uniform_rows(items, n, sh, stream, &rc)) return rc;
+    }
     const size_t cap = RING_SLOT_BYTES / sizeof(Item);
     auto entries = [&](uint32_t tile) {
         uint64_t m = 0;
@@ -397,18 +483,12 @@ int launch_table(const Item *items, size_t n, dl_launch_shape sh, hipStream_t st
         }
         if (m == 0) break;
         if (m >= TABLE_STAGE_MIN) {
-            // Stage the table in device memory with a 1:1 copy of our own, enqueued in front of the
-            // kernel that uses it (it does not wait for a doorbell: the table is final now).  The
-            // workgroups then find their entries in HBM instead of each fetching one over the host link.
-            Item *dslot = (Item *)(g_ring.dev + s * RING_SLOT_BYTES);
-            dl_plain_item stage{(const char *)slot, (char *)dslot, (m * sizeof(Item) + 15u) & ~(uint64_t)15u};
-            const dl_launch_shape ssh = dl_choose_shape(stage.bytes, stage.bytes, 1);
-            uint64_t stage_tiles = dl_item_tiles(stage, ssh.tile_bytes);
-            dl_launch_shape rsh = ssh;
-            rsh.rows = true;
-            const int rc = launch_klist<dl_plain_item, NMAX_SMALL>(&stage, 1, &stage_tiles, rsh, stream, nullptr);
+            // Stage the table in device memory, in front of the kernel that uses it (the copy does not
+            // wait for a doorbell: the table is final now).  The workgroups then find their entries in
+            // HBM instead of each fetching one over the host link.
+            const int rc = stage_slot(s, (m * sizeof(Item) + 15u) & ~(uint64_t)15u, stream);
             if (rc != DL_OK) return rc;
-            slot = dslot;
+            slot = (Item *)(g_ring.dev + s * RING_SLOT_BYTES);
         }
         if (arm) {
             dl_arm a = *arm;

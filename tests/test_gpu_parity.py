@@ -357,6 +357,17 @@ def test_batch_copy_with_and_without_broadcast_inference(ref, cfg, infer):
     assert np.array_equal(extra_dst.host(), extra_src.host()) and extra_dst.guards_intact()
 
 
+@pytest.mark.parametrize("n,nb", [(9, 8 * MiB), (64, 1 * MiB), (65, 1 * MiB), (200, 512 * KiB), (70, 100 * KiB)])
+def test_long_lists_of_equal_large_copies(ref, n, nb):
+    """Lists of equal, aligned, large copies: up to 64 of them travel in the kernel arguments (general path),
+    longer lists take the row kernel over a table staged in device memory; every byte of the arena is compared."""
+    run_batch(ref, n, nb, 2 * n * nb + 64 * MiB, seed=n, align=4096)
+
+
+def test_alltoall_uniform_2MiB_chunks_every_chunk(ref):
+    run_alltoall(ref, inputs.uniform_chunks(8, 2 * MiB), seed=3, kind="fp16")
+
+
 # ------------------------------------------- KV-cache fetch / save (Sec. V-C)
 
 @pytest.mark.parametrize("block_bytes", [16 * KiB, 160 * KiB, 1 * MiB + 4096])
