@@ -158,6 +158,16 @@ def test_broadcast_default_split_every_fanout(ref, k):
         assert np.array_equal(b.host(), w) and b.guards_intact()
 
 
+@pytest.mark.parametrize("cap", [1, 7, 64, 4096])
+def test_capped_grid_workgroups_stride_over_tiles(ref, cfg, cap):
+    """max_blocks caps the one-shot grid; the workgroups then take tiles b, b + grid, ... (general path)."""
+    cfg(max_blocks=cap)
+    run_allgather(ref, 8, 300 * KiB + 16, seed=cap)
+    run_allgather(ref, 3, 70001, seed=cap + 1)
+    run_alltoall(ref, inputs.random_chunks(8, 90000, seed=cap, zero_frac=0.2), seed=cap + 2)
+    run_batch(ref, 5, 200000, 8 * MiB, seed=cap + 3, align=16)
+
+
 def test_allgather_nontemporal_path(ref, cfg):
     cfg(nontemporal_min_bytes=0)
     run_allgather(ref, 8, 300001, seed=8)

@@ -127,7 +127,7 @@ def test_alltoall_long_list_goes_through_table(ref, armed):
         assert np.array_equal(d_out[j].host(), want[j]) and d_out[j].guards_intact()
 
 
-@pytest.mark.parametrize("k,n", [(7, 2 * MiB), (1, 333), (20, 70001)])
+@pytest.mark.parametrize("k,n", [(7, 2 * MiB), (1, 333), (20, 70001), (1, 64 * KiB), (2, 1 * MiB), (4, 48 * KiB)])
 def test_broadcast(ref, armed, k, n):
     src = inputs.payload(np.random.default_rng(k), n, "bf16" if n % 2 == 0 else "u8")
     d_src = DevBuf(n, fill=src)
@@ -308,6 +308,18 @@ def test_phase_stamps_are_ordered_and_clock_relates_to_host(ref, armed):
     with pytest.raises(dl.DlError) as e:
         dl.dl_get_trace(dl.dl_last_ticket() + 1)
     assert e.value.status == dl.DL_ERR_INVALID
+
+
+@pytest.mark.parametrize("blocks", [1, 5, 300])
+def test_armed_grid_cap(ref, armed, blocks):
+    """armed_blocks caps an armed kernel's grid: 1 workgroup (it polls and copies everything), a handful (all
+    poll), hundreds (one polls, the rest follow its flags)."""
+    dl.dl_set_config(armed_blocks=blocks)
+    try:
+        allgather_case(ref, 8, 200 * KiB + 16, seed=blocks, kind="bf16")
+        allgather_case(ref, 5, 7001, seed=blocks + 1)
+    finally:
+        dl.dl_set_config(armed_blocks=0)
 
 
 def test_armed_requests_back_to_back_with_changing_sources(armed):
