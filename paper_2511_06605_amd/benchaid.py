@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 AID_PATH = os.path.join(_HERE, "libdl_benchaid.so")
 
 OP_BATCH, OP_BROADCAST, OP_ALLGATHER, OP_ALLTOALL, OP_MEMCPY_ASYNC, OP_MEMCPY_BATCH, OP_SWAP, OP_ALLTOALL_INPLACE, OP_TOKEN_DISPATCH, OP_FANOUT = range(10)
-WAIT_STREAM, WAIT_TRIGGER, WAIT_ARM_AND_TRIGGER = 0, 1, 2
+WAIT_STREAM, WAIT_TRIGGER, WAIT_ARM_AND_TRIGGER, WAIT_SIGNAL = 0, 1, 2, 3
 
 
 class Request(ctypes.Structure):

@@ -28,6 +28,7 @@ DL_MAX_FANOUT = 64
 DL_PLAN_FANOUT = 8
 DL_MODE_ONESHOT = 0
 DL_MODE_PRELAUNCH = 1
+DL_MODE_SIGNAL = 2
 
 # every symbol include/dmalatte.h declares
 EXPORTS = [

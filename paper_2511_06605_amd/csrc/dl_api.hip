@@ -282,7 +282,7 @@ int run_in_mode(void *stream, Launch launch)
     hipStream_t hs = (hipStream_t)stream;
     dl_arm arm;
     const dl_arm *armp = nullptr;
-    if (g_dl.mode == DL_MODE_PRELAUNCH) {
+    if (g_dl.mode != DL_MODE_ONESHOT) {
         const int rc = dl_armed_begin(&arm, &hs);
         if (rc != DL_OK) return rc;
         armp = &arm;
@@ -389,8 +389,8 @@ int dl_shutdown(void)
 
 int dl_set_mode(int mode)
 {
-    if (mode != DL_MODE_ONESHOT && mode != DL_MODE_PRELAUNCH) return DL_ERR_INVALID;
-    if (mode == DL_MODE_PRELAUNCH && !dl_armed_ready()) return DL_ERR_STATE;
+    if (mode != DL_MODE_ONESHOT && mode != DL_MODE_PRELAUNCH && mode != DL_MODE_SIGNAL) return DL_ERR_INVALID;
+    if (mode != DL_MODE_ONESHOT && !dl_armed_ready()) return DL_ERR_STATE;
     g_dl.mode = mode;
     return DL_OK;
 }

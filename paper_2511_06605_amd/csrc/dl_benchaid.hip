@@ -91,6 +91,7 @@ int dlb_issue(const dlb_request *r, void *stream)
 // wait_mode 1 (prelaunch): the request is armed and seen resident first (untimed);
 //             clock before dl_trigger() -> dl_wait() returns.
 // wait_mode 2 (prelaunch): clock before the arming call -> dl_trigger() -> dl_wait() returns.
+// wait_mode 3 (signal): clock before the call -> dl_wait() on its ticket returns (no trigger, no stream sync).
 int dlb_time_host(const dlb_request *r, void *stream, int wait_mode, int warmup, int iters, double *us)
 {
     for (int i = -warmup; i < iters; ++i) {
@@ -100,6 +101,9 @@ int dlb_time_host(const dlb_request *r, void *stream, int wait_mode, int warmup,
         if (wait_mode == 0) {
             hipError_t e = hipStreamSynchronize((hipStream_t)stream);
             if (e != hipSuccess) return 1000 + (int)e;
+        } else if (wait_mode == 3) {
+            rc = dl_wait(dl_last_ticket(), 2000000000ull);
+            if (rc) return rc;
         } else {
             const uint64_t t = dl_last_ticket();
             if (wait_mode == 1) {

@@ -84,6 +84,17 @@ __device__ __forceinline__ T dl_ld_sys(const T *p)
 // if the request was cancelled or the limit ran out.  Uniform over the workgroup.
 __device__ __forceinline__ uint32_t dl_arm_wait(const dl_arm &a)
 {
+    if (a.nowait) {  // uniform over the grid: started without a doorbell
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            __hip_atomic_store(a.armed, a.ticket, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            if (a.trace_host) {
+                const uint64_t t = (uint64_t)wall_clock64();
+                __hip_atomic_store(a.trace_host, t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                __hip_atomic_store(a.trace_host + 1, t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            }
+        }
+        return DL_GO_RUN;
+    }
     __shared__ uint32_t s_go;
     if (threadIdx.x == 0) {
         uint32_t go = DL_GO_SKIP;

@@ -54,6 +54,7 @@ struct dl_arm {
     uint64_t margin_ticks;  // extra time a non-polling workgroup grants the polling one
     uint32_t direct;        // 1: every workgroup polls the host doorbell itself
     uint32_t max_spins;     // backstop that does not depend on the clock: give up after this many polls
+    uint32_t nowait;        // 1: no doorbell, copy at once (DL_MODE_SIGNAL); the completion side is unchanged
     // Phase stamps (device wall-clock ticks), null unless tracing is on: host-coherent, 4 words: doorbell seen,
     // first copy begins (the polling workgroup's), last copy ends (the last arriver's), completion issued
     uint64_t *trace_host;

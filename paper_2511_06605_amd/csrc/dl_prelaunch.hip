@@ -98,6 +98,7 @@ int dl_armed_begin(dl_arm *arm, hipStream_t *stream)
     arm->limit_ticks = (uint64_t)g_dl.cfg.arm_timeout_us * g_arm.clock_khz / 1000ull;
     arm->margin_ticks = 5000ull * g_arm.clock_khz / 1000ull;  // 5 ms
     arm->direct = 0;
+    arm->nowait = g_dl.mode == DL_MODE_SIGNAL ? 1u : 0u;
     // a poll takes well over 100 ns (a host-link round trip, or a sleep plus a device-memory load)
     arm->max_spins = (g_dl.cfg.arm_timeout_us + 5000u) * 10u;
     arm->trace_host = g_dl.trace ? g_arm.host->trace[slot] : nullptr;
@@ -149,7 +150,7 @@ int dl_prelaunch_stop(void)
     (void)hipFree(g_arm.dev);
     (void)hipHostFree(g_arm.host);
     g_arm = arm_state{};
-    if (g_dl.mode == DL_MODE_PRELAUNCH) g_dl.mode = DL_MODE_ONESHOT;
+    if (g_dl.mode != DL_MODE_ONESHOT) g_dl.mode = DL_MODE_ONESHOT;
     return DL_OK;
 }
 

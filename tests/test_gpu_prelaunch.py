@@ -348,6 +348,51 @@ def test_armed_requests_back_to_back_with_changing_sources(armed):
     assert int(bad.item()) == 0
 
 
+def test_signal_mode_completes_without_trigger_or_stream_sync(ref):
+    """DL_MODE_SIGNAL: the kernel starts at once; dl_wait on the ticket is the only synchronisation used here
+    between the library's stream and the reads below."""
+    import torch
+    dl.dl_prelaunch_start()
+    dl.dl_set_mode(dl.DL_MODE_SIGNAL)
+    try:
+        for W, B in ((8, 4 * KiB), (8, 300 * KiB + 16), (3, 7001), (13, 5000)):
+            ins = inputs.allgather_inputs(W, B, seed=B)
+            d_in = [DevBuf(B, fill=a) for a in ins]
+            d_out = [DevBuf(W * B) for _ in range(W)]
+            sync()
+            before = dl.dl_last_ticket()
+            dl.dl_allgather([b.ptr() for b in d_in], [b.ptr() for b in d_out], B)
+            assert dl.dl_last_ticket() == before + 1
+            dl.dl_wait()
+            for r, w in zip(d_out, ref.allgather(ins)):
+                assert np.array_equal(r.host(), w) and r.guards_intact()
+        C = inputs.moe_dispatch_chunks(8, 16, seed=4)
+        ins = inputs.alltoall_inputs(C, seed=5, kind="bf16")
+        want = ref.alltoall(ins, C)
+        d_in = [DevBuf(a.size, fill=a) for a in ins]
+        d_out = [DevBuf(w.size) for w in want]
+        sync()
+        dl.dl_alltoall([b.ptr() for b in d_in], [b.ptr() for b in d_out], C)
+        dl.dl_wait()
+        for r, w in zip(d_out, want):
+            assert np.array_equal(r.host(), w) and r.guards_intact()
+        # a request issued in prelaunch mode right after still waits for its doorbell
+        dl.dl_set_mode(dl.DL_MODE_PRELAUNCH)
+        src = DevBuf(4096, fill=inputs.payload(np.random.default_rng(1), 4096))
+        dst = DevBuf(4096)
+        sync()
+        dl.dl_batch_copy([(src.ptr(), dst.ptr(), 4096)])
+        with pytest.raises(dl.DlError) as e:
+            dl.dl_wait(timeout_ns=2_000_000)
+        assert e.value.status == dl.DL_ERR_TIMEOUT
+        assert (dst.host() == CANARY).all()
+        fire()
+        assert np.array_equal(dst.host(), src.host())
+    finally:
+        dl.dl_set_mode(dl.DL_MODE_ONESHOT)
+        dl.dl_prelaunch_stop()
+
+
 def test_untriggered_request_expires_and_copies_nothing(ref):
     dl.dl_set_config(arm_timeout_us=3000)
     try:
