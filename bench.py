@@ -183,10 +183,15 @@ def other_operations(dl, benchaid, inputs, torch, stream, ag_reqs, ag_bufs, ag_s
         nbytes = (W * T + int(dest.sum())) * row_bytes
         row = {"tokens_per_rank": T, "row_bytes": row_bytes, "copies": int(dest.sum()),
                "mean_fanout": float(dest.sum()) / (W * T)}
-        lowered, row["lowering_host_us"] = benchaid.lowered_token_dispatch(req)
-        row["items"] = lowered.req.n
-        row.update(timed(lowered, nbytes, False, calls=10))            # the lowered list alone: device-bound
+        # the whole call: from 512 tokens on only the mask goes to the device, which builds the copy list itself
         row["call_to_sync_host_us"] = lat_stats(benchaid.time_host(req, stream, benchaid.WAIT_STREAM, 10, 100))
+        row["GBps_call_to_sync"] = nbytes / row["call_to_sync_host_us"]["p50"] / 1e3
+        # the same request lowered on the host: the lowering alone, and the whole call with device lowering off
+        lowered, row["host_lowering_us"] = benchaid.lowered_token_dispatch(req)
+        row["items"] = lowered.req.n
+        dl.dl_set_config(device_lowering=0)
+        row["host_lowered_call_to_sync_us"] = lat_stats(benchaid.time_host(req, stream, benchaid.WAIT_STREAM, 10, 100))
+        dl.dl_set_config(device_lowering=1)
         rows.append(row)
     res["token_dispatch_moe"] = rows
 

@@ -239,6 +239,8 @@ typedef struct dl_config {
     uint32_t max_blocks;         /* cap on the one-shot grid; workgroups then stride over the tiles; 0 = one workgroup per tile */
     uint32_t fan_split;          /* sub-groups of a workgroup that share out the destinations of a fused copy: 1, 2 or 4; 0 = choose */
     uint32_t infer_broadcast;    /* 1: dl_batch_copy merges copies that share source and size into read-once/write-k copies; default 1 */
+    uint32_t device_lowering;    /* 1: dl_token_dispatch with 512 tokens or more (W = 8, aligned rows, one-shot mode, validation off) sends only the mask to the device, which derives the copies itself; default 1 */
+    uint32_t reserved;
     uint64_t write_through_max_bytes; /* requests moving at most this many bytes (read + written) use write-through stores; default 144 MiB */
 } dl_config;
 
@@ -277,6 +279,8 @@ int dl_batch_fanout(const dl_plan_item *items, size_t n, void *stream);
  * hold row_bytes times the number of non-zero entries in column j of dest.
  * Lowered to one read-once/write-k copy per token; a token with no destination
  * moves nothing.  tokens: host array of W counts.  1 <= W <= DL_MAX_FANOUT.
+ * The lowering runs on the host, or (dl_config.device_lowering, many tokens) on
+ * the device from the mask alone; the result is the same.
  */
 int dl_token_dispatch(const void *const *in, void *const *out, int W, const uint32_t *tokens, size_t row_bytes,
                       const uint8_t *dest, void *stream);

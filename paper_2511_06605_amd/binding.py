@@ -73,6 +73,8 @@ class Config(ctypes.Structure):
         ("max_blocks", ctypes.c_uint32),
         ("fan_split", ctypes.c_uint32),
         ("infer_broadcast", ctypes.c_uint32),
+        ("device_lowering", ctypes.c_uint32),
+        ("reserved", ctypes.c_uint32),
         ("write_through_max_bytes", ctypes.c_uint64),
     ]
 
@@ -82,7 +84,7 @@ class PlanItem(ctypes.Structure):
         ("src", ctypes.c_void_p),
         ("bytes", ctypes.c_size_t),
         ("k", ctypes.c_uint32),
-        ("infer_broadcast", ctypes.c_uint32),
+        ("reserved", ctypes.c_uint32),
         ("dst", ctypes.c_void_p * DL_PLAN_FANOUT),
     ]
 

@@ -369,6 +369,7 @@ int dl_init(int device)
     g_dl.cfg.arm_timeout_us = 20000;
     g_dl.cfg.fuse_broadcast = 1;
     g_dl.cfg.infer_broadcast = 1;
+    g_dl.cfg.device_lowering = 1;
     const int rc = dl_exec_init();
     if (rc != DL_OK) return rc;
     g_dl.inited = true;
@@ -467,6 +468,12 @@ int dl_batch_fanout(const dl_plan_item *items, size_t n, void *stream)
 int dl_token_dispatch(const void *const *in, void *const *out, int W, const uint32_t *tokens, size_t row_bytes,
                       const uint8_t *dest, void *stream)
 {
+    if (g_dl.inited && g_dl.mode == DL_MODE_ONESHOT && !g_dl.validate && g_dl.cfg.device_lowering) {
+        // many tokens: only the destination mask goes to the device, which works out the rest itself
+        bool taken = false;
+        const int rc = dl_dispatch_on_device(in, out, W, tokens, row_bytes, dest, (hipStream_t)stream, &taken);
+        if (taken || rc != DL_OK) return rc;
+    }
     return lower_and_execute([&](sink &s) { return lower_token_dispatch(in, out, W, tokens, row_bytes, dest, s); },
                              stream);
 }

@@ -1,0 +1,168 @@
+// Token dispatch lowered on the device (Sec. IV-B: a token that goes to several experts is one
+// source with several destinations).  The host-side lowering writes one 88-byte item per token and
+// ships that table over the host link; for thousands of tokens that "control" work (Sec. III-B2) is
+// as long as the copy.  Here only the destination mask (W bytes per token) crosses the link:
+//   1. the mask is copied to device memory,
+//   2. a small kernel builds the item table there, one token per thread: its source row and, for
+//      every rank it goes to, the row it lands on (receive buffers are packed in token order, so
+//      that is an exclusive prefix count per column of the mask),
+//   3. the row kernel for long lists of equal items executes the table.
+#include "dl_device.h"
+#include "dl_internal.h"
+
+#include <string.h>
+
+namespace {
+
+constexpr int DISPATCH_W = 8;            // ranks this path handles: exactly 8 (one 64-bit mask word per token)
+constexpr uint32_t BUILD_THREADS = 256;  // tokens per workgroup of the build kernel
+constexpr uint32_t BUILD_WAVES = BUILD_THREADS / 64;
+
+struct build_args {
+    const char *in[DISPATCH_W];
+    char *out[DISPATCH_W];
+    uint32_t first_token[DISPATCH_W + 1];  // tokens before rank i; entries past W hold the total
+    uint32_t W;
+    uint32_t tokens;  // over all ranks
+    uint64_t row_bytes;
+};
+
+// Workgroup b builds the items of tokens 256 b .. 256 b + 255, one token per thread.  No workgroup
+// waits for another: the rows that earlier tokens took in each receive buffer are counted again by
+// every workgroup straight from the mask (at most a few tens of KiB, from the L2), the rows taken
+// inside the block come from wavefront ballots.
+__global__ void __launch_bounds__(BUILD_THREADS) dl_dispatch_build_kernel(const uint8_t *__restrict__ mask, const build_args a,
+                                                                          dl_fused_item *__restrict__ items)
+{
+    __shared__ uint32_t before_block[BUILD_WAVES][DISPATCH_W];  // per wavefront: set bytes it saw in earlier blocks
+    __shared__ uint32_t in_wave[BUILD_WAVES][DISPATCH_W];       // per wavefront: destinations of its own 64 tokens
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    constexpr uint32_t W = DISPATCH_W;
+    const uint32_t block0 = blockIdx.x * BUILD_THREADS;
+
+    // W is 8 and every mask byte is 0 or 1 (the host wrote it so): a token is one 64-bit word, a 16-byte
+    // load brings two, and adding words adds the eight columns bytewise (a thread adds at most
+    // tokens / 256 < 256 of them).  Several loads are in flight at once.
+    uint64_t acc = 0;
+    const ulonglong2 *pairs = (const ulonglong2 *)mask;
+#pragma unroll 8
+    for (uint32_t v = tid; v < block0 / 2; v += BUILD_THREADS) {
+        const ulonglong2 two = pairs[v];
+        acc += two.x + two.y;
+    }
+#pragma unroll
+    for (int j = 0; j < DISPATCH_W; ++j) {
+        uint32_t x = (uint32_t)(acc >> (8 * j)) & 0xFFu;
+#pragma unroll
+        for (int d = 32; d >= 1; d /= 2) x += __shfl_xor(x, d, 64);
+        if (lane == 0) before_block[wave][j] = x;
+    }
+
+    const uint32_t token = block0 + tid;
+    const bool valid = token < a.tokens;
+    const uint64_t mine = valid ? ((const uint64_t *)mask)[token] : 0ull;
+    bool m[DISPATCH_W];
+    uint32_t pos[DISPATCH_W], k = 0;
+#pragma unroll
+    for (int j = 0; j < DISPATCH_W; ++j) {
+        m[j] = ((mine >> (8 * j)) & 0xFFu) != 0;
+        const uint64_t votes = __ballot(m[j]);
+        pos[j] = (uint32_t)__popcll(votes & ((1ull << lane) - 1ull));  // earlier tokens of this wavefront
+        if (lane == 0) in_wave[wave][j] = (uint32_t)__popcll(votes);
+        k += m[j] ? 1u : 0u;
+    }
+    __syncthreads();
+    if (!valid) return;
+#pragma unroll
+    for (int j = 0; j < DISPATCH_W; ++j) {
+#pragma unroll
+        for (uint32_t w = 0; w < BUILD_WAVES; ++w) pos[j] += before_block[w][j] + (w < wave ? in_wave[w][j] : 0u);
+    }
+
+    // the token's rank is the last one that starts at or before it; its send buffer and first token are
+    // picked by compares against kernel arguments (no load depends on the token)
+    const char *base = a.in[0];
+    uint32_t first = 0;
+#pragma unroll
+    for (int r = 1; r < DISPATCH_W; ++r)
+        if ((uint32_t)r < W && a.first_token[r] <= token) {
+            base = a.in[r];
+            first = a.first_token[r];
+        }
+    dl_fused_item it;
+    it.src = base + (uint64_t)(token - first) * a.row_bytes;
+    it.bytes = a.row_bytes;
+    it.k = k;
+    it.pad = 0;
+#pragma unroll
+    for (int s = 0; s < DL_FAN; ++s) it.dst[s] = nullptr;
+    // destination number d (in rank order) goes to sub-group d / per, slot 2 (d / per) + d % per,
+    // per = ceil(k / 4) being 1 or 2: slot 2 d or slot d
+    const uint32_t per = (k + 3u) >> 2;
+    uint32_t d = 0;
+#pragma unroll
+    for (int j = 0; j < DISPATCH_W; ++j) {
+        if (m[j]) {
+            char *p = a.out[j] + (uint64_t)pos[j] * a.row_bytes;
+            const uint32_t slot = per == 1 ? 2u * d : d;
+#pragma unroll
+            for (int s = 0; s < DL_FAN; ++s)
+                if ((uint32_t)s == slot) it.dst[s] = p;
+            ++d;
+        }
+    }
+    items[token] = it;
+}
+
+}  // namespace
+
+int dl_dispatch_on_device(const void *const *in, void *const *out, int W, const uint32_t *tokens, size_t row_bytes,
+                          const uint8_t *dest, hipStream_t stream, bool *taken)
+{
+    *taken = false;
+    const dl_config &c = g_dl.cfg;
+    if (W != DISPATCH_W || !in || !out || !tokens || !dest) return DL_OK;
+    if (c.tile_bytes || c.block_threads || c.max_blocks || (c.fan_split != 0 && c.fan_split != 4)) return DL_OK;
+    if (row_bytes == 0 || (row_bytes & 15u)) return DL_OK;
+    uint64_t total = 0;
+    for (int i = 0; i < W; ++i) {
+        total += tokens[i];
+        if (((uint64_t)in[i] | (uint64_t)out[i]) & 15u) return DL_OK;
+        if ((tokens[i] && !in[i]) || !out[i]) return DL_OK;  // the host lowering reports what is wrong
+    }
+    // worth three small launches only for many tokens; mask and item table share one ring slot;
+    // the build kernel's bytewise column sums hold up to 255 tokens per thread
+    const uint64_t mask_bytes = (total * (uint64_t)W + 255u) & ~(uint64_t)255u;
+    if (total < 512 || total >= 255u * BUILD_THREADS ||
+        mask_bytes + total * sizeof(dl_fused_item) > DL_RING_SLOT_BYTES)
+        return DL_OK;
+
+    size_t slot;
+    char *host, *dev;
+    int rc = dl_ring_acquire(&slot, &host, &dev);
+    if (rc != DL_OK) return rc;
+    *taken = true;
+    for (size_t b = 0; b < total * (size_t)W; ++b) host[b] = dest[b] != 0;  // the device adds these bytes
+    rc = dl_ring_stage(slot, mask_bytes, stream);
+    if (rc != DL_OK) return rc;
+
+    build_args a;
+    uint32_t first = 0;
+    for (int i = 0; i < DISPATCH_W; ++i) {
+        a.in[i] = i < W ? (const char *)in[i] : nullptr;
+        a.out[i] = i < W ? (char *)out[i] : nullptr;
+        a.first_token[i] = first;
+        if (i < W) first += tokens[i];
+    }
+    a.first_token[DISPATCH_W] = first;
+    a.W = (uint32_t)W;
+    a.tokens = (uint32_t)total;
+    a.row_bytes = row_bytes;
+    dl_fused_item *items = (dl_fused_item *)(dev + mask_bytes);
+    hipLaunchKernelGGL(dl_dispatch_build_kernel, dim3((uint32_t)((total + BUILD_THREADS - 1) / BUILD_THREADS)),
+                       dim3(BUILD_THREADS), 0, stream, (const uint8_t *)dev, a, items);
+    DL_HIP(hipGetLastError());
+    rc = dl_launch_fused_rows_table(items, (uint32_t)total, row_bytes, stream);
+    if (rc != DL_OK) return rc;
+    return dl_ring_release(slot, stream);
+}

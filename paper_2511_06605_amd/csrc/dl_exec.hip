@@ -246,7 +246,7 @@ constexpr uint64_t TABLE_ENTRIES_TARGET = 8192;  // table kernels: aim for at mo
 constexpr uint64_t UNIFORM_ROWS_MIN_BYTES = 4ull << 20;  // source bytes from which a uniform long list takes the row kernel
 constexpr size_t TABLE_STAGE_MIN = 512;          // tables at least this long are staged in device memory first
 constexpr size_t RING_SLOTS = 4;
-constexpr size_t RING_SLOT_BYTES = 1u << 20;
+constexpr size_t RING_SLOT_BYTES = DL_RING_SLOT_BYTES;
 
 struct ring_t {
     char *base = nullptr;  // pinned host memory: the host writes tables here
@@ -625,6 +625,41 @@ int dl_exec_fused(const dl_fused_item *items, size_t n, hipStream_t stream, cons
 int dl_exec_swap(const dl_swap_item *items, size_t n, hipStream_t stream, const dl_arm *arm, bool *launched)
 {
     return exec_list(items, n, stream, arm, launched);
+}
+
+int dl_launch_fused_rows_table(const dl_fused_item *dev_items, uint32_t n, uint64_t item_bytes, hipStream_t stream)
+{
+    // the table's destinations are laid out for four sub-groups (see slots_by_subgroup)
+    const uint32_t split = 4, tile = 4096u / split;
+    const uint64_t tpi = (item_bytes + tile - 1) / tile;
+    if (n == 0 || tpi * n >= (1ull << 30)) return DL_ERR_INVALID;
+    const dl_launch_shape sh = dl_choose_shape((uint64_t)n * item_bytes, item_bytes, 8);
+    with_policy(sh.policy, [&](auto pol) {
+        hipLaunchKernelGGL((dl_exec_urows_kernel<dl_fused_item, decltype(pol)::value>), dim3((uint32_t)(tpi * n)),
+                           dim3(256), 0, stream, dev_items, n, (uint32_t)tpi, log2u(4u / split), log2u(split));
+    });
+    DL_HIP(hipGetLastError());
+    return DL_OK;
+}
+
+int dl_ring_acquire(size_t *slot, char **host, char **dev)
+{
+    if (!g_ring.base) return DL_ERR_STATE;
+    const size_t s = g_ring.next++ % RING_SLOTS;
+    if (g_ring.used[s]) DL_HIP(hipEventSynchronize(g_ring.ev[s]));
+    *slot = s;
+    *host = g_ring.base + s * RING_SLOT_BYTES;
+    *dev = g_ring.dev + s * RING_SLOT_BYTES;
+    return DL_OK;
+}
+
+int dl_ring_stage(size_t slot, uint64_t bytes, hipStream_t stream) { return stage_slot(slot, bytes, stream); }
+
+int dl_ring_release(size_t slot, hipStream_t stream)
+{
+    DL_HIP(hipEventRecord(g_ring.ev[slot], stream));
+    g_ring.used[slot] = true;
+    return DL_OK;
 }
 
 int dl_exec_init()

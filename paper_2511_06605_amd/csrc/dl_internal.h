@@ -74,6 +74,25 @@ int dl_exec_init();
 int dl_exec_shutdown();
 dl_launch_shape dl_choose_shape(uint64_t src_bytes, uint64_t max_item_bytes, uint32_t max_k);
 
+// dl_exec.hip: the staging ring (pinned host slots of DL_RING_SLOT_BYTES, each with a device mirror).
+//   dl_ring_acquire  waits until the next slot's previous user has finished on the device
+//   dl_ring_stage    enqueues a copy of the first `bytes` (a multiple of 16) of the host slot to its mirror
+//   dl_ring_release  marks the slot as in use until everything enqueued on `stream` so far has finished
+constexpr size_t DL_RING_SLOT_BYTES = 1u << 20;
+int dl_ring_acquire(size_t *slot, char **host, char **dev);
+int dl_ring_stage(size_t slot, uint64_t bytes, hipStream_t stream);
+int dl_ring_release(size_t slot, hipStream_t stream);
+
+// dl_exec.hip: the row kernel over a table of n equally sized read-once/write-k items that is already in
+// device memory, destinations laid out for four sub-groups (sub-group g owns slots 2g and 2g + 1).
+int dl_launch_fused_rows_table(const dl_fused_item *dev_items, uint32_t n, uint64_t item_bytes, hipStream_t stream);
+
+// dl_dispatch.hip: token dispatch lowered on the device (the destination mask is scanned into a table of
+// read-once/write-k items in device memory, which the row kernel then executes).  *taken says whether the request qualified; if not,
+// nothing was enqueued and the caller lowers on the host.
+int dl_dispatch_on_device(const void *const *in, void *const *out, int W, const uint32_t *tokens, size_t row_bytes,
+                          const uint8_t *dest, hipStream_t stream, bool *taken);
+
 // dl_prelaunch.hip: tickets, doorbell and completion words of armed requests.
 bool dl_armed_ready();
 int dl_armed_begin(dl_arm *arm, hipStream_t *stream);  // next ticket's words; picks the library stream if *stream is null

@@ -324,6 +324,18 @@ def test_token_dispatch_ragged(ref, W, counts, row, drop):
     run_token_dispatch(ref, W, counts, row, seed=W * 7 + row, drop=drop, experts=16 * W, top_k=min(8, W))
 
 
+@pytest.mark.parametrize("device_lowering", [0, 1])
+@pytest.mark.parametrize("W,counts,row,drop", [(8, 100, 14336, None), (8, [300, 0, 5, 700, 64, 0, 1, 90], 1040, 3),
+                                               (3, [400, 1, 200], 48, 5), (1, [600], 4096, 4),
+                                               (5, [0, 0, 513, 0, 0], 2048 + 16, None), (8, 2000, 256, 7)])
+def test_token_dispatch_lowered_on_device_and_on_host(ref, cfg, device_lowering, W, counts, row, drop):
+    """512 tokens or more with aligned rows take the device-side lowering (mask copied over, scanned by one
+    workgroup, rows addressed from the scan); the host lowering of the same request must give the same
+    bytes.  Empty ranks, tokens without destination, fewer than 8 ranks, rows shorter than one tile."""
+    cfg(device_lowering=device_lowering)
+    run_token_dispatch(ref, W, counts, row, seed=W + row, drop=drop, experts=32 * W, top_k=min(8, W))
+
+
 def test_token_dispatch_skewed_experts(ref):
     run_token_dispatch(ref, 8, 128, 14336, seed=21, kind="bf16", skew=0.3)
 

@@ -47,6 +47,18 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(L, name), name
 
 
+def test_binding_structs_have_the_layout_of_the_header():
+    """Sizes and offsets the C side asserts or implies: a mismatch here silently corrupts every call."""
+    assert ctypes.sizeof(binding.PlanItem) == 88 and binding.PlanItem.dst.offset == 24
+    assert ctypes.sizeof(binding.CopyDesc) == 24 and ctypes.sizeof(binding.SwapDesc) == 24
+    assert ctypes.sizeof(binding.Trace) == 32
+    assert ctypes.sizeof(binding.Config) == 56 and binding.Config.write_through_max_bytes.offset == 48
+    header = open(os.path.join(ROOT, "include", "dmalatte.h")).read()
+    body = header[header.index("typedef struct dl_config {"):header.index("} dl_config;")]
+    names = re.findall(r"^\s*uint(?:32|64)_t\s+(\w+);", body, flags=re.M)
+    assert names == [f[0] for f in binding.Config._fields_]
+
+
 def test_strerror_and_state_without_gpu():
     assert dl.binding.strerror(dl.DL_OK) == "ok"
     assert "overlap" in dl.binding.strerror(dl.DL_ERR_OVERLAP)
