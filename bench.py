@@ -33,7 +33,7 @@ HBM_PEAK_GBS = 8000.0
 # for a plain copy of known size.  Valid only for the kernel sources whose digest is given; with
 # any other sources the figure is reported as null until the counters are taken again.
 KERNEL_SOURCES = ["dl_work.h", "dl_device.h", "dl_exec.hip"]
-MEASURED_TRAFFIC = {"sources_sha256": "8f3fd50af5b5986c464fcc7ff176610b87fc233d8889a91cafba5aea65df3e19", "bytes_per_rank": 64 * MiB, "bytes_per_launch": 4831886319}
+MEASURED_TRAFFIC = {"sources_sha256": "6247dc86c21d343ce15fa4b3014704618d9a66022029dda75d77a4ced35b0141", "bytes_per_rank": 64 * MiB, "bytes_per_launch": 4831886463}
 
 
 def kernel_sources_digest() -> str:
@@ -316,7 +316,7 @@ def main() -> int:
                          "token-granular MoE dispatch, for kernel traces")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU (W virtual ranks share its HBM); --gpus must be 1",
+        print("bench.py: this library runs on one GPU (W virtual ranks share its HBM); --gpus must be 1",
               file=sys.stderr)
         return 2
 
@@ -404,7 +404,7 @@ def main() -> int:
                                                                           calls=50 if B <= MiB else 10)}
             row["GBps"] = ag_bytes(B) / row["device_us"] / 1e3
             if B <= 4 * MiB:
-                lat = benchaid.time_host(reqs[B], stream, benchaid.WAIT_STREAM, warmup=50, iters=500)
+                lat = benchaid.time_host(reqs[B], stream, benchaid.WAIT_STREAM, warmup=50, iters=1000)
                 row["oneshot_host_us"] = lat_stats(lat)
             detail["allgather"].append(row)
         # prelaunch mode: the request is armed ahead of time; timed from the doorbell write to the
@@ -415,13 +415,13 @@ def main() -> int:
             B = row["bytes_per_rank"]
             if B > 4 * MiB:
                 continue
-            lat = benchaid.time_host(reqs[B], None, benchaid.WAIT_TRIGGER, warmup=50, iters=500)
+            lat = benchaid.time_host(reqs[B], None, benchaid.WAIT_TRIGGER, warmup=50, iters=1000)
             row["prelaunch_trigger_to_done_us"] = lat_stats(lat)
-            lat = benchaid.time_host(reqs[B], None, benchaid.WAIT_ARM_AND_TRIGGER, warmup=50, iters=500)
+            lat = benchaid.time_host(reqs[B], None, benchaid.WAIT_ARM_AND_TRIGGER, warmup=50, iters=1000)
             row["prelaunch_arm_to_done_us"] = lat_stats(lat)
             # signal mode: an ordinary launch whose completion word the host watches instead of synchronising the stream
             dl.dl_set_mode(dl.DL_MODE_SIGNAL)
-            lat = benchaid.time_host(reqs[B], None, benchaid.WAIT_SIGNAL, warmup=50, iters=500)
+            lat = benchaid.time_host(reqs[B], None, benchaid.WAIT_SIGNAL, warmup=50, iters=1000)
             row["signal_call_to_done_us"] = lat_stats(lat)
             dl.dl_set_mode(dl.DL_MODE_PRELAUNCH)
         # phase breakdown (the form of the paper's Fig. 4: one transfer split into control / schedule / copy / sync,

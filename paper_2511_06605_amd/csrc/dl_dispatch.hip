@@ -96,15 +96,16 @@ __global__ void __launch_bounds__(BUILD_THREADS) dl_dispatch_build_kernel(const 
     it.pad = 0;
 #pragma unroll
     for (int s = 0; s < DL_FAN; ++s) it.dst[s] = nullptr;
-    // destination number d (in rank order) goes to sub-group d / per, slot 2 (d / per) + d % per,
-    // per = ceil(k / 4) being 1 or 2: slot 2 d or slot d
-    const uint32_t per = (k + 3u) >> 2;
+    // destination number d (in rank order) goes to sub-group d / per (0 or 1), slot 4 (d / per) + d % per,
+    // per = ceil(k / 2): the layout of slots_by_subgroup for DL_TABLE_ROWS_SPLIT sub-groups
+    static_assert(DL_TABLE_ROWS_SPLIT == 2 && DL_FAN == 8, "slot layout below is written for two sub-groups of four");
+    const uint32_t per = (k + 1u) >> 1;
     uint32_t d = 0;
 #pragma unroll
     for (int j = 0; j < DISPATCH_W; ++j) {
         if (m[j]) {
             char *p = a.out[j] + (uint64_t)pos[j] * a.row_bytes;
-            const uint32_t slot = per == 1 ? 2u * d : d;
+            const uint32_t slot = d >= per ? 4u + d - per : d;
 #pragma unroll
             for (int s = 0; s < DL_FAN; ++s)
                 if ((uint32_t)s == slot) it.dst[s] = p;
@@ -122,7 +123,7 @@ int dl_dispatch_on_device(const void *const *in, void *const *out, int W, const 
     *taken = false;
     const dl_config &c = g_dl.cfg;
     if (W != DISPATCH_W || !in || !out || !tokens || !dest) return DL_OK;
-    if (c.tile_bytes || c.block_threads || c.max_blocks || (c.fan_split != 0 && c.fan_split != 4)) return DL_OK;
+    if (c.tile_bytes || c.block_threads || c.max_blocks || (c.fan_split != 0 && c.fan_split != DL_TABLE_ROWS_SPLIT)) return DL_OK;
     if (row_bytes == 0 || (row_bytes & 15u)) return DL_OK;
     uint64_t total = 0;
     for (int i = 0; i < W; ++i) {

@@ -74,12 +74,6 @@ __global__ void __launch_bounds__(512) dl_exec_table_kernel(const Item *__restri
 
 enum : uint32_t { DL_GO_WAIT = 0, DL_GO_RUN = 1, DL_GO_SKIP = 2 };
 
-template <typename T>
-__device__ __forceinline__ T dl_ld_sys(const T *p)
-{
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-}
-
 // Returns DL_GO_RUN once the doorbell has been rung for this ticket, DL_GO_SKIP
 // if the request was cancelled or the limit ran out.  Uniform over the workgroup.
 __device__ __forceinline__ uint32_t dl_arm_wait(const dl_arm &a)
@@ -104,8 +98,10 @@ __device__ __forceinline__ uint32_t dl_arm_wait(const dl_arm &a)
         if (a.direct || blockIdx.x == 0) {
             // poll the host doorbell (uncached system-scope loads over the host link)
             for (uint32_t spins = 1;; ++spins) {
-                const uint64_t cancel = dl_ld_sys(a.bell + 1);
-                const uint64_t bell = dl_ld_sys(a.bell);
+                // doorbell and cancel word sit side by side in one aligned 16 bytes: one read over the link
+                const dl_u32x4 w = dl_ld<DL_POL_COHERENT>(dl_global<dl_u32x4>(a.bell));
+                const uint64_t bell = (uint64_t)w.x | ((uint64_t)w.y << 32);
+                const uint64_t cancel = (uint64_t)w.z | ((uint64_t)w.w << 32);
                 if (cancel >= a.ticket) break;
                 if (bell >= a.ticket) {
                     go = DL_GO_RUN;
@@ -167,7 +163,8 @@ __device__ __forceinline__ void dl_arm_finish(const dl_arm &a, uint32_t go)
     __syncthreads();
     if (threadIdx.x == 0) {
         const uint32_t grid = gridDim.x;
-        const uint32_t groups = grid < DL_ARM_GROUPS ? grid : DL_ARM_GROUPS;
+        const bool flat = grid <= DL_ARM_FLAT_MAX;  // few enough to count at one word without queueing there
+        const uint32_t groups = flat ? grid : DL_ARM_GROUPS;
         const uint32_t g = blockIdx.x % DL_ARM_GROUPS;
         const uint32_t gsize = (grid - g + DL_ARM_GROUPS - 1) / DL_ARM_GROUPS;
         uint32_t *gcount = (uint32_t *)((char *)a.arrive + g * DL_ARM_STRIDE);
@@ -177,7 +174,7 @@ __device__ __forceinline__ void dl_arm_finish(const dl_arm &a, uint32_t go)
         const uint64_t t_end = a.trace_host ? (uint64_t)wall_clock64() : 0ull;
         uint32_t add = 1u + (go == DL_GO_RUN ? 0u : 0x10000u);
         uint32_t old;
-        if (grid > DL_ARM_GROUPS) {
+        if (!flat) {
             old = __hip_atomic_fetch_add(gcount, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if ((old & 0xFFFFu) != gsize - 1u) return;
             // last of the group: leave the counter at zero for the slot's next request (the reset has
@@ -186,7 +183,7 @@ __device__ __forceinline__ void dl_arm_finish(const dl_arm &a, uint32_t go)
             dl_drain_stores();
             add = 1u + (((old >> 16) + (add >> 16)) << 16);
         }
-        // a grid of at most DL_ARM_GROUPS workgroups has one workgroup per group: counted at the top directly
+        // a small grid is counted at the top directly
         old = __hip_atomic_fetch_add(top, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if ((old & 0xFFFFu) != groups - 1u) return;
         // last of all
@@ -391,7 +388,16 @@ template <class Item>
 bool launch_uniform_rows(const Item *items, size_t n, const dl_launch_shape &sh, hipStream_t stream, int *rc)
 {
     const dl_config &c = g_dl.cfg;
-    if (c.tile_bytes || c.block_threads || sh.max_blocks) return false;
+    if (c.tile_bytes || sh.max_blocks) return false;
+    // Read-once/write-k items with a mix of fan-outs (token rows: 1 to 8 destinations, 5.3 on average) go
+    // fastest with two wavefronts per 1 KiB row, each storing to up to four destinations, in workgroups of
+    // just those two: 5-20 % faster over mean fan-outs 1.9 .. 8 than four wavefronts with two stores each,
+    // of which the ones without a destination are dead weight at the rate wavefronts can be started.
+    const bool fused = std::is_same<Item, dl_fused_item>::value;
+    const uint32_t split = c.fan_split ? sh.split : fused ? DL_TABLE_ROWS_SPLIT : 1u;
+    const uint32_t threads = c.block_threads ? c.block_threads : fused && !c.fan_split ? DL_TABLE_ROWS_THREADS : 256u;
+    if (threads > 512u || threads % (64u * split) || ((threads / 64u / split) & (threads / 64u / split - 1u)))
+        return false;  // whole sub-groups of a power-of-two number of wavefronts
     if (n * sizeof(Item) > RING_SLOT_BYTES) return false;
     const uint64_t bytes = items[0].bytes;
     uint32_t kmax = 1;
@@ -400,7 +406,7 @@ bool launch_uniform_rows(const Item *items, size_t n, const dl_launch_shape &sh,
         if (item_k(items[i]) > kmax) kmax = item_k(items[i]);
     }
     if (bytes * n < UNIFORM_ROWS_MIN_BYTES) return false;
-    const uint32_t split = sh.split, tile = 4096u / split;  // 256 threads: one 1 KiB row per wavefront of a sub-group
+    const uint32_t tile = 16u * threads / split;  // one 1 KiB row per wavefront of a sub-group
     const uint64_t tpi = (bytes + tile - 1) / tile;
     if (tpi * n >= (1ull << 30)) return false;
 
@@ -422,8 +428,8 @@ bool launch_uniform_rows(const Item *items, size_t n, const dl_launch_shape &sh,
     if (*rc != DL_OK) return true;
     const Item *dslot = (const Item *)(g_ring.dev + s * RING_SLOT_BYTES);
     with_policy(sh.policy, [&](auto pol) {
-        hipLaunchKernelGGL((dl_exec_urows_kernel<Item, decltype(pol)::value>), dim3((uint32_t)(tpi * n)), dim3(256), 0,
-                           stream, dslot, (uint32_t)n, (uint32_t)tpi, log2u(4u / split), log2u(split));
+        hipLaunchKernelGGL((dl_exec_urows_kernel<Item, decltype(pol)::value>), dim3((uint32_t)(tpi * n)), dim3(threads), 0,
+                           stream, dslot, (uint32_t)n, (uint32_t)tpi, log2u(threads / 64u / split), log2u(split));
     });
     hipError_t e = hipGetLastError();
     if (e == hipSuccess) e = hipEventRecord(g_ring.ev[s], stream);
@@ -540,6 +546,19 @@ int exec_list(const Item *items, size_t n, hipStream_t stream, const dl_arm *arm
         sh.tile_bytes = 4096;
         sh.block_threads = biggest >= 4096 ? 256u : sh.block_threads;
         sh.split = 1;
+        // Up to ARMED_DIRECT_MAX workgroups see the doorbell themselves (all-gather: 5.0-5.2 us up to 16 KiB per
+        // rank; 32 or 64 pollers took 7 and 9.5 us, the fan-out through device flags 6.5).  A request too long for
+        // that takes eight wavefronts per workgroup where that cuts the number of workgroups: more of them stay
+        // below the limit, and above it arrivals and passes over a capped grid halve (1 MiB per rank: 17.1 -> 14.6 us).
+        uint64_t t4 = 0, t8 = 0;
+        for (size_t i = 0; i < n; ++i) {
+            t4 += dl_item_tiles(items[i], 4096);
+            t8 += dl_item_tiles(items[i], 8192);
+        }
+        if (sh.block_threads == 256u && t4 > ARMED_DIRECT_MAX && 3u * t8 <= 2u * t4) {
+            sh.tile_bytes = 8192;
+            sh.block_threads = 512;
+        }
     }
 
     constexpr int NBIG = list_cap<Item>::big;
@@ -629,14 +648,15 @@ int dl_exec_swap(const dl_swap_item *items, size_t n, hipStream_t stream, const 
 
 int dl_launch_fused_rows_table(const dl_fused_item *dev_items, uint32_t n, uint64_t item_bytes, hipStream_t stream)
 {
-    // the table's destinations are laid out for four sub-groups (see slots_by_subgroup)
-    const uint32_t split = 4, tile = 4096u / split;
+    // the table's destinations are laid out for DL_TABLE_ROWS_SPLIT sub-groups (see slots_by_subgroup)
+    const uint32_t split = DL_TABLE_ROWS_SPLIT, threads = DL_TABLE_ROWS_THREADS, tile = 16u * threads / split;
     const uint64_t tpi = (item_bytes + tile - 1) / tile;
     if (n == 0 || tpi * n >= (1ull << 30)) return DL_ERR_INVALID;
     const dl_launch_shape sh = dl_choose_shape((uint64_t)n * item_bytes, item_bytes, 8);
     with_policy(sh.policy, [&](auto pol) {
         hipLaunchKernelGGL((dl_exec_urows_kernel<dl_fused_item, decltype(pol)::value>), dim3((uint32_t)(tpi * n)),
-                           dim3(256), 0, stream, dev_items, n, (uint32_t)tpi, log2u(4u / split), log2u(split));
+                           dim3(threads), 0, stream, dev_items, n, (uint32_t)tpi, log2u(threads / 64u / split),
+                           log2u(split));
     });
     DL_HIP(hipGetLastError());
     return DL_OK;

@@ -60,6 +60,7 @@ struct dl_arm {
     uint64_t *trace_host;
 };
 constexpr uint32_t DL_ARM_GROUPS = 16;  // workgroup b belongs to group b % DL_ARM_GROUPS
+constexpr uint32_t DL_ARM_FLAT_MAX = 64;  // grids up to this size count their arrivals at one word (0.5 us less than two levels; 256 arrivals at one word: 1.3 us more)
 constexpr uint32_t DL_ARM_STRIDE = 4352;  // flags and counters sit 4 KiB + 256 B apart: separate lines and memory channels
 constexpr uint64_t DL_DONE_SKIPPED = 1ull << 63;  // set in the completion word when nothing was copied
 
@@ -73,6 +74,11 @@ int dl_exec_swap(const dl_swap_item *items, size_t n, hipStream_t stream, const 
 int dl_exec_init();
 int dl_exec_shutdown();
 dl_launch_shape dl_choose_shape(uint64_t src_bytes, uint64_t max_item_bytes, uint32_t max_k);
+
+// Shape of the row kernel over a table of read-once/write-k items in device memory: sub-groups per
+// 1 KiB row (each stores to DL_FAN / split destinations) and threads per workgroup.
+constexpr uint32_t DL_TABLE_ROWS_SPLIT = 2;
+constexpr uint32_t DL_TABLE_ROWS_THREADS = 128;
 
 // dl_exec.hip: the staging ring (pinned host slots of DL_RING_SLOT_BYTES, each with a device mirror).
 //   dl_ring_acquire  waits until the next slot's previous user has finished on the device

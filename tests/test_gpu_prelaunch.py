@@ -72,7 +72,7 @@ def test_allgather_config0(ref, armed):
     allgather_case(ref, 8, 64 * KiB, seed=0)
 
 
-@pytest.mark.parametrize("B", [1, 17, 4096, 4097, 256 * KiB + 5, 16 * MiB])
+@pytest.mark.parametrize("B", [1, 17, 4096, 4097, 8192, 8192 - 16, 8192 + 16, 256 * KiB + 5, 16 * MiB])
 def test_allgather_sizes(ref, armed, B):
     allgather_case(ref, 8, B, seed=B, kind="bf16" if B % 2 == 0 else "u8")
 
