@@ -138,6 +138,45 @@ def b2b_batch(n: int, copy_bytes: int, arena_bytes: int, seed: int, align: int =
     return arena, out
 
 
+def mixed_batch(n: int, max_bytes: int, arena_bytes: int, seed: int, shared_sources: float = 0.0):
+    """n independent copies of unequal sizes and alignments inside one arena.
+
+    Sizes are log-uniform in [1, max_bytes] (one in ten is 0); source and
+    destination offsets are multiples of 1, 4, 16 or 256 drawn per copy and
+    per side, so one list mixes every element width, with heads and tails.
+    With probability ``shared_sources`` a copy reuses the previous copy's
+    source and size (what a fan-out looks like when handed over as plain
+    copies).  Same return value and the same disjointness as ``b2b_batch``.
+    """
+    rng = np.random.default_rng(seed)
+    arena = rng.integers(0, 256, arena_bytes, dtype=np.uint8)
+    srcs: list[tuple[int, int]] = []
+    dsts: list[tuple[int, int]] = []
+
+    def hits(a0, a1, ranges):
+        return a1 > a0 and any(a0 < b1 and b0 < a1 for b0, b1 in ranges)
+
+    out = np.zeros((n, 3), dtype=np.uint64)
+    i = 0
+    while i < n:
+        if i and rng.random() < shared_sources:
+            s, nb = int(out[i - 1][0]), int(out[i - 1][2])
+        else:
+            nb = 0 if rng.random() < 0.1 else int(np.exp(rng.uniform(0.0, np.log(max_bytes))))
+            sa = int(rng.choice([1, 4, 16, 256]))
+            s = int(rng.integers(0, (arena_bytes - nb) // sa + 1)) * sa
+        da = int(rng.choice([1, 4, 16, 256]))
+        d = int(rng.integers(0, (arena_bytes - nb) // da + 1)) * da
+        sr, dr = (s, s + nb), (d, d + nb)
+        if hits(*dr, dsts) or hits(*dr, srcs) or hits(*sr, dsts) or hits(*dr, [sr]):
+            continue
+        srcs.append(sr)
+        dsts.append(dr)
+        out[i] = (s, d, nb)
+        i += 1
+    return arena, out
+
+
 def swap_batch(n: int, swap_bytes: int, arena_bytes: int, seed: int, align: int = 256):
     """n independent swaps inside one arena.
 

@@ -281,6 +281,20 @@ def test_batch_shapes(ref, n, nb, arena, align):
     run_batch(ref, n, nb, arena, seed=n, align=align)
 
 
+@pytest.mark.parametrize("n,max_bytes,shared", [(7, 3000, 0.0), (40, 200000, 0.0), (64, 70000, 0.5), (300, 40000, 0.3),
+                                                (2000, 9000, 0.0)])
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_batch_of_unequal_sizes_and_alignments(ref, n, max_bytes, shared, seed):
+    """One list mixing 16-, 4- and 1-byte element paths, heads, tails, empty copies and shared sources."""
+    arena, descs = inputs.mixed_batch(n, max_bytes, 48 * MiB, seed=1000 * seed + n, shared_sources=shared)
+    want = ref.batch_copy([arena.copy()], [(0, s, 0, d, nb) for s, d, nb in descs])[0]
+    d = DevBuf(arena.size, fill=arena)
+    dl.dl_batch_copy([(d.ptr(int(s)), d.ptr(int(t)), int(nb)) for s, t, nb in descs], stream())
+    sync()
+    assert np.array_equal(d.host(), want)
+    assert d.guards_intact()
+
+
 def test_batch_long_list_with_large_items(ref, cfg):
     """More copies than the argument list holds, each several tiles long."""
     cfg(tile_bytes=4096)

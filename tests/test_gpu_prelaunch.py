@@ -150,6 +150,17 @@ def test_batch(ref, armed, n, nb, arena, align):
     assert np.array_equal(d.host(), want) and d.guards_intact()
 
 
+@pytest.mark.parametrize("n,max_bytes,shared", [(7, 3000, 0.0), (40, 200000, 0.0), (64, 70000, 0.5), (300, 40000, 0.3)])
+def test_batch_of_unequal_sizes_and_alignments_armed(ref, armed, n, max_bytes, shared):
+    a, descs = inputs.mixed_batch(n, max_bytes, 48 * MiB, seed=n, shared_sources=shared)
+    want = ref.batch_copy([a.copy()], [(0, s, 0, d, m) for s, d, m in descs])[0]
+    d = DevBuf(a.size, fill=a)
+    sync()
+    dl.dl_batch_copy([(d.ptr(int(s)), d.ptr(int(t)), int(m)) for s, t, m in descs])
+    fire()
+    assert np.array_equal(d.host(), want) and d.guards_intact()
+
+
 @pytest.mark.parametrize("W,c", [(8, 64 * KiB), (8, 1000), (3, 300 * KiB + 16), (13, 5001)])
 def test_alltoall_inplace_armed(ref, armed, W, c):
     bufs = inputs.alltoall_inputs(inputs.uniform_chunks(W, c), seed=W + c, kind="fp16" if c % 2 == 0 else "u8")

@@ -164,6 +164,23 @@ def test_batch_lowering_drops_empty_and_identical(ref):
     assert np.array_equal(work, want)
 
 
+@pytest.mark.parametrize("n,max_bytes,shared", [(7, 3000, 0.0), (64, 70000, 0.5), (500, 9000, 0.3)])
+def test_batch_lowering_of_unequal_copies_with_and_without_inference(ref, n, max_bytes, shared):
+    arena, descs = inputs.mixed_batch(n, max_bytes, 8 * 1024 * 1024, seed=n, shared_sources=shared)
+    want = ref.batch_copy([arena.copy()], [(0, s, 0, d, m) for s, d, m in descs])[0]
+    live = sum(1 for s, d, m in descs if m and s != d)
+    for plan in (dl.dl_plan_batch, dl.dl_plan_batch_inferred):
+        work = arena.copy()
+        items = plan([(addr(work, int(s)), addr(work, int(d)), int(m)) for s, d, m in descs])
+        assert sum(len(it["dst"]) for it in items) == live     # every live copy appears exactly once
+        if plan is dl.dl_plan_batch:
+            assert len(items) == live
+        elif shared:
+            assert len(items) < live                            # copies of one source were merged
+        replay(items)
+        assert np.array_equal(work, want)
+
+
 def test_invalid_arguments():
     a = np.zeros(64, dtype=np.uint8)
     with pytest.raises(dl.DlError) as e:

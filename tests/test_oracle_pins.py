@@ -234,6 +234,17 @@ def test_hazard_rule(ref):
     assert np.array_equal(same, buf)
 
 
+@pytest.mark.parametrize("n,max_bytes,shared", [(7, 3000, 0.0), (64, 70000, 0.5), (500, 9000, 0.2)])
+def test_batch_of_unequal_sizes_matches_slice_assignment(ref, n, max_bytes, shared):
+    arena, descs = inputs.mixed_batch(n, max_bytes, 8 * 1024 * 1024, seed=n, shared_sources=shared)
+    assert ref.first_hazard([arena], [(0, s, 0, d, m) for s, d, m in descs]) == -1
+    want = arena.copy()
+    for s, d, m in descs.astype(np.int64):
+        want[d:d + m] = arena[s:s + m]
+    got = ref.batch_copy([arena.copy()], [(0, s, 0, d, m) for s, d, m in descs])[0]
+    assert np.array_equal(got, want)
+
+
 def test_generated_batches_are_hazard_free(ref):
     for seed in range(5):
         arena, descs = inputs.b2b_batch(64, 16 * 1024, 8 * 1024 * 1024, seed=seed)
