@@ -103,6 +103,8 @@ def other_operations(dl, benchaid, inputs, torch, stream, ag_reqs, ag_bufs, ag_s
     def dev(t):
         return torch.from_numpy(t).cuda()
 
+    armed_cases = []   # (row, request, buffers kept alive): timed again in prelaunch and signal mode at the end
+
     def timed(req, nbytes, small, calls=None):
         us = benchaid.time_device(req, stream, warmup=3, calls=calls or (50 if small else 10))
         row = {"device_us": us, "GBps": nbytes / us / 1e3}
@@ -144,6 +146,8 @@ def other_operations(dl, benchaid, inputs, torch, stream, ag_reqs, ag_bufs, ag_s
         row = {"chunk_bytes": c}
         row.update(timed(req, 2 * W * W * c, c <= 128 * KiB))
         rows.append(row)
+        if c <= 128 * KiB:
+            armed_cases.append((row, req, (d_in, d_out)))
     res["alltoall_uniform"] = rows
 
     # in-place all-to-all (one swap per pair of ranks): every off-diagonal chunk is read once and written once
@@ -155,6 +159,8 @@ def other_operations(dl, benchaid, inputs, torch, stream, ag_reqs, ag_bufs, ag_s
         row = {"chunk_bytes": c}
         row.update(timed(req, 2 * W * (W - 1) * c, c <= 128 * KiB, calls=(50 if c <= 128 * KiB else 10)))
         rows.append(row)
+        if c <= 128 * KiB:
+            armed_cases.append((row, req, d_buf))
     res["alltoall_inplace_uniform"] = rows
 
     # MoE dispatch all-to-all: hidden 7168 bf16, 256 experts over 8 ranks, top-8
@@ -206,6 +212,7 @@ def other_operations(dl, benchaid, inputs, torch, stream, ag_reqs, ag_bufs, ag_s
         row = {"tokens": tokens, "bytes_per_rank": B}
         row.update(timed(req, ag_bytes(B), True))
         rows.append(row)
+        armed_cases.append((row, req, (d_in, d_out)))
     res["allgather_tp_decode"] = rows
 
     # KV-cache fetch: 256 dispersed blocks per request, pinned host pool -> device pool (over the host link),
@@ -239,7 +246,9 @@ def other_operations(dl, benchaid, inputs, torch, stream, ag_reqs, ag_bufs, ag_s
     src = dev(inputs.payload(np.random.default_rng(7), n, "bf16"))
     dsts = [torch.empty(n, dtype=torch.uint8, device="cuda") for _ in range(7)]
     row = {"bytes": n, "k": 7}
-    row.update(timed(benchaid.broadcast_request(src, dsts, n), 8 * n, True))
+    req = benchaid.broadcast_request(src, dsts, n)
+    row.update(timed(req, 8 * n, True))
+    armed_cases.append((row, req, (src, dsts)))
     res["broadcast"] = row
     arena_h, descs = inputs.b2b_batch(64, 16 * KiB, 64 * MiB, seed=3)
     arena = dev(arena_h)
@@ -249,13 +258,19 @@ def other_operations(dl, benchaid, inputs, torch, stream, ag_reqs, ag_bufs, ag_s
     row.update(timed(benchaid.copy_list_request(dlist, benchaid.OP_BATCH), 2 * 64 * 16 * KiB, True))
     req = benchaid.copy_list_request(dlist, benchaid.OP_MEMCPY_ASYNC)
     row["memcpy_async_per_copy_host_us"] = lat_stats(benchaid.time_host(req, stream, benchaid.WAIT_STREAM, 5, 50))
+    armed_cases.append((row, benchaid.copy_list_request(dlist, benchaid.OP_BATCH), arena))
+    res["batch_b2b"] = row
+
+    # the latency-bound cases again in prelaunch mode (doorbell -> completion word) and in signal mode
+    # (call -> completion word, no stream synchronisation)
     dl.dl_prelaunch_start()
-    dl.dl_set_mode(dl.DL_MODE_PRELAUNCH)
-    req = benchaid.copy_list_request(dlist, benchaid.OP_BATCH)
-    row["prelaunch_trigger_to_done_us"] = lat_stats(benchaid.time_host(req, None, benchaid.WAIT_TRIGGER, 30, 300))
+    for row, req, _keep in armed_cases:
+        dl.dl_set_mode(dl.DL_MODE_PRELAUNCH)
+        row["prelaunch_trigger_to_done_us"] = lat_stats(benchaid.time_host(req, None, benchaid.WAIT_TRIGGER, 30, 300))
+        dl.dl_set_mode(dl.DL_MODE_SIGNAL)
+        row["signal_call_to_done_us"] = lat_stats(benchaid.time_host(req, None, benchaid.WAIT_SIGNAL, 30, 300))
     dl.dl_set_mode(dl.DL_MODE_ONESHOT)
     dl.dl_prelaunch_stop()
-    res["batch_b2b"] = row
     return res
 
 
