@@ -343,11 +343,34 @@ def test_token_dispatch_ragged(ref, W, counts, row, drop):
                                                (3, [400, 1, 200], 48, 5), (1, [600], 4096, 4),
                                                (5, [0, 0, 513, 0, 0], 2048 + 16, None), (8, 2000, 256, 7)])
 def test_token_dispatch_lowered_on_device_and_on_host(ref, cfg, device_lowering, W, counts, row, drop):
-    """512 tokens or more with aligned rows take the device-side lowering (mask copied over, scanned by one
-    workgroup, rows addressed from the scan); the host lowering of the same request must give the same
-    bytes.  Empty ranks, tokens without destination, fewer than 8 ranks, rows shorter than one tile."""
+    """With 8 ranks, 512 tokens or more and aligned rows the copy list is built on the device from the mask;
+    the host lowering of the same request must give the same bytes.  Empty ranks, tokens without
+    destination, rows shorter than one tile; other rank counts (host lowering either way)."""
     cfg(device_lowering=device_lowering)
     run_token_dispatch(ref, W, counts, row, seed=W + row, drop=drop, experts=32 * W, top_k=min(8, W))
+
+
+@pytest.mark.parametrize("counts,row,top_k,mask_value", [
+    ([64] * 8, 16, 8, 1),                       # exactly the smallest request the device lowering takes
+    ([63] * 7 + [70], 32, 8, 255),              # 511: just below it; mask bytes other than 1
+    ([8159] * 8, 16, 2, 1),                     # 65 272 tokens: just below the largest it takes
+    ([8160] * 8, 16, 2, 1),                     # 65 280: just above
+    ([700, 1, 0, 300, 0, 0, 29, 2], 1024, 1, 2),     # every token to exactly one rank
+    ([100] * 8, 2048, 64, 7),                   # (nearly) every token to all eight ranks
+    ([257, 255, 256, 1, 0, 511, 64, 63], 1040, 3, 1),  # rank boundaries off the builder's 256-token blocks
+])
+def test_token_dispatch_device_lowering_edges(ref, counts, row, top_k, mask_value):
+    W = 8
+    ins = inputs.token_rows(W, counts, row, seed=sum(counts) + row, kind="u8")
+    dest = inputs.moe_token_destinations(W, counts, seed=top_k + row, n_experts=256, top_k=top_k) * np.uint8(mask_value)
+    want = ref.token_dispatch(ins, row, dest)
+    d_in = [DevBuf(a.size, fill=a) for a in ins]
+    d_out = [DevBuf(w.size) for w in want]
+    dl.dl_token_dispatch([b.ptr() for b in d_in], [b.ptr() for b in d_out], counts, row, dest, stream())
+    sync()
+    for j in range(W):
+        assert np.array_equal(d_out[j].host(), want[j]), f"receiver {j} differs"
+        assert d_out[j].guards_intact()
 
 
 def test_token_dispatch_skewed_experts(ref):
