@@ -25,6 +25,7 @@ if ROOT not in sys.path:
 
 W = 8
 KiB, MiB = 1024, 1024 * 1024
+RUNTIME_COPY_SIZES = (4 * KiB, 64 * KiB, MiB, 16 * MiB)   # per-rank sizes at which the runtime's own copy calls are timed
 HBM_PEAK_GBS = 8000.0
 
 
@@ -89,11 +90,26 @@ def cpu_baseline(sizes, budget_s=10.0):
     }
 
 
+def runtime_batch_comparison():
+    """hipMemcpyBatchAsync on the all-gather's 64 block copies, run by the comparison program that links the
+    ROCm installation's HIP runtime (the runtime PyTorch brings along does not export the call)."""
+    import subprocess
+    from paper_2511_06605_amd import build as dl_build
+    exe = dl_build.RUNTIME_BATCH
+    if not os.path.exists(exe):
+        return {"error": "comparison program not built"}
+    try:
+        r = subprocess.run([exe] + [str(B) for B in RUNTIME_COPY_SIZES], capture_output=True, text=True, timeout=120)
+        return json.loads(r.stdout.strip().splitlines()[-1])
+    except Exception as e:   # a comparison leg: report, never fail the benchmark
+        return {"error": f"{type(e).__name__}: {e}"}
+
+
 def lat_stats(lat):
     return {"p50": pct(lat, .5), "p10": pct(lat, .1), "p90": pct(lat, .9)}
 
 
-def other_operations(dl, benchaid, inputs, torch, stream, ag_reqs, ag_bufs, ag_sizes):
+def other_operations(dl, benchaid, inputs, torch, stream, ag_reqs, ag_bufs, ag_sizes, runtime_batch):
     """The other operations of the library and the runtime's own copy paths, timed
     beside the all-gather sweep (context, not part of `value`)."""
     import numpy as np
@@ -115,7 +131,7 @@ def other_operations(dl, benchaid, inputs, torch, stream, ag_reqs, ag_bufs, ag_s
     # runtime copy engines / blit path: one hipMemcpyAsync per chunk (W*W calls + one sync), and the batched call
     rows = []
     for B, (d_in, d_out) in zip(ag_sizes, ag_bufs):
-        if B not in (4 * KiB, 64 * KiB, MiB, 16 * MiB):
+        if B not in RUNTIME_COPY_SIZES:
             continue
         descs = [(d_in[j].data_ptr(), d_out[r].data_ptr() + j * B, B) for r in range(W) for j in range(W)]
         row = {"bytes_per_rank": B}
@@ -127,6 +143,14 @@ def other_operations(dl, benchaid, inputs, torch, stream, ag_reqs, ag_bufs, ag_s
             row["memcpy_batch_host_us"] = lat_stats(benchaid.time_host(req, stream, benchaid.WAIT_STREAM, 5, 50))
         except RuntimeError as e:
             row["memcpy_batch_host_us"] = f"unavailable in the loaded HIP runtime ({e})"
+        # the same call and the per-chunk calls under the ROCm installation's runtime, from the comparison program
+        if runtime_batch and "rows" in runtime_batch:
+            for other in runtime_batch["rows"]:
+                if other["bytes_per_rank"] == B:
+                    row["rocm_runtime_%s" % runtime_batch["runtime_version"]] = {k: v for k, v in other.items()
+                                                                                 if k != "bytes_per_rank"}
+        elif runtime_batch:
+            row["rocm_runtime"] = runtime_batch
         req = benchaid.copy_list_request(descs, benchaid.OP_BATCH)   # same 64 plain copies through dl_batch_copy
         dl.dl_set_config(infer_broadcast=0)                          # ... kept as 64 copies (each source re-read 8 times)
         row["dl_batch_copy_unfused"] = timed(req, 2 * W * W * B, B <= MiB)
@@ -335,6 +359,11 @@ def main() -> int:
               file=sys.stderr)
         return 2
 
+    # the runtime's batched copy call, timed by a program of its own before this process touches the GPU
+    runtime_batch = None
+    if args.case == "sweep" and not args.no_detail:
+        runtime_batch = runtime_batch_comparison()
+
     import numpy as np
     import torch
 
@@ -467,7 +496,7 @@ def main() -> int:
                              "schedule_and_sync_launch_and_stream_sync": med(total) - med(call) - dev_us,
                              "total": med(total)}
         detail["phase_breakdown_allgather"] = rows
-        detail.update(other_operations(dl, benchaid, inputs, torch, stream, reqs, keep, sizes))
+        detail.update(other_operations(dl, benchaid, inputs, torch, stream, reqs, keep, sizes, runtime_batch))
         out["detail"] = detail
         small = detail["allgather"][0]
         out["latency_us_4KiB_allgather"] = {
