@@ -99,6 +99,7 @@ __device__ __forceinline__ uint32_t dl_arm_wait(const dl_arm &a)
             // poll the host doorbell (uncached system-scope loads over the host link)
             for (uint32_t spins = 1;; ++spins) {
                 // doorbell and cancel word sit side by side in one aligned 16 bytes: one read over the link
+                // (each is an aligned 8-byte word that the host writes with one store, so neither can tear)
                 const dl_u32x4 w = dl_ld<DL_POL_COHERENT>(dl_global<dl_u32x4>(a.bell));
                 const uint64_t bell = (uint64_t)w.x | ((uint64_t)w.y << 32);
                 const uint64_t cancel = (uint64_t)w.z | ((uint64_t)w.w << 32);
