@@ -285,6 +285,38 @@ def other_operations(dl, benchaid, inputs, torch, stream, ag_reqs, ag_bufs, ag_s
     armed_cases.append((row, benchaid.copy_list_request(dlist, benchaid.OP_BATCH), arena))
     res["batch_b2b"] = row
 
+    # a decode step's worth of collectives (32 all-gathers of 8 tokens x hidden 8192 bf16, buffers of their own)
+    # issued one by one and replayed from a HIP graph captured once; microseconds per step, call -> synchronised
+    L, B = 32, inputs.tp_decode_bytes_per_rank(8)
+    layers = [([torch.zeros(B, dtype=torch.uint8, device="cuda") for _ in range(W)],
+               [torch.empty(W * B, dtype=torch.uint8, device="cuda") for _ in range(W)]) for _ in range(L)]
+    ptrs = [([t.data_ptr() for t in i], [t.data_ptr() for t in o]) for i, o in layers]
+
+    def issue_all(st):
+        for i, o in ptrs:
+            dl.dl_allgather(i, o, B, st)
+
+    def host_us(fn, reps=60):
+        lat = []
+        for r in range(reps + 10):
+            t0 = time.perf_counter()
+            fn()
+            torch.cuda.synchronize()
+            if r >= 10:
+                lat.append((time.perf_counter() - t0) * 1e6)
+        return lat_stats(lat)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(stream)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        issue_all(torch.cuda.current_stream())
+    res["decode_step_32_allgathers"] = {
+        "bytes_per_rank": B, "collectives": L,
+        "eager_calls_through_the_python_binding_us": host_us(lambda: issue_all(stream)),
+        "graph_replay_us": host_us(graph.replay),
+    }
+
     # the latency-bound cases again in prelaunch mode (doorbell -> completion word) and in signal mode
     # (call -> completion word, no stream synchronisation)
     dl.dl_prelaunch_start()
