@@ -47,6 +47,27 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(L, name), name
 
 
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C header: it must compile as C99 on its own, with nothing but the standard headers,
+    and every declared function must link against the built library from a C program."""
+    import subprocess
+    header = open(os.path.join(ROOT, "include", "dmalatte.h")).read()
+    names = sorted(set(re.findall(r"\b(dl_[a-z_]+)\s*\(", header)))
+    src = tmp_path / "uses_header.c"
+    src.write_text('#include "dmalatte.h"\n'
+                   "typedef void (*fn)(void);\n"
+                   "fn table[] = {" + ", ".join(f"(fn){n}" for n in names) + "};\n"
+                   "int main(void) { return sizeof(dl_plan_item) == 88 && sizeof(dl_copy_desc) == 24 && "
+                   "sizeof(dl_config) == 56 && sizeof(table) > 0 ? 0 : 1; }\n")
+    inc = os.path.join(ROOT, "include")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I" + inc, "-fsyntax-only", str(src)],
+                   check=True)
+    libdir = os.path.dirname(binding.LIB_PATH)
+    exe = tmp_path / "uses_header"
+    subprocess.run(["gcc", "-std=c99", "-I" + inc, str(src), "-L" + libdir, "-ldmalatte", "-Wl,-rpath," + libdir,
+                    "-Wl,--allow-shlib-undefined", "-o", str(exe)], check=True)
+
+
 def test_binding_structs_have_the_layout_of_the_header():
     """Sizes and offsets the C side asserts or implies: a mismatch here silently corrupts every call."""
     assert ctypes.sizeof(binding.PlanItem) == 88 and binding.PlanItem.dst.offset == 24
