@@ -32,8 +32,9 @@ class DevBuf:
         return self.view().cpu().numpy()
 
     def guards_intact(self):
-        r = self.raw.cpu().numpy()
-        return bool((r[:self.lo] == CANARY).all() and (r[self.lo + self.n:] == CANARY).all())
+        lo = self.raw[:self.lo].cpu().numpy()              # only the two bands cross to the host
+        hi = self.raw[self.lo + self.n:].cpu().numpy()
+        return bool((lo == CANARY).all() and (hi == CANARY).all())
 
 
 def stream():

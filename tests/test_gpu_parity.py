@@ -533,6 +533,64 @@ def test_swap_validation_rejects_overlap_and_enqueues_nothing():
     assert np.array_equal(d.host(), before)
 
 
+@pytest.mark.parametrize("shift", [0, 4, 1])
+def test_items_longer_than_4GiB(ref, shift):
+    """Byte offsets inside one item pass 2^32: a single copy and a 1 -> 2 broadcast of 4 GiB + 4112 bytes, with
+    the destinations aligned like the source (16-byte path), 4 bytes off (4-byte path) and 1 byte off (byte
+    path).  Too long for the CPU checker within a test's time: the device compares every byte with the source
+    (a copy has no other correct result), and the checker runs on windows around the start, 2^31, 2^32 and the end."""
+    import torch
+    n = (4 << 30) + 4112
+    src = DevBuf(n)
+    src.view().random_(0, 256)
+    d1, d2 = DevBuf(n, shift=shift), DevBuf(n, shift=shift)
+    dl.dl_batch_copy([(src.ptr(), d1.ptr(), n)], stream())
+    sync()
+    assert torch.equal(d1.view(), src.view()) and d1.guards_intact()
+    d1.view().zero_()
+    dl.dl_broadcast(src.ptr(), [d1.ptr(), d2.ptr()], n, stream())
+    sync()
+    assert torch.equal(d1.view(), src.view()) and torch.equal(d2.view(), src.view())
+    assert d1.guards_intact() and d2.guards_intact() and src.guards_intact()
+    for lo in (0, (1 << 31) - 2048, (1 << 32) - 2048, n - 4096):
+        win = src.view()[lo:lo + 4096].cpu().numpy()
+        want = ref.broadcast(win, 2)
+        assert np.array_equal(d1.view()[lo:lo + 4096].cpu().numpy(), want[0])
+        assert np.array_equal(d2.view()[lo:lo + 4096].cpu().numpy(), want[1])
+
+
+def test_swap_and_allgather_beyond_4GiB(ref):
+    """A swap of two ranges of 4 GiB + 48 bytes, and an all-gather whose receive offsets j * B pass 2^32
+    (W = 3, B = 2 GiB + 16); compared on the device with what the definitions give."""
+    import torch
+    n = (4 << 30) + 48
+    a, b = DevBuf(n), DevBuf(n)
+    a.view().random_(0, 256)
+    b.view().random_(0, 256)
+    a0, b0 = a.view().clone(), b.view().clone()
+    dl.dl_batch_swap([(a.ptr(), b.ptr(), n)], stream())
+    sync()
+    assert torch.equal(a.view(), b0) and torch.equal(b.view(), a0) and a.guards_intact() and b.guards_intact()
+    del a, b, a0, b0
+    W, B = 3, (2 << 30) + 16
+    d_in = [DevBuf(B) for _ in range(W)]
+    for t in d_in:
+        t.view().random_(0, 256)
+    d_out = [DevBuf(W * B) for _ in range(W)]
+    dl.dl_allgather([t.ptr() for t in d_in], [t.ptr() for t in d_out], B, stream())
+    sync()
+    for r in range(W):
+        for j in range(W):
+            assert torch.equal(d_out[r].view()[j * B:(j + 1) * B], d_in[j].view()), (r, j)
+        assert d_out[r].guards_intact()
+    lo = B - 2048                                   # a window across the first block boundary, against the checker
+    want = ref.allgather([t.view()[lo:].cpu().numpy() for t in d_in])
+    for r in range(W):
+        for j in range(W):
+            got = d_out[r].view()[j * B + lo:(j + 1) * B].cpu().numpy()
+            assert np.array_equal(got, want[r][j * 2048:(j + 1) * 2048])
+
+
 def test_short_one_shot_requests_replay_from_a_graph(ref):
     """A one-shot request whose list fits the kernel arguments is exactly one kernel launch on the caller's
     stream (no allocation, no copy, no event), so a caller can capture it in a HIP graph.  Three requests are

@@ -161,6 +161,21 @@ def test_batch_of_unequal_sizes_and_alignments_armed(ref, armed, n, max_bytes, s
     assert np.array_equal(d.host(), want) and d.guards_intact()
 
 
+def test_item_longer_than_4GiB_armed(ref, armed):
+    """Byte offsets past 2^32 in the armed kernels, whose capped grid strides over the tiles."""
+    import torch
+    n = (4 << 30) + 4112
+    src, dst = DevBuf(n), DevBuf(n)
+    src.view().random_(0, 256)
+    sync()
+    dl.dl_batch_copy([(src.ptr(), dst.ptr(), n)])
+    fire()
+    assert torch.equal(dst.view(), src.view()) and dst.guards_intact()
+    lo = (1 << 32) - 2048
+    win = src.view()[lo:lo + 4096].cpu().numpy()
+    assert np.array_equal(dst.view()[lo:lo + 4096].cpu().numpy(), ref.broadcast(win, 1)[0])
+
+
 @pytest.mark.parametrize("W,c", [(8, 64 * KiB), (8, 1000), (3, 300 * KiB + 16), (13, 5001)])
 def test_alltoall_inplace_armed(ref, armed, W, c):
     bufs = inputs.alltoall_inputs(inputs.uniform_chunks(W, c), seed=W + c, kind="fp16" if c % 2 == 0 else "u8")
