@@ -396,6 +396,47 @@ def test_batch_fanout_mixed_items(ref):
     assert np.array_equal(d.host(), want) and d.guards_intact()
 
 
+def in_chunks(ref, arena, copies, chunk=4000):
+    """The checker on a long list whose sources lie in a part of the arena that no copy writes: applied a few
+    thousand copies at a time (its hazard check compares all pairs), which gives what the whole batch gives."""
+    for i in range(0, len(copies), chunk):
+        ref.batch_copy([arena], copies[i:i + chunk])
+    return arena
+
+
+def test_lists_longer_than_one_staging_slot(ref):
+    """45 000 plain copies and 13 000 read-once/write-2 copies: more table entries than one slot of the staging
+    ring holds, so each request takes several table kernels.  Ragged sizes below one row, offsets on 80-byte
+    slots (every alignment)."""
+    rng = np.random.default_rng(12)
+    n, slot = 45000, 80
+    arena = rng.integers(0, 256, 2 * n * slot, dtype=np.uint8)
+    d = DevBuf(arena.size, fill=arena)
+    src = rng.integers(0, n, n) * slot + rng.integers(0, 8, n)
+    dst = (n + rng.permutation(n)) * slot + rng.integers(0, 8, n)
+    nb = rng.integers(1, slot - 8, n)
+    want = in_chunks(ref, arena.copy(), [(0, s, 0, t, m) for s, t, m in zip(src, dst, nb)])
+    dl.dl_batch_copy([(d.ptr(int(s)), d.ptr(int(t)), int(m)) for s, t, m in zip(src, dst, nb)], stream())
+    sync()
+    assert np.array_equal(d.host(), want) and d.guards_intact()
+
+    n = 13000
+    arena = rng.integers(0, 256, 3 * n * slot, dtype=np.uint8)
+    d = DevBuf(arena.size, fill=arena)
+    src = rng.integers(0, n, n) * slot
+    perm = rng.permutation(2 * n)
+    nb = rng.integers(1, slot + 1, n)
+    items, copies = [], []
+    for i in range(n):
+        t0, t1 = (n + int(perm[2 * i])) * slot, (n + int(perm[2 * i + 1])) * slot
+        items.append(dict(src=d.ptr(int(src[i])), bytes=int(nb[i]), dst=[d.ptr(t0), d.ptr(t1)]))
+        copies += [(0, int(src[i]), 0, t0, int(nb[i])), (0, int(src[i]), 0, t1, int(nb[i]))]
+    want = in_chunks(ref, arena.copy(), copies)
+    dl.dl_batch_fanout(items, stream())
+    sync()
+    assert np.array_equal(d.host(), want) and d.guards_intact()
+
+
 @pytest.mark.parametrize("infer", [0, 1])
 def test_batch_copy_with_and_without_broadcast_inference(ref, cfg, infer):
     """An all-gather written as 64 plain copies (receiver-major), plus unrelated copies: same bytes either way."""
