@@ -78,6 +78,12 @@ enum : uint32_t { DL_GO_WAIT = 0, DL_GO_RUN = 1, DL_GO_SKIP = 2 };
 // if the request was cancelled or the limit ran out.  Uniform over the workgroup.
 __device__ __forceinline__ uint32_t dl_arm_wait(const dl_arm &a)
 {
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        // off the critical path: clear the counters that the slot's next request will count on
+        for (uint32_t g = 0; g <= DL_ARM_GROUPS; ++g)
+            __hip_atomic_store((uint32_t *)((char *)a.arrive_clear + g * DL_ARM_STRIDE), 0u, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+    }
     if (a.nowait) {  // uniform over the grid: started without a doorbell
         if (blockIdx.x == 0 && threadIdx.x == 0) {
             __hip_atomic_store(a.armed, a.ticket, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
@@ -178,23 +184,22 @@ __device__ __forceinline__ void dl_arm_finish(const dl_arm &a, uint32_t go)
         if (!flat) {
             old = __hip_atomic_fetch_add(gcount, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if ((old & 0xFFFFu) != gsize - 1u) return;
-            // last of the group: leave the counter at zero for the slot's next request (the reset has
-            // completed before anything that can let that request start), carry the result to the top
-            __hip_atomic_store(gcount, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            dl_drain_stores();
+            // last of the group: carry the result to the top
             add = 1u + (((old >> 16) + (add >> 16)) << 16);
         }
         // a small grid is counted at the top directly
         old = __hip_atomic_fetch_add(top, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if ((old & 0xFFFFu) != groups - 1u) return;
         // last of all
+        // The counters stay as they are: the slot's next request counts on the other set and clears this one
+        // (see dl_arm).  Nothing is in flight from this wavefront here except, when tracing, the stamps, which
+        // must have landed before the completion word.
         const uint32_t skipped = (old >> 16) + (add >> 16);
-        __hip_atomic_store(top, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (a.trace_host) {
             __hip_atomic_store(a.trace_host + 2, t_end, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
             __hip_atomic_store(a.trace_host + 3, (uint64_t)wall_clock64(), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            dl_drain_stores();
         }
-        dl_drain_stores();
         __hip_atomic_store(a.done, a.ticket | (skipped ? DL_DONE_SKIPPED : 0ull), __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_SYSTEM);
     }

@@ -49,6 +49,10 @@ struct dl_arm {
     uint64_t *armed;       // host-coherent: "resident and polling" word of this ticket's slot
     uint64_t *go;          // device: fan-out flags of this ticket's slot, one per group, DL_ARM_STRIDE bytes apart
     uint32_t *arrive;      // device: arrival counters of this slot: one per group, then the top one, same spacing
+    // A slot has two sets of counters, used by its requests in turn.  A request leaves its set as counted
+    // (no reset on the way to the completion word) and clears the other one before it waits: that set's last
+    // user has finished, and its next user is armed only after this request has.
+    uint32_t *arrive_clear;
     uint64_t ticket;
     uint64_t limit_ticks;   // give up this long after becoming resident
     uint64_t margin_ticks;  // extra time a non-polling workgroup grants the polling one

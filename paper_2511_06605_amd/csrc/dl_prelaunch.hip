@@ -34,7 +34,7 @@ struct arm_host {  // pinned, host-coherent
 
 struct arm_dev {  // device memory; every flag and counter in a cache line of its own
     uint8_t go[SLOTS][DL_ARM_GROUPS * DL_ARM_STRIDE];
-    uint8_t arrive[SLOTS][(DL_ARM_GROUPS + 1) * DL_ARM_STRIDE];
+    uint8_t arrive[SLOTS][2][(DL_ARM_GROUPS + 1) * DL_ARM_STRIDE];  // two sets per slot, see dl_arm
 };
 
 struct arm_state {
@@ -93,7 +93,9 @@ int dl_armed_begin(dl_arm *arm, hipStream_t *stream)
     arm->done = &g_arm.host->done[slot];
     arm->armed = &g_arm.host->armed[slot];
     arm->go = (uint64_t *)g_arm.dev->go[slot];
-    arm->arrive = (uint32_t *)g_arm.dev->arrive[slot];
+    const uint32_t set = (uint32_t)(ticket / SLOTS) & 1u;
+    arm->arrive = (uint32_t *)g_arm.dev->arrive[slot][set];
+    arm->arrive_clear = (uint32_t *)g_arm.dev->arrive[slot][set ^ 1u];
     arm->ticket = ticket;
     arm->limit_ticks = (uint64_t)g_dl.cfg.arm_timeout_us * g_arm.clock_khz / 1000ull;
     arm->margin_ticks = 5000ull * g_arm.clock_khz / 1000ull;  // 5 ms
