@@ -119,7 +119,7 @@ __device__ __forceinline__ uint32_t dl_arm_wait(const dl_arm &a)
                 }
                 if ((spins & 3u) == 0 && (uint64_t)wall_clock64() - t0 > a.limit_ticks) break;
                 if (spins >= a.max_spins) break;
-                if (blockIdx.x) __builtin_amdgcn_s_sleep(8);
+                if (blockIdx.x && !a.direct) __builtin_amdgcn_s_sleep(8);
             }
             if (!a.direct) {
                 // pass the word on: one flag per group of workgroups, each in its own cache line
