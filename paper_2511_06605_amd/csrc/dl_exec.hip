@@ -74,19 +74,22 @@ __global__ void __launch_bounds__(512) dl_exec_table_kernel(const Item *__restri
 
 enum : uint32_t { DL_GO_WAIT = 0, DL_GO_RUN = 1, DL_GO_SKIP = 2 };
 
+// Housekeeping of a request, done by one thread where its stores' round trips delay nothing: clear the
+// counters that the slot's next request will count on, and tell the host that the kernel is resident.
+__device__ __forceinline__ void dl_arm_housekeeping(const dl_arm &a)
+{
+    for (uint32_t g = 0; g <= DL_ARM_GROUPS; ++g)
+        __hip_atomic_store((uint32_t *)((char *)a.arrive_clear + g * DL_ARM_STRIDE), 0u, __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(a.armed, a.ticket, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
 // Returns DL_GO_RUN once the doorbell has been rung for this ticket, DL_GO_SKIP
 // if the request was cancelled or the limit ran out.  Uniform over the workgroup.
 __device__ __forceinline__ uint32_t dl_arm_wait(const dl_arm &a)
 {
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
-        // off the critical path: clear the counters that the slot's next request will count on
-        for (uint32_t g = 0; g <= DL_ARM_GROUPS; ++g)
-            __hip_atomic_store((uint32_t *)((char *)a.arrive_clear + g * DL_ARM_STRIDE), 0u, __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_AGENT);
-    }
-    if (a.nowait) {  // uniform over the grid: started without a doorbell
+    if (a.nowait) {  // uniform over the grid: started without a doorbell; housekeeping follows the copy
         if (blockIdx.x == 0 && threadIdx.x == 0) {
-            __hip_atomic_store(a.armed, a.ticket, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
             if (a.trace_host) {
                 const uint64_t t = (uint64_t)wall_clock64();
                 __hip_atomic_store(a.trace_host, t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
@@ -99,8 +102,7 @@ __device__ __forceinline__ uint32_t dl_arm_wait(const dl_arm &a)
     if (threadIdx.x == 0) {
         uint32_t go = DL_GO_SKIP;
         const uint64_t t0 = wall_clock64();
-        if (blockIdx.x == 0)
-            __hip_atomic_store(a.armed, a.ticket, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        if (blockIdx.x == 0) dl_arm_housekeeping(a);  // before the wait: off the critical path
         if (a.direct || blockIdx.x == 0) {
             // poll the host doorbell (uncached system-scope loads over the host link)
             for (uint32_t spins = 1;; ++spins) {
@@ -166,6 +168,9 @@ __device__ __forceinline__ uint32_t dl_arm_wait(const dl_arm &a)
 // itself in; that serialised per XCD and cost ~0.5 us per workgroup.)
 __device__ __forceinline__ void dl_arm_finish(const dl_arm &a, uint32_t go)
 {
+    // without a doorbell there was no wait to hide the housekeeping behind: its stores go out behind the copy's
+    // and share their round trip
+    if (a.nowait && blockIdx.x == 0 && threadIdx.x == 0) dl_arm_housekeeping(a);
     dl_drain_stores();
     __syncthreads();
     if (threadIdx.x == 0) {
