@@ -47,6 +47,17 @@ def run_pins(lib):
     buf = np.arange(256, dtype=np.uint8)
     assert ref.first_hazard([buf], [(0, 0, 0, 100, 50), (0, 60, 0, 150, 10)], lib=lib) == -1
     assert ref.first_hazard([buf], [(0, 0, 0, 100, 50), (0, 120, 0, 200, 10)], lib=lib) == 0
+    assert ref.first_hazard([buf], [(0, 0, 0, 100, 50), (0, 60, 0, 149, 10)], lib=lib) == 0   # two destinations share a byte
+    assert ref.first_hazard([buf], [(0, 0, 0, 10, 50)], lib=lib) == 0                         # a copy onto its own source
+    assert ref.first_hazard([buf], [(0, 5, 0, 5, 50)], lib=lib) == -1                         # identical range: no-op
+    kept = buf.copy()
+    try:                                                     # a batch with a hazard is refused and moves nothing
+        ref.batch_copy([kept], [(0, 0, 0, 100, 50), (0, 60, 0, 149, 10)], lib=lib)
+    except ValueError:
+        pass
+    else:
+        raise AssertionError("hazard accepted")
+    assert np.array_equal(kept, buf)
 
     arena, descs = inputs.swap_batch(5, 30, 2048, seed=6, align=2)
     want = arena.copy()

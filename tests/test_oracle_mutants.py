@@ -54,6 +54,18 @@ MUTANTS = {
                       "memcpy((char *)out[j] + (placed ? placed - 1 : 0) * row_bytes, (const char *)in[i] + (size_t)t * row_bytes, row_bytes);"),
     "td_global_row": ("(const char *)in[i] + (size_t)t * row_bytes, row_bytes);\n                }\n                ++placed;",
                       "(const char *)in[i] + (size_t)(t ? t - 1 : 0) * row_bytes, row_bytes);\n                }\n                ++placed;"),
+    "td_local_token_index": ("if (!dest[g * (size_t)W + (size_t)j])", "if (!dest[(size_t)t * (size_t)W + (size_t)j])"),
+    "aa_stops_at_empty_chunk": ("            if (n == 0)\n                continue;", "            if (n == 0)\n                break;"),
+    "hz_ignores_destinations": ("if (a != b && ranges_overlap(d[a].dst, d[a].bytes, d[b].dst, d[b].bytes))\n                return (long)a;",
+                                "if (0)\n                return (long)a;"),
+    "hz_noop_copy_flagged": ("            if (a == b && d[a].src == d[a].dst)\n                continue;\n", ""),
+    "bt_no_hazard_check": ("    if (ref_first_hazard(d, n) >= 0)\n        return -2;\n", ""),
+    "bc_always_first_destination": ("memcpy(dsts[d], src, bytes);", "memcpy(dsts[0], src, bytes);"),
+    "sw_hazard_skips_neighbour": ("for (size_t m = k + 1; m < n; ++m) {", "for (size_t m = k + 2; m < n; ++m) {"),
+    "td_rows_counted_across_receivers": ("size_t placed = 0; /* rows already written to out[j] */",
+                                         "static size_t placed; if (j == 0) placed = 0;"),
+    "ag_rank_stride_off": ("memcpy((char *)out[r] + (size_t)j * B, in[j], B);",
+                           "memcpy((char *)out[r] + (size_t)j * B, in[j], B - (j == W - 1 && B > 1));"),
     "td_counts_skipped": ("                if (!dest[g * (size_t)W + (size_t)j])\n                    continue;",
                           "                if (!dest[g * (size_t)W + (size_t)j]) {\n                    ++placed;\n                    continue;\n                }"),
 }
