@@ -50,6 +50,8 @@ def run_pins(lib):
     assert ref.first_hazard([buf], [(0, 0, 0, 100, 50), (0, 60, 0, 149, 10)], lib=lib) == 0   # two destinations share a byte
     assert ref.first_hazard([buf], [(0, 0, 0, 10, 50)], lib=lib) == 0                         # a copy onto its own source
     assert ref.first_hazard([buf], [(0, 5, 0, 5, 50)], lib=lib) == -1                         # identical range: no-op
+    assert ref.first_hazard([buf], [(0, 0, 0, 105, 0), (0, 0, 0, 100, 10)], lib=lib) == -1    # an empty copy collides with nothing,
+    assert ref.first_hazard([buf], [(0, 0, 0, 100, 10), (0, 105, 0, 200, 0)], lib=lib) == -1  # not even from inside a range
     kept = buf.copy()
     try:                                                     # a batch with a hazard is refused and moves nothing
         ref.batch_copy([kept], [(0, 0, 0, 100, 50), (0, 60, 0, 149, 10)], lib=lib)
@@ -66,7 +68,9 @@ def run_pins(lib):
     got = ref.batch_swap([arena.copy()], [(0, a, 0, b, n) for a, b, n in descs], lib=lib)[0]
     assert np.array_equal(got, want)
     for bad in ([(0, 0, 0, 100, 20), (0, 110, 0, 200, 20)], [(0, 0, 0, 100, 20), (0, 200, 0, 19, 20)],
-                [(0, 0, 0, 10, 20)]):
+                [(0, 0, 0, 10, 20)],
+                [(0, 0, 0, 100, 20), (0, 10, 0, 200, 20)],      # the two first ranges share bytes
+                [(0, 0, 0, 100, 20), (0, 200, 0, 110, 20)]):    # the two second ranges share bytes
         try:
             ref.batch_swap([buf.copy()], bad, lib=lib)
         except ValueError:
@@ -79,6 +83,9 @@ def run_pins(lib):
     bufs = inputs.alltoall_inputs(inputs.uniform_chunks(W, c), seed=8)
     got = ref.alltoall_inplace(bufs, c, lib=lib)
     assert np.array_equal(np.stack(got), np.stack(bufs).reshape(W, W, c).transpose(1, 0, 2).reshape(W, W * c))
+
+    empty = [np.zeros(0, dtype=np.uint8) for _ in range(W)]
+    assert all(b.size == 0 for b in ref.alltoall_inplace(empty, 0, lib=lib))                   # empty chunks: a no-op, not an error
 
     counts, row = [3, 0, 4], 6
     tin = inputs.token_rows(W, counts, row, seed=9)

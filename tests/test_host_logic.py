@@ -313,6 +313,9 @@ def test_swap_hazard_validator_agrees_with_the_checker(ref):
         "own ranges overlap": [(0, 30, 50)],
         "a hits other b": [(0, 100, 50), (500, 40, 50)],
         "b hits other a": [(0, 100, 50), (120, 600, 50)],
+        "a hits other a": [(0, 100, 50), (30, 600, 50)],
+        "b hits other b": [(0, 100, 50), (600, 130, 50)],
+        "empty range inside another": [(0, 100, 50), (700, 120, 0)],
         "contained": [(0, 1000, 500), (100, 2000, 10)],
         "identical range is a no-op": [(10, 10, 100), (20, 300, 50)],
         "empty ranges never collide": [(0, 10, 0), (0, 100, 50)],

@@ -66,6 +66,11 @@ MUTANTS = {
                                          "static size_t placed; if (j == 0) placed = 0;"),
     "ag_rank_stride_off": ("memcpy((char *)out[r] + (size_t)j * B, in[j], B);",
                            "memcpy((char *)out[r] + (size_t)j * B, in[j], B - (j == W - 1 && B > 1));"),
+    "ro_empty_ranges_collide": ("    if (an == 0 || bn == 0)\n        return 0;\n", ""),
+    "sw_hazard_aa": ("if (ranges_overlap(d[k].a, d[k].bytes, d[m].a, d[m].bytes) ||", "if (0 ||"),
+    "sw_hazard_a_with_later_b": ("ranges_overlap(d[k].a, d[k].bytes, d[m].b, d[m].bytes) ||", "0 ||"),
+    "sw_hazard_bb": ("ranges_overlap(d[k].b, d[k].bytes, d[m].b, d[m].bytes))", "0)"),
+    "ip_empty_chunks_not_noop": ("    if (c == 0)\n        return 0;\n", "    if (c == 0)\n        return -1;\n"),
     "td_counts_skipped": ("                if (!dest[g * (size_t)W + (size_t)j])\n                    continue;",
                           "                if (!dest[g * (size_t)W + (size_t)j]) {\n                    ++placed;\n                    continue;\n                }"),
 }

@@ -227,6 +227,8 @@ def test_hazard_rule(ref):
     assert ref.first_hazard([buf], [(0, 0, 0, 10, 50)]) == 0                         # src-dst of one copy
     assert ref.first_hazard([buf], [(0, 5, 0, 5, 50)]) == -1                         # identical range: no-op
     assert ref.first_hazard([buf], [(0, 0, 0, 100, 0), (0, 0, 0, 100, 10)]) == -1    # empty copies never collide
+    assert ref.first_hazard([buf], [(0, 0, 0, 105, 0), (0, 0, 0, 100, 10)]) == -1    # ... not even from inside a range
+    assert ref.first_hazard([buf], [(0, 0, 0, 100, 10), (0, 105, 0, 200, 0)]) == -1
     with pytest.raises(ValueError):
         ref.batch_copy([buf.copy()], [(0, 0, 0, 100, 50), (0, 60, 0, 149, 10)])
     same = buf.copy()
