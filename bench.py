@@ -317,6 +317,52 @@ def other_operations(dl, benchaid, inputs, torch, stream, ag_reqs, ag_bufs, ag_s
         "graph_replay_us": host_us(graph.replay),
     }
 
+    # the price of copying on compute units (the paper's motive for DMA offload, Sec. I): a bf16 GEMM 8192^3 on one
+    # stream, all-gathers of 16 MiB per rank back to back on another for as long as the GEMMs run
+    B = 16 * MiB
+    ag_req, ag_keep = None, None
+    for size, bufs in zip(ag_sizes, ag_bufs):
+        if size == B:
+            ag_req, ag_keep = ag_reqs[B], bufs
+    if ag_req is not None:
+        n = 8192
+        ga = torch.randn(n, n, dtype=torch.bfloat16, device="cuda")
+        gb = torch.randn(n, n, dtype=torch.bfloat16, device="cuda")
+        gc = torch.empty(n, n, dtype=torch.bfloat16, device="cuda")
+        other = torch.cuda.Stream()
+
+        def gemms(k):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(k):
+                torch.matmul(ga, gb, out=gc)
+            e1.record(stream)
+            return e0, e1
+
+        torch.matmul(ga, gb, out=gc)
+        torch.cuda.synchronize()
+        e0, e1 = gemms(10)
+        torch.cuda.synchronize()
+        gemm_alone = e0.elapsed_time(e1) * 1e2
+        ag_alone = benchaid.time_device(ag_req, other, warmup=2, calls=10)
+        e0, e1 = gemms(10)
+        s0, s1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        s0.record(other)
+        issued = 0
+        while not e1.query() and issued < 1000:
+            benchaid.issue(ag_req, other)
+            issued += 1
+            if issued % 4 == 0:
+                other.synchronize()
+        s1.record(other)
+        torch.cuda.synchronize()
+        res["overlap_with_gemm"] = {
+            "gemm": "bf16 8192 x 8192 x 8192 (torch.matmul)", "allgather_bytes_per_rank": B,
+            "gemm_alone_us": gemm_alone, "allgather_alone_us": ag_alone,
+            "gemm_beside_allgathers_us": e0.elapsed_time(e1) * 1e2,
+            "allgather_beside_gemm_us": s0.elapsed_time(s1) * 1e3 / max(issued, 1), "allgathers_issued": issued,
+        }
+
     # the latency-bound cases again in prelaunch mode (doorbell -> completion word) and in signal mode
     # (call -> completion word, no stream synchronisation)
     dl.dl_prelaunch_start()
