@@ -2,6 +2,8 @@
 the CPU checker on the same seeded inputs.  The bar is bit-exact (pure data
 movement), and bytes outside every destination must stay untouched."""
 
+import os
+
 import numpy as np
 import pytest
 
@@ -13,6 +15,8 @@ from gpu_util import DevBuf, stream, sync
 
 pytestmark = pytest.mark.gpu
 
+VALIDATE_ALL = os.environ.get("DL_TEST_VALIDATE") == "1"
+
 
 @pytest.fixture(scope="module", autouse=True)
 def library():
@@ -21,6 +25,8 @@ def library():
     torch.cuda.set_device(0)
     dl.dl_init(0)
     base = dl.dl_get_config()
+    # DL_TEST_VALIDATE=1 runs every test with the hazard check on: it must refuse none of the valid requests
+    dl.dl_set_validate(VALIDATE_ALL)
     yield
     dl.dl_set_config(base)
     dl.dl_set_validate(False)
@@ -569,7 +575,7 @@ def test_swap_validation_rejects_overlap_and_enqueues_nothing():
             dl.dl_batch_swap([(d.ptr(0), d.ptr(100), 500)], stream())
         assert e.value.status == dl.DL_ERR_OVERLAP
     finally:
-        dl.dl_set_validate(False)
+        dl.dl_set_validate(VALIDATE_ALL)
     sync()
     assert np.array_equal(d.host(), before)
 
@@ -701,7 +707,7 @@ def test_validation_rejects_hazards_and_enqueues_nothing():
         assert e.value.status == dl.DL_ERR_OVERLAP
         dl.dl_batch_copy([(d.ptr(0), d.ptr(1000), 500), (d.ptr(100), d.ptr(1500), 500)], stream())
     finally:
-        dl.dl_set_validate(False)
+        dl.dl_set_validate(VALIDATE_ALL)
     sync()
     after = d.host()
     assert np.array_equal(after[:1000], before[:1000]) and np.array_equal(after[2000:], before[2000:])

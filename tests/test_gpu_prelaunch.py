@@ -5,6 +5,8 @@ untriggered or cancelled request copies nothing and says so.
 Every armed kernel gives up by itself after the arm limit set below, so no
 test can leave waves on the device."""
 
+import os
+
 import numpy as np
 import pytest
 
@@ -33,6 +35,7 @@ def library():
     torch.cuda.set_device(0)
     dl.dl_init(0)
     dl.dl_set_config(arm_timeout_us=ARM_US)
+    dl.dl_set_validate(os.environ.get("DL_TEST_VALIDATE") == "1")   # see test_gpu_parity.py
     yield
     dl.dl_shutdown()
 
