@@ -27,6 +27,10 @@ def library():
     base = dl.dl_get_config()
     # DL_TEST_VALIDATE=1 runs every test with the hazard check on: it must refuse none of the valid requests
     dl.dl_set_validate(VALIDATE_ALL)
+    # DL_TEST_CONFIG="max_blocks=64,fan_split=1" runs every test with those tunables as the defaults
+    forced = dict(kv.split("=") for kv in os.environ.get("DL_TEST_CONFIG", "").split(",") if kv)
+    if forced:
+        dl.dl_set_config(**{k: int(v) for k, v in forced.items()})
     yield
     dl.dl_set_config(base)
     dl.dl_set_validate(False)
