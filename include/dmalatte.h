@@ -240,7 +240,7 @@ typedef struct dl_config {
     uint32_t tile_bytes;         /* bytes of one workgroup tile; 0 = choose from the fan-out; power of two >= 1024 */
     uint32_t block_threads;      /* workgroup size of the one-shot kernel: 64, 128, 256 or 512; 0 = choose */
     uint64_t nontemporal_min_bytes; /* requests moving at least this many bytes use streaming loads/stores; default: never */
-    uint32_t armed_blocks;       /* cap on the grid of an armed kernel (its workgroups stride over the tiles); 0 = 4 per compute unit */
+    uint32_t armed_blocks;       /* cap on the grid of an armed kernel (its workgroups stride over the tiles); 0 = half the wavefront slots of the GPU, so that the kernels that produce the request's inputs can run beside it */
     uint32_t arm_timeout_us;     /* an armed kernel gives up this long after becoming resident; 1 .. 1000000, default 20000 */
     uint32_t fuse_broadcast;     /* 1: all-gather reads each source once (W fused copies); 0: W*W plain copies */
     uint32_t max_blocks;         /* cap on the one-shot grid; workgroups then stride over the tiles; 0 = one workgroup per tile */

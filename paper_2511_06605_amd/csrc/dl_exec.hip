@@ -313,9 +313,15 @@ inline uint32_t item_k(const dl_fused_item &it) { return it.k; }
 
 constexpr uint32_t ARMED_DIRECT_MAX = 16;  // up to this many workgroups all poll the host doorbell themselves
 
-uint32_t armed_grid(uint64_t tiles)
+// Workgroups of an armed kernel.  While it waits for its doorbell the kernel must leave room for other
+// kernels, above all for the ones that produce what it is going to copy: unless the caller sets the cap, the
+// grid takes at most half of the wavefront slots (16 of 32 per compute unit: four workgroups of 256 threads,
+// two of 512).
+uint32_t armed_grid(uint64_t tiles, uint32_t block_threads)
 {
-    uint32_t cap = g_dl.cfg.armed_blocks ? g_dl.cfg.armed_blocks : 4u * (uint32_t)(g_dl.num_cu > 0 ? g_dl.num_cu : 256);
+    const uint32_t cus = (uint32_t)(g_dl.num_cu > 0 ? g_dl.num_cu : 256);
+    uint32_t cap = g_dl.cfg.armed_blocks ? g_dl.cfg.armed_blocks : 16u * cus / (block_threads / 64u);
+    if (cap < 1u) cap = 1u;
     if (cap > 32768u) cap = 32768u;  // the arrival counter keeps 16 bits for the count
     return (uint32_t)(tiles < cap ? tiles : cap);
 }
@@ -340,7 +346,7 @@ int launch_klist(const Item *items, size_t n, const uint64_t *tile_end, const dl
     const uint32_t grid = (uint32_t)tile_end[n - 1];
     if (arm) {
         dl_arm a = *arm;
-        const uint32_t g = armed_grid(grid);
+        const uint32_t g = armed_grid(grid, sh.block_threads);
         a.direct = g <= ARMED_DIRECT_MAX ? 1u : 0u;
         if (sh.rows)
             hipLaunchKernelGGL((dl_armed_list_kernel<Item, NMAX, true>), dim3(g), dim3(sh.block_threads), 0, stream, p, a);
@@ -520,7 +526,7 @@ int launch_table(const Item *items, size_t n, dl_launch_shape sh, hipStream_t st
         }
         if (arm) {
             dl_arm a = *arm;
-            const uint32_t g = armed_grid(m);
+            const uint32_t g = armed_grid(m, sh.block_threads);
             a.direct = g <= ARMED_DIRECT_MAX ? 1u : 0u;
             hipLaunchKernelGGL((dl_armed_table_kernel<Item>), dim3(g), dim3(sh.block_threads), 0, stream, slot,
                                (uint32_t)m, sh.tile_bytes, sh.split, a);

@@ -36,6 +36,9 @@ def library():
     dl.dl_init(0)
     dl.dl_set_config(arm_timeout_us=ARM_US)
     dl.dl_set_validate(os.environ.get("DL_TEST_VALIDATE") == "1")   # see test_gpu_parity.py
+    forced = dict(kv.split("=") for kv in os.environ.get("DL_TEST_CONFIG", "").split(",") if kv)
+    if forced:
+        dl.dl_set_config(**{k: int(v) for k, v in forced.items()})
     yield
     dl.dl_shutdown()
 
@@ -241,6 +244,34 @@ def test_sources_written_after_arming_are_seen(ref, armed):
         want = ref.allgather(ins)
         for r in range(W):
             assert np.array_equal(d_out[r].host(), want[r]), f"round {rnd} rank {r}"
+
+
+@pytest.mark.parametrize("B", [1 * MiB, 8 * MiB])
+def test_large_armed_request_leaves_room_for_its_producers(ref, armed, B):
+    """A request with more tiles than the armed grid holds is armed first; then kernels on another stream
+    produce its sources, and only then is the doorbell rung.  The armed kernel, resident and polling all the
+    while, must not take every wavefront slot: the producers have to run beside it, or the request can only
+    expire.  Unfused (64 copies), so that the grid is at its cap."""
+    import torch
+    W = 8
+    dl.dl_set_config(fuse_broadcast=0)
+    try:
+        d_in = [torch.zeros(B, dtype=torch.uint8, device="cuda") for _ in range(W)]
+        d_out = [torch.zeros(W * B, dtype=torch.uint8, device="cuda") for _ in range(W)]
+        sync()
+        dl.dl_allgather(d_in, d_out, B)
+        dl.dl_wait_armed()
+        for round_ in range(20):                      # producers that need many workgroups of their own
+            for j in range(W):
+                d_in[j].fill_((round_ * 13 + j * 29) % 251)
+        sync()
+        fire()
+        for r in (0, 5):
+            got = d_out[r].view(W, B)
+            want = torch.tensor([(19 * 13 + j * 29) % 251 for j in range(W)], dtype=torch.uint8, device="cuda")
+            assert bool((got == want[:, None]).all())
+    finally:
+        dl.dl_set_config(fuse_broadcast=1)
 
 
 def test_many_requests_armed_at_once(ref, armed):
