@@ -188,6 +188,11 @@ int dl_alltoall_inplace(void *const *buf, int W, size_t chunk_bytes, void *strea
  * Requests on one stream run in ticket order.  The armed kernel occupies its
  * stream until it is triggered, cancelled or expires; later work on that
  * stream waits for it.  At most 64 requests may be armed and unfinished.
+ * While it waits, an armed kernel holds wavefront slots: at most half of the
+ * GPU's for one request (dl_config.armed_blocks), so that the kernels which
+ * produce its inputs can run beside it.  Requests armed on different streams
+ * are resident together and their slots add up: arm large requests on one
+ * stream, where they become resident one after the other.
  * Lists too long for one kernel (hundreds of thousands of tiles) are refused
  * with DL_ERR_INVALID in this mode.  An empty request enqueues nothing and
  * takes no ticket.
