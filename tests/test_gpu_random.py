@@ -204,3 +204,33 @@ N_CASES = int(os.environ.get("DL_TEST_RANDOM_CASES", "240"))
 def test_random_requests(ref, first):
     for seed in range(first, min(first + 20, N_CASES)):
         run_case(ref, seed)
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_requests_back_to_back_depend_on_each_other_in_stream_order(ref, seed):
+    """Thirty batches on one stream with no synchronisation between them, each reading what earlier ones wrote
+    (inside one arena): lists in the kernel arguments, table kernels reading the pinned ring, tables staged in
+    device memory and swaps, so that the ring's four slots are reused while earlier requests are still queued.
+    The checker applies the same batches one after the other."""
+    import torch
+    rng = np.random.default_rng(seed)
+    size_ = 12 << 20
+    arena = rng.integers(0, 256, size_, dtype=np.uint8)
+    want = arena.copy()
+    d = DevBuf(size_, fill=arena)
+    sync()
+    st = torch.cuda.current_stream()
+    for step in range(30):
+        n = int(rng.choice([3, 8, 60, 100, 700, 3000]))
+        if rng.random() < 0.25:
+            _, descs = inputs.swap_batch(min(n, 200), int(rng.choice([48, 1000, 20000])), size_, seed=1000 * seed + step,
+                                         align=int(rng.choice([1, 16])))
+            ref.batch_swap([want], [(0, a, 0, b, m) for a, b, m in descs])
+            dl.dl_batch_swap([(d.ptr(int(a)), d.ptr(int(b)), int(m)) for a, b, m in descs], st)
+        else:
+            _, descs = inputs.mixed_batch(n, int(rng.choice([300, 6000, 60000] if n < 1000 else [300])), size_,
+                                          seed=1000 * seed + step, shared_sources=float(rng.choice([0.0, 0.3])))
+            ref.batch_copy([want], [(0, s, 0, t, m) for s, t, m in descs])
+            dl.dl_batch_copy([(d.ptr(int(s)), d.ptr(int(t)), int(m)) for s, t, m in descs], st)
+    sync()
+    assert np.array_equal(d.host(), want) and d.guards_intact()
