@@ -234,3 +234,27 @@ def test_requests_back_to_back_depend_on_each_other_in_stream_order(ref, seed):
             dl.dl_batch_copy([(d.ptr(int(s)), d.ptr(int(t)), int(m)) for s, t, m in descs], st)
     sync()
     assert np.array_equal(d.host(), want) and d.guards_intact()
+
+
+def test_token_dispatches_back_to_back_reuse_the_staging_ring(ref):
+    """Twelve token dispatches on one stream without synchronisation, each with its own mask and receive
+    buffers; three times as many as the staging ring has slots, alternating between the device-side lowering
+    (mask staged) and the host lowering (item table staged)."""
+    import torch
+    W, row = 8, 1024
+    st = torch.cuda.current_stream()
+    ins = inputs.token_rows(W, 100, row, seed=5)
+    d_in = [DevBuf(a.size, fill=a) for a in ins]
+    runs = []
+    sync()
+    for k in range(12):
+        dest = inputs.moe_token_destinations(W, 100, seed=50 + k, top_k=1 + k % 8)
+        want = ref.token_dispatch(ins, row, dest)
+        d_out = [DevBuf(w.size) for w in want]
+        dl.dl_set_config(device_lowering=k % 2)
+        dl.dl_token_dispatch([b.ptr() for b in d_in], [b.ptr() for b in d_out], [100] * W, row, dest, st)
+        runs.append((d_out, want))
+    dl.dl_set_config(device_lowering=1)
+    sync()
+    for k, (d_out, want) in enumerate(runs):
+        check(d_out, want, f"dispatch {k}")
