@@ -82,7 +82,7 @@ def check(bufs, want, what):
         assert b.guards_intact(), f"{what}: guard band of buffer {i} written"
 
 
-def run_case(ref, seed):
+def run_case(ref, seed, scale=1):
     import torch
     rng = np.random.default_rng(seed)
     op = str(rng.choice(["allgather", "alltoall", "broadcast", "batch", "swap", "inplace", "token", "fanout"]))
@@ -99,7 +99,7 @@ def run_case(ref, seed):
     before = dl.dl_last_ticket()
     try:
         if op == "allgather":
-            B = size(rng, 300 * KiB)
+            B = size(rng, scale * 300 * KiB)
             sh = shifts(rng, 2 * W)
             ins = inputs.allgather_inputs(W, B, seed)
             d_in = [DevBuf(B, fill=ins[r], shift=sh[r]) for r in range(W)]
@@ -110,7 +110,7 @@ def run_case(ref, seed):
             check(d_out, ref.allgather(ins), what)
             check(d_in, ins, what + " (sources)")
         elif op == "alltoall":
-            C = np.array([[size(rng, 40 * KiB) for _ in range(W)] for _ in range(W)], dtype=np.uint64)
+            C = np.array([[size(rng, scale * 40 * KiB) for _ in range(W)] for _ in range(W)], dtype=np.uint64)
             ins = inputs.alltoall_inputs(C, seed)
             want = ref.alltoall(ins, C)
             sh = shifts(rng, 2 * W)
@@ -121,7 +121,7 @@ def run_case(ref, seed):
             finish(mode, before)
             check(d_out, want, what)
         elif op == "broadcast":
-            k, n = int(rng.integers(1, 20)), size(rng, 600 * KiB)
+            k, n = int(rng.integers(1, 20)), size(rng, scale * 600 * KiB)
             src = inputs.payload(rng, n)
             sh = shifts(rng, k + 1)
             d_src = DevBuf(n, fill=src, shift=sh[0])
@@ -132,7 +132,7 @@ def run_case(ref, seed):
             check(d_dst, ref.broadcast(src, k), what)
         elif op == "batch":
             n = int(rng.choice([1, 3, 8, 9, 40, 64, 65, 300, 700]))
-            arena, descs = inputs.mixed_batch(n, int(rng.choice([200, 5000, 120000])), 24 << 20, seed=seed,
+            arena, descs = inputs.mixed_batch(n, int(rng.choice([200, 5000, 120000])) * (scale if n <= 65 else 1), scale * (24 << 20), seed=seed,
                                               shared_sources=float(rng.choice([0.0, 0.0, 0.4])))
             want = ref.batch_copy([arena.copy()], [(0, s, 0, d, m) for s, d, m in descs])[0]
             d = DevBuf(arena.size, fill=arena)
@@ -142,7 +142,7 @@ def run_case(ref, seed):
             check([d], [want], what)
         elif op == "swap":
             n = int(rng.choice([1, 5, 30, 70, 200]))
-            arena, descs = inputs.swap_batch(n, max(1, size(rng, 30 * KiB)), 16 << 20, seed=seed,
+            arena, descs = inputs.swap_batch(n, max(1, size(rng, (scale if n <= 70 else 1) * 30 * KiB)), scale * (16 << 20), seed=seed,
                                              align=int(rng.choice([1, 4, 16, 256])))
             want = ref.batch_swap([arena.copy()], [(0, a, 0, b, m) for a, b, m in descs])[0]
             d = DevBuf(arena.size, fill=arena)
@@ -151,7 +151,7 @@ def run_case(ref, seed):
             finish(mode, before)
             check([d], [want], what)
         elif op == "inplace":
-            c = size(rng, 100 * KiB)
+            c = size(rng, scale * 100 * KiB)
             bufs = inputs.alltoall_inputs(inputs.uniform_chunks(W, c), seed=seed)
             d = [DevBuf(W * c, fill=bufs[i]) for i in range(W)]
             sync()
@@ -160,7 +160,7 @@ def run_case(ref, seed):
             check(d, ref.alltoall_inplace(bufs, c), what)
         elif op == "token":
             row = int(rng.choice([16, 48, 100, 1024, 1040, 4097, 14336]))
-            top = int(rng.choice([3, 40, 200]))
+            top = int(rng.choice([3, 40, 200])) * (4 if scale > 1 else 1)
             counts = [int(rng.integers(0, top)) for _ in range(W)]
             ins = inputs.token_rows(W, counts, row, seed=seed)
             dest = inputs.moe_token_destinations(W, counts, seed=seed + 1, n_experts=16 * W, top_k=int(rng.integers(1, min(8, W) + 1)))
@@ -204,6 +204,17 @@ N_CASES = int(os.environ.get("DL_TEST_RANDOM_CASES", "240"))
 def test_random_requests(ref, first):
     for seed in range(first, min(first + 20, N_CASES)):
         run_case(ref, seed)
+
+
+N_LARGE = int(os.environ.get("DL_TEST_RANDOM_LARGE_CASES", "24"))
+
+
+@pytest.mark.parametrize("first", range(0, N_LARGE, 8))
+def test_random_requests_large(ref, first):
+    """The same draws with sizes up to 16 times larger: across the thresholds of the store policies, of the row
+    kernel over staged tables and of the armed grid's cap."""
+    for seed in range(first, min(first + 8, N_LARGE)):
+        run_case(ref, 1_000_000 + seed, scale=16)
 
 
 @pytest.mark.parametrize("seed", [1, 2, 3])
