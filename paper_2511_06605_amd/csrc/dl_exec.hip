@@ -213,6 +213,18 @@ __device__ __forceinline__ void dl_arm_finish(const dl_arm &a, uint32_t go)
 template <class Item, int NMAX, bool ROWS>
 __global__ void __launch_bounds__(512) dl_armed_list_kernel(const dl_klist<Item, NMAX> p, const dl_arm a)
 {
+    {
+        // Before the wait: read what the workgroup's first tile will need from the list, so that after the
+        // doorbell those scalar loads hit the scalar cache instead of going to memory one after the other.
+        uint32_t first;
+        const uint32_t d = dl_find_item(p, blockIdx.x, &first);
+        uint64_t touched = first + p.n + p.tile_end[p.n - 1];
+        if (d < p.n) {
+            const Item &it = p.item[d];
+            touched += (uint64_t)it.src + it.bytes + (uint64_t)dl_item_dst(it, 0) + (uint64_t)dl_item_dst(it, DL_FAN - 1);
+        }
+        asm volatile("" ::"s"(touched));
+    }
     const uint32_t go = dl_arm_wait(a);
     if (go == DL_GO_RUN) {
         const uint32_t total = p.tile_end[p.n - 1];
