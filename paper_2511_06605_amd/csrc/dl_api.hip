@@ -289,7 +289,7 @@ int run_in_mode(void *stream, Launch launch)
     }
     bool launched = false;
     const int rc = launch(hs, armp, &launched);
-    if (armp && rc == DL_OK && launched) dl_armed_commit();
+    if (armp && rc == DL_OK && launched) dl_armed_commit(g_dl.armed_words);
     return rc;
 }
 

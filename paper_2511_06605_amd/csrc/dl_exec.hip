@@ -173,6 +173,12 @@ __device__ __forceinline__ void dl_arm_finish(const dl_arm &a, uint32_t go)
     if (a.nowait && blockIdx.x == 0 && threadIdx.x == 0) dl_arm_housekeeping(a);
     dl_drain_stores();
     __syncthreads();
+    if (threadIdx.x == 0 && a.own_word) {
+        // a small grid: the host waits for one word per workgroup, no count in between
+        __hip_atomic_store(a.done + blockIdx.x, a.ticket | (go == DL_GO_RUN ? 0ull : DL_DONE_SKIPPED), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_SYSTEM);
+        return;
+    }
     if (threadIdx.x == 0) {
         const uint32_t grid = gridDim.x;
         const bool flat = grid <= DL_ARM_FLAT_MAX;  // few enough to count at one word without queueing there
@@ -360,6 +366,8 @@ int launch_klist(const Item *items, size_t n, const uint64_t *tile_end, const dl
         dl_arm a = *arm;
         const uint32_t g = armed_grid(grid, sh.block_threads);
         a.direct = g <= ARMED_DIRECT_MAX ? 1u : 0u;
+        a.own_word = g <= DL_DONE_WORDS && !a.trace_host ? 1u : 0u;  // the stamps come from the last arriver
+        g_dl.armed_words = a.own_word ? g : 1u;
         if (sh.rows)
             hipLaunchKernelGGL((dl_armed_list_kernel<Item, NMAX, true>), dim3(g), dim3(sh.block_threads), 0, stream, p, a);
         else
@@ -540,6 +548,8 @@ int launch_table(const Item *items, size_t n, dl_launch_shape sh, hipStream_t st
             dl_arm a = *arm;
             const uint32_t g = armed_grid(m, sh.block_threads);
             a.direct = g <= ARMED_DIRECT_MAX ? 1u : 0u;
+            a.own_word = g <= DL_DONE_WORDS && !a.trace_host ? 1u : 0u;
+            g_dl.armed_words = a.own_word ? g : 1u;
             hipLaunchKernelGGL((dl_armed_table_kernel<Item>), dim3(g), dim3(sh.block_threads), 0, stream, slot,
                                (uint32_t)m, sh.tile_bytes, sh.split, a);
         } else {

@@ -17,6 +17,7 @@ struct dl_state {
     int validate = 0;
     int last_hip = 0;
     int trace = 0;  // armed kernels record phase stamps
+    uint32_t armed_words = 0;  // completion words the armed kernel launched last reports in (see dl_arm::own_word)
     dl_config cfg{};
 };
 extern dl_state g_dl;
@@ -59,10 +60,15 @@ struct dl_arm {
     uint32_t direct;        // 1: every workgroup polls the host doorbell itself
     uint32_t max_spins;     // backstop that does not depend on the clock: give up after this many polls
     uint32_t nowait;        // 1: no doorbell, copy at once (DL_MODE_SIGNAL); the completion side is unchanged
+    // 1: a grid of at most DL_DONE_WORDS workgroups, each of which reports in a completion word of its own
+    // (done[blockIdx.x]) as soon as its stores have drained: no arrival count on the way to the host, which
+    // waits for all of the grid's words.  0: arrivals are counted and the last workgroup writes done[0].
+    uint32_t own_word;
     // Phase stamps (device wall-clock ticks), null unless tracing is on: host-coherent, 4 words: doorbell seen,
     // first copy begins (the polling workgroup's), last copy ends (the last arriver's), completion issued
     uint64_t *trace_host;
 };
+constexpr uint32_t DL_DONE_WORDS = 16;  // completion words per slot (two cache lines of host memory)
 constexpr uint32_t DL_ARM_GROUPS = 16;  // workgroup b belongs to group b % DL_ARM_GROUPS
 constexpr uint32_t DL_ARM_FLAT_MAX = 64;  // grids up to this size count their arrivals at one word (0.5 us less than two levels; 256 arrivals at one word: 1.3 us more)
 constexpr uint32_t DL_ARM_STRIDE = 4352;  // flags and counters sit 4 KiB + 256 B apart: separate lines and memory channels
@@ -106,4 +112,4 @@ int dl_dispatch_on_device(const void *const *in, void *const *out, int W, const 
 // dl_prelaunch.hip: tickets, doorbell and completion words of armed requests.
 bool dl_armed_ready();
 int dl_armed_begin(dl_arm *arm, hipStream_t *stream);  // next ticket's words; picks the library stream if *stream is null
-void dl_armed_commit();                                // the ticket of the last dl_armed_begin was launched
+void dl_armed_commit(uint32_t done_words);             // the ticket of the last dl_armed_begin was launched and reports in that many words

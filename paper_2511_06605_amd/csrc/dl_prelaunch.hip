@@ -26,7 +26,9 @@ struct arm_host {  // pinned, host-coherent
     uint64_t bell;    // host -> device: every ticket <= bell may run
     uint64_t cancel;  // host -> device: every ticket <= cancel gives up
     uint64_t pad[6];
-    uint64_t done[SLOTS];   // device -> host: ticket (| DL_DONE_SKIPPED) of the last request finished in the slot
+    // device -> host: ticket (| DL_DONE_SKIPPED) of the last request finished in the slot; a request reports
+    // in word 0 or, if its grid is small, in one word per workgroup (arm_state::words)
+    uint64_t done[SLOTS][DL_DONE_WORDS];
     uint64_t armed[SLOTS];  // device -> host: ticket of the last request seen resident in the slot
     uint64_t trace[SLOTS][4];  // device -> host, when tracing: phase stamps of the slot's last request (device ticks)
     uint64_t ping[2];       // clock calibration: host -> device round number, device -> host its clock at that round
@@ -43,6 +45,7 @@ struct arm_state {
     arm_dev *dev = nullptr;
     hipStream_t stream = nullptr;
     uint64_t seq = 0;  // last ticket issued
+    uint32_t words[SLOTS] = {};  // completion words that the slot's current request reports in
     uint64_t clock_khz = 100000;
 } g_arm;
 
@@ -55,20 +58,40 @@ uint64_t now_ns()
 
 inline uint64_t load_word(const uint64_t *p) { return __atomic_load_n(p, __ATOMIC_ACQUIRE); }
 
-// Spin until `word` holds `ticket` or a later one (slots are reused in ticket order).
-int wait_word(const uint64_t *word, uint64_t ticket, uint64_t timeout_ns, uint64_t *seen)
+// Spin until each of the `count` words holds `ticket` or a later one (slots are reused in ticket
+// order).  *seen: the ticket, with DL_DONE_SKIPPED if any of the words that hold exactly it says so.
+int wait_words(const uint64_t *words, uint32_t count, uint64_t ticket, uint64_t timeout_ns, uint64_t *seen)
 {
     const uint64_t t0 = now_ns();
+    uint32_t have = 0;  // words 0 .. have-1 have been seen complete
+    uint64_t skipped = 0;
     for (uint32_t spins = 1;; ++spins) {
-        const uint64_t v = load_word(word);
-        if ((v & ~DL_DONE_SKIPPED) >= ticket) {
-            if (seen) *seen = v;
+        while (have < count) {
+            const uint64_t v = load_word(words + have);
+            if ((v & ~DL_DONE_SKIPPED) < ticket) break;
+            if ((v & ~DL_DONE_SKIPPED) == ticket) skipped |= v & DL_DONE_SKIPPED;
+            ++have;
+        }
+        if (have == count) {
+            if (seen) *seen = ticket | skipped;
             return DL_OK;
         }
         if (timeout_ns == 0) return DL_ERR_TIMEOUT;
         _mm_pause();
         if ((spins & 63u) == 0 && now_ns() - t0 >= timeout_ns) return DL_ERR_TIMEOUT;
     }
+}
+
+int wait_word(const uint64_t *word, uint64_t ticket, uint64_t timeout_ns, uint64_t *seen)
+{
+    return wait_words(word, 1, ticket, timeout_ns, seen);
+}
+
+// Completion of request `ticket`, which must be one of the last SLOTS issued.
+int wait_done(uint64_t ticket, uint64_t timeout_ns, uint64_t *seen)
+{
+    const uint32_t slot = (uint32_t)(ticket % SLOTS);
+    return wait_words(g_arm.host->done[slot], g_arm.words[slot] ? g_arm.words[slot] : 1u, ticket, timeout_ns, seen);
 }
 
 // Upper bound, in ns, on how long an armed kernel can still be on the device
@@ -86,11 +109,12 @@ int dl_armed_begin(dl_arm *arm, hipStream_t *stream)
     const uint32_t slot = (uint32_t)(ticket % SLOTS);
     if (ticket > SLOTS) {
         // the slot's previous request must have left the device before its words are reused
-        const int rc = wait_word(&g_arm.host->done[slot], ticket - SLOTS, drain_ns(), nullptr);
+        const int rc = wait_done(ticket - SLOTS, drain_ns(), nullptr);
         if (rc != DL_OK) return rc;
     }
     arm->bell = &g_arm.host->bell;
-    arm->done = &g_arm.host->done[slot];
+    arm->done = g_arm.host->done[slot];
+    arm->own_word = 0;
     arm->armed = &g_arm.host->armed[slot];
     arm->go = (uint64_t *)g_arm.dev->go[slot];
     const uint32_t set = (uint32_t)(ticket / SLOTS) & 1u;
@@ -108,7 +132,11 @@ int dl_armed_begin(dl_arm *arm, hipStream_t *stream)
     return DL_OK;
 }
 
-void dl_armed_commit() { ++g_arm.seq; }
+void dl_armed_commit(uint32_t done_words)
+{
+    ++g_arm.seq;
+    g_arm.words[g_arm.seq % SLOTS] = done_words >= 1 && done_words <= DL_DONE_WORDS ? done_words : 1u;
+}
 
 extern "C" {
 
@@ -145,7 +173,7 @@ int dl_prelaunch_stop(void)
     int rc = DL_OK;
     const uint64_t first = g_arm.seq > SLOTS ? g_arm.seq - SLOTS + 1 : 1;
     for (uint64_t t = first; t <= g_arm.seq && rc == DL_OK; ++t)
-        rc = wait_word(&g_arm.host->done[t % SLOTS], t, drain_ns(), nullptr);
+        rc = wait_done(t, drain_ns(), nullptr);
     if (rc != DL_OK) return rc;  // words stay allocated: a kernel may still use them
     (void)hipStreamSynchronize(g_arm.stream);
     (void)hipStreamDestroy(g_arm.stream);
@@ -249,11 +277,11 @@ int dl_wait(uint64_t ticket, uint64_t timeout_ns)
     if (!g_arm.started) return DL_ERR_STATE;
     if (ticket == 0) return DL_OK;
     if (ticket > g_arm.seq) return DL_ERR_INVALID;
+    if (g_arm.seq - ticket >= SLOTS) return DL_OK;  // its slot has been reused since, which waited for it
     uint64_t seen = 0;
-    const int rc = wait_word(&g_arm.host->done[ticket % SLOTS], ticket, timeout_ns, &seen);
+    const int rc = wait_done(ticket, timeout_ns, &seen);
     if (rc != DL_OK) return rc;
-    if ((seen & ~DL_DONE_SKIPPED) == ticket && (seen & DL_DONE_SKIPPED)) return DL_ERR_EXPIRED;
-    return DL_OK;
+    return seen & DL_DONE_SKIPPED ? DL_ERR_EXPIRED : DL_OK;
 }
 
 }  // extern "C"

@@ -297,6 +297,28 @@ def test_many_requests_armed_at_once(ref, armed):
             assert np.array_equal(d_out[r].host(), want[r])
 
 
+def test_slots_reused_by_requests_with_other_completion_words(ref, armed):
+    """200 requests, more than three rounds over the 64 slots, their grids cycling through 1, 3, 13 and 40
+    workgroups, so that a slot's next request reports in fewer or more completion words than the one before;
+    waiting for a ticket whose slot has long been reused is not an error."""
+    sizes = [100, 10000, 100000, 160 * KiB]
+    srcs = {n: inputs.payload(np.random.default_rng(n), n) for n in sizes}
+    d_src = {n: DevBuf(n, fill=srcs[n]) for n in sizes}
+    d_dst = {n: DevBuf(n) for n in sizes}
+    sync()
+    first = None
+    for i in range(200):
+        n = sizes[(i * 7 + i // 5) % len(sizes)]
+        d_dst[n].view().zero_()
+        sync()
+        dl.dl_broadcast(d_src[n].ptr(), [d_dst[n].ptr()], n)
+        first = first or dl.dl_last_ticket()
+        fire()
+        assert np.array_equal(d_dst[n].host(), srcs[n]), (i, n)
+    dl.dl_wait(first)
+    dl.dl_wait(first + 100)
+
+
 def test_trigger_in_ticket_order(ref, armed):
     """Ringing for ticket t releases t and everything before it, nothing after it."""
     B = 2000
@@ -453,15 +475,18 @@ def test_signal_mode_completes_without_trigger_or_stream_sync(ref):
         dl.dl_prelaunch_stop()
 
 
-def test_untriggered_request_expires_and_copies_nothing(ref):
+@pytest.mark.parametrize("n", [3000, 100000, 1 * MiB])
+def test_untriggered_request_expires_and_copies_nothing(ref, n):
+    """One workgroup, a grid whose workgroups each report in a completion word of their own, and a grid whose
+    arrivals are counted."""
     dl.dl_set_config(arm_timeout_us=3000)
     try:
         dl.dl_prelaunch_start()
         dl.dl_set_mode(dl.DL_MODE_PRELAUNCH)
-        src = DevBuf(100000, fill=inputs.payload(np.random.default_rng(1), 100000))
-        dst = [DevBuf(100000) for _ in range(8)]
+        src = DevBuf(n, fill=inputs.payload(np.random.default_rng(1), n))
+        dst = [DevBuf(n) for _ in range(8)]
         sync()
-        dl.dl_broadcast(src.ptr(), [b.ptr() for b in dst], 100000)
+        dl.dl_broadcast(src.ptr(), [b.ptr() for b in dst], n)
         with pytest.raises(dl.DlError) as e:
             dl.dl_wait()                       # never triggered
         assert e.value.status == dl.DL_ERR_EXPIRED
@@ -470,7 +495,7 @@ def test_untriggered_request_expires_and_copies_nothing(ref):
         # a late doorbell does nothing, and the next request works
         dl.dl_trigger()
         dl.dl_set_config(arm_timeout_us=ARM_US)
-        dl.dl_broadcast(src.ptr(), [b.ptr() for b in dst], 100000)
+        dl.dl_broadcast(src.ptr(), [b.ptr() for b in dst], n)
         fire()
         for b in dst:
             assert np.array_equal(b.host(), src.host())
