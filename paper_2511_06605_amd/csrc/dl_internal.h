@@ -68,7 +68,7 @@ struct dl_arm {
     // first copy begins (the polling workgroup's), last copy ends (the last arriver's), completion issued
     uint64_t *trace_host;
 };
-constexpr uint32_t DL_DONE_WORDS = 16;  // completion words per slot (two cache lines of host memory)
+constexpr uint32_t DL_DONE_WORDS = 16;  // completion words per slot (two cache lines of host memory); with 32 or 64 words the host-side wait cost more than the count on the device
 constexpr uint32_t DL_ARM_GROUPS = 16;  // workgroup b belongs to group b % DL_ARM_GROUPS
 constexpr uint32_t DL_ARM_FLAT_MAX = 64;  // grids up to this size count their arrivals at one word (0.5 us less than two levels; 256 arrivals at one word: 1.3 us more)
 constexpr uint32_t DL_ARM_STRIDE = 4352;  // flags and counters sit 4 KiB + 256 B apart: separate lines and memory channels
