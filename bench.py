@@ -419,6 +419,34 @@ def token_case(args, dl, benchaid, inputs, torch, stream) -> int:
     return 0
 
 
+def alltoall_case(args, dl, benchaid, inputs, torch, stream) -> int:
+    """Only the all-to-all sweep (W = 8, uniform chunks 1 KiB .. 4 MiB, fp16) and the MoE dispatch all-to-all
+    (tokens per rank 16 / 128 / 512), every point with buffers of its own, --steps passes over all points with
+    one synchronisation per pass: for kernel traces."""
+    reqs, keep = [], []
+    for c in [KiB << i for i in range(13)]:
+        C = inputs.uniform_chunks(W, c)
+        ins = inputs.alltoall_inputs(C, seed=c.bit_length(), kind="fp16")
+        d_in = [torch.from_numpy(a).cuda() for a in ins]
+        d_out = [torch.empty(W * c, dtype=torch.uint8, device="cuda") for _ in range(W)]
+        reqs.append(benchaid.alltoall_request(d_in, d_out, C))
+        keep.append((d_in, d_out))
+    for T in (16, 128, 512):
+        C = inputs.moe_dispatch_chunks(W, T, seed=T)
+        ins = inputs.alltoall_inputs(C, seed=T + 1, kind="bf16")
+        d_in = [torch.from_numpy(a).cuda() for a in ins]
+        d_out = [torch.empty(int(C[:, j].sum()), dtype=torch.uint8, device="cuda") for j in range(W)]
+        reqs.append(benchaid.alltoall_request(d_in, d_out, C))
+        keep.append((d_in, d_out))
+    for _ in range(args.warmup + args.steps):
+        for r in reqs:
+            benchaid.issue(r, stream)
+        stream.synchronize()
+    dl.dl_shutdown()
+    print(json.dumps({"case": "alltoall", "passes": args.warmup + args.steps}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -427,7 +455,7 @@ def main() -> int:
     ap.add_argument("--max-bytes", type=int, default=64 * MiB, help="largest per-rank payload of the sweep")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline leg")
     ap.add_argument("--no-detail", action="store_true", help="skip per-size latency and comparison legs")
-    ap.add_argument("--case", choices=["sweep", "pmc", "token_dispatch"], default="sweep",
+    ap.add_argument("--case", choices=["sweep", "pmc", "token_dispatch", "alltoall"], default="sweep",
                     help="pmc: only --steps launches of the largest all-gather and of a plain 1 GiB copy "
                          "(the calibration kernel), for hardware-counter runs; token_dispatch: only the "
                          "token-granular MoE dispatch, for kernel traces")
@@ -457,6 +485,8 @@ def main() -> int:
         return pmc_case(args, dl, benchaid, torch, stream)
     if args.case == "token_dispatch":
         return token_case(args, dl, benchaid, inputs, torch, stream)
+    if args.case == "alltoall":
+        return alltoall_case(args, dl, benchaid, inputs, torch, stream)
 
     sizes = [B for B in (4 * KiB << i for i in range(15)) if B <= args.max_bytes]
     reqs, keep, check = {}, [], None
