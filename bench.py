@@ -575,6 +575,11 @@ def main() -> int:
             dl.dl_set_mode(dl.DL_MODE_SIGNAL)
             lat = benchaid.time_host(reqs[B], None, benchaid.WAIT_SIGNAL, warmup=50, iters=1000)
             row["signal_call_to_done_us"] = lat_stats(lat)
+            if W * B <= 16 * 8192:
+                # standby mode: the request is handed to a kernel that is already waiting (no launch in between)
+                dl.dl_set_mode(dl.DL_MODE_STANDBY)
+                lat = benchaid.time_host(reqs[B], None, benchaid.WAIT_SIGNAL, warmup=50, iters=1000)
+                row["standby_call_to_done_us"] = lat_stats(lat)
             dl.dl_set_mode(dl.DL_MODE_PRELAUNCH)
         # phase breakdown (the form of the paper's Fig. 4: one transfer split into control / schedule / copy / sync,
         # 4 KB .. 2 MB), medians in microseconds
@@ -613,6 +618,7 @@ def main() -> int:
             "prelaunch_trigger_to_done_p50": small["prelaunch_trigger_to_done_us"]["p50"],
             "prelaunch_arm_to_done_p50": small["prelaunch_arm_to_done_us"]["p50"],
             "signal_call_to_done_p50": small["signal_call_to_done_us"]["p50"],
+            "standby_call_to_done_p50": small["standby_call_to_done_us"]["p50"],
         }
 
     dl.dl_shutdown()

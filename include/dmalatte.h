@@ -56,8 +56,11 @@ typedef enum dl_status {
 typedef enum dl_mode {
     DL_MODE_ONESHOT = 0,   /* one kernel launch per call, ordered on `stream` */
     DL_MODE_PRELAUNCH = 1, /* one armed kernel per call, started by dl_trigger() */
-    DL_MODE_SIGNAL = 2     /* one kernel launch per call that starts at once and writes a completion word: the
+    DL_MODE_SIGNAL = 2,    /* one kernel launch per call that starts at once and writes a completion word: the
                               request has a ticket, dl_wait() observes its end without a stream synchronisation */
+    DL_MODE_STANDBY = 3    /* small requests are handed to a kernel that is already waiting on the device: no
+                              launch between the call and the copy (see "standby mode" below); the rest run as in
+                              DL_MODE_SIGNAL */
 } dl_mode;
 
 /* One copy of a batch: `bytes` bytes from device pointer src to device pointer dst. */
@@ -77,8 +80,8 @@ int dl_init(int device);
 /* Leave prelaunch mode if it was started, release the staging memory. */
 int dl_shutdown(void);
 
-/* Select how the operations are executed.  DL_MODE_PRELAUNCH and DL_MODE_SIGNAL
- * require dl_prelaunch_start() first (DL_ERR_STATE otherwise): both use its
+/* Select how the operations are executed.  Every mode but DL_MODE_ONESHOT
+ * requires dl_prelaunch_start() first (DL_ERR_STATE otherwise): they use its
  * completion words. */
 int dl_set_mode(int mode);
 int dl_get_mode(void);
@@ -202,6 +205,34 @@ int dl_alltoall_inplace(void *const *buf, int W, size_t chunk_bytes, void *strea
  * completion word (the analogue of the sync command that ends a queue of
  * copies, paper Sec. III-B2).  dl_wait() on its ticket returns about 3 us
  * earlier than a stream synchronisation would for the same kernel.
+ *
+ * Standby mode (DL_MODE_STANDBY) is prelaunch for requests that are not known
+ * ahead of time: the library keeps two generic kernels waiting on the device
+ * (16 workgroups each, on streams of its own).  A call whose lowered list is
+ * short enough (at most 8 copies or read-once/write-k copies, at most 16 tiles
+ * of 8 KiB: an all-gather of up to 16 KiB per rank at W = 8, a broadcast of up
+ * to 128 KiB, ...) writes that list where the waiting kernel will look for it
+ * (device memory, through the BAR, if the host can store there; else
+ * host-coherent memory) and rings that kernel's doorbell; the kernel reads
+ * the list, copies, and reports in the request's completion words.  The call
+ * takes a ticket as in signal mode and dl_wait() observes the end; `stream`
+ * plays no part, so everything the request reads must be complete before the
+ * call, and two requests are ordered only if the first was waited for.  A
+ * waiting kernel serves one request and ends; one that has waited 2 ms (or
+ * dl_config.arm_timeout_us, if that is shorter) gives up, so after an idle
+ * period no kernel of the library is on the device.  Requests that do not
+ * fit, or that find no kernel that is sure to be waiting still (fresh ones
+ * are armed at once), run as in DL_MODE_SIGNAL.
+ *
+ * Waiting kernels and hardware queues.  A kernel that waits (an armed request,
+ * a standby kernel) holds the hardware queue that its stream is mapped to, and
+ * the HIP runtime maps all streams of a process to a few hardware queues
+ * (GPU_MAX_HW_QUEUES, 4 by default): work on another stream that shares the
+ * queue starts only when the waiting kernel has ended, i.e. after its
+ * doorbell or at its limit.  With at most four streams in use (the default
+ * stream, the library's, the two of standby mode) every stream has a queue of
+ * its own; a process that uses more should raise GPU_MAX_HW_QUEUES, or keep
+ * to DL_MODE_SIGNAL, which never waits on the device.
  *
  * dl_prelaunch_start() allocates the doorbell and completion words and the
  * library's stream; dl_prelaunch_stop() cancels whatever is still armed, waits

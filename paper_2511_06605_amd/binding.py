@@ -29,6 +29,7 @@ DL_PLAN_FANOUT = 8
 DL_MODE_ONESHOT = 0
 DL_MODE_PRELAUNCH = 1
 DL_MODE_SIGNAL = 2
+DL_MODE_STANDBY = 3
 
 # every symbol include/dmalatte.h declares
 EXPORTS = [

@@ -298,6 +298,11 @@ int execute(const dl_plan_item *items, size_t n, void *stream)
     if (!g_dl.inited) return DL_ERR_STATE;
     if (n == 0) return DL_OK;
     if (g_dl.validate && first_hazard(items, n) >= 0) return DL_ERR_OVERLAP;
+    if (g_dl.mode == DL_MODE_STANDBY) {
+        bool taken = false;
+        const int rc = dl_standby_try(items, n, &taken);
+        if (rc != DL_OK || taken) return rc;
+    }
     bool all_plain = true;
     for (size_t i = 0; i < n; ++i) all_plain &= items[i].k == 1;
     return run_in_mode(stream, [&](hipStream_t hs, const dl_arm *armp, bool *launched) {
@@ -390,8 +395,18 @@ int dl_shutdown(void)
 
 int dl_set_mode(int mode)
 {
-    if (mode != DL_MODE_ONESHOT && mode != DL_MODE_PRELAUNCH && mode != DL_MODE_SIGNAL) return DL_ERR_INVALID;
+    if (mode != DL_MODE_ONESHOT && mode != DL_MODE_PRELAUNCH && mode != DL_MODE_SIGNAL && mode != DL_MODE_STANDBY)
+        return DL_ERR_INVALID;
     if (mode != DL_MODE_ONESHOT && !dl_armed_ready()) return DL_ERR_STATE;
+    if (mode == g_dl.mode) return DL_OK;
+    if (g_dl.mode == DL_MODE_STANDBY) {
+        const int rc = dl_standby_leave();
+        if (rc != DL_OK) return rc;
+    }
+    if (mode == DL_MODE_STANDBY) {
+        const int rc = dl_standby_enter();
+        if (rc != DL_OK) return rc;
+    }
     g_dl.mode = mode;
     return DL_OK;
 }

@@ -78,7 +78,7 @@ enum : uint32_t { DL_GO_WAIT = 0, DL_GO_RUN = 1, DL_GO_SKIP = 2 };
 // counters that the slot's next request will count on, and tell the host that the kernel is resident.
 __device__ __forceinline__ void dl_arm_housekeeping(const dl_arm &a)
 {
-    for (uint32_t g = 0; g <= DL_ARM_GROUPS; ++g)
+    for (uint32_t g = 0; a.arrive_clear && g <= DL_ARM_GROUPS; ++g)
         __hip_atomic_store((uint32_t *)((char *)a.arrive_clear + g * DL_ARM_STRIDE), 0u, __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_AGENT);
     __hip_atomic_store(a.armed, a.ticket, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
@@ -242,6 +242,49 @@ __global__ void __launch_bounds__(512) dl_armed_list_kernel(const dl_klist<Item,
         }
     }
     dl_arm_finish(a, go);
+}
+
+// What a standby executor reads from host memory once its doorbell has rung.  The two copies of the ticket
+// and the activation number let the executor refuse a record that is not the one its doorbell announced.
+struct dl_standby_rec {
+    uint64_t ticket_front;
+    uint64_t activation;  // which arming of this pool slot the record is for (the executor's doorbell value)
+    uint64_t *done;       // the request's completion words (host-coherent), DL_STANDBY_GRID of them
+    uint64_t rows;        // 1: every address and byte count is a multiple of 16 (the row path's precondition)
+    dl_klist<dl_fused_item, 8> list;
+    uint64_t ticket_back;
+};
+static_assert(sizeof(dl_standby_rec) <= DL_STANDBY_REC_BYTES && sizeof(dl_standby_rec) % 8 == 0, "record size");
+
+// Standby executor: a generic armed kernel (see dl_internal.h).  Its doorbell is its pool slot's, its "ticket"
+// the slot's activation number; the request's own ticket and completion words come with the record.
+__global__ void __launch_bounds__(DL_STANDBY_THREADS) dl_standby_kernel(const dl_standby_rec *rec_host, const dl_arm a)
+{
+    constexpr uint32_t VEC = (uint32_t)((sizeof(dl_standby_rec) + 15) / 16);
+    static_assert(VEC <= DL_STANDBY_THREADS, "one 16-byte load per thread fetches the record");
+    __shared__ dl_u32x4 raw[VEC];
+    if (dl_arm_wait(a) != DL_GO_RUN) return;  // cancelled or never used: no request, nothing to report
+    // the record was complete before the doorbell was rung; these loads go to host memory, past every cache
+    if (threadIdx.x < VEC) raw[threadIdx.x] = dl_ld<DL_POL_COHERENT>(dl_global<dl_u32x4>(rec_host) + threadIdx.x);
+    __syncthreads();
+    const dl_standby_rec &rec = *reinterpret_cast<const dl_standby_rec *>(raw);
+    const bool ok = rec.ticket_front != 0 && rec.ticket_front == rec.ticket_back && rec.activation == a.ticket &&
+                    rec.done != nullptr && rec.list.n >= 1 && rec.list.n <= 8 && rec.list.tile_bytes == DL_STANDBY_TILE &&
+                    rec.list.split == 1 && rec.list.tile_end[rec.list.n - 1] <= gridDim.x;
+    if (!ok) return;  // not the announced record: touch nothing (the host's wait for the request times out)
+    if (blockIdx.x < rec.list.tile_end[rec.list.n - 1]) {
+        if (rec.rows)
+            dl_run_rows<DL_POL_COHERENT>(rec.list, blockIdx.x);
+        else
+            dl_run_tile<DL_POL_COHERENT>(rec.list, blockIdx.x);
+    }
+    dl_arm f = a;
+    f.done = rec.done;
+    f.ticket = rec.ticket_front;
+    f.own_word = 1;
+    f.nowait = 0;
+    f.trace_host = nullptr;
+    dl_arm_finish(f, DL_GO_RUN);
 }
 
 template <class Item>
@@ -683,6 +726,50 @@ int dl_exec_fused(const dl_fused_item *items, size_t n, hipStream_t stream, cons
 int dl_exec_swap(const dl_swap_item *items, size_t n, hipStream_t stream, const dl_arm *arm, bool *launched)
 {
     return exec_list(items, n, stream, arm, launched);
+}
+
+bool dl_standby_fill(void *rec_host, const dl_plan_item *items, size_t n, uint64_t activation, uint64_t ticket,
+                     uint64_t *done)
+{
+    const dl_config &c = g_dl.cfg;
+    if (n == 0 || n > 8 || c.tile_bytes || c.block_threads || c.max_blocks || c.armed_blocks) return false;
+    static_assert(sizeof(dl_plan_item) == sizeof(dl_fused_item), "plan items are fused items");
+    const dl_fused_item *it = reinterpret_cast<const dl_fused_item *>(items);
+    dl_standby_rec r;
+    memset(&r, 0, sizeof r);
+    uint64_t acc = 0;
+    r.rows = 1;
+    for (size_t i = 0; i < 8; ++i) {
+        if (i < n) {
+            acc += dl_item_tiles(it[i], DL_STANDBY_TILE);
+            r.list.item[i] = it[i];
+            if (!item_aligned16(it[i])) r.rows = 0;
+        }
+        r.list.tile_end[i] = i < n ? (uint32_t)acc : 0xFFFFFFFFu;
+    }
+    if (acc == 0 || acc > DL_STANDBY_GRID) return false;  // one tile per workgroup, one pass
+    r.list.n = (uint32_t)n;
+    r.list.tile_bytes = DL_STANDBY_TILE;
+    r.list.split = 1;
+    r.list.split_log2 = 0;
+    r.list.wpg_log2 = log2u(DL_STANDBY_THREADS / 64u);
+    r.ticket_front = r.ticket_back = ticket;
+    r.activation = activation;
+    r.done = done;
+    // the record may live in device memory mapped write-combined: plain 8-byte stores in ascending order
+    uint64_t words[sizeof r / 8];
+    memcpy(words, &r, sizeof r);
+    volatile uint64_t *out = (volatile uint64_t *)rec_host;
+    for (size_t q = 0; q < sizeof r / 8; ++q) out[q] = words[q];
+    return true;
+}
+
+int dl_standby_launch(const void *rec_host, const dl_arm *a, hipStream_t stream)
+{
+    hipLaunchKernelGGL(dl_standby_kernel, dim3(DL_STANDBY_GRID), dim3(DL_STANDBY_THREADS), 0, stream,
+                       (const dl_standby_rec *)rec_host, *a);
+    DL_HIP(hipGetLastError());
+    return DL_OK;
 }
 
 int dl_launch_fused_rows_table(const dl_fused_item *dev_items, uint32_t n, uint64_t item_bytes, hipStream_t stream)

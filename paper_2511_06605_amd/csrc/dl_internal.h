@@ -59,7 +59,7 @@ struct dl_arm {
     uint64_t margin_ticks;  // extra time a non-polling workgroup grants the polling one
     uint32_t direct;        // 1: every workgroup polls the host doorbell itself
     uint32_t max_spins;     // backstop that does not depend on the clock: give up after this many polls
-    uint32_t nowait;        // 1: no doorbell, copy at once (DL_MODE_SIGNAL); the completion side is unchanged
+    uint32_t nowait;        // 1: no doorbell, copy at once (DL_MODE_SIGNAL, and what DL_MODE_STANDBY cannot hand to an executor); the completion side is unchanged
     // 1: a grid of at most DL_DONE_WORDS workgroups, each of which reports in a completion word of its own
     // (done[blockIdx.x]) as soon as its stores have drained: no arrival count on the way to the host, which
     // waits for all of the grid's words.  0: arrivals are counted and the last workgroup writes done[0].
@@ -108,6 +108,27 @@ int dl_launch_fused_rows_table(const dl_fused_item *dev_items, uint32_t n, uint6
 // nothing was enqueued and the caller lowers on the host.
 int dl_dispatch_on_device(const void *const *in, void *const *out, int W, const uint32_t *tokens, size_t row_bytes,
                           const uint8_t *dest, hipStream_t stream, bool *taken);
+
+// Standby executors (DL_MODE_STANDBY): armed kernels that wait, not for a request that is known already, but for
+// any small request.  The host writes the request's copy list into a record in host-coherent memory and rings
+// the executor's own doorbell; the executor reads the record, copies, and reports in the request's completion
+// words like a small armed grid does (one word per workgroup).  An executor serves one request and ends; the
+// library keeps DL_STANDBY_POOL of them armed, each on a stream of its own.
+constexpr int DL_STANDBY_POOL = 2;
+constexpr uint32_t DL_STANDBY_GRID = 16;      // workgroups of an executor (= completion words of its request)
+constexpr uint32_t DL_STANDBY_THREADS = 512;
+constexpr uint32_t DL_STANDBY_TILE = 8192;     // one 1 KiB row per wavefront
+constexpr size_t DL_STANDBY_REC_BYTES = 1024;  // room for the record
+constexpr uint32_t DL_STANDBY_IDLE_US = 2000;  // an executor that has waited this long gives up (or the arm limit, if shorter)
+// dl_exec.hip: write the record of a request that fits an executor (at most 8 items and DL_STANDBY_GRID tiles;
+// default tunables); false if it does not fit.  Launch an executor that will read that record.
+bool dl_standby_fill(void *rec_host, const dl_plan_item *items, size_t n, uint64_t activation, uint64_t ticket,
+                     uint64_t *done);
+int dl_standby_launch(const void *rec_host, const dl_arm *a, hipStream_t stream);
+// dl_prelaunch.hip: hand the request to a waiting executor if it fits and one is fresh; *taken says whether.
+int dl_standby_try(const dl_plan_item *items, size_t n, bool *taken);
+int dl_standby_enter();  // arm the pool
+int dl_standby_leave();  // cancel what is armed and wait until it has left the device
 
 // dl_prelaunch.hip: tickets, doorbell and completion words of armed requests.
 bool dl_armed_ready();

@@ -32,11 +32,19 @@ struct arm_host {  // pinned, host-coherent
     uint64_t armed[SLOTS];  // device -> host: ticket of the last request seen resident in the slot
     uint64_t trace[SLOTS][4];  // device -> host, when tracing: phase stamps of the slot's last request (device ticks)
     uint64_t ping[2];       // clock calibration: host -> device round number, device -> host its clock at that round
+    // standby executors, per pool slot: {doorbell = activation number, cancel} side by side, the "resident" word,
+    // and the record the executor reads after its doorbell
+    uint64_t sb_bell[DL_STANDBY_POOL][2];
+    uint64_t sb_resident[DL_STANDBY_POOL];
+    uint64_t sb_pad[8 - (DL_STANDBY_POOL % 8)];
+    alignas(16) uint8_t sb_rec[DL_STANDBY_POOL][DL_STANDBY_REC_BYTES];
 };
+static_assert(offsetof(arm_host, sb_bell) % 16 == 0 && offsetof(arm_host, sb_rec) % 16 == 0, "16-byte loads");
 
 struct arm_dev {  // device memory; every flag and counter in a cache line of its own
     uint8_t go[SLOTS][DL_ARM_GROUPS * DL_ARM_STRIDE];
     uint8_t arrive[SLOTS][2][(DL_ARM_GROUPS + 1) * DL_ARM_STRIDE];  // two sets per slot, see dl_arm
+    uint8_t sb_go[DL_STANDBY_POOL][DL_ARM_GROUPS * DL_ARM_STRIDE];  // fan-out flags of the standby executors
 };
 
 struct arm_state {
@@ -46,6 +54,14 @@ struct arm_state {
     hipStream_t stream = nullptr;
     uint64_t seq = 0;  // last ticket issued
     uint32_t words[SLOTS] = {};  // completion words that the slot's current request reports in
+    // standby pool: a stream per executor, when the executor armed last was armed, the ticket the slot served
+    // last, and the slot that takes the next request
+    bool standby = false;
+    hipStream_t sb_stream[DL_STANDBY_POOL] = {};
+    uint64_t sb_armed_at[DL_STANDBY_POOL] = {};
+    uint64_t sb_limit_ns[DL_STANDBY_POOL] = {};  // the arm limit that executor was given
+    uint64_t sb_ticket[DL_STANDBY_POOL] = {};
+    int sb_next = 0;
     uint64_t clock_khz = 100000;
 } g_arm;
 
@@ -96,6 +112,15 @@ int wait_done(uint64_t ticket, uint64_t timeout_ns, uint64_t *seen)
 
 // Upper bound, in ns, on how long an armed kernel can still be on the device
 // once it has started: arm limit + margin + slack for the copy.
+// limits of a kernel that is armed now
+void arm_limits(dl_arm *arm, uint32_t limit_us)
+{
+    arm->limit_ticks = (uint64_t)limit_us * g_arm.clock_khz / 1000ull;
+    arm->margin_ticks = 5000ull * g_arm.clock_khz / 1000ull;  // 5 ms
+    // a poll takes well over 100 ns (a host-link round trip, or a sleep plus a device-memory load)
+    arm->max_spins = (limit_us + 5000u) * 10u;
+}
+
 uint64_t drain_ns() { return ((uint64_t)g_dl.cfg.arm_timeout_us + 5000ull) * 1000ull + 2000000000ull; }
 
 }  // namespace
@@ -121,15 +146,177 @@ int dl_armed_begin(dl_arm *arm, hipStream_t *stream)
     arm->arrive = (uint32_t *)g_arm.dev->arrive[slot][set];
     arm->arrive_clear = (uint32_t *)g_arm.dev->arrive[slot][set ^ 1u];
     arm->ticket = ticket;
-    arm->limit_ticks = (uint64_t)g_dl.cfg.arm_timeout_us * g_arm.clock_khz / 1000ull;
-    arm->margin_ticks = 5000ull * g_arm.clock_khz / 1000ull;  // 5 ms
+    arm_limits(arm, g_dl.cfg.arm_timeout_us);
     arm->direct = 0;
-    arm->nowait = g_dl.mode == DL_MODE_SIGNAL ? 1u : 0u;
-    // a poll takes well over 100 ns (a host-link round trip, or a sleep plus a device-memory load)
-    arm->max_spins = (g_dl.cfg.arm_timeout_us + 5000u) * 10u;
+    arm->nowait = g_dl.mode == DL_MODE_PRELAUNCH ? 0u : 1u;  // signal mode, and what standby mode launches itself
     arm->trace_host = g_dl.trace ? g_arm.host->trace[slot] : nullptr;
     if (!*stream) *stream = g_arm.stream;
     return DL_OK;
+}
+
+namespace {
+
+// Where the records live.  With a large BAR the host can store into device memory: the record is pushed there
+// (posted writes, which the link delivers before the completion of the read that shows the executor its
+// doorbell), and the executor finds it in device memory instead of fetching it over the link (1 us less).  The
+// allocation is made once per process and never freed.  Without a large BAR the records stay in host memory.
+uint8_t *g_sb_rec_dev = nullptr;
+bool g_sb_rec_dev_tried = false;
+constexpr size_t SB_DEV_STRIDE = 2 * DL_STANDBY_REC_BYTES;  // per pool slot: the record, then {doorbell, cancel}
+
+// Activation number of the executor armed last in each pool slot (0: none yet).  It only ever grows, over the
+// whole life of the process, because the doorbells in device memory outlive a prelaunch session.
+uint64_t g_sb_act[DL_STANDBY_POOL] = {};
+
+void *standby_rec(int e)
+{
+    if (g_sb_rec_dev) return g_sb_rec_dev + (size_t)e * SB_DEV_STRIDE;
+    return g_arm.host->sb_rec[e];
+}
+
+// The executor's {doorbell, cancel} pair.  With the records in device memory the doorbell is there too, behind
+// its record: the two are posted writes on one path, so whoever sees the doorbell finds the record.  (A doorbell
+// in host memory would be seen through a read completion, which the host's writes to the device need not precede.)
+uint64_t *standby_bell(int e)
+{
+    if (g_sb_rec_dev) return (uint64_t *)(g_sb_rec_dev + (size_t)e * SB_DEV_STRIDE + DL_STANDBY_REC_BYTES);
+    return g_arm.host->sb_bell[e];
+}
+
+void standby_store(uint64_t *word, uint64_t v)
+{
+    if (g_sb_rec_dev) {
+        _mm_sfence();  // everything written to the device so far leaves first
+        *(volatile uint64_t *)word = v;
+        _mm_sfence();
+    } else {
+        __atomic_store_n(word, v, __ATOMIC_RELEASE);
+    }
+}
+
+void standby_place_records()
+{
+    if (g_sb_rec_dev_tried) return;
+    g_sb_rec_dev_tried = true;
+    int large_bar = 0;
+    if (hipDeviceGetAttribute(&large_bar, hipDeviceAttributeIsLargeBar, g_dl.device) != hipSuccess || large_bar != 1) {
+        (void)hipGetLastError();
+        return;
+    }
+    void *p = nullptr;
+    if (hipExtMallocWithFlags(&p, DL_STANDBY_POOL * SB_DEV_STRIDE, hipDeviceMallocFinegrained) != hipSuccess) {
+        (void)hipGetLastError();
+        return;
+    }
+    if (hipMemset(p, 0, DL_STANDBY_POOL * SB_DEV_STRIDE) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
+        (void)hipGetLastError();
+        return;  // left allocated and unused
+    }
+    g_sb_rec_dev = (uint8_t *)p;
+}
+
+// A fresh executor in pool slot e, behind whatever that slot's stream still holds.
+int standby_arm(int e)
+{
+    dl_arm a;
+    memset(&a, 0, sizeof a);
+    a.bell = standby_bell(e);
+    a.armed = &g_arm.host->sb_resident[e];
+    a.go = (uint64_t *)g_arm.dev->sb_go[e];
+    a.ticket = ++g_sb_act[e];
+    // An executor waits for a request that nobody has promised, on a hardware queue that other streams of the
+    // process may have been mapped to as well (the runtime multiplexes streams on a few hardware queues): work on
+    // such a stream waits behind the executor.  So an executor gives up early, and idle periods longer than this
+    // end with no executor on the device; the first request afterwards takes the ordinary launch.
+    const uint32_t limit_us = g_dl.cfg.arm_timeout_us < DL_STANDBY_IDLE_US ? g_dl.cfg.arm_timeout_us : DL_STANDBY_IDLE_US;
+    arm_limits(&a, limit_us);
+    // A doorbell in device memory is polled by every workgroup.  One in host memory is polled by one workgroup
+    // per executor, which passes the word on: with every workgroup of both executors polling over the host link
+    // the reads queued up there and each doorbell took 2 us longer to be seen.
+    a.direct = g_sb_rec_dev ? 1u : 0u;
+    a.own_word = 1;
+    const int rc = dl_standby_launch(standby_rec(e), &a, g_arm.sb_stream[e]);
+    g_arm.sb_armed_at[e] = now_ns();
+    g_arm.sb_limit_ns[e] = (uint64_t)limit_us * 1000ull;
+    return rc;
+}
+
+// An executor may be handed a request only while it cannot have reached its arm limit: its clock starts when
+// it becomes resident, which is not before it was armed.
+bool standby_fresh(int e)
+{
+    const uint64_t limit_ns = g_arm.sb_limit_ns[e];
+    const uint64_t margin_ns = limit_ns / 4 < 2000000ull ? limit_ns / 4 : 2000000ull;
+    return g_sb_act[e] != 0 && now_ns() - g_arm.sb_armed_at[e] + margin_ns < limit_ns;
+}
+
+void standby_cancel(int e)
+{
+    if (g_sb_act[e]) standby_store(standby_bell(e) + 1, g_sb_act[e]);
+}
+
+}  // namespace
+
+int dl_standby_enter()
+{
+    if (!g_arm.started) return DL_ERR_STATE;
+    if (g_arm.standby) return DL_OK;
+    standby_place_records();
+    for (int e = 0; e < DL_STANDBY_POOL; ++e)
+        if (!g_arm.sb_stream[e]) DL_HIP(hipStreamCreateWithFlags(&g_arm.sb_stream[e], hipStreamNonBlocking));
+    for (int e = 0; e < DL_STANDBY_POOL; ++e) {
+        const int rc = standby_arm(e);
+        if (rc != DL_OK) return rc;
+    }
+    g_arm.sb_next = 0;
+    g_arm.standby = true;
+    return DL_OK;
+}
+
+int dl_standby_leave()
+{
+    if (!g_arm.started || !g_arm.standby) return DL_OK;
+    for (int e = 0; e < DL_STANDBY_POOL; ++e) standby_cancel(e);
+    for (int e = 0; e < DL_STANDBY_POOL; ++e) DL_HIP(hipStreamSynchronize(g_arm.sb_stream[e]));
+    g_arm.standby = false;
+    return DL_OK;
+}
+
+int dl_standby_try(const dl_plan_item *items, size_t n, bool *taken)
+{
+    *taken = false;
+    if (!g_arm.started || !g_arm.standby) return DL_OK;
+    const int e = g_arm.sb_next;
+    if (!standby_fresh(e)) {
+        // too old to be trusted with a request (it may be about to give up): replace it and any other that has
+        // aged as much, and let this request take the ordinary launch
+        for (int k = 0; k < DL_STANDBY_POOL; ++k) {
+            if (standby_fresh(k)) continue;
+            standby_cancel(k);
+            const int rc = standby_arm(k);
+            if (rc != DL_OK) return rc;
+        }
+        return DL_OK;
+    }
+    const uint64_t ticket = g_arm.seq + 1;
+    const uint32_t slot = (uint32_t)(ticket % SLOTS);
+    if (ticket > SLOTS) {
+        const int rc = wait_done(ticket - SLOTS, drain_ns(), nullptr);
+        if (rc != DL_OK) return rc;
+    }
+    // the record of this pool slot must have been read by the executor that served the slot's last request
+    if (g_arm.sb_ticket[e] && g_arm.seq - g_arm.sb_ticket[e] < SLOTS) {
+        const int rc = wait_done(g_arm.sb_ticket[e], drain_ns(), nullptr);
+        if (rc != DL_OK) return rc;
+    }
+    if (!dl_standby_fill(standby_rec(e), items, n, g_sb_act[e], ticket, g_arm.host->done[slot])) return DL_OK;
+    standby_store(standby_bell(e), g_sb_act[e]);  // the executor's doorbell, behind its record
+    __atomic_store_n(&g_arm.host->armed[slot], ticket, __ATOMIC_RELAXED);             // it was resident already
+    dl_armed_commit(DL_STANDBY_GRID);
+    g_arm.sb_ticket[e] = ticket;
+    g_arm.sb_next = (e + 1) % DL_STANDBY_POOL;
+    *taken = true;
+    return standby_arm(e);  // the replacement, queued behind the executor that is serving this request
 }
 
 void dl_armed_commit(uint32_t done_words)
@@ -168,6 +355,10 @@ int dl_prelaunch_start(void)
 int dl_prelaunch_stop(void)
 {
     if (!g_arm.started) return DL_ERR_STATE;
+    {
+        const int rc = dl_standby_leave();
+        if (rc != DL_OK) return rc;
+    }
     // every request still armed gives up; then wait until all of them have left the device
     __atomic_store_n(&g_arm.host->cancel, g_arm.seq, __ATOMIC_RELEASE);
     int rc = DL_OK;
@@ -177,6 +368,8 @@ int dl_prelaunch_stop(void)
     if (rc != DL_OK) return rc;  // words stay allocated: a kernel may still use them
     (void)hipStreamSynchronize(g_arm.stream);
     (void)hipStreamDestroy(g_arm.stream);
+    for (int e = 0; e < DL_STANDBY_POOL; ++e)
+        if (g_arm.sb_stream[e]) (void)hipStreamDestroy(g_arm.sb_stream[e]);
     (void)hipFree(g_arm.dev);
     (void)hipHostFree(g_arm.host);
     g_arm = arm_state{};

@@ -1,0 +1,224 @@
+"""GPU parity of standby mode (requests handed to a kernel that is already waiting on the device), run as a
+script in a process of its own: exit status 0 = every check held.
+
+Why its own process: a waiting kernel holds the hardware queue of its stream, and the HIP runtime maps all
+streams of a process to a few hardware queues.  In a process that has created more streams than there are
+queues (a long test session does) other work can land behind a waiting kernel and stall until that kernel gives
+up, which makes such a session slow, not wrong.  Here the streams are the default one, the library's and the
+two of standby mode: one hardware queue each.
+
+Every waiting kernel gives up by itself after 2 ms, so nothing stays on the device."""
+
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+import paper_2511_06605_amd as dl  # noqa: E402
+from paper_2511_06605_amd import inputs  # noqa: E402
+from paper_2511_06605_amd.inputs import KiB, MiB  # noqa: E402
+
+from gpu_util import DevBuf, stream, sync  # noqa: E402
+from oracle import ref  # noqa: E402
+
+ARM_US = 300_000
+
+
+class standby:
+    """A prelaunch session in standby mode."""
+
+    def __enter__(self):
+        dl.dl_set_config(arm_timeout_us=ARM_US)
+        dl.dl_prelaunch_start()
+        dl.dl_set_mode(dl.DL_MODE_STANDBY)
+
+    def __exit__(self, *exc):
+        dl.dl_set_mode(dl.DL_MODE_ONESHOT)
+        dl.dl_prelaunch_stop()
+
+
+def allgather(W, B, seed, shifts=None):
+    ins = inputs.allgather_inputs(W, B, seed)
+    shifts = shifts or [0] * (2 * W)
+    d_in = [DevBuf(B, fill=ins[r], shift=shifts[r]) for r in range(W)]
+    d_out = [DevBuf(W * B, shift=shifts[W + r]) for r in range(W)]
+    sync()
+    before = dl.dl_last_ticket()
+    dl.dl_allgather([b.ptr() for b in d_in], [b.ptr() for b in d_out], B)
+    assert dl.dl_last_ticket() == before + (1 if B else 0)
+    dl.dl_wait()
+    want = ref.allgather(ins)
+    for r in range(W):
+        assert np.array_equal(d_out[r].host(), want[r]), f"rank {r} (W={W}, B={B})"
+        assert d_out[r].guards_intact()
+
+
+def allgather_sizes():
+    """Requests that fit a waiting kernel (at most 8 items and 16 tiles of 8 KiB) and requests that do not
+    (more items, more tiles: they take the ordinary launch), with no other synchronisation than dl_wait."""
+    for W, B in [(8, 4096), (8, 1), (8, 1000), (8, 16 * KiB), (8, 16 * KiB + 16), (8, 64 * KiB), (8, 0),
+                 (3, 40000), (1, 100000), (9, 4096), (16, 512), (8, 1 * MiB)]:
+        with standby():
+            allgather(W, B, seed=W * 131 + B)
+
+
+def allgather_misaligned():
+    for shifts in ([5] * 8, [0, 4, 8, 12, 0, 4, 8, 12], [0, 1, 2, 3, 7, 9, 11, 13]):
+        with standby():
+            allgather(4, 9000, seed=3, shifts=shifts)
+
+
+def other_operations():
+    with standby():
+        # broadcast, 7 destinations, 100 KiB: one read-once/write-7 item, 13 tiles
+        src = inputs.payload(np.random.default_rng(1), 100 * KiB + 5)
+        d_src = DevBuf(src.size, fill=src)
+        d_dst = [DevBuf(src.size) for _ in range(7)]
+        sync()
+        dl.dl_broadcast(d_src.ptr(), [b.ptr() for b in d_dst], src.size)
+        dl.dl_wait()
+        for b in d_dst:
+            assert np.array_equal(b.host(), src) and b.guards_intact()
+        # a batch of 6 copies of unequal sizes and alignments
+        arena, descs = inputs.mixed_batch(6, 9000, 1 * MiB, seed=4)
+        want = ref.batch_copy([arena.copy()], [(0, s, 0, d, m) for s, d, m in descs])[0]
+        d = DevBuf(arena.size, fill=arena)
+        sync()
+        dl.dl_batch_copy([(d.ptr(int(s)), d.ptr(int(t)), int(m)) for s, t, m in descs])
+        dl.dl_wait()
+        assert np.array_equal(d.host(), want) and d.guards_intact()
+        # all-to-all between two ranks (4 chunks), and between eight (64 chunks: the ordinary launch)
+        for W in (2, 8):
+            C = inputs.random_chunks(W, 5000, seed=W, zero_frac=0.2)
+            ins = inputs.alltoall_inputs(C, seed=W + 1)
+            want = ref.alltoall(ins, C)
+            d_in = [DevBuf(a.size, fill=a) for a in ins]
+            d_out = [DevBuf(w.size) for w in want]
+            sync()
+            dl.dl_alltoall([b.ptr() for b in d_in], [b.ptr() for b in d_out], C)
+            dl.dl_wait()
+            for j in range(W):
+                assert np.array_equal(d_out[j].host(), want[j]) and d_out[j].guards_intact()
+        # an in-place all-to-all (swaps): never handed to a waiting kernel, same result
+        bufs = inputs.alltoall_inputs(inputs.uniform_chunks(4, 3000), seed=9)
+        d_buf = [DevBuf(a.size, fill=a) for a in bufs]
+        sync()
+        dl.dl_alltoall_inplace([b.ptr() for b in d_buf], 3000)
+        dl.dl_wait()
+        for b, w in zip(d_buf, ref.alltoall_inplace(bufs, 3000)):
+            assert np.array_equal(b.host(), w) and b.guards_intact()
+
+
+def many_requests_with_changing_sources():
+    """3000 requests in a row over the same buffers, sizes cycling between what a waiting kernel takes and what
+    it does not, the sources rewritten before every call and two receive buffers checked after every dl_wait."""
+    import torch
+    W = 8
+    sizes = [4 * KiB, 16 * KiB, 48 * KiB, 1000]
+    d_in = {B: [torch.zeros(B, dtype=torch.uint8, device="cuda") for _ in range(W)] for B in sizes}
+    d_out = {B: [torch.zeros(W * B, dtype=torch.uint8, device="cuda") for _ in range(W)] for B in sizes}
+    bad = torch.zeros(1, dtype=torch.int64, device="cuda")
+    with standby():
+        t0 = time.monotonic()
+        for it in range(3000):
+            B = sizes[it % len(sizes)]
+            for j in range(W):
+                d_in[B][j].fill_((it * 7 + j * 31) % 251)
+            sync()
+            dl.dl_allgather(d_in[B], d_out[B], B)
+            dl.dl_wait()
+            for r in (it % W, (it + 3) % W):
+                got = d_out[B][r].view(W, B)
+                want = torch.tensor([(it * 7 + j * 31) % 251 for j in range(W)], dtype=torch.uint8, device="cuda")
+                bad += (got != want[:, None]).sum()
+            if it % 500 == 499:
+                print(f"  {it + 1} requests, {time.monotonic() - t0:.1f} s", flush=True)
+        sync()
+    assert int(bad.item()) == 0
+
+
+def kernels_that_gave_up_are_replaced():
+    """While the caller idles the waiting kernels give up (2 ms, or the arm limit if that is shorter); the next
+    requests must still be served (by the ordinary launch, then by fresh kernels), and none may be lost."""
+    for limit_us in (ARM_US, 1000):
+        dl.dl_set_config(arm_timeout_us=limit_us)
+        try:
+            dl.dl_prelaunch_start()
+            dl.dl_set_mode(dl.DL_MODE_STANDBY)
+            for pause in (0.0, 0.02, 0.0, 0.0, 0.0008, 0.0012, 0.0016, 0.002, 0.0024, 0.02, 0.0):
+                time.sleep(pause)
+                allgather(8, 4096, seed=int(pause * 1e4))
+        finally:
+            dl.dl_set_mode(dl.DL_MODE_ONESHOT)
+            dl.dl_prelaunch_stop()
+            dl.dl_set_config(arm_timeout_us=ARM_US)
+
+
+def mode_switches_and_stop():
+    dl.dl_prelaunch_start()
+    try:
+        for mode in (dl.DL_MODE_STANDBY, dl.DL_MODE_SIGNAL, dl.DL_MODE_STANDBY, dl.DL_MODE_ONESHOT, dl.DL_MODE_STANDBY):
+            dl.dl_set_mode(mode)
+            ins = inputs.allgather_inputs(8, 4096, seed=mode)
+            d_in = [DevBuf(4096, fill=a) for a in ins]
+            d_out = [DevBuf(8 * 4096) for _ in range(8)]
+            sync()
+            dl.dl_allgather([b.ptr() for b in d_in], [b.ptr() for b in d_out], 4096, stream() if mode == dl.DL_MODE_ONESHOT else None)
+            if mode == dl.DL_MODE_ONESHOT:
+                sync()
+            else:
+                dl.dl_wait()
+            for r, w in zip(d_out, ref.allgather(ins)):
+                assert np.array_equal(r.host(), w)
+    finally:
+        dl.dl_prelaunch_stop()          # with kernels waiting: they are cancelled
+    assert dl.dl_get_mode() == dl.DL_MODE_ONESHOT
+    try:
+        dl.dl_set_mode(dl.DL_MODE_STANDBY)   # needs dl_prelaunch_start
+    except dl.DlError as e:
+        assert e.status == dl.DL_ERR_STATE
+    else:
+        raise AssertionError("standby mode accepted without a prelaunch session")
+
+
+def random_requests():
+    """The seeded random requests of test_gpu_random.py with standby mode among the modes drawn."""
+    import test_gpu_random as rnd
+    dl.dl_set_config(arm_timeout_us=ARM_US)
+    dl.dl_prelaunch_start()
+    try:
+        for seed in range(5000, 5000 + int(os.environ.get("DL_TEST_RANDOM_CASES", "150"))):
+            rnd.run_case(ref, seed, modes=("standby", "standby", "standby", "signal", "oneshot"))
+    finally:
+        dl.dl_set_mode(dl.DL_MODE_ONESHOT)
+        dl.dl_prelaunch_stop()
+
+
+CHECKS = [allgather_sizes, allgather_misaligned, other_operations, many_requests_with_changing_sources,
+          kernels_that_gave_up_are_replaced, mode_switches_and_stop, random_requests]
+
+
+def main():
+    import torch
+    assert torch.cuda.is_available()
+    torch.cuda.set_device(0)
+    ref.build()
+    dl.dl_init(0)
+    try:
+        for fn in CHECKS:
+            print(f"standby: {fn.__name__} ...", flush=True)
+            t0 = time.monotonic()
+            fn()
+            print(f"standby: {fn.__name__} ok ({time.monotonic() - t0:.2f} s)", flush=True)
+    finally:
+        dl.dl_shutdown()
+    print("standby: all ok", flush=True)
+
+
+if __name__ == "__main__":
+    main()

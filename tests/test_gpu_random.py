@@ -82,11 +82,14 @@ def check(bufs, want, what):
         assert b.guards_intact(), f"{what}: guard band of buffer {i} written"
 
 
-def run_case(ref, seed, scale=1):
+MODES = ("oneshot", "oneshot", "prelaunch", "signal")
+
+
+def run_case(ref, seed, scale=1, modes=MODES):
     import torch
     rng = np.random.default_rng(seed)
     op = str(rng.choice(["allgather", "alltoall", "broadcast", "batch", "swap", "inplace", "token", "fanout"]))
-    mode = str(rng.choice(["oneshot", "oneshot", "prelaunch", "signal"]))
+    mode = str(rng.choice(list(modes)))
     tun = dict(TUNABLES[int(rng.integers(0, len(TUNABLES)))])
     W = int(rng.choice([1, 2, 3, 4, 7, 8, 8, 8, 9, 16]))
     what = f"seed {seed}: {op}, W={W}, {mode}, {tun}"
@@ -94,7 +97,8 @@ def run_case(ref, seed, scale=1):
     base = dl.dl_get_config()
     saved = {f[0]: getattr(base, f[0]) for f in base._fields_}
     dl.dl_set_config(**tun)
-    dl.dl_set_mode({"oneshot": dl.DL_MODE_ONESHOT, "prelaunch": dl.DL_MODE_PRELAUNCH, "signal": dl.DL_MODE_SIGNAL}[mode])
+    dl.dl_set_mode({"oneshot": dl.DL_MODE_ONESHOT, "prelaunch": dl.DL_MODE_PRELAUNCH, "signal": dl.DL_MODE_SIGNAL,
+                    "standby": dl.DL_MODE_STANDBY}[mode])
     s_arg = st if mode == "oneshot" else None
     before = dl.dl_last_ticket()
     try:
