@@ -235,10 +235,9 @@ int standby_arm(int e)
     // the reads queued up there and each doorbell took 2 us longer to be seen.
     a.direct = g_sb_rec_dev ? 1u : 0u;
     a.own_word = 1;
-    const int rc = dl_standby_launch(standby_rec(e), &a, g_arm.sb_stream[e]);
-    g_arm.sb_armed_at[e] = now_ns();
+    g_arm.sb_armed_at[e] = now_ns();  // before the launch: the kernel's own clock starts later than this
     g_arm.sb_limit_ns[e] = (uint64_t)limit_us * 1000ull;
-    return rc;
+    return dl_standby_launch(standby_rec(e), &a, g_arm.sb_stream[e]);
 }
 
 // An executor may be handed a request only while it cannot have reached its arm limit: its clock starts when
@@ -311,12 +310,26 @@ int dl_standby_try(const dl_plan_item *items, size_t n, bool *taken)
     }
     if (!dl_standby_fill(standby_rec(e), items, n, g_sb_act[e], ticket, g_arm.host->done[slot])) return DL_OK;
     standby_store(standby_bell(e), g_sb_act[e]);  // the executor's doorbell, behind its record
+    const bool in_time = now_ns() - g_arm.sb_armed_at[e] + 100000ull < g_arm.sb_limit_ns[e];
     __atomic_store_n(&g_arm.host->armed[slot], ticket, __ATOMIC_RELAXED);             // it was resident already
     dl_armed_commit(DL_STANDBY_GRID);
     g_arm.sb_ticket[e] = ticket;
     g_arm.sb_next = (e + 1) % DL_STANDBY_POOL;
-    *taken = true;
-    return standby_arm(e);  // the replacement, queued behind the executor that is serving this request
+    if (in_time) {
+        *taken = true;
+        return standby_arm(e);  // the replacement, queued behind the executor that is serving this request
+    }
+    // This thread was held up between the age check and the doorbell, and the executor may have given up in the
+    // meantime, all of it or some of its workgroups.  Wait until it has left; if it did not finish the request,
+    // close that ticket by hand and let the request run again through the ordinary launch, under the next
+    // ticket: it has no swaps, so copying some of its bytes twice gives the same result.
+    DL_HIP(hipStreamSynchronize(g_arm.sb_stream[e]));
+    const int served = wait_done(ticket, 0, nullptr);
+    if (served != DL_OK)
+        for (uint32_t w = 0; w < DL_STANDBY_GRID; ++w)
+            __atomic_store_n(&g_arm.host->done[slot][w], ticket, __ATOMIC_RELEASE);
+    *taken = served == DL_OK;
+    return standby_arm(e);
 }
 
 void dl_armed_commit(uint32_t done_words)

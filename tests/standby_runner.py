@@ -159,6 +159,38 @@ def kernels_that_gave_up_are_replaced():
             dl.dl_set_config(arm_timeout_us=ARM_US)
 
 
+def requests_close_to_the_limit():
+    """With a limit of 150 us, requests that come some 20 .. 120 us apart find the waiting kernel young (handed
+    over), close to its limit (handed over, then the library makes sure that the kernel did serve it) or too old
+    (ordinary launch); every one of them must be served exactly as asked."""
+    import torch
+    W, B, SETS = 8, 4 * KiB, 5
+    d_in = [[torch.full((B,), 16 * k + j, dtype=torch.uint8, device="cuda") for j in range(W)] for k in range(SETS)]
+    want = [torch.tensor([16 * k + j for j in range(W)], dtype=torch.uint8, device="cuda")[:, None] for k in range(SETS)]
+    d_out = [torch.zeros(W * B, dtype=torch.uint8, device="cuda") for _ in range(W)]
+    bad = torch.zeros(1, dtype=torch.int64, device="cuda")
+    dl.dl_set_config(arm_timeout_us=150)
+    try:
+        dl.dl_prelaunch_start()
+        dl.dl_set_mode(dl.DL_MODE_STANDBY)
+        sync()
+        for it in range(1500):
+            t_end = time.perf_counter() + (it % 41) * 2.5e-6
+            while time.perf_counter() < t_end:
+                pass
+            k = it % SETS
+            dl.dl_allgather(d_in[k], d_out, B)
+            dl.dl_wait()
+            bad += (d_out[it % W].view(W, B) != want[k]).sum()
+            sync()   # the comparison has read the receive buffer before the next request rewrites it
+        sync()
+    finally:
+        dl.dl_set_mode(dl.DL_MODE_ONESHOT)
+        dl.dl_prelaunch_stop()
+        dl.dl_set_config(arm_timeout_us=ARM_US)
+    assert int(bad.item()) == 0
+
+
 def mode_switches_and_stop():
     dl.dl_prelaunch_start()
     try:
@@ -200,7 +232,7 @@ def random_requests():
 
 
 CHECKS = [allgather_sizes, allgather_misaligned, other_operations, many_requests_with_changing_sources,
-          kernels_that_gave_up_are_replaced, mode_switches_and_stop, random_requests]
+          kernels_that_gave_up_are_replaced, requests_close_to_the_limit, mode_switches_and_stop, random_requests]
 
 
 def main():

@@ -21,7 +21,7 @@ pytestmark = pytest.mark.gpu
 ARM_US = 300_000  # generous for a Python caller, still far below any watchdog
 
 
-@pytest.mark.skip(reason="a long-lived resident kernel (one launch serving many requests) ended a GPU box with a "
+@pytest.mark.skip(reason="a long-lived resident kernel (one launch serving many requests) ended its first run on a GPU with a "
                          "fault or hung queue; no cause could be shown from the code, so that variant was taken "
                          "out and must not run on a GPU.  Armed per-request kernels below replace it")
 def test_resident_kernel_variant_withdrawn():
