@@ -283,7 +283,7 @@ typedef struct dl_config {
     uint32_t fan_split;          /* sub-groups of a workgroup that share out the destinations of a fused copy: 1, 2 or 4; 0 = choose */
     uint32_t infer_broadcast;    /* 1: dl_batch_copy merges copies that share source and size into read-once/write-k copies; default 1 */
     uint32_t device_lowering;    /* 1: dl_token_dispatch with 512 tokens or more (W = 8, aligned rows, one-shot mode, validation off) sends only the mask to the device, which derives the copies itself; default 1 */
-    uint32_t reserved;
+    uint32_t table_push;         /* 1: the table of a long list (more copies than fit the kernel arguments) is written by the host straight into device memory, through the BAR, when the device exposes one that covers its memory and the table is short enough; 0: always through pinned host memory; default 1 */
     uint64_t write_through_max_bytes; /* requests moving at most this many bytes (read + written) use write-through stores; default 144 MiB */
 } dl_config;
 

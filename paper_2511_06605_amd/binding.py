@@ -75,7 +75,7 @@ class Config(ctypes.Structure):
         ("fan_split", ctypes.c_uint32),
         ("infer_broadcast", ctypes.c_uint32),
         ("device_lowering", ctypes.c_uint32),
-        ("reserved", ctypes.c_uint32),
+        ("table_push", ctypes.c_uint32),
         ("write_through_max_bytes", ctypes.c_uint64),
     ]
 

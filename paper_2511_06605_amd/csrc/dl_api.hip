@@ -375,6 +375,7 @@ int dl_init(int device)
     g_dl.cfg.fuse_broadcast = 1;
     g_dl.cfg.infer_broadcast = 1;
     g_dl.cfg.device_lowering = 1;
+    g_dl.cfg.table_push = 1;
     const int rc = dl_exec_init();
     if (rc != DL_OK) return rc;
     g_dl.inited = true;

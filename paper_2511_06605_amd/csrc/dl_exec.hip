@@ -11,6 +11,7 @@
 #include "dl_device.h"
 #include "dl_internal.h"
 
+#include <immintrin.h>
 #include <string.h>
 
 #include <type_traits>
@@ -26,17 +27,34 @@ __global__ void __launch_bounds__(512) dl_exec_rows_kernel(const dl_klist<Item, 
     dl_run_rows<POL>(p, blockIdx.x);
 }
 
+// Entry i of a table that the host wrote into device memory through the BAR just before the launch.  A line
+// of the table that used this memory before may still sit in a cache, so the entry is read past every cache,
+// once per workgroup (8 bytes per lane), and handed on through LDS.  Call with the whole workgroup.
+template <class Item>
+__device__ __forceinline__ const Item &dl_pushed_entry(const Item *items, uint32_t i)
+{
+    static_assert(sizeof(Item) % 8 == 0 && sizeof(Item) / 8 <= 64, "one 8-byte load per lane of the first wavefront");
+    __shared__ uint64_t raw[sizeof(Item) / 8];
+    if (threadIdx.x < sizeof(Item) / 8)
+        raw[threadIdx.x] = dl_ld<DL_POL_COHERENT>(dl_global<uint64_t>(items + i) + threadIdx.x);
+    __syncthreads();
+    return *reinterpret_cast<const Item *>(raw);
+}
+
 // Row path over a table of equally sized items in device memory (long lists: thousands of token
 // rows, hundreds of cache blocks): workgroup b works on item b / tiles_per_item, which every
-// workgroup of that item finds in the scalar cache.
-template <class Item, int POL>
+// workgroup of that item finds in the scalar cache.  PUSHED: see dl_pushed_entry.
+template <class Item, int POL, bool PUSHED = false>
 __global__ void __launch_bounds__(512) dl_exec_urows_kernel(const Item *__restrict__ items, uint32_t n,
                                                             uint32_t tiles_per_item, uint32_t wpg_log2,
                                                             uint32_t split_log2)
 {
     const uint32_t d = blockIdx.x / tiles_per_item;
     if (d >= n) return;
-    dl_rows_body<POL>(items[d], blockIdx.x - d * tiles_per_item, wpg_log2, split_log2);
+    if constexpr (PUSHED)
+        dl_rows_body<POL>(dl_pushed_entry(items, d), blockIdx.x - d * tiles_per_item, wpg_log2, split_log2);
+    else
+        dl_rows_body<POL>(items[d], blockIdx.x - d * tiles_per_item, wpg_log2, split_log2);
 }
 
 // General path: any alignment and tile size, one workgroup per tile.
@@ -54,14 +72,19 @@ __global__ void __launch_bounds__(512) dl_exec_list_strided_kernel(const dl_klis
     for (uint32_t b = blockIdx.x; b < total; b += gridDim.x) dl_run_tile<POL>(p, b);
 }
 
-template <class Item, int POL>
+template <class Item, int POL, bool PUSHED = false>
 __global__ void __launch_bounds__(512) dl_exec_table_kernel(const Item *__restrict__ items, uint32_t n,
                                                             uint32_t tile_bytes, uint32_t split)
 {
     const uint32_t b = blockIdx.x;
     if (b >= n) return;
-    const Item it = items[b];
-    dl_run_item<POL>(it, 0, tile_bytes, split);
+    if constexpr (PUSHED) {
+        const Item it = dl_pushed_entry(items, b);
+        dl_run_item<POL>(it, 0, tile_bytes, split);
+    } else {
+        const Item it = items[b];
+        dl_run_item<POL>(it, 0, tile_bytes, split);
+    }
 }
 
 // ------------------------------------------------------------ armed kernels
@@ -317,9 +340,20 @@ constexpr size_t TABLE_STAGE_MIN = 512;          // tables at least this long ar
 constexpr size_t RING_SLOTS = 4;
 constexpr size_t RING_SLOT_BYTES = DL_RING_SLOT_BYTES;
 
+constexpr size_t PUSH_SLOT_BYTES = 64u << 10;  // longest table that is written through the BAR
+constexpr size_t PUSH_SLOTS = 64, PUSH_HALF = PUSH_SLOTS / 2;
+
 struct ring_t {
     char *base = nullptr;  // pinned host memory: the host writes tables here
     char *dev = nullptr;   // device memory of the same shape: long tables are staged here before they are used
+    // Tables written through the BAR (see push_acquire): PUSH_SLOTS slots of device memory that the host can
+    // store into, used in turn.  No event per table: one per half of the ring, recorded behind the half's last
+    // launch and waited for before the half is entered again, PUSH_HALF requests later.
+    char *push = nullptr;
+    size_t push_next = 0;                 // slot that the next table takes
+    hipEvent_t push_ev[2]{};
+    bool push_pending[2]{};               // the half's event has been recorded and not waited for yet
+    hipStream_t push_stream[2]{};         // the stream on which the half's tables so far were launched
     hipEvent_t ev[RING_SLOTS]{};
     bool used[RING_SLOTS]{};
     size_t next = 0;
@@ -446,6 +480,62 @@ inline void advance(dl_fused_item &it, uint64_t off)
     for (uint32_t j = 0; j < it.k; ++j) it.dst[j] += off;
 }
 
+// Short tables skip the pinned ring.  Where the device exposes all of its memory through a PCIe BAR the host
+// writes the table straight into device memory (write-combined stores, nothing is ever read back), fences, and
+// launches: posted writes reach the device in order, the launch's doorbell is one of them, so the kernel finds
+// the table complete, and in its own memory.  (Through the pinned ring every workgroup fetched its entry over
+// the host link, or a staging kernel ran in front.)
+//
+// push_acquire: a slot for a table of table_bytes whose kernel will be launched on `stream` next, or null if
+// this table cannot go that way (*rc says whether that is an error).  push_commit: after that launch.
+int push_close_half(size_t h)
+{
+    if (hipEventRecord(g_ring.push_ev[h], g_ring.push_stream[h]) == hipSuccess) {
+        g_ring.push_pending[h] = true;
+    } else {
+        // the caller has destroyed that stream since; destroying a stream waits for the work queued on it
+        (void)hipGetLastError();
+        g_ring.push_pending[h] = false;
+    }
+    return DL_OK;
+}
+
+char *push_acquire(size_t table_bytes, hipStream_t stream, int *rc)
+{
+    *rc = DL_OK;
+    if (!g_ring.push || !g_dl.cfg.table_push || table_bytes > PUSH_SLOT_BYTES) return nullptr;
+    size_t s = g_ring.push_next, h = s / PUSH_HALF;
+    if (s % PUSH_HALF != 0 && stream != g_ring.push_stream[h]) {
+        // one event covers a half only if all of its launches are on one stream: leave this half here
+        if ((*rc = push_close_half(h)) != DL_OK) return nullptr;
+        h ^= 1;
+        s = h * PUSH_HALF;
+    }
+    if (s % PUSH_HALF == 0) {
+        if (g_ring.push_pending[h]) {  // the kernels that read this half's previous tables must have ended
+            const hipError_t e = hipEventSynchronize(g_ring.push_ev[h]);
+            if (e != hipSuccess) {
+                g_dl.last_hip = (int)e;
+                (void)hipGetLastError();
+                *rc = DL_ERR_HIP;
+                return nullptr;
+            }
+            g_ring.push_pending[h] = false;
+        }
+        g_ring.push_stream[h] = stream;
+    }
+    g_ring.push_next = s + 1;
+    return g_ring.push + s * PUSH_SLOT_BYTES;
+}
+
+int push_commit()
+{
+    if (g_ring.push_next % PUSH_HALF != 0) return DL_OK;
+    const size_t h = (g_ring.push_next - 1) / PUSH_HALF;  // the half whose last slot was just used
+    g_ring.push_next = (h ^ 1) * PUSH_HALF;
+    return push_close_half(h);
+}
+
 // Copy `bytes` (a multiple of 16) from a slot of the pinned ring to the same slot of its device
 // mirror with a 1:1 row kernel of our own, enqueued on `stream` in front of the kernel that reads it.
 int stage_slot(size_t s, uint64_t bytes, hipStream_t stream)
@@ -490,32 +580,53 @@ bool launch_uniform_rows(const Item *items, size_t n, const dl_launch_shape &sh,
     const uint64_t tpi = (bytes + tile - 1) / tile;
     if (tpi * n >= (1ull << 30)) return false;
 
-    const size_t s = g_ring.next++ % RING_SLOTS;
+    char *pushed = push_acquire(n * sizeof(Item), stream, rc);
+    if (*rc != DL_OK) return true;
+    size_t s = 0;
     *rc = DL_ERR_HIP;
-    if (g_ring.used[s]) {
-        const hipError_t e = hipEventSynchronize(g_ring.ev[s]);
-        if (e != hipSuccess) {
-            g_dl.last_hip = (int)e;
-            return true;
+    if (!pushed) {
+        s = g_ring.next++ % RING_SLOTS;
+        if (g_ring.used[s]) {
+            const hipError_t e = hipEventSynchronize(g_ring.ev[s]);
+            if (e != hipSuccess) {
+                g_dl.last_hip = (int)e;
+                return true;
+            }
         }
     }
-    Item *slot = (Item *)(g_ring.base + s * RING_SLOT_BYTES);
+    Item *slot = (Item *)(pushed ? pushed : g_ring.base + s * RING_SLOT_BYTES);
     for (size_t i = 0; i < n; ++i) {
-        slot[i] = items[i];
-        slots_by_subgroup(slot[i], split);
+        Item it = items[i];
+        slots_by_subgroup(it, split);
+        slot[i] = it;  // write only: the slot may be device memory behind the BAR
     }
-    *rc = stage_slot(s, (n * sizeof(Item) + 15u) & ~(uint64_t)15u, stream);
-    if (*rc != DL_OK) return true;
-    const Item *dslot = (const Item *)(g_ring.dev + s * RING_SLOT_BYTES);
+    const Item *dslot = slot;
+    if (pushed) {
+        _mm_sfence();  // the table leaves the write-combining buffers before the launch does
+    } else {
+        *rc = stage_slot(s, (n * sizeof(Item) + 15u) & ~(uint64_t)15u, stream);
+        if (*rc != DL_OK) return true;
+        dslot = (const Item *)(g_ring.dev + s * RING_SLOT_BYTES);
+    }
     with_policy(sh.policy, [&](auto pol) {
-        hipLaunchKernelGGL((dl_exec_urows_kernel<Item, decltype(pol)::value>), dim3((uint32_t)(tpi * n)), dim3(threads), 0,
-                           stream, dslot, (uint32_t)n, (uint32_t)tpi, log2u(threads / 64u / split), log2u(split));
+        if (pushed)
+            hipLaunchKernelGGL((dl_exec_urows_kernel<Item, decltype(pol)::value, true>), dim3((uint32_t)(tpi * n)),
+                               dim3(threads), 0, stream, dslot, (uint32_t)n, (uint32_t)tpi,
+                               log2u(threads / 64u / split), log2u(split));
+        else
+            hipLaunchKernelGGL((dl_exec_urows_kernel<Item, decltype(pol)::value, false>), dim3((uint32_t)(tpi * n)),
+                               dim3(threads), 0, stream, dslot, (uint32_t)n, (uint32_t)tpi,
+                               log2u(threads / 64u / split), log2u(split));
     });
     hipError_t e = hipGetLastError();
-    if (e == hipSuccess) e = hipEventRecord(g_ring.ev[s], stream);
+    if (e == hipSuccess && !pushed) e = hipEventRecord(g_ring.ev[s], stream);
     if (e != hipSuccess) {
         g_dl.last_hip = (int)e;
         *rc = DL_ERR_HIP;
+        return true;
+    }
+    if (pushed) {
+        *rc = push_commit();
         return true;
     }
     g_ring.used[s] = true;
@@ -558,12 +669,23 @@ int launch_table(const Item *items, size_t n, dl_launch_shape sh, hipStream_t st
             sh.tile_bytes *= 2;
         }
     }
+    const uint64_t all_entries = entries(sh.tile_bytes);
     size_t i = 0;
     uint64_t off = 0;  // progress inside items[i]
     while (i < n) {
-        const size_t s = g_ring.next++ % RING_SLOTS;
-        if (g_ring.used[s]) DL_HIP(hipEventSynchronize(g_ring.ev[s]));
-        Item *slot = (Item *)(g_ring.base + s * RING_SLOT_BYTES);
+        // a short table that is all of the request (and not an armed one: that kernel reads its entries in a loop)
+        char *pushed = nullptr;
+        if (!arm && i == 0 && off == 0) {
+            int rc = DL_OK;
+            pushed = push_acquire(all_entries * sizeof(Item), stream, &rc);
+            if (rc != DL_OK) return rc;
+        }
+        size_t s = 0;
+        if (!pushed) {
+            s = g_ring.next++ % RING_SLOTS;
+            if (g_ring.used[s]) DL_HIP(hipEventSynchronize(g_ring.ev[s]));
+        }
+        Item *slot = (Item *)(pushed ? pushed : g_ring.base + s * RING_SLOT_BYTES);
         size_t m = 0;
         while (i < n && m < cap) {
             const uint64_t left = items[i].bytes - off;
@@ -575,11 +697,13 @@ int launch_table(const Item *items, size_t n, dl_launch_shape sh, hipStream_t st
             Item it = items[i];
             advance(it, off);
             it.bytes = left < sh.tile_bytes ? left : sh.tile_bytes;
-            slot[m++] = it;
+            slot[m++] = it;  // write only: the slot may be device memory behind the BAR
             off += it.bytes;
         }
         if (m == 0) break;
-        if (m >= TABLE_STAGE_MIN) {
+        if (pushed) {
+            _mm_sfence();  // the table leaves the write-combining buffers before the launch does
+        } else if (m >= TABLE_STAGE_MIN) {
             // Stage the table in device memory, in front of the kernel that uses it (the copy does not
             // wait for a doorbell: the table is final now).  The workgroups then find their entries in
             // HBM instead of each fetching one over the host link.
@@ -597,11 +721,20 @@ int launch_table(const Item *items, size_t n, dl_launch_shape sh, hipStream_t st
                                (uint32_t)m, sh.tile_bytes, sh.split, a);
         } else {
             with_policy(sh.policy, [&](auto pol) {
-                hipLaunchKernelGGL((dl_exec_table_kernel<Item, decltype(pol)::value>), dim3((uint32_t)m),
-                                   dim3(sh.block_threads), 0, stream, slot, (uint32_t)m, sh.tile_bytes, sh.split);
+                if (pushed)
+                    hipLaunchKernelGGL((dl_exec_table_kernel<Item, decltype(pol)::value, true>), dim3((uint32_t)m),
+                                       dim3(sh.block_threads), 0, stream, slot, (uint32_t)m, sh.tile_bytes, sh.split);
+                else
+                    hipLaunchKernelGGL((dl_exec_table_kernel<Item, decltype(pol)::value, false>), dim3((uint32_t)m),
+                                       dim3(sh.block_threads), 0, stream, slot, (uint32_t)m, sh.tile_bytes, sh.split);
             });
         }
         DL_HIP(hipGetLastError());
+        if (pushed) {
+            const int rc = push_commit();
+            if (rc != DL_OK) return rc;
+            continue;
+        }
         DL_HIP(hipEventRecord(g_ring.ev[s], stream));
         g_ring.used[s] = true;
     }
@@ -808,9 +941,42 @@ int dl_ring_release(size_t slot, hipStream_t stream)
     return DL_OK;
 }
 
+// Device memory that the host can store into: only where one PCIe BAR covers all of the device's memory.  Made
+// once per process and kept until it ends.
+void *dl_bar_memory(size_t bytes)
+{
+    int large_bar = 0;
+    if (hipDeviceGetAttribute(&large_bar, hipDeviceAttributeIsLargeBar, g_dl.device) != hipSuccess || large_bar != 1) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    void *p = nullptr;
+    if (hipExtMallocWithFlags(&p, bytes, hipDeviceMallocFinegrained) != hipSuccess) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    if (hipMemset(p, 0, bytes) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
+        (void)hipGetLastError();
+        return nullptr;  // left allocated and unused
+    }
+    return p;
+}
+
 int dl_exec_init()
 {
+    static bool push_tried = false;
+    static char *push_memory = nullptr;
+    if (!push_tried) {
+        push_tried = true;
+        push_memory = (char *)dl_bar_memory(PUSH_SLOTS * PUSH_SLOT_BYTES);
+    }
     if (g_ring.base) return DL_OK;
+    g_ring.push = push_memory;
+    g_ring.push_next = 0;
+    for (int h = 0; h < 2; ++h) {
+        DL_HIP(hipEventCreateWithFlags(&g_ring.push_ev[h], hipEventDisableTiming));
+        g_ring.push_pending[h] = false;
+    }
     DL_HIP(hipHostMalloc((void **)&g_ring.base, RING_SLOTS * RING_SLOT_BYTES, hipHostMallocDefault));
     DL_HIP(hipMalloc((void **)&g_ring.dev, RING_SLOTS * RING_SLOT_BYTES));
     for (size_t s = 0; s < RING_SLOTS; ++s) {
@@ -828,6 +994,12 @@ int dl_exec_shutdown()
         if (g_ring.used[s]) (void)hipEventSynchronize(g_ring.ev[s]);
         (void)hipEventDestroy(g_ring.ev[s]);
     }
+    for (int h = 0; h < 2; ++h) {
+        if (g_ring.push_pending[h]) (void)hipEventSynchronize(g_ring.push_ev[h]);
+        (void)hipEventDestroy(g_ring.push_ev[h]);
+    }
+    // a half that was left part-used has launches that no event covers, on a stream that may be gone by now
+    if (g_ring.push && g_ring.push_next % PUSH_HALF != 0) (void)hipDeviceSynchronize();
     (void)hipHostFree(g_ring.base);
     (void)hipFree(g_ring.dev);
     g_ring.base = nullptr;

@@ -130,6 +130,10 @@ int dl_standby_try(const dl_plan_item *items, size_t n, bool *taken);
 int dl_standby_enter();  // arm the pool
 int dl_standby_leave();  // cancel what is armed and wait until it has left the device
 
+// dl_exec.hip: `bytes` of zeroed device memory that the host can store into through the BAR (null where the
+// device does not expose all of its memory that way); never freed.
+void *dl_bar_memory(size_t bytes);
+
 // dl_prelaunch.hip: tickets, doorbell and completion words of armed requests.
 bool dl_armed_ready();
 int dl_armed_begin(dl_arm *arm, hipStream_t *stream);  // next ticket's words; picks the library stream if *stream is null

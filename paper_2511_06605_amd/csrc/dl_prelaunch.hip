@@ -198,20 +198,8 @@ void standby_place_records()
 {
     if (g_sb_rec_dev_tried) return;
     g_sb_rec_dev_tried = true;
-    int large_bar = 0;
-    if (hipDeviceGetAttribute(&large_bar, hipDeviceAttributeIsLargeBar, g_dl.device) != hipSuccess || large_bar != 1) {
-        (void)hipGetLastError();
-        return;
-    }
-    void *p = nullptr;
-    if (hipExtMallocWithFlags(&p, DL_STANDBY_POOL * SB_DEV_STRIDE, hipDeviceMallocFinegrained) != hipSuccess) {
-        (void)hipGetLastError();
-        return;
-    }
-    if (hipMemset(p, 0, DL_STANDBY_POOL * SB_DEV_STRIDE) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
-        (void)hipGetLastError();
-        return;  // left allocated and unused
-    }
+    void *p = dl_bar_memory(DL_STANDBY_POOL * SB_DEV_STRIDE);
+    if (!p) return;
     g_sb_rec_dev = (uint8_t *)p;
 }
 

@@ -447,6 +447,36 @@ def test_lists_longer_than_one_staging_slot(ref):
     assert np.array_equal(d.host(), want) and d.guards_intact()
 
 
+@pytest.mark.parametrize("push", [1, 0])
+def test_many_table_requests_in_flight_on_changing_streams(ref, cfg, push):
+    """220 requests of 70 to 400 copies each (more than fit the kernel arguments: every request writes a table),
+    issued back to back without any synchronisation between them, on three streams that take turns every few
+    requests, each request on buffers of its own (one in ten with equal copies of 16 KiB: the row kernel over a
+    table of whole items).  The table memory is reused several times over while earlier
+    requests may still be running, so a table overwritten too early or read stale shows as a wrong byte."""
+    import torch
+    cfg(table_push=push)
+    streams = [torch.cuda.current_stream(), torch.cuda.Stream(), torch.cuda.Stream()]
+    rng = np.random.default_rng(77)
+    cases = []
+    for r in range(220):
+        n, slot = int(rng.integers(70, 400)), int(rng.choice([48, 512, 2048, 16384], p=[0.3, 0.3, 0.3, 0.1]))
+        arena = rng.integers(0, 256, 2 * n * slot, dtype=np.uint8)
+        src = rng.integers(0, n, n) * slot + (rng.integers(0, 4, n) if slot == 48 else 0)
+        dst = (n + rng.permutation(n)) * slot
+        nb = rng.integers(1, slot - 4, n) if slot == 48 else np.full(n, slot if r % 3 else slot - 16)
+        copies = [(int(a), int(b), int(m)) for a, b, m in zip(src, dst, nb)]
+        cases.append((arena, DevBuf(arena.size, fill=arena), copies))
+    torch.cuda.synchronize()
+    for r, (arena, d, copies) in enumerate(cases):
+        st = streams[(r // 5) % 3 if r % 40 < 25 else 0]
+        dl.dl_batch_copy([(d.ptr(a), d.ptr(b), m) for a, b, m in copies], st)
+    torch.cuda.synchronize()
+    for r, (arena, d, copies) in enumerate(cases):
+        want = ref.batch_copy([arena.copy()], [(0, a, 0, b, m) for a, b, m in copies])[0]
+        assert np.array_equal(d.host(), want) and d.guards_intact(), f"request {r}"
+
+
 @pytest.mark.parametrize("infer", [0, 1])
 def test_batch_copy_with_and_without_broadcast_inference(ref, cfg, infer):
     """An all-gather written as 64 plain copies (receiver-major), plus unrelated copies: same bytes either way."""

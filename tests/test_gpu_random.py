@@ -22,7 +22,7 @@ TUNABLES = [
     {"tile_bytes": 65536, "block_threads": 256},
     {"max_blocks": 7}, {"armed_blocks": 5},
     {"fuse_broadcast": 0}, {"infer_broadcast": 0}, {"device_lowering": 0},
-    {"write_through_max_bytes": 0}, {"nontemporal_min_bytes": 1},
+    {"write_through_max_bytes": 0}, {"nontemporal_min_bytes": 1}, {"table_push": 0},
 ]
 
 
