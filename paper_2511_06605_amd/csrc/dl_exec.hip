@@ -575,7 +575,9 @@ bool launch_uniform_rows(const Item *items, size_t n, const dl_launch_shape &sh,
         if (items[i].bytes != bytes || !item_aligned16(items[i])) return false;
         if (item_k(items[i]) > kmax) kmax = item_k(items[i]);
     }
-    if (bytes * n < UNIFORM_ROWS_MIN_BYTES) return false;
+    // a table that needs staging must move enough bytes to pay for it; one written through the BAR needs none
+    const bool pushable = g_ring.push && c.table_push && n * sizeof(Item) <= PUSH_SLOT_BYTES;
+    if (!pushable && bytes * n < UNIFORM_ROWS_MIN_BYTES) return false;
     const uint32_t tile = 16u * threads / split;  // one 1 KiB row per wavefront of a sub-group
     const uint64_t tpi = (bytes + tile - 1) / tile;
     if (tpi * n >= (1ull << 30)) return false;
