@@ -2,7 +2,8 @@
 // source with several destinations).  The host-side lowering writes one 88-byte item per token and
 // ships that table over the host link; for thousands of tokens that "control" work (Sec. III-B2) is
 // as long as the copy.  Here only the destination mask (W bytes per token) crosses the link:
-//   1. the mask is copied to device memory,
+//   1. the mask goes to device memory (written there by the host through the BAR where that is possible, else
+//      through the pinned ring and a copy),
 //   2. a small kernel builds the item table there, one token per thread: its source row and, for
 //      every rank it goes to, the row it lands on (receive buffers are packed in token order, so
 //      that is an exclusive prefix count per column of the mask),
@@ -10,6 +11,7 @@
 #include "dl_device.h"
 #include "dl_internal.h"
 
+#include <immintrin.h>
 #include <string.h>
 
 namespace {
@@ -31,9 +33,14 @@ struct build_args {
 // waits for another: the rows that earlier tokens took in each receive buffer are counted again by
 // every workgroup straight from the mask (at most a few tens of KiB, from the L2), the rows taken
 // inside the block come from wavefront ballots.
+//
+// PUSHED: the host wrote the mask into device memory just before the launch; it is read past the caches, where
+// a line of whatever used that memory before may linger.
+template <bool PUSHED>
 __global__ void __launch_bounds__(BUILD_THREADS) dl_dispatch_build_kernel(const uint8_t *__restrict__ mask, const build_args a,
                                                                           dl_fused_item *__restrict__ items)
 {
+    constexpr int POL = PUSHED ? DL_POL_COHERENT : DL_POL_PLAIN;
     __shared__ uint32_t before_block[BUILD_WAVES][DISPATCH_W];  // per wavefront: set bytes it saw in earlier blocks
     __shared__ uint32_t in_wave[BUILD_WAVES][DISPATCH_W];       // per wavefront: destinations of its own 64 tokens
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
@@ -44,11 +51,19 @@ __global__ void __launch_bounds__(BUILD_THREADS) dl_dispatch_build_kernel(const 
     // load brings two, and adding words adds the eight columns bytewise (a thread adds at most
     // tokens / 256 < 256 of them).  Several loads are in flight at once.
     uint64_t acc = 0;
-    const ulonglong2 *pairs = (const ulonglong2 *)mask;
+    if constexpr (PUSHED) {
+        // 8-byte loads: the compiler keeps several of these in flight (the 16-byte form of this policy waits
+        // for each load)
+        const DL_GLOBAL uint64_t *words = dl_global<uint64_t>(mask);
 #pragma unroll 8
-    for (uint32_t v = tid; v < block0 / 2; v += BUILD_THREADS) {
-        const ulonglong2 two = pairs[v];
-        acc += two.x + two.y;
+        for (uint32_t v = tid; v < block0; v += BUILD_THREADS) acc += dl_ld<POL>(words + v);
+    } else {
+        const ulonglong2 *pairs = (const ulonglong2 *)mask;
+#pragma unroll 8
+        for (uint32_t v = tid; v < block0 / 2; v += BUILD_THREADS) {
+            const ulonglong2 two = pairs[v];
+            acc += two.x + two.y;
+        }
     }
 #pragma unroll
     for (int j = 0; j < DISPATCH_W; ++j) {
@@ -60,7 +75,7 @@ __global__ void __launch_bounds__(BUILD_THREADS) dl_dispatch_build_kernel(const 
 
     const uint32_t token = block0 + tid;
     const bool valid = token < a.tokens;
-    const uint64_t mine = valid ? ((const uint64_t *)mask)[token] : 0ull;
+    const uint64_t mine = valid ? dl_ld<POL>(dl_global<uint64_t>(mask) + token) : 0ull;
     bool m[DISPATCH_W];
     uint32_t pos[DISPATCH_W], k = 0;
 #pragma unroll
@@ -140,12 +155,30 @@ int dl_dispatch_on_device(const void *const *in, void *const *out, int W, const 
 
     size_t slot;
     char *host, *dev;
-    int rc = dl_ring_acquire(&slot, &host, &dev);
+    int rc = dl_ring_acquire(&slot, &host, &dev);  // the item table's place (and the mask's, if it is staged)
+    if (rc != DL_OK) return rc;
+    char *pushed = dl_push_acquire(mask_bytes, stream, &rc);
     if (rc != DL_OK) return rc;
     *taken = true;
-    for (size_t b = 0; b < total * (size_t)W; ++b) host[b] = dest[b] != 0;  // the device adds these bytes
-    rc = dl_ring_stage(slot, mask_bytes, stream);
-    if (rc != DL_OK) return rc;
+    // one 64-bit word per token, every byte 0 or 1: the device adds these bytes
+    static_assert(DISPATCH_W == 8, "a token's mask is one 64-bit word");
+    uint64_t *words = (uint64_t *)(pushed ? pushed : host);
+    for (size_t t = 0; t < total; ++t) {
+        uint64_t w;
+        memcpy(&w, dest + t * (size_t)DISPATCH_W, sizeof w);
+        // a non-zero byte becomes 1: fold its bits into bit 0, keep bit 0 of every byte
+        w |= w >> 4;
+        w |= w >> 2;
+        w |= w >> 1;
+        words[t] = w & 0x0101010101010101ull;  // write only: the slot may be device memory behind the BAR
+    }
+    if (pushed) {
+        _mm_sfence();
+    } else {
+        rc = dl_ring_stage(slot, mask_bytes, stream);
+        if (rc != DL_OK) return rc;
+    }
+    const uint8_t *mask = (const uint8_t *)(pushed ? pushed : dev);
 
     build_args a;
     uint32_t first = 0;
@@ -160,9 +193,16 @@ int dl_dispatch_on_device(const void *const *in, void *const *out, int W, const 
     a.tokens = (uint32_t)total;
     a.row_bytes = row_bytes;
     dl_fused_item *items = (dl_fused_item *)(dev + mask_bytes);
-    hipLaunchKernelGGL(dl_dispatch_build_kernel, dim3((uint32_t)((total + BUILD_THREADS - 1) / BUILD_THREADS)),
-                       dim3(BUILD_THREADS), 0, stream, (const uint8_t *)dev, a, items);
+    const dim3 grid((uint32_t)((total + BUILD_THREADS - 1) / BUILD_THREADS));
+    if (pushed)
+        hipLaunchKernelGGL(dl_dispatch_build_kernel<true>, grid, dim3(BUILD_THREADS), 0, stream, mask, a, items);
+    else
+        hipLaunchKernelGGL(dl_dispatch_build_kernel<false>, grid, dim3(BUILD_THREADS), 0, stream, mask, a, items);
     DL_HIP(hipGetLastError());
+    if (pushed) {
+        rc = dl_push_commit();
+        if (rc != DL_OK) return rc;
+    }
     rc = dl_launch_fused_rows_table(items, (uint32_t)total, row_bytes, stream);
     if (rc != DL_OK) return rc;
     return dl_ring_release(slot, stream);

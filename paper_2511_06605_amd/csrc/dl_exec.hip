@@ -936,6 +936,9 @@ int dl_ring_acquire(size_t *slot, char **host, char **dev)
 
 int dl_ring_stage(size_t slot, uint64_t bytes, hipStream_t stream) { return stage_slot(slot, bytes, stream); }
 
+char *dl_push_acquire(size_t bytes, hipStream_t stream, int *rc) { return push_acquire(bytes, stream, rc); }
+int dl_push_commit() { return push_commit(); }
+
 int dl_ring_release(size_t slot, hipStream_t stream)
 {
     DL_HIP(hipEventRecord(g_ring.ev[slot], stream));

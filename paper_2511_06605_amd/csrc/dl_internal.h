@@ -98,6 +98,13 @@ constexpr size_t DL_RING_SLOT_BYTES = 1u << 20;
 int dl_ring_acquire(size_t *slot, char **host, char **dev);
 int dl_ring_stage(size_t slot, uint64_t bytes, hipStream_t stream);
 int dl_ring_release(size_t slot, hipStream_t stream);
+// dl_exec.hip: short tables written by the host straight into device memory (through the BAR).
+//   dl_push_acquire  a slot for `bytes` that a kernel launched on `stream` next will read, or null if that way is
+//                    not open (no such BAR, switched off, too long); *rc != DL_OK on an error.  Write only, then
+//                    _mm_sfence(), then launch; the kernel must read the slot past the caches.
+//   dl_push_commit   after that launch
+char *dl_push_acquire(size_t bytes, hipStream_t stream, int *rc);
+int dl_push_commit();
 
 // dl_exec.hip: the row kernel over a table of n equally sized read-once/write-k items that is already in
 // device memory, destinations laid out for four sub-groups (sub-group g owns slots 2g and 2g + 1).

@@ -348,15 +348,16 @@ def test_token_dispatch_ragged(ref, W, counts, row, drop):
     run_token_dispatch(ref, W, counts, row, seed=W * 7 + row, drop=drop, experts=16 * W, top_k=min(8, W))
 
 
-@pytest.mark.parametrize("device_lowering", [0, 1])
+@pytest.mark.parametrize("device_lowering,push", [(0, 1), (1, 1), (0, 0), (1, 0)])
 @pytest.mark.parametrize("W,counts,row,drop", [(8, 100, 14336, None), (8, [300, 0, 5, 700, 64, 0, 1, 90], 1040, 3),
                                                (3, [400, 1, 200], 48, 5), (1, [600], 4096, 4),
                                                (5, [0, 0, 513, 0, 0], 2048 + 16, None), (8, 2000, 256, 7)])
-def test_token_dispatch_lowered_on_device_and_on_host(ref, cfg, device_lowering, W, counts, row, drop):
+def test_token_dispatch_lowered_on_device_and_on_host(ref, cfg, device_lowering, push, W, counts, row, drop):
     """With 8 ranks, 512 tokens or more and aligned rows the copy list is built on the device from the mask;
     the host lowering of the same request must give the same bytes.  Empty ranks, tokens without
-    destination, rows shorter than one tile; other rank counts (host lowering either way)."""
-    cfg(device_lowering=device_lowering)
+    destination, rows shorter than one tile; other rank counts (host lowering either way).  Mask or table
+    written through the BAR, or through the pinned ring."""
+    cfg(device_lowering=device_lowering, table_push=push)
     run_token_dispatch(ref, W, counts, row, seed=W + row, drop=drop, experts=32 * W, top_k=min(8, W))
 
 
@@ -368,6 +369,8 @@ def test_token_dispatch_lowered_on_device_and_on_host(ref, cfg, device_lowering,
     ([700, 1, 0, 300, 0, 0, 29, 2], 1024, 1, 2),     # every token to exactly one rank
     ([100] * 8, 2048, 64, 7),                   # (nearly) every token to all eight ranks
     ([257, 255, 256, 1, 0, 511, 64, 63], 1040, 3, 1),  # rank boundaries off the builder's 256-token blocks
+    ([300] * 8, 64, 4, 0x80),                   # mask bytes whose only set bit is the highest
+    ([300] * 8, 64, 4, 0x10),
 ])
 def test_token_dispatch_device_lowering_edges(ref, counts, row, top_k, mask_value):
     W = 8
