@@ -6,7 +6,8 @@
 //      through the pinned ring and a copy),
 //   2. a small kernel builds the item table there, one token per thread: its source row and, for
 //      every rank it goes to, the row it lands on (receive buffers are packed in token order, so
-//      that is an exclusive prefix count per column of the mask),
+//      that is an exclusive prefix count per column of the mask; the host, which touches every mask
+//      word anyway, sends along the counts at every 256th token, the kernel counts inside its 256),
 //   3. the row kernel for long lists of equal items executes the table.
 #include "dl_device.h"
 #include "dl_internal.h"
@@ -30,48 +31,25 @@ struct build_args {
 };
 
 // Workgroup b builds the items of tokens 256 b .. 256 b + 255, one token per thread.  No workgroup
-// waits for another: the rows that earlier tokens took in each receive buffer are counted again by
-// every workgroup straight from the mask (at most a few tens of KiB, from the L2), the rows taken
-// inside the block come from wavefront ballots.
+// waits for another: the rows that earlier blocks' tokens took in each receive buffer come with the
+// mask (block_rows: W counts per block, written by the host), the rows taken inside the block come
+// from wavefront ballots.
 //
 // PUSHED: the host wrote the mask into device memory just before the launch; it is read past the caches, where
 // a line of whatever used that memory before may linger.
 template <bool PUSHED>
-__global__ void __launch_bounds__(BUILD_THREADS) dl_dispatch_build_kernel(const uint8_t *__restrict__ mask, const build_args a,
+__global__ void __launch_bounds__(BUILD_THREADS) dl_dispatch_build_kernel(const uint8_t *__restrict__ mask,
+                                                                          const uint32_t *__restrict__ block_rows,
+                                                                          const build_args a,
                                                                           dl_fused_item *__restrict__ items)
 {
     constexpr int POL = PUSHED ? DL_POL_COHERENT : DL_POL_PLAIN;
-    __shared__ uint32_t before_block[BUILD_WAVES][DISPATCH_W];  // per wavefront: set bytes it saw in earlier blocks
-    __shared__ uint32_t in_wave[BUILD_WAVES][DISPATCH_W];       // per wavefront: destinations of its own 64 tokens
+    __shared__ uint32_t before_block[DISPATCH_W];          // rows taken by the tokens of earlier blocks
+    __shared__ uint32_t in_wave[BUILD_WAVES][DISPATCH_W];  // per wavefront: destinations of its own 64 tokens
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     constexpr uint32_t W = DISPATCH_W;
     const uint32_t block0 = blockIdx.x * BUILD_THREADS;
-
-    // W is 8 and every mask byte is 0 or 1 (the host wrote it so): a token is one 64-bit word, a 16-byte
-    // load brings two, and adding words adds the eight columns bytewise (a thread adds at most
-    // tokens / 256 < 256 of them).  Several loads are in flight at once.
-    uint64_t acc = 0;
-    if constexpr (PUSHED) {
-        // 8-byte loads: the compiler keeps several of these in flight (the 16-byte form of this policy waits
-        // for each load)
-        const DL_GLOBAL uint64_t *words = dl_global<uint64_t>(mask);
-#pragma unroll 8
-        for (uint32_t v = tid; v < block0; v += BUILD_THREADS) acc += dl_ld<POL>(words + v);
-    } else {
-        const ulonglong2 *pairs = (const ulonglong2 *)mask;
-#pragma unroll 8
-        for (uint32_t v = tid; v < block0 / 2; v += BUILD_THREADS) {
-            const ulonglong2 two = pairs[v];
-            acc += two.x + two.y;
-        }
-    }
-#pragma unroll
-    for (int j = 0; j < DISPATCH_W; ++j) {
-        uint32_t x = (uint32_t)(acc >> (8 * j)) & 0xFFu;
-#pragma unroll
-        for (int d = 32; d >= 1; d /= 2) x += __shfl_xor(x, d, 64);
-        if (lane == 0) before_block[wave][j] = x;
-    }
+    if (tid < DISPATCH_W) before_block[tid] = dl_ld<POL>(dl_global<uint32_t>(block_rows) + blockIdx.x * DISPATCH_W + tid);
 
     const uint32_t token = block0 + tid;
     const bool valid = token < a.tokens;
@@ -90,8 +68,9 @@ __global__ void __launch_bounds__(BUILD_THREADS) dl_dispatch_build_kernel(const 
     if (!valid) return;
 #pragma unroll
     for (int j = 0; j < DISPATCH_W; ++j) {
+        pos[j] += before_block[j];
 #pragma unroll
-        for (uint32_t w = 0; w < BUILD_WAVES; ++w) pos[j] += before_block[w][j] + (w < wave ? in_wave[w][j] : 0u);
+        for (uint32_t w = 0; w < BUILD_WAVES; ++w) pos[j] += w < wave ? in_wave[w][j] : 0u;
     }
 
     // the token's rank is the last one that starts at or before it; its send buffer and first token are
@@ -146,39 +125,52 @@ int dl_dispatch_on_device(const void *const *in, void *const *out, int W, const 
         if (((uint64_t)in[i] | (uint64_t)out[i]) & 15u) return DL_OK;
         if ((tokens[i] && !in[i]) || !out[i]) return DL_OK;  // the host lowering reports what is wrong
     }
-    // worth three small launches only for many tokens; mask and item table share one ring slot;
-    // the build kernel's bytewise column sums hold up to 255 tokens per thread
-    const uint64_t mask_bytes = (total * (uint64_t)W + 255u) & ~(uint64_t)255u;
-    if (total < 512 || total >= 255u * BUILD_THREADS ||
-        mask_bytes + total * sizeof(dl_fused_item) > DL_RING_SLOT_BYTES)
+    // worth two small launches only for many tokens; mask, block counts and item table share one ring slot
+    const uint64_t blocks = (total + BUILD_THREADS - 1) / BUILD_THREADS;
+    const uint64_t mask_bytes = (total * (uint64_t)W + 255u) & ~(uint64_t)255u;               // then the block counts:
+    const uint64_t head_bytes = (mask_bytes + blocks * DISPATCH_W * sizeof(uint32_t) + 255u) & ~(uint64_t)255u;
+    if (total < 512 || head_bytes + total * sizeof(dl_fused_item) > DL_RING_SLOT_BYTES)
         return DL_OK;
 
     size_t slot;
     char *host, *dev;
     int rc = dl_ring_acquire(&slot, &host, &dev);  // the item table's place (and the mask's, if it is staged)
     if (rc != DL_OK) return rc;
-    char *pushed = dl_push_acquire(mask_bytes, stream, &rc);
+    char *pushed = dl_push_acquire(head_bytes, stream, &rc);
     if (rc != DL_OK) return rc;
     *taken = true;
-    // one 64-bit word per token, every byte 0 or 1: the device adds these bytes
-    static_assert(DISPATCH_W == 8, "a token's mask is one 64-bit word");
+    // One 64-bit word per token, every byte 0 or 1.  Adding words adds the eight columns bytewise: the running
+    // sums are unpacked every 128 tokens (a byte holds 255), and before every 256th token they go out as that
+    // block's counts of rows already taken.
+    static_assert(DISPATCH_W == 8 && BUILD_THREADS == 256, "a token's mask is one 64-bit word; blocks of 256 tokens");
     uint64_t *words = (uint64_t *)(pushed ? pushed : host);
-    for (size_t t = 0; t < total; ++t) {
-        uint64_t w;
-        memcpy(&w, dest + t * (size_t)DISPATCH_W, sizeof w);
-        // a non-zero byte becomes 1: fold its bits into bit 0, keep bit 0 of every byte
-        w |= w >> 4;
-        w |= w >> 2;
-        w |= w >> 1;
-        words[t] = w & 0x0101010101010101ull;  // write only: the slot may be device memory behind the BAR
+    uint32_t *block_rows = (uint32_t *)((char *)words + mask_bytes);
+    uint32_t taken_rows[DISPATCH_W] = {0};
+    for (size_t t0 = 0; t0 < total; t0 += 128) {
+        if ((t0 & 255u) == 0)
+            for (int j = 0; j < DISPATCH_W; ++j) block_rows[(t0 >> 8) * DISPATCH_W + j] = taken_rows[j];
+        const size_t t1 = t0 + 128 < total ? t0 + 128 : total;
+        uint64_t acc = 0;
+        for (size_t t = t0; t < t1; ++t) {  // a plain loop over words: the compiler vectorises it
+            uint64_t w;
+            memcpy(&w, dest + t * (size_t)DISPATCH_W, sizeof w);
+            // a non-zero byte becomes 1: fold its bits into bit 0, keep bit 0 of every byte
+            w |= w >> 4;
+            w |= w >> 2;
+            w |= w >> 1;
+            w &= 0x0101010101010101ull;
+            words[t] = w;  // write only: the slot may be device memory behind the BAR
+            acc += w;
+        }
+        for (int j = 0; j < DISPATCH_W; ++j) taken_rows[j] += (uint32_t)(acc >> (8 * j)) & 0xFFu;
     }
     if (pushed) {
         _mm_sfence();
     } else {
-        rc = dl_ring_stage(slot, mask_bytes, stream);
+        rc = dl_ring_stage(slot, head_bytes, stream);
         if (rc != DL_OK) return rc;
     }
-    const uint8_t *mask = (const uint8_t *)(pushed ? pushed : dev);
+    const char *head = pushed ? pushed : dev;
 
     build_args a;
     uint32_t first = 0;
@@ -192,12 +184,14 @@ int dl_dispatch_on_device(const void *const *in, void *const *out, int W, const 
     a.W = (uint32_t)W;
     a.tokens = (uint32_t)total;
     a.row_bytes = row_bytes;
-    dl_fused_item *items = (dl_fused_item *)(dev + mask_bytes);
-    const dim3 grid((uint32_t)((total + BUILD_THREADS - 1) / BUILD_THREADS));
+    dl_fused_item *items = (dl_fused_item *)(dev + head_bytes);
+    const dim3 grid((uint32_t)blocks);
+    const uint8_t *mask = (const uint8_t *)head;
+    const uint32_t *rows_before = (const uint32_t *)(head + mask_bytes);
     if (pushed)
-        hipLaunchKernelGGL(dl_dispatch_build_kernel<true>, grid, dim3(BUILD_THREADS), 0, stream, mask, a, items);
+        hipLaunchKernelGGL(dl_dispatch_build_kernel<true>, grid, dim3(BUILD_THREADS), 0, stream, mask, rows_before, a, items);
     else
-        hipLaunchKernelGGL(dl_dispatch_build_kernel<false>, grid, dim3(BUILD_THREADS), 0, stream, mask, a, items);
+        hipLaunchKernelGGL(dl_dispatch_build_kernel<false>, grid, dim3(BUILD_THREADS), 0, stream, mask, rows_before, a, items);
     DL_HIP(hipGetLastError());
     if (pushed) {
         rc = dl_push_commit();

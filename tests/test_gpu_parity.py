@@ -364,8 +364,11 @@ def test_token_dispatch_lowered_on_device_and_on_host(ref, cfg, device_lowering,
 @pytest.mark.parametrize("counts,row,top_k,mask_value", [
     ([64] * 8, 16, 8, 1),                       # exactly the smallest request the device lowering takes
     ([63] * 7 + [70], 32, 8, 255),              # 511: just below it; mask bytes other than 1
-    ([8159] * 8, 16, 2, 1),                     # 65 272 tokens: just below the largest it takes
-    ([8160] * 8, 16, 2, 1),                     # 65 280: just above
+    ([1363] * 8, 16, 2, 1),                     # 10 904 tokens: the most whose mask and table fit the staging slot
+    ([1364] * 8, 16, 2, 1),                     # 10 912: just above
+    ([8160] * 8, 16, 2, 1),                     # 65 280: far above
+    ([1000] * 8, 32, 3, 1),                     # 8000: about the longest mask that goes through the BAR
+    ([1030] * 8, 32, 3, 1),                     # 8240: just too long for that
     ([700, 1, 0, 300, 0, 0, 29, 2], 1024, 1, 2),     # every token to exactly one rank
     ([100] * 8, 2048, 64, 7),                   # (nearly) every token to all eight ranks
     ([257, 255, 256, 1, 0, 511, 64, 63], 1040, 3, 1),  # rank boundaries off the builder's 256-token blocks
