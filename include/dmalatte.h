@@ -196,6 +196,13 @@ int dl_alltoall_inplace(void *const *buf, int W, size_t chunk_bytes, void *strea
  * produce its inputs can run beside it.  Requests armed on different streams
  * are resident together and their slots add up: arm large requests on one
  * stream, where they become resident one after the other.
+ * A request whose list is too long for the kernel arguments (more than 64
+ * plain copies or swaps, 32 read-once/write-k copies) keeps a table in memory
+ * that the library reuses in turn: at least 32 such requests may be armed and
+ * unfinished if their tables go through the BAR (dl_config.table_push, tables
+ * up to 64 KiB, all armed on one stream), 4 otherwise; a call that could get
+ * its table memory only by outwaiting a request that has not been triggered
+ * returns DL_ERR_STATE at once and arms nothing.
  * Lists too long for one kernel (hundreds of thousands of tiles) are refused
  * with DL_ERR_INVALID in this mode.  An empty request enqueues nothing and
  * takes no ticket.

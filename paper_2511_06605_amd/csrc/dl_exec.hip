@@ -310,18 +310,51 @@ __global__ void __launch_bounds__(DL_STANDBY_THREADS) dl_standby_kernel(const dl
     dl_arm_finish(f, DL_GO_RUN);
 }
 
+// Entry i of a table written through the BAR (see dl_pushed_entry), read by every lane for itself: all lanes
+// load the same 8 bytes, which costs one request per wavefront, and no barrier.  For kernels that walk a table.
 template <class Item>
+__device__ __forceinline__ Item dl_pushed_entry_per_lane(const Item *items, uint32_t i)
+{
+    static_assert(sizeof(Item) % 8 == 0, "whole 8-byte words");
+    union {
+        Item it;
+        uint64_t w[sizeof(Item) / 8];
+    } u;
+#pragma unroll
+    for (uint32_t q = 0; q < sizeof(Item) / 8; ++q) {
+        const uint64_t v = dl_ld<DL_POL_COHERENT>(dl_global<uint64_t>(items + i) + q);
+        u.w[q] = dl_uniform64(v);  // the same in every lane: keep it in scalar registers
+    }
+    return u.it;
+}
+
+// PUSHED: the table was written through the BAR when the request was armed; the workgroup's first entry is
+// fetched before the wait.
+template <class Item, bool PUSHED = false>
 __global__ void __launch_bounds__(512) dl_armed_table_kernel(const Item *__restrict__ items, uint32_t n,
                                                              uint32_t tile_bytes, uint32_t split, const dl_arm a)
 {
-    const uint32_t go = dl_arm_wait(a);
-    if (go == DL_GO_RUN) {
-        for (uint32_t b = blockIdx.x; b < n; b += gridDim.x) {
-            const Item it = items[b];
-            dl_run_item<DL_POL_COHERENT>(it, 0, tile_bytes, split);
+    if constexpr (PUSHED) {
+        Item it{};
+        if (blockIdx.x < n) it = dl_pushed_entry_per_lane(items, blockIdx.x);
+        const uint32_t go = dl_arm_wait(a);
+        if (go == DL_GO_RUN) {
+            for (uint32_t b = blockIdx.x; b < n; b += gridDim.x) {
+                if (b != blockIdx.x) it = dl_pushed_entry_per_lane(items, b);
+                dl_run_item<DL_POL_COHERENT>(it, 0, tile_bytes, split);
+            }
         }
+        dl_arm_finish(a, go);
+    } else {
+        const uint32_t go = dl_arm_wait(a);
+        if (go == DL_GO_RUN) {
+            for (uint32_t b = blockIdx.x; b < n; b += gridDim.x) {
+                const Item it = items[b];
+                dl_run_item<DL_POL_COHERENT>(it, 0, tile_bytes, split);
+            }
+        }
+        dl_arm_finish(a, go);
     }
-    dl_arm_finish(a, go);
 }
 
 // ---------------------------------------------------------------- host side
@@ -354,8 +387,10 @@ struct ring_t {
     hipEvent_t push_ev[2]{};
     bool push_pending[2]{};               // the half's event has been recorded and not waited for yet
     hipStream_t push_stream[2]{};         // the stream on which the half's tables so far were launched
+    uint64_t push_armed[2]{};             // last ticket of an armed (prelaunch mode) request with a table in the half, or 0
     hipEvent_t ev[RING_SLOTS]{};
     bool used[RING_SLOTS]{};
+    uint64_t armed[RING_SLOTS]{};         // ticket of the armed (prelaunch mode) request whose table is in the slot, or 0
     size_t next = 0;
 } g_ring;
 
@@ -488,6 +523,15 @@ inline void advance(dl_fused_item &it, uint64_t off)
 //
 // push_acquire: a slot for a table of table_bytes whose kernel will be launched on `stream` next, or null if
 // this table cannot go that way (*rc says whether that is an error).  push_commit: after that launch.
+// Wait for `ev`, behind which the memory that is about to be reused was last read.  If that reader is an armed
+// request that nobody has triggered yet, the wait could only end with that request's expiry: refuse instead.
+int wait_for_readers(hipEvent_t ev, uint64_t armed_ticket)
+{
+    if (armed_ticket && dl_armed_untriggered(armed_ticket)) return DL_ERR_STATE;
+    DL_HIP(hipEventSynchronize(ev));
+    return DL_OK;
+}
+
 int push_close_half(size_t h)
 {
     if (hipEventRecord(g_ring.push_ev[h], g_ring.push_stream[h]) == hipSuccess) {
@@ -510,18 +554,14 @@ char *push_acquire(size_t table_bytes, hipStream_t stream, int *rc)
         if ((*rc = push_close_half(h)) != DL_OK) return nullptr;
         h ^= 1;
         s = h * PUSH_HALF;
+        g_ring.push_next = s;  // also if the wait below refuses
     }
     if (s % PUSH_HALF == 0) {
         if (g_ring.push_pending[h]) {  // the kernels that read this half's previous tables must have ended
-            const hipError_t e = hipEventSynchronize(g_ring.push_ev[h]);
-            if (e != hipSuccess) {
-                g_dl.last_hip = (int)e;
-                (void)hipGetLastError();
-                *rc = DL_ERR_HIP;
-                return nullptr;
-            }
+            if ((*rc = wait_for_readers(g_ring.push_ev[h], g_ring.push_armed[h])) != DL_OK) return nullptr;
             g_ring.push_pending[h] = false;
         }
+        g_ring.push_armed[h] = 0;
         g_ring.push_stream[h] = stream;
     }
     g_ring.push_next = s + 1;
@@ -589,12 +629,13 @@ bool launch_uniform_rows(const Item *items, size_t n, const dl_launch_shape &sh,
     if (!pushed) {
         s = g_ring.next++ % RING_SLOTS;
         if (g_ring.used[s]) {
-            const hipError_t e = hipEventSynchronize(g_ring.ev[s]);
-            if (e != hipSuccess) {
-                g_dl.last_hip = (int)e;
+            if ((*rc = wait_for_readers(g_ring.ev[s], g_ring.armed[s])) != DL_OK) {
+                --g_ring.next;
                 return true;
             }
+            *rc = DL_ERR_HIP;
         }
+        g_ring.armed[s] = 0;
     }
     Item *slot = (Item *)(pushed ? pushed : g_ring.base + s * RING_SLOT_BYTES);
     for (size_t i = 0; i < n; ++i) {
@@ -675,9 +716,9 @@ int launch_table(const Item *items, size_t n, dl_launch_shape sh, hipStream_t st
     size_t i = 0;
     uint64_t off = 0;  // progress inside items[i]
     while (i < n) {
-        // a short table that is all of the request (and not an armed one: that kernel reads its entries in a loop)
+        // a short table that is all of the request
         char *pushed = nullptr;
-        if (!arm && i == 0 && off == 0) {
+        if (i == 0 && off == 0) {
             int rc = DL_OK;
             pushed = push_acquire(all_entries * sizeof(Item), stream, &rc);
             if (rc != DL_OK) return rc;
@@ -685,7 +726,14 @@ int launch_table(const Item *items, size_t n, dl_launch_shape sh, hipStream_t st
         size_t s = 0;
         if (!pushed) {
             s = g_ring.next++ % RING_SLOTS;
-            if (g_ring.used[s]) DL_HIP(hipEventSynchronize(g_ring.ev[s]));
+            if (g_ring.used[s]) {
+                const int rc = wait_for_readers(g_ring.ev[s], g_ring.armed[s]);
+                if (rc != DL_OK) {
+                    --g_ring.next;
+                    return rc;
+                }
+            }
+            g_ring.armed[s] = 0;
         }
         Item *slot = (Item *)(pushed ? pushed : g_ring.base + s * RING_SLOT_BYTES);
         size_t m = 0;
@@ -719,8 +767,14 @@ int launch_table(const Item *items, size_t n, dl_launch_shape sh, hipStream_t st
             a.direct = g <= ARMED_DIRECT_MAX ? 1u : 0u;
             a.own_word = g <= DL_DONE_WORDS && !a.trace_host ? 1u : 0u;
             g_dl.armed_words = a.own_word ? g : 1u;
-            hipLaunchKernelGGL((dl_armed_table_kernel<Item>), dim3(g), dim3(sh.block_threads), 0, stream, slot,
-                               (uint32_t)m, sh.tile_bytes, sh.split, a);
+            if (pushed)
+                hipLaunchKernelGGL((dl_armed_table_kernel<Item, true>), dim3(g), dim3(sh.block_threads), 0, stream, slot,
+                                   (uint32_t)m, sh.tile_bytes, sh.split, a);
+            else
+                hipLaunchKernelGGL((dl_armed_table_kernel<Item, false>), dim3(g), dim3(sh.block_threads), 0, stream, slot,
+                                   (uint32_t)m, sh.tile_bytes, sh.split, a);
+            // whoever wants this memory next must not wait for a request that nobody has triggered
+            if (!a.nowait) (pushed ? g_ring.push_armed[(g_ring.push_next - 1) / PUSH_HALF] : g_ring.armed[s]) = a.ticket;
         } else {
             with_policy(sh.policy, [&](auto pol) {
                 if (pushed)
@@ -927,7 +981,14 @@ int dl_ring_acquire(size_t *slot, char **host, char **dev)
 {
     if (!g_ring.base) return DL_ERR_STATE;
     const size_t s = g_ring.next++ % RING_SLOTS;
-    if (g_ring.used[s]) DL_HIP(hipEventSynchronize(g_ring.ev[s]));
+    if (g_ring.used[s]) {
+        const int rc = wait_for_readers(g_ring.ev[s], g_ring.armed[s]);
+        if (rc != DL_OK) {
+            --g_ring.next;
+            return rc;
+        }
+    }
+    g_ring.armed[s] = 0;
     *slot = s;
     *host = g_ring.base + s * RING_SLOT_BYTES;
     *dev = g_ring.dev + s * RING_SLOT_BYTES;
@@ -935,6 +996,12 @@ int dl_ring_acquire(size_t *slot, char **host, char **dev)
 }
 
 int dl_ring_stage(size_t slot, uint64_t bytes, hipStream_t stream) { return stage_slot(slot, bytes, stream); }
+
+void dl_ring_forget_armed()
+{
+    for (size_t s = 0; s < RING_SLOTS; ++s) g_ring.armed[s] = 0;
+    g_ring.push_armed[0] = g_ring.push_armed[1] = 0;
+}
 
 char *dl_push_acquire(size_t bytes, hipStream_t stream, int *rc) { return push_acquire(bytes, stream, rc); }
 int dl_push_commit() { return push_commit(); }

@@ -103,6 +103,8 @@ int dl_ring_release(size_t slot, hipStream_t stream);
 //                    not open (no such BAR, switched off, too long); *rc != DL_OK on an error.  Write only, then
 //                    _mm_sfence(), then launch; the kernel must read the slot past the caches.
 //   dl_push_commit   after that launch
+//   dl_ring_forget_armed  every armed request has finished (their tickets start over with the next session)
+void dl_ring_forget_armed();
 char *dl_push_acquire(size_t bytes, hipStream_t stream, int *rc);
 int dl_push_commit();
 
@@ -143,5 +145,6 @@ void *dl_bar_memory(size_t bytes);
 
 // dl_prelaunch.hip: tickets, doorbell and completion words of armed requests.
 bool dl_armed_ready();
+bool dl_armed_untriggered(uint64_t ticket);  // armed, neither triggered nor cancelled, and not finished
 int dl_armed_begin(dl_arm *arm, hipStream_t *stream);  // next ticket's words; picks the library stream if *stream is null
 void dl_armed_commit(uint32_t done_words);             // the ticket of the last dl_armed_begin was launched and reports in that many words

@@ -127,6 +127,13 @@ uint64_t drain_ns() { return ((uint64_t)g_dl.cfg.arm_timeout_us + 5000ull) * 100
 
 bool dl_armed_ready() { return g_arm.started; }
 
+bool dl_armed_untriggered(uint64_t ticket)
+{
+    if (!g_arm.started || ticket == 0 || ticket > g_arm.seq || g_arm.seq - ticket >= SLOTS) return false;
+    if (ticket <= load_word(&g_arm.host->bell) || ticket <= load_word(&g_arm.host->cancel)) return false;
+    return wait_done(ticket, 0, nullptr) != DL_OK;
+}
+
 int dl_armed_begin(dl_arm *arm, hipStream_t *stream)
 {
     if (!g_arm.started) return DL_ERR_STATE;
@@ -367,6 +374,7 @@ int dl_prelaunch_stop(void)
     for (uint64_t t = first; t <= g_arm.seq && rc == DL_OK; ++t)
         rc = wait_done(t, drain_ns(), nullptr);
     if (rc != DL_OK) return rc;  // words stay allocated: a kernel may still use them
+    dl_ring_forget_armed();
     (void)hipStreamSynchronize(g_arm.stream);
     (void)hipStreamDestroy(g_arm.stream);
     for (int e = 0; e < DL_STANDBY_POOL; ++e)

@@ -297,6 +297,42 @@ def test_many_requests_armed_at_once(ref, armed):
             assert np.array_equal(d_out[r].host(), want[r])
 
 
+@pytest.mark.parametrize("push,count", [(1, 40), (0, 4)])
+def test_many_long_lists_armed_at_once(ref, armed, push, count):
+    """Armed requests whose copy lists are too long for the kernel arguments keep their tables in memory that
+    is reused in turn: 40 of them at once with the tables written through the BAR; through the pinned ring four,
+    and the fifth is refused at once (it could only get its slot by outwaiting an untriggered request) and can
+    be armed after the others have run."""
+    base = dl.dl_get_config()
+    saved = {f[0]: getattr(base, f[0]) for f in base._fields_}
+    dl.dl_set_config(table_push=push)
+    try:
+        cases = []
+        for i in range(count + 1):
+            arena, descs = inputs.mixed_batch(90 + i, 3000, 2 * MiB, seed=300 + i)
+            want = ref.batch_copy([arena.copy()], [(0, s, 0, d, m) for s, d, m in descs])[0]
+            d = DevBuf(arena.size, fill=arena)
+            cases.append((d, [(d.ptr(int(s)), d.ptr(int(t)), int(m)) for s, t, m in descs], want))
+        sync()
+        for d, copies, want in cases[:count]:
+            dl.dl_batch_copy(copies)
+        last = dl.dl_last_ticket()
+        extra = cases[count]
+        if not push:
+            with pytest.raises(dl.DlError) as e:
+                dl.dl_batch_copy(extra[1])
+            assert e.value.status == dl.DL_ERR_STATE
+            assert dl.dl_last_ticket() == last        # and it took no ticket
+        dl.dl_trigger(last)
+        dl.dl_wait(last)
+        dl.dl_batch_copy(extra[1])
+        fire()
+        for d, copies, want in cases:
+            assert np.array_equal(d.host(), want) and d.guards_intact()
+    finally:
+        dl.dl_set_config(**saved)
+
+
 def test_slots_reused_by_requests_with_other_completion_words(ref, armed):
     """200 requests, more than three rounds over the 64 slots, their grids cycling through 1, 3, 13 and 40
     workgroups, so that a slot's next request reports in fewer or more completion words than the one before;
