@@ -287,6 +287,21 @@ def other_operations(dl, benchaid, inputs, torch, stream, ag_reqs, ag_bufs, ag_s
     armed_cases.append((row, benchaid.copy_list_request(dlist, benchaid.OP_BATCH), arena))
     res["batch_b2b"] = row
 
+    # the latency-bound cases again in prelaunch mode (doorbell -> completion word) and in signal mode
+    # (call -> completion word, no stream synchronisation); before the sections below create further streams:
+    # a waiting kernel holds the hardware queue of its stream, and more streams than queues would share them
+    dl.dl_prelaunch_start()
+    for row, req, _keep in armed_cases:
+        dl.dl_set_mode(dl.DL_MODE_PRELAUNCH)
+        row["prelaunch_trigger_to_done_us"] = lat_stats(benchaid.time_host(req, None, benchaid.WAIT_TRIGGER, 30, 300))
+        dl.dl_set_mode(dl.DL_MODE_SIGNAL)
+        row["signal_call_to_done_us"] = lat_stats(benchaid.time_host(req, None, benchaid.WAIT_SIGNAL, 30, 300))
+        if row.get("tokens", 99) <= 8:  # decode all-gathers short enough for a kernel that already waits (standby mode)
+            dl.dl_set_mode(dl.DL_MODE_STANDBY)
+            row["standby_call_to_done_us"] = lat_stats(benchaid.time_host(req, None, benchaid.WAIT_SIGNAL, 30, 300))
+    dl.dl_set_mode(dl.DL_MODE_ONESHOT)
+    dl.dl_prelaunch_stop()
+
     # a decode step's worth of collectives (32 all-gathers of 8 tokens x hidden 8192 bf16, buffers of their own)
     # issued one by one and replayed from a HIP graph captured once; microseconds per step, call -> synchronised
     L, B = 32, inputs.tp_decode_bytes_per_rank(8)
@@ -365,16 +380,6 @@ def other_operations(dl, benchaid, inputs, torch, stream, ag_reqs, ag_bufs, ag_s
             "allgather_beside_gemm_us": s0.elapsed_time(s1) * 1e3 / max(issued, 1), "allgathers_issued": issued,
         }
 
-    # the latency-bound cases again in prelaunch mode (doorbell -> completion word) and in signal mode
-    # (call -> completion word, no stream synchronisation)
-    dl.dl_prelaunch_start()
-    for row, req, _keep in armed_cases:
-        dl.dl_set_mode(dl.DL_MODE_PRELAUNCH)
-        row["prelaunch_trigger_to_done_us"] = lat_stats(benchaid.time_host(req, None, benchaid.WAIT_TRIGGER, 30, 300))
-        dl.dl_set_mode(dl.DL_MODE_SIGNAL)
-        row["signal_call_to_done_us"] = lat_stats(benchaid.time_host(req, None, benchaid.WAIT_SIGNAL, 30, 300))
-    dl.dl_set_mode(dl.DL_MODE_ONESHOT)
-    dl.dl_prelaunch_stop()
     return res
 
 
