@@ -24,8 +24,9 @@
  *    all-gather up to 16 ranks, every broadcast, all-to-all up to 8 ranks)
  *    is exactly one kernel launch and nothing else, so it may be
  *    issued on a stream that is being captured into a HIP graph.  Longer
- *    lists go through the library's staging ring (host writes, an event) and
- *    must not be captured; neither may prelaunch or signal mode.
+ *    lists go through table memory that the library reuses (host writes at
+ *    call time, events) and must not be captured; neither may prelaunch,
+ *    signal or standby mode.
  *  - Return value: DL_OK (0) or a negative dl_status.  No exceptions, no
  *    aborts.  On DL_ERR_HIP, dl_last_hip_error() gives the hipError_t.
  *  - Not thread-safe: one host thread drives the library at a time.

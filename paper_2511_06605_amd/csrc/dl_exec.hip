@@ -6,8 +6,10 @@
 // Short lists travel by value in the kernel-argument segment, so the device
 // needs no extra memory round trip to find its work: workgroup b finds its
 // (item, tile) from an inclusive prefix sum of tile counts.  Long lists are cut
-// into one-tile entries on the host, written to a pinned host ring (and copied
-// to device memory first when there are many), workgroup b taking entry b.
+// into one-tile entries on the host and become a table, workgroup b taking
+// entry b: written straight into device memory through the BAR where that is
+// possible (see push_acquire), else into a pinned host ring (and copied to
+// device memory first when there are many entries).
 #include "dl_device.h"
 #include "dl_internal.h"
 
@@ -281,14 +283,15 @@ static_assert(sizeof(dl_standby_rec) <= DL_STANDBY_REC_BYTES && sizeof(dl_standb
 
 // Standby executor: a generic armed kernel (see dl_internal.h).  Its doorbell is its pool slot's, its "ticket"
 // the slot's activation number; the request's own ticket and completion words come with the record.
-__global__ void __launch_bounds__(DL_STANDBY_THREADS) dl_standby_kernel(const dl_standby_rec *rec_host, const dl_arm a)
+__global__ void __launch_bounds__(DL_STANDBY_THREADS) dl_standby_kernel(const dl_standby_rec *rec_mem, const dl_arm a)
 {
     constexpr uint32_t VEC = (uint32_t)((sizeof(dl_standby_rec) + 15) / 16);
     static_assert(VEC <= DL_STANDBY_THREADS, "one 16-byte load per thread fetches the record");
     __shared__ dl_u32x4 raw[VEC];
     if (dl_arm_wait(a) != DL_GO_RUN) return;  // cancelled or never used: no request, nothing to report
-    // the record was complete before the doorbell was rung; these loads go to host memory, past every cache
-    if (threadIdx.x < VEC) raw[threadIdx.x] = dl_ld<DL_POL_COHERENT>(dl_global<dl_u32x4>(rec_host) + threadIdx.x);
+    // the record was complete before the doorbell was rung; these loads go to where it lies (device or host
+    // memory), past every cache
+    if (threadIdx.x < VEC) raw[threadIdx.x] = dl_ld<DL_POL_COHERENT>(dl_global<dl_u32x4>(rec_mem) + threadIdx.x);
     __syncthreads();
     const dl_standby_rec &rec = *reinterpret_cast<const dl_standby_rec *>(raw);
     const bool ok = rec.ticket_front != 0 && rec.ticket_front == rec.ticket_back && rec.activation == a.ticket &&
@@ -691,12 +694,13 @@ int launch_table(const Item *items, size_t n, dl_launch_shape sh, hipStream_t st
         for (size_t i = 0; i < n; ++i) m += (items[i].bytes + tile - 1) / tile;
         return m;
     };
-    // Every workgroup fetches its table entry over the host link (~1.5 us each, a few hundred in
-    // flight), so entries are what a long list pays for: with one entry per 4 KiB, 256 copies of
-    // 1 MiB ran at 2.3 TB/s and 256 copies of 16 KiB took 11.6 us.  Unless the caller fixed the
-    // tile: one entry per item up to 64 KiB (7.6 us for the same 256 copies), 64 KiB tiles for larger
-    // items (4.7 TB/s), and coarser still when that leaves more than a few thousand entries.  The
-    // workgroup loops over its tile.
+    // Entries are what a long list pays for (a table in the pinned ring: every workgroup fetches its
+    // entry over the host link, ~1.5 us each, a few hundred in flight): with one entry per 4 KiB,
+    // 256 copies of 1 MiB ran at 2.3 TB/s and 256 copies of 16 KiB took 11.6 us.  Unless the caller
+    // fixed the tile: one entry per item up to 64 KiB (7.6 us for the same 256 copies), 64 KiB tiles
+    // for larger items (4.7 TB/s), and coarser still when that leaves more than a few thousand
+    // entries.  The workgroup loops over its tile.  (With the table in device memory, through the BAR,
+    // tiles from 4 to 64 KiB were within 1 us of each other; the same rule is kept.)
     if (g_dl.cfg.tile_bytes == 0) {
         uint64_t biggest = 0;
         for (size_t i = 0; i < n; ++i) biggest = items[i].bytes > biggest ? items[i].bytes : biggest;
@@ -917,7 +921,7 @@ int dl_exec_swap(const dl_swap_item *items, size_t n, hipStream_t stream, const 
     return exec_list(items, n, stream, arm, launched);
 }
 
-bool dl_standby_fill(void *rec_host, const dl_plan_item *items, size_t n, uint64_t activation, uint64_t ticket,
+bool dl_standby_fill(void *rec_mem, const dl_plan_item *items, size_t n, uint64_t activation, uint64_t ticket,
                      uint64_t *done)
 {
     const dl_config &c = g_dl.cfg;
@@ -948,15 +952,15 @@ bool dl_standby_fill(void *rec_host, const dl_plan_item *items, size_t n, uint64
     // the record may live in device memory mapped write-combined: plain 8-byte stores in ascending order
     uint64_t words[sizeof r / 8];
     memcpy(words, &r, sizeof r);
-    volatile uint64_t *out = (volatile uint64_t *)rec_host;
+    volatile uint64_t *out = (volatile uint64_t *)rec_mem;
     for (size_t q = 0; q < sizeof r / 8; ++q) out[q] = words[q];
     return true;
 }
 
-int dl_standby_launch(const void *rec_host, const dl_arm *a, hipStream_t stream)
+int dl_standby_launch(const void *rec_mem, const dl_arm *a, hipStream_t stream)
 {
     hipLaunchKernelGGL(dl_standby_kernel, dim3(DL_STANDBY_GRID), dim3(DL_STANDBY_THREADS), 0, stream,
-                       (const dl_standby_rec *)rec_host, *a);
+                       (const dl_standby_rec *)rec_mem, *a);
     DL_HIP(hipGetLastError());
     return DL_OK;
 }

@@ -109,7 +109,7 @@ char *dl_push_acquire(size_t bytes, hipStream_t stream, int *rc);
 int dl_push_commit();
 
 // dl_exec.hip: the row kernel over a table of n equally sized read-once/write-k items that is already in
-// device memory, destinations laid out for four sub-groups (sub-group g owns slots 2g and 2g + 1).
+// device memory, destinations laid out for DL_TABLE_ROWS_SPLIT sub-groups (see slots_by_subgroup).
 int dl_launch_fused_rows_table(const dl_fused_item *dev_items, uint32_t n, uint64_t item_bytes, hipStream_t stream);
 
 // dl_dispatch.hip: token dispatch lowered on the device (the destination mask is scanned into a table of
@@ -119,8 +119,9 @@ int dl_dispatch_on_device(const void *const *in, void *const *out, int W, const 
                           const uint8_t *dest, hipStream_t stream, bool *taken);
 
 // Standby executors (DL_MODE_STANDBY): armed kernels that wait, not for a request that is known already, but for
-// any small request.  The host writes the request's copy list into a record in host-coherent memory and rings
-// the executor's own doorbell; the executor reads the record, copies, and reports in the request's completion
+// any small request.  The host writes the request's copy list into a record (in device memory, through the BAR,
+// where the device has one that covers its memory; else in host-coherent memory) and rings the executor's own
+// doorbell, which sits behind the record; the executor reads the record, copies, and reports in the request's completion
 // words like a small armed grid does (one word per workgroup).  An executor serves one request and ends; the
 // library keeps DL_STANDBY_POOL of them armed, each on a stream of its own.
 constexpr int DL_STANDBY_POOL = 2;
@@ -131,9 +132,9 @@ constexpr size_t DL_STANDBY_REC_BYTES = 1024;  // room for the record
 constexpr uint32_t DL_STANDBY_IDLE_US = 2000;  // an executor that has waited this long gives up (or the arm limit, if shorter)
 // dl_exec.hip: write the record of a request that fits an executor (at most 8 items and DL_STANDBY_GRID tiles;
 // default tunables); false if it does not fit.  Launch an executor that will read that record.
-bool dl_standby_fill(void *rec_host, const dl_plan_item *items, size_t n, uint64_t activation, uint64_t ticket,
+bool dl_standby_fill(void *rec_mem, const dl_plan_item *items, size_t n, uint64_t activation, uint64_t ticket,
                      uint64_t *done);
-int dl_standby_launch(const void *rec_host, const dl_arm *a, hipStream_t stream);
+int dl_standby_launch(const void *rec_mem, const dl_arm *a, hipStream_t stream);
 // dl_prelaunch.hip: hand the request to a waiting executor if it fits and one is fresh; *taken says whether.
 int dl_standby_try(const dl_plan_item *items, size_t n, bool *taken);
 int dl_standby_enter();  // arm the pool
