@@ -114,47 +114,59 @@ long lower_batch(const dl_copy_desc *desc, size_t n, sink &s)
 long lower_batch_inferred(const dl_copy_desc *desc, size_t n, sink &s)
 {
     if (n && !desc) return DL_ERR_INVALID;
-    // open[] holds, per distinct (src, bytes), the index in `groups` of the item still taking destinations
-    struct group {
-        const void *src;
-        size_t bytes;
-        uint32_t k;
-        void *dst[DL_PLAN_FANOUT];
-    };
-    static std::vector<group> groups;
-    static std::vector<uint32_t> slots;  // open-addressing table of indices into groups (+1), 0 = empty
-    groups.clear();
+    // slots[]: open-addressing table over the distinct (src, bytes), each entry the index (+1, 0 = empty) of the
+    // item that still takes destinations for that key
+    static std::vector<uint32_t> slots;
     size_t want = 16;
     while (want < 2 * n) want *= 2;
     slots.assign(want, 0);
+    // The items are built where they are wanted if there is room for the worst case (no two copies share a
+    // source); else in a buffer of our own, from which the sink takes what it has room for and counts the rest.
+    static std::vector<dl_plan_item> own;
+    dl_plan_item *out = s.items;
+    if (s.cap < n) {
+        if (own.size() < n) own.resize(n);
+        out = own.data();
+    }
+    size_t m = 0;
+    auto open_item = [&](const dl_copy_desc &d) {
+        dl_plan_item &it = out[m++];
+        it.src = d.src;
+        it.bytes = d.bytes;
+        it.k = 1;
+        it.reserved = 0;
+        it.dst[0] = d.dst;
+        for (uint32_t j = 1; j < (uint32_t)DL_PLAN_FANOUT; ++j) it.dst[j] = nullptr;
+        return (uint32_t)m;
+    };
     for (size_t i = 0; i < n; ++i) {
-        if (desc[i].bytes == 0) continue;
-        if (!desc[i].src || !desc[i].dst) return DL_ERR_INVALID;
-        if (desc[i].src == desc[i].dst) continue;
-        uint64_t h = ((uint64_t)desc[i].src * 0x9E3779B97F4A7C15ull) ^ ((uint64_t)desc[i].bytes * 0xC2B2AE3D27D4EB4Full);
+        const dl_copy_desc &d = desc[i];
+        if (d.bytes == 0) continue;
+        if (!d.src || !d.dst) return DL_ERR_INVALID;
+        if (d.src == d.dst) continue;
+        const uint64_t h = ((uint64_t)d.src * 0x9E3779B97F4A7C15ull) ^ ((uint64_t)d.bytes * 0xC2B2AE3D27D4EB4Full);
         size_t q = (size_t)(h >> 20) & (want - 1);
         for (;;) {
             const uint32_t g = slots[q];
             if (g == 0) {  // first copy from this (src, bytes)
-                groups.push_back({desc[i].src, desc[i].bytes, 1u, {desc[i].dst}});
-                slots[q] = (uint32_t)groups.size();
+                slots[q] = open_item(d);
                 break;
             }
-            group &gr = groups[g - 1];
-            if (gr.src == desc[i].src && gr.bytes == desc[i].bytes) {
-                if (gr.k < (uint32_t)DL_PLAN_FANOUT) {
-                    gr.dst[gr.k++] = desc[i].dst;
-                } else {  // full: a fresh item takes over this key
-                    groups.push_back({desc[i].src, desc[i].bytes, 1u, {desc[i].dst}});
-                    slots[q] = (uint32_t)groups.size();
-                }
+            dl_plan_item &it = out[g - 1];
+            if (it.src == d.src && it.bytes == d.bytes) {
+                if (it.k < (uint32_t)DL_PLAN_FANOUT)
+                    it.dst[it.k++] = d.dst;
+                else  // full: a fresh item takes over this key
+                    slots[q] = open_item(d);
                 break;
             }
             q = (q + 1) & (want - 1);
         }
     }
-    for (const group &g : groups) s.put(g.src, g.bytes, g.dst, g.k);
-    return (long)s.n;
+    if (out != s.items)
+        for (size_t g = 0; g < m && g < s.cap; ++g) s.items[g] = out[g];
+    s.n = m;
+    return (long)m;
 }
 
 // One read-once/write-k item per token that has a destination; receive buffers
