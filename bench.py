@@ -296,7 +296,7 @@ def other_operations(dl, benchaid, inputs, torch, stream, ag_reqs, ag_bufs, ag_s
         row["prelaunch_trigger_to_done_us"] = lat_stats(benchaid.time_host(req, None, benchaid.WAIT_TRIGGER, 30, 300))
         dl.dl_set_mode(dl.DL_MODE_SIGNAL)
         row["signal_call_to_done_us"] = lat_stats(benchaid.time_host(req, None, benchaid.WAIT_SIGNAL, 30, 300))
-        if row.get("tokens", 99) <= 8:  # decode all-gathers short enough for a kernel that already waits (standby mode)
+        if row.get("tokens", 99) <= 32:  # decode all-gathers short enough for a kernel that already waits (standby mode)
             dl.dl_set_mode(dl.DL_MODE_STANDBY)
             row["standby_call_to_done_us"] = lat_stats(benchaid.time_host(req, None, benchaid.WAIT_SIGNAL, 30, 300))
     dl.dl_set_mode(dl.DL_MODE_ONESHOT)
@@ -582,7 +582,7 @@ def main() -> int:
             dl.dl_set_mode(dl.DL_MODE_SIGNAL)
             lat = benchaid.time_host(reqs[B], None, benchaid.WAIT_SIGNAL, warmup=50, iters=1000)
             row["signal_call_to_done_us"] = lat_stats(lat)
-            if W * B <= 16 * 8192:
+            if W * B <= 64 * 8192:
                 # standby mode: the request is handed to a kernel that is already waiting (no launch in between)
                 dl.dl_set_mode(dl.DL_MODE_STANDBY)
                 lat = benchaid.time_host(reqs[B], None, benchaid.WAIT_SIGNAL, warmup=50, iters=1000)

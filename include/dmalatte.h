@@ -216,13 +216,14 @@ int dl_alltoall_inplace(void *const *buf, int W, size_t chunk_bytes, void *strea
  *
  * Standby mode (DL_MODE_STANDBY) is prelaunch for requests that are not known
  * ahead of time: the library keeps two generic kernels waiting on the device
- * (16 workgroups each, on streams of its own).  A call whose lowered list is
- * short enough (at most 8 copies or read-once/write-k copies, at most 16 tiles
- * of 8 KiB: an all-gather of up to 16 KiB per rank at W = 8, a broadcast of up
- * to 128 KiB, ...) writes that list where the waiting kernel will look for it
- * (device memory, through the BAR, if the host can store there; else
- * host-coherent memory) and rings that kernel's doorbell; the kernel reads
- * the list, copies, and reports in the request's completion words.  The call
+ * (64 workgroups each, on streams of its own).  A call whose lowered list is
+ * short enough (at most 8 copies or read-once/write-k copies, at most 64 tiles
+ * of 8 KiB: an all-gather of up to 64 KiB per rank at W = 8, a broadcast of up
+ * to 512 KiB, ...; 16 tiles where the device's memory cannot be written by
+ * the host through a BAR) writes that list where the waiting kernel will
+ * look for it (device memory, through the BAR, or else host-coherent memory)
+ * and rings that kernel's doorbell; the kernel reads the list, copies, and
+ * reports in the request's completion words.  The call
  * takes a ticket as in signal mode and dl_wait() observes the end; `stream`
  * plays no part, so everything the request reads must be complete before the
  * call, and two requests are ordered only if the first was waited for.  A

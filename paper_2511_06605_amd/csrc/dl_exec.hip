@@ -269,21 +269,23 @@ __global__ void __launch_bounds__(512) dl_armed_list_kernel(const dl_klist<Item,
     dl_arm_finish(a, go);
 }
 
-// What a standby executor reads from host memory once its doorbell has rung.  The two copies of the ticket
-// and the activation number let the executor refuse a record that is not the one its doorbell announced.
+// What a standby executor reads once its doorbell has rung.  The two copies of the ticket and the activation
+// number let the executor refuse a record that is not the one its doorbell announced.
 struct dl_standby_rec {
     uint64_t ticket_front;
     uint64_t activation;  // which arming of this pool slot the record is for (the executor's doorbell value)
-    uint64_t *done;       // the request's completion words (host-coherent), DL_STANDBY_GRID of them
+    uint64_t *done;       // the request's completion words (host-coherent): one per tile up to DL_DONE_WORDS tiles, else one
     uint64_t rows;        // 1: every address and byte count is a multiple of 16 (the row path's precondition)
+    uint64_t arrivals;    // written as 0; requests of more than DL_DONE_WORDS tiles count their workgroups in here
     dl_klist<dl_fused_item, 8> list;
     uint64_t ticket_back;
 };
 static_assert(sizeof(dl_standby_rec) <= DL_STANDBY_REC_BYTES && sizeof(dl_standby_rec) % 8 == 0, "record size");
 
 // Standby executor: a generic armed kernel (see dl_internal.h).  Its doorbell is its pool slot's, its "ticket"
-// the slot's activation number; the request's own ticket and completion words come with the record.
-__global__ void __launch_bounds__(DL_STANDBY_THREADS) dl_standby_kernel(const dl_standby_rec *rec_mem, const dl_arm a)
+// the slot's activation number; the request's own ticket and completion words come with the record.  Workgroup b
+// copies tile b of the request; workgroups beyond its last tile have nothing to do and nothing to report.
+__global__ void __launch_bounds__(DL_STANDBY_THREADS) dl_standby_kernel(dl_standby_rec *rec_mem, const dl_arm a)
 {
     constexpr uint32_t VEC = (uint32_t)((sizeof(dl_standby_rec) + 15) / 16);
     static_assert(VEC <= DL_STANDBY_THREADS, "one 16-byte load per thread fetches the record");
@@ -298,19 +300,25 @@ __global__ void __launch_bounds__(DL_STANDBY_THREADS) dl_standby_kernel(const dl
                     rec.done != nullptr && rec.list.n >= 1 && rec.list.n <= 8 && rec.list.tile_bytes == DL_STANDBY_TILE &&
                     rec.list.split == 1 && rec.list.tile_end[rec.list.n - 1] <= gridDim.x;
     if (!ok) return;  // not the announced record: touch nothing (the host's wait for the request times out)
-    if (blockIdx.x < rec.list.tile_end[rec.list.n - 1]) {
-        if (rec.rows)
-            dl_run_rows<DL_POL_COHERENT>(rec.list, blockIdx.x);
-        else
-            dl_run_tile<DL_POL_COHERENT>(rec.list, blockIdx.x);
+    const uint32_t tiles = rec.list.tile_end[rec.list.n - 1];
+    if (blockIdx.x >= tiles) return;
+    if (rec.rows)
+        dl_run_rows<DL_POL_COHERENT>(rec.list, blockIdx.x);
+    else
+        dl_run_tile<DL_POL_COHERENT>(rec.list, blockIdx.x);
+    // the copy stored at system scope: once the memory counters have drained, the bytes are where everybody sees them
+    dl_drain_stores();
+    __syncthreads();
+    if (threadIdx.x != 0) return;
+    if (tiles <= DL_DONE_WORDS) {
+        // the host waits for one word per tile, no count in between
+        __hip_atomic_store(rec.done + blockIdx.x, rec.ticket_front, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    } else {
+        // count in at the record (device memory: the host sends such requests only there); the last one reports
+        const uint64_t before = __hip_atomic_fetch_add(&rec_mem->arrivals, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (before == tiles - 1u)
+            __hip_atomic_store(rec.done, rec.ticket_front, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     }
-    dl_arm f = a;
-    f.done = rec.done;
-    f.ticket = rec.ticket_front;
-    f.own_word = 1;
-    f.nowait = 0;
-    f.trace_host = nullptr;
-    dl_arm_finish(f, DL_GO_RUN);
 }
 
 // Entry i of a table written through the BAR (see dl_pushed_entry), read by every lane for itself: all lanes
@@ -921,11 +929,11 @@ int dl_exec_swap(const dl_swap_item *items, size_t n, hipStream_t stream, const 
     return exec_list(items, n, stream, arm, launched);
 }
 
-bool dl_standby_fill(void *rec_mem, const dl_plan_item *items, size_t n, uint64_t activation, uint64_t ticket,
-                     uint64_t *done)
+uint32_t dl_standby_fill(void *rec_mem, const dl_plan_item *items, size_t n, uint64_t activation, uint64_t ticket,
+                         uint64_t *done, uint32_t max_tiles)
 {
     const dl_config &c = g_dl.cfg;
-    if (n == 0 || n > 8 || c.tile_bytes || c.block_threads || c.max_blocks || c.armed_blocks) return false;
+    if (n == 0 || n > 8 || c.tile_bytes || c.block_threads || c.max_blocks || c.armed_blocks) return 0;
     static_assert(sizeof(dl_plan_item) == sizeof(dl_fused_item), "plan items are fused items");
     const dl_fused_item *it = reinterpret_cast<const dl_fused_item *>(items);
     dl_standby_rec r;
@@ -935,12 +943,13 @@ bool dl_standby_fill(void *rec_mem, const dl_plan_item *items, size_t n, uint64_
     for (size_t i = 0; i < 8; ++i) {
         if (i < n) {
             acc += dl_item_tiles(it[i], DL_STANDBY_TILE);
+            if (acc > max_tiles) return 0;  // one tile per workgroup, one pass
             r.list.item[i] = it[i];
             if (!item_aligned16(it[i])) r.rows = 0;
         }
         r.list.tile_end[i] = i < n ? (uint32_t)acc : 0xFFFFFFFFu;
     }
-    if (acc == 0 || acc > DL_STANDBY_GRID) return false;  // one tile per workgroup, one pass
+    if (acc == 0) return 0;
     r.list.n = (uint32_t)n;
     r.list.tile_bytes = DL_STANDBY_TILE;
     r.list.split = 1;
@@ -949,18 +958,19 @@ bool dl_standby_fill(void *rec_mem, const dl_plan_item *items, size_t n, uint64_
     r.ticket_front = r.ticket_back = ticket;
     r.activation = activation;
     r.done = done;
+    r.arrivals = 0;
     // the record may live in device memory mapped write-combined: plain 8-byte stores in ascending order
     uint64_t words[sizeof r / 8];
     memcpy(words, &r, sizeof r);
     volatile uint64_t *out = (volatile uint64_t *)rec_mem;
     for (size_t q = 0; q < sizeof r / 8; ++q) out[q] = words[q];
-    return true;
+    return acc <= DL_DONE_WORDS ? (uint32_t)acc : 1u;
 }
 
-int dl_standby_launch(const void *rec_mem, const dl_arm *a, hipStream_t stream)
+int dl_standby_launch(void *rec_mem, const dl_arm *a, hipStream_t stream)
 {
     hipLaunchKernelGGL(dl_standby_kernel, dim3(DL_STANDBY_GRID), dim3(DL_STANDBY_THREADS), 0, stream,
-                       (const dl_standby_rec *)rec_mem, *a);
+                       (dl_standby_rec *)rec_mem, *a);
     DL_HIP(hipGetLastError());
     return DL_OK;
 }

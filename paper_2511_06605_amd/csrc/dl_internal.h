@@ -125,16 +125,18 @@ int dl_dispatch_on_device(const void *const *in, void *const *out, int W, const 
 // words like a small armed grid does (one word per workgroup).  An executor serves one request and ends; the
 // library keeps DL_STANDBY_POOL of them armed, each on a stream of its own.
 constexpr int DL_STANDBY_POOL = 2;
-constexpr uint32_t DL_STANDBY_GRID = 16;      // workgroups of an executor (= completion words of its request)
+constexpr uint32_t DL_STANDBY_GRID = 64;      // workgroups of an executor: the most tiles a request may have
 constexpr uint32_t DL_STANDBY_THREADS = 512;
 constexpr uint32_t DL_STANDBY_TILE = 8192;     // one 1 KiB row per wavefront
 constexpr size_t DL_STANDBY_REC_BYTES = 1024;  // room for the record
 constexpr uint32_t DL_STANDBY_IDLE_US = 2000;  // an executor that has waited this long gives up (or the arm limit, if shorter)
-// dl_exec.hip: write the record of a request that fits an executor (at most 8 items and DL_STANDBY_GRID tiles;
-// default tunables); false if it does not fit.  Launch an executor that will read that record.
-bool dl_standby_fill(void *rec_mem, const dl_plan_item *items, size_t n, uint64_t activation, uint64_t ticket,
-                     uint64_t *done);
-int dl_standby_launch(const void *rec_mem, const dl_arm *a, hipStream_t stream);
+// dl_exec.hip: write the record of a request that fits an executor (at most 8 items and max_tiles tiles; default
+// tunables) and return the number of completion words it will report in (one per tile up to DL_DONE_WORDS tiles,
+// else one, counted at the record, which must then be in device memory); 0 if it does not fit.  Launch an
+// executor that will read that record.
+uint32_t dl_standby_fill(void *rec_mem, const dl_plan_item *items, size_t n, uint64_t activation, uint64_t ticket,
+                         uint64_t *done, uint32_t max_tiles);
+int dl_standby_launch(void *rec_mem, const dl_arm *a, hipStream_t stream);
 // dl_prelaunch.hip: hand the request to a waiting executor if it fits and one is fresh; *taken says whether.
 int dl_standby_try(const dl_plan_item *items, size_t n, bool *taken);
 int dl_standby_enter();  // arm the pool

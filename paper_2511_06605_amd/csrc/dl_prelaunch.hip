@@ -303,11 +303,19 @@ int dl_standby_try(const dl_plan_item *items, size_t n, bool *taken)
         const int rc = wait_done(g_arm.sb_ticket[e], drain_ns(), nullptr);
         if (rc != DL_OK) return rc;
     }
-    if (!dl_standby_fill(standby_rec(e), items, n, g_sb_act[e], ticket, g_arm.host->done[slot])) return DL_OK;
+    // The record is rewritten only once the executor that will read it is on the device: kernels of one stream
+    // run one after the other, so by then every workgroup of the executor before it, which read the record's
+    // previous contents (also those that had no tile and reported nothing), has ended.  Mostly true already; a
+    // caller that comes back faster than the launch gap waits here for what it would have waited for anyway.
+    if (wait_word(&g_arm.host->sb_resident[e], g_sb_act[e], 20000ull, nullptr) != DL_OK) return DL_OK;
+    // a request of more tiles than completion words counts its workgroups in at the record: device memory only
+    const uint32_t words = dl_standby_fill(standby_rec(e), items, n, g_sb_act[e], ticket, g_arm.host->done[slot],
+                                           g_sb_rec_dev ? DL_STANDBY_GRID : DL_DONE_WORDS);
+    if (words == 0) return DL_OK;
     standby_store(standby_bell(e), g_sb_act[e]);  // the executor's doorbell, behind its record
     const bool in_time = now_ns() - g_arm.sb_armed_at[e] + 100000ull < g_arm.sb_limit_ns[e];
     __atomic_store_n(&g_arm.host->armed[slot], ticket, __ATOMIC_RELAXED);             // it was resident already
-    dl_armed_commit(DL_STANDBY_GRID);
+    dl_armed_commit(words);
     g_arm.sb_ticket[e] = ticket;
     g_arm.sb_next = (e + 1) % DL_STANDBY_POOL;
     if (in_time) {
@@ -321,7 +329,7 @@ int dl_standby_try(const dl_plan_item *items, size_t n, bool *taken)
     DL_HIP(hipStreamSynchronize(g_arm.sb_stream[e]));
     const int served = wait_done(ticket, 0, nullptr);
     if (served != DL_OK)
-        for (uint32_t w = 0; w < DL_STANDBY_GRID; ++w)
+        for (uint32_t w = 0; w < words; ++w)
             __atomic_store_n(&g_arm.host->done[slot][w], ticket, __ATOMIC_RELEASE);
     *taken = served == DL_OK;
     return standby_arm(e);

@@ -59,10 +59,12 @@ def allgather(W, B, seed, shifts=None):
 
 
 def allgather_sizes():
-    """Requests that fit a waiting kernel (at most 8 items and 16 tiles of 8 KiB) and requests that do not
-    (more items, more tiles: they take the ordinary launch), with no other synchronisation than dl_wait."""
-    for W, B in [(8, 4096), (8, 1), (8, 1000), (8, 16 * KiB), (8, 16 * KiB + 16), (8, 64 * KiB), (8, 0),
-                 (3, 40000), (1, 100000), (9, 4096), (16, 512), (8, 1 * MiB)]:
+    """Requests that fit a waiting kernel (at most 8 items and 64 tiles of 8 KiB; up to 16 tiles each tile reports
+    for itself, above that they are counted) and requests that do not (more items, more tiles: they take the
+    ordinary launch), with no other synchronisation than dl_wait."""
+    for W, B in [(8, 4096), (8, 1), (8, 1000), (8, 16 * KiB), (8, 16 * KiB + 16), (8, 20000), (8, 32 * KiB),
+                 (8, 64 * KiB), (8, 64 * KiB + 16), (8, 0), (3, 40000), (1, 100000), (2, 250000), (1, 512 * KiB),
+                 (1, 512 * KiB + 1), (9, 4096), (16, 512), (8, 1 * MiB)]:
         with standby():
             allgather(W, B, seed=W * 131 + B)
 
@@ -75,7 +77,16 @@ def allgather_misaligned():
 
 def other_operations():
     with standby():
-        # broadcast, 7 destinations, 100 KiB: one read-once/write-7 item, 13 tiles
+        # broadcast, 7 destinations, 100 KiB: one read-once/write-7 item, 13 tiles; then 300 KiB: 38 tiles, counted
+        for nbytes in (100 * KiB + 5, 300 * KiB):
+            src = inputs.payload(np.random.default_rng(nbytes), nbytes)
+            d_src = DevBuf(src.size, fill=src, shift=nbytes % 2)
+            d_dst = [DevBuf(src.size) for _ in range(7)]
+            sync()
+            dl.dl_broadcast(d_src.ptr(), [b.ptr() for b in d_dst], src.size)
+            dl.dl_wait()
+            for b in d_dst:
+                assert np.array_equal(b.host(), src) and b.guards_intact()
         src = inputs.payload(np.random.default_rng(1), 100 * KiB + 5)
         d_src = DevBuf(src.size, fill=src)
         d_dst = [DevBuf(src.size) for _ in range(7)]
@@ -119,7 +130,7 @@ def many_requests_with_changing_sources():
     it does not, the sources rewritten before every call and two receive buffers checked after every dl_wait."""
     import torch
     W = 8
-    sizes = [4 * KiB, 16 * KiB, 48 * KiB, 1000]
+    sizes = [4 * KiB, 16 * KiB, 48 * KiB, 1000, 80 * KiB, 64 * KiB]
     d_in = {B: [torch.zeros(B, dtype=torch.uint8, device="cuda") for _ in range(W)] for B in sizes}
     d_out = {B: [torch.zeros(W * B, dtype=torch.uint8, device="cuda") for _ in range(W)] for B in sizes}
     bad = torch.zeros(1, dtype=torch.int64, device="cuda")
