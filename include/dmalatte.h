@@ -192,10 +192,12 @@ int dl_alltoall_inplace(void *const *buf, int W, size_t chunk_bytes, void *strea
  * Requests on one stream run in ticket order.  The armed kernel occupies its
  * stream until it is triggered, cancelled or expires; later work on that
  * stream waits for it.  At most 64 requests may be armed and unfinished.
- * While it waits, an armed kernel holds wavefront slots: at most half of the
- * GPU's for one request (dl_config.armed_blocks), so that the kernels which
- * produce its inputs can run beside it.  Requests armed on different streams
- * are resident together and their slots add up: arm large requests on one
+ * While it waits, an armed kernel occupies compute units: at most one
+ * workgroup for every other compute unit for one request
+ * (dl_config.armed_blocks), so that the kernels which produce its inputs can
+ * run beside it, also those that cannot share a SIMD with another wavefront
+ * (large matrix multiplications).  Requests armed on different streams are
+ * resident together and their workgroups add up: arm large requests on one
  * stream, where they become resident one after the other.
  * A request whose list is too long for the kernel arguments (more than 64
  * plain copies or swaps, 32 read-once/write-k copies) keeps a table in memory
@@ -285,7 +287,7 @@ typedef struct dl_config {
     uint32_t tile_bytes;         /* bytes of one workgroup tile; 0 = choose from the fan-out; power of two >= 1024 */
     uint32_t block_threads;      /* workgroup size of the one-shot kernel: 64, 128, 256 or 512; 0 = choose */
     uint64_t nontemporal_min_bytes; /* requests moving at least this many bytes use streaming loads/stores; default: never */
-    uint32_t armed_blocks;       /* cap on the grid of an armed kernel (its workgroups stride over the tiles); 0 = half the wavefront slots of the GPU, so that the kernels that produce the request's inputs can run beside it */
+    uint32_t armed_blocks;       /* cap on the grid of an armed kernel (its workgroups stride over the tiles); 0 = half as many as the GPU has compute units, so that the kernels that produce the request's inputs can run beside it */
     uint32_t arm_timeout_us;     /* an armed kernel gives up this long after becoming resident; 1 .. 1000000, default 20000 */
     uint32_t fuse_broadcast;     /* 1: all-gather reads each source once (W fused copies); 0: W*W plain copies */
     uint32_t max_blocks;         /* cap on the one-shot grid; workgroups then stride over the tiles; 0 = one workgroup per tile */

@@ -455,13 +455,16 @@ inline uint32_t item_k(const dl_fused_item &it) { return it.k; }
 constexpr uint32_t ARMED_DIRECT_MAX = 16;  // up to this many workgroups all poll the host doorbell themselves
 
 // Workgroups of an armed kernel.  While it waits for its doorbell the kernel must leave room for other
-// kernels, above all for the ones that produce what it is going to copy: unless the caller sets the cap, the
-// grid takes at most half of the wavefront slots (16 of 32 per compute unit: four workgroups of 256 threads,
-// two of 512).
+// kernels, above all for the ones that produce what it is going to copy.  Room means whole compute units: a
+// kernel whose wavefronts take all the vector registers of a SIMD (a large matrix multiplication's do) cannot
+// share that SIMD with even one waiting wavefront, and behind a grid that had a workgroup on every compute
+// unit such a kernel did not start until the armed request expired.  Unless the caller sets the cap, the grid
+// has at most one workgroup for every other compute unit.
 uint32_t armed_grid(uint64_t tiles, uint32_t block_threads)
 {
+    (void)block_threads;
     const uint32_t cus = (uint32_t)(g_dl.num_cu > 0 ? g_dl.num_cu : 256);
-    uint32_t cap = g_dl.cfg.armed_blocks ? g_dl.cfg.armed_blocks : 16u * cus / (block_threads / 64u);
+    uint32_t cap = g_dl.cfg.armed_blocks ? g_dl.cfg.armed_blocks : cus / 2u;
     if (cap < 1u) cap = 1u;
     if (cap > 32768u) cap = 32768u;  // the arrival counter keeps 16 bits for the count
     return (uint32_t)(tiles < cap ? tiles : cap);
@@ -488,7 +491,7 @@ int launch_klist(const Item *items, size_t n, const uint64_t *tile_end, const dl
     if (arm) {
         dl_arm a = *arm;
         const uint32_t g = armed_grid(grid, sh.block_threads);
-        a.direct = g <= ARMED_DIRECT_MAX ? 1u : 0u;
+        a.direct = g <= a.direct_max ? 1u : 0u;
         a.own_word = g <= DL_DONE_WORDS && !a.trace_host ? 1u : 0u;  // the stamps come from the last arriver
         g_dl.armed_words = a.own_word ? g : 1u;
         if (sh.rows)
@@ -776,7 +779,7 @@ int launch_table(const Item *items, size_t n, dl_launch_shape sh, hipStream_t st
         if (arm) {
             dl_arm a = *arm;
             const uint32_t g = armed_grid(m, sh.block_threads);
-            a.direct = g <= ARMED_DIRECT_MAX ? 1u : 0u;
+            a.direct = g <= a.direct_max ? 1u : 0u;
             a.own_word = g <= DL_DONE_WORDS && !a.trace_host ? 1u : 0u;
             g_dl.armed_words = a.own_word ? g : 1u;
             if (pushed)

@@ -45,7 +45,7 @@ struct dl_launch_shape {
 // What an armed (prelaunched) kernel needs to wait for its doorbell and to
 // report completion.  Passed by value in the kernel arguments.
 struct dl_arm {
-    const uint64_t *bell;  // host-coherent: bell[0] = doorbell, bell[1] = cancel; both only ever grow
+    const uint64_t *bell;  // bell[0] = doorbell, bell[1] = cancel; both only ever grow.  Host-coherent memory, or device memory that the host writes through the BAR
     uint64_t *done;        // host-coherent: completion word of this ticket's slot
     uint64_t *armed;       // host-coherent: "resident and polling" word of this ticket's slot
     uint64_t *go;          // device: fan-out flags of this ticket's slot, one per group, DL_ARM_STRIDE bytes apart
@@ -57,7 +57,8 @@ struct dl_arm {
     uint64_t ticket;
     uint64_t limit_ticks;   // give up this long after becoming resident
     uint64_t margin_ticks;  // extra time a non-polling workgroup grants the polling one
-    uint32_t direct;        // 1: every workgroup polls the host doorbell itself
+    uint32_t direct;        // 1: every workgroup polls the doorbell itself
+    uint32_t direct_max;    // grids up to this many workgroups do so (more where the doorbell is in device memory: polls there do not queue up on the host link)
     uint32_t max_spins;     // backstop that does not depend on the clock: give up after this many polls
     uint32_t nowait;        // 1: no doorbell, copy at once (DL_MODE_SIGNAL, and what DL_MODE_STANDBY cannot hand to an executor); the completion side is unchanged
     // 1: a grid of at most DL_DONE_WORDS workgroups, each of which reports in a completion word of its own
@@ -69,6 +70,8 @@ struct dl_arm {
     uint64_t *trace_host;
 };
 constexpr uint32_t DL_DONE_WORDS = 16;  // completion words per slot (two cache lines of host memory); with 32 or 64 words the host-side wait cost more than the count on the device
+constexpr uint32_t DL_ARM_DIRECT_MAX_HOST = 16;    // grids up to this size poll a doorbell in host memory themselves
+constexpr uint32_t DL_ARM_DIRECT_MAX_DEVICE = 1024;  // ... and one in device memory
 constexpr uint32_t DL_ARM_GROUPS = 16;  // workgroup b belongs to group b % DL_ARM_GROUPS
 constexpr uint32_t DL_ARM_FLAT_MAX = 64;  // grids up to this size count their arrivals at one word (0.5 us less than two levels; 256 arrivals at one word: 1.3 us more)
 constexpr uint32_t DL_ARM_STRIDE = 4352;  // flags and counters sit 4 KiB + 256 B apart: separate lines and memory channels

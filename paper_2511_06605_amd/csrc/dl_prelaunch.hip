@@ -134,6 +134,26 @@ bool dl_armed_untriggered(uint64_t ticket)
     return wait_done(ticket, 0, nullptr) != DL_OK;
 }
 
+namespace {
+
+// The doorbell pair {doorbell, cancel} of armed requests in device memory, where the host can store there through
+// the BAR (made once per process, never freed; set to zero at the start of every session, before anything is
+// armed).  The pair in host memory is kept up to date as well: the host reads its own doorbell there.
+uint64_t *g_bell_dev = nullptr;
+bool g_bell_dev_tried = false;
+
+void bell_store(uint64_t *host_word, uint64_t *dev_word, uint64_t v)
+{
+    __atomic_store_n(host_word, v, __ATOMIC_RELEASE);
+    if (dev_word) {
+        _mm_sfence();
+        *(volatile uint64_t *)dev_word = v;
+        _mm_sfence();
+    }
+}
+
+}  // namespace
+
 int dl_armed_begin(dl_arm *arm, hipStream_t *stream)
 {
     if (!g_arm.started) return DL_ERR_STATE;
@@ -144,7 +164,8 @@ int dl_armed_begin(dl_arm *arm, hipStream_t *stream)
         const int rc = wait_done(ticket - SLOTS, drain_ns(), nullptr);
         if (rc != DL_OK) return rc;
     }
-    arm->bell = &g_arm.host->bell;
+    arm->bell = g_bell_dev ? g_bell_dev : &g_arm.host->bell;
+    arm->direct_max = g_bell_dev ? DL_ARM_DIRECT_MAX_DEVICE : DL_ARM_DIRECT_MAX_HOST;
     arm->done = g_arm.host->done[slot];
     arm->own_word = 0;
     arm->armed = &g_arm.host->armed[slot];
@@ -363,6 +384,14 @@ int dl_prelaunch_start(void)
         g_arm = arm_state{};
         return DL_ERR_HIP;
     }
+    if (!g_bell_dev_tried) {
+        g_bell_dev_tried = true;
+        g_bell_dev = (uint64_t *)dl_bar_memory(256);
+    }
+    if (g_bell_dev) {  // tickets start over: so do doorbell and cancel word (nothing is armed yet)
+        bell_store(&g_arm.host->bell, g_bell_dev, 0);
+        bell_store(&g_arm.host->cancel, g_bell_dev + 1, 0);
+    }
     g_arm.seq = 0;
     g_arm.started = true;
     return DL_OK;
@@ -376,7 +405,7 @@ int dl_prelaunch_stop(void)
         if (rc != DL_OK) return rc;
     }
     // every request still armed gives up; then wait until all of them have left the device
-    __atomic_store_n(&g_arm.host->cancel, g_arm.seq, __ATOMIC_RELEASE);
+    bell_store(&g_arm.host->cancel, g_bell_dev ? g_bell_dev + 1 : nullptr, g_arm.seq);
     int rc = DL_OK;
     const uint64_t first = g_arm.seq > SLOTS ? g_arm.seq - SLOTS + 1 : 1;
     for (uint64_t t = first; t <= g_arm.seq && rc == DL_OK; ++t)
@@ -471,7 +500,7 @@ int dl_trigger(uint64_t ticket)
 {
     if (!g_arm.started) return DL_ERR_STATE;
     if (ticket == 0 || ticket > g_arm.seq) return DL_ERR_INVALID;
-    if (ticket > g_arm.host->bell) __atomic_store_n(&g_arm.host->bell, ticket, __ATOMIC_RELEASE);  // the doorbell
+    if (ticket > g_arm.host->bell) bell_store(&g_arm.host->bell, g_bell_dev, ticket);  // the doorbell
     return DL_OK;
 }
 

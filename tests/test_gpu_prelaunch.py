@@ -274,6 +274,36 @@ def test_large_armed_request_leaves_room_for_its_producers(ref, armed, B):
         dl.dl_set_config(fuse_broadcast=1)
 
 
+def test_armed_request_waits_beside_a_matrix_multiplication(armed):
+    """The producer of an armed request's input is a large bf16 matrix multiplication, whose wavefronts take all
+    the vector registers of a SIMD and so cannot share one with a waiting wavefront.  It must run, and in its own
+    time, while a request with more tiles than the armed grid holds waits for the doorbell (a grid with a
+    workgroup on every compute unit kept it from starting until the request expired)."""
+    import time
+    import torch
+    W, B, n = 8, 2 * MiB, 4096
+    a = torch.randn(n, n, dtype=torch.bfloat16, device="cuda")
+    b = torch.randn(n, n, dtype=torch.bfloat16, device="cuda")
+    torch.matmul(a, b)                                   # library set-up stays outside
+    sync()
+    d_in = [torch.zeros(B, dtype=torch.uint8, device="cuda") for _ in range(W)]
+    d_out = [torch.zeros(W * B, dtype=torch.uint8, device="cuda") for _ in range(W)]
+    sync()
+    dl.dl_allgather(d_in, d_out, B)
+    dl.dl_wait_armed()
+    t0 = time.perf_counter()
+    c = torch.matmul(a, b)
+    src = c.view(torch.uint8).reshape(-1)                # 32 MiB of results: the request's sources
+    for j in range(W):
+        d_in[j].copy_(src[j * B:(j + 1) * B])
+    sync()
+    waited = time.perf_counter() - t0
+    fire()
+    assert waited < ARM_US * 1e-6 / 3, f"the producers took {waited * 1e3:.1f} ms beside the waiting request"
+    for r in (0, 6):
+        assert torch.equal(d_out[r], src[:W * B])
+
+
 def test_many_requests_armed_at_once(ref, armed):
     """A full set of 64 armed requests on one stream, one doorbell write for all."""
     W, B, N = 4, 3000, 64
