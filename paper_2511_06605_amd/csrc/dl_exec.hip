@@ -277,6 +277,10 @@ struct dl_standby_rec {
     uint64_t *done;       // the request's completion words (host-coherent): one per tile up to DL_DONE_WORDS tiles, else one
     uint64_t rows;        // 1: every address and byte count is a multiple of 16 (the row path's precondition)
     uint64_t arrivals;    // written as 0; requests of more than DL_DONE_WORDS tiles count their workgroups in here
+    // The ticket's slot has two sets of arrival counters that its requests use in turn, each clearing the set it
+    // does not use (see dl_arm).  A request served here counts nothing there, but it keeps that chain: this is
+    // the set it clears.
+    uint32_t *arrive_clear;
     dl_klist<dl_fused_item, 8> list;
     uint64_t ticket_back;
 };
@@ -302,6 +306,10 @@ __global__ void __launch_bounds__(DL_STANDBY_THREADS) dl_standby_kernel(dl_stand
     if (!ok) return;  // not the announced record: touch nothing (the host's wait for the request times out)
     const uint32_t tiles = rec.list.tile_end[rec.list.n - 1];
     if (blockIdx.x >= tiles) return;
+    if (blockIdx.x == 0 && threadIdx.x == 0)  // in flight beside the copy, drained with it before the completion word
+        for (uint32_t g = 0; rec.arrive_clear && g <= DL_ARM_GROUPS; ++g)
+            __hip_atomic_store((uint32_t *)((char *)rec.arrive_clear + g * DL_ARM_STRIDE), 0u, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
     if (rec.rows)
         dl_run_rows<DL_POL_COHERENT>(rec.list, blockIdx.x);
     else
@@ -933,7 +941,7 @@ int dl_exec_swap(const dl_swap_item *items, size_t n, hipStream_t stream, const 
 }
 
 uint32_t dl_standby_fill(void *rec_mem, const dl_plan_item *items, size_t n, uint64_t activation, uint64_t ticket,
-                         uint64_t *done, uint32_t max_tiles)
+                         uint64_t *done, uint32_t *arrive_clear, uint32_t max_tiles)
 {
     const dl_config &c = g_dl.cfg;
     if (n == 0 || n > 8 || c.tile_bytes || c.block_threads || c.max_blocks || c.armed_blocks) return 0;
@@ -961,6 +969,7 @@ uint32_t dl_standby_fill(void *rec_mem, const dl_plan_item *items, size_t n, uin
     r.ticket_front = r.ticket_back = ticket;
     r.activation = activation;
     r.done = done;
+    r.arrive_clear = arrive_clear;
     r.arrivals = 0;
     // the record may live in device memory mapped write-combined: plain 8-byte stores in ascending order
     uint64_t words[sizeof r / 8];

@@ -136,9 +136,10 @@ constexpr uint32_t DL_STANDBY_IDLE_US = 2000;  // an executor that has waited th
 // dl_exec.hip: write the record of a request that fits an executor (at most 8 items and max_tiles tiles; default
 // tunables) and return the number of completion words it will report in (one per tile up to DL_DONE_WORDS tiles,
 // else one, counted at the record, which must then be in device memory); 0 if it does not fit.  Launch an
-// executor that will read that record.
+// executor that will read that record.  arrive_clear: the counter set of the ticket's slot that the request is
+// to clear (see dl_arm).
 uint32_t dl_standby_fill(void *rec_mem, const dl_plan_item *items, size_t n, uint64_t activation, uint64_t ticket,
-                         uint64_t *done, uint32_t max_tiles);
+                         uint64_t *done, uint32_t *arrive_clear, uint32_t max_tiles);
 int dl_standby_launch(void *rec_mem, const dl_arm *a, hipStream_t stream);
 // dl_prelaunch.hip: hand the request to a waiting executor if it fits and one is fresh; *taken says whether.
 int dl_standby_try(const dl_plan_item *items, size_t n, bool *taken);

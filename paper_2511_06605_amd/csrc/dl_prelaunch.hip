@@ -330,7 +330,9 @@ int dl_standby_try(const dl_plan_item *items, size_t n, bool *taken)
     // caller that comes back faster than the launch gap waits here for what it would have waited for anyway.
     if (wait_word(&g_arm.host->sb_resident[e], g_sb_act[e], 20000ull, nullptr) != DL_OK) return DL_OK;
     // a request of more tiles than completion words counts its workgroups in at the record: device memory only
+    const uint32_t set = (uint32_t)(ticket / SLOTS) & 1u;  // as in dl_armed_begin: this ticket's set; it clears the other
     const uint32_t words = dl_standby_fill(standby_rec(e), items, n, g_sb_act[e], ticket, g_arm.host->done[slot],
+                                           (uint32_t *)g_arm.dev->arrive[slot][set ^ 1u],
                                            g_sb_rec_dev ? DL_STANDBY_GRID : DL_DONE_WORDS);
     if (words == 0) return DL_OK;
     standby_store(standby_bell(e), g_sb_act[e]);  // the executor's doorbell, behind its record
@@ -349,9 +351,14 @@ int dl_standby_try(const dl_plan_item *items, size_t n, bool *taken)
     // ticket: it has no swaps, so copying some of its bytes twice gives the same result.
     DL_HIP(hipStreamSynchronize(g_arm.sb_stream[e]));
     const int served = wait_done(ticket, 0, nullptr);
-    if (served != DL_OK)
+    if (served != DL_OK) {
+        // what the executor would have done for the slot besides copying: clear the other set of counters
+        DL_HIP(hipMemsetAsync(g_arm.dev->arrive[slot][set ^ 1u], 0, sizeof g_arm.dev->arrive[slot][set ^ 1u],
+                              g_arm.sb_stream[e]));
+        DL_HIP(hipStreamSynchronize(g_arm.sb_stream[e]));
         for (uint32_t w = 0; w < words; ++w)
             __atomic_store_n(&g_arm.host->done[slot][w], ticket, __ATOMIC_RELEASE);
+    }
     *taken = served == DL_OK;
     return standby_arm(e);
 }
