@@ -468,11 +468,11 @@ constexpr uint32_t ARMED_DIRECT_MAX = 16;  // up to this many workgroups all pol
 // share that SIMD with even one waiting wavefront, and behind a grid that had a workgroup on every compute
 // unit such a kernel did not start until the armed request expired.  Unless the caller sets the cap, the grid
 // has at most one workgroup for every other compute unit.
-uint32_t armed_grid(uint64_t tiles, uint32_t block_threads)
+// A kernel that does not wait (signal mode) is in nobody's way: it gets half of the wavefront slots.
+uint32_t armed_grid(uint64_t tiles, uint32_t block_threads, bool waits)
 {
-    (void)block_threads;
     const uint32_t cus = (uint32_t)(g_dl.num_cu > 0 ? g_dl.num_cu : 256);
-    uint32_t cap = g_dl.cfg.armed_blocks ? g_dl.cfg.armed_blocks : cus / 2u;
+    uint32_t cap = g_dl.cfg.armed_blocks ? g_dl.cfg.armed_blocks : waits ? cus / 2u : 16u * cus / (block_threads / 64u);
     if (cap < 1u) cap = 1u;
     if (cap > 32768u) cap = 32768u;  // the arrival counter keeps 16 bits for the count
     return (uint32_t)(tiles < cap ? tiles : cap);
@@ -498,7 +498,7 @@ int launch_klist(const Item *items, size_t n, const uint64_t *tile_end, const dl
     const uint32_t grid = (uint32_t)tile_end[n - 1];
     if (arm) {
         dl_arm a = *arm;
-        const uint32_t g = armed_grid(grid, sh.block_threads);
+        const uint32_t g = armed_grid(grid, sh.block_threads, !a.nowait);
         a.direct = g <= a.direct_max ? 1u : 0u;
         a.own_word = g <= DL_DONE_WORDS && !a.trace_host ? 1u : 0u;  // the stamps come from the last arriver
         g_dl.armed_words = a.own_word ? g : 1u;
@@ -786,7 +786,7 @@ int launch_table(const Item *items, size_t n, dl_launch_shape sh, hipStream_t st
         }
         if (arm) {
             dl_arm a = *arm;
-            const uint32_t g = armed_grid(m, sh.block_threads);
+            const uint32_t g = armed_grid(m, sh.block_threads, !a.nowait);
             a.direct = g <= a.direct_max ? 1u : 0u;
             a.own_word = g <= DL_DONE_WORDS && !a.trace_host ? 1u : 0u;
             g_dl.armed_words = a.own_word ? g : 1u;
