@@ -27,6 +27,11 @@
  *    lists go through table memory that the library reuses (host writes at
  *    call time, events) and must not be captured; neither may prelaunch,
  *    signal or standby mode.
+ *  - Where the device exposes all of its memory to the host through a PCIe
+ *    BAR, the library writes what its kernels read first (doorbells, the
+ *    tables of long lists, standby records) straight into device memory.
+ *    With DL_NO_BAR=1 in the environment at dl_init() it keeps all of that in
+ *    host-coherent memory, as it does on a device without such a BAR.
  *  - Return value: DL_OK (0) or a negative dl_status.  No exceptions, no
  *    aborts.  On DL_ERR_HIP, dl_last_hip_error() gives the hipError_t.
  *  - Not thread-safe: one host thread drives the library at a time.

@@ -14,6 +14,7 @@
 #include "dl_internal.h"
 
 #include <immintrin.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <type_traits>
@@ -1043,6 +1044,8 @@ int dl_ring_release(size_t slot, hipStream_t stream)
 // once per process and kept until it ends.
 void *dl_bar_memory(size_t bytes)
 {
+    const char *off = getenv("DL_NO_BAR");  // "1": keep everything the host writes in host memory
+    if (off && off[0] == '1') return nullptr;
     int large_bar = 0;
     if (hipDeviceGetAttribute(&large_bar, hipDeviceAttributeIsLargeBar, g_dl.device) != hipSuccess || large_bar != 1) {
         (void)hipGetLastError();

@@ -229,6 +229,38 @@ def mode_switches_and_stop():
         raise AssertionError("standby mode accepted without a prelaunch session")
 
 
+def armed_requests_of_every_grid_size():
+    """Prelaunch mode beside the standby checks, so that both ways of placing the doorbell (device memory, host
+    memory with a hop through device flags above 16 workgroups) get the same requests: all-gathers from one
+    workgroup to the capped grid, and a long list."""
+    dl.dl_set_config(arm_timeout_us=ARM_US)
+    dl.dl_prelaunch_start()
+    try:
+        dl.dl_set_mode(dl.DL_MODE_PRELAUNCH)
+        for W, B in [(8, 512), (8, 4 * KiB), (8, 16 * KiB), (8, 24 * KiB + 48), (8, 64 * KiB), (8, 256 * KiB),
+                     (8, 1 * MiB + 16), (3, 5 * MiB + 7)]:
+            ins = inputs.allgather_inputs(W, B, seed=B + W)
+            d_in = [DevBuf(B, fill=a) for a in ins]
+            d_out = [DevBuf(W * B) for _ in range(W)]
+            sync()
+            dl.dl_allgather([b.ptr() for b in d_in], [b.ptr() for b in d_out], B)
+            dl.dl_trigger()
+            dl.dl_wait()
+            for r, w in zip(d_out, ref.allgather(ins)):
+                assert np.array_equal(r.host(), w) and r.guards_intact(), f"armed all-gather W={W} B={B}"
+        arena, descs = inputs.mixed_batch(300, 5000, 4 * MiB, seed=11)
+        want = ref.batch_copy([arena.copy()], [(0, s, 0, d, m) for s, d, m in descs])[0]
+        d = DevBuf(arena.size, fill=arena)
+        sync()
+        dl.dl_batch_copy([(d.ptr(int(s)), d.ptr(int(t)), int(m)) for s, t, m in descs])
+        dl.dl_trigger()
+        dl.dl_wait()
+        assert np.array_equal(d.host(), want) and d.guards_intact()
+    finally:
+        dl.dl_set_mode(dl.DL_MODE_ONESHOT)
+        dl.dl_prelaunch_stop()
+
+
 def random_requests():
     """The seeded random requests of test_gpu_random.py with standby mode among the modes drawn."""
     import test_gpu_random as rnd
@@ -236,14 +268,15 @@ def random_requests():
     dl.dl_prelaunch_start()
     try:
         for seed in range(5000, 5000 + int(os.environ.get("DL_TEST_RANDOM_CASES", "150"))):
-            rnd.run_case(ref, seed, modes=("standby", "standby", "standby", "signal", "oneshot"))
+            rnd.run_case(ref, seed, modes=("standby", "standby", "standby", "signal", "oneshot", "prelaunch"))
     finally:
         dl.dl_set_mode(dl.DL_MODE_ONESHOT)
         dl.dl_prelaunch_stop()
 
 
 CHECKS = [allgather_sizes, allgather_misaligned, other_operations, many_requests_with_changing_sources,
-          kernels_that_gave_up_are_replaced, requests_close_to_the_limit, mode_switches_and_stop, random_requests]
+          kernels_that_gave_up_are_replaced, requests_close_to_the_limit, mode_switches_and_stop,
+          armed_requests_of_every_grid_size, random_requests]
 
 
 def main():
