@@ -194,7 +194,7 @@ int dl_dispatch_on_device(const void *const *in, void *const *out, int W, const 
         hipLaunchKernelGGL(dl_dispatch_build_kernel<false>, grid, dim3(BUILD_THREADS), 0, stream, mask, rows_before, a, items);
     DL_HIP(hipGetLastError());
     if (pushed) {
-        rc = dl_push_commit();
+        rc = dl_push_commit(stream);
         if (rc != DL_OK) return rc;
     }
     rc = dl_launch_fused_rows_table(items, (uint32_t)total, row_bytes, stream);

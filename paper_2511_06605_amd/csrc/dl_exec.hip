@@ -394,20 +394,27 @@ constexpr size_t RING_SLOTS = 4;
 constexpr size_t RING_SLOT_BYTES = DL_RING_SLOT_BYTES;
 
 constexpr size_t PUSH_SLOT_BYTES = 64u << 10;  // longest table that is written through the BAR
-constexpr size_t PUSH_SLOTS = 64, PUSH_HALF = PUSH_SLOTS / 2;
+constexpr size_t PUSH_SLOTS = 64, PUSH_BATCH = PUSH_SLOTS / 2;
 
 struct ring_t {
     char *base = nullptr;  // pinned host memory: the host writes tables here
     char *dev = nullptr;   // device memory of the same shape: long tables are staged here before they are used
     // Tables written through the BAR (see push_acquire): PUSH_SLOTS slots of device memory that the host can
-    // store into, used in turn.  No event per table: one per half of the ring, recorded behind the half's last
-    // launch and waited for before the half is entered again, PUSH_HALF requests later.
+    // store into, used in turn.  Before a slot is used again the kernel that read its table must have ended:
+    // cover[s] names the slot whose event was recorded behind that kernel.  On a stream that cannot go away
+    // between calls (the default stream, the library's own) the launches of up to PUSH_BATCH calls in a row
+    // share one event, recorded behind the last of them; on a caller's stream every launch gets its own, while
+    // the handle is known to be good.
     char *push = nullptr;
     size_t push_next = 0;                 // slot that the next table takes
-    hipEvent_t push_ev[2]{};
-    bool push_pending[2]{};               // the half's event has been recorded and not waited for yet
-    hipStream_t push_stream[2]{};         // the stream on which the half's tables so far were launched
-    uint64_t push_armed[2]{};             // last ticket of an armed (prelaunch mode) request with a table in the half, or 0
+    hipEvent_t push_ev[PUSH_SLOTS]{};
+    int push_cover[PUSH_SLOTS]{};         // -1: never used, or used in the batch that is still open
+    bool push_used[PUSH_SLOTS]{};
+    uint64_t push_armed[PUSH_SLOTS]{};    // ticket of the armed (prelaunch mode) request whose table is in the slot, or 0
+    size_t batch_first = 0, batch_len = 0;  // the open batch: slots batch_first .. batch_first + batch_len - 1 (mod PUSH_SLOTS)
+    hipStream_t batch_stream = nullptr;
+    hipStream_t own_stream = nullptr;     // the library's stream for armed requests, while it exists
+    // the pinned ring: an event per slot, recorded behind the kernel that reads it
     hipEvent_t ev[RING_SLOTS]{};
     bool used[RING_SLOTS]{};
     uint64_t armed[RING_SLOTS]{};         // ticket of the armed (prelaunch mode) request whose table is in the slot, or 0
@@ -555,15 +562,14 @@ int wait_for_readers(hipEvent_t ev, uint64_t armed_ticket)
     return DL_OK;
 }
 
-int push_close_half(size_t h)
+// Record one event behind everything the open batch has launched; its slots are covered by it from now on.
+int push_close_batch()
 {
-    if (hipEventRecord(g_ring.push_ev[h], g_ring.push_stream[h]) == hipSuccess) {
-        g_ring.push_pending[h] = true;
-    } else {
-        // the caller has destroyed that stream since; destroying a stream waits for the work queued on it
-        (void)hipGetLastError();
-        g_ring.push_pending[h] = false;
-    }
+    if (g_ring.batch_len == 0) return DL_OK;
+    const size_t last = (g_ring.batch_first + g_ring.batch_len - 1) % PUSH_SLOTS;
+    DL_HIP(hipEventRecord(g_ring.push_ev[last], g_ring.batch_stream));
+    for (size_t q = 0; q < g_ring.batch_len; ++q) g_ring.push_cover[(g_ring.batch_first + q) % PUSH_SLOTS] = (int)last;
+    g_ring.batch_len = 0;
     return DL_OK;
 }
 
@@ -571,32 +577,43 @@ char *push_acquire(size_t table_bytes, hipStream_t stream, int *rc)
 {
     *rc = DL_OK;
     if (!g_ring.push || !g_dl.cfg.table_push || table_bytes > PUSH_SLOT_BYTES) return nullptr;
-    size_t s = g_ring.push_next, h = s / PUSH_HALF;
-    if (s % PUSH_HALF != 0 && stream != g_ring.push_stream[h]) {
-        // one event covers a half only if all of its launches are on one stream: leave this half here
-        if ((*rc = push_close_half(h)) != DL_OK) return nullptr;
-        h ^= 1;
-        s = h * PUSH_HALF;
-        g_ring.push_next = s;  // also if the wait below refuses
-    }
-    if (s % PUSH_HALF == 0) {
-        if (g_ring.push_pending[h]) {  // the kernels that read this half's previous tables must have ended
-            if ((*rc = wait_for_readers(g_ring.push_ev[h], g_ring.push_armed[h])) != DL_OK) return nullptr;
-            g_ring.push_pending[h] = false;
+    // a batch is one stream's: another stream ends it (on its own stream, which is one that cannot have gone)
+    if (g_ring.batch_len && (stream != g_ring.batch_stream || g_ring.batch_len >= PUSH_BATCH))
+        if ((*rc = push_close_batch()) != DL_OK) return nullptr;
+    const size_t s = g_ring.push_next;
+    if (g_ring.push_used[s]) {  // the kernel that read this slot's previous table must have ended
+        if (g_ring.push_cover[s] < 0) {
+            *rc = DL_ERR_STATE;  // cannot happen: a batch is shorter than the ring
+            return nullptr;
         }
-        g_ring.push_armed[h] = 0;
-        g_ring.push_stream[h] = stream;
+        if ((*rc = wait_for_readers(g_ring.push_ev[g_ring.push_cover[s]], g_ring.push_armed[s])) != DL_OK) return nullptr;
     }
-    g_ring.push_next = s + 1;
+    g_ring.push_used[s] = false;  // free until push_commit: a call that fails in between leaves it so
+    g_ring.push_armed[s] = 0;
     return g_ring.push + s * PUSH_SLOT_BYTES;
 }
 
-int push_commit()
+// After the launch that reads the slot push_acquire gave out last (only then is the slot taken).  armed_ticket: that launch is a request armed
+// in prelaunch mode (0: it is not).
+int push_commit(hipStream_t stream, uint64_t armed_ticket)
 {
-    if (g_ring.push_next % PUSH_HALF != 0) return DL_OK;
-    const size_t h = (g_ring.push_next - 1) / PUSH_HALF;  // the half whose last slot was just used
-    g_ring.push_next = (h ^ 1) * PUSH_HALF;
-    return push_close_half(h);
+    const size_t s = g_ring.push_next;
+    g_ring.push_next = (s + 1) % PUSH_SLOTS;
+    g_ring.push_used[s] = true;
+    g_ring.push_cover[s] = -1;
+    g_ring.push_armed[s] = armed_ticket;
+    if (stream == nullptr || stream == g_ring.own_stream) {
+        if (g_ring.batch_len == 0) {
+            g_ring.batch_first = s;
+            g_ring.batch_stream = stream;
+        }
+        ++g_ring.batch_len;
+        return DL_OK;
+    }
+    // a caller's stream: it may be gone by the next call, so its event is recorded now
+    DL_HIP(hipEventRecord(g_ring.push_ev[s], stream));
+    g_ring.push_cover[s] = (int)s;
+    return DL_OK;
 }
 
 // Copy `bytes` (a multiple of 16) from a slot of the pinned ring to the same slot of its device
@@ -692,7 +709,7 @@ bool launch_uniform_rows(const Item *items, size_t n, const dl_launch_shape &sh,
         return true;
     }
     if (pushed) {
-        *rc = push_commit();
+        *rc = push_commit(stream, 0);
         return true;
     }
     g_ring.used[s] = true;
@@ -742,6 +759,7 @@ int launch_table(const Item *items, size_t n, dl_launch_shape sh, hipStream_t st
     while (i < n) {
         // a short table that is all of the request
         char *pushed = nullptr;
+        uint64_t pushed_armed_ticket = 0;
         if (i == 0 && off == 0) {
             int rc = DL_OK;
             pushed = push_acquire(all_entries * sizeof(Item), stream, &rc);
@@ -798,7 +816,12 @@ int launch_table(const Item *items, size_t n, dl_launch_shape sh, hipStream_t st
                 hipLaunchKernelGGL((dl_armed_table_kernel<Item, false>), dim3(g), dim3(sh.block_threads), 0, stream, slot,
                                    (uint32_t)m, sh.tile_bytes, sh.split, a);
             // whoever wants this memory next must not wait for a request that nobody has triggered
-            if (!a.nowait) (pushed ? g_ring.push_armed[(g_ring.push_next - 1) / PUSH_HALF] : g_ring.armed[s]) = a.ticket;
+            if (!a.nowait) {
+                if (pushed)
+                    pushed_armed_ticket = a.ticket;
+                else
+                    g_ring.armed[s] = a.ticket;
+            }
         } else {
             with_policy(sh.policy, [&](auto pol) {
                 if (pushed)
@@ -811,7 +834,7 @@ int launch_table(const Item *items, size_t n, dl_launch_shape sh, hipStream_t st
         }
         DL_HIP(hipGetLastError());
         if (pushed) {
-            const int rc = push_commit();
+            const int rc = push_commit(stream, pushed_armed_ticket);
             if (rc != DL_OK) return rc;
             continue;
         }
@@ -1027,11 +1050,17 @@ int dl_ring_stage(size_t slot, uint64_t bytes, hipStream_t stream) { return stag
 void dl_ring_forget_armed()
 {
     for (size_t s = 0; s < RING_SLOTS; ++s) g_ring.armed[s] = 0;
-    g_ring.push_armed[0] = g_ring.push_armed[1] = 0;
+    for (size_t s = 0; s < PUSH_SLOTS; ++s) g_ring.push_armed[s] = 0;
+}
+
+void dl_ring_own_stream(hipStream_t stream)
+{
+    if (!stream && g_ring.batch_len && g_ring.batch_stream == g_ring.own_stream) (void)push_close_batch();
+    g_ring.own_stream = stream;
 }
 
 char *dl_push_acquire(size_t bytes, hipStream_t stream, int *rc) { return push_acquire(bytes, stream, rc); }
-int dl_push_commit() { return push_commit(); }
+int dl_push_commit(hipStream_t stream) { return push_commit(stream, 0); }
 
 int dl_ring_release(size_t slot, hipStream_t stream)
 {
@@ -1074,9 +1103,13 @@ int dl_exec_init()
     if (g_ring.base) return DL_OK;
     g_ring.push = push_memory;
     g_ring.push_next = 0;
-    for (int h = 0; h < 2; ++h) {
-        DL_HIP(hipEventCreateWithFlags(&g_ring.push_ev[h], hipEventDisableTiming));
-        g_ring.push_pending[h] = false;
+    g_ring.batch_len = 0;
+    g_ring.own_stream = nullptr;
+    for (size_t q = 0; q < PUSH_SLOTS; ++q) {
+        DL_HIP(hipEventCreateWithFlags(&g_ring.push_ev[q], hipEventDisableTiming));
+        g_ring.push_used[q] = false;
+        g_ring.push_cover[q] = -1;
+        g_ring.push_armed[q] = 0;
     }
     DL_HIP(hipHostMalloc((void **)&g_ring.base, RING_SLOTS * RING_SLOT_BYTES, hipHostMallocDefault));
     DL_HIP(hipMalloc((void **)&g_ring.dev, RING_SLOTS * RING_SLOT_BYTES));
@@ -1095,12 +1128,10 @@ int dl_exec_shutdown()
         if (g_ring.used[s]) (void)hipEventSynchronize(g_ring.ev[s]);
         (void)hipEventDestroy(g_ring.ev[s]);
     }
-    for (int h = 0; h < 2; ++h) {
-        if (g_ring.push_pending[h]) (void)hipEventSynchronize(g_ring.push_ev[h]);
-        (void)hipEventDestroy(g_ring.push_ev[h]);
-    }
-    // a half that was left part-used has launches that no event covers, on a stream that may be gone by now
-    if (g_ring.push && g_ring.push_next % PUSH_HALF != 0) (void)hipDeviceSynchronize();
+    // everything launched has ended before the tables' memory is handed out again after the next dl_exec_init
+    // (the open batch has no event yet; its stream is the default one or the library's, which is gone by now)
+    (void)hipDeviceSynchronize();
+    for (size_t q = 0; q < PUSH_SLOTS; ++q) (void)hipEventDestroy(g_ring.push_ev[q]);
     (void)hipHostFree(g_ring.base);
     (void)hipFree(g_ring.dev);
     g_ring.base = nullptr;

@@ -105,11 +105,14 @@ int dl_ring_release(size_t slot, hipStream_t stream);
 //   dl_push_acquire  a slot for `bytes` that a kernel launched on `stream` next will read, or null if that way is
 //                    not open (no such BAR, switched off, too long); *rc != DL_OK on an error.  Write only, then
 //                    _mm_sfence(), then launch; the kernel must read the slot past the caches.
-//   dl_push_commit   after that launch
+//   dl_push_commit   after that launch, with its stream
 //   dl_ring_forget_armed  every armed request has finished (their tickets start over with the next session)
+//   dl_ring_own_stream  the library's own stream for armed requests exists (or, null, is about to be destroyed):
+//                    the one stream besides the default stream that cannot go away between two calls
 void dl_ring_forget_armed();
+void dl_ring_own_stream(hipStream_t stream);
 char *dl_push_acquire(size_t bytes, hipStream_t stream, int *rc);
-int dl_push_commit();
+int dl_push_commit(hipStream_t stream);
 
 // dl_exec.hip: the row kernel over a table of n equally sized read-once/write-k items that is already in
 // device memory, destinations laid out for DL_TABLE_ROWS_SPLIT sub-groups (see slots_by_subgroup).

@@ -401,6 +401,7 @@ int dl_prelaunch_start(void)
     }
     g_arm.seq = 0;
     g_arm.started = true;
+    dl_ring_own_stream(g_arm.stream);
     return DL_OK;
 }
 
@@ -419,6 +420,7 @@ int dl_prelaunch_stop(void)
         rc = wait_done(t, drain_ns(), nullptr);
     if (rc != DL_OK) return rc;  // words stay allocated: a kernel may still use them
     dl_ring_forget_armed();
+    dl_ring_own_stream(nullptr);
     (void)hipStreamSynchronize(g_arm.stream);
     (void)hipStreamDestroy(g_arm.stream);
     for (int e = 0; e < DL_STANDBY_POOL; ++e)

@@ -9,6 +9,7 @@ two of standby mode: one hardware queue each.
 
 Every waiting kernel gives up by itself after 2 ms, so nothing stays on the device."""
 
+import faulthandler
 import os
 import sys
 import time
@@ -281,6 +282,7 @@ CHECKS = [allgather_sizes, allgather_misaligned, other_operations, many_requests
 
 def main():
     import torch
+    faulthandler.enable()   # a crash in native code names the Python line it came from
     assert torch.cuda.is_available()
     torch.cuda.set_device(0)
     ref.build()

@@ -333,6 +333,8 @@ def test_many_long_lists_armed_at_once(ref, armed, push, count):
     is reused in turn: 40 of them at once with the tables written through the BAR; through the pinned ring four,
     and the fifth is refused at once (it could only get its slot by outwaiting an untriggered request) and can
     be armed after the others have run."""
+    if push and os.environ.get("DL_NO_BAR") == "1":
+        pytest.skip("tables are kept in the pinned ring: four at a time")
     base = dl.dl_get_config()
     saved = {f[0]: getattr(base, f[0]) for f in base._fields_}
     dl.dl_set_config(table_push=push)
