@@ -52,8 +52,8 @@ typedef enum dl_status {
     DL_ERR_OVERLAP = -2,  /* a destination overlaps another destination or a source (validation on) */
     DL_ERR_HIP = -3,      /* a HIP call failed; see dl_last_hip_error() */
     DL_ERR_TIMEOUT = -4,  /* a host-side wait gave up */
-    DL_ERR_STATE = -5,    /* not initialised; prelaunch mode not started; started twice */
-    DL_ERR_EXPIRED = -6   /* an armed request was cancelled or not triggered within its arm limit: nothing was copied */
+    DL_ERR_STATE = -5,    /* not initialised; prelaunch mode not started; started twice; table memory still held by an armed request that has not been triggered */
+    DL_ERR_EXPIRED = -6   /* an armed request was cancelled or not triggered within its arm limit: nothing, or (triggered at the very limit) only part, was copied */
 } dl_status;
 
 /* Largest number of destinations of one dl_broadcast call / ranks of a collective. */
@@ -184,8 +184,10 @@ int dl_alltoall_inplace(void *const *buf, int W, size_t chunk_bytes, void *strea
  * path).  In DL_MODE_PRELAUNCH each of the four operations enqueues ONE kernel
  * immediately, on `stream` (NULL = a non-blocking stream owned by the library),
  * and returns; dl_last_ticket() then names the request.  The kernel's
- * workgroups become resident and poll a doorbell word in host-coherent memory.
- *   dl_trigger(t)  rings the doorbell for every ticket <= t: one 8-byte store.
+ * workgroups become resident and poll a doorbell word (in device memory that
+ * the host writes through the BAR, else in host-coherent memory).
+ *   dl_trigger(t)  rings the doorbell for every ticket <= t: one 8-byte store
+ *                  (and one more for the host's own copy).
  *                  Everything the request reads must be complete before it.
  *   dl_wait(t, ns) spins on the host until request t has finished: DL_OK,
  *                  DL_ERR_EXPIRED (the request gave up without copying a byte,
@@ -201,7 +203,9 @@ int dl_alltoall_inplace(void *const *buf, int W, size_t chunk_bytes, void *strea
  * workgroup for every other compute unit for one request
  * (dl_config.armed_blocks), so that the kernels which produce its inputs can
  * run beside it, also those that cannot share a SIMD with another wavefront
- * (large matrix multiplications).  Requests armed on different streams are
+ * (large matrix multiplications; such a kernel still runs slower beside any
+ * waiting kernel, because some compute units are closed to it).  Requests
+ * armed on different streams are
  * resident together and their workgroups add up: arm large requests on one
  * stream, where they become resident one after the other.
  * A request whose list is too long for the kernel arguments (more than 64
@@ -240,8 +244,10 @@ int dl_alltoall_inplace(void *const *buf, int W, size_t chunk_bytes, void *strea
  * fit, or that find no kernel that is sure to be waiting still (fresh ones
  * are armed at once), run as in DL_MODE_SIGNAL.
  *
- * Waiting kernels and hardware queues.  A kernel that waits (an armed request,
- * a standby kernel) holds the hardware queue that its stream is mapped to, and
+ * What waiting costs others.  A standby kernel holds its compute units like an
+ * armed request does: kernels that can share a SIMD hardly notice, a large
+ * matrix multiplication beside it ran a third to a half slower.  And a kernel
+ * that waits (an armed request, a standby kernel) holds the hardware queue that its stream is mapped to, and
  * the HIP runtime maps all streams of a process to a few hardware queues
  * (GPU_MAX_HW_QUEUES, 4 by default): work on another stream that shares the
  * queue starts only when the waiting kernel has ended, i.e. after its
