@@ -296,7 +296,9 @@ def other_operations(dl, benchaid, inputs, torch, stream, ag_reqs, ag_bufs, ag_s
         row["prelaunch_trigger_to_done_us"] = lat_stats(benchaid.time_host(req, None, benchaid.WAIT_TRIGGER, 30, 300))
         dl.dl_set_mode(dl.DL_MODE_SIGNAL)
         row["signal_call_to_done_us"] = lat_stats(benchaid.time_host(req, None, benchaid.WAIT_SIGNAL, 30, 300))
-        if row.get("tokens", 99) <= 32:  # decode all-gathers short enough for a kernel that already waits (standby mode)
+        # requests short enough for a kernel that already waits (standby mode): decode all-gathers up to 32 tokens,
+        # all-to-alls with chunks up to 8 KiB
+        if row.get("tokens", 99) <= 32 or row.get("chunk_bytes", 1 << 30) <= 8 * KiB:
             dl.dl_set_mode(dl.DL_MODE_STANDBY)
             row["standby_call_to_done_us"] = lat_stats(benchaid.time_host(req, None, benchaid.WAIT_SIGNAL, 30, 300))
     dl.dl_set_mode(dl.DL_MODE_ONESHOT)

@@ -228,10 +228,12 @@ int dl_alltoall_inplace(void *const *buf, int W, size_t chunk_bytes, void *strea
  * Standby mode (DL_MODE_STANDBY) is prelaunch for requests that are not known
  * ahead of time: the library keeps two generic kernels waiting on the device
  * (64 workgroups each, on streams of its own).  A call whose lowered list is
- * short enough (at most 8 copies or read-once/write-k copies, at most 64 tiles
- * of 8 KiB: an all-gather of up to 64 KiB per rank at W = 8, a broadcast of up
- * to 512 KiB, ...; 16 tiles where the device's memory cannot be written by
- * the host through a BAR) writes that list where the waiting kernel will
+ * short enough (at most 8 read-once/write-k copies, or at most 64 plain
+ * copies, and at most 64 tiles of 8 KiB, every copy starting a tile of its
+ * own: an all-gather of up to 64 KiB per rank at W = 8, a broadcast of up to
+ * 512 KiB, an all-to-all between 8 ranks with chunks of up to 8 KiB, ...;
+ * 16 tiles where the device's memory cannot be written by the host through a
+ * BAR) writes that list where the waiting kernel will
  * look for it (device memory, through the BAR, or else host-coherent memory)
  * and rings that kernel's doorbell; the kernel reads the list, copies, and
  * reports in the request's completion words.  The call

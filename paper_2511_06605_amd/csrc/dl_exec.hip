@@ -282,10 +282,17 @@ struct dl_standby_rec {
     // does not use (see dl_arm).  A request served here counts nothing there, but it keeps that chain: this is
     // the set it clears.
     uint32_t *arrive_clear;
-    dl_klist<dl_fused_item, 8> list;
+    uint64_t plain;       // 1: `copies` holds the request (up to 64 plain copies); 0: `list` (up to 8 read-once/write-k items)
+    union {
+        dl_klist<dl_fused_item, 8> list;
+        dl_klist<dl_plain_item, 64> copies;
+    };
     uint64_t ticket_back;
 };
 static_assert(sizeof(dl_standby_rec) <= DL_STANDBY_REC_BYTES && sizeof(dl_standby_rec) % 8 == 0, "record size");
+static_assert(offsetof(dl_standby_rec, list.tile_end) == offsetof(dl_standby_rec, copies.tile_end) &&
+                  offsetof(dl_standby_rec, list.n) == offsetof(dl_standby_rec, copies.n),
+              "the two kinds of list start alike");
 
 // Standby executor: a generic armed kernel (see dl_internal.h).  Its doorbell is its pool slot's, its "ticket"
 // the slot's activation number; the request's own ticket and completion words come with the record.  Workgroup b
@@ -301,20 +308,29 @@ __global__ void __launch_bounds__(DL_STANDBY_THREADS) dl_standby_kernel(dl_stand
     if (threadIdx.x < VEC) raw[threadIdx.x] = dl_ld<DL_POL_COHERENT>(dl_global<dl_u32x4>(rec_mem) + threadIdx.x);
     __syncthreads();
     const dl_standby_rec &rec = *reinterpret_cast<const dl_standby_rec *>(raw);
+    // n, tile_bytes, split and tile_end[] sit at the same offsets in both kinds of list
+    const uint32_t n_max = rec.plain ? 64u : 8u;
     const bool ok = rec.ticket_front != 0 && rec.ticket_front == rec.ticket_back && rec.activation == a.ticket &&
-                    rec.done != nullptr && rec.list.n >= 1 && rec.list.n <= 8 && rec.list.tile_bytes == DL_STANDBY_TILE &&
-                    rec.list.split == 1 && rec.list.tile_end[rec.list.n - 1] <= gridDim.x;
+                    rec.done != nullptr && rec.list.n >= 1 && rec.list.n <= n_max && rec.list.tile_bytes == DL_STANDBY_TILE &&
+                    rec.list.split == 1 && rec.copies.tile_end[rec.list.n - 1] <= gridDim.x;
     if (!ok) return;  // not the announced record: touch nothing (the host's wait for the request times out)
-    const uint32_t tiles = rec.list.tile_end[rec.list.n - 1];
+    const uint32_t tiles = rec.copies.tile_end[rec.list.n - 1];
     if (blockIdx.x >= tiles) return;
     if (blockIdx.x == 0 && threadIdx.x == 0)  // in flight beside the copy, drained with it before the completion word
         for (uint32_t g = 0; rec.arrive_clear && g <= DL_ARM_GROUPS; ++g)
             __hip_atomic_store((uint32_t *)((char *)rec.arrive_clear + g * DL_ARM_STRIDE), 0u, __ATOMIC_RELAXED,
                                __HIP_MEMORY_SCOPE_AGENT);
-    if (rec.rows)
-        dl_run_rows<DL_POL_COHERENT>(rec.list, blockIdx.x);
-    else
-        dl_run_tile<DL_POL_COHERENT>(rec.list, blockIdx.x);
+    if (rec.plain) {
+        if (rec.rows)
+            dl_run_rows<DL_POL_COHERENT>(rec.copies, blockIdx.x);
+        else
+            dl_run_tile<DL_POL_COHERENT>(rec.copies, blockIdx.x);
+    } else {
+        if (rec.rows)
+            dl_run_rows<DL_POL_COHERENT>(rec.list, blockIdx.x);
+        else
+            dl_run_tile<DL_POL_COHERENT>(rec.list, blockIdx.x);
+    }
     // the copy stored at system scope: once the memory counters have drained, the bytes are where everybody sees them
     dl_drain_stores();
     __syncthreads();
@@ -964,42 +980,63 @@ int dl_exec_swap(const dl_swap_item *items, size_t n, hipStream_t stream, const 
     return exec_list(items, n, stream, arm, launched);
 }
 
+template <class Item, int NMAX, class Get>
+uint64_t standby_list(dl_klist<Item, NMAX> &l, size_t n, uint32_t max_tiles, uint64_t *rows, Get get)
+{
+    uint64_t acc = 0;
+    for (size_t i = 0; i < (size_t)NMAX; ++i) {
+        if (i < n) {
+            const Item it = get(i);
+            acc += dl_item_tiles(it, DL_STANDBY_TILE);
+            if (acc > max_tiles) return 0;  // one tile per workgroup, one pass
+            l.item[i] = it;
+            if (!item_aligned16(it)) *rows = 0;
+        }
+        l.tile_end[i] = i < n ? (uint32_t)acc : 0xFFFFFFFFu;
+    }
+    l.n = (uint32_t)n;
+    l.tile_bytes = DL_STANDBY_TILE;
+    l.split = 1;
+    l.split_log2 = 0;
+    l.wpg_log2 = log2u(DL_STANDBY_THREADS / 64u);
+    return acc;
+}
+
 uint32_t dl_standby_fill(void *rec_mem, const dl_plan_item *items, size_t n, uint64_t activation, uint64_t ticket,
                          uint64_t *done, uint32_t *arrive_clear, uint32_t max_tiles)
 {
     const dl_config &c = g_dl.cfg;
-    if (n == 0 || n > 8 || c.tile_bytes || c.block_threads || c.max_blocks || c.armed_blocks) return 0;
+    if (n == 0 || n > 64 || c.tile_bytes || c.block_threads || c.max_blocks || c.armed_blocks) return 0;
     static_assert(sizeof(dl_plan_item) == sizeof(dl_fused_item), "plan items are fused items");
     const dl_fused_item *it = reinterpret_cast<const dl_fused_item *>(items);
-    dl_standby_rec r;
-    memset(&r, 0, sizeof r);
-    uint64_t acc = 0;
+    static dl_standby_rec r;  // 2 KiB: not on the stack of every call
+    uint64_t acc, used;
     r.rows = 1;
-    for (size_t i = 0; i < 8; ++i) {
-        if (i < n) {
-            acc += dl_item_tiles(it[i], DL_STANDBY_TILE);
-            if (acc > max_tiles) return 0;  // one tile per workgroup, one pass
-            r.list.item[i] = it[i];
-            if (!item_aligned16(it[i])) r.rows = 0;
-        }
-        r.list.tile_end[i] = i < n ? (uint32_t)acc : 0xFFFFFFFFu;
+    if (n <= 8) {
+        r.plain = 0;
+        acc = standby_list(r.list, n, max_tiles, &r.rows, [&](size_t i) { return it[i]; });
+        used = offsetof(dl_standby_rec, list) + sizeof r.list;
+    } else {
+        for (size_t i = 0; i < n; ++i)
+            if (it[i].k != 1) return 0;
+        r.plain = 1;
+        acc = standby_list(r.copies, n, max_tiles, &r.rows,
+                           [&](size_t i) { return dl_plain_item{it[i].src, it[i].dst[0], it[i].bytes}; });
+        used = offsetof(dl_standby_rec, copies) + sizeof r.copies;
     }
     if (acc == 0) return 0;
-    r.list.n = (uint32_t)n;
-    r.list.tile_bytes = DL_STANDBY_TILE;
-    r.list.split = 1;
-    r.list.split_log2 = 0;
-    r.list.wpg_log2 = log2u(DL_STANDBY_THREADS / 64u);
     r.ticket_front = r.ticket_back = ticket;
     r.activation = activation;
     r.done = done;
     r.arrive_clear = arrive_clear;
     r.arrivals = 0;
-    // the record may live in device memory mapped write-combined: plain 8-byte stores in ascending order
-    uint64_t words[sizeof r / 8];
+    // The record may live in device memory mapped write-combined: plain 8-byte stores in ascending order, of the
+    // part that this kind of list uses and of the closing ticket.
+    static uint64_t words[sizeof r / 8];
     memcpy(words, &r, sizeof r);
     volatile uint64_t *out = (volatile uint64_t *)rec_mem;
-    for (size_t q = 0; q < sizeof r / 8; ++q) out[q] = words[q];
+    for (size_t q = 0; q < (used + 7) / 8; ++q) out[q] = words[q];
+    out[sizeof r / 8 - 1] = words[sizeof r / 8 - 1];
     return acc <= DL_DONE_WORDS ? (uint32_t)acc : 1u;
 }
 

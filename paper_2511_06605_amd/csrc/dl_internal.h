@@ -134,10 +134,10 @@ constexpr int DL_STANDBY_POOL = 2;
 constexpr uint32_t DL_STANDBY_GRID = 64;      // workgroups of an executor: the most tiles a request may have
 constexpr uint32_t DL_STANDBY_THREADS = 512;
 constexpr uint32_t DL_STANDBY_TILE = 8192;     // one 1 KiB row per wavefront
-constexpr size_t DL_STANDBY_REC_BYTES = 1024;  // room for the record
+constexpr size_t DL_STANDBY_REC_BYTES = 2048;  // room for the record
 constexpr uint32_t DL_STANDBY_IDLE_US = 2000;  // an executor that has waited this long gives up (or the arm limit, if shorter)
-// dl_exec.hip: write the record of a request that fits an executor (at most 8 items and max_tiles tiles; default
-// tunables) and return the number of completion words it will report in (one per tile up to DL_DONE_WORDS tiles,
+// dl_exec.hip: write the record of a request that fits an executor (at most 8 items, or at most 64 that are all
+// plain copies, and max_tiles tiles; default tunables) and return the number of completion words it will report in (one per tile up to DL_DONE_WORDS tiles,
 // else one, counted at the record, which must then be in device memory); 0 if it does not fit.  Launch an
 // executor that will read that record.  arrive_clear: the counter set of the ticket's slot that the request is
 // to clear (see dl_arm).

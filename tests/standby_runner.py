@@ -104,9 +104,11 @@ def other_operations():
         dl.dl_batch_copy([(d.ptr(int(s)), d.ptr(int(t)), int(m)) for s, t, m in descs])
         dl.dl_wait()
         assert np.array_equal(d.host(), want) and d.guards_intact()
-        # all-to-all between two ranks (4 chunks), and between eight (64 chunks: the ordinary launch)
-        for W in (2, 8):
-            C = inputs.random_chunks(W, 5000, seed=W, zero_frac=0.2)
+        # all-to-all between two ranks (4 chunks), between eight (64 plain copies of up to 5000 bytes: one tile each),
+        # between eight with chunks of up to three tiles (too many tiles: the ordinary launch) and between nine
+        # (81 copies: too many)
+        for W, top in ((2, 5000), (8, 5000), (8, 8192), (8, 20000), (9, 3000)):
+            C = inputs.random_chunks(W, top, seed=W + top, zero_frac=0.2)
             ins = inputs.alltoall_inputs(C, seed=W + 1)
             want = ref.alltoall(ins, C)
             d_in = [DevBuf(a.size, fill=a) for a in ins]
@@ -116,6 +118,15 @@ def other_operations():
             dl.dl_wait()
             for j in range(W):
                 assert np.array_equal(d_out[j].host(), want[j]) and d_out[j].guards_intact()
+        # batches of 9, 40 and 64 copies of unequal sizes and alignments (plain lists), and 65 (too many)
+        for n in (9, 40, 64, 65):
+            arena, descs = inputs.mixed_batch(n, 6000, 2 * MiB, seed=100 + n)
+            want = ref.batch_copy([arena.copy()], [(0, s, 0, t, m) for s, t, m in descs])[0]
+            d = DevBuf(arena.size, fill=arena)
+            sync()
+            dl.dl_batch_copy([(d.ptr(int(s)), d.ptr(int(t)), int(m)) for s, t, m in descs])
+            dl.dl_wait()
+            assert np.array_equal(d.host(), want) and d.guards_intact(), f"batch of {n}"
         # an in-place all-to-all (swaps): never handed to a waiting kernel, same result
         bufs = inputs.alltoall_inputs(inputs.uniform_chunks(4, 3000), seed=9)
         d_buf = [DevBuf(a.size, fill=a) for a in bufs]
