@@ -130,7 +130,7 @@ __device__ __forceinline__ uint32_t dl_arm_wait(const dl_arm &a)
         const uint64_t t0 = wall_clock64();
         if (blockIdx.x == 0) dl_arm_housekeeping(a);  // before the wait: off the critical path
         if (a.direct || blockIdx.x == 0) {
-            // poll the host doorbell (uncached system-scope loads over the host link)
+            // poll the doorbell (system-scope loads past every cache: device memory, or host memory over the link)
             for (uint32_t spins = 1;; ++spins) {
                 // doorbell and cancel word sit side by side in one aligned 16 bytes: one read over the link
                 // (each is an aligned 8-byte word that the host writes with one store, so neither can tear)
@@ -484,7 +484,7 @@ inline void slots_by_subgroup(dl_fused_item &it, uint32_t split)
 inline uint32_t item_k(const dl_plain_item &) { return 1; }
 inline uint32_t item_k(const dl_fused_item &it) { return it.k; }
 
-constexpr uint32_t ARMED_DIRECT_MAX = 16;  // up to this many workgroups all poll the host doorbell themselves
+constexpr uint32_t ARMED_DIRECT_MAX = 16;  // grids up to this size report in a completion word per workgroup; the shape rule below aims for them
 
 // Workgroups of an armed kernel.  While it waits for its doorbell the kernel must leave room for other
 // kernels, above all for the ones that produce what it is going to copy.  Room means whole compute units: a
@@ -880,10 +880,11 @@ int exec_list(const Item *items, size_t n, hipStream_t stream, const dl_arm *arm
         sh.tile_bytes = 4096;
         sh.block_threads = biggest >= 4096 ? 256u : sh.block_threads;
         sh.split = 1;
-        // Up to ARMED_DIRECT_MAX workgroups see the doorbell themselves (all-gather: 5.0-5.2 us up to 16 KiB per
-        // rank; 32 or 64 pollers took 7 and 9.5 us, the fan-out through device flags 6.5).  A request too long for
-        // that takes eight wavefronts per workgroup where that cuts the number of workgroups: more of them stay
-        // below the limit, and above it arrivals and passes over a capped grid halve (1 MiB per rank: 17.1 -> 14.6 us).
+        // Up to ARMED_DIRECT_MAX workgroups report each in a completion word of its own, and with the doorbell
+        // in host memory only that many poll it themselves (32 or 64 pollers over the link took 7 and 9.5 us,
+        // the hop through device flags 6.5, against 5.0-5.2).  A request too long for that takes eight
+        // wavefronts per workgroup where that cuts the number of workgroups: more of them stay below the limit,
+        // and above it arrivals and passes over a capped grid halve (1 MiB per rank: 17.1 -> 14.6 us).
         uint64_t t4 = 0, t8 = 0;
         for (size_t i = 0; i < n; ++i) {
             t4 += dl_item_tiles(items[i], 4096);

@@ -4,14 +4,17 @@
 //
 // Each request issued in prelaunch mode is its own kernel, enqueued at once on
 // the caller's stream (or the library's non-blocking stream).  Its workgroups
-// poll the doorbell in host-coherent memory until it reaches the request's
-// ticket, copy, and the last workgroup to finish writes the ticket into the
-// request's completion word, again in host-coherent memory.  dl_trigger() is
-// one 8-byte store; dl_wait() spins on the completion word.
+// poll the doorbell (in device memory that the host writes through the BAR,
+// else in host-coherent memory) until it reaches the request's ticket, copy,
+// and report in the request's completion words, in host-coherent memory: each
+// workgroup in a word of its own if they are few, else the last one to finish
+// in one word.  dl_trigger() is one 8-byte store (two where the doorbell has a
+// copy on the device); dl_wait() spins on the completion words.
 //
 // A wave never lives longer than the arm limit (plus the copy itself): a
 // request that is not triggered in time gives up without copying and reports
-// that.  Nothing stays resident between requests.
+// that.  Nothing stays resident between requests, except in standby mode, where
+// two generic kernels wait for whatever small request comes next (2 ms at most).
 #include "dl_internal.h"
 
 #include <immintrin.h>
