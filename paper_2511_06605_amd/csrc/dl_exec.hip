@@ -1132,10 +1132,11 @@ void *dl_bar_memory(size_t bytes)
 
 int dl_exec_init()
 {
-    static bool push_tried = false;
+    // kept for the life of the process, per device: what was made for another device is left behind
+    static int push_device = -1;
     static char *push_memory = nullptr;
-    if (!push_tried) {
-        push_tried = true;
+    if (push_device != g_dl.device) {
+        push_device = g_dl.device;
         push_memory = (char *)dl_bar_memory(PUSH_SLOTS * PUSH_SLOT_BYTES);
     }
     if (g_ring.base) return DL_OK;

@@ -143,7 +143,7 @@ namespace {
 // the BAR (made once per process, never freed; set to zero at the start of every session, before anything is
 // armed).  The pair in host memory is kept up to date as well: the host reads its own doorbell there.
 uint64_t *g_bell_dev = nullptr;
-bool g_bell_dev_tried = false;
+int g_bell_dev_device = -1;  // the device it was made for (what was made for another device is left behind)
 
 void bell_store(uint64_t *host_word, uint64_t *dev_word, uint64_t v)
 {
@@ -192,7 +192,7 @@ namespace {
 // doorbell), and the executor finds it in device memory instead of fetching it over the link (1 us less).  The
 // allocation is made once per process and never freed.  Without a large BAR the records stay in host memory.
 uint8_t *g_sb_rec_dev = nullptr;
-bool g_sb_rec_dev_tried = false;
+int g_sb_rec_dev_device = -1;  // the device it was made for
 constexpr size_t SB_DEV_STRIDE = 2 * DL_STANDBY_REC_BYTES;  // per pool slot: the record, then {doorbell, cancel}
 
 // Activation number of the executor armed last in each pool slot (0: none yet).  It only ever grows, over the
@@ -227,8 +227,10 @@ void standby_store(uint64_t *word, uint64_t v)
 
 void standby_place_records()
 {
-    if (g_sb_rec_dev_tried) return;
-    g_sb_rec_dev_tried = true;
+    if (g_sb_rec_dev_device == g_dl.device) return;
+    g_sb_rec_dev_device = g_dl.device;
+    g_sb_rec_dev = nullptr;
+    for (int e = 0; e < DL_STANDBY_POOL; ++e) g_sb_act[e] = 0;  // fresh doorbells (zero) on this device
     void *p = dl_bar_memory(DL_STANDBY_POOL * SB_DEV_STRIDE);
     if (!p) return;
     g_sb_rec_dev = (uint8_t *)p;
@@ -394,8 +396,8 @@ int dl_prelaunch_start(void)
         g_arm = arm_state{};
         return DL_ERR_HIP;
     }
-    if (!g_bell_dev_tried) {
-        g_bell_dev_tried = true;
+    if (g_bell_dev_device != g_dl.device) {
+        g_bell_dev_device = g_dl.device;
         g_bell_dev = (uint64_t *)dl_bar_memory(256);
     }
     if (g_bell_dev) {  // tickets start over: so do doorbell and cancel word (nothing is armed yet)
