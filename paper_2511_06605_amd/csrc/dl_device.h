@@ -261,6 +261,17 @@ __device__ __forceinline__ void dl_swap_tile(char *a, char *b, uint64_t bytes, u
         dl_swap_elems<uint8_t, POL>(a, b, off, n, tid, nthr);
 }
 
+// A slot that the host filled through the BAR carries a stamp behind its payload, written after it; writes that
+// cross the link arrive in order, so once the stamp is there what was written before it is there too.  The word
+// that holds it (`slot` is the slot's first byte):
+__device__ __forceinline__ const DL_GLOBAL uint64_t *dl_pushed_stamp(const void *slot)
+{
+    return dl_global<uint64_t>((const char *)slot + DL_PUSH_PAYLOAD_BYTES);
+}
+// How often a kernel looks again if the stamp is not there at the first look (the launch overtook the writes
+// inside the device; they were on their way before it): bounded, like every wait in this library.
+constexpr uint32_t DL_PUSHED_TRIES = 1u << 22;
+
 // ------------------------------------------------ items and lists on the device
 
 __device__ __forceinline__ uint64_t dl_uniform64(uint64_t v)

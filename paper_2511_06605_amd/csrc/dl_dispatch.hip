@@ -12,7 +12,6 @@
 #include "dl_device.h"
 #include "dl_internal.h"
 
-#include <immintrin.h>
 #include <string.h>
 
 namespace {
@@ -41,7 +40,7 @@ template <bool PUSHED>
 __global__ void __launch_bounds__(BUILD_THREADS) dl_dispatch_build_kernel(const uint8_t *__restrict__ mask,
                                                                           const uint32_t *__restrict__ block_rows,
                                                                           const build_args a,
-                                                                          dl_fused_item *__restrict__ items)
+                                                                          dl_fused_item *__restrict__ items, uint64_t stamp)
 {
     constexpr int POL = PUSHED ? DL_POL_COHERENT : DL_POL_PLAIN;
     __shared__ uint32_t before_block[DISPATCH_W];          // rows taken by the tokens of earlier blocks
@@ -49,11 +48,26 @@ __global__ void __launch_bounds__(BUILD_THREADS) dl_dispatch_build_kernel(const 
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     constexpr uint32_t W = DISPATCH_W;
     const uint32_t block0 = blockIdx.x * BUILD_THREADS;
-    if (tid < DISPATCH_W) before_block[tid] = dl_ld<POL>(dl_global<uint32_t>(block_rows) + blockIdx.x * DISPATCH_W + tid);
-
     const uint32_t token = block0 + tid;
     const bool valid = token < a.tokens;
-    const uint64_t mine = valid ? dl_ld<POL>(dl_global<uint64_t>(mask) + token) : 0ull;
+    uint64_t mine = 0;
+    if constexpr (PUSHED) {
+        // mask, counts and the slot's stamp in one round trip; again if the stamp is not the mask's yet
+        __shared__ uint32_t sealed;
+        for (uint32_t tries = 0;; ++tries) {
+            if (tid < DISPATCH_W)
+                before_block[tid] = dl_ld<POL>(dl_global<uint32_t>(block_rows) + blockIdx.x * DISPATCH_W + tid);
+            if (tid == DISPATCH_W) sealed = dl_ld<POL>(dl_pushed_stamp(mask)) == stamp ? 1u : 0u;
+            mine = valid ? dl_ld<POL>(dl_global<uint64_t>(mask) + token) : 0ull;
+            __syncthreads();
+            if (sealed) break;
+            if (tries >= DL_PUSHED_TRIES) return;  // never: the writes were on their way before the launch
+            __syncthreads();
+        }
+    } else {
+        if (tid < DISPATCH_W) before_block[tid] = dl_ld<POL>(dl_global<uint32_t>(block_rows) + blockIdx.x * DISPATCH_W + tid);
+        mine = valid ? dl_ld<POL>(dl_global<uint64_t>(mask) + token) : 0ull;
+    }
     bool m[DISPATCH_W];
     uint32_t pos[DISPATCH_W], k = 0;
 #pragma unroll
@@ -164,8 +178,9 @@ int dl_dispatch_on_device(const void *const *in, void *const *out, int W, const 
         }
         for (int j = 0; j < DISPATCH_W; ++j) taken_rows[j] += (uint32_t)(acc >> (8 * j)) & 0xFFu;
     }
+    uint64_t stamp = 0;
     if (pushed) {
-        _mm_sfence();
+        stamp = dl_push_seal(pushed);
     } else {
         rc = dl_ring_stage(slot, head_bytes, stream);
         if (rc != DL_OK) return rc;
@@ -189,9 +204,9 @@ int dl_dispatch_on_device(const void *const *in, void *const *out, int W, const 
     const uint8_t *mask = (const uint8_t *)head;
     const uint32_t *rows_before = (const uint32_t *)(head + mask_bytes);
     if (pushed)
-        hipLaunchKernelGGL(dl_dispatch_build_kernel<true>, grid, dim3(BUILD_THREADS), 0, stream, mask, rows_before, a, items);
+        hipLaunchKernelGGL(dl_dispatch_build_kernel<true>, grid, dim3(BUILD_THREADS), 0, stream, mask, rows_before, a, items, stamp);
     else
-        hipLaunchKernelGGL(dl_dispatch_build_kernel<false>, grid, dim3(BUILD_THREADS), 0, stream, mask, rows_before, a, items);
+        hipLaunchKernelGGL(dl_dispatch_build_kernel<false>, grid, dim3(BUILD_THREADS), 0, stream, mask, rows_before, a, items, stamp);
     DL_HIP(hipGetLastError());
     if (pushed) {
         rc = dl_push_commit(stream);

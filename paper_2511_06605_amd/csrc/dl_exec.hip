@@ -32,16 +32,24 @@ __global__ void __launch_bounds__(512) dl_exec_rows_kernel(const dl_klist<Item, 
 
 // Entry i of a table that the host wrote into device memory through the BAR just before the launch.  A line
 // of the table that used this memory before may still sit in a cache, so the entry is read past every cache,
-// once per workgroup (8 bytes per lane), and handed on through LDS.  Call with the whole workgroup.
+// once per workgroup (8 bytes per lane), together with the slot's stamp, and handed on through LDS; if the stamp
+// is not the table's yet, both are read again.  Call with the whole workgroup.  Null if the stamp never came.
 template <class Item>
-__device__ __forceinline__ const Item &dl_pushed_entry(const Item *items, uint32_t i)
+__device__ __forceinline__ const Item *dl_pushed_entry(const Item *items, uint32_t i, uint64_t stamp)
 {
-    static_assert(sizeof(Item) % 8 == 0 && sizeof(Item) / 8 <= 64, "one 8-byte load per lane of the first wavefront");
-    __shared__ uint64_t raw[sizeof(Item) / 8];
-    if (threadIdx.x < sizeof(Item) / 8)
-        raw[threadIdx.x] = dl_ld<DL_POL_COHERENT>(dl_global<uint64_t>(items + i) + threadIdx.x);
-    __syncthreads();
-    return *reinterpret_cast<const Item *>(raw);
+    constexpr uint32_t WORDS = sizeof(Item) / 8;
+    static_assert(sizeof(Item) % 8 == 0 && WORDS < 64, "one 8-byte load per lane of the first wavefront");
+    __shared__ uint64_t raw[WORDS + 1];
+    for (uint32_t tries = 0; tries < DL_PUSHED_TRIES; ++tries) {
+        if (threadIdx.x < WORDS)
+            raw[threadIdx.x] = dl_ld<DL_POL_COHERENT>(dl_global<uint64_t>(items + i) + threadIdx.x);
+        else if (threadIdx.x == WORDS)
+            raw[WORDS] = dl_ld<DL_POL_COHERENT>(dl_pushed_stamp(items));
+        __syncthreads();
+        if (raw[WORDS] == stamp) return reinterpret_cast<const Item *>(raw);
+        __syncthreads();
+    }
+    return nullptr;
 }
 
 // Row path over a table of equally sized items in device memory (long lists: thousands of token
@@ -50,13 +58,14 @@ __device__ __forceinline__ const Item &dl_pushed_entry(const Item *items, uint32
 template <class Item, int POL, bool PUSHED = false>
 __global__ void __launch_bounds__(512) dl_exec_urows_kernel(const Item *__restrict__ items, uint32_t n,
                                                             uint32_t tiles_per_item, uint32_t wpg_log2,
-                                                            uint32_t split_log2)
+                                                            uint32_t split_log2, uint64_t stamp)
 {
     const uint32_t d = blockIdx.x / tiles_per_item;
     if (d >= n) return;
-    if constexpr (PUSHED)
-        dl_rows_body<POL>(dl_pushed_entry(items, d), blockIdx.x - d * tiles_per_item, wpg_log2, split_log2);
-    else
+    if constexpr (PUSHED) {
+        const Item *it = dl_pushed_entry(items, d, stamp);
+        if (it) dl_rows_body<POL>(*it, blockIdx.x - d * tiles_per_item, wpg_log2, split_log2);
+    } else
         dl_rows_body<POL>(items[d], blockIdx.x - d * tiles_per_item, wpg_log2, split_log2);
 }
 
@@ -77,12 +86,14 @@ __global__ void __launch_bounds__(512) dl_exec_list_strided_kernel(const dl_klis
 
 template <class Item, int POL, bool PUSHED = false>
 __global__ void __launch_bounds__(512) dl_exec_table_kernel(const Item *__restrict__ items, uint32_t n,
-                                                            uint32_t tile_bytes, uint32_t split)
+                                                            uint32_t tile_bytes, uint32_t split, uint64_t stamp)
 {
     const uint32_t b = blockIdx.x;
     if (b >= n) return;
     if constexpr (PUSHED) {
-        const Item it = dl_pushed_entry(items, b);
+        const Item *pushed = dl_pushed_entry(items, b, stamp);
+        if (!pushed) return;
+        const Item it = *pushed;
         dl_run_item<POL>(it, 0, tile_bytes, split);
     } else {
         const Item it = items[b];
@@ -348,18 +359,23 @@ __global__ void __launch_bounds__(DL_STANDBY_THREADS) dl_standby_kernel(dl_stand
 
 // Entry i of a table written through the BAR (see dl_pushed_entry), read by every lane for itself: all lanes
 // load the same 8 bytes, which costs one request per wavefront, and no barrier.  For kernels that walk a table.
+// *sealed: the slot's stamp, read along with the entry, is the table's (else the entry is not to be used).
 template <class Item>
-__device__ __forceinline__ Item dl_pushed_entry_per_lane(const Item *items, uint32_t i)
+__device__ __forceinline__ Item dl_pushed_entry_per_lane(const Item *items, uint32_t i, uint64_t stamp, bool *sealed)
 {
     static_assert(sizeof(Item) % 8 == 0, "whole 8-byte words");
     union {
         Item it;
         uint64_t w[sizeof(Item) / 8];
     } u;
+    *sealed = false;
+    for (uint32_t tries = 0; tries < DL_PUSHED_TRIES && !*sealed; ++tries) {
 #pragma unroll
-    for (uint32_t q = 0; q < sizeof(Item) / 8; ++q) {
-        const uint64_t v = dl_ld<DL_POL_COHERENT>(dl_global<uint64_t>(items + i) + q);
-        u.w[q] = dl_uniform64(v);  // the same in every lane: keep it in scalar registers
+        for (uint32_t q = 0; q < sizeof(Item) / 8; ++q) {
+            const uint64_t v = dl_ld<DL_POL_COHERENT>(dl_global<uint64_t>(items + i) + q);
+            u.w[q] = dl_uniform64(v);  // the same in every lane: keep it in scalar registers
+        }
+        *sealed = dl_uniform64(dl_ld<DL_POL_COHERENT>(dl_pushed_stamp(items))) == stamp;
     }
     return u.it;
 }
@@ -368,15 +384,18 @@ __device__ __forceinline__ Item dl_pushed_entry_per_lane(const Item *items, uint
 // fetched before the wait.
 template <class Item, bool PUSHED = false>
 __global__ void __launch_bounds__(512) dl_armed_table_kernel(const Item *__restrict__ items, uint32_t n,
-                                                             uint32_t tile_bytes, uint32_t split, const dl_arm a)
+                                                             uint32_t tile_bytes, uint32_t split, uint64_t stamp,
+                                                             const dl_arm a)
 {
     if constexpr (PUSHED) {
         Item it{};
-        if (blockIdx.x < n) it = dl_pushed_entry_per_lane(items, blockIdx.x);
-        const uint32_t go = dl_arm_wait(a);
+        bool sealed = true;  // checked with the first entry; once the stamp has been seen the whole table is there
+        if (blockIdx.x < n) it = dl_pushed_entry_per_lane(items, blockIdx.x, stamp, &sealed);
+        uint32_t go = dl_arm_wait(a);
+        if (!sealed && go == DL_GO_RUN) go = DL_GO_SKIP;  // reported like a request that gave up
         if (go == DL_GO_RUN) {
             for (uint32_t b = blockIdx.x; b < n; b += gridDim.x) {
-                if (b != blockIdx.x) it = dl_pushed_entry_per_lane(items, b);
+                if (b != blockIdx.x) it = dl_pushed_entry_per_lane(items, b, stamp, &sealed);
                 dl_run_item<DL_POL_COHERENT>(it, 0, tile_bytes, split);
             }
         }
@@ -409,7 +428,8 @@ constexpr size_t TABLE_STAGE_MIN = 512;          // tables at least this long ar
 constexpr size_t RING_SLOTS = 4;
 constexpr size_t RING_SLOT_BYTES = DL_RING_SLOT_BYTES;
 
-constexpr size_t PUSH_SLOT_BYTES = 64u << 10;  // longest table that is written through the BAR
+constexpr size_t PUSH_SLOT_BYTES = DL_PUSH_SLOT_BYTES;        // a slot of the tables written through the BAR
+constexpr size_t PUSH_PAYLOAD_BYTES = DL_PUSH_PAYLOAD_BYTES;  // the longest such table
 constexpr size_t PUSH_SLOTS = 64, PUSH_BATCH = PUSH_SLOTS / 2;
 
 struct ring_t {
@@ -592,7 +612,7 @@ int push_close_batch()
 char *push_acquire(size_t table_bytes, hipStream_t stream, int *rc)
 {
     *rc = DL_OK;
-    if (!g_ring.push || !g_dl.cfg.table_push || table_bytes > PUSH_SLOT_BYTES) return nullptr;
+    if (!g_ring.push || !g_dl.cfg.table_push || table_bytes > PUSH_PAYLOAD_BYTES) return nullptr;
     // a batch is one stream's: another stream ends it (on its own stream, which is one that cannot have gone)
     if (g_ring.batch_len && (stream != g_ring.batch_stream || g_ring.batch_len >= PUSH_BATCH))
         if ((*rc = push_close_batch()) != DL_OK) return nullptr;
@@ -607,6 +627,18 @@ char *push_acquire(size_t table_bytes, hipStream_t stream, int *rc)
     g_ring.push_used[s] = false;  // free until push_commit: a call that fails in between leaves it so
     g_ring.push_armed[s] = 0;
     return g_ring.push + s * PUSH_SLOT_BYTES;
+}
+
+// After the last write into the slot: the payload leaves the write-combining buffers, then the stamp, then
+// whatever the caller does next (the launch).
+uint64_t push_seal(char *slot)
+{
+    static uint64_t stamps = 0;
+    const uint64_t stamp = ++stamps;
+    _mm_sfence();
+    *(volatile uint64_t *)(slot + PUSH_PAYLOAD_BYTES) = stamp;
+    _mm_sfence();
+    return stamp;
 }
 
 // After the launch that reads the slot push_acquire gave out last (only then is the slot taken).  armed_ticket: that launch is a request armed
@@ -672,7 +704,7 @@ bool launch_uniform_rows(const Item *items, size_t n, const dl_launch_shape &sh,
         if (item_k(items[i]) > kmax) kmax = item_k(items[i]);
     }
     // a table that needs staging must move enough bytes to pay for it; one written through the BAR needs none
-    const bool pushable = g_ring.push && c.table_push && n * sizeof(Item) <= PUSH_SLOT_BYTES;
+    const bool pushable = g_ring.push && c.table_push && n * sizeof(Item) <= PUSH_PAYLOAD_BYTES;
     if (!pushable && bytes * n < UNIFORM_ROWS_MIN_BYTES) return false;
     const uint32_t tile = 16u * threads / split;  // one 1 KiB row per wavefront of a sub-group
     const uint64_t tpi = (bytes + tile - 1) / tile;
@@ -700,8 +732,9 @@ bool launch_uniform_rows(const Item *items, size_t n, const dl_launch_shape &sh,
         slot[i] = it;  // write only: the slot may be device memory behind the BAR
     }
     const Item *dslot = slot;
+    uint64_t stamp = 0;
     if (pushed) {
-        _mm_sfence();  // the table leaves the write-combining buffers before the launch does
+        stamp = push_seal(pushed);
     } else {
         *rc = stage_slot(s, (n * sizeof(Item) + 15u) & ~(uint64_t)15u, stream);
         if (*rc != DL_OK) return true;
@@ -711,11 +744,11 @@ bool launch_uniform_rows(const Item *items, size_t n, const dl_launch_shape &sh,
         if (pushed)
             hipLaunchKernelGGL((dl_exec_urows_kernel<Item, decltype(pol)::value, true>), dim3((uint32_t)(tpi * n)),
                                dim3(threads), 0, stream, dslot, (uint32_t)n, (uint32_t)tpi,
-                               log2u(threads / 64u / split), log2u(split));
+                               log2u(threads / 64u / split), log2u(split), stamp);
         else
             hipLaunchKernelGGL((dl_exec_urows_kernel<Item, decltype(pol)::value, false>), dim3((uint32_t)(tpi * n)),
                                dim3(threads), 0, stream, dslot, (uint32_t)n, (uint32_t)tpi,
-                               log2u(threads / 64u / split), log2u(split));
+                               log2u(threads / 64u / split), log2u(split), stamp);
     });
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && !pushed) e = hipEventRecord(g_ring.ev[s], stream);
@@ -809,8 +842,9 @@ int launch_table(const Item *items, size_t n, dl_launch_shape sh, hipStream_t st
             off += it.bytes;
         }
         if (m == 0) break;
+        uint64_t stamp = 0;
         if (pushed) {
-            _mm_sfence();  // the table leaves the write-combining buffers before the launch does
+            stamp = push_seal(pushed);
         } else if (m >= TABLE_STAGE_MIN) {
             // Stage the table in device memory, in front of the kernel that uses it (the copy does not
             // wait for a doorbell: the table is final now).  The workgroups then find their entries in
@@ -827,10 +861,10 @@ int launch_table(const Item *items, size_t n, dl_launch_shape sh, hipStream_t st
             g_dl.armed_words = a.own_word ? g : 1u;
             if (pushed)
                 hipLaunchKernelGGL((dl_armed_table_kernel<Item, true>), dim3(g), dim3(sh.block_threads), 0, stream, slot,
-                                   (uint32_t)m, sh.tile_bytes, sh.split, a);
+                                   (uint32_t)m, sh.tile_bytes, sh.split, stamp, a);
             else
                 hipLaunchKernelGGL((dl_armed_table_kernel<Item, false>), dim3(g), dim3(sh.block_threads), 0, stream, slot,
-                                   (uint32_t)m, sh.tile_bytes, sh.split, a);
+                                   (uint32_t)m, sh.tile_bytes, sh.split, stamp, a);
             // whoever wants this memory next must not wait for a request that nobody has triggered
             if (!a.nowait) {
                 if (pushed)
@@ -842,10 +876,12 @@ int launch_table(const Item *items, size_t n, dl_launch_shape sh, hipStream_t st
             with_policy(sh.policy, [&](auto pol) {
                 if (pushed)
                     hipLaunchKernelGGL((dl_exec_table_kernel<Item, decltype(pol)::value, true>), dim3((uint32_t)m),
-                                       dim3(sh.block_threads), 0, stream, slot, (uint32_t)m, sh.tile_bytes, sh.split);
+                                       dim3(sh.block_threads), 0, stream, slot, (uint32_t)m, sh.tile_bytes, sh.split,
+                                       stamp);
                 else
                     hipLaunchKernelGGL((dl_exec_table_kernel<Item, decltype(pol)::value, false>), dim3((uint32_t)m),
-                                       dim3(sh.block_threads), 0, stream, slot, (uint32_t)m, sh.tile_bytes, sh.split);
+                                       dim3(sh.block_threads), 0, stream, slot, (uint32_t)m, sh.tile_bytes, sh.split,
+                                       stamp);
             });
         }
         DL_HIP(hipGetLastError());
@@ -1059,7 +1095,7 @@ int dl_launch_fused_rows_table(const dl_fused_item *dev_items, uint32_t n, uint6
     with_policy(sh.policy, [&](auto pol) {
         hipLaunchKernelGGL((dl_exec_urows_kernel<dl_fused_item, decltype(pol)::value>), dim3((uint32_t)(tpi * n)),
                            dim3(threads), 0, stream, dev_items, n, (uint32_t)tpi, log2u(threads / 64u / split),
-                           log2u(split));
+                           log2u(split), (uint64_t)0);
     });
     DL_HIP(hipGetLastError());
     return DL_OK;
@@ -1098,6 +1134,7 @@ void dl_ring_own_stream(hipStream_t stream)
 }
 
 char *dl_push_acquire(size_t bytes, hipStream_t stream, int *rc) { return push_acquire(bytes, stream, rc); }
+uint64_t dl_push_seal(char *slot) { return push_seal(slot); }
 int dl_push_commit(hipStream_t stream) { return push_commit(stream, 0); }
 
 int dl_ring_release(size_t slot, hipStream_t stream)

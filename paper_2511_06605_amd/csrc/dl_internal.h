@@ -102,13 +102,18 @@ int dl_ring_acquire(size_t *slot, char **host, char **dev);
 int dl_ring_stage(size_t slot, uint64_t bytes, hipStream_t stream);
 int dl_ring_release(size_t slot, hipStream_t stream);
 // dl_exec.hip: short tables written by the host straight into device memory (through the BAR).
-//   dl_push_acquire  a slot for `bytes` that a kernel launched on `stream` next will read, or null if that way is
-//                    not open (no such BAR, switched off, too long); *rc != DL_OK on an error.  Write only, then
-//                    _mm_sfence(), then launch; the kernel must read the slot past the caches.
-//   dl_push_commit   after that launch, with its stream
+//   dl_push_acquire  a slot for `bytes` (at most DL_PUSH_PAYLOAD_BYTES) that a kernel launched on `stream` next
+//                    will read, or null if that way is not open (no such BAR, switched off, too long);
+//                    *rc != DL_OK on an error.  Write only.
+//   dl_push_seal     after the last write: fences, writes the slot's stamp behind the payload, fences again, and
+//                    returns the stamp.  The kernel gets the stamp as an argument and reads the payload, past the
+//                    caches, only once it sees the stamp (dl_pushed_sealed in dl_device.h): writes that cross the
+//                    link arrive in order, so the stamp vouches for what was written before it.
+//   dl_push_commit   after the launch, with its stream
 //   dl_ring_forget_armed  every armed request has finished (their tickets start over with the next session)
 //   dl_ring_own_stream  the library's own stream for armed requests exists (or, null, is about to be destroyed):
 //                    the one stream besides the default stream that cannot go away between two calls
+uint64_t dl_push_seal(char *slot);
 void dl_ring_forget_armed();
 void dl_ring_own_stream(hipStream_t stream);
 char *dl_push_acquire(size_t bytes, hipStream_t stream, int *rc);

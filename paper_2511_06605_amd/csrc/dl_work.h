@@ -13,6 +13,11 @@
 
 constexpr int DL_FAN = 8;  // destinations one work item can write from a single read
 
+// A slot of device memory that the host fills through the BAR (short copy tables, masks): the payload, and in the
+// last 8 bytes a stamp that is written after it.
+constexpr uint32_t DL_PUSH_SLOT_BYTES = 64u << 10;
+constexpr uint32_t DL_PUSH_PAYLOAD_BYTES = DL_PUSH_SLOT_BYTES - 8;
+
 // Plain copy: one source, one destination.
 struct dl_plain_item {
     const char *src;
