@@ -383,3 +383,29 @@ def test_broadcast_inference_merges_copies_with_same_source_and_size(ref):
         or [(it["src"] - p, it["bytes"], len(it["dst"])) for it in items] == [(0, 50, 8), (0, 50, 3), (0, 40, 1), (8, 50, 1)]
     assert sorted(d - p for it in items if it["bytes"] == 50 and it["src"] == p for d in it["dst"]) == \
         [1000 + 100 * d for d in range(11)]
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_broadcast_inference_gives_the_same_items_into_any_capacity(seed):
+    """The lowering builds its items where they are wanted if there is room for one item per copy, and in a
+    buffer of its own otherwise: the same items either way, and the same count with no room at all."""
+    from paper_2511_06605_amd import binding
+    lib = binding.lib()
+    n = [1, 7, 64, 300, 1000, 2500][seed]
+    arena, descs = inputs.mixed_batch(n, 4000, 8 << 20, seed=seed, shared_sources=0.5)
+    p = addr(arena)
+    d = binding._desc_array([(p + int(s), p + int(t), int(m)) for s, t, m in descs])
+
+    def items_with_capacity(cap):
+        arr = (binding.PlanItem * max(cap, 1))()
+        m = lib.dl_plan_batch_inferred(d, n, arr, cap)
+        return m, [(arr[i].src, arr[i].bytes, arr[i].k, tuple(arr[i].dst[j] for j in range(arr[i].k))) for i in range(min(m, cap))]
+
+    count, none = items_with_capacity(0)
+    exact = items_with_capacity(count)
+    roomy = items_with_capacity(n + 5)
+    assert count <= n and none == []
+    assert exact == roomy and exact[0] == count and len(exact[1]) == count
+    if count > 1:
+        short = items_with_capacity(count - 1)
+        assert short[0] == count and short[1] == exact[1][:count - 1]
