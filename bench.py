@@ -6,7 +6,8 @@ GPU, per-rank payload 4 KiB ... 64 MiB in powers of two (15 calls), bf16 values
 ~N(0,1) from a seeded generator, one receive buffer of W x payload per rank.
 All buffers are resident in HBM before the timed region starts.
 
-Prints ONE JSON line.  `value` is algorithmic (read + write) bytes per second
+Prints ONE short JSON line (per-size rows and the comparison legs go to
+--detail-file).  `value` is algorithmic (read + write) bytes per second
 over the timed steps: an all-gather of B bytes per rank reads W*B and writes
 W*W*B bytes (each source is read once and written W times).
 """
@@ -60,38 +61,103 @@ def pct(xs, q):
     return xs[min(len(xs) - 1, int(q * len(xs)))]
 
 
-def cpu_baseline(sizes, budget_s=10.0):
-    """The CPU checker as it stands (single thread, plain memcpy), timed on the
-    host on the sweep points up to 16 MiB per rank, repeated until the budget
-    is used.  Buffers are touched once before timing."""
+def host_cores() -> int:
+    """Cores this process may run on (the scheduler's view, and the box's thread setting if it is narrower)."""
+    n = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+    try:
+        n = min(n, max(1, int(os.environ.get("OMP_NUM_THREADS", n))))
+    except ValueError:
+        pass
+    return max(1, n)
+
+
+def cpu_model() -> str:
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def cpu_baseline(sizes, budget_s=6.0):
+    """The CPU checker as it stands (plain memcpy, single-threaded source), timed on the host on the whole sweep:
+    once from one thread, once from T threads that each call the checker's broadcast on a slice of one source
+    (disjoint destinations; the foreign calls run outside the interpreter lock).  One buffer set sized for the
+    largest point serves every point (the smaller ones use its front), touched before timing; if the host's
+    free memory does not hold it, the largest points are left out and the cap is stated."""
+    import ctypes
+    from concurrent.futures import ThreadPoolExecutor
+
     import numpy as np
     from oracle import ref
 
     ref.build()
     lib = ref.load()
-    sample = [B for B in sizes if B <= 16 * MiB]
+    try:
+        avail = os.sysconf("SC_AVPHYS_PAGES") * os.sysconf("SC_PAGE_SIZE")
+    except (ValueError, OSError):
+        avail = 16 << 30
+    sample = [B for B in sizes if (W + W * W) * B <= avail // 3]
+    cap_note = "" if len(sample) == len(sizes) else \
+        f"; points above {sample[-1] // MiB} MiB per rank left out: {avail / 2**30:.0f} GiB of host memory free"
+    big = sample[-1]
     rng = np.random.default_rng(0)
-    cases = []
-    for B in sample:
-        ins = [rng.integers(0, 256, B, dtype=np.uint8) for _ in range(W)]
-        outs = [np.ones(W * B, dtype=np.uint8) for _ in range(W)]
-        cases.append((B, ref._ptrs(ins), ref._ptrs(outs), ins, outs))
-    moved, passes = 0, 0
-    t0 = time.perf_counter()
-    while True:
-        for B, pi, po, _, _ in cases:
-            rc = lib.ref_allgather(pi, po, W, B)
-            assert rc == 0
-            moved += ag_bytes(B)
-        passes += 1
-        if time.perf_counter() - t0 >= budget_s and passes >= 2:
-            break
-    dt = time.perf_counter() - t0
+    ins = [rng.integers(0, 256, big, dtype=np.uint8) for _ in range(W)]
+    outs = [np.empty(W * big, dtype=np.uint8) for _ in range(W)]   # first touched by the untimed pass below
+    pi, po = ref._ptrs(ins), ref._ptrs(outs)
+    T = host_cores()
+
+    def one_thread(B):
+        assert lib.ref_allgather(pi, po, W, B) == 0
+
+    pool = ThreadPoolExecutor(T)
+
+    def piece(j, B, off, n):
+        dsts = (ctypes.c_void_p * W)(*[outs[r].ctypes.data + j * B + off for r in range(W)])
+        assert lib.ref_broadcast(ins[j].ctypes.data + off, dsts, W, n) == 0
+
+    def threads(B):
+        parts = max(1, min(-(-T // W), B // 4096))      # slices per source: T tasks in all, none under 4 KiB
+        cut = -(-B // parts)
+        jobs = [pool.submit(piece, j, B, off, min(cut, B - off)) for j in range(W) for off in range(0, B, cut)]
+        for f in jobs:
+            f.result()
+
+    def leg(fn):
+        moved, passes, big_s = 0, 0, []
+        t0 = time.perf_counter()
+        while True:
+            for B in sample:
+                t1 = time.perf_counter()
+                fn(B)
+                if B == big:
+                    big_s.append(time.perf_counter() - t1)
+                moved += ag_bytes(B)
+            passes += 1
+            if time.perf_counter() - t0 >= budget_s:
+                break
+        dt = time.perf_counter() - t0
+        return moved / dt / 1e9, ag_bytes(big) / min(big_s) / 1e9, passes, dt
+
+    threads(big)   # untimed: brings every page of the receive buffers in, from all cores at once
+    v1, big1, p1, dt1 = leg(one_thread)
+    vt, bigt, pt, dtt = leg(threads)
+    pool.shutdown()
+    # every output must hold the concatenation (the threaded leg ran last)
+    for r in (0, W - 1):
+        for j in (0, W - 1):
+            assert np.array_equal(outs[r][j * big:(j + 1) * big], ins[j]), "CPU baseline result is wrong"
     return {
-        "value": moved / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
-        "sample": f"{passes} passes of the all-gather sweep points 4 KiB..16 MiB per rank (W=8), "
-                  f"{moved / 2**30:.1f} GiB moved in {dt:.1f} s, single thread",
-        "host_cpus": os.cpu_count(),
+        "value": vt, "unit": "GB/s", "cores": T, "kind": "oracle",
+        "single_thread": v1, "threads": vt,
+        f"single_thread_{big // MiB}MiB": big1, f"threads_{big // MiB}MiB": bigt,
+        "cpu": cpu_model(), "host_cpus": os.cpu_count(),
+        "sample": f"all-gather sweep {sample[0] // KiB} KiB..{big // MiB} MiB per rank (W=8): {p1} passes in {dt1:.1f} s "
+                  f"from one thread, {pt} passes in {dtt:.1f} s from {T} threads (each a broadcast of a source slice "
+                  f"by the checker){cap_note}",
     }
 
 
@@ -99,8 +165,8 @@ def runtime_batch_comparison():
     """hipMemcpyBatchAsync on the all-gather's 64 block copies, run by the comparison program that links the
     ROCm installation's HIP runtime (the runtime PyTorch brings along does not export the call)."""
     import subprocess
-    from paper_2511_06605_amd import build as dl_build
-    exe = dl_build.RUNTIME_BATCH
+    from bench_aid import build as aid_build
+    exe = aid_build.RUNTIME_BATCH
     if not os.path.exists(exe):
         return {"error": "comparison program not built"}
     try:
@@ -108,6 +174,17 @@ def runtime_batch_comparison():
         return json.loads(r.stdout.strip().splitlines()[-1])
     except Exception as e:   # a comparison leg: report, never fail the benchmark
         return {"error": f"{type(e).__name__}: {e}"}
+
+
+def short(x):
+    """Floats to five significant digits (the printed line is read back whole by the caller's harness)."""
+    if isinstance(x, float):
+        return float(f"{x:.5g}")
+    if isinstance(x, dict):
+        return {k: short(v) for k, v in x.items()}
+    if isinstance(x, (list, tuple)):
+        return [short(v) for v in x]
+    return x
 
 
 def lat_stats(lat):
@@ -461,6 +538,37 @@ def alltoall_case(args, dl, benchaid, inputs, torch, stream) -> int:
     return 0
 
 
+def armed_case(args, dl, benchaid, inputs, torch, stream) -> int:
+    """The kernels behind the latency figures (Sec. IV-E on compute units): all-gathers of 4 KiB .. 4 MiB per rank,
+    each armed, seen resident, triggered and waited for --steps times in prelaunch mode, then issued --steps times in
+    signal mode and (where they fit a waiting kernel) in standby mode.  Prints host-observed medians; meant to
+    run under a kernel trace."""
+    rows = []
+    reqs = []
+    for B in [4 * KiB << i for i in range(11)]:
+        ins = inputs.allgather_inputs(W, B, seed=B.bit_length() - 1, kind="bf16")
+        d_in = [torch.from_numpy(a).cuda() for a in ins]
+        d_out = [torch.empty(W * B, dtype=torch.uint8, device="cuda") for _ in range(W)]
+        reqs.append((B, benchaid.allgather_request(d_in, d_out, B), (d_in, d_out)))
+    stream.synchronize()
+    dl.dl_prelaunch_start()
+    for B, req, _keep in reqs:
+        row = {"bytes_per_rank": B}
+        dl.dl_set_mode(dl.DL_MODE_PRELAUNCH)
+        row["prelaunch_trigger_to_done_us"] = pct(benchaid.time_host(req, None, benchaid.WAIT_TRIGGER, args.warmup, args.steps), .5)
+        dl.dl_set_mode(dl.DL_MODE_SIGNAL)
+        row["signal_call_to_done_us"] = pct(benchaid.time_host(req, None, benchaid.WAIT_SIGNAL, args.warmup, args.steps), .5)
+        if W * B <= 64 * 8192:
+            dl.dl_set_mode(dl.DL_MODE_STANDBY)
+            row["standby_call_to_done_us"] = pct(benchaid.time_host(req, None, benchaid.WAIT_SIGNAL, args.warmup, args.steps), .5)
+        rows.append(row)
+    dl.dl_set_mode(dl.DL_MODE_ONESHOT)
+    dl.dl_prelaunch_stop()
+    dl.dl_shutdown()
+    print(json.dumps({"case": "armed", "calls_per_point_and_mode": args.warmup + args.steps, "rows": rows}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -469,10 +577,14 @@ def main() -> int:
     ap.add_argument("--max-bytes", type=int, default=64 * MiB, help="largest per-rank payload of the sweep")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline leg")
     ap.add_argument("--no-detail", action="store_true", help="skip per-size latency and comparison legs")
-    ap.add_argument("--case", choices=["sweep", "pmc", "token_dispatch", "alltoall"], default="sweep",
+    ap.add_argument("--detail-file", default=os.path.join(ROOT, "gpurun_out", "bench_detail.json"),
+                    help="where the per-size latency and comparison rows go (the printed line stays short)")
+    ap.add_argument("--case", choices=["sweep", "pmc", "token_dispatch", "alltoall", "armed"], default="sweep",
                     help="pmc: only --steps launches of the largest all-gather and of a plain 1 GiB copy "
                          "(the calibration kernel), for hardware-counter runs; token_dispatch: only the "
-                         "token-granular MoE dispatch, for kernel traces")
+                         "token-granular MoE dispatch, for kernel traces; armed: all-gathers of 4 KiB .. 4 MiB per "
+                         "rank armed, triggered and waited for (prelaunch), then in signal and standby mode, for "
+                         "kernel traces of the waiting kernels")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this library runs on one GPU (W virtual ranks share its HBM); --gpus must be 1",
@@ -482,13 +594,22 @@ def main() -> int:
     # the runtime's batched copy call, timed by a program of its own before this process touches the GPU
     runtime_batch = None
     if args.case == "sweep" and not args.no_detail:
+        from bench_aid import build as aid_build
+        if not os.path.exists(aid_build.RUNTIME_BATCH):
+            try:
+                aid_build.build()
+            except Exception as e:   # a comparison leg: report, never fail the benchmark
+                print(f"bench.py: comparison program did not build: {e}", file=sys.stderr)
         runtime_batch = runtime_batch_comparison()
 
     import numpy as np
     import torch
 
     import paper_2511_06605_amd as dl
-    from paper_2511_06605_amd import benchaid, inputs
+    from paper_2511_06605_amd import inputs
+    from bench_aid import benchaid, build as aid_build
+    if not os.path.exists(aid_build.AID_LIB):   # normally built beforehand, with the library
+        aid_build.build()
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
@@ -501,6 +622,8 @@ def main() -> int:
         return token_case(args, dl, benchaid, inputs, torch, stream)
     if args.case == "alltoall":
         return alltoall_case(args, dl, benchaid, inputs, torch, stream)
+    if args.case == "armed":
+        return armed_case(args, dl, benchaid, inputs, torch, stream)
 
     sizes = [B for B in (4 * KiB << i for i in range(15)) if B <= args.max_bytes]
     reqs, keep, check = {}, [], None
@@ -553,16 +676,17 @@ def main() -> int:
         "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "u8", "data": "synthetic",
-        "config": {"workload": "all-gather size sweep, W=8 virtual ranks on one GPU, per-rank payload "
-                               f"{sizes[0] // KiB} KiB..{big // MiB} MiB in powers of 2, bf16 ~N(0,1) seeded",
+        "config": {"workload": f"all-gather size sweep, W=8 virtual ranks on one GPU, {sizes[0] // KiB} KiB.."
+                               f"{big // MiB} MiB per rank in powers of 2, bf16 ~N(0,1) seeded",
                    "W": W, "calls_per_step": len(sizes), "bytes_per_step": step_bytes, "mode": "oneshot"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "kernel": "dl_exec_rows_kernel<dl_fused_item, 8, 0>",
-                     "launch": f"all-gather {big // MiB} MiB per rank: {ag_bytes(big)} algorithmic bytes, "
-                               f"{big_ms * 1e3:.1f} us average over {len(events)} launches (HIP events)"},
+                     "launch": f"all-gather {big // MiB} MiB/rank: {ag_bytes(big)} B in {big_ms * 1e3:.1f} us "
+                               f"(mean of {len(events)} launches, HIP events)"},
     }
 
+    detail = None
     if not args.no_detail:
         detail = {"allgather": []}
         for B in sizes:
@@ -573,6 +697,26 @@ def main() -> int:
                 lat = benchaid.time_host(reqs[B], stream, benchaid.WAIT_STREAM, warmup=50, iters=1000)
                 row["oneshot_host_us"] = lat_stats(lat)
             detail["allgather"].append(row)
+        # The same sizes with cold caches: enough buffer sets of each size that one pass over them moves more than
+        # the on-die caches hold (256 MiB Infinity Cache, 32 MiB of L2), issued round-robin back to back.
+        spare = {}
+        for row in detail["allgather"]:
+            B = row["bytes_per_rank"]
+            if B < 64 * KiB or B > 8 * MiB:
+                continue
+            sets = max(3, min(64, -(-(1 << 30) // ag_bytes(B))))
+            ring = [reqs[B]]
+            for q in range(sets - 1):
+                d_in = [torch.empty(B, dtype=torch.uint8, device="cuda").random_(0, 256) for _ in range(W)]
+                d_out = [torch.empty(W * B, dtype=torch.uint8, device="cuda") for _ in range(W)]
+                ring.append(benchaid.allgather_request(d_in, d_out, B))
+                spare[(B, q)] = (d_in, d_out)
+            stream.synchronize()
+            row["cold"] = {"buffer_sets": sets, "device_us": benchaid.time_device_rotating(ring, stream, 1, 3)}
+            row["cold"]["GBps"] = ag_bytes(B) / row["cold"]["device_us"] / 1e3
+            row["cold"]["frac_of_hbm_peak"] = row["cold"]["GBps"] / HBM_PEAK_GBS
+            for q in range(sets - 1):
+                del spare[(B, q)]
         # prelaunch mode: the request is armed ahead of time; timed from the doorbell write to the
         # completion word seen on the host, and from the arming call for comparison
         dl.dl_prelaunch_start()
@@ -624,21 +768,34 @@ def main() -> int:
                              "total": med(total)}
         detail["phase_breakdown_allgather"] = rows
         detail.update(other_operations(dl, benchaid, inputs, torch, stream, reqs, keep, sizes, runtime_batch))
-        out["detail"] = detail
         small = detail["allgather"][0]
         out["latency_us_4KiB_allgather"] = {
-            "oneshot_call_to_stream_sync_p50": small["oneshot_host_us"]["p50"],
-            "oneshot_device": small["device_us"],
-            "prelaunch_trigger_to_done_p50": small["prelaunch_trigger_to_done_us"]["p50"],
-            "prelaunch_arm_to_done_p50": small["prelaunch_arm_to_done_us"]["p50"],
-            "signal_call_to_done_p50": small["signal_call_to_done_us"]["p50"],
-            "standby_call_to_done_p50": small["standby_call_to_done_us"]["p50"],
+            "oneshot_call_to_stream_sync_p50": round(small["oneshot_host_us"]["p50"], 2),
+            "oneshot_device": round(small["device_us"], 2),
+            "prelaunch_trigger_to_done_p50": round(small["prelaunch_trigger_to_done_us"]["p50"], 2),
+            "prelaunch_arm_to_done_p50": round(small["prelaunch_arm_to_done_us"]["p50"], 2),
+            "signal_call_to_done_p50": round(small["signal_call_to_done_us"]["p50"], 2),
+            "standby_call_to_done_p50": round(small["standby_call_to_done_us"]["p50"], 2),
         }
+        # fraction of HBM peak per sweep point from 1 MiB per rank, cold caches where measured
+        out["frac_of_hbm_peak_by_MiB_per_rank"] = {
+            str(r_["bytes_per_rank"] // MiB): round((r_["cold"]["GBps"] if "cold" in r_ else r_["GBps"]) / HBM_PEAK_GBS, 3)
+            for r_ in detail["allgather"] if r_["bytes_per_rank"] >= MiB}
 
     dl.dl_shutdown()
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(sizes)
-    print(json.dumps(out))
+    if detail is not None:
+        # the long part goes to a file: the printed line has to stay short enough to be read back whole
+        detail["summary"] = out
+        try:
+            os.makedirs(os.path.dirname(args.detail_file), exist_ok=True)
+            with open(args.detail_file, "w") as f:
+                json.dump(detail, f, indent=1)
+            out["detail_file"] = os.path.relpath(args.detail_file, ROOT)
+        except OSError as e:
+            out["detail_file"] = f"not written: {e}"
+    print(json.dumps(short(out)))
     return 0
 
 

@@ -7,7 +7,7 @@ from __future__ import annotations
 import ctypes
 import os
 
-from . import binding
+from paper_2511_06605_amd import binding
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 AID_PATH = os.path.join(_HERE, "libdl_benchaid.so")
@@ -35,7 +35,7 @@ def aid() -> ctypes.CDLL:
     if _aid is None:
         binding.lib()  # the aid links against the library
         if not os.path.exists(AID_PATH):
-            raise ImportError(f"{AID_PATH} is missing: run `python -m paper_2511_06605_amd.build`")
+            raise ImportError(f"{AID_PATH} is missing: run `python bench_aid/build.py`")
         L = ctypes.CDLL(AID_PATH)
         rp, dp = ctypes.POINTER(Request), ctypes.POINTER(ctypes.c_double)
         L.dlb_issue.restype = ctypes.c_int
@@ -44,6 +44,9 @@ def aid() -> ctypes.CDLL:
         L.dlb_time_host.argtypes = [rp, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, dp]
         L.dlb_time_device.restype = ctypes.c_int
         L.dlb_time_device.argtypes = [rp, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, dp]
+        L.dlb_time_device_rotating.restype = ctypes.c_int
+        L.dlb_time_device_rotating.argtypes = [ctypes.POINTER(rp), ctypes.c_int, ctypes.c_void_p, ctypes.c_int,
+                                               ctypes.c_int, dp]
         L.dlb_time_call.restype = ctypes.c_int
         L.dlb_time_call.argtypes = [rp, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, dp, dp]
         L.dlb_phases.restype = ctypes.c_int
@@ -149,6 +152,16 @@ def time_device(p: Prepared, stream=None, warmup=5, calls=20) -> float:
     out = ctypes.c_double(0)
     _rc(aid().dlb_time_device(ctypes.byref(p.req), binding._stream(stream), warmup, calls, ctypes.byref(out)),
         "dlb_time_device")
+    return out.value
+
+
+def time_device_rotating(ps, stream=None, warmup_rounds=1, rounds=3) -> float:
+    """Microseconds per call from HIP events around ``rounds`` passes over the requests ``ps`` (same shape, buffers
+    of their own each), issued back to back: with enough of them every call starts with cold caches."""
+    arr = (ctypes.POINTER(Request) * len(ps))(*[ctypes.pointer(p.req) for p in ps])
+    out = ctypes.c_double(0)
+    _rc(aid().dlb_time_device_rotating(arr, len(ps), binding._stream(stream), warmup_rounds, rounds, ctypes.byref(out)),
+        "dlb_time_device_rotating")
     return out.value
 
 

@@ -10,7 +10,7 @@
 
 #include <vector>
 
-#include "../../include/dmalatte.h"
+#include "../include/dmalatte.h"
 
 extern "C" {
 
@@ -214,6 +214,31 @@ int dlb_time_device(const dlb_request *r, void *stream, int warmup, int calls, d
         if (hipEventSynchronize(b) != hipSuccess) rc = rc ? rc : 1000;
         float ms = 0;
         if (!rc && hipEventElapsedTime(&ms, a, b) == hipSuccess) *us_per_call = ms * 1e3 / calls;
+    }
+    (void)hipEventDestroy(a);
+    (void)hipEventDestroy(b);
+    return rc;
+}
+
+// Device time per call with cold caches: `rounds` passes over nreq requests of the same shape, each on buffers of
+// its own (the caller sizes nreq so that one pass moves more bytes than the on-die caches hold), issued back to
+// back between two HIP events.
+int dlb_time_device_rotating(const dlb_request *const *reqs, int nreq, void *stream, int warmup_rounds, int rounds,
+                             double *us_per_call)
+{
+    if (nreq < 1 || rounds < 1) return DL_ERR_INVALID;
+    hipEvent_t a, b;
+    if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return 1000;
+    int rc = 0;
+    for (int i = 0; i < warmup_rounds * nreq && !rc; ++i) rc = dlb_issue(reqs[i % nreq], stream);
+    if (!rc && hipStreamSynchronize((hipStream_t)stream) != hipSuccess) rc = 1000;
+    if (!rc) {
+        (void)hipEventRecord(a, (hipStream_t)stream);
+        for (int i = 0; i < rounds * nreq && !rc; ++i) rc = dlb_issue(reqs[i % nreq], stream);
+        (void)hipEventRecord(b, (hipStream_t)stream);
+        if (hipEventSynchronize(b) != hipSuccess) rc = rc ? rc : 1000;
+        float ms = 0;
+        if (!rc && hipEventElapsedTime(&ms, a, b) == hipSuccess) *us_per_call = ms * 1e3 / (rounds * nreq);
     }
     (void)hipEventDestroy(a);
     (void)hipEventDestroy(b);

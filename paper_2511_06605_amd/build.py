@@ -19,11 +19,6 @@ HIPCC_FLAGS = [
 ]
 
 
-AID_LIB = os.path.join(HERE, "libdl_benchaid.so")
-# comparison program for the benchmark: the runtime's batched copy call under the ROCm installation's own HIP runtime
-RUNTIME_BATCH = os.path.join(HERE, "dl_runtime_batch")
-
-
 def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
@@ -38,15 +33,9 @@ def _run(cmd, verbose):
 
 
 def build(verbose: bool = False) -> str:
-    """The library, the measurement aid that links against it, and the benchmark's comparison program."""
+    """The library."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     _run([hipcc, *HIPCC_FLAGS, *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB], verbose)
-    _run([hipcc, *HIPCC_FLAGS, os.path.join(CSRC, "dl_benchaid.hip"), "-L" + HERE, "-ldmalatte",
-          "-Wl,-rpath,$ORIGIN", "-ldl", "-o", AID_LIB], verbose)
-    rocm_lib = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(hipcc))), "lib")
-    _run([hipcc, "--offload-arch=gfx950", "-O2", "-std=c++17", "-Wall", "-Wextra", "-Xclang", "-target-feature", "-Xclang",
-          "-packed-fp32-ops", os.path.join(CSRC, "dl_runtime_batch.hip"),
-          "-Wl,-rpath," + rocm_lib, "-o", RUNTIME_BATCH], verbose)
     return LIB
 
 
