@@ -53,7 +53,8 @@ typedef enum dl_status {
     DL_ERR_HIP = -3,      /* a HIP call failed; see dl_last_hip_error() */
     DL_ERR_TIMEOUT = -4,  /* a host-side wait gave up */
     DL_ERR_STATE = -5,    /* not initialised; prelaunch mode not started; started twice; table memory still held by an armed request that has not been triggered */
-    DL_ERR_EXPIRED = -6   /* an armed request was cancelled or not triggered within its arm limit: nothing, or (triggered at the very limit) only part, was copied */
+    DL_ERR_EXPIRED = -6,  /* an armed request was cancelled or not triggered within its arm limit: nothing, or (triggered at the very limit) only part, was copied */
+    DL_ERR_LOST = -7      /* a kernel of an EARLIER request gave up waiting for the copy table that the host had written into device memory, so that request copied nothing or only part; every operation returns this until dl_last_device_error() has been called */
 } dl_status;
 
 /* Largest number of destinations of one dl_broadcast call / ranks of a collective. */
@@ -98,6 +99,29 @@ int dl_set_validate(int on);
 
 const char *dl_strerror(int status);
 int dl_last_hip_error(void);
+
+/*
+ * Failures that only the device can notice.  The table of a long list (more
+ * copies than fit the kernel arguments), and the mask of a token dispatch
+ * lowered on the device, are written by the host straight into device memory
+ * and sealed with a stamp; the kernel looks for the stamp before it reads
+ * (the two cross the host link in order, and the launch follows them; paper
+ * Sec. III-B2: the engine fetches its commands after the doorbell).  Every
+ * such wait is bounded.  A kernel whose stamp never appears copies nothing
+ * from then on, ends normally and sets an error word in host memory; the
+ * call that launched it has returned DL_OK long before.
+ *   dl_last_device_error() returns DL_ERR_LOST if that has happened since
+ * it was last called (and clears the word), else DL_OK.  While the word is
+ * set, every operation returns DL_ERR_LOST and enqueues nothing.  For an
+ * armed request the same case is reported as DL_ERR_EXPIRED by dl_wait().
+ *   dl_debug_lose_next_table(tries) is a test hook for this path: the
+ * kernel of the next table that is written through the BAR is told a stamp
+ * that its slot will never hold and gives up after `tries` (1..1024) looks;
+ * tries == 0 takes the hook back.
+ * DL_ERR_STATE where no table goes that way (no BAR, dl_config.table_push 0).
+ */
+int dl_last_device_error(void);
+int dl_debug_lose_next_table(uint32_t tries);
 
 /* ----------------------------------------------------------------- operations */
 

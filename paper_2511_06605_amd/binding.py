@@ -24,6 +24,7 @@ DL_ERR_HIP = -3
 DL_ERR_TIMEOUT = -4
 DL_ERR_STATE = -5
 DL_ERR_EXPIRED = -6
+DL_ERR_LOST = -7
 DL_MAX_FANOUT = 64
 DL_PLAN_FANOUT = 8
 DL_MODE_ONESHOT = 0
@@ -41,6 +42,7 @@ EXPORTS = [
     "dl_plan_first_hazard", "dl_plan_tiles", "dl_batch_swap", "dl_alltoall_inplace", "dl_plan_alltoall_inplace",
     "dl_plan_swap_first_hazard", "dl_batch_fanout", "dl_token_dispatch", "dl_plan_token_dispatch",
     "dl_plan_batch_inferred", "dl_set_trace", "dl_get_trace", "dl_trace_clock",
+    "dl_last_device_error", "dl_debug_lose_next_table",
 ]
 
 
@@ -119,6 +121,8 @@ def lib() -> ctypes.CDLL:
         "dl_set_validate": (ctypes.c_int, [ctypes.c_int]),
         "dl_strerror": (ctypes.c_char_p, [ctypes.c_int]),
         "dl_last_hip_error": (ctypes.c_int, []),
+        "dl_last_device_error": (ctypes.c_int, []),
+        "dl_debug_lose_next_table": (ctypes.c_int, [ctypes.c_uint32]),
         "dl_batch_copy": (ctypes.c_int, [ctypes.POINTER(CopyDesc), ctypes.c_size_t, vp]),
         "dl_broadcast": (ctypes.c_int, [vp, vpp, ctypes.c_int, ctypes.c_size_t, vp]),
         "dl_allgather": (ctypes.c_int, [vpp, vpp, ctypes.c_int, ctypes.c_size_t, vp]),
@@ -221,6 +225,15 @@ def strerror(status: int) -> str:
 
 def last_hip_error() -> int:
     return lib().dl_last_hip_error()
+
+
+def dl_last_device_error() -> int:
+    """DL_ERR_LOST if a kernel has given up on its copy table since the last call (clears the report), else DL_OK."""
+    return int(lib().dl_last_device_error())
+
+
+def dl_debug_lose_next_table(tries: int = 4) -> None:
+    _check(lib().dl_debug_lose_next_table(int(tries)), "dl_debug_lose_next_table")
 
 
 def dl_init(device: int = 0) -> None:

@@ -229,14 +229,18 @@ long first_hazard(const dl_plan_item *items, size_t n)
         }
         if (dst[q].hi > dst[owner].hi) owner = q;
     }
-    if (worst >= 0) return worst;
-    // destinations are now known disjoint, so sorted by start is sorted by end:
-    // binary search the first destination ending after the source starts
+    const bool disjoint = worst < 0;
+    // destination against source.  With disjoint destinations, sorted by start is sorted by end: binary search
+    // the first destination that ends after the source starts, then take every one that starts before it ends.
+    // A batch that has failed already (an error path) is searched the plain way, so that the index reported is
+    // the smallest over both kinds of overlap.
     for (size_t i = 0; i < n; ++i) {
         if (items[i].bytes == 0) continue;
         const uint64_t lo = (uint64_t)items[i].src, hi = lo + items[i].bytes;
-        auto it = std::partition_point(dst.begin(), dst.end(), [&](const interval &d) { return d.hi <= lo; });
-        if (it != dst.end() && it->lo < hi) flag(it->item);
+        auto it = disjoint ? std::partition_point(dst.begin(), dst.end(), [&](const interval &d) { return d.hi <= lo; })
+                           : dst.begin();
+        for (; it != dst.end() && it->lo < hi; ++it)
+            if (it->hi > lo) flag(it->item);
     }
     return worst;
 }
@@ -308,6 +312,7 @@ int run_in_mode(void *stream, Launch launch)
 int execute(const dl_plan_item *items, size_t n, void *stream)
 {
     if (!g_dl.inited) return DL_ERR_STATE;
+    if (dl_device_error_pending()) return DL_ERR_LOST;
     if (n == 0) return DL_OK;
     if (g_dl.validate && first_hazard(items, n) >= 0) return DL_ERR_OVERLAP;
     if (g_dl.mode == DL_MODE_STANDBY) {
@@ -331,6 +336,7 @@ int execute(const dl_plan_item *items, size_t n, void *stream)
 int execute_swaps(const dl_swap_desc *d, size_t n, void *stream)
 {
     if (!g_dl.inited) return DL_ERR_STATE;
+    if (dl_device_error_pending()) return DL_ERR_LOST;
     if (n && !d) return DL_ERR_INVALID;
     g_swaps.clear();
     for (size_t i = 0; i < n; ++i) {
@@ -442,6 +448,7 @@ const char *dl_strerror(int status)
     case DL_ERR_TIMEOUT: return "timed out";
     case DL_ERR_STATE: return "library or prelaunch mode not in the required state";
     case DL_ERR_EXPIRED: return "armed request cancelled or not triggered in time; nothing or only part was copied";
+    case DL_ERR_LOST: return "a kernel of an earlier request never saw its copy table complete and copied nothing or only part";
     default: return "unknown status";
     }
 }
@@ -496,6 +503,7 @@ int dl_batch_fanout(const dl_plan_item *items, size_t n, void *stream)
 int dl_token_dispatch(const void *const *in, void *const *out, int W, const uint32_t *tokens, size_t row_bytes,
                       const uint8_t *dest, void *stream)
 {
+    if (g_dl.inited && dl_device_error_pending()) return DL_ERR_LOST;
     if (g_dl.inited && g_dl.mode == DL_MODE_ONESHOT && !g_dl.validate && g_dl.cfg.device_lowering) {
         // many tokens: only the destination mask goes to the device, which works out the rest itself
         bool taken = false;

@@ -86,6 +86,39 @@ __device__ __forceinline__ void dl_drain_stores()
     asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
 }
 
+// N 16-byte loads issued back to back, so that a lane has N requests in flight.  For the coherent policy the
+// loads and the one wait behind them are a single assembly statement: the compiler cannot see that such a load
+// completes later, so its results must not be visible to it before the wait (outputs are early-clobber: the
+// addresses of the later loads are still needed when the first result register is written).  Every address
+// must be readable; what a lane does not want it simply does not store.
+template <int POL, int N, class P>
+__device__ __forceinline__ void dl_ld_many(dl_u32x4 (&v)[N], P (&p)[N])
+{
+    static_assert(N == 1 || N == 2 || N == 4, "one, two or four loads in flight");
+    if constexpr (POL != DL_POL_COHERENT) {
+#pragma unroll
+        for (int u = 0; u < N; ++u) v[u] = dl_ld<POL>(p[u]);
+    } else if constexpr (N == 1) {
+        v[0] = dl_ld<POL>(p[0]);
+    } else if constexpr (N == 2) {
+        asm volatile("global_load_dwordx4 %0, %2, off sc0 sc1\n\t"
+                     "global_load_dwordx4 %1, %3, off sc0 sc1\n\t"
+                     "s_waitcnt vmcnt(0)"
+                     : "=&v"(v[0]), "=&v"(v[1])
+                     : "v"(p[0]), "v"(p[1])
+                     : "memory");
+    } else {
+        asm volatile("global_load_dwordx4 %0, %4, off sc0 sc1\n\t"
+                     "global_load_dwordx4 %1, %5, off sc0 sc1\n\t"
+                     "global_load_dwordx4 %2, %6, off sc0 sc1\n\t"
+                     "global_load_dwordx4 %3, %7, off sc0 sc1\n\t"
+                     "s_waitcnt vmcnt(0)"
+                     : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3])
+                     : "v"(p[0]), "v"(p[1]), "v"(p[2]), "v"(p[3])
+                     : "memory");
+    }
+}
+
 // n 16-byte vectors from s to the first K of the destinations, by nthr threads.
 template <int K, int FAN, int POL>
 __device__ __forceinline__ void dl_copy_vec16(const DL_GLOBAL dl_u32x4 *__restrict__ s, char *const (&dsts)[FAN],
@@ -100,8 +133,10 @@ __device__ __forceinline__ void dl_copy_vec16(const DL_GLOBAL dl_u32x4 *__restri
     const uint32_t step = nthr * DL_UNROLL;
     for (; i + (DL_UNROLL - 1) * nthr < n; i += step) {
         dl_u32x4 v[DL_UNROLL];
+        const DL_GLOBAL dl_u32x4 *from[DL_UNROLL];
 #pragma unroll
-        for (int u = 0; u < DL_UNROLL; ++u) v[u] = dl_ld<POL>(s + i + u * nthr);
+        for (int u = 0; u < DL_UNROLL; ++u) from[u] = s + i + u * nthr;
+        dl_ld_many<POL, DL_UNROLL>(v, from);
 #pragma unroll
         for (int u = 0; u < DL_UNROLL; ++u)
 #pragma unroll
@@ -226,10 +261,18 @@ __device__ __forceinline__ void dl_swap_elems(char *a, char *b, uint64_t byte_of
     DL_GLOBAL V *pa = dl_global<V>(a + byte_off);
     DL_GLOBAL V *pb = dl_global<V>(b + byte_off);
     for (uint32_t i = tid; i < n; i += nthr) {
-        const V x = dl_ld<POL>(pa + i);
-        const V y = dl_ld<POL>(pb + i);
-        dl_st<POL>(pa + i, y);
-        dl_st<POL>(pb + i, x);
+        if constexpr (sizeof(V) == 16) {
+            dl_u32x4 xy[2];
+            const DL_GLOBAL dl_u32x4 *const from[2] = {pa + i, pb + i};
+            dl_ld_many<POL, 2>(xy, from);  // both in flight together
+            dl_st<POL>(pa + i, xy[1]);
+            dl_st<POL>(pb + i, xy[0]);
+        } else {
+            const V x = dl_ld<POL>(pa + i);
+            const V y = dl_ld<POL>(pb + i);
+            dl_st<POL>(pa + i, y);
+            dl_st<POL>(pb + i, x);
+        }
     }
 }
 
@@ -271,6 +314,23 @@ __device__ __forceinline__ const DL_GLOBAL uint64_t *dl_pushed_stamp(const void 
 // How often a kernel looks again if the stamp is not there at the first look (the launch overtook the writes
 // inside the device; they were on their way before it): bounded, like every wait in this library.
 constexpr uint32_t DL_PUSHED_TRIES = 1u << 22;
+
+// The kernel gave up on its table: say so where the host will look (any non-zero value; the stamp tells which).
+__device__ __forceinline__ void dl_pushed_report_lost(const dl_pushed &ps)
+{
+    __hip_atomic_store(ps.lost, ps.stamp | (1ull << 63), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
+// Wait (bounded) until the slot's stamp is the table's.  The host writes the table, then the stamp; only what is
+// read AFTER the stamp has been seen is vouched for by it, so every reader looks at the stamp first and loads
+// table words behind this call.  One lane's business; the compiler barrier keeps later loads behind the loop.
+__device__ __forceinline__ bool dl_pushed_sealed(const void *slot, const dl_pushed &ps)
+{
+    bool ok = false;
+    for (uint32_t t = 0; t < ps.tries && !ok; ++t) ok = dl_ld<DL_POL_COHERENT>(dl_pushed_stamp(slot)) == ps.stamp;
+    asm volatile("" ::: "memory");
+    return ok;
+}
 
 // ------------------------------------------------ items and lists on the device
 
@@ -374,10 +434,11 @@ __device__ __forceinline__ void dl_rows_body(const Item &it, uint32_t tile, uint
         const char *pa = it.src;
         const char *pb = it.dst;
         if (byte >= it.bytes) return;
-        const dl_u32x4 x = dl_ld<POL>(dl_global<dl_u32x4>(pa + byte));
-        const dl_u32x4 y = dl_ld<POL>(dl_global<dl_u32x4>(pb + byte));
-        dl_st<POL>(dl_global<dl_u32x4>(pa + byte), y);
-        dl_st<POL>(dl_global<dl_u32x4>(pb + byte), x);
+        dl_u32x4 xy[2];
+        const DL_GLOBAL dl_u32x4 *const from[2] = {dl_global<dl_u32x4>(pa + byte), dl_global<dl_u32x4>(pb + byte)};
+        dl_ld_many<POL, 2>(xy, from);
+        dl_st<POL>(dl_global<dl_u32x4>(pa + byte), xy[1]);
+        dl_st<POL>(dl_global<dl_u32x4>(pb + byte), xy[0]);
     } else if constexpr (std::is_same<Item, dl_plain_item>::value) {
         const char *src = it.src;
         const char *dst = dl_item_dst(it, 0);
@@ -414,6 +475,60 @@ __device__ __forceinline__ void dl_run_rows(const dl_klist<Item, NMAX> &p, uint3
     const uint32_t d = dl_find_item(p, b, &first_tile);
     if (d >= p.n) return;
     dl_rows_body<POL>(p.item[d], b - first_tile, p.wpg_log2, p.split_log2);
+}
+
+// Row path of the armed kernels, whose loads go to memory at system scope and take long to come back: a
+// wavefront takes up to R global tiles per pass (b0, b0 + stride, ...; those below `total`), issues the loads
+// of all of them, waits once and stores.  Same preconditions as dl_rows_body, and one sub-group per workgroup
+// (every wavefront stores its row to all of the item's destinations).  b0 < total.  Not for swaps.
+template <int R, class Item, int NMAX>
+__device__ __forceinline__ void dl_run_rows_coherent(const dl_klist<Item, NMAX> &p, uint32_t b0, uint32_t stride,
+                                                     uint32_t total)
+{
+    static_assert(!std::is_same<Item, dl_swap_item>::value, "a swap has two loads per row already");
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wl = p.wpg_log2;
+    uint32_t first;
+    const uint32_t d0 = dl_find_item(p, b0, &first);
+    // what a lane without work loads instead: the first 16 bytes of tile b0's item (non-empty, a multiple of 16)
+    const DL_GLOBAL dl_u32x4 *const safe = dl_global<dl_u32x4>(p.item[d0].src);
+    uint32_t d[R];
+    uint64_t byte[R];
+    bool live[R];
+    const DL_GLOBAL dl_u32x4 *from[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const uint32_t b = b0 + (uint32_t)r * stride;
+        d[r] = d0;
+        byte[r] = 0;
+        live[r] = false;
+        from[r] = safe;
+        if (b < total && b >= b0) {  // (b >= b0: no wrap-around)
+            d[r] = dl_find_item(p, b, &first);
+            const uint64_t row = ((uint64_t)(b - first) << wl) + (wave & ((1u << wl) - 1u));
+            byte[r] = (row << 10) + (lane << 4);
+            live[r] = d[r] < p.n && byte[r] < p.item[d[r]].bytes;
+            if (live[r]) from[r] = dl_global<dl_u32x4>(p.item[d[r]].src + byte[r]);
+        }
+    }
+    dl_u32x4 v[R];
+    dl_ld_many<DL_POL_COHERENT, R>(v, from);
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        if (!live[r]) continue;
+        const Item &it = p.item[d[r]];
+        if constexpr (std::is_same<Item, dl_plain_item>::value) {
+            dl_st<DL_POL_COHERENT>(dl_global<dl_u32x4>(it.dst + byte[r]), v[r]);
+        } else {
+#pragma unroll
+            for (uint32_t q = 0; q < (uint32_t)DL_FAN; ++q) {
+                const char *dq = it.dst[q];  // filled from the front, the rest null
+                if (!dq) break;
+                dl_st<DL_POL_COHERENT>(dl_global<dl_u32x4>(dq + byte[r]), v[r]);
+            }
+        }
+    }
 }
 
 // Global tile b of a list, any alignment and tile size: find its item, then

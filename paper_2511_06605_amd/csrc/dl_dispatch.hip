@@ -40,7 +40,8 @@ template <bool PUSHED>
 __global__ void __launch_bounds__(BUILD_THREADS) dl_dispatch_build_kernel(const uint8_t *__restrict__ mask,
                                                                           const uint32_t *__restrict__ block_rows,
                                                                           const build_args a,
-                                                                          dl_fused_item *__restrict__ items, uint64_t stamp)
+                                                                          dl_fused_item *__restrict__ items,
+                                                                          const dl_pushed ps)
 {
     constexpr int POL = PUSHED ? DL_POL_COHERENT : DL_POL_PLAIN;
     __shared__ uint32_t before_block[DISPATCH_W];          // rows taken by the tokens of earlier blocks
@@ -52,18 +53,30 @@ __global__ void __launch_bounds__(BUILD_THREADS) dl_dispatch_build_kernel(const 
     const bool valid = token < a.tokens;
     uint64_t mine = 0;
     if constexpr (PUSHED) {
-        // mask, counts and the slot's stamp in one round trip; again if the stamp is not the mask's yet
+        // one lane sees the slot's stamp first: only what is read after that is known to be this request's
         __shared__ uint32_t sealed;
-        for (uint32_t tries = 0;; ++tries) {
-            if (tid < DISPATCH_W)
-                before_block[tid] = dl_ld<POL>(dl_global<uint32_t>(block_rows) + blockIdx.x * DISPATCH_W + tid);
-            if (tid == DISPATCH_W) sealed = dl_ld<POL>(dl_pushed_stamp(mask)) == stamp ? 1u : 0u;
-            mine = valid ? dl_ld<POL>(dl_global<uint64_t>(mask) + token) : 0ull;
-            __syncthreads();
-            if (sealed) break;
-            if (tries >= DL_PUSHED_TRIES) return;  // never: the writes were on their way before the launch
-            __syncthreads();
+        if (tid == 0) sealed = dl_pushed_sealed(mask, ps) ? 1u : 0u;
+        __syncthreads();
+        if (!sealed) {
+            // The mask never became complete (the writes were on their way before the launch, so: never).  The row
+            // kernel behind this one executes whatever the table holds: give it an entry that moves nothing for
+            // every token of this block, and let the host hear of the loss.
+            if (valid) {
+                dl_fused_item none;
+                none.src = nullptr;
+                none.bytes = 0;
+                none.k = 0;
+                none.pad = 0;
+#pragma unroll
+                for (int q = 0; q < DL_FAN; ++q) none.dst[q] = nullptr;
+                items[token] = none;
+            }
+            if (tid == 0) dl_pushed_report_lost(ps);
+            return;
         }
+        if (tid < DISPATCH_W)
+            before_block[tid] = dl_ld<POL>(dl_global<uint32_t>(block_rows) + blockIdx.x * DISPATCH_W + tid);
+        mine = valid ? dl_ld<POL>(dl_global<uint64_t>(mask) + token) : 0ull;
     } else {
         if (tid < DISPATCH_W) before_block[tid] = dl_ld<POL>(dl_global<uint32_t>(block_rows) + blockIdx.x * DISPATCH_W + tid);
         mine = valid ? dl_ld<POL>(dl_global<uint64_t>(mask) + token) : 0ull;
@@ -203,10 +216,11 @@ int dl_dispatch_on_device(const void *const *in, void *const *out, int W, const 
     const dim3 grid((uint32_t)blocks);
     const uint8_t *mask = (const uint8_t *)head;
     const uint32_t *rows_before = (const uint32_t *)(head + mask_bytes);
+    const dl_pushed ps = dl_push_kernel_args(stamp);
     if (pushed)
-        hipLaunchKernelGGL(dl_dispatch_build_kernel<true>, grid, dim3(BUILD_THREADS), 0, stream, mask, rows_before, a, items, stamp);
+        hipLaunchKernelGGL(dl_dispatch_build_kernel<true>, grid, dim3(BUILD_THREADS), 0, stream, mask, rows_before, a, items, ps);
     else
-        hipLaunchKernelGGL(dl_dispatch_build_kernel<false>, grid, dim3(BUILD_THREADS), 0, stream, mask, rows_before, a, items, stamp);
+        hipLaunchKernelGGL(dl_dispatch_build_kernel<false>, grid, dim3(BUILD_THREADS), 0, stream, mask, rows_before, a, items, ps);
     DL_HIP(hipGetLastError());
     if (pushed) {
         rc = dl_push_commit(stream);

@@ -32,24 +32,21 @@ __global__ void __launch_bounds__(512) dl_exec_rows_kernel(const dl_klist<Item, 
 
 // Entry i of a table that the host wrote into device memory through the BAR just before the launch.  A line
 // of the table that used this memory before may still sit in a cache, so the entry is read past every cache,
-// once per workgroup (8 bytes per lane), together with the slot's stamp, and handed on through LDS; if the stamp
-// is not the table's yet, both are read again.  Call with the whole workgroup.  Null if the stamp never came.
+// once per workgroup (8 bytes per lane), and handed on through LDS; before that, one lane has seen the slot's
+// stamp.  Call with the whole workgroup.  Null if the stamp never came (reported by the caller).
 template <class Item>
-__device__ __forceinline__ const Item *dl_pushed_entry(const Item *items, uint32_t i, uint64_t stamp)
+__device__ __forceinline__ const Item *dl_pushed_entry(const Item *items, uint32_t i, const dl_pushed &ps)
 {
     constexpr uint32_t WORDS = sizeof(Item) / 8;
     static_assert(sizeof(Item) % 8 == 0 && WORDS < 64, "one 8-byte load per lane of the first wavefront");
-    __shared__ uint64_t raw[WORDS + 1];
-    for (uint32_t tries = 0; tries < DL_PUSHED_TRIES; ++tries) {
-        if (threadIdx.x < WORDS)
-            raw[threadIdx.x] = dl_ld<DL_POL_COHERENT>(dl_global<uint64_t>(items + i) + threadIdx.x);
-        else if (threadIdx.x == WORDS)
-            raw[WORDS] = dl_ld<DL_POL_COHERENT>(dl_pushed_stamp(items));
-        __syncthreads();
-        if (raw[WORDS] == stamp) return reinterpret_cast<const Item *>(raw);
-        __syncthreads();
-    }
-    return nullptr;
+    __shared__ uint64_t raw[WORDS];
+    __shared__ uint32_t sealed;
+    if (threadIdx.x == 0) sealed = dl_pushed_sealed(items, ps) ? 1u : 0u;
+    __syncthreads();
+    if (!sealed) return nullptr;
+    if (threadIdx.x < WORDS) raw[threadIdx.x] = dl_ld<DL_POL_COHERENT>(dl_global<uint64_t>(items + i) + threadIdx.x);
+    __syncthreads();
+    return reinterpret_cast<const Item *>(raw);
 }
 
 // Row path over a table of equally sized items in device memory (long lists: thousands of token
@@ -58,13 +55,16 @@ __device__ __forceinline__ const Item *dl_pushed_entry(const Item *items, uint32
 template <class Item, int POL, bool PUSHED = false>
 __global__ void __launch_bounds__(512) dl_exec_urows_kernel(const Item *__restrict__ items, uint32_t n,
                                                             uint32_t tiles_per_item, uint32_t wpg_log2,
-                                                            uint32_t split_log2, uint64_t stamp)
+                                                            uint32_t split_log2, const dl_pushed ps)
 {
     const uint32_t d = blockIdx.x / tiles_per_item;
     if (d >= n) return;
     if constexpr (PUSHED) {
-        const Item *it = dl_pushed_entry(items, d, stamp);
-        if (it) dl_rows_body<POL>(*it, blockIdx.x - d * tiles_per_item, wpg_log2, split_log2);
+        const Item *it = dl_pushed_entry(items, d, ps);
+        if (it)
+            dl_rows_body<POL>(*it, blockIdx.x - d * tiles_per_item, wpg_log2, split_log2);
+        else if (threadIdx.x == 0)
+            dl_pushed_report_lost(ps);  // nothing copied by this workgroup; the host hears of it
     } else
         dl_rows_body<POL>(items[d], blockIdx.x - d * tiles_per_item, wpg_log2, split_log2);
 }
@@ -86,13 +86,16 @@ __global__ void __launch_bounds__(512) dl_exec_list_strided_kernel(const dl_klis
 
 template <class Item, int POL, bool PUSHED = false>
 __global__ void __launch_bounds__(512) dl_exec_table_kernel(const Item *__restrict__ items, uint32_t n,
-                                                            uint32_t tile_bytes, uint32_t split, uint64_t stamp)
+                                                            uint32_t tile_bytes, uint32_t split, const dl_pushed ps)
 {
     const uint32_t b = blockIdx.x;
     if (b >= n) return;
     if constexpr (PUSHED) {
-        const Item *pushed = dl_pushed_entry(items, b, stamp);
-        if (!pushed) return;
+        const Item *pushed = dl_pushed_entry(items, b, ps);
+        if (!pushed) {
+            if (threadIdx.x == 0) dl_pushed_report_lost(ps);  // nothing copied by this workgroup; the host hears of it
+            return;
+        }
         const Item it = *pushed;
         dl_run_item<POL>(it, 0, tile_bytes, split);
     } else {
@@ -271,11 +274,23 @@ __global__ void __launch_bounds__(512) dl_armed_list_kernel(const dl_klist<Item,
     const uint32_t go = dl_arm_wait(a);
     if (go == DL_GO_RUN) {
         const uint32_t total = p.tile_end[p.n - 1];
-        for (uint32_t b = blockIdx.x; b < total; b += gridDim.x) {
-            if constexpr (ROWS)
-                dl_run_rows<DL_POL_COHERENT>(p, b);
+        if constexpr (ROWS && !std::is_same<Item, dl_swap_item>::value) {
+            // A grid that makes several passes (it is capped while it waits) keeps four rows in flight per
+            // wavefront, or two: a coherent load takes a microsecond or two, and one per pass left the memory idle.
+            const uint32_t grid = gridDim.x;
+            if (total <= grid)
+                dl_run_rows<DL_POL_COHERENT>(p, blockIdx.x);
+            else if (total <= 2u * grid)
+                dl_run_rows_coherent<2>(p, blockIdx.x, grid, total);
             else
-                dl_run_tile<DL_POL_COHERENT>(p, b);
+                for (uint32_t b = blockIdx.x; b < total; b += 4u * grid) dl_run_rows_coherent<4>(p, b, grid, total);
+        } else {
+            for (uint32_t b = blockIdx.x; b < total; b += gridDim.x) {
+                if constexpr (ROWS)
+                    dl_run_rows<DL_POL_COHERENT>(p, b);
+                else
+                    dl_run_tile<DL_POL_COHERENT>(p, b);
+            }
         }
     }
     dl_arm_finish(a, go);
@@ -359,23 +374,21 @@ __global__ void __launch_bounds__(DL_STANDBY_THREADS) dl_standby_kernel(dl_stand
 
 // Entry i of a table written through the BAR (see dl_pushed_entry), read by every lane for itself: all lanes
 // load the same 8 bytes, which costs one request per wavefront, and no barrier.  For kernels that walk a table.
-// *sealed: the slot's stamp, read along with the entry, is the table's (else the entry is not to be used).
+// *sealed: the slot's stamp has been seen (looked for here, before the entry is read, unless an earlier call
+// saw it already: once the stamp is there the whole table is); if it is not, the entry is not to be used.
 template <class Item>
-__device__ __forceinline__ Item dl_pushed_entry_per_lane(const Item *items, uint32_t i, uint64_t stamp, bool *sealed)
+__device__ __forceinline__ Item dl_pushed_entry_per_lane(const Item *items, uint32_t i, const dl_pushed &ps, bool *sealed)
 {
     static_assert(sizeof(Item) % 8 == 0, "whole 8-byte words");
     union {
         Item it;
         uint64_t w[sizeof(Item) / 8];
     } u;
-    *sealed = false;
-    for (uint32_t tries = 0; tries < DL_PUSHED_TRIES && !*sealed; ++tries) {
+    if (!*sealed) *sealed = dl_uniform64(dl_pushed_sealed(items, ps) ? 1ull : 0ull) != 0;
 #pragma unroll
-        for (uint32_t q = 0; q < sizeof(Item) / 8; ++q) {
-            const uint64_t v = dl_ld<DL_POL_COHERENT>(dl_global<uint64_t>(items + i) + q);
-            u.w[q] = dl_uniform64(v);  // the same in every lane: keep it in scalar registers
-        }
-        *sealed = dl_uniform64(dl_ld<DL_POL_COHERENT>(dl_pushed_stamp(items))) == stamp;
+    for (uint32_t q = 0; q < sizeof(Item) / 8; ++q) {
+        const uint64_t v = *sealed ? dl_ld<DL_POL_COHERENT>(dl_global<uint64_t>(items + i) + q) : 0ull;
+        u.w[q] = dl_uniform64(v);  // the same in every lane: keep it in scalar registers
     }
     return u.it;
 }
@@ -384,18 +397,18 @@ __device__ __forceinline__ Item dl_pushed_entry_per_lane(const Item *items, uint
 // fetched before the wait.
 template <class Item, bool PUSHED = false>
 __global__ void __launch_bounds__(512) dl_armed_table_kernel(const Item *__restrict__ items, uint32_t n,
-                                                             uint32_t tile_bytes, uint32_t split, uint64_t stamp,
+                                                             uint32_t tile_bytes, uint32_t split, const dl_pushed ps,
                                                              const dl_arm a)
 {
     if constexpr (PUSHED) {
         Item it{};
-        bool sealed = true;  // checked with the first entry; once the stamp has been seen the whole table is there
-        if (blockIdx.x < n) it = dl_pushed_entry_per_lane(items, blockIdx.x, stamp, &sealed);
+        bool sealed = blockIdx.x >= n;  // looked for with the first entry; once the stamp has been seen the whole table is there
+        if (blockIdx.x < n) it = dl_pushed_entry_per_lane(items, blockIdx.x, ps, &sealed);
         uint32_t go = dl_arm_wait(a);
         if (!sealed && go == DL_GO_RUN) go = DL_GO_SKIP;  // reported like a request that gave up
         if (go == DL_GO_RUN) {
             for (uint32_t b = blockIdx.x; b < n; b += gridDim.x) {
-                if (b != blockIdx.x) it = dl_pushed_entry_per_lane(items, b, stamp, &sealed);
+                if (b != blockIdx.x) it = dl_pushed_entry_per_lane(items, b, ps, &sealed);
                 dl_run_item<DL_POL_COHERENT>(it, 0, tile_bytes, split);
             }
         }
@@ -740,15 +753,16 @@ bool launch_uniform_rows(const Item *items, size_t n, const dl_launch_shape &sh,
         if (*rc != DL_OK) return true;
         dslot = (const Item *)(g_ring.dev + s * RING_SLOT_BYTES);
     }
+    const dl_pushed ps = dl_push_kernel_args(stamp);
     with_policy(sh.policy, [&](auto pol) {
         if (pushed)
             hipLaunchKernelGGL((dl_exec_urows_kernel<Item, decltype(pol)::value, true>), dim3((uint32_t)(tpi * n)),
                                dim3(threads), 0, stream, dslot, (uint32_t)n, (uint32_t)tpi,
-                               log2u(threads / 64u / split), log2u(split), stamp);
+                               log2u(threads / 64u / split), log2u(split), ps);
         else
             hipLaunchKernelGGL((dl_exec_urows_kernel<Item, decltype(pol)::value, false>), dim3((uint32_t)(tpi * n)),
                                dim3(threads), 0, stream, dslot, (uint32_t)n, (uint32_t)tpi,
-                               log2u(threads / 64u / split), log2u(split), stamp);
+                               log2u(threads / 64u / split), log2u(split), ps);
     });
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && !pushed) e = hipEventRecord(g_ring.ev[s], stream);
@@ -853,6 +867,7 @@ int launch_table(const Item *items, size_t n, dl_launch_shape sh, hipStream_t st
             if (rc != DL_OK) return rc;
             slot = (Item *)(g_ring.dev + s * RING_SLOT_BYTES);
         }
+        const dl_pushed ps = dl_push_kernel_args(stamp);
         if (arm) {
             dl_arm a = *arm;
             const uint32_t g = armed_grid(m, sh.block_threads, !a.nowait);
@@ -861,10 +876,10 @@ int launch_table(const Item *items, size_t n, dl_launch_shape sh, hipStream_t st
             g_dl.armed_words = a.own_word ? g : 1u;
             if (pushed)
                 hipLaunchKernelGGL((dl_armed_table_kernel<Item, true>), dim3(g), dim3(sh.block_threads), 0, stream, slot,
-                                   (uint32_t)m, sh.tile_bytes, sh.split, stamp, a);
+                                   (uint32_t)m, sh.tile_bytes, sh.split, ps, a);
             else
                 hipLaunchKernelGGL((dl_armed_table_kernel<Item, false>), dim3(g), dim3(sh.block_threads), 0, stream, slot,
-                                   (uint32_t)m, sh.tile_bytes, sh.split, stamp, a);
+                                   (uint32_t)m, sh.tile_bytes, sh.split, ps, a);
             // whoever wants this memory next must not wait for a request that nobody has triggered
             if (!a.nowait) {
                 if (pushed)
@@ -877,11 +892,11 @@ int launch_table(const Item *items, size_t n, dl_launch_shape sh, hipStream_t st
                 if (pushed)
                     hipLaunchKernelGGL((dl_exec_table_kernel<Item, decltype(pol)::value, true>), dim3((uint32_t)m),
                                        dim3(sh.block_threads), 0, stream, slot, (uint32_t)m, sh.tile_bytes, sh.split,
-                                       stamp);
+                                       ps);
                 else
                     hipLaunchKernelGGL((dl_exec_table_kernel<Item, decltype(pol)::value, false>), dim3((uint32_t)m),
                                        dim3(sh.block_threads), 0, stream, slot, (uint32_t)m, sh.tile_bytes, sh.split,
-                                       stamp);
+                                       ps);
             });
         }
         DL_HIP(hipGetLastError());
@@ -1095,7 +1110,7 @@ int dl_launch_fused_rows_table(const dl_fused_item *dev_items, uint32_t n, uint6
     with_policy(sh.policy, [&](auto pol) {
         hipLaunchKernelGGL((dl_exec_urows_kernel<dl_fused_item, decltype(pol)::value>), dim3((uint32_t)(tpi * n)),
                            dim3(threads), 0, stream, dev_items, n, (uint32_t)tpi, log2u(threads / 64u / split),
-                           log2u(split), (uint64_t)0);
+                           log2u(split), dl_push_kernel_args(0));
     });
     DL_HIP(hipGetLastError());
     return DL_OK;
@@ -1131,6 +1146,41 @@ void dl_ring_own_stream(hipStream_t stream)
 {
     if (!stream && g_ring.batch_len && g_ring.batch_stream == g_ring.own_stream) (void)push_close_batch();
     g_ring.own_stream = stream;
+}
+
+// The device error word: host-coherent memory that a kernel writes when it gives up on a table that never
+// became complete (see dl_pushed).  Read, and cleared, by dl_last_device_error().
+static uint64_t *g_lost = nullptr;
+// Test hook (dl_debug_lose_next_table): the kernel of the next table that goes through the BAR is told a stamp
+// that its slot will never hold and this many looks, so that the give-up path runs, every wait still bounded.
+static uint32_t g_debug_lose_tries = 0;
+
+dl_pushed dl_push_kernel_args(uint64_t stamp)
+{
+    dl_pushed ps{stamp, DL_PUSHED_TRIES, 0u, g_lost};
+    if (stamp && g_debug_lose_tries) {
+        ps.stamp = stamp | (1ull << 62);
+        ps.tries = g_debug_lose_tries;
+        g_debug_lose_tries = 0;
+    }
+    return ps;
+}
+
+bool dl_device_error_pending() { return g_lost && __atomic_load_n(g_lost, __ATOMIC_ACQUIRE) != 0; }
+
+extern "C" int dl_last_device_error(void)
+{
+    if (!g_lost) return DL_OK;
+    return __atomic_exchange_n(g_lost, 0ull, __ATOMIC_ACQ_REL) ? DL_ERR_LOST : DL_OK;
+}
+
+extern "C" int dl_debug_lose_next_table(uint32_t tries)
+{
+    if (!g_dl.inited) return DL_ERR_STATE;
+    if (!g_ring.push || !g_dl.cfg.table_push) return DL_ERR_STATE;  // no table goes through the BAR here
+    if (tries > 1024) return DL_ERR_INVALID;  // 0 disarms the hook
+    g_debug_lose_tries = tries;
+    return DL_OK;
 }
 
 char *dl_push_acquire(size_t bytes, hipStream_t stream, int *rc) { return push_acquire(bytes, stream, rc); }
@@ -1187,6 +1237,9 @@ int dl_exec_init()
         g_ring.push_cover[q] = -1;
         g_ring.push_armed[q] = 0;
     }
+    DL_HIP(hipHostMalloc((void **)&g_lost, 64, hipHostMallocCoherent | hipHostMallocMapped));
+    *g_lost = 0;
+    g_debug_lose_tries = 0;
     DL_HIP(hipHostMalloc((void **)&g_ring.base, RING_SLOTS * RING_SLOT_BYTES, hipHostMallocDefault));
     DL_HIP(hipMalloc((void **)&g_ring.dev, RING_SLOTS * RING_SLOT_BYTES));
     for (size_t s = 0; s < RING_SLOTS; ++s) {
@@ -1210,6 +1263,8 @@ int dl_exec_shutdown()
     for (size_t q = 0; q < PUSH_SLOTS; ++q) (void)hipEventDestroy(g_ring.push_ev[q]);
     (void)hipHostFree(g_ring.base);
     (void)hipFree(g_ring.dev);
+    (void)hipHostFree(g_lost);
+    g_lost = nullptr;
     g_ring.base = nullptr;
     g_ring.dev = nullptr;
     return DL_OK;

@@ -113,7 +113,12 @@ int dl_ring_release(size_t slot, hipStream_t stream);
 //   dl_ring_forget_armed  every armed request has finished (their tickets start over with the next session)
 //   dl_ring_own_stream  the library's own stream for armed requests exists (or, null, is about to be destroyed):
 //                    the one stream besides the default stream that cannot go away between two calls
+//   dl_push_kernel_args  what the kernel that reads the slot gets: the stamp, how often to look for it, where to
+//                    report that it never came (stamp 0: a kernel whose table did not go this way)
+//   dl_device_error_pending  a kernel has reported such a loss and dl_last_device_error() has not been called since
 uint64_t dl_push_seal(char *slot);
+dl_pushed dl_push_kernel_args(uint64_t stamp);
+bool dl_device_error_pending();
 void dl_ring_forget_armed();
 void dl_ring_own_stream(hipStream_t stream);
 char *dl_push_acquire(size_t bytes, hipStream_t stream, int *rc);

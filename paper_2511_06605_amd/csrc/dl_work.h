@@ -18,6 +18,15 @@ constexpr int DL_FAN = 8;  // destinations one work item can write from a single
 constexpr uint32_t DL_PUSH_SLOT_BYTES = 64u << 10;
 constexpr uint32_t DL_PUSH_PAYLOAD_BYTES = DL_PUSH_SLOT_BYTES - 8;
 
+// What a kernel that reads a table written through the BAR needs besides the table: the stamp that the slot
+// holds once the table is complete, how often to look for it, and where to report that it never came.
+struct dl_pushed {
+    uint64_t stamp;
+    uint32_t tries;
+    uint32_t pad;
+    uint64_t *lost;  // host-coherent: the library's device error word
+};
+
 // Plain copy: one source, one destination.
 struct dl_plain_item {
     const char *src;

@@ -752,3 +752,108 @@ def test_validation_rejects_hazards_and_enqueues_nothing():
     after = d.host()
     assert np.array_equal(after[:1000], before[:1000]) and np.array_equal(after[2000:], before[2000:])
     assert np.array_equal(after[1000:1500], before[0:500]) and np.array_equal(after[1500:2000], before[100:600])
+
+
+# ----------------------------------- failure reports from the device; table memory after a stream has gone
+
+def _lose_next_table():
+    """Arm the test hook, or skip where no table goes through the BAR."""
+    try:
+        dl.dl_debug_lose_next_table(3)
+    except dl.DlError as e:
+        if e.status == dl.DL_ERR_STATE:
+            pytest.skip("no table is written through the BAR in this configuration")
+        raise
+
+
+@pytest.mark.parametrize("kind", ["table", "rows_table", "token_dispatch"])
+def test_a_table_that_never_completes_is_reported_and_nothing_is_copied(ref, kind):
+    """The kernel of a long list is told (by the test hook) a stamp that its table's slot will never hold, and
+    three looks: every workgroup gives up its bounded wait and leaves.  The call has returned DL_OK long before;
+    the loss shows in dl_last_device_error(), every operation refuses until it has been read, no destination
+    byte has changed, and the same request issued again gives the checker's result."""
+    assert dl.dl_last_device_error() == dl.DL_OK
+    W = 8
+    if kind == "token_dispatch":
+        counts, row = [96] * W, 512
+        ins = inputs.token_rows(W, counts, row, seed=5, kind="u8")
+        dest = inputs.moe_token_destinations(W, counts, seed=6, n_experts=256, top_k=8)
+        want = ref.token_dispatch(ins, row, dest)
+        d_in = [DevBuf(a.size, fill=a) for a in ins]
+        outs = [DevBuf(w.size, fill=np.full(w.size, 0x3C, dtype=np.uint8)) for w in want]
+        before = [np.full(w.size, 0x3C, dtype=np.uint8) for w in want]
+
+        def issue():
+            dl.dl_token_dispatch([b.ptr() for b in d_in], [b.ptr() for b in outs], counts, row, dest, stream())
+    else:
+        n, nb = (200, 16 * KiB) if kind == "rows_table" else (300, 5000)
+        arena, descs = inputs.b2b_batch(n, nb, 32 * MiB, seed=n, align=256 if kind == "rows_table" else 1)
+        want = [ref.batch_copy([arena.copy()], [(0, s, 0, d, m) for s, d, m in descs])[0]]
+        outs = [DevBuf(arena.size, fill=arena)]
+        before = [arena]
+
+        def issue():
+            d = outs[0]
+            dl.dl_batch_copy([(d.ptr(int(s)), d.ptr(int(t)), int(m)) for s, t, m in descs], stream())
+
+    _lose_next_table()
+    issue()
+    sync()
+    with pytest.raises(dl.DlError) as refused:
+        issue()
+    assert refused.value.status == dl.DL_ERR_LOST
+    assert dl.dl_last_device_error() == dl.DL_ERR_LOST
+    assert dl.dl_last_device_error() == dl.DL_OK
+    for d, b in zip(outs, before):
+        assert np.array_equal(d.host(), b) and d.guards_intact(), "a request whose table was lost changed a byte"
+    issue()
+    sync()
+    assert dl.dl_last_device_error() == dl.DL_OK
+    for d, w in zip(outs, want):
+        assert np.array_equal(d.host(), w) and d.guards_intact()
+
+
+def _hip_runtime():
+    """The HIP runtime this process has loaded already (the one that owns every stream here)."""
+    import ctypes
+    with open("/proc/self/maps") as f:
+        paths = {line.split()[-1] for line in f if "libamdhip64" in line}
+    assert paths, "no HIP runtime loaded"
+    return ctypes.CDLL(sorted(paths)[0])
+
+
+@pytest.mark.parametrize("push", [1, 0])
+def test_table_memory_is_reused_after_the_callers_stream_is_gone(ref, cfg, push):
+    """A long-list request on a stream of the caller's, which the caller destroys once it has synchronised; then
+    enough long-list requests on the default stream that every table slot is used again.  The library must not
+    touch the dead stream (its event was recorded while the stream was alive)."""
+    import ctypes
+    import torch
+    cfg(table_push=push)
+    hip = _hip_runtime()
+    hip.hipStreamCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+    hip.hipStreamSynchronize.argtypes = [ctypes.c_void_p]
+    hip.hipStreamDestroy.argtypes = [ctypes.c_void_p]
+    rng = np.random.default_rng(5)
+    cases = []
+    for r in range(71):
+        n = int(rng.integers(70, 300))
+        arena, descs = inputs.b2b_batch(n, int(rng.choice([512, 3000, 16 * KiB])), 16 * MiB, seed=100 + r)
+        cases.append((arena, DevBuf(arena.size, fill=arena), descs))
+    torch.cuda.synchronize()
+
+    def issue(case, st):
+        _, d, descs = case
+        dl.dl_batch_copy([(d.ptr(int(s)), d.ptr(int(t)), int(m)) for s, t, m in descs], st)
+
+    own = ctypes.c_void_p()
+    assert hip.hipStreamCreate(ctypes.byref(own)) == 0
+    issue(cases[0], own.value)
+    assert hip.hipStreamSynchronize(own) == 0
+    assert hip.hipStreamDestroy(own) == 0
+    for case in cases[1:]:
+        issue(case, stream())
+    sync()
+    for r, (arena, d, descs) in enumerate(cases):
+        want = ref.batch_copy([arena.copy()], [(0, s, 0, t, m) for s, t, m in descs])[0]
+        assert np.array_equal(d.host(), want) and d.guards_intact(), f"request {r}"
