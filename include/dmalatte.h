@@ -54,7 +54,8 @@ typedef enum dl_status {
     DL_ERR_TIMEOUT = -4,  /* a host-side wait gave up */
     DL_ERR_STATE = -5,    /* not initialised; prelaunch mode not started; started twice; table memory still held by an armed request that has not been triggered */
     DL_ERR_EXPIRED = -6,  /* an armed request was cancelled or not triggered within its arm limit: nothing, or (triggered at the very limit) only part, was copied */
-    DL_ERR_LOST = -7      /* a kernel of an EARLIER request gave up waiting for the copy table that the host had written into device memory, so that request copied nothing or only part; every operation returns this until dl_last_device_error() has been called */
+    DL_ERR_LOST = -7,     /* a kernel of an EARLIER request gave up waiting for the copy table that the host had written into device memory, so that request copied nothing or only part; every operation returns this until dl_last_device_error() has been called */
+    DL_ERR_CAPACITY = -8  /* the request is larger than the stated maximum of the entry point (dl_batch_copy_static) */
 } dl_status;
 
 /* Largest number of destinations of one dl_broadcast call / ranks of a collective. */
@@ -137,6 +138,31 @@ int dl_debug_lose_next_table(uint32_t tries);
  * desc: host array of n descriptors.  n == 0 or all bytes == 0: DL_OK, no work.
  */
 int dl_batch_copy(const dl_copy_desc *desc, size_t n, void *stream);
+
+/*
+ * dl_batch_copy for callers that cannot allocate: code under HIP stream
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * semantics, arguments and hazard rule as dl_batch_copy, with these
+ * differences:
+ *  - it calls no hipMalloc, no hipFree, no event, memset or other allocating
+ *    routine, on the host or the device side, and keeps nothing of the
+ *    caller's after it returns;
+ *  - the table of the cut list lives in a static device array of
+ *    DL_STATIC_MAX_COPIES entries of 24 bytes (384 KiB, held by every GPU the
+ *    library runs on until the process ends).  n > DL_STATIC_MAX_COPIES, or a
+ *    batch that cannot be cut into that many pieces of at most 1 GiB, returns
+ *    DL_ERR_CAPACITY and enqueues nothing;
+ *  - it always executes as in DL_MODE_ONESHOT, on `stream`: ceil(entries/64)
+ *    small kernels that carry the table to the device in their arguments,
+ *    then the table kernel.  No broadcast inference and no hazard check
+ *    (dl_set_validate has no effect here);
+ *  - all calls on one GPU share the array: calls on one stream are ordered
+ *    by the stream; calls that overlap on different streams race and give
+ *    undefined results.  Nothing in the array has to start at zero: a call
+ *    reads only the entries it wrote itself.
+ */
+#define DL_STATIC_MAX_COPIES 16384
+int dl_batch_copy_static(const dl_copy_desc *desc, size_t n, void *stream);
 
 /*
  * Broadcast (paper Sec. IV-B, generalised from 2 to k destinations): every

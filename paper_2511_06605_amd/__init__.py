@@ -7,7 +7,7 @@ result on the CPU.
 """
 
 from .binding import (  # noqa: F401
-    DL_ERR_EXPIRED, DL_ERR_LOST, DL_ERR_HIP, DL_ERR_INVALID, DL_ERR_OVERLAP, DL_ERR_STATE, DL_ERR_TIMEOUT, DL_MAX_FANOUT,
+    DL_ERR_EXPIRED, DL_ERR_LOST, DL_ERR_CAPACITY, DL_STATIC_MAX_COPIES, DL_ERR_HIP, DL_ERR_INVALID, DL_ERR_OVERLAP, DL_ERR_STATE, DL_ERR_TIMEOUT, DL_MAX_FANOUT,
     DL_MODE_ONESHOT, DL_MODE_PRELAUNCH, DL_MODE_SIGNAL, DL_MODE_STANDBY, DL_OK, DL_PLAN_FANOUT, Config, DlError, dl_allgather,
     dl_alltoall, dl_batch_copy, dl_broadcast, dl_get_config, dl_get_mode, dl_init, dl_last_ticket,
     dl_plan_allgather, dl_plan_alltoall, dl_plan_batch, dl_plan_broadcast, dl_plan_first_hazard,
@@ -15,4 +15,4 @@ from .binding import (  # noqa: F401
     dl_set_validate, dl_shutdown, dl_trigger, dl_wait, dl_wait_armed, dl_batch_swap, dl_alltoall_inplace,
     dl_plan_alltoall_inplace, dl_plan_swap_first_hazard, dl_batch_fanout, dl_token_dispatch,
     dl_plan_token_dispatch, dl_plan_batch_inferred, dl_set_trace, dl_get_trace, dl_trace_clock,
-    dl_last_device_error, dl_debug_lose_next_table)
+    dl_last_device_error, dl_debug_lose_next_table, dl_batch_copy_static)

@@ -25,6 +25,8 @@ DL_ERR_TIMEOUT = -4
 DL_ERR_STATE = -5
 DL_ERR_EXPIRED = -6
 DL_ERR_LOST = -7
+DL_ERR_CAPACITY = -8
+DL_STATIC_MAX_COPIES = 16384
 DL_MAX_FANOUT = 64
 DL_PLAN_FANOUT = 8
 DL_MODE_ONESHOT = 0
@@ -42,7 +44,7 @@ EXPORTS = [
     "dl_plan_first_hazard", "dl_plan_tiles", "dl_batch_swap", "dl_alltoall_inplace", "dl_plan_alltoall_inplace",
     "dl_plan_swap_first_hazard", "dl_batch_fanout", "dl_token_dispatch", "dl_plan_token_dispatch",
     "dl_plan_batch_inferred", "dl_set_trace", "dl_get_trace", "dl_trace_clock",
-    "dl_last_device_error", "dl_debug_lose_next_table",
+    "dl_last_device_error", "dl_debug_lose_next_table", "dl_batch_copy_static",
 ]
 
 
@@ -124,6 +126,7 @@ def lib() -> ctypes.CDLL:
         "dl_last_device_error": (ctypes.c_int, []),
         "dl_debug_lose_next_table": (ctypes.c_int, [ctypes.c_uint32]),
         "dl_batch_copy": (ctypes.c_int, [ctypes.POINTER(CopyDesc), ctypes.c_size_t, vp]),
+        "dl_batch_copy_static": (ctypes.c_int, [ctypes.POINTER(CopyDesc), ctypes.c_size_t, vp]),
         "dl_broadcast": (ctypes.c_int, [vp, vpp, ctypes.c_int, ctypes.c_size_t, vp]),
         "dl_allgather": (ctypes.c_int, [vpp, vpp, ctypes.c_int, ctypes.c_size_t, vp]),
         "dl_alltoall": (ctypes.c_int, [vpp, vpp, ctypes.c_int, szp, vp]),
@@ -277,6 +280,12 @@ def dl_batch_copy(descs, stream=None) -> None:
     """descs: sequence of (src, dst, bytes)."""
     descs = list(descs)
     _check(lib().dl_batch_copy(_desc_array(descs), len(descs), _stream(stream)), "dl_batch_copy")
+
+
+def dl_batch_copy_static(descs, stream=None) -> None:
+    """descs: sequence of (src, dst, bytes); the variant that allocates nothing."""
+    descs = list(descs)
+    _check(lib().dl_batch_copy_static(_desc_array(descs), len(descs), _stream(stream)), "dl_batch_copy_static")
 
 
 def dl_broadcast(src, dsts, nbytes: int, stream=None) -> None:

@@ -9,7 +9,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdmalatte.so")
-SOURCES = ["dl_api.hip", "dl_exec.hip", "dl_prelaunch.hip", "dl_dispatch.hip"]
+SOURCES = ["dl_api.hip", "dl_exec.hip", "dl_prelaunch.hip", "dl_dispatch.hip", "dl_static.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno-gpu-rdc",

@@ -394,7 +394,8 @@ int dl_init(int device)
     g_dl.cfg.infer_broadcast = 1;
     g_dl.cfg.device_lowering = 1;
     g_dl.cfg.table_push = 1;
-    const int rc = dl_exec_init();
+    int rc = dl_exec_init();
+    if (rc == DL_OK) rc = dl_static_init(device);
     if (rc != DL_OK) return rc;
     g_dl.inited = true;
     return DL_OK;
@@ -448,6 +449,7 @@ const char *dl_strerror(int status)
     case DL_ERR_TIMEOUT: return "timed out";
     case DL_ERR_STATE: return "library or prelaunch mode not in the required state";
     case DL_ERR_EXPIRED: return "armed request cancelled or not triggered in time; nothing or only part was copied";
+    case DL_ERR_CAPACITY: return "the request exceeds the stated maximum of this entry point";
     case DL_ERR_LOST: return "a kernel of an earlier request never saw its copy table complete and copied nothing or only part";
     default: return "unknown status";
     }

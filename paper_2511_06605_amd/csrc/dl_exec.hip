@@ -1116,6 +1116,18 @@ int dl_launch_fused_rows_table(const dl_fused_item *dev_items, uint32_t n, uint6
     return DL_OK;
 }
 
+int dl_launch_plain_table(const dl_plain_item *dev_items, uint32_t m, uint32_t tile_bytes, uint64_t moved, hipStream_t stream)
+{
+    if (m == 0) return DL_OK;
+    const dl_launch_shape sh = dl_choose_shape(moved / 2, tile_bytes, 1);  // for the cache policy
+    with_policy(sh.policy, [&](auto pol) {
+        hipLaunchKernelGGL((dl_exec_table_kernel<dl_plain_item, decltype(pol)::value, false>), dim3(m), dim3(256), 0,
+                           stream, dev_items, m, tile_bytes, 1u, dl_push_kernel_args(0));
+    });
+    DL_HIP(hipGetLastError());
+    return DL_OK;
+}
+
 int dl_ring_acquire(size_t *slot, char **host, char **dev)
 {
     if (!g_ring.base) return DL_ERR_STATE;

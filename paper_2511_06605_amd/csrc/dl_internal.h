@@ -128,6 +128,13 @@ int dl_push_commit(hipStream_t stream);
 // device memory, destinations laid out for DL_TABLE_ROWS_SPLIT sub-groups (see slots_by_subgroup).
 int dl_launch_fused_rows_table(const dl_fused_item *dev_items, uint32_t n, uint64_t item_bytes, hipStream_t stream);
 
+// dl_exec.hip: the table kernel over m one-tile plain copies that are already in device memory (entry b is
+// workgroup b's), with the cache policy that suits `moved` bytes read + written.
+int dl_launch_plain_table(const dl_plain_item *dev_items, uint32_t m, uint32_t tile_bytes, uint64_t moved, hipStream_t stream);
+
+// dl_static.hip: the address of this device's copy of the static table (dl_batch_copy_static).
+int dl_static_init(int device);
+
 // dl_dispatch.hip: token dispatch lowered on the device (the destination mask is scanned into a table of
 // read-once/write-k items in device memory, which the row kernel then executes).  *taken says whether the request qualified; if not,
 // nothing was enqueued and the caller lowers on the host.
