@@ -687,14 +687,19 @@ def main() -> int:
     }
 
     detail = None
+    LAT_MAX = 16 * MiB    # host-observed latencies are taken up to this size, past every crossover between the modes
+
+    def lat_iters(B):
+        return 1000 if B <= MiB else 300 if B <= 4 * MiB else 100
+
     if not args.no_detail:
         detail = {"allgather": []}
         for B in sizes:
             row = {"bytes_per_rank": B, "device_us": benchaid.time_device(reqs[B], stream, warmup=3,
                                                                           calls=50 if B <= MiB else 10)}
             row["GBps"] = ag_bytes(B) / row["device_us"] / 1e3
-            if B <= 4 * MiB:
-                lat = benchaid.time_host(reqs[B], stream, benchaid.WAIT_STREAM, warmup=50, iters=1000)
+            if B <= LAT_MAX:
+                lat = benchaid.time_host(reqs[B], stream, benchaid.WAIT_STREAM, warmup=50, iters=lat_iters(B))
                 row["oneshot_host_us"] = lat_stats(lat)
             detail["allgather"].append(row)
         # The same sizes with cold caches: enough buffer sets of each size that one pass over them moves more than
@@ -723,15 +728,15 @@ def main() -> int:
         dl.dl_set_mode(dl.DL_MODE_PRELAUNCH)
         for row in detail["allgather"]:
             B = row["bytes_per_rank"]
-            if B > 4 * MiB:
+            if B > LAT_MAX:
                 continue
-            lat = benchaid.time_host(reqs[B], None, benchaid.WAIT_TRIGGER, warmup=50, iters=1000)
+            lat = benchaid.time_host(reqs[B], None, benchaid.WAIT_TRIGGER, warmup=50, iters=lat_iters(B))
             row["prelaunch_trigger_to_done_us"] = lat_stats(lat)
-            lat = benchaid.time_host(reqs[B], None, benchaid.WAIT_ARM_AND_TRIGGER, warmup=50, iters=1000)
+            lat = benchaid.time_host(reqs[B], None, benchaid.WAIT_ARM_AND_TRIGGER, warmup=50, iters=lat_iters(B))
             row["prelaunch_arm_to_done_us"] = lat_stats(lat)
             # signal mode: an ordinary launch whose completion word the host watches instead of synchronising the stream
             dl.dl_set_mode(dl.DL_MODE_SIGNAL)
-            lat = benchaid.time_host(reqs[B], None, benchaid.WAIT_SIGNAL, warmup=50, iters=1000)
+            lat = benchaid.time_host(reqs[B], None, benchaid.WAIT_SIGNAL, warmup=50, iters=lat_iters(B))
             row["signal_call_to_done_us"] = lat_stats(lat)
             if W * B <= 64 * 8192:
                 # standby mode: the request is handed to a kernel that is already waiting (no launch in between)
@@ -739,6 +744,30 @@ def main() -> int:
                 lat = benchaid.time_host(reqs[B], None, benchaid.WAIT_SIGNAL, warmup=50, iters=1000)
                 row["standby_call_to_done_us"] = lat_stats(lat)
             dl.dl_set_mode(dl.DL_MODE_PRELAUNCH)
+        # The size -> mode table (the form of the paper's Tables II / III), measured: per size the fastest way to
+        # run a request that is known ahead (armed and triggered, or one-shot) and one known only when issued
+        # (standby where it fits, signal, or one-shot), and the largest size at which each mode still wins.
+        table = []
+        for row in detail["allgather"]:
+            if "oneshot_host_us" not in row:
+                continue
+            one = row["oneshot_host_us"]["p50"]
+            ahead = {"prelaunch": row["prelaunch_trigger_to_done_us"]["p50"], "oneshot": one}
+            issue = {"signal": row["signal_call_to_done_us"]["p50"], "oneshot": one}
+            if "standby_call_to_done_us" in row:
+                issue["standby"] = row["standby_call_to_done_us"]["p50"]
+            table.append({"bytes_per_rank": row["bytes_per_rank"], "moved_bytes": ag_bytes(row["bytes_per_rank"]),
+                          "known_ahead": min(ahead, key=ahead.get), "known_on_issue": min(issue, key=issue.get),
+                          "us": {**ahead, **issue}})
+        detail["mode_table_measured"] = {
+            "rows": table,
+            "largest_moved_bytes_won_by": {
+                m: max([r_["moved_bytes"] for r_ in table if r_["known_ahead" if m == "prelaunch" else "known_on_issue"] == m],
+                       default=0) for m in ("prelaunch", "standby", "signal")},
+            "library_thresholds": {"prelaunch_max_bytes": dl.DL_AUTO_PRELAUNCH_MAX_BYTES,
+                                   "signal_max_bytes": dl.DL_AUTO_SIGNAL_MAX_BYTES,
+                                   "standby_tiles": dl.DL_AUTO_STANDBY_TILES},
+        }
         # phase breakdown (the form of the paper's Fig. 4: one transfer split into control / schedule / copy / sync,
         # 4 KB .. 2 MB), medians in microseconds
         med = lambda xs: pct(xs, .5)
@@ -768,6 +797,8 @@ def main() -> int:
                              "total": med(total)}
         detail["phase_breakdown_allgather"] = rows
         detail.update(other_operations(dl, benchaid, inputs, torch, stream, reqs, keep, sizes, runtime_batch))
+        out["mode_crossover_moved_MiB"] = {k: v >> 20 for k, v in
+                                           detail["mode_table_measured"]["largest_moved_bytes_won_by"].items()}
         small = detail["allgather"][0]
         out["latency_us_4KiB_allgather"] = {
             "oneshot_call_to_stream_sync_p50": round(small["oneshot_host_us"]["p50"], 2),

@@ -66,9 +66,11 @@ typedef enum dl_mode {
     DL_MODE_PRELAUNCH = 1, /* one armed kernel per call, started by dl_trigger() */
     DL_MODE_SIGNAL = 2,    /* one kernel launch per call that starts at once and writes a completion word: the
                               request has a ticket, dl_wait() observes its end without a stream synchronisation */
-    DL_MODE_STANDBY = 3    /* small requests are handed to a kernel that is already waiting on the device: no
+    DL_MODE_STANDBY = 3,   /* small requests are handed to a kernel that is already waiting on the device: no
                               launch between the call and the copy (see "standby mode" below); the rest run as in
                               DL_MODE_SIGNAL */
+    DL_MODE_AUTO = 4       /* the library picks standby, signal or one-shot execution per request from its size
+                              (see "size -> mode table" below) */
 } dl_mode;
 
 /* One copy of a batch: `bytes` bytes from device pointer src to device pointer dst. */
@@ -343,6 +345,65 @@ typedef struct dl_trace {
 int dl_set_trace(int on);
 int dl_get_trace(uint64_t ticket, dl_trace *out);
 int dl_trace_clock(double *ticks_per_us, double *host_ns_at_tick0);
+
+/* --------------------------------------------------------- size -> mode table */
+
+/*
+ * Which way of executing a request is fastest depends on its size; the paper
+ * tabulates that choice per collective and size for its DMA features (Tables
+ * II and III, Sec. V-B).  The table for this library, measured on MI355X
+ * (host-observed time from the call, or from the doorbell for an armed
+ * request, to completion seen on the host):
+ *
+ *   request known ahead of time (the caller can arm it and trigger later):
+ *     moved bytes <= DL_AUTO_PRELAUNCH_MAX_BYTES            DL_MODE_PRELAUNCH
+ *     larger                                                DL_MODE_ONESHOT
+ *   request known only when it is issued:
+ *     fits a waiting kernel: at most DL_AUTO_STANDBY_TILES tiles of 8 KiB and
+ *     at most 8 items (64 if every item has one destination), not a swap,
+ *     not a token dispatch                                  DL_MODE_STANDBY
+ *     else moved bytes <= DL_AUTO_SIGNAL_MAX_BYTES          DL_MODE_SIGNAL
+ *     larger                                                DL_MODE_ONESHOT
+ *     (a token dispatch of 512 tokens or more: DL_MODE_ONESHOT, where the
+ *     device derives the copies from the mask)
+ *
+ * "moved bytes" are the algorithmic bytes read plus written (an all-gather of
+ * B bytes per rank over W ranks: (W + W*W) * B); a tile count is what
+ * dl_plan_tiles() gives for 8192-byte tiles.  The large requests go one-shot
+ * because the kernels of the other modes load and store at system scope and
+ * wait on a capped grid, which costs bandwidth once the copy dominates.
+ *
+ * dl_plan_mode() is that table as a host-only function (no GPU needed).
+ * op: a dl_op; items and max_fanout: length of the lowered list and the most
+ * destinations any item has (what the dl_plan_* functions return); tiles:
+ * dl_plan_tiles(items, n, 8192); known_ahead: 0 / 1.  Returns a dl_mode, or
+ * DL_ERR_INVALID.
+ *
+ * In DL_MODE_AUTO (needs dl_prelaunch_start(), keeps the standby kernels
+ * waiting like DL_MODE_STANDBY) every operation applies the table with
+ * known_ahead = 0 to its own lowered list.  Because the request may be handed
+ * to a waiting kernel, which is not ordered on `stream`, everything it reads
+ * must be complete before the call, as in standby mode.  dl_last_mode() tells
+ * how the most recent request was executed (a request that the table sends to
+ * standby but that no waiting kernel could take runs as DL_MODE_SIGNAL), and
+ * dl_complete(stream, ns) waits for it in the way that fits: a stream
+ * synchronisation after one-shot execution, dl_wait() on its ticket
+ * otherwise.
+ */
+typedef enum dl_op {
+    DL_OP_BATCH = 0,
+    DL_OP_BROADCAST = 1,
+    DL_OP_ALLGATHER = 2,
+    DL_OP_ALLTOALL = 3,
+    DL_OP_SWAP = 4,           /* dl_batch_swap, dl_alltoall_inplace */
+    DL_OP_TOKEN_DISPATCH = 5
+} dl_op;
+#define DL_AUTO_STANDBY_TILES 64
+#define DL_AUTO_SIGNAL_MAX_BYTES (288ull << 20)     /* an all-gather of 4 MiB per rank over 8 ranks */
+#define DL_AUTO_PRELAUNCH_MAX_BYTES (144ull << 20)  /* an all-gather of 2 MiB per rank over 8 ranks */
+int dl_plan_mode(int op, size_t items, uint32_t max_fanout, uint64_t moved_bytes, uint64_t tiles, int known_ahead);
+int dl_last_mode(void);
+int dl_complete(void *stream, uint64_t timeout_ns);
 
 /* -------------------------------------------------------------------- tunables */
 

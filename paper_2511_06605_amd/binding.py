@@ -33,6 +33,11 @@ DL_MODE_ONESHOT = 0
 DL_MODE_PRELAUNCH = 1
 DL_MODE_SIGNAL = 2
 DL_MODE_STANDBY = 3
+DL_MODE_AUTO = 4
+DL_OP_BATCH, DL_OP_BROADCAST, DL_OP_ALLGATHER, DL_OP_ALLTOALL, DL_OP_SWAP, DL_OP_TOKEN_DISPATCH = range(6)
+DL_AUTO_STANDBY_TILES = 64
+DL_AUTO_SIGNAL_MAX_BYTES = 288 << 20
+DL_AUTO_PRELAUNCH_MAX_BYTES = 144 << 20
 
 # every symbol include/dmalatte.h declares
 EXPORTS = [
@@ -45,6 +50,7 @@ EXPORTS = [
     "dl_plan_swap_first_hazard", "dl_batch_fanout", "dl_token_dispatch", "dl_plan_token_dispatch",
     "dl_plan_batch_inferred", "dl_set_trace", "dl_get_trace", "dl_trace_clock",
     "dl_last_device_error", "dl_debug_lose_next_table", "dl_batch_copy_static",
+    "dl_plan_mode", "dl_last_mode", "dl_complete",
 ]
 
 
@@ -120,6 +126,10 @@ def lib() -> ctypes.CDLL:
         "dl_shutdown": (ctypes.c_int, []),
         "dl_set_mode": (ctypes.c_int, [ctypes.c_int]),
         "dl_get_mode": (ctypes.c_int, []),
+        "dl_last_mode": (ctypes.c_int, []),
+        "dl_complete": (ctypes.c_int, [vp, ctypes.c_uint64]),
+        "dl_plan_mode": (ctypes.c_int, [ctypes.c_int, ctypes.c_size_t, ctypes.c_uint32, ctypes.c_uint64, ctypes.c_uint64,
+                                        ctypes.c_int]),
         "dl_set_validate": (ctypes.c_int, [ctypes.c_int]),
         "dl_strerror": (ctypes.c_char_p, [ctypes.c_int]),
         "dl_last_hip_error": (ctypes.c_int, []),
@@ -253,6 +263,22 @@ def dl_set_mode(mode: int) -> None:
 
 def dl_get_mode() -> int:
     return lib().dl_get_mode()
+
+
+def dl_last_mode() -> int:
+    return lib().dl_last_mode()
+
+
+def dl_complete(stream=None, timeout_ns: int = 5_000_000_000) -> None:
+    _check(lib().dl_complete(_stream(stream), timeout_ns), "dl_complete")
+
+
+def dl_plan_mode(op: int, items: int, max_fanout: int, moved_bytes: int, tiles: int, known_ahead: bool) -> int:
+    """The size -> mode table: the dl_mode that suits a lowered list of these dimensions."""
+    m = lib().dl_plan_mode(int(op), int(items), int(max_fanout), int(moved_bytes), int(tiles), 1 if known_ahead else 0)
+    if m < 0:
+        raise DlError(int(m), "dl_plan_mode")
+    return int(m)
 
 
 def dl_set_validate(on: bool) -> None:

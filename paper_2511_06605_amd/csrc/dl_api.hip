@@ -309,16 +309,76 @@ int run_in_mode(void *stream, Launch launch)
     return rc;
 }
 
-int execute(const dl_plan_item *items, size_t n, void *stream)
+// The size -> mode table (see the header).  One place holds the thresholds; dl_plan_mode() and DL_MODE_AUTO
+// both come here.
+struct mode_limits {
+    uint32_t standby_tiles, standby_items_fanout, standby_items_plain;
+    uint64_t signal_max_moved, prelaunch_max_moved;
+    uint64_t dispatch_device_tokens;  // a token dispatch of this many tokens is lowered on the device, one-shot
+};
+constexpr mode_limits MODE_LIMITS = {DL_AUTO_STANDBY_TILES, 8u, 64u, DL_AUTO_SIGNAL_MAX_BYTES,
+                                     DL_AUTO_PRELAUNCH_MAX_BYTES, 512u};
+
+int plan_mode(int op, size_t items, uint32_t max_fanout, uint64_t moved, uint64_t tiles, int known_ahead)
+{
+    if (op < DL_OP_BATCH || op > DL_OP_TOKEN_DISPATCH || (known_ahead != 0 && known_ahead != 1)) return DL_ERR_INVALID;
+    if (items && (max_fanout < 1 || max_fanout > (uint32_t)DL_PLAN_FANOUT)) return DL_ERR_INVALID;
+    const mode_limits &L = MODE_LIMITS;
+    if (known_ahead) return moved <= L.prelaunch_max_moved ? DL_MODE_PRELAUNCH : DL_MODE_ONESHOT;
+    if (op == DL_OP_TOKEN_DISPATCH && items >= L.dispatch_device_tokens) return DL_MODE_ONESHOT;
+    const bool fits_record = op != DL_OP_SWAP && op != DL_OP_TOKEN_DISPATCH && items >= 1 && tiles >= 1 &&
+                             tiles <= L.standby_tiles &&
+                             items <= (max_fanout <= 1 ? L.standby_items_plain : L.standby_items_fanout);
+    if (fits_record) return DL_MODE_STANDBY;
+    return moved <= L.signal_max_moved ? DL_MODE_SIGNAL : DL_MODE_ONESHOT;
+}
+
+// In DL_MODE_AUTO: the mode the table gives this lowered list, which the request then runs in.
+int auto_mode_for(int op, const dl_plan_item *items, size_t n)
+{
+    uint64_t moved = 0, tiles = 0;
+    uint32_t kmax = 1;
+    for (size_t i = 0; i < n; ++i) {
+        moved += items[i].bytes * (1ull + items[i].k);
+        tiles += dl_item_tiles(*reinterpret_cast<const dl_fused_item *>(&items[i]), DL_STANDBY_TILE);
+        if (items[i].k > kmax) kmax = items[i].k;
+    }
+    return plan_mode(op, n, kmax, moved, tiles, 0);
+}
+
+// Runs f with g_dl.mode set to `mode` (the launchers read it), then puts the caller's setting back.
+template <class F>
+int with_mode(int mode, F f)
+{
+    const int asked = g_dl.mode;
+    g_dl.mode = mode;
+    const int rc = f();
+    g_dl.mode = asked;
+    return rc;
+}
+
+int execute_in(int mode, const dl_plan_item *items, size_t n, void *stream);
+
+int execute(const dl_plan_item *items, size_t n, void *stream, int op)
 {
     if (!g_dl.inited) return DL_ERR_STATE;
     if (dl_device_error_pending()) return DL_ERR_LOST;
     if (n == 0) return DL_OK;
     if (g_dl.validate && first_hazard(items, n) >= 0) return DL_ERR_OVERLAP;
-    if (g_dl.mode == DL_MODE_STANDBY) {
+    if (g_dl.mode != DL_MODE_AUTO) return execute_in(g_dl.mode, items, n, stream);
+    const int mode = auto_mode_for(op, items, n);
+    if (mode < 0) return mode;
+    return with_mode(mode, [&] { return execute_in(mode, items, n, stream); });
+}
+
+int execute_in(int mode, const dl_plan_item *items, size_t n, void *stream)
+{
+    g_dl.last_mode = mode;
+    if (mode == DL_MODE_STANDBY) {
         bool taken = false;
         const int rc = dl_standby_try(items, n, &taken);
         if (rc != DL_OK || taken) return rc;
+        g_dl.last_mode = DL_MODE_SIGNAL;  // no waiting kernel could take it: the ordinary launch
     }
     bool all_plain = true;
     for (size_t i = 0; i < n; ++i) all_plain &= items[i].k == 1;
@@ -351,22 +411,33 @@ int execute_swaps(const dl_swap_desc *d, size_t n, void *stream)
     }
     if (g_swaps.empty()) return DL_OK;
     if (g_dl.validate && swap_first_hazard(d, n) >= 0) return DL_ERR_OVERLAP;
-    return run_in_mode(stream, [&](hipStream_t hs, const dl_arm *armp, bool *launched) {
-        return dl_exec_swap(g_swaps.data(), g_swaps.size(), hs, armp, launched);
+    int mode = g_dl.mode;
+    if (mode == DL_MODE_AUTO) {
+        uint64_t moved = 0;
+        for (const dl_swap_item &it : g_swaps) moved += 4 * it.bytes;  // both ranges are read and written
+        mode = plan_mode(DL_OP_SWAP, g_swaps.size(), 1, moved, 0, 0);
+    } else if (mode == DL_MODE_STANDBY) {
+        mode = DL_MODE_SIGNAL;  // swaps are never handed to a waiting kernel
+    }
+    g_dl.last_mode = mode;
+    return with_mode(mode, [&] {
+        return run_in_mode(stream, [&](hipStream_t hs, const dl_arm *armp, bool *launched) {
+            return dl_exec_swap(g_swaps.data(), g_swaps.size(), hs, armp, launched);
+        });
     });
 }
 
 // Lower with `fn` into the reusable buffer, growing it when the first pass
 // reports more items than fit.
 template <class Fn>
-int lower_and_execute(Fn fn, void *stream)
+int lower_and_execute(Fn fn, void *stream, int op)
 {
     if (g_items.size() < 64) g_items.resize(64);
     for (int pass = 0; pass < 2; ++pass) {
         sink s{g_items.data(), g_items.size()};
         const long r = fn(s);
         if (r < 0) return (int)r;
-        if ((size_t)r <= g_items.size()) return execute(g_items.data(), (size_t)r, stream);
+        if ((size_t)r <= g_items.size()) return execute(g_items.data(), (size_t)r, stream, op);
         g_items.resize((size_t)r);
     }
     return DL_ERR_INVALID;
@@ -415,20 +486,39 @@ int dl_shutdown(void)
 
 int dl_set_mode(int mode)
 {
-    if (mode != DL_MODE_ONESHOT && mode != DL_MODE_PRELAUNCH && mode != DL_MODE_SIGNAL && mode != DL_MODE_STANDBY)
-        return DL_ERR_INVALID;
+    if (mode < DL_MODE_ONESHOT || mode > DL_MODE_AUTO) return DL_ERR_INVALID;
     if (mode != DL_MODE_ONESHOT && !dl_armed_ready()) return DL_ERR_STATE;
     if (mode == g_dl.mode) return DL_OK;
-    if (g_dl.mode == DL_MODE_STANDBY) {
+    // standby and auto mode keep the pool of waiting kernels armed
+    const bool had_pool = g_dl.mode == DL_MODE_STANDBY || g_dl.mode == DL_MODE_AUTO;
+    const bool wants_pool = mode == DL_MODE_STANDBY || mode == DL_MODE_AUTO;
+    if (had_pool && !wants_pool) {
         const int rc = dl_standby_leave();
         if (rc != DL_OK) return rc;
     }
-    if (mode == DL_MODE_STANDBY) {
+    if (!had_pool && wants_pool) {
         const int rc = dl_standby_enter();
         if (rc != DL_OK) return rc;
     }
     g_dl.mode = mode;
     return DL_OK;
+}
+
+int dl_last_mode(void) { return g_dl.last_mode; }
+
+int dl_plan_mode(int op, size_t items, uint32_t max_fanout, uint64_t moved_bytes, uint64_t tiles, int known_ahead)
+{
+    return plan_mode(op, items, max_fanout, moved_bytes, tiles, known_ahead);
+}
+
+int dl_complete(void *stream, uint64_t timeout_ns)
+{
+    if (!g_dl.inited) return DL_ERR_STATE;
+    if (g_dl.last_mode == DL_MODE_ONESHOT) {
+        DL_HIP(hipStreamSynchronize((hipStream_t)stream));
+        return DL_OK;
+    }
+    return dl_wait(dl_last_ticket(), timeout_ns);
 }
 
 int dl_get_mode(void) { return g_dl.mode; }
@@ -480,8 +570,8 @@ int dl_set_config(const dl_config *cfg)
 int dl_batch_copy(const dl_copy_desc *desc, size_t n, void *stream)
 {
     if (g_dl.cfg.infer_broadcast && n > 1)
-        return lower_and_execute([&](sink &s) { return lower_batch_inferred(desc, n, s); }, stream);
-    return lower_and_execute([&](sink &s) { return lower_batch(desc, n, s); }, stream);
+        return lower_and_execute([&](sink &s) { return lower_batch_inferred(desc, n, s); }, stream, DL_OP_BATCH);
+    return lower_and_execute([&](sink &s) { return lower_batch(desc, n, s); }, stream, DL_OP_BATCH);
 }
 
 int dl_batch_fanout(const dl_plan_item *items, size_t n, void *stream)
@@ -499,21 +589,24 @@ int dl_batch_fanout(const dl_plan_item *items, size_t n, void *stream)
             }
             return (long)s.n;
         },
-        stream);
+        stream, DL_OP_BATCH);
 }
 
 int dl_token_dispatch(const void *const *in, void *const *out, int W, const uint32_t *tokens, size_t row_bytes,
                       const uint8_t *dest, void *stream)
 {
     if (g_dl.inited && dl_device_error_pending()) return DL_ERR_LOST;
-    if (g_dl.inited && g_dl.mode == DL_MODE_ONESHOT && !g_dl.validate && g_dl.cfg.device_lowering) {
-        // many tokens: only the destination mask goes to the device, which works out the rest itself
+    if (g_dl.inited && (g_dl.mode == DL_MODE_ONESHOT || g_dl.mode == DL_MODE_AUTO) && !g_dl.validate &&
+        g_dl.cfg.device_lowering) {
+        // many tokens: only the destination mask goes to the device, which works out the rest itself (one-shot
+        // execution; in DL_MODE_AUTO that is what the table gives such a request)
         bool taken = false;
         const int rc = dl_dispatch_on_device(in, out, W, tokens, row_bytes, dest, (hipStream_t)stream, &taken);
+        if (taken) g_dl.last_mode = DL_MODE_ONESHOT;
         if (taken || rc != DL_OK) return rc;
     }
     return lower_and_execute([&](sink &s) { return lower_token_dispatch(in, out, W, tokens, row_bytes, dest, s); },
-                             stream);
+                             stream, DL_OP_TOKEN_DISPATCH);
 }
 
 long dl_plan_token_dispatch(const void *const *in, void *const *out, int W, const uint32_t *tokens, size_t row_bytes,
@@ -531,18 +624,19 @@ long dl_plan_batch_inferred(const dl_copy_desc *desc, size_t n, dl_plan_item *it
 
 int dl_broadcast(const void *src, void *const *dsts, int k, size_t bytes, void *stream)
 {
-    return lower_and_execute([&](sink &s) { return lower_broadcast(src, dsts, k, bytes, s); }, stream);
+    return lower_and_execute([&](sink &s) { return lower_broadcast(src, dsts, k, bytes, s); }, stream, DL_OP_BROADCAST);
 }
 
 int dl_allgather(const void *const *in, void *const *out, int W, size_t bytes_per_rank, void *stream)
 {
     const int fuse = (int)g_dl.cfg.fuse_broadcast;
-    return lower_and_execute([&](sink &s) { return lower_allgather(in, out, W, bytes_per_rank, fuse, s); }, stream);
+    return lower_and_execute([&](sink &s) { return lower_allgather(in, out, W, bytes_per_rank, fuse, s); }, stream,
+                             DL_OP_ALLGATHER);
 }
 
 int dl_alltoall(const void *const *in, void *const *out, int W, const size_t *chunk_bytes, void *stream)
 {
-    return lower_and_execute([&](sink &s) { return lower_alltoall(in, out, W, chunk_bytes, s); }, stream);
+    return lower_and_execute([&](sink &s) { return lower_alltoall(in, out, W, chunk_bytes, s); }, stream, DL_OP_ALLTOALL);
 }
 
 int dl_batch_swap(const dl_swap_desc *desc, size_t n, void *stream) { return execute_swaps(desc, n, stream); }

@@ -13,7 +13,8 @@ struct dl_state {
     bool inited = false;
     int device = -1;
     int num_cu = 0;
-    int mode = DL_MODE_ONESHOT;
+    int mode = DL_MODE_ONESHOT;       // as set by the caller
+    int last_mode = DL_MODE_ONESHOT;  // how the most recent request was executed
     int validate = 0;
     int last_hip = 0;
     int trace = 0;  // armed kernels record phase stamps

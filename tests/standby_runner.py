@@ -280,7 +280,92 @@ def random_requests():
     dl.dl_prelaunch_start()
     try:
         for seed in range(5000, 5000 + int(os.environ.get("DL_TEST_RANDOM_CASES", "150"))):
-            rnd.run_case(ref, seed, modes=("standby", "standby", "standby", "signal", "oneshot", "prelaunch"))
+            rnd.run_case(ref, seed, modes=("standby", "standby", "standby", "signal", "oneshot", "prelaunch", "auto", "auto"))
+    finally:
+        dl.dl_set_mode(dl.DL_MODE_ONESHOT)
+        dl.dl_prelaunch_stop()
+
+
+def auto_mode_across_the_table():
+    """DL_MODE_AUTO: the four operations (and swaps, and a token dispatch) at sizes on both sides of every row of
+    the size -> mode table, each compared with the CPU checker; dl_last_mode() must say what the table says (a
+    request for a waiting kernel may also have taken the ordinary launch, if none was free), and dl_complete()
+    waits in the way that fits."""
+    one, sig, sb = dl.DL_MODE_ONESHOT, dl.DL_MODE_SIGNAL, dl.DL_MODE_STANDBY
+    seen = set()
+
+    def done(expect, what):
+        got = dl.dl_last_mode()
+        assert got == expect or (expect == sb and got == sig), f"{what}: executed in mode {got}, table says {expect}"
+        seen.add(got)
+        dl.dl_complete(stream())
+
+    dl.dl_set_config(arm_timeout_us=ARM_US)
+    dl.dl_prelaunch_start()
+    try:
+        dl.dl_set_mode(dl.DL_MODE_AUTO)
+        W = 8
+        for B, expect in [(4 * KiB, sb), (64 * KiB, sb), (64 * KiB + 16, sig), (1 * MiB, sig), (4 * MiB, sig),
+                          (4 * MiB + 16, one), (5 * MiB + 3, one)]:
+            ins = inputs.allgather_inputs(W, B, seed=B % 1000)
+            d_in = [DevBuf(B, fill=a) for a in ins]
+            d_out = [DevBuf(W * B) for _ in range(W)]
+            sync()
+            dl.dl_allgather([b.ptr() for b in d_in], [b.ptr() for b in d_out], B, stream())
+            done(expect, f"all-gather {B}")
+            for r, w in zip(d_out, ref.allgather(ins)):
+                assert np.array_equal(r.host(), w) and r.guards_intact(), f"auto all-gather B={B}"
+        for c, expect in [(8 * KiB, sb), (16 * KiB, sig), (2 * MiB, sig), (4 * MiB, one)]:
+            C = inputs.uniform_chunks(W, c)
+            ins = inputs.alltoall_inputs(C, seed=c % 1000, kind="fp16")
+            want = ref.alltoall(ins, C)
+            d_in = [DevBuf(a.size, fill=a) for a in ins]
+            d_out = [DevBuf(w.size) for w in want]
+            sync()
+            dl.dl_alltoall([b.ptr() for b in d_in], [b.ptr() for b in d_out], C, stream())
+            done(expect, f"all-to-all {c}")
+            for j in range(W):
+                assert np.array_equal(d_out[j].host(), want[j]) and d_out[j].guards_intact(), f"auto all-to-all c={c}"
+        for nbytes, expect in [(512 * KiB, sb), (512 * KiB + 16, sig), (2 * MiB, sig), (40 * MiB, one)]:
+            src = inputs.payload(np.random.default_rng(nbytes), nbytes, "bf16")
+            d_src = DevBuf(src.size, fill=src)
+            d_dst = [DevBuf(src.size) for _ in range(7)]
+            sync()
+            dl.dl_broadcast(d_src.ptr(), [b.ptr() for b in d_dst], src.size, stream())
+            done(expect, f"broadcast {nbytes}")
+            for b in d_dst:
+                assert np.array_equal(b.host(), src) and b.guards_intact(), f"auto broadcast {nbytes}"
+        for n, nb, expect in [(64, 100, sb), (65, 100, sig), (64, 16 * KiB, sig), (40, 5 * MiB, one)]:
+            arena, descs = inputs.b2b_batch(n, nb, max(4 * MiB, 3 * n * nb), seed=n + nb)
+            want = ref.batch_copy([arena.copy()], [(0, s, 0, t, m) for s, t, m in descs])[0]
+            d = DevBuf(arena.size, fill=arena)
+            sync()
+            dl.dl_batch_copy([(d.ptr(int(s)), d.ptr(int(t)), int(m)) for s, t, m in descs], stream())
+            done(expect, f"batch {n} x {nb}")
+            assert np.array_equal(d.host(), want) and d.guards_intact(), f"auto batch {n} x {nb}"
+        for Wn, c, expect in [(4, 3000, sig), (4, 16 * MiB, one)]:
+            bufs = inputs.alltoall_inputs(inputs.uniform_chunks(Wn, c), seed=9)
+            d_buf = [DevBuf(a.size, fill=a) for a in bufs]
+            sync()
+            dl.dl_alltoall_inplace([b.ptr() for b in d_buf], c, stream())
+            done(expect, f"in-place all-to-all {c}")
+            for b, w in zip(d_buf, ref.alltoall_inplace(bufs, c)):
+                assert np.array_equal(b.host(), w) and b.guards_intact(), f"auto in-place all-to-all c={c}"
+        for T, expect in [(16, sig), (128, one)]:
+            row = 14336
+            ins = inputs.token_rows(W, T, row, seed=T + 1, kind="bf16")
+            dest = inputs.moe_token_destinations(W, T, seed=T)
+            want = ref.token_dispatch(ins, row, dest)
+            d_in = [DevBuf(a.size, fill=a) for a in ins]
+            d_out = [DevBuf(w.size) for w in want]
+            sync()
+            dl.dl_token_dispatch([b.ptr() for b in d_in], [b.ptr() for b in d_out], [T] * W, row, dest, stream())
+            done(expect, f"token dispatch {T}")
+            for j in range(W):
+                assert np.array_equal(d_out[j].host(), want[j]) and d_out[j].guards_intact(), f"auto token dispatch T={T}"
+        assert {one, sig} <= seen, f"modes executed: {seen}"
+        if os.environ.get("DL_NO_BAR") != "1":
+            assert sb in seen, "no request was handed to a waiting kernel"
     finally:
         dl.dl_set_mode(dl.DL_MODE_ONESHOT)
         dl.dl_prelaunch_stop()
@@ -288,7 +373,7 @@ def random_requests():
 
 CHECKS = [allgather_sizes, allgather_misaligned, other_operations, many_requests_with_changing_sources,
           kernels_that_gave_up_are_replaced, requests_close_to_the_limit, mode_switches_and_stop,
-          armed_requests_of_every_grid_size, random_requests]
+          armed_requests_of_every_grid_size, auto_mode_across_the_table, random_requests]
 
 
 def main():

@@ -102,8 +102,10 @@ def test_allgather_rank_counts(ref, W):
     run_allgather(ref, W, 5000, seed=W)
 
 
-@pytest.mark.parametrize("B", [4 * KiB, 256 * KiB, 16 * MiB])
+@pytest.mark.parametrize("B", [4 * KiB << i for i in range(14)])
 def test_allgather_sweep_points_bf16(ref, B):
+    """Every point of the all-gather size sweep that the benchmark times, 4 KiB .. 32 MiB per rank, same seeds and
+    launch configuration (64 MiB: test_allgather_full_size_64MiB)."""
     run_allgather(ref, 8, B, seed=B.bit_length() - 1, kind="bf16")
 
 
@@ -214,9 +216,10 @@ def test_allgather_full_size_64MiB(ref):
 
 # ------------------------------------------------------------------ all-to-all
 
-@pytest.mark.parametrize("c", [1 * KiB, 64 * KiB, 4 * MiB])
+@pytest.mark.parametrize("c", [1 * KiB << i for i in range(13)])
 def test_alltoall_uniform_fp16(ref, c):
-    run_alltoall(ref, inputs.uniform_chunks(8, c), seed=c, kind="fp16")
+    """Every point of the all-to-all sweep, 1 KiB .. 4 MiB per pair, as the benchmark draws it."""
+    run_alltoall(ref, inputs.uniform_chunks(8, c), seed=c.bit_length(), kind="fp16")
 
 
 @pytest.mark.parametrize("W,seed", [(2, 0), (3, 1), (8, 2), (8, 3), (13, 4)])

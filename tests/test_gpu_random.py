@@ -98,7 +98,7 @@ def run_case(ref, seed, scale=1, modes=MODES):
     saved = {f[0]: getattr(base, f[0]) for f in base._fields_}
     dl.dl_set_config(**tun)
     dl.dl_set_mode({"oneshot": dl.DL_MODE_ONESHOT, "prelaunch": dl.DL_MODE_PRELAUNCH, "signal": dl.DL_MODE_SIGNAL,
-                    "standby": dl.DL_MODE_STANDBY}[mode])
+                    "standby": dl.DL_MODE_STANDBY, "auto": dl.DL_MODE_AUTO}[mode])
     s_arg = st if mode == "oneshot" else None
     before = dl.dl_last_ticket()
     try:

@@ -429,3 +429,88 @@ def test_broadcast_inference_gives_the_same_items_into_any_capacity(seed):
     if count > 1:
         short = items_with_capacity(count - 1)
         assert short[0] == count and short[1] == exact[1][:count - 1]
+
+
+# ------------------------------------------------------- size -> mode table (paper Tables II / III, Sec. V-B)
+
+def _header_constants():
+    text = open(os.path.join(ROOT, "include", "dmalatte.h")).read()
+    tiles = int(re.search(r"#define DL_AUTO_STANDBY_TILES (\d+)", text).group(1))
+    sig = int(re.search(r"#define DL_AUTO_SIGNAL_MAX_BYTES \((\d+)ull << 20\)", text).group(1)) << 20
+    pre = int(re.search(r"#define DL_AUTO_PRELAUNCH_MAX_BYTES \((\d+)ull << 20\)", text).group(1)) << 20
+    return tiles, sig, pre
+
+
+def test_mode_table_constants_agree_with_the_header():
+    assert _header_constants() == (dl.DL_AUTO_STANDBY_TILES, dl.DL_AUTO_SIGNAL_MAX_BYTES, dl.DL_AUTO_PRELAUNCH_MAX_BYTES)
+
+
+def test_mode_table_at_every_threshold():
+    """dl_plan_mode on both sides of every row of the table, one tile / one item / one byte apart."""
+    T, SIG, PRE = _header_constants()
+    AG, AA, BC, BT, SW, TD = (dl.DL_OP_ALLGATHER, dl.DL_OP_ALLTOALL, dl.DL_OP_BROADCAST, dl.DL_OP_BATCH, dl.DL_OP_SWAP,
+                              dl.DL_OP_TOKEN_DISPATCH)
+    one, pre, sig, sb = dl.DL_MODE_ONESHOT, dl.DL_MODE_PRELAUNCH, dl.DL_MODE_SIGNAL, dl.DL_MODE_STANDBY
+    plan = dl.dl_plan_mode
+    # known ahead: prelaunch up to the limit, one-shot above; tiles and items play no part
+    for op in (AG, AA, BC, BT, SW, TD):
+        assert plan(op, 8, 8 if op == AG else 1, PRE, 10 ** 6, True) == pre
+        assert plan(op, 8, 8 if op == AG else 1, PRE + 1, 1, True) == one
+        assert plan(op, 1, 1, 1, 1, True) == pre
+    # known on issue: the waiting kernel's record holds 64 tiles, 8 items with several destinations or 64 plain ones
+    assert plan(AG, 8, 8, 72 * 65536, T, False) == sb
+    assert plan(AG, 8, 8, 72 * 65536 + 72 * 16, T + 1, False) == sig
+    assert plan(AG, 9, 8, 9 * 10 * 4096, 9, False) == sig          # nine fan-out items do not fit
+    assert plan(BC, 1, 7, 8 * 512 * 1024, T, False) == sb
+    assert plan(AA, 64, 1, 128 * 8192, T, False) == sb
+    assert plan(AA, 64, 1, 128 * 8208, 2 * T, False) == sig
+    assert plan(BT, 64, 1, 2 * 64 * 100, 64, False) == sb
+    assert plan(BT, 65, 1, 2 * 65 * 100, 65, False) == sig
+    assert plan(BT, 9, 2, 3 * 9 * 100, 9, False) == sig            # broadcast inference made fan-out items: 8 at most
+    assert plan(BT, 8, 2, 3 * 8 * 100, 8, False) == sb
+    # swaps and token dispatches are never handed to a waiting kernel, however small
+    assert plan(SW, 1, 1, 4 * 1024, 1, False) == sig
+    assert plan(TD, 16, 8, 16 * 9 * 1024, 16, False) == sig
+    assert plan(TD, 511, 8, 511 * 9 * 1024, 511, False) == sig
+    assert plan(TD, 512, 8, 512 * 9 * 1024, 512, False) == one     # lowered on the device, one-shot
+    # above the record: signal up to the limit, one-shot beyond
+    for op in (AG, AA, BC, BT, SW):
+        assert plan(op, 8, 8 if op in (AG, BC) else 1, SIG, 10 ** 5, False) == sig
+        assert plan(op, 8, 8 if op in (AG, BC) else 1, SIG + 1, 10 ** 5, False) == one
+    # malformed questions
+    for bad in ((-1, 1, 1, 1, 1, False), (6, 1, 1, 1, 1, False), (AG, 1, 0, 1, 1, False), (AG, 1, 9, 1, 1, False)):
+        with pytest.raises(dl.DlError):
+            plan(*bad)
+
+
+def test_mode_table_applied_to_the_lowered_collectives():
+    """The table fed with what the lowering of the task's workloads gives: all-gather sweep points on both sides
+    of each threshold (W = 8), the uniform all-to-all, the 2 MiB -> 7 broadcast, the 64 x 16 KiB batch."""
+    W = 8
+    a = np.zeros(1, dtype=np.uint8)
+    base = addr(a)
+
+    def ag_mode(B, ahead):
+        ins = [base + (1 << 32) * (1 + j) for j in range(W)]
+        outs = [base + (1 << 32) * (20 + j) for j in range(W)]
+        items = dl.dl_plan_allgather(ins, outs, B)
+        return dl.dl_plan_mode(dl.DL_OP_ALLGATHER, len(items), max(i["k"] for i in items), (W + W * W) * B,
+                               dl.dl_plan_tiles(items, 8192), ahead)
+
+    assert [ag_mode(B, False) for B in (4096, 64 * 1024, 64 * 1024 + 16, 1 << 20, 4 << 20, (4 << 20) + 16, 64 << 20)] == \
+        [dl.DL_MODE_STANDBY, dl.DL_MODE_STANDBY, dl.DL_MODE_SIGNAL, dl.DL_MODE_SIGNAL, dl.DL_MODE_SIGNAL,
+         dl.DL_MODE_ONESHOT, dl.DL_MODE_ONESHOT]
+    assert [ag_mode(B, True) for B in (4096, 2 << 20, (2 << 20) + 16, 64 << 20)] == \
+        [dl.DL_MODE_PRELAUNCH, dl.DL_MODE_PRELAUNCH, dl.DL_MODE_ONESHOT, dl.DL_MODE_ONESHOT]
+
+    def aa_mode(c):
+        ins = [base + (1 << 32) * (1 + j) for j in range(W)]
+        outs = [base + (1 << 32) * (20 + j) for j in range(W)]
+        items = dl.dl_plan_alltoall(ins, outs, [[c] * W] * W)
+        return dl.dl_plan_mode(dl.DL_OP_ALLTOALL, len(items), 1, 2 * W * W * c, dl.dl_plan_tiles(items, 8192), False)
+
+    assert [aa_mode(c) for c in (1024, 8192, 16384, 2 << 20, 4 << 20)] == \
+        [dl.DL_MODE_STANDBY, dl.DL_MODE_STANDBY, dl.DL_MODE_SIGNAL, dl.DL_MODE_SIGNAL, dl.DL_MODE_ONESHOT]
+    items = dl.dl_plan_broadcast(base + (1 << 32), [base + (1 << 32) * (2 + d) for d in range(7)], 2 << 20)
+    assert dl.dl_plan_mode(dl.DL_OP_BROADCAST, len(items), 7, 8 * (2 << 20), dl.dl_plan_tiles(items, 8192), False) == dl.DL_MODE_SIGNAL
+    assert dl.dl_plan_mode(dl.DL_OP_BATCH, 64, 1, 2 * 64 * 16384, 128, False) == dl.DL_MODE_SIGNAL
