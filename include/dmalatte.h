@@ -420,6 +420,7 @@ typedef struct dl_config {
     uint32_t device_lowering;    /* 1: dl_token_dispatch with 512 tokens or more (W = 8, aligned rows, one-shot mode, validation off) sends only the mask to the device, which derives the copies itself; default 1 */
     uint32_t table_push;         /* 1: the table of a long list (more copies than fit the kernel arguments) is written by the host straight into device memory, through the BAR, when the device exposes one that covers its memory and the table is short enough; 0: always through pinned host memory; default 1 */
     uint64_t write_through_max_bytes; /* requests moving at most this many bytes (read + written) use write-through stores; default 144 MiB */
+    uint64_t stream_plain_min_bytes;  /* lists of plain 1:1 copies (all-to-all, batches) moving at least this many bytes use streaming loads/stores: nothing of such a request fits the on-die caches, and keeping it out of them measured 3-6 % faster; default 512 MiB; UINT64_MAX = never */
 } dl_config;
 
 int dl_get_config(dl_config *cfg);

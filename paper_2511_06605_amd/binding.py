@@ -87,6 +87,7 @@ class Config(ctypes.Structure):
         ("device_lowering", ctypes.c_uint32),
         ("table_push", ctypes.c_uint32),
         ("write_through_max_bytes", ctypes.c_uint64),
+        ("stream_plain_min_bytes", ctypes.c_uint64),
     ]
 
 

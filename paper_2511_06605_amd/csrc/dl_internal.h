@@ -41,6 +41,7 @@ struct dl_launch_shape {
     uint32_t max_blocks;  // 0 = one workgroup per tile
     int policy;           // cache policy of the copy loop (DL_POL_*)
     bool rows = false;    // the list qualifies for the row path of the list kernels
+    uint32_t rows2d_width = 0;  // row path on a two-dimensional grid (item by item), this many tiles wide; 0: one-dimensional
 };
 
 // What an armed (prelaunched) kernel needs to wait for its doorbell and to
