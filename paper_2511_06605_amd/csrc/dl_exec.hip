@@ -119,7 +119,8 @@ __global__ void __launch_bounds__(512) dl_exec_table_kernel(const Item *__restri
 //
 // The compute-unit analogue of a poll command queued in front of the copies
 // (Sec. IV-E): the kernel is enqueued ahead of time, its workgroups wait until
-// the doorbell word in host-coherent memory reaches their ticket, then copy.
+// the doorbell word (in device memory that the host writes through the BAR, else
+// in host-coherent memory) reaches their ticket, then copy.
 // No workgroup ever waits for another one to make progress, and every wait is
 // bounded by a wall-clock limit, so every wave leaves the kernel.
 
