@@ -34,7 +34,13 @@
  *    host-coherent memory, as it does on a device without such a BAR.
  *  - Return value: DL_OK (0) or a negative dl_status.  No exceptions, no
  *    aborts.  On DL_ERR_HIP, dl_last_hip_error() gives the hipError_t.
- *  - Not thread-safe: one host thread drives the library at a time.
+ *  - Host threads: the library's host state sits behind one lock, which every
+ *    entry point takes for the length of the call, so several threads may
+ *    issue requests, trigger and wait at once (the waits spin without the
+ *    lock).  Mode, tunables and the prelaunch session are process-wide;
+ *    dl_last_ticket(), dl_last_mode() and dl_complete() refer to the most
+ *    recent request of the CALLING thread.  dl_prelaunch_stop() and
+ *    dl_shutdown() must not run while another thread is inside a wait.
  */
 #ifndef DMALATTE_H
 #define DMALATTE_H
@@ -316,7 +322,7 @@ int dl_alltoall_inplace(void *const *buf, int W, size_t chunk_bytes, void *strea
  */
 int dl_prelaunch_start(void);
 int dl_prelaunch_stop(void);
-uint64_t dl_last_ticket(void); /* ticket of the most recent request issued in prelaunch mode (0 = none yet) */
+uint64_t dl_last_ticket(void); /* ticket of the calling thread's most recent request that took one (prelaunch, signal, standby mode; 0 = none yet in this session) */
 int dl_trigger(uint64_t ticket);
 int dl_wait(uint64_t ticket, uint64_t timeout_ns);
 int dl_wait_armed(uint64_t ticket, uint64_t timeout_ns);

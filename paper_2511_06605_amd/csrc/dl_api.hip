@@ -9,6 +9,8 @@
 #include <vector>
 
 dl_state g_dl;
+std::recursive_mutex g_dl_lock;
+thread_local dl_thread_last t_dl_last;
 
 static_assert(sizeof(dl_plan_item) == sizeof(dl_fused_item), "public and device item must share a layout");
 static_assert(offsetof(dl_plan_item, dst) == offsetof(dl_fused_item, dst), "public and device item must share a layout");
@@ -373,12 +375,12 @@ int execute(const dl_plan_item *items, size_t n, void *stream, int op)
 
 int execute_in(int mode, const dl_plan_item *items, size_t n, void *stream)
 {
-    g_dl.last_mode = mode;
+    t_dl_last.mode = mode;
     if (mode == DL_MODE_STANDBY) {
         bool taken = false;
         const int rc = dl_standby_try(items, n, &taken);
         if (rc != DL_OK || taken) return rc;
-        g_dl.last_mode = DL_MODE_SIGNAL;  // no waiting kernel could take it: the ordinary launch
+        t_dl_last.mode = DL_MODE_SIGNAL;  // no waiting kernel could take it: the ordinary launch
     }
     bool all_plain = true;
     for (size_t i = 0; i < n; ++i) all_plain &= items[i].k == 1;
@@ -419,7 +421,7 @@ int execute_swaps(const dl_swap_desc *d, size_t n, void *stream)
     } else if (mode == DL_MODE_STANDBY) {
         mode = DL_MODE_SIGNAL;  // swaps are never handed to a waiting kernel
     }
-    g_dl.last_mode = mode;
+    t_dl_last.mode = mode;
     return with_mode(mode, [&] {
         return run_in_mode(stream, [&](hipStream_t hs, const dl_arm *armp, bool *launched) {
             return dl_exec_swap(g_swaps.data(), g_swaps.size(), hs, armp, launched);
@@ -449,6 +451,7 @@ extern "C" {
 
 int dl_init(int device)
 {
+    DL_LOCKED;
     if (g_dl.inited) return g_dl.device == device ? DL_OK : DL_ERR_STATE;
     DL_HIP(hipSetDevice(device));
     int cus = 0;
@@ -475,6 +478,7 @@ int dl_init(int device)
 
 int dl_shutdown(void)
 {
+    DL_LOCKED;
     if (!g_dl.inited) return DL_OK;
     int rc = DL_OK;
     if (dl_armed_ready()) rc = dl_prelaunch_stop();
@@ -487,6 +491,7 @@ int dl_shutdown(void)
 
 int dl_set_mode(int mode)
 {
+    DL_LOCKED;
     if (mode < DL_MODE_ONESHOT || mode > DL_MODE_AUTO) return DL_ERR_INVALID;
     if (mode != DL_MODE_ONESHOT && !dl_armed_ready()) return DL_ERR_STATE;
     if (mode == g_dl.mode) return DL_OK;
@@ -505,7 +510,7 @@ int dl_set_mode(int mode)
     return DL_OK;
 }
 
-int dl_last_mode(void) { return g_dl.last_mode; }
+int dl_last_mode(void) { return t_dl_last.mode; }  // the calling thread's own
 
 int dl_plan_mode(int op, size_t items, uint32_t max_fanout, uint64_t moved_bytes, uint64_t tiles, int known_ahead)
 {
@@ -514,18 +519,27 @@ int dl_plan_mode(int op, size_t items, uint32_t max_fanout, uint64_t moved_bytes
 
 int dl_complete(void *stream, uint64_t timeout_ns)
 {
-    if (!g_dl.inited) return DL_ERR_STATE;
-    if (g_dl.last_mode == DL_MODE_ONESHOT) {
+    {
+        DL_LOCKED;
+        if (!g_dl.inited) return DL_ERR_STATE;
+    }
+    // the waiting itself happens without the lock
+    if (t_dl_last.mode == DL_MODE_ONESHOT) {
         DL_HIP(hipStreamSynchronize((hipStream_t)stream));
         return DL_OK;
     }
     return dl_wait(dl_last_ticket(), timeout_ns);
 }
 
-int dl_get_mode(void) { return g_dl.mode; }
+int dl_get_mode(void)
+{
+    DL_LOCKED;
+    return g_dl.mode;
+}
 
 int dl_set_validate(int on)
 {
+    DL_LOCKED;
     g_dl.validate = on ? 1 : 0;
     return DL_OK;
 }
@@ -550,6 +564,7 @@ int dl_last_hip_error(void) { return g_dl.last_hip; }
 
 int dl_get_config(dl_config *cfg)
 {
+    DL_LOCKED;
     if (!cfg) return DL_ERR_INVALID;
     *cfg = g_dl.cfg;
     return DL_OK;
@@ -557,6 +572,7 @@ int dl_get_config(dl_config *cfg)
 
 int dl_set_config(const dl_config *cfg)
 {
+    DL_LOCKED;
     if (!cfg) return DL_ERR_INVALID;
     const uint32_t t = cfg->tile_bytes, b = cfg->block_threads;
     if (t && (t < 1024 || (t & (t - 1)) || t > (1u << 24))) return DL_ERR_INVALID;
@@ -570,6 +586,7 @@ int dl_set_config(const dl_config *cfg)
 
 int dl_batch_copy(const dl_copy_desc *desc, size_t n, void *stream)
 {
+    DL_LOCKED;
     if (g_dl.cfg.infer_broadcast && n > 1)
         return lower_and_execute([&](sink &s) { return lower_batch_inferred(desc, n, s); }, stream, DL_OP_BATCH);
     return lower_and_execute([&](sink &s) { return lower_batch(desc, n, s); }, stream, DL_OP_BATCH);
@@ -577,6 +594,7 @@ int dl_batch_copy(const dl_copy_desc *desc, size_t n, void *stream)
 
 int dl_batch_fanout(const dl_plan_item *items, size_t n, void *stream)
 {
+    DL_LOCKED;
     if (n && !items) return DL_ERR_INVALID;
     return lower_and_execute(
         [&](sink &s) -> long {
@@ -596,6 +614,7 @@ int dl_batch_fanout(const dl_plan_item *items, size_t n, void *stream)
 int dl_token_dispatch(const void *const *in, void *const *out, int W, const uint32_t *tokens, size_t row_bytes,
                       const uint8_t *dest, void *stream)
 {
+    DL_LOCKED;
     if (g_dl.inited && dl_device_error_pending()) return DL_ERR_LOST;
     if (g_dl.inited && (g_dl.mode == DL_MODE_ONESHOT || g_dl.mode == DL_MODE_AUTO) && !g_dl.validate &&
         g_dl.cfg.device_lowering) {
@@ -603,7 +622,7 @@ int dl_token_dispatch(const void *const *in, void *const *out, int W, const uint
         // execution; in DL_MODE_AUTO that is what the table gives such a request)
         bool taken = false;
         const int rc = dl_dispatch_on_device(in, out, W, tokens, row_bytes, dest, (hipStream_t)stream, &taken);
-        if (taken) g_dl.last_mode = DL_MODE_ONESHOT;
+        if (taken) t_dl_last.mode = DL_MODE_ONESHOT;
         if (taken || rc != DL_OK) return rc;
     }
     return lower_and_execute([&](sink &s) { return lower_token_dispatch(in, out, W, tokens, row_bytes, dest, s); },
@@ -619,17 +638,20 @@ long dl_plan_token_dispatch(const void *const *in, void *const *out, int W, cons
 
 long dl_plan_batch_inferred(const dl_copy_desc *desc, size_t n, dl_plan_item *items, size_t cap)
 {
+    DL_LOCKED;
     sink s{items, items ? cap : 0};
     return lower_batch_inferred(desc, n, s);
 }
 
 int dl_broadcast(const void *src, void *const *dsts, int k, size_t bytes, void *stream)
 {
+    DL_LOCKED;
     return lower_and_execute([&](sink &s) { return lower_broadcast(src, dsts, k, bytes, s); }, stream, DL_OP_BROADCAST);
 }
 
 int dl_allgather(const void *const *in, void *const *out, int W, size_t bytes_per_rank, void *stream)
 {
+    DL_LOCKED;
     const int fuse = (int)g_dl.cfg.fuse_broadcast;
     return lower_and_execute([&](sink &s) { return lower_allgather(in, out, W, bytes_per_rank, fuse, s); }, stream,
                              DL_OP_ALLGATHER);
@@ -637,13 +659,19 @@ int dl_allgather(const void *const *in, void *const *out, int W, size_t bytes_pe
 
 int dl_alltoall(const void *const *in, void *const *out, int W, const size_t *chunk_bytes, void *stream)
 {
+    DL_LOCKED;
     return lower_and_execute([&](sink &s) { return lower_alltoall(in, out, W, chunk_bytes, s); }, stream, DL_OP_ALLTOALL);
 }
 
-int dl_batch_swap(const dl_swap_desc *desc, size_t n, void *stream) { return execute_swaps(desc, n, stream); }
+int dl_batch_swap(const dl_swap_desc *desc, size_t n, void *stream)
+{
+    DL_LOCKED;
+    return execute_swaps(desc, n, stream);
+}
 
 int dl_alltoall_inplace(void *const *buf, int W, size_t chunk_bytes, void *stream)
 {
+    DL_LOCKED;
     const long n = lower_alltoall_inplace(buf, W, chunk_bytes, nullptr, 0);
     if (n < 0) return (int)n;
     g_swap_descs.resize((size_t)n);

@@ -5,16 +5,32 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "../../include/dmalatte.h"
 #include "dl_work.h"
 
-// Library state (one device, one host thread).
+// One lock around the library's host state: every entry point that reads or changes it takes the lock for
+// the length of the call (lowering and launch: microseconds), so several host threads may drive the library.
+// The waits (dl_wait, dl_wait_armed, dl_complete) look their words up under the lock and spin without it.
+// Recursive, because entry points call each other.
+extern std::recursive_mutex g_dl_lock;
+#define DL_LOCKED std::lock_guard<std::recursive_mutex> dl_lock_guard_(g_dl_lock)
+
+// What "the most recent request" means to a caller: the most recent one of the calling thread.
+struct dl_thread_last {
+    uint64_t session = 0;  // the prelaunch session the ticket belongs to
+    uint64_t ticket = 0;
+    int mode = DL_MODE_ONESHOT;
+};
+extern thread_local dl_thread_last t_dl_last;
+
+// Library state (one device).
 struct dl_state {
     bool inited = false;
     int device = -1;
     int num_cu = 0;
     int mode = DL_MODE_ONESHOT;       // as set by the caller
-    int last_mode = DL_MODE_ONESHOT;  // how the most recent request was executed
     int validate = 0;
     int last_hip = 0;
     int trace = 0;  // armed kernels record phase stamps

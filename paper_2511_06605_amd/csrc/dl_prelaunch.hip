@@ -56,6 +56,7 @@ struct arm_state {
     arm_dev *dev = nullptr;
     hipStream_t stream = nullptr;
     uint64_t seq = 0;  // last ticket issued
+    uint64_t session = 0;  // which prelaunch session this is (tickets start over with each)
     uint32_t words[SLOTS] = {};  // completion words that the slot's current request reports in
     // standby pool: a stream per executor, when the executor armed last was armed, the ticket the slot served
     // last, and the slot that takes the next request
@@ -372,12 +373,16 @@ void dl_armed_commit(uint32_t done_words)
 {
     ++g_arm.seq;
     g_arm.words[g_arm.seq % SLOTS] = done_words >= 1 && done_words <= DL_DONE_WORDS ? done_words : 1u;
+    t_dl_last.session = g_arm.session;  // the calling thread's most recent request
+    t_dl_last.ticket = g_arm.seq;
 }
 
 extern "C" {
 
 int dl_prelaunch_start(void)
 {
+    DL_LOCKED;
+    static uint64_t sessions = 0;
     if (!g_dl.inited) return DL_ERR_STATE;
     if (g_arm.started) return DL_ERR_STATE;
     int clock_khz = 0;
@@ -405,6 +410,7 @@ int dl_prelaunch_start(void)
         bell_store(&g_arm.host->cancel, g_bell_dev + 1, 0);
     }
     g_arm.seq = 0;
+    g_arm.session = ++sessions;
     g_arm.started = true;
     dl_ring_own_stream(g_arm.stream);
     return DL_OK;
@@ -412,6 +418,7 @@ int dl_prelaunch_start(void)
 
 int dl_prelaunch_stop(void)
 {
+    DL_LOCKED;
     if (!g_arm.started) return DL_ERR_STATE;
     {
         const int rc = dl_standby_leave();
@@ -437,16 +444,22 @@ int dl_prelaunch_stop(void)
     return DL_OK;
 }
 
-uint64_t dl_last_ticket(void) { return g_arm.seq; }
+uint64_t dl_last_ticket(void)
+{
+    DL_LOCKED;
+    return g_arm.started && t_dl_last.session == g_arm.session ? t_dl_last.ticket : 0;
+}
 
 int dl_set_trace(int on)
 {
+    DL_LOCKED;
     g_dl.trace = on ? 1 : 0;
     return DL_OK;
 }
 
 int dl_get_trace(uint64_t ticket, dl_trace *out)
 {
+    DL_LOCKED;
     if (!g_arm.started) return DL_ERR_STATE;
     if (!out || ticket == 0 || ticket > g_arm.seq || ticket + SLOTS <= g_arm.seq) return DL_ERR_INVALID;
     const uint64_t *t = g_arm.host->trace[ticket % SLOTS];
@@ -473,6 +486,7 @@ __global__ void dl_clock_ping_kernel(uint64_t *ping, uint32_t rounds, uint64_t l
 
 int dl_trace_clock(double *ticks_per_us, double *host_ns_at_tick0)
 {
+    DL_LOCKED;
     if (!g_arm.started) return DL_ERR_STATE;
     if (!ticks_per_us || !host_ns_at_tick0) return DL_ERR_INVALID;
     constexpr uint32_t ROUNDS = 32;
@@ -512,27 +526,43 @@ int dl_trace_clock(double *ticks_per_us, double *host_ns_at_tick0)
 
 int dl_trigger(uint64_t ticket)
 {
+    DL_LOCKED;
     if (!g_arm.started) return DL_ERR_STATE;
     if (ticket == 0 || ticket > g_arm.seq) return DL_ERR_INVALID;
     if (ticket > g_arm.host->bell) bell_store(&g_arm.host->bell, g_bell_dev, ticket);  // the doorbell
     return DL_OK;
 }
 
+// The two waits look their words up under the lock and spin without it, so that another thread can issue
+// and trigger requests meanwhile.  (The words live until dl_prelaunch_stop, which must not run beside a wait.)
 int dl_wait_armed(uint64_t ticket, uint64_t timeout_ns)
 {
-    if (!g_arm.started) return DL_ERR_STATE;
-    if (ticket == 0 || ticket > g_arm.seq) return DL_ERR_INVALID;
-    return wait_word(&g_arm.host->armed[ticket % SLOTS], ticket, timeout_ns, nullptr);
+    const uint64_t *word;
+    {
+        DL_LOCKED;
+        if (!g_arm.started) return DL_ERR_STATE;
+        if (ticket == 0 || ticket > g_arm.seq) return DL_ERR_INVALID;
+        word = &g_arm.host->armed[ticket % SLOTS];
+    }
+    return wait_word(word, ticket, timeout_ns, nullptr);
 }
 
 int dl_wait(uint64_t ticket, uint64_t timeout_ns)
 {
-    if (!g_arm.started) return DL_ERR_STATE;
-    if (ticket == 0) return DL_OK;
-    if (ticket > g_arm.seq) return DL_ERR_INVALID;
-    if (g_arm.seq - ticket >= SLOTS) return DL_OK;  // its slot has been reused since, which waited for it
+    const uint64_t *words;
+    uint32_t count;
+    {
+        DL_LOCKED;
+        if (!g_arm.started) return DL_ERR_STATE;
+        if (ticket == 0) return DL_OK;
+        if (ticket > g_arm.seq) return DL_ERR_INVALID;
+        if (g_arm.seq - ticket >= SLOTS) return DL_OK;  // its slot has been reused since, which waited for it
+        const uint32_t slot = (uint32_t)(ticket % SLOTS);
+        words = g_arm.host->done[slot];
+        count = g_arm.words[slot] ? g_arm.words[slot] : 1u;
+    }
     uint64_t seen = 0;
-    const int rc = wait_done(ticket, timeout_ns, &seen);
+    const int rc = wait_words(words, count, ticket, timeout_ns, &seen);
     if (rc != DL_OK) return rc;
     return seen & DL_DONE_SKIPPED ? DL_ERR_EXPIRED : DL_OK;
 }

@@ -46,6 +46,7 @@ int dl_static_init(int device)
 
 extern "C" int dl_batch_copy_static(const dl_copy_desc *desc, size_t n, void *stream)
 {
+    DL_LOCKED;  // a mutex, not an allocation: calls of several threads on one stream stay whole
     if (!g_dl.inited) return DL_ERR_STATE;
     if (dl_device_error_pending()) return DL_ERR_LOST;
     if (n && !desc) return DL_ERR_INVALID;
