@@ -37,7 +37,7 @@ DL_MODE_AUTO = 4
 DL_OP_BATCH, DL_OP_BROADCAST, DL_OP_ALLGATHER, DL_OP_ALLTOALL, DL_OP_SWAP, DL_OP_TOKEN_DISPATCH = range(6)
 DL_AUTO_STANDBY_TILES = 64
 DL_AUTO_SIGNAL_MAX_BYTES = 288 << 20
-DL_AUTO_PRELAUNCH_MAX_BYTES = 144 << 20
+DL_AUTO_PRELAUNCH_MAX_BYTES = 288 << 20
 
 # every symbol include/dmalatte.h declares
 EXPORTS = [
@@ -88,6 +88,7 @@ class Config(ctypes.Structure):
         ("table_push", ctypes.c_uint32),
         ("write_through_max_bytes", ctypes.c_uint64),
         ("stream_plain_min_bytes", ctypes.c_uint64),
+        ("armed_chain_min_bytes", ctypes.c_uint64),
     ]
 
 

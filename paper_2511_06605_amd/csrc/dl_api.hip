@@ -463,6 +463,7 @@ int dl_init(int device)
     g_dl.cfg = dl_config{};
     g_dl.cfg.nontemporal_min_bytes = ~0ull;  // streaming hints measured slower: off unless asked for
     g_dl.cfg.write_through_max_bytes = 144ull << 20;  // all-gather of 2 MiB per rank over 8 ranks
+    g_dl.cfg.armed_chain_min_bytes = 256ull << 20;    // what the Infinity Cache holds; all-gather: from 4 MiB per rank over 8 ranks
     g_dl.cfg.stream_plain_min_bytes = 512ull << 20;   // twice the Infinity Cache: all-to-all of 4 MiB chunks between 8 ranks
     g_dl.cfg.arm_timeout_us = 20000;
     g_dl.cfg.fuse_broadcast = 1;

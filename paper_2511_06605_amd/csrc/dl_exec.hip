@@ -140,6 +140,19 @@ __device__ __forceinline__ void dl_arm_housekeeping(const dl_arm &a)
 // if the request was cancelled or the limit ran out.  Uniform over the workgroup.
 __device__ __forceinline__ uint32_t dl_arm_wait(const dl_arm &a)
 {
+    __shared__ uint32_t s_go;
+    if (a.nowait && a.gated) {
+        // uniform over the grid: the waiting was done by the gate kernel that ran before this one on the stream
+        // (see dl_arm_gate_kernel); what it decided lies in the slot's first flag
+        if (threadIdx.x == 0) {
+            const uint64_t g = __hip_atomic_load(a.go, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            s_go = (g >> 2) == a.ticket ? (uint32_t)(g & 3u) : (uint32_t)DL_GO_SKIP;
+            if (a.trace_host && blockIdx.x == 0 && s_go == DL_GO_RUN)
+                __hip_atomic_store(a.trace_host + 1, (uint64_t)wall_clock64(), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
+        __syncthreads();
+        return s_go;
+    }
     if (a.nowait) {  // uniform over the grid: started without a doorbell; housekeeping follows the copy
         if (blockIdx.x == 0 && threadIdx.x == 0) {
             if (a.trace_host) {
@@ -150,7 +163,6 @@ __device__ __forceinline__ uint32_t dl_arm_wait(const dl_arm &a)
         }
         return DL_GO_RUN;
     }
-    __shared__ uint32_t s_go;
     if (threadIdx.x == 0) {
         uint32_t go = DL_GO_SKIP;
         const uint64_t t0 = wall_clock64();
@@ -266,6 +278,19 @@ __device__ __forceinline__ void dl_arm_finish(const dl_arm &a, uint32_t go)
         __hip_atomic_store(a.done, a.ticket | (skipped ? DL_DONE_SKIPPED : 0ull), __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_SYSTEM);
     }
+}
+
+// Gate of a large prelaunched request.  A grid that waits for a doorbell must stay small (see armed_grid), and a
+// small grid is what bounds a large copy.  So the waiting is done by this kernel, one workgroup, and the copy by
+// an ordinary signal-style kernel with a full grid that is enqueued behind it on the same stream: it starts when
+// this one ends, reads what this one decided, and copies or reports that the request gave up.  One more kernel
+// start (0.5-1.5 us measured) on the critical path, which pays from about 256 MiB moved; and while the request waits it
+// holds one workgroup instead of one on every other compute unit.
+__global__ void __launch_bounds__(64) dl_arm_gate_kernel(const dl_arm a)
+{
+    const uint32_t go = dl_arm_wait(a);
+    if (threadIdx.x == 0)
+        __hip_atomic_store(a.go, (a.ticket << 2) | (uint64_t)go, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 template <class Item, int NMAX, bool ROWS>
@@ -547,6 +572,20 @@ uint32_t armed_grid(uint64_t tiles, uint32_t block_threads, bool waits)
     return (uint32_t)(tiles < cap ? tiles : cap);
 }
 
+// Enqueue the gate of a chained request and turn `a` into what the copy kernel behind it gets.
+int launch_gate(dl_arm &a, hipStream_t stream)
+{
+    dl_arm gate = a;
+    gate.direct = 1;  // one workgroup: it polls the doorbell itself wherever that lies
+    gate.own_word = 0;
+    gate.gated = 0;
+    hipLaunchKernelGGL(dl_arm_gate_kernel, dim3(1), dim3(64), 0, stream, gate);
+    DL_HIP(hipGetLastError());
+    a.nowait = 1;
+    a.gated = 1;
+    return DL_OK;
+}
+
 template <class Item, int NMAX>
 int launch_klist(const Item *items, size_t n, const uint64_t *tile_end, const dl_launch_shape &sh, hipStream_t stream,
                  const dl_arm *arm)
@@ -567,6 +606,10 @@ int launch_klist(const Item *items, size_t n, const uint64_t *tile_end, const dl
     const uint32_t grid = (uint32_t)tile_end[n - 1];
     if (arm) {
         dl_arm a = *arm;
+        if (sh.chain && !a.nowait) {
+            const int rc = launch_gate(a, stream);
+            if (rc != DL_OK) return rc;
+        }
         const uint32_t g = armed_grid(grid, sh.block_threads, !a.nowait);
         a.direct = g <= a.direct_max ? 1u : 0u;
         a.own_word = g <= DL_DONE_WORDS && !a.trace_host ? 1u : 0u;  // the stamps come from the last arriver
@@ -887,6 +930,10 @@ int launch_table(const Item *items, size_t n, dl_launch_shape sh, hipStream_t st
         const dl_pushed ps = dl_push_kernel_args(stamp);
         if (arm) {
             dl_arm a = *arm;
+            if (sh.chain && !a.nowait) {
+                const int rc = launch_gate(a, stream);
+                if (rc != DL_OK) return rc;
+            }
             const uint32_t g = armed_grid(m, sh.block_threads, !a.nowait);
             a.direct = g <= a.direct_max ? 1u : 0u;
             a.own_word = g <= DL_DONE_WORDS && !a.trace_host ? 1u : 0u;
@@ -898,7 +945,8 @@ int launch_table(const Item *items, size_t n, dl_launch_shape sh, hipStream_t st
                 hipLaunchKernelGGL((dl_armed_table_kernel<Item, false>), dim3(g), dim3(sh.block_threads), 0, stream, slot,
                                    (uint32_t)m, sh.tile_bytes, sh.split, ps, a);
             // whoever wants this memory next must not wait for a request that nobody has triggered
-            if (!a.nowait) {
+            // (arm->nowait: a chained request's copy kernel does not wait itself, but its gate does)
+            if (!arm->nowait) {
                 if (pushed)
                     pushed_armed_ticket = a.ticket;
                 else
@@ -942,6 +990,13 @@ int exec_list(const Item *items, size_t n, hipStream_t stream, const dl_arm *arm
     }
     if (total == 0) return DL_OK;
     dl_launch_shape sh = dl_choose_shape(total, biggest, kmax);
+    if (arm && !arm->nowait && g_dl.cfg.armed_blocks == 0) {
+        // prelaunch mode, and the caller has not fixed the waiting grid: large requests wait in a gate kernel
+        uint64_t moved = 0;
+        for (size_t i = 0; i < n; ++i)
+            moved += items[i].bytes * (std::is_same<Item, dl_swap_item>::value ? 4ull : 1ull + item_k(items[i]));
+        sh.chain = moved > g_dl.cfg.armed_chain_min_bytes;
+    }
     if (arm && g_dl.cfg.tile_bytes == 0 && g_dl.cfg.block_threads == 0) {
         // armed kernels pay per workgroup for the doorbell fan-out and the arrival count:
         // four wavefronts per workgroup, each still moving 1 KiB rows

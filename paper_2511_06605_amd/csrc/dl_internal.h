@@ -57,6 +57,7 @@ struct dl_launch_shape {
     uint32_t max_blocks;  // 0 = one workgroup per tile
     int policy;           // cache policy of the copy loop (DL_POL_*)
     bool rows = false;    // the list qualifies for the row path of the list kernels
+    bool chain = false;   // prelaunch mode, a large request: a one-workgroup gate kernel waits, the copy kernel follows it on the stream
     uint32_t rows2d_width = 0;  // row path on a two-dimensional grid (item by item), this many tiles wide; 0: one-dimensional
 };
 
@@ -83,6 +84,9 @@ struct dl_arm {
     // (done[blockIdx.x]) as soon as its stores have drained: no arrival count on the way to the host, which
     // waits for all of the grid's words.  0: arrivals are counted and the last workgroup writes done[0].
     uint32_t own_word;
+    // 1 (with nowait): the kernel runs behind a gate kernel on the same stream, which did the waiting with a single
+    // workgroup and left (ticket << 2 | go) in go[0]; this kernel copies only if that says "run" for its ticket.
+    uint32_t gated;
     // Phase stamps (device wall-clock ticks), null unless tracing is on: host-coherent, 4 words: doorbell seen,
     // first copy begins (the polling workgroup's), last copy ends (the last arriver's), completion issued
     uint64_t *trace_host;

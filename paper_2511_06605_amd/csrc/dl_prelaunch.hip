@@ -172,6 +172,7 @@ int dl_armed_begin(dl_arm *arm, hipStream_t *stream)
     arm->direct_max = g_bell_dev ? DL_ARM_DIRECT_MAX_DEVICE : DL_ARM_DIRECT_MAX_HOST;
     arm->done = g_arm.host->done[slot];
     arm->own_word = 0;
+    arm->gated = 0;
     arm->armed = &g_arm.host->armed[slot];
     arm->go = (uint64_t *)g_arm.dev->go[slot];
     const uint32_t set = (uint32_t)(ticket / SLOTS) & 1u;

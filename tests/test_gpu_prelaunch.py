@@ -637,3 +637,107 @@ def test_lifecycle_errors():
     finally:
         dl.dl_prelaunch_stop()
     assert dl.dl_get_mode() == dl.DL_MODE_ONESHOT
+
+
+# ------------------------------------------ large armed requests: a gate kernel waits, the copy kernel follows
+
+def test_large_armed_request_sources_written_after_arming(ref, armed):
+    """4 MiB per rank (288 MiB moved: above the 256 MiB from which a one-workgroup gate kernel does the waiting and a
+    full-grid copy kernel follows it on the stream).  Armed first, sources produced afterwards on another stream,
+    then the doorbell; twice over the same buffers with new contents."""
+    import torch
+    W, B = 8, 4 * MiB
+    d_in = [DevBuf(B) for _ in range(W)]
+    d_out = [DevBuf(W * B) for _ in range(W)]
+    up = torch.cuda.Stream()
+    for rnd in range(2):
+        dl.dl_allgather([b.ptr() for b in d_in], [b.ptr() for b in d_out], B)
+        dl.dl_wait_armed()
+        ins = inputs.allgather_inputs(W, B, seed=300 + rnd, kind="bf16")
+        with torch.cuda.stream(up):
+            for r in range(W):
+                d_in[r].view().copy_(torch.from_numpy(ins[r]))
+        up.synchronize()
+        fire()
+        want = ref.allgather(ins)
+        for r in range(W):
+            assert np.array_equal(d_out[r].host(), want[r]) and d_out[r].guards_intact(), f"round {rnd} rank {r}"
+
+
+@pytest.mark.parametrize("what", ["misaligned", "long_list", "swap"])
+def test_large_armed_requests_of_other_kinds(ref, armed, what):
+    """The gate in front of the general path (addresses that disagree modulo 16), of a table kernel (300 copies of
+    512 KiB) and of swaps (an in-place all-to-all of 12 MiB chunks between four ranks); each moves 280 MiB or more."""
+    if what == "misaligned":
+        W, B = 4, 14 * MiB + 5
+        ins = inputs.allgather_inputs(W, B, seed=41)
+        d_in = [DevBuf(B, fill=ins[r], shift=r + 1) for r in range(W)]
+        d_out = [DevBuf(W * B, shift=2 * r) for r in range(W)]
+        sync()
+        dl.dl_allgather([b.ptr() for b in d_in], [b.ptr() for b in d_out], B)
+        fire()
+        for got, want in zip(d_out, ref.allgather(ins)):
+            assert np.array_equal(got.host(), want) and got.guards_intact()
+    elif what == "long_list":
+        arena, descs = inputs.b2b_batch(300, 512 * KiB, 400 * MiB, seed=42, align=4096)
+        want = ref.batch_copy([arena.copy()], [(0, s, 0, t, m) for s, t, m in descs])[0]
+        d = DevBuf(arena.size, fill=arena)
+        sync()
+        dl.dl_batch_copy([(d.ptr(int(s)), d.ptr(int(t)), int(m)) for s, t, m in descs])
+        fire()
+        assert np.array_equal(d.host(), want) and d.guards_intact()
+    else:
+        W, c = 4, 12 * MiB
+        bufs = inputs.alltoall_inputs(inputs.uniform_chunks(W, c), seed=43)
+        d_buf = [DevBuf(a.size, fill=a) for a in bufs]
+        sync()
+        dl.dl_alltoall_inplace([b.ptr() for b in d_buf], c)
+        fire()
+        for b, w in zip(d_buf, ref.alltoall_inplace(bufs, c)):
+            assert np.array_equal(b.host(), w) and b.guards_intact()
+
+
+def test_large_untriggered_request_expires_and_copies_nothing(ref):
+    """The gate kernel gives up at the arm limit; the copy kernel behind it reads that and reports the request as
+    expired without touching a byte.  A request that follows works."""
+    dl.dl_set_config(arm_timeout_us=3000)
+    try:
+        dl.dl_prelaunch_start()
+        dl.dl_set_mode(dl.DL_MODE_PRELAUNCH)
+        n = 32 * MiB                                      # 1 + 8 destinations: 288 MiB moved
+        src = DevBuf(n, fill=inputs.payload(np.random.default_rng(1), n))
+        dst = [DevBuf(n) for _ in range(8)]
+        sync()
+        dl.dl_broadcast(src.ptr(), [b.ptr() for b in dst], n)
+        with pytest.raises(dl.DlError) as e:
+            dl.dl_wait()                                  # never triggered
+        assert e.value.status == dl.DL_ERR_EXPIRED
+        for b in dst:
+            assert (b.host() == CANARY).all()
+        dl.dl_trigger()                                   # a late doorbell does nothing
+        dl.dl_set_config(arm_timeout_us=ARM_US)
+        dl.dl_broadcast(src.ptr(), [b.ptr() for b in dst], n)
+        fire()
+        for b in dst:
+            assert np.array_equal(b.host(), src.host()) and b.guards_intact()
+    finally:
+        dl.dl_set_mode(dl.DL_MODE_ONESHOT)
+        dl.dl_prelaunch_stop()
+        dl.dl_set_config(arm_timeout_us=ARM_US)
+
+
+def test_stop_cancels_a_large_armed_request(ref):
+    import time
+    dl.dl_prelaunch_start()
+    dl.dl_set_mode(dl.DL_MODE_PRELAUNCH)
+    n = 160 * MiB
+    src = DevBuf(n, fill=inputs.payload(np.random.default_rng(2), n))
+    dst = DevBuf(n)
+    sync()
+    dl.dl_broadcast(src.ptr(), [dst.ptr()], n)
+    dl.dl_wait_armed()
+    t0 = time.perf_counter()
+    dl.dl_set_mode(dl.DL_MODE_ONESHOT)
+    dl.dl_prelaunch_stop()                       # cancels: well before the 300 ms arm limit
+    assert time.perf_counter() - t0 < 0.2
+    assert (dst.host() == CANARY).all()

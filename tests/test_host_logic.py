@@ -58,7 +58,7 @@ def test_header_is_plain_c(tmp_path):
                    "typedef void (*fn)(void);\n"
                    "fn table[] = {" + ", ".join(f"(fn){n}" for n in names) + "};\n"
                    "int main(void) { return sizeof(dl_plan_item) == 88 && sizeof(dl_copy_desc) == 24 && "
-                   "sizeof(dl_config) == 64 && sizeof(table) > 0 ? 0 : 1; }\n")
+                   "sizeof(dl_config) == 72 && sizeof(table) > 0 ? 0 : 1; }\n")
     inc = os.path.join(ROOT, "include")
     subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I" + inc, "-fsyntax-only", str(src)],
                    check=True)
@@ -73,7 +73,7 @@ def test_binding_structs_have_the_layout_of_the_header():
     assert ctypes.sizeof(binding.PlanItem) == 88 and binding.PlanItem.dst.offset == 24
     assert ctypes.sizeof(binding.CopyDesc) == 24 and ctypes.sizeof(binding.SwapDesc) == 24
     assert ctypes.sizeof(binding.Trace) == 32
-    assert ctypes.sizeof(binding.Config) == 64 and binding.Config.write_through_max_bytes.offset == 48
+    assert ctypes.sizeof(binding.Config) == 72 and binding.Config.write_through_max_bytes.offset == 48
     assert binding.Config.stream_plain_min_bytes.offset == 56
     header = open(os.path.join(ROOT, "include", "dmalatte.h")).read()
     body = header[header.index("typedef struct dl_config {"):header.index("} dl_config;")]
@@ -501,7 +501,7 @@ def test_mode_table_applied_to_the_lowered_collectives():
     assert [ag_mode(B, False) for B in (4096, 64 * 1024, 64 * 1024 + 16, 1 << 20, 4 << 20, (4 << 20) + 16, 64 << 20)] == \
         [dl.DL_MODE_STANDBY, dl.DL_MODE_STANDBY, dl.DL_MODE_SIGNAL, dl.DL_MODE_SIGNAL, dl.DL_MODE_SIGNAL,
          dl.DL_MODE_ONESHOT, dl.DL_MODE_ONESHOT]
-    assert [ag_mode(B, True) for B in (4096, 2 << 20, (2 << 20) + 16, 64 << 20)] == \
+    assert [ag_mode(B, True) for B in (4096, 4 << 20, (4 << 20) + 16, 64 << 20)] == \
         [dl.DL_MODE_PRELAUNCH, dl.DL_MODE_PRELAUNCH, dl.DL_MODE_ONESHOT, dl.DL_MODE_ONESHOT]
 
     def aa_mode(c):
