@@ -251,6 +251,20 @@ def other_operations(dl, benchaid, inputs, torch, stream, ag_reqs, ag_bufs, ag_s
         req = benchaid.alltoall_request(d_in, d_out, C)
         row = {"chunk_bytes": c}
         row.update(timed(req, 2 * W * W * c, c <= 128 * KiB))
+        if 64 * KiB <= c:
+            # cold: buffer sets of this size rotated so that a pass moves 1 GiB
+            sets = max(3, min(48, -(-(1 << 30) // (2 * W * W * c))))
+            spare, ring = [], [req]
+            for _ in range(sets - 1):
+                e_in = [torch.empty(W * c, dtype=torch.uint8, device="cuda").random_(0, 256) for _ in range(W)]
+                e_out = [torch.empty(W * c, dtype=torch.uint8, device="cuda") for _ in range(W)]
+                spare.append((e_in, e_out))
+                ring.append(benchaid.alltoall_request(e_in, e_out, C))
+            stream.synchronize()
+            us = benchaid.time_device_rotating(ring, stream, 1, 3)
+            row["cold"] = {"buffer_sets": sets, "device_us": us, "GBps": 2 * W * W * c / us / 1e3,
+                           "frac_of_hbm_peak": 2 * W * W * c / us / 1e3 / HBM_PEAK_GBS}
+            del spare, ring
         rows.append(row)
         if c <= 128 * KiB:
             armed_cases.append((row, req, (d_in, d_out)))
@@ -812,6 +826,9 @@ def main() -> int:
             "standby_call_to_done_p50": round(small["standby_call_to_done_us"]["p50"], 2),
         }
         # fraction of HBM peak per sweep point from 1 MiB per rank, cold caches where measured
+        out["alltoall_frac_of_hbm_peak_by_MiB_per_pair"] = {
+            str(r_["chunk_bytes"] // MiB): round(r_["cold"]["frac_of_hbm_peak"], 3)
+            for r_ in detail["alltoall_uniform"] if r_["chunk_bytes"] >= MiB and "cold" in r_}
         out["frac_of_hbm_peak_by_MiB_per_rank"] = {
             str(r_["bytes_per_rank"] // MiB): round((r_["cold"]["GBps"] if "cold" in r_ else r_["GBps"]) / HBM_PEAK_GBS, 3)
             for r_ in detail["allgather"] if r_["bytes_per_rank"] >= MiB}
