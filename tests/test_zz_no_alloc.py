@@ -67,3 +67,28 @@ def test_static_entry_point_large_copies_and_limits(ref):
     dl.dl_batch_copy_static([(d_src.ptr(0), d_dst.ptr(0), 0)], stream())
     sync()
     assert got[n] == 0
+
+
+def test_static_entry_point_replays_from_a_graph(ref):
+    """What the entry point is for: a long list (500 copies: a table on the device) issued on a stream that is
+    being captured.  Only kernel launches are recorded (the fills of the static table and the table kernel), so
+    the graph can be replayed with new bytes in the arena; every replay is compared with the CPU checker, with
+    eager work and synchronisations in between."""
+    import torch
+    arena, descs = inputs.b2b_batch(500, 3000, 8 * MiB, seed=21, align=16)
+    d = DevBuf(arena.size, fill=arena)
+    dlist = [(d.ptr(int(s)), d.ptr(int(t)), int(m)) for s, t, m in descs]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        dl.dl_batch_copy_static(dlist, torch.cuda.current_stream())
+    rng = np.random.default_rng(22)
+    for replay in range(4):
+        fresh = rng.integers(0, 256, arena.size, dtype=np.uint8)
+        d.view().copy_(torch.from_numpy(fresh))
+        sync()
+        g.replay()
+        torch.cuda.synchronize()
+        want = ref.batch_copy([fresh.copy()], [(0, s, 0, t, m) for s, t, m in descs])[0]
+        assert np.array_equal(d.host(), want) and d.guards_intact(), f"replay {replay}"
