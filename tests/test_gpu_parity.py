@@ -759,6 +759,16 @@ def test_validation_rejects_hazards_and_enqueues_nothing():
 
 # ----------------------------------- failure reports from the device; table memory after a stream has gone
 
+def lib_error_pending():
+    """Whether a loss has been reported, without clearing the report: an empty request is refused while it is."""
+    try:
+        dl.dl_batch_copy_static([(1 << 20, 2 << 20, 0)], stream())   # moves nothing, enqueues nothing
+    except dl.DlError as e:
+        assert e.status == dl.DL_ERR_LOST
+        return True
+    return False
+
+
 def _lose_next_table():
     """Arm the test hook, or skip where no table goes through the BAR."""
     try:
@@ -778,7 +788,7 @@ def test_a_table_that_never_completes_is_reported_and_nothing_is_copied(ref, kin
     assert dl.dl_last_device_error() == dl.DL_OK
     W = 8
     if kind == "token_dispatch":
-        counts, row = [96] * W, 512
+        counts, row = [80] * W, 512      # 640 tokens: lowered on the device, and on the host still one table slot
         ins = inputs.token_rows(W, counts, row, seed=5, kind="u8")
         dest = inputs.moe_token_destinations(W, counts, seed=6, n_experts=256, top_k=8)
         want = ref.token_dispatch(ins, row, dest)
@@ -800,8 +810,13 @@ def test_a_table_that_never_completes_is_reported_and_nothing_is_copied(ref, kin
             dl.dl_batch_copy([(d.ptr(int(s)), d.ptr(int(t)), int(m)) for s, t, m in descs], stream())
 
     _lose_next_table()
-    issue()
+    try:
+        issue()
+    finally:
+        dl.dl_debug_lose_next_table(0)    # taken back if no table took it
     sync()
+    if os.environ.get("DL_TEST_CONFIG") and not lib_error_pending():
+        pytest.skip("with these forced tunables the request's table does not go through the BAR")
     with pytest.raises(dl.DlError) as refused:
         issue()
     assert refused.value.status == dl.DL_ERR_LOST
