@@ -441,6 +441,13 @@ typedef struct dl_config {
 int dl_get_config(dl_config *cfg);
 int dl_set_config(const dl_config *cfg);
 
+/* Host-only: apply "name=value,name=value" (names as in dl_config, values as
+ * C integer literals) to *cfg.  Unknown names, malformed values and settings
+ * that dl_set_config would refuse return DL_ERR_INVALID and leave *cfg as it
+ * was.  dl_init() applies the environment variable DL_CONFIG this way on top
+ * of the defaults (and fails with DL_ERR_INVALID if it does not parse). */
+int dl_parse_config(const char *text, dl_config *cfg);
+
 /* -------------------------------------------------- lowering, for inspection */
 
 /* One lowered copy: read `bytes` at src once, write them to k destinations. */

@@ -17,4 +17,4 @@ from .binding import (  # noqa: F401
     dl_plan_alltoall_inplace, dl_plan_swap_first_hazard, dl_batch_fanout, dl_token_dispatch,
     dl_plan_token_dispatch, dl_plan_batch_inferred, dl_set_trace, dl_get_trace, dl_trace_clock,
     dl_last_device_error, dl_debug_lose_next_table, dl_batch_copy_static, dl_plan_mode, dl_last_mode,
-    dl_complete)
+    dl_complete, dl_parse_config)

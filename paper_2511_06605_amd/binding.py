@@ -15,7 +15,9 @@ import ctypes
 import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libdmalatte.so")
+# DL_LIBRARY names another build of the same library (the host-sanitizer build of the tests); there is still no
+# fallback: whatever it names must exist.
+LIB_PATH = os.environ.get("DL_LIBRARY") or os.path.join(_HERE, "libdmalatte.so")
 
 DL_OK = 0
 DL_ERR_INVALID = -1
@@ -50,7 +52,7 @@ EXPORTS = [
     "dl_plan_swap_first_hazard", "dl_batch_fanout", "dl_token_dispatch", "dl_plan_token_dispatch",
     "dl_plan_batch_inferred", "dl_set_trace", "dl_get_trace", "dl_trace_clock",
     "dl_last_device_error", "dl_debug_lose_next_table", "dl_batch_copy_static",
-    "dl_plan_mode", "dl_last_mode", "dl_complete",
+    "dl_plan_mode", "dl_last_mode", "dl_complete", "dl_parse_config",
 ]
 
 
@@ -150,6 +152,7 @@ def lib() -> ctypes.CDLL:
         "dl_wait_armed": (ctypes.c_int, [ctypes.c_uint64, ctypes.c_uint64]),
         "dl_get_config": (ctypes.c_int, [ctypes.POINTER(Config)]),
         "dl_set_config": (ctypes.c_int, [ctypes.POINTER(Config)]),
+        "dl_parse_config": (ctypes.c_int, [ctypes.c_char_p, ctypes.POINTER(Config)]),
         "dl_plan_allgather": (ctypes.c_long, [vpp, vpp, ctypes.c_int, ctypes.c_size_t, ctypes.c_int,
                                               ctypes.POINTER(PlanItem), ctypes.c_size_t]),
         "dl_plan_alltoall": (ctypes.c_long, [vpp, vpp, ctypes.c_int, szp, ctypes.POINTER(PlanItem), ctypes.c_size_t]),
@@ -290,6 +293,13 @@ def dl_set_validate(on: bool) -> None:
 def dl_get_config() -> Config:
     c = Config()
     _check(lib().dl_get_config(ctypes.byref(c)), "dl_get_config")
+    return c
+
+
+def dl_parse_config(text: str, cfg: Config | None = None) -> Config:
+    """``text`` ("name=value,...") applied to ``cfg`` (or to an all-zero one with arm_timeout_us = 1); host-only."""
+    c = cfg or Config(arm_timeout_us=1)
+    _check(lib().dl_parse_config(text.encode(), ctypes.byref(c)), "dl_parse_config")
     return c
 
 

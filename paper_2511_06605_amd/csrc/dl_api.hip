@@ -3,6 +3,7 @@
 // and dispatch to the one-shot or the armed (prelaunched) launcher.
 #include "dl_internal.h"
 
+#include <stdlib.h>
 #include <string.h>
 
 #include <algorithm>
@@ -445,9 +446,44 @@ int lower_and_execute(Fn fn, void *stream, int op)
     return DL_ERR_INVALID;
 }
 
+bool config_valid(const dl_config &cfg)
+{
+    const uint32_t t = cfg.tile_bytes, b = cfg.block_threads;
+    if (t && (t < 1024 || (t & (t - 1)) || t > (1u << 24))) return false;
+    if (b && b != 64 && b != 128 && b != 256 && b != 512) return false;
+    if (cfg.arm_timeout_us < 1 || cfg.arm_timeout_us > 1000000) return false;
+    const uint32_t fs = cfg.fan_split;
+    return fs == 0 || fs == 1 || fs == 2 || fs == 4;
+}
+
+// The tunables by name, for dl_parse_config (and so for the DL_CONFIG environment variable).
+struct config_field {
+    const char *name;
+    uint32_t dl_config::*p32;
+    uint64_t dl_config::*p64;
+};
+const config_field CONFIG_FIELDS[] = {
+    {"tile_bytes", &dl_config::tile_bytes, nullptr},
+    {"block_threads", &dl_config::block_threads, nullptr},
+    {"nontemporal_min_bytes", nullptr, &dl_config::nontemporal_min_bytes},
+    {"armed_blocks", &dl_config::armed_blocks, nullptr},
+    {"arm_timeout_us", &dl_config::arm_timeout_us, nullptr},
+    {"fuse_broadcast", &dl_config::fuse_broadcast, nullptr},
+    {"max_blocks", &dl_config::max_blocks, nullptr},
+    {"fan_split", &dl_config::fan_split, nullptr},
+    {"infer_broadcast", &dl_config::infer_broadcast, nullptr},
+    {"device_lowering", &dl_config::device_lowering, nullptr},
+    {"table_push", &dl_config::table_push, nullptr},
+    {"write_through_max_bytes", nullptr, &dl_config::write_through_max_bytes},
+    {"stream_plain_min_bytes", nullptr, &dl_config::stream_plain_min_bytes},
+    {"armed_chain_min_bytes", nullptr, &dl_config::armed_chain_min_bytes},
+};
+
 }  // namespace
 
 extern "C" {
+
+int dl_parse_config(const char *text, dl_config *cfg);
 
 int dl_init(int device)
 {
@@ -470,6 +506,8 @@ int dl_init(int device)
     g_dl.cfg.infer_broadcast = 1;
     g_dl.cfg.device_lowering = 1;
     g_dl.cfg.table_push = 1;
+    // defaults first, then what the environment asks for (DL_CONFIG="fan_split=2,table_push=0")
+    if (dl_parse_config(getenv("DL_CONFIG"), &g_dl.cfg) != DL_OK) return DL_ERR_INVALID;
     int rc = dl_exec_init();
     if (rc == DL_OK) rc = dl_static_init(device);
     if (rc != DL_OK) return rc;
@@ -574,14 +612,42 @@ int dl_get_config(dl_config *cfg)
 int dl_set_config(const dl_config *cfg)
 {
     DL_LOCKED;
-    if (!cfg) return DL_ERR_INVALID;
-    const uint32_t t = cfg->tile_bytes, b = cfg->block_threads;
-    if (t && (t < 1024 || (t & (t - 1)) || t > (1u << 24))) return DL_ERR_INVALID;
-    if (b && b != 64 && b != 128 && b != 256 && b != 512) return DL_ERR_INVALID;
-    if (cfg->arm_timeout_us < 1 || cfg->arm_timeout_us > 1000000) return DL_ERR_INVALID;
-    const uint32_t fs = cfg->fan_split;
-    if (fs != 0 && fs != 1 && fs != 2 && fs != 4) return DL_ERR_INVALID;
+    if (!cfg || !config_valid(*cfg)) return DL_ERR_INVALID;
     g_dl.cfg = *cfg;
+    return DL_OK;
+}
+
+int dl_parse_config(const char *text, dl_config *cfg)
+{
+    if (!cfg) return DL_ERR_INVALID;
+    if (!text) return DL_OK;
+    dl_config c = *cfg;
+    const char *p = text;
+    while (*p) {
+        while (*p == ',' || *p == ' ') ++p;
+        if (!*p) break;
+        const char *eq = strchr(p, '=');
+        if (!eq || eq == p) return DL_ERR_INVALID;
+        char *end = nullptr;
+        const unsigned long long v = strtoull(eq + 1, &end, 0);
+        if (end == eq + 1 || (*end && *end != ',' && *end != ' ')) return DL_ERR_INVALID;
+        const size_t len = (size_t)(eq - p);
+        bool known = false;
+        for (const config_field &f : CONFIG_FIELDS) {
+            if (strlen(f.name) != len || strncmp(f.name, p, len)) continue;
+            if (f.p32) {
+                if (v > 0xFFFFFFFFull) return DL_ERR_INVALID;
+                c.*(f.p32) = (uint32_t)v;
+            } else {
+                c.*(f.p64) = (uint64_t)v;
+            }
+            known = true;
+        }
+        if (!known) return DL_ERR_INVALID;
+        p = end;
+    }
+    if (!config_valid(c)) return DL_ERR_INVALID;
+    *cfg = c;
     return DL_OK;
 }
 

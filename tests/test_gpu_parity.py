@@ -875,3 +875,39 @@ def test_table_memory_is_reused_after_the_callers_stream_is_gone(ref, cfg, push)
     for r, (arena, d, descs) in enumerate(cases):
         want = ref.batch_copy([arena.copy()], [(0, s, 0, t, m) for s, t, m in descs])[0]
         assert np.array_equal(d.host(), want) and d.guards_intact(), f"request {r}"
+
+
+def test_tunables_from_the_environment(ref):
+    """DL_CONFIG is applied by dl_init on top of the defaults (a process of its own: the library of this process
+    is initialised already); a value that does not parse makes dl_init fail."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    child = (
+        "import sys, numpy as np, torch\n"
+        f"sys.path.insert(0, {root!r})\n"
+        "import paper_2511_06605_amd as dl\n"
+        "from paper_2511_06605_amd import inputs\n"
+        "from oracle import ref\n"
+        "torch.cuda.set_device(0)\n"
+        "try:\n"
+        "    dl.dl_init(0)\n"
+        "except dl.DlError as e:\n"
+        "    print('init refused', e.status); sys.exit(0)\n"
+        "c = dl.dl_get_config()\n"
+        "print('config', c.fan_split, c.table_push, c.tile_bytes, c.infer_broadcast)\n"
+        "ins = inputs.allgather_inputs(8, 50000, seed=1)\n"
+        "d_in = [torch.from_numpy(a).cuda() for a in ins]\n"
+        "d_out = [torch.zeros(8 * 50000, dtype=torch.uint8, device='cuda') for _ in range(8)]\n"
+        "dl.dl_allgather(d_in, d_out, 50000, torch.cuda.current_stream()); torch.cuda.synchronize()\n"
+        "assert all(np.array_equal(g.cpu().numpy(), w) for g, w in zip(d_out, ref.allgather(ins)))\n"
+        "dl.dl_shutdown(); print('result ok')\n")
+
+    def run(text):
+        env = dict(os.environ, DL_CONFIG=text)
+        return subprocess.run([sys.executable, "-c", child], capture_output=True, text=True, env=env, timeout=120)
+
+    r = run("fan_split=2,table_push=0")
+    assert "config 2 0 0 1" in r.stdout and "result ok" in r.stdout, r.stdout + r.stderr
+    r = run("fan_split=3")
+    assert f"init refused {dl.DL_ERR_INVALID}" in r.stdout, r.stdout + r.stderr

@@ -515,3 +515,23 @@ def test_mode_table_applied_to_the_lowered_collectives():
     items = dl.dl_plan_broadcast(base + (1 << 32), [base + (1 << 32) * (2 + d) for d in range(7)], 2 << 20)
     assert dl.dl_plan_mode(dl.DL_OP_BROADCAST, len(items), 7, 8 * (2 << 20), dl.dl_plan_tiles(items, 8192), False) == dl.DL_MODE_SIGNAL
     assert dl.dl_plan_mode(dl.DL_OP_BATCH, 64, 1, 2 * 64 * 16384, 128, False) == dl.DL_MODE_SIGNAL
+
+
+def test_config_from_text():
+    """dl_parse_config (what dl_init does with the DL_CONFIG environment variable): every tunable by name, C
+    integer literals, refusal of anything it does not understand without touching the struct."""
+    c = dl.dl_parse_config("tile_bytes=4096, block_threads=256,fan_split=2,table_push=0,write_through_max_bytes=0x100000,"
+                           "stream_plain_min_bytes=18446744073709551615,armed_chain_min_bytes=0,arm_timeout_us=500")
+    assert (c.tile_bytes, c.block_threads, c.fan_split, c.table_push) == (4096, 256, 2, 0)
+    assert c.write_through_max_bytes == 1 << 20 and c.stream_plain_min_bytes == (1 << 64) - 1
+    assert c.armed_chain_min_bytes == 0 and c.arm_timeout_us == 500
+    names = [f[0] for f in binding.Config._fields_]
+    c = dl.dl_parse_config(",".join(f"{n}={1 if n != 'tile_bytes' and n != 'block_threads' else 0}" for n in names))
+    assert all(getattr(c, n) == (0 if n in ("tile_bytes", "block_threads") else 1) for n in names)   # every field has a name
+    base = binding.Config(arm_timeout_us=7, fan_split=4)
+    for bad in ("tile_bytes=3000", "nosuch=1", "fan_split=3", "fan_split", "=4", "block_threads=abc", "tile_bytes=4096;fan_split=2",
+                "arm_timeout_us=0", "fan_split=99999999999"):
+        with pytest.raises(dl.DlError):
+            dl.dl_parse_config(bad, base)
+        assert (base.arm_timeout_us, base.fan_split, base.tile_bytes) == (7, 4, 0), bad
+    assert dl.dl_parse_config("", base).fan_split == 4
