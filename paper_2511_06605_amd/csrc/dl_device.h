@@ -313,7 +313,7 @@ __device__ __forceinline__ const DL_GLOBAL uint64_t *dl_pushed_stamp(const void 
 }
 // How often a kernel looks again if the stamp is not there at the first look (the launch overtook the writes
 // inside the device; they were on their way before it): bounded, like every wait in this library.
-constexpr uint32_t DL_PUSHED_TRIES = 1u << 22;
+constexpr uint32_t DL_PUSHED_TRIES = 1u << 18;  // a look takes about a microsecond: a quarter of a second in all
 
 // The kernel gave up on its table: say so where the host will look (any non-zero value; the stamp tells which).
 __device__ __forceinline__ void dl_pushed_report_lost(const dl_pushed &ps)
