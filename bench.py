@@ -320,6 +320,11 @@ def other_operations(dl, benchaid, inputs, torch, stream, ag_reqs, ag_bufs, ag_s
         dl.dl_set_config(device_lowering=0)
         row["host_lowered_call_to_sync_us"] = lat_stats(benchaid.time_host(req, stream, benchaid.WAIT_STREAM, 50, 200))
         dl.dl_set_config(device_lowering=1)
+        # the routing mask already in device memory (where a router kernel leaves it): nothing crosses the host link
+        d_mask = torch.from_numpy(np.ascontiguousarray(dest)).cuda()
+        dreq = benchaid.token_dispatch_device_request(d_in, d_out, [T] * W, row_bytes, d_mask)
+        row["mask_in_device_memory_call_to_sync_us"] = lat_stats(benchaid.time_host(dreq, stream, benchaid.WAIT_STREAM, 50, 200))
+        row["mask_in_device_memory_device_us"] = benchaid.time_device(dreq, stream, warmup=3, calls=20)
         rows.append(row)
     res["token_dispatch_moe"] = rows
 

@@ -12,7 +12,7 @@ from paper_2511_06605_amd import binding
 _HERE = os.path.dirname(os.path.abspath(__file__))
 AID_PATH = os.path.join(_HERE, "libdl_benchaid.so")
 
-OP_BATCH, OP_BROADCAST, OP_ALLGATHER, OP_ALLTOALL, OP_MEMCPY_ASYNC, OP_MEMCPY_BATCH, OP_SWAP, OP_ALLTOALL_INPLACE, OP_TOKEN_DISPATCH, OP_FANOUT = range(10)
+OP_BATCH, OP_BROADCAST, OP_ALLGATHER, OP_ALLTOALL, OP_MEMCPY_ASYNC, OP_MEMCPY_BATCH, OP_SWAP, OP_ALLTOALL_INPLACE, OP_TOKEN_DISPATCH, OP_FANOUT, OP_TOKEN_DISPATCH_DEVICE = range(11)
 WAIT_STREAM, WAIT_TRIGGER, WAIT_ARM_AND_TRIGGER, WAIT_SIGNAL = 0, 1, 2, 3
 
 
@@ -112,6 +112,20 @@ def token_dispatch_request(ins, outs, tokens, row_bytes, dest) -> Prepared:
     r.tokens = ctypes.cast(tok, ctypes.POINTER(ctypes.c_uint32))
     r.dest = ctypes.cast(d, ctypes.POINTER(ctypes.c_uint8))
     return Prepared(r, (a, b, tok, d))
+
+
+def token_dispatch_device_request(ins, outs, tokens, row_bytes, mask) -> Prepared:
+    """mask: device tensor of (total tokens) x W bytes."""
+    ins, outs = list(ins), list(outs)
+    W = len(ins)
+    a, b = binding._ptr_array(ins), binding._ptr_array(outs)
+    tok = (ctypes.c_uint32 * W)(*[int(t) for t in tokens])
+    r = Request(op=OP_TOKEN_DISPATCH_DEVICE, W=W, bytes=int(row_bytes))
+    r.in_ = ctypes.cast(a, ctypes.POINTER(ctypes.c_void_p))
+    r.out = ctypes.cast(b, ctypes.POINTER(ctypes.c_void_p))
+    r.tokens = ctypes.cast(tok, ctypes.POINTER(ctypes.c_uint32))
+    r.dest = ctypes.cast(ctypes.c_void_p(binding._addr(mask)), ctypes.POINTER(ctypes.c_uint8))
+    return Prepared(r, (a, b, tok, mask))
 
 
 def lowered_token_dispatch(p: Prepared, iters=20):

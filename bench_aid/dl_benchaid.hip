@@ -17,7 +17,8 @@ extern "C" {
 typedef struct dlb_request {
     int op;  // 0 batch, 1 broadcast, 2 all-gather, 3 all-to-all, 4 hipMemcpyAsync per desc, 5 hipMemcpyBatchAsync,
              // 6 batch of swaps (desc as {a, b, bytes}), 7 in-place all-to-all (out = buffers, bytes = chunk),
-             // 8 token dispatch (in, out, W, tokens, bytes = row, dest), 9 fan-out batch (desc = dl_plan_item array)
+             // 8 token dispatch (in, out, W, tokens, bytes = row, dest), 9 fan-out batch (desc = dl_plan_item array),
+             // 10 token dispatch with the mask in device memory (dest is a device pointer)
     int k;
     int W;
     int pad;
@@ -82,6 +83,7 @@ int dlb_issue(const dlb_request *r, void *stream)
     case 7: return dl_alltoall_inplace(r->out, r->W, r->bytes, stream);
     case 8: return dl_token_dispatch(r->in, r->out, r->W, r->tokens, r->bytes, r->dest, stream);
     case 9: return dl_batch_fanout((const dl_plan_item *)r->desc, r->n, stream);
+    case 10: return dl_token_dispatch_device(r->in, r->out, r->W, r->tokens, r->bytes, r->dest, stream);  // dest: device
     default: return DL_ERR_INVALID;
     }
 }

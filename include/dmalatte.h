@@ -487,6 +487,24 @@ int dl_token_dispatch(const void *const *in, void *const *out, int W, const uint
                       const uint8_t *dest, void *stream);
 
 /*
+ * dl_token_dispatch with the routing mask in DEVICE memory, where the router
+ * kernel of a mixture-of-experts layer leaves it: same layout (one byte per
+ * (token, rank), non-zero = send), same result, but dest_device is a device
+ * pointer (8-byte aligned) and nothing of the mask crosses the host link: the
+ * device counts, builds the copy list and executes it, three launches on
+ * `stream`, ordered behind whatever produced the mask there.  Always executed
+ * as in DL_MODE_ONESHOT.  The host does not learn how many rows each rank
+ * receives: out[j] must have room for what the mask sends it (at most all
+ * tokens).  Limits: exactly 8 ranks, row_bytes a multiple of 16, buffers
+ * 16-byte aligned (DL_ERR_INVALID otherwise); at most
+ * DL_DISPATCH_DEVICE_MAX_TOKENS tokens in all (one slot of the library's table
+ * memory holds their copy list; more: DL_ERR_CAPACITY, nothing is enqueued).
+ */
+#define DL_DISPATCH_DEVICE_MAX_TOKENS 10240
+int dl_token_dispatch_device(const void *const *in, void *const *out, int W, const uint32_t *tokens, size_t row_bytes,
+                             const uint8_t *dest_device, void *stream);
+
+/*
  * Host-only: lower a collective to the list of copies the device executes
  * (the analogue of building the command list, paper Sec. III-B2 "control").
  * Pointers are treated as opaque addresses and never dereferenced, so these

@@ -7,7 +7,7 @@ result on the CPU.
 """
 
 from .binding import (  # noqa: F401
-    DL_ERR_EXPIRED, DL_ERR_LOST, DL_ERR_CAPACITY, DL_STATIC_MAX_COPIES, DL_ERR_HIP, DL_ERR_INVALID, DL_ERR_OVERLAP, DL_ERR_STATE, DL_ERR_TIMEOUT, DL_MAX_FANOUT,
+    DL_ERR_EXPIRED, DL_ERR_LOST, DL_ERR_CAPACITY, DL_STATIC_MAX_COPIES, DL_DISPATCH_DEVICE_MAX_TOKENS, DL_ERR_HIP, DL_ERR_INVALID, DL_ERR_OVERLAP, DL_ERR_STATE, DL_ERR_TIMEOUT, DL_MAX_FANOUT,
     DL_MODE_ONESHOT, DL_MODE_PRELAUNCH, DL_MODE_SIGNAL, DL_MODE_STANDBY, DL_MODE_AUTO, DL_OK, DL_OP_BATCH, DL_OP_BROADCAST, DL_OP_ALLGATHER, DL_OP_ALLTOALL, DL_OP_SWAP,
     DL_OP_TOKEN_DISPATCH, DL_AUTO_STANDBY_TILES, DL_AUTO_SIGNAL_MAX_BYTES, DL_AUTO_PRELAUNCH_MAX_BYTES, DL_PLAN_FANOUT, Config, DlError, dl_allgather,
     dl_alltoall, dl_batch_copy, dl_broadcast, dl_get_config, dl_get_mode, dl_init, dl_last_ticket,
@@ -17,4 +17,4 @@ from .binding import (  # noqa: F401
     dl_plan_alltoall_inplace, dl_plan_swap_first_hazard, dl_batch_fanout, dl_token_dispatch,
     dl_plan_token_dispatch, dl_plan_batch_inferred, dl_set_trace, dl_get_trace, dl_trace_clock,
     dl_last_device_error, dl_debug_lose_next_table, dl_batch_copy_static, dl_plan_mode, dl_last_mode,
-    dl_complete, dl_parse_config)
+    dl_complete, dl_parse_config, dl_token_dispatch_device)

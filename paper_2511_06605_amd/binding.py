@@ -29,6 +29,7 @@ DL_ERR_EXPIRED = -6
 DL_ERR_LOST = -7
 DL_ERR_CAPACITY = -8
 DL_STATIC_MAX_COPIES = 16384
+DL_DISPATCH_DEVICE_MAX_TOKENS = 10240
 DL_MAX_FANOUT = 64
 DL_PLAN_FANOUT = 8
 DL_MODE_ONESHOT = 0
@@ -52,7 +53,7 @@ EXPORTS = [
     "dl_plan_swap_first_hazard", "dl_batch_fanout", "dl_token_dispatch", "dl_plan_token_dispatch",
     "dl_plan_batch_inferred", "dl_set_trace", "dl_get_trace", "dl_trace_clock",
     "dl_last_device_error", "dl_debug_lose_next_table", "dl_batch_copy_static",
-    "dl_plan_mode", "dl_last_mode", "dl_complete", "dl_parse_config",
+    "dl_plan_mode", "dl_last_mode", "dl_complete", "dl_parse_config", "dl_token_dispatch_device",
 ]
 
 
@@ -173,6 +174,8 @@ def lib() -> ctypes.CDLL:
         "dl_batch_fanout": (ctypes.c_int, [ctypes.POINTER(PlanItem), ctypes.c_size_t, vp]),
         "dl_token_dispatch": (ctypes.c_int, [vpp, vpp, ctypes.c_int, ctypes.POINTER(ctypes.c_uint32), ctypes.c_size_t,
                                              ctypes.POINTER(ctypes.c_uint8), vp]),
+        "dl_token_dispatch_device": (ctypes.c_int, [vpp, vpp, ctypes.c_int, ctypes.POINTER(ctypes.c_uint32), ctypes.c_size_t,
+                                                    vp, vp]),
         "dl_plan_token_dispatch": (ctypes.c_long, [vpp, vpp, ctypes.c_int, ctypes.POINTER(ctypes.c_uint32),
                                                    ctypes.c_size_t, ctypes.POINTER(ctypes.c_uint8),
                                                    ctypes.POINTER(PlanItem), ctypes.c_size_t]),
@@ -384,6 +387,17 @@ def dl_batch_fanout(items, stream=None) -> None:
 def dl_token_dispatch(ins, outs, tokens, row_bytes: int, dest, stream=None) -> None:
     a, b, W, tok, d = _dispatch_args(ins, outs, tokens, dest)
     _check(lib().dl_token_dispatch(a, b, W, tok, int(row_bytes), d, _stream(stream)), "dl_token_dispatch")
+
+
+def dl_token_dispatch_device(ins, outs, tokens, row_bytes: int, dest_device, stream=None) -> None:
+    """dest_device: device buffer of (total tokens) x W bytes, non-zero where a token goes to a rank."""
+    ins, outs = list(ins), list(outs)
+    W = len(ins)
+    if len(outs) != W or len(tokens) != W:
+        raise ValueError("need W send buffers, W receive buffers and W token counts")
+    tok = (ctypes.c_uint32 * W)(*[int(t) for t in tokens])
+    _check(lib().dl_token_dispatch_device(_ptr_array(ins), _ptr_array(outs), W, tok, int(row_bytes), _addr(dest_device),
+                                          _stream(stream)), "dl_token_dispatch_device")
 
 
 # -------------------------------------------------------------------- prelaunch

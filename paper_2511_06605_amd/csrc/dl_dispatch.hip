@@ -36,7 +36,32 @@ struct build_args {
 //
 // PUSHED: the host wrote the mask into device memory just before the launch; it is read past the caches, where
 // a line of whatever used that memory before may linger.
-template <bool PUSHED>
+// Per block of 256 tokens and per rank: how many of the block's tokens go to that rank (any non-zero mask byte
+// counts).  For a mask that is already in device memory: what the host otherwise counts while it folds the mask.
+__global__ void __launch_bounds__(BUILD_THREADS) dl_dispatch_count_kernel(const uint8_t *__restrict__ mask, uint32_t tokens,
+                                                                          uint32_t *__restrict__ counts)
+{
+    __shared__ uint32_t in_wave[BUILD_WAVES][DISPATCH_W];
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const uint32_t token = blockIdx.x * BUILD_THREADS + tid;
+    const uint64_t mine = token < tokens ? dl_global<uint64_t>(mask)[token] : 0ull;
+#pragma unroll
+    for (int j = 0; j < DISPATCH_W; ++j) {
+        const uint64_t votes = __ballot(((mine >> (8 * j)) & 0xFFu) != 0);
+        if (lane == 0) in_wave[wave][j] = (uint32_t)__popcll(votes);
+    }
+    __syncthreads();
+    if (tid < DISPATCH_W) {
+        uint32_t c = 0;
+#pragma unroll
+        for (uint32_t w = 0; w < BUILD_WAVES; ++w) c += in_wave[w][tid];
+        counts[blockIdx.x * DISPATCH_W + tid] = c;
+    }
+}
+
+// COUNTS: block_rows holds every block's own counts (dl_dispatch_count_kernel), and the rows taken by earlier
+// blocks are summed up here; else it holds those sums already (the host's).
+template <bool PUSHED, bool COUNTS = false>
 __global__ void __launch_bounds__(BUILD_THREADS) dl_dispatch_build_kernel(const uint8_t *__restrict__ mask,
                                                                           const uint32_t *__restrict__ block_rows,
                                                                           const build_args a,
@@ -76,6 +101,13 @@ __global__ void __launch_bounds__(BUILD_THREADS) dl_dispatch_build_kernel(const 
         }
         if (tid < DISPATCH_W)
             before_block[tid] = dl_ld<POL>(dl_global<uint32_t>(block_rows) + blockIdx.x * DISPATCH_W + tid);
+        mine = valid ? dl_ld<POL>(dl_global<uint64_t>(mask) + token) : 0ull;
+    } else if constexpr (COUNTS) {
+        if (tid < DISPATCH_W) {
+            uint32_t before = 0;
+            for (uint32_t b = 0; b < blockIdx.x; ++b) before += block_rows[b * DISPATCH_W + tid];
+            before_block[tid] = before;
+        }
         mine = valid ? dl_ld<POL>(dl_global<uint64_t>(mask) + token) : 0ull;
     } else {
         if (tid < DISPATCH_W) before_block[tid] = dl_ld<POL>(dl_global<uint32_t>(block_rows) + blockIdx.x * DISPATCH_W + tid);
@@ -229,4 +261,61 @@ int dl_dispatch_on_device(const void *const *in, void *const *out, int W, const 
     rc = dl_launch_fused_rows_table(items, (uint32_t)total, row_bytes, stream);
     if (rc != DL_OK) return rc;
     return dl_ring_release(slot, stream);
+}
+
+// Token dispatch with the routing mask in device memory (dl_token_dispatch_device): nothing of the request but
+// the kernel arguments comes from the host.  Three launches on the caller's stream: count per block, build the
+// item table (in a slot of the library's table memory), execute it.
+extern "C" int dl_token_dispatch_device(const void *const *in, void *const *out, int W, const uint32_t *tokens,
+                                        size_t row_bytes, const uint8_t *dest_device, void *stream)
+{
+    DL_LOCKED;
+    if (!g_dl.inited) return DL_ERR_STATE;
+    if (dl_device_error_pending()) return DL_ERR_LOST;
+    if (W != DISPATCH_W || !in || !out || !tokens) return DL_ERR_INVALID;
+    if (row_bytes & 15u) return DL_ERR_INVALID;
+    uint64_t total = 0;
+    for (int i = 0; i < W; ++i) total += tokens[i];
+    if (total == 0 || row_bytes == 0) return DL_OK;
+    if (!dest_device || ((uint64_t)dest_device & 7u)) return DL_ERR_INVALID;
+    for (int i = 0; i < W; ++i) {
+        if ((tokens[i] && !in[i]) || !out[i]) return DL_ERR_INVALID;
+        if (((uint64_t)in[i] | (uint64_t)out[i]) & 15u) return DL_ERR_INVALID;
+    }
+    if (total > DL_DISPATCH_DEVICE_MAX_TOKENS) return DL_ERR_CAPACITY;
+    const uint64_t blocks = (total + BUILD_THREADS - 1) / BUILD_THREADS;
+    const uint64_t head_bytes = (blocks * DISPATCH_W * sizeof(uint32_t) + 255u) & ~(uint64_t)255u;
+    static_assert((((DL_DISPATCH_DEVICE_MAX_TOKENS + BUILD_THREADS - 1) / BUILD_THREADS * DISPATCH_W * sizeof(uint32_t) + 255u) & ~(size_t)255u) +
+                          DL_DISPATCH_DEVICE_MAX_TOKENS * sizeof(dl_fused_item) <= DL_RING_SLOT_BYTES,
+                  "counts and table of the largest request fit one slot of the table memory");
+    hipStream_t hs = (hipStream_t)stream;
+
+    size_t slot;
+    char *host, *dev;
+    int rc = dl_ring_acquire(&slot, &host, &dev);
+    if (rc != DL_OK) return rc;
+    uint32_t *counts = (uint32_t *)dev;
+    dl_fused_item *items = (dl_fused_item *)(dev + head_bytes);
+    hipLaunchKernelGGL(dl_dispatch_count_kernel, dim3((uint32_t)blocks), dim3(BUILD_THREADS), 0, hs, dest_device,
+                       (uint32_t)total, counts);
+    DL_HIP(hipGetLastError());
+    build_args a;
+    uint32_t first = 0;
+    for (int i = 0; i < DISPATCH_W; ++i) {
+        a.in[i] = (const char *)in[i];
+        a.out[i] = (char *)out[i];
+        a.first_token[i] = first;
+        first += tokens[i];
+    }
+    a.first_token[DISPATCH_W] = first;
+    a.W = (uint32_t)W;
+    a.tokens = (uint32_t)total;
+    a.row_bytes = row_bytes;
+    hipLaunchKernelGGL((dl_dispatch_build_kernel<false, true>), dim3((uint32_t)blocks), dim3(BUILD_THREADS), 0, hs,
+                       dest_device, (const uint32_t *)counts, a, items, dl_push_kernel_args(0));
+    DL_HIP(hipGetLastError());
+    rc = dl_launch_fused_rows_table(items, (uint32_t)total, row_bytes, hs);
+    if (rc != DL_OK) return rc;
+    t_dl_last.mode = DL_MODE_ONESHOT;
+    return dl_ring_release(slot, hs);
 }
