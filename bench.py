@@ -703,7 +703,7 @@ def main() -> int:
                    "W": W, "calls_per_step": len(sizes), "bytes_per_step": step_bytes, "mode": "oneshot"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "kernel": "dl_exec_rows_kernel<dl_fused_item, 8, 0>",
+                     "kernel": "dl_exec_rows_kernel<dl_fused_item, 8, 0, true>",
                      "launch": f"all-gather {big // MiB} MiB/rank: {ag_bytes(big)} B in {big_ms * 1e3:.1f} us "
                                f"(mean of {len(events)} launches, HIP events)"},
     }

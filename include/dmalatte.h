@@ -542,7 +542,10 @@ long dl_plan_alltoall_inplace(void *const *buf, int W, size_t chunk_bytes, dl_sw
 long dl_plan_swap_first_hazard(const dl_swap_desc *swaps, size_t n);
 
 /* Host-only: number of workgroup tiles the item list is cut into for a given
- * tile size (the grid of the one-shot launch). */
+ * tile size, a multiple of 128 (the grid of the one-shot launch).  Tiles lie on
+ * the grid of tile_bytes of each item's first destination: an item whose first
+ * destination stands s bytes behind a 128-byte boundary takes
+ * ceil((bytes + s) / tile_bytes) tiles. */
 uint64_t dl_plan_tiles(const dl_plan_item *items, size_t n, uint32_t tile_bytes);
 
 #ifdef __cplusplus

@@ -791,7 +791,7 @@ long dl_plan_first_hazard(const dl_plan_item *items, size_t n)
 
 uint64_t dl_plan_tiles(const dl_plan_item *items, size_t n, uint32_t tile_bytes)
 {
-    if (!items || tile_bytes < 16) return 0;
+    if (!items || tile_bytes < DL_CUT || tile_bytes % DL_CUT) return 0;
     uint64_t t = 0;
     for (size_t i = 0; i < n; ++i) t += dl_item_tiles(*reinterpret_cast<const dl_fused_item *>(&items[i]), tile_bytes);
     return t;

@@ -86,20 +86,65 @@ __device__ __forceinline__ void dl_drain_stores()
     asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
 }
 
-// N 16-byte loads issued back to back, so that a lane has N requests in flight.  For the coherent policy the
-// loads and the one wait behind them are a single assembly statement: the compiler cannot see that such a load
-// completes later, so its results must not be visible to it before the wait (outputs are early-clobber: the
-// addresses of the later loads are still needed when the first result register is written).  Every address
-// must be readable; what a lane does not want it simply does not store.
-template <int POL, int N, class P>
-__device__ __forceinline__ void dl_ld_many(dl_u32x4 (&v)[N], P (&p)[N])
+// 16 bytes at any address.  A 16-byte global access needs no alignment on this hardware (the runtime enables
+// unaligned access for the whole process, and the compiler counts on it: it emits one global_load_dwordx4 for a
+// load that it knows nothing about the alignment of).  The pointee type says "alignment 1" so that nothing is
+// ever assumed about the low address bits; aligned and unaligned addresses take the same instruction.
+typedef dl_u32x4 dl_u32x4u __attribute__((aligned(1)));
+
+template <int POL>
+__device__ __forceinline__ dl_u32x4 dl_ld16(const char *p)
+{
+    const DL_GLOBAL dl_u32x4u *q = (const DL_GLOBAL dl_u32x4u *)(uint64_t)p;
+    if constexpr (POL == DL_POL_STREAM) {
+        return __builtin_nontemporal_load(q);
+    } else if constexpr (POL == DL_POL_COHERENT) {
+        dl_u32x4 v;
+        asm volatile("global_load_dwordx4 %0, %1, off sc0 sc1\n\ts_waitcnt vmcnt(0)" : "=v"(v) : "v"(q) : "memory");
+        return v;
+    } else {
+        return *q;
+    }
+}
+
+template <int POL>
+__device__ __forceinline__ void dl_st16(char *p, dl_u32x4 v)
+{
+    DL_GLOBAL dl_u32x4u *q = (DL_GLOBAL dl_u32x4u *)(uint64_t)p;
+    if constexpr (POL == DL_POL_STREAM)
+        __builtin_nontemporal_store(v, q);
+    else if constexpr (POL == DL_POL_WT)  // (the s_nop: see dl_st)
+        asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" : : "v"(q), "v"(v) : "memory");
+    else if constexpr (POL == DL_POL_COHERENT)
+        asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1\n\ts_nop 1" : : "v"(q), "v"(v) : "memory");
+    else
+        *q = v;
+}
+
+// One byte from src + i to the same offset of the first k destinations.
+template <int FAN, int POL>
+__device__ __forceinline__ void dl_copy_byte(const char *src, char *const (&dsts)[FAN], uint32_t k, uint64_t i)
+{
+    const uint8_t v = dl_ld<POL>(dl_global<uint8_t>(src) + i);
+#pragma unroll
+    for (int j = 0; j < FAN; ++j)
+        if ((uint32_t)j < k) dl_st<POL>(dl_global<uint8_t>(dsts[j]) + i, v);
+}
+
+// N 16-byte loads (any alignment) issued back to back, so that a lane has N requests in flight.  For the coherent
+// policy the loads and the one wait behind them are a single assembly statement: the compiler cannot see that
+// such a load completes later, so its results must not be visible to it before the wait (outputs are
+// early-clobber: the addresses of the later loads are still needed when the first result register is written).
+// Every address must be readable; what a lane does not want it simply does not store.
+template <int POL, int N>
+__device__ __forceinline__ void dl_ld_many(dl_u32x4 (&v)[N], const char *const (&p)[N])
 {
     static_assert(N == 1 || N == 2 || N == 4, "one, two or four loads in flight");
     if constexpr (POL != DL_POL_COHERENT) {
 #pragma unroll
-        for (int u = 0; u < N; ++u) v[u] = dl_ld<POL>(p[u]);
+        for (int u = 0; u < N; ++u) v[u] = dl_ld16<POL>(p[u]);
     } else if constexpr (N == 1) {
-        v[0] = dl_ld<POL>(p[0]);
+        v[0] = dl_ld16<POL>(p[0]);
     } else if constexpr (N == 2) {
         asm volatile("global_load_dwordx4 %0, %2, off sc0 sc1\n\t"
                      "global_load_dwordx4 %1, %3, off sc0 sc1\n\t"
@@ -119,189 +164,152 @@ __device__ __forceinline__ void dl_ld_many(dl_u32x4 (&v)[N], P (&p)[N])
     }
 }
 
-// n 16-byte vectors from s to the first K of the destinations, by nthr threads.
+// n 16-byte vectors from s to the same offsets of the first K of the destinations, by nthr threads.
 template <int K, int FAN, int POL>
-__device__ __forceinline__ void dl_copy_vec16(const DL_GLOBAL dl_u32x4 *__restrict__ s, char *const (&dsts)[FAN],
-                                              uint64_t byte_off, uint32_t n, uint32_t tid, uint32_t nthr)
+__device__ __forceinline__ void dl_copy_vec16(const char *__restrict__ s, char *const (&dsts)[FAN], uint64_t byte_off,
+                                              uint32_t n, uint32_t tid, uint32_t nthr)
 {
     static_assert(K <= FAN, "fan-out");
-    DL_GLOBAL dl_u32x4 *d[K];
+    s += byte_off;
+    char *d[K];
 #pragma unroll
-    for (int j = 0; j < K; ++j) d[j] = dl_global<dl_u32x4>(dsts[j] + byte_off);
+    for (int j = 0; j < K; ++j) d[j] = dsts[j] + byte_off;
 
     uint32_t i = tid;
     const uint32_t step = nthr * DL_UNROLL;
     for (; i + (DL_UNROLL - 1) * nthr < n; i += step) {
         dl_u32x4 v[DL_UNROLL];
-        const DL_GLOBAL dl_u32x4 *from[DL_UNROLL];
+        const char *from[DL_UNROLL];
 #pragma unroll
-        for (int u = 0; u < DL_UNROLL; ++u) from[u] = s + i + u * nthr;
+        for (int u = 0; u < DL_UNROLL; ++u) from[u] = s + 16ull * (i + u * nthr);
         dl_ld_many<POL, DL_UNROLL>(v, from);
 #pragma unroll
         for (int u = 0; u < DL_UNROLL; ++u)
 #pragma unroll
-            for (int j = 0; j < K; ++j) dl_st<POL>(d[j] + i + u * nthr, v[u]);
+            for (int j = 0; j < K; ++j) dl_st16<POL>(d[j] + 16ull * (i + u * nthr), v[u]);
     }
     for (; i < n; i += nthr) {
-        dl_u32x4 v = dl_ld<POL>(s + i);
+        const dl_u32x4 v = dl_ld16<POL>(s + 16ull * i);
 #pragma unroll
-        for (int j = 0; j < K; ++j) dl_st<POL>(d[j] + i, v);
+        for (int j = 0; j < K; ++j) dl_st16<POL>(d[j] + 16ull * i, v);
     }
 }
 
-// Narrow elements (addresses that do not agree modulo 16): correctness path.
-template <typename V, int FAN, int POL>
-__device__ __forceinline__ void dl_copy_narrow(const char *src, char *const (&dsts)[FAN], uint32_t k,
-                                               uint64_t byte_off, uint32_t n, uint32_t tid, uint32_t nthr)
-{
-    const DL_GLOBAL V *s = dl_global<V>(src + byte_off);
-    for (uint32_t i = tid; i < n; i += nthr) {
-        V v = dl_ld<POL>(s + i);
-#pragma unroll
-        for (int j = 0; j < FAN; ++j)
-            if ((uint32_t)j < k) dl_st<POL>(dl_global<V>(dsts[j] + byte_off) + i, v);
-    }
-}
-
-// Move tile `tile` of the copy (src -> dsts[0..k)), all threads of the
-// workgroup taking part.  src, dsts, k, bytes, tile, split must be uniform
-// across the workgroup; 1 <= k <= FAN; nthr >= 64.
+// Move bytes [lo, hi) of the copy (src -> dsts[0..k)), all threads of the workgroup taking part: up to 15 bytes
+// one by one until the first destination stands on a 16-byte boundary, then 16-byte vectors (aligned stores to
+// the first destination; the other addresses are whatever they are), then up to 15 bytes one by one.
+// src, dsts, k, lo, hi, split must be uniform across the workgroup; 1 <= k <= FAN; nthr >= 64; hi - lo < 2^32.
 //
 // split in {1, 2, 4} divides the workgroup into that many sub-groups of whole
-// wavefronts.  Every sub-group reads the whole tile (the first read brings it
+// wavefronts.  Every sub-group reads the whole range (the first read brings it
 // into the compute unit's cache, the others hit there) and writes it to its
 // own share of ceil(k / split) destinations, so a lane issues few stores per
 // load.  On MI355X one load followed by two stores per wavefront moved an
 // 8-way fan-out about 10 % faster than one load followed by eight stores.
 template <int FAN, int POL>
+__device__ __forceinline__ void dl_move_range(const char *src, char *const (&dsts)[FAN], uint32_t k, uint64_t lo,
+                                              uint64_t hi, uint32_t split, uint32_t tid, uint32_t nthr)
+{
+    if (lo >= hi) return;
+    const uint64_t len = hi - lo;
+    uint64_t head = (0 - ((uint64_t)dsts[0] + lo)) & 15u;
+    if (head > len) head = len;
+    const uint32_t n = (uint32_t)((len - head) >> 4);
+    const uint32_t tail = (uint32_t)(len - head) & 15u;
+    const uint64_t off = lo + head;
+    // head bytes by threads 0..15, tail bytes by threads 32..47
+    if (tid < head) dl_copy_byte<FAN, POL>(src, dsts, k, lo + tid);
+    if (tid >= 32 && tid - 32 < tail) dl_copy_byte<FAN, POL>(src, dsts, k, off + 16ull * n + (tid - 32));
+    if (n == 0) return;
+
+    if constexpr (FAN == 1) {
+        dl_copy_vec16<1, FAN, POL>(src, dsts, off, n, tid, nthr);
+    } else {
+        static_assert(FAN == 8, "fan-out switch and shifter below are written for 8");
+        char *my[FAN];
+#pragma unroll
+        for (int j = 0; j < FAN; ++j) my[j] = dsts[j];
+        uint32_t my_k = k;
+        if (split > 1) {
+            // sub-group `grp` (whole wavefronts) takes destinations first .. first + my_k - 1
+            nthr /= split;
+            const uint32_t grp = __builtin_amdgcn_readfirstlane(tid / nthr);
+            tid -= grp * nthr;
+            const uint32_t per = (k + split - 1) / split;
+            const uint32_t first = grp * per;
+            my_k = first < k ? (k - first < per ? k - first : per) : 0u;
+            // my[q] = dsts[first + q]: shift the (uniform) pointer array down by first, bit by bit
+#pragma unroll
+            for (int sh = 1; sh < FAN; sh *= 2)
+                if (first & (uint32_t)sh) {
+#pragma unroll
+                    for (int j = 0; j + sh < FAN; ++j) my[j] = my[j + sh];
+                }
+        }
+        switch (my_k) {
+        case 0: break;
+        case 1: dl_copy_vec16<1, FAN, POL>(src, my, off, n, tid, nthr); break;
+        case 2: dl_copy_vec16<2, FAN, POL>(src, my, off, n, tid, nthr); break;
+        case 3: dl_copy_vec16<3, FAN, POL>(src, my, off, n, tid, nthr); break;
+        case 4: dl_copy_vec16<4, FAN, POL>(src, my, off, n, tid, nthr); break;
+        case 5: dl_copy_vec16<5, FAN, POL>(src, my, off, n, tid, nthr); break;
+        case 6: dl_copy_vec16<6, FAN, POL>(src, my, off, n, tid, nthr); break;
+        case 7: dl_copy_vec16<7, FAN, POL>(src, my, off, n, tid, nthr); break;
+        default: dl_copy_vec16<8, FAN, POL>(src, my, off, n, tid, nthr); break;
+        }
+    }
+}
+
+// Tile `tile` of the copy: the bytes that lie in that tile of the first destination's grid (see dl_tile_range).
+template <int FAN, int POL>
 __device__ __forceinline__ void dl_move_tile(const char *src, char *const (&dsts)[FAN], uint32_t k, uint64_t bytes,
                                              uint64_t tile, uint32_t tile_bytes, uint32_t split, uint32_t tid,
                                              uint32_t nthr)
 {
-    uint64_t diff = 0;
-#pragma unroll
-    for (int j = 0; j < FAN; ++j)
-        if ((uint32_t)j < k) diff |= (uint64_t)src ^ (uint64_t)dsts[j];
-    const dl_geom g = dl_make_geom((uint64_t)src, diff, bytes);
-
-    if (tile == 0) {
-        // head bytes by threads 0..15, tail bytes by threads 32..47
-        if (tid < g.head) {
-            uint8_t v = dl_ld<POL>(dl_global<uint8_t>(src) + tid);
-#pragma unroll
-            for (int j = 0; j < FAN; ++j)
-                if ((uint32_t)j < k) dl_st<POL>(dl_global<uint8_t>(dsts[j]) + tid, v);
-        }
-        if (tid >= 32 && tid - 32 < g.tail) {
-            uint64_t off = (uint64_t)g.head + g.body * g.esize + (tid - 32);
-            uint8_t v = dl_ld<POL>(dl_global<uint8_t>(src) + off);
-#pragma unroll
-            for (int j = 0; j < FAN; ++j)
-                if ((uint32_t)j < k) dl_st<POL>(dl_global<uint8_t>(dsts[j]) + off, v);
-        }
-    }
-
-    const uint64_t per_tile = tile_bytes / g.esize;
-    const uint64_t first = tile * per_tile;
-    if (first >= g.body) return;
-    const uint64_t left = g.body - first;
-    const uint32_t n = (uint32_t)(left < per_tile ? left : per_tile);
-    const uint64_t off = (uint64_t)g.head + first * g.esize;
-
-    if (g.esize == 16) {
-        const DL_GLOBAL dl_u32x4 *s = dl_global<dl_u32x4>(src + off);
-        if constexpr (FAN == 1) {
-            dl_copy_vec16<1, FAN, POL>(s, dsts, off, n, tid, nthr);
-        } else {
-            static_assert(FAN == 8, "fan-out switch and shifter below are written for 8");
-            char *my[FAN];
-#pragma unroll
-            for (int j = 0; j < FAN; ++j) my[j] = dsts[j];
-            uint32_t my_k = k;
-            if (split > 1) {
-                // sub-group `grp` (whole wavefronts) takes destinations first .. first + my_k - 1
-                nthr /= split;
-                const uint32_t grp = __builtin_amdgcn_readfirstlane(tid / nthr);
-                tid -= grp * nthr;
-                const uint32_t per = (k + split - 1) / split;
-                const uint32_t first = grp * per;
-                my_k = first < k ? (k - first < per ? k - first : per) : 0u;
-                // my[q] = dsts[first + q]: shift the (uniform) pointer array down by first, bit by bit
-#pragma unroll
-                for (int sh = 1; sh < FAN; sh *= 2)
-                    if (first & (uint32_t)sh) {
-#pragma unroll
-                        for (int j = 0; j + sh < FAN; ++j) my[j] = my[j + sh];
-                    }
-            }
-            switch (my_k) {
-            case 0: break;
-            case 1: dl_copy_vec16<1, FAN, POL>(s, my, off, n, tid, nthr); break;
-            case 2: dl_copy_vec16<2, FAN, POL>(s, my, off, n, tid, nthr); break;
-            case 3: dl_copy_vec16<3, FAN, POL>(s, my, off, n, tid, nthr); break;
-            case 4: dl_copy_vec16<4, FAN, POL>(s, my, off, n, tid, nthr); break;
-            case 5: dl_copy_vec16<5, FAN, POL>(s, my, off, n, tid, nthr); break;
-            case 6: dl_copy_vec16<6, FAN, POL>(s, my, off, n, tid, nthr); break;
-            case 7: dl_copy_vec16<7, FAN, POL>(s, my, off, n, tid, nthr); break;
-            default: dl_copy_vec16<8, FAN, POL>(s, my, off, n, tid, nthr); break;
-            }
-        }
-    } else if (g.esize == 4) {
-        dl_copy_narrow<uint32_t, FAN, POL>(src, dsts, k, off, n, tid, nthr);
-    } else {
-        dl_copy_narrow<uint8_t, FAN, POL>(src, dsts, k, off, n, tid, nthr);
-    }
+    uint64_t lo, hi;
+    dl_tile_range((uint32_t)((uint64_t)dsts[0] & (DL_CUT - 1u)), bytes, tile, tile_bytes, &lo, &hi);
+    dl_move_range<FAN, POL>(src, dsts, k, lo, hi, split, tid, nthr);
 }
 
-// Exchange n elements of type V between a and b (disjoint ranges).
-template <typename V, int POL>
-__device__ __forceinline__ void dl_swap_elems(char *a, char *b, uint64_t byte_off, uint32_t n, uint32_t tid,
-                                              uint32_t nthr)
+// Exchange bytes [lo, hi) of a and b (disjoint ranges): cut like dl_move_range with b in the place of the first
+// destination.  Every byte of either range is read and written by exactly one lane, so no lane depends on another.
+template <int POL>
+__device__ __forceinline__ void dl_swap_byte(char *a, char *b, uint64_t i)
 {
-    DL_GLOBAL V *pa = dl_global<V>(a + byte_off);
-    DL_GLOBAL V *pb = dl_global<V>(b + byte_off);
+    const uint8_t x = dl_ld<POL>(dl_global<uint8_t>(a) + i);
+    const uint8_t y = dl_ld<POL>(dl_global<uint8_t>(b) + i);
+    dl_st<POL>(dl_global<uint8_t>(a) + i, y);
+    dl_st<POL>(dl_global<uint8_t>(b) + i, x);
+}
+
+template <int POL>
+__device__ __forceinline__ void dl_swap_range(char *a, char *b, uint64_t lo, uint64_t hi, uint32_t tid, uint32_t nthr)
+{
+    if (lo >= hi) return;
+    const uint64_t len = hi - lo;
+    uint64_t head = (0 - ((uint64_t)b + lo)) & 15u;
+    if (head > len) head = len;
+    const uint32_t n = (uint32_t)((len - head) >> 4);
+    const uint32_t tail = (uint32_t)(len - head) & 15u;
+    const uint64_t off = lo + head;
+    if (tid < head) dl_swap_byte<POL>(a, b, lo + tid);
+    if (tid >= 32 && tid - 32 < tail) dl_swap_byte<POL>(a, b, off + 16ull * n + (tid - 32));
     for (uint32_t i = tid; i < n; i += nthr) {
-        if constexpr (sizeof(V) == 16) {
-            dl_u32x4 xy[2];
-            const DL_GLOBAL dl_u32x4 *const from[2] = {pa + i, pb + i};
-            dl_ld_many<POL, 2>(xy, from);  // both in flight together
-            dl_st<POL>(pa + i, xy[1]);
-            dl_st<POL>(pb + i, xy[0]);
-        } else {
-            const V x = dl_ld<POL>(pa + i);
-            const V y = dl_ld<POL>(pb + i);
-            dl_st<POL>(pa + i, y);
-            dl_st<POL>(pb + i, x);
-        }
+        dl_u32x4 xy[2];
+        const char *const from[2] = {a + off + 16ull * i, b + off + 16ull * i};
+        dl_ld_many<POL, 2>(xy, from);  // both in flight together
+        dl_st16<POL>(a + off + 16ull * i, xy[1]);
+        dl_st16<POL>(b + off + 16ull * i, xy[0]);
     }
 }
 
-// Tile `tile` of a swap, any alignment: same cut as dl_move_tile (element size
-// from the two addresses, head and tail bytes with tile 0).  Every byte of
-// either range is read and written by exactly one lane, so no lane depends on
-// another.
 template <int POL>
 __device__ __forceinline__ void dl_swap_tile(char *a, char *b, uint64_t bytes, uint64_t tile, uint32_t tile_bytes,
                                              uint32_t tid, uint32_t nthr)
 {
-    const dl_geom g = dl_make_geom((uint64_t)a, (uint64_t)a ^ (uint64_t)b, bytes);
-    if (tile == 0) {
-        if (tid < g.head) dl_swap_elems<uint8_t, POL>(a, b, tid, 1u, 0u, 1u);
-        if (tid >= 32 && tid - 32 < g.tail)
-            dl_swap_elems<uint8_t, POL>(a, b, (uint64_t)g.head + g.body * g.esize + (tid - 32), 1u, 0u, 1u);
-    }
-    const uint64_t per_tile = tile_bytes / g.esize;
-    const uint64_t first = tile * per_tile;
-    if (first >= g.body) return;
-    const uint64_t left = g.body - first;
-    const uint32_t n = (uint32_t)(left < per_tile ? left : per_tile);
-    const uint64_t off = (uint64_t)g.head + first * g.esize;
-    if (g.esize == 16)
-        dl_swap_elems<dl_u32x4, POL>(a, b, off, n, tid, nthr);
-    else if (g.esize == 4)
-        dl_swap_elems<uint32_t, POL>(a, b, off, n, tid, nthr);
-    else
-        dl_swap_elems<uint8_t, POL>(a, b, off, n, tid, nthr);
+    uint64_t lo, hi;
+    dl_tile_range((uint32_t)((uint64_t)b & (DL_CUT - 1u)), bytes, tile, tile_bytes, &lo, &hi);
+    dl_swap_range<POL>(a, b, lo, hi, tid, nthr);
 }
 
 // A slot that the host filled through the BAR carries a stamp behind its payload, written after it; writes that
@@ -367,6 +375,32 @@ __device__ __forceinline__ void dl_run_item(const dl_fused_item &it, uint64_t ti
                              dl_uniform64(it.bytes), tile, tile_bytes, split, threadIdx.x, blockDim.x);
 }
 
+// A whole item by one workgroup (an entry of a table: the host has cut those to a tile's length at most).
+template <int POL>
+__device__ __forceinline__ void dl_run_entry(const dl_plain_item &it, uint32_t)
+{
+    char *d[1] = {(char *)dl_uniform64((uint64_t)it.dst)};
+    dl_move_range<1, POL>((const char *)dl_uniform64((uint64_t)it.src), d, 1u, 0, dl_uniform64(it.bytes), 1u, threadIdx.x,
+                          blockDim.x);
+}
+
+template <int POL>
+__device__ __forceinline__ void dl_run_entry(const dl_swap_item &it, uint32_t)
+{
+    dl_swap_range<POL>((char *)dl_uniform64((uint64_t)it.src), (char *)dl_uniform64((uint64_t)it.dst), 0,
+                       dl_uniform64(it.bytes), threadIdx.x, blockDim.x);
+}
+
+template <int POL>
+__device__ __forceinline__ void dl_run_entry(const dl_fused_item &it, uint32_t split)
+{
+    char *d[DL_FAN];
+#pragma unroll
+    for (int j = 0; j < DL_FAN; ++j) d[j] = (char *)dl_uniform64((uint64_t)it.dst[j]);
+    dl_move_range<DL_FAN, POL>((const char *)dl_uniform64((uint64_t)it.src), d, __builtin_amdgcn_readfirstlane(it.k), 0,
+                               dl_uniform64(it.bytes), split, threadIdx.x, blockDim.x);
+}
+
 template <class Item, int NMAX>
 struct dl_klist {
     uint32_t n;
@@ -411,79 +445,142 @@ __device__ __forceinline__ uint32_t dl_find_item(const dl_klist<Item, NMAX> &p, 
 __device__ __forceinline__ const char *dl_item_dst(const dl_plain_item &it, uint32_t) { return it.dst; }
 __device__ __forceinline__ const char *dl_item_dst(const dl_fused_item &it, uint32_t j) { return it.dst[j]; }
 
-// Row path: the hot loop of large aligned requests, kept to a few dozen
-// instructions and two scalar round trips per wavefront.  Preconditions
-// (established on the host): every address of every item is a multiple of 16
-// and so is every byte count; a tile is (1 << wpg_log2) rows of 1 KiB; the
-// destinations of a fused item are stored by sub-group: sub-group g owns slots
-// g * (DL_FAN >> split_log2) onwards, filled from the front, the rest null.
-// Wavefront w of the workgroup belongs to sub-group w >> wpg_log2 and moves row
-// w & (rows - 1) of the tile: one 16-byte load per lane, then one store per
-// destination in its sub-group's slots.  At this granularity (a wavefront lives
-// for one load and one or two stores) the per-wavefront instruction count and
-// the dependent scalar loads in front of the vector load decide the rate.
-// `tile` is the tile's index within the item.
-template <int POL, class Item>
+// What a lane of the row path owns of an item of `bytes` bytes when its 16 bytes begin at offset `byte` (which
+// has wrapped below zero in front of the item): 0 nothing, 1 all 16 bytes, 2 only bytes [*lo, *hi) (the item
+// begins or ends inside).  ragged: the item's first destination or its length is not a multiple of 16; without
+// that there is no case 2 and one compare decides.
+__device__ __forceinline__ int dl_lane_part(uint64_t byte, uint64_t bytes, bool ragged, uint64_t *lo, uint64_t *hi)
+{
+    if (!ragged) return byte < bytes ? 1 : 0;
+    const int64_t o = (int64_t)byte;
+    const int64_t l = o < 0 ? 0 : o;
+    const int64_t h = o + 16 < (int64_t)bytes ? o + 16 : (int64_t)bytes;
+    if (l >= h) return 0;
+    if (h - l == 16) return 1;
+    *lo = (uint64_t)l;
+    *hi = (uint64_t)h;
+    return 2;
+}
+
+template <class Item>
+__device__ __forceinline__ bool dl_item_ragged(const Item &it)
+{
+    return __builtin_amdgcn_readfirstlane((dl_item_shift(it) | (uint32_t)it.bytes) & 15u) != 0;
+}
+
+// Row path: the hot loop of large requests, kept to a few dozen instructions and two scalar round trips per
+// wavefront.  Rows are the 1 KiB rows of the grid of the item's first destination (see dl_tile_range; a tile
+// is (1 << wpg_log2) rows), and lane l of a row moves the 16 bytes at row * 1024 + 16 l - shift of the item:
+// one 16-byte load, then one store per destination.  No address needs any alignment.  The lanes under which
+// an item begins or ends in mid-vector (two per item at most, none if its first destination and its length are
+// multiples of 16) move their bytes one by one.
+// The destinations of a fused item are stored by sub-group (established on the host): sub-group g owns slots
+// g * (DL_FAN >> split_log2) onwards, filled from the front, the rest null; slot 0 is the first destination.
+// Wavefront w of the workgroup belongs to sub-group w >> wpg_log2 and moves row w & (rows - 1) of the tile, to
+// the destinations in its sub-group's slots.  At this granularity (a wavefront lives for one load and one or two
+// stores) the per-wavefront instruction count and the dependent scalar loads in front of the vector load decide
+// the rate.  `tile` is the tile's index within the item.
+// ON_GRID: the host has seen that every item's first destination stands on a DL_CUT boundary and that every
+// length is a multiple of 16.  Nothing of the above is computed then; the dozen scalar instructions that it
+// takes cost the all-gather of 4 .. 64 MiB per rank 1-2.5 % of its rate.
+template <int POL, bool ON_GRID = false, class Item>
 __device__ __forceinline__ void dl_rows_body(const Item &it, uint32_t tile, uint32_t wl, uint32_t sl)
 {
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t lane = threadIdx.x & 63u;
     const uint64_t row = ((uint64_t)tile << wl) + (wave & ((1u << wl) - 1u));
-    const uint64_t byte = (row << 10) + (lane << 4);
+    // everything the wavefront needs from the item is requested before the first use
+    const char *src = it.src;
+    const uint64_t bytes = it.bytes;
+    const bool ragged = ON_GRID ? false : dl_item_ragged(it);
+    const uint64_t byte = ((row << 10) - (ON_GRID ? 0u : dl_item_shift(it))) + (lane << 4);
+    uint64_t lo = 0, hi = 0;
     if constexpr (std::is_same<Item, dl_swap_item>::value) {
-        const char *pa = it.src;
-        const char *pb = it.dst;
-        if (byte >= it.bytes) return;
+        char *pa = const_cast<char *>(src);
+        char *pb = it.dst;
+        if (!ragged) {  // (a uniform branch in front of the common case, which stays as short as it was)
+            if (byte >= bytes) return;
+        } else {
+            const int part = dl_lane_part(byte, bytes, true, &lo, &hi);
+            if (part == 0) return;
+            if (part == 2) {
+                for (uint64_t i = lo; i < hi; ++i) dl_swap_byte<POL>(pa, pb, i);
+                return;
+            }
+        }
         dl_u32x4 xy[2];
-        const DL_GLOBAL dl_u32x4 *const from[2] = {dl_global<dl_u32x4>(pa + byte), dl_global<dl_u32x4>(pb + byte)};
+        const char *const from[2] = {pa + byte, pb + byte};
         dl_ld_many<POL, 2>(xy, from);
-        dl_st<POL>(dl_global<dl_u32x4>(pa + byte), xy[1]);
-        dl_st<POL>(dl_global<dl_u32x4>(pb + byte), xy[0]);
+        dl_st16<POL>(pa + byte, xy[1]);
+        dl_st16<POL>(pb + byte, xy[0]);
     } else if constexpr (std::is_same<Item, dl_plain_item>::value) {
-        const char *src = it.src;
-        const char *dst = dl_item_dst(it, 0);
-        if (byte >= it.bytes) return;
-        dl_st<POL>(dl_global<dl_u32x4>(dst + byte), dl_ld<POL>(dl_global<dl_u32x4>(src + byte)));
+        char *dst = it.dst;
+        if (!ragged) {
+            if (byte >= bytes) return;
+        } else {
+            const int part = dl_lane_part(byte, bytes, true, &lo, &hi);
+            if (part == 0) return;
+            if (part == 2) {
+                char *const d[1] = {dst};
+                for (uint64_t i = lo; i < hi; ++i) dl_copy_byte<1, POL>(src, d, 1u, i);
+                return;
+            }
+        }
+        dl_st16<POL>(dst + byte, dl_ld16<POL>(src + byte));
     } else {
         const uint32_t slots = (uint32_t)DL_FAN >> sl;
         const uint32_t base = (wave >> wl) * slots;
-        // everything the wavefront needs from the item is requested before the first use
-        const char *src = it.src;
-        const uint64_t bytes = it.bytes;
-        const char *d0 = dl_item_dst(it, base);
-        const char *d1 = slots > 1 ? dl_item_dst(it, base + 1) : nullptr;
-        if (byte >= bytes || !d0) return;
-        const dl_u32x4 v = dl_ld<POL>(dl_global<dl_u32x4>(src + byte));
-        dl_st<POL>(dl_global<dl_u32x4>(d0 + byte), v);
+        char *d0 = it.dst[base];
+        char *d1 = slots > 1 ? it.dst[base + 1] : nullptr;
+        if (!ragged) {
+            if (byte >= bytes || !d0) return;
+        } else {
+            const int part = d0 ? dl_lane_part(byte, bytes, true, &lo, &hi) : 0;
+            if (part == 0) return;
+            if (part == 2) {
+                for (uint64_t i = lo; i < hi; ++i) {
+                    const uint8_t v = dl_ld<POL>(dl_global<uint8_t>(src) + i);
+                    for (uint32_t q = 0; q < slots; ++q) {
+                        char *dq = it.dst[base + q];
+                        if (!dq) break;
+                        dl_st<POL>(dl_global<uint8_t>(dq) + i, v);
+                    }
+                }
+                return;
+            }
+        }
+        const dl_u32x4 v = dl_ld16<POL>(src + byte);
+        dl_st16<POL>(d0 + byte, v);
         if (!d1) return;
-        dl_st<POL>(dl_global<dl_u32x4>(d1 + byte), v);
+        dl_st16<POL>(d1 + byte, v);
 #pragma unroll
         for (uint32_t q = 2; q < (uint32_t)DL_FAN; ++q) {
             if (q >= slots) break;
-            const char *dq = dl_item_dst(it, base + q);
+            char *dq = it.dst[base + q];
             if (!dq) break;
-            dl_st<POL>(dl_global<dl_u32x4>(dq + byte), v);
+            dl_st16<POL>(dq + byte, v);
         }
     }
 }
 
 // Row path over a list in the kernel arguments: global tile b -> (item, tile).
-template <int POL, class Item, int NMAX>
+template <int POL, bool ON_GRID = false, class Item, int NMAX>
 __device__ __forceinline__ void dl_run_rows(const dl_klist<Item, NMAX> &p, uint32_t b)
 {
     uint32_t first_tile;
     const uint32_t d = dl_find_item(p, b, &first_tile);
     if (d >= p.n) return;
-    dl_rows_body<POL>(p.item[d], b - first_tile, p.wpg_log2, p.split_log2);
+    dl_rows_body<POL, ON_GRID>(p.item[d], b - first_tile, p.wpg_log2, p.split_log2);
 }
 
 // Row path of the armed kernels, whose loads go to memory at system scope and take long to come back: a
 // wavefront takes up to R global tiles per pass (b0, b0 + stride, ...; those below `total`), issues the loads
-// of all of them, waits once and stores.  Same preconditions as dl_rows_body, and one sub-group per workgroup
+// of all of them, waits once and stores.  Rows and lanes as in dl_rows_body, with one sub-group per workgroup
 // (every wavefront stores its row to all of the item's destinations).  b0 < total.  Not for swaps.
+// spare: 16 readable bytes of device memory, for the lanes that have no vector of their own to load.
 template <int R, class Item, int NMAX>
 __device__ __forceinline__ void dl_run_rows_coherent(const dl_klist<Item, NMAX> &p, uint32_t b0, uint32_t stride,
-                                                     uint32_t total)
+                                                     uint32_t total, const void *spare)
 {
     static_assert(!std::is_same<Item, dl_swap_item>::value, "a swap has two loads per row already");
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -491,41 +588,61 @@ __device__ __forceinline__ void dl_run_rows_coherent(const dl_klist<Item, NMAX> 
     const uint32_t wl = p.wpg_log2;
     uint32_t first;
     const uint32_t d0 = dl_find_item(p, b0, &first);
-    // what a lane without work loads instead: the first 16 bytes of tile b0's item (non-empty, a multiple of 16)
-    const DL_GLOBAL dl_u32x4 *const safe = dl_global<dl_u32x4>(p.item[d0].src);
+    // what a lane without a vector loads instead: the first 16 bytes of tile b0's item, if it has that many
+    const char *const safe = p.item[d0].bytes >= 16u ? p.item[d0].src : (const char *)spare;
     uint32_t d[R];
     uint64_t byte[R];
-    bool live[R];
-    const DL_GLOBAL dl_u32x4 *from[R];
+    int part[R];
+    const char *from[R];
+    uint64_t lo = 0, hi = 0;
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const uint32_t b = b0 + (uint32_t)r * stride;
         d[r] = d0;
         byte[r] = 0;
-        live[r] = false;
+        part[r] = 0;
         from[r] = safe;
         if (b < total && b >= b0) {  // (b >= b0: no wrap-around)
             d[r] = dl_find_item(p, b, &first);
-            const uint64_t row = ((uint64_t)(b - first) << wl) + (wave & ((1u << wl) - 1u));
-            byte[r] = (row << 10) + (lane << 4);
-            live[r] = d[r] < p.n && byte[r] < p.item[d[r]].bytes;
-            if (live[r]) from[r] = dl_global<dl_u32x4>(p.item[d[r]].src + byte[r]);
+            if (d[r] < p.n) {
+                const Item &it = p.item[d[r]];
+                const uint64_t row = ((uint64_t)(b - first) << wl) + (wave & ((1u << wl) - 1u));
+                byte[r] = ((row << 10) - dl_item_shift(it)) + (lane << 4);
+                part[r] = dl_lane_part(byte[r], it.bytes, dl_item_ragged(it), &lo, &hi);
+                if (part[r] == 1) from[r] = it.src + byte[r];
+            }
         }
     }
     dl_u32x4 v[R];
     dl_ld_many<DL_POL_COHERENT, R>(v, from);
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-        if (!live[r]) continue;
+        if (part[r] == 0) continue;
         const Item &it = p.item[d[r]];
+        if (part[r] == 2) {
+            (void)dl_lane_part(byte[r], it.bytes, true, &lo, &hi);
+            for (uint64_t i = lo; i < hi; ++i) {
+                const uint8_t x = dl_ld<DL_POL_COHERENT>(dl_global<uint8_t>(it.src) + i);
+                if constexpr (std::is_same<Item, dl_plain_item>::value) {
+                    dl_st<DL_POL_COHERENT>(dl_global<uint8_t>(it.dst) + i, x);
+                } else {
+                    for (uint32_t q = 0; q < (uint32_t)DL_FAN; ++q) {
+                        char *dq = it.dst[q];  // filled from the front, the rest null
+                        if (!dq) break;
+                        dl_st<DL_POL_COHERENT>(dl_global<uint8_t>(dq) + i, x);
+                    }
+                }
+            }
+            continue;
+        }
         if constexpr (std::is_same<Item, dl_plain_item>::value) {
-            dl_st<DL_POL_COHERENT>(dl_global<dl_u32x4>(it.dst + byte[r]), v[r]);
+            dl_st16<DL_POL_COHERENT>(it.dst + byte[r], v[r]);
         } else {
 #pragma unroll
             for (uint32_t q = 0; q < (uint32_t)DL_FAN; ++q) {
-                const char *dq = it.dst[q];  // filled from the front, the rest null
+                char *dq = it.dst[q];  // filled from the front, the rest null
                 if (!dq) break;
-                dl_st<DL_POL_COHERENT>(dl_global<dl_u32x4>(dq + byte[r]), v[r]);
+                dl_st16<DL_POL_COHERENT>(dq + byte[r], v[r]);
             }
         }
     }

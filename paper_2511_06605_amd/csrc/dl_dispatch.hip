@@ -168,6 +168,15 @@ __global__ void __launch_bounds__(BUILD_THREADS) dl_dispatch_build_kernel(const 
     items[token] = it;
 }
 
+// How far behind a DL_CUT boundary the first destination of a row can lie: rows stand whole multiples of
+// row_bytes into the receive buffers, and all of these are multiples of 16.
+uint32_t worst_shift(void *const *out, int W, size_t row_bytes)
+{
+    uint64_t m = row_bytes;
+    for (int i = 0; i < W; ++i) m |= (uint64_t)out[i];
+    return (m & (DL_CUT - 1u)) ? DL_CUT - 16u : 0u;
+}
+
 }  // namespace
 
 int dl_dispatch_on_device(const void *const *in, void *const *out, int W, const uint32_t *tokens, size_t row_bytes,
@@ -258,7 +267,7 @@ int dl_dispatch_on_device(const void *const *in, void *const *out, int W, const 
         rc = dl_push_commit(stream);
         if (rc != DL_OK) return rc;
     }
-    rc = dl_launch_fused_rows_table(items, (uint32_t)total, row_bytes, stream);
+    rc = dl_launch_fused_rows_table(items, (uint32_t)total, row_bytes, worst_shift(out, W, row_bytes), stream);
     if (rc != DL_OK) return rc;
     return dl_ring_release(slot, stream);
 }
@@ -314,7 +323,7 @@ extern "C" int dl_token_dispatch_device(const void *const *in, void *const *out,
     hipLaunchKernelGGL((dl_dispatch_build_kernel<false, true>), dim3((uint32_t)blocks), dim3(BUILD_THREADS), 0, hs,
                        dest_device, (const uint32_t *)counts, a, items, dl_push_kernel_args(0));
     DL_HIP(hipGetLastError());
-    rc = dl_launch_fused_rows_table(items, (uint32_t)total, row_bytes, hs);
+    rc = dl_launch_fused_rows_table(items, (uint32_t)total, row_bytes, worst_shift(out, W, row_bytes), hs);
     if (rc != DL_OK) return rc;
     t_dl_last.mode = DL_MODE_ONESHOT;
     return dl_ring_release(slot, hs);

@@ -24,10 +24,11 @@
 
 // Row path only (see dl_run_rows).  A kernel of its own: sharing one kernel with
 // the general path cost 5 % of the all-gather rate through its register count.
-template <class Item, int NMAX, int POL>
+// ON_GRID: see dl_rows_body.
+template <class Item, int NMAX, int POL, bool ON_GRID>
 __global__ void __launch_bounds__(512) dl_exec_rows_kernel(const dl_klist<Item, NMAX> p)
 {
-    dl_run_rows<POL>(p, blockIdx.x);
+    dl_run_rows<POL, ON_GRID>(p, blockIdx.x);
 }
 
 // Row path over a list too long for the scalar compares of dl_find_item (the 64 chunks of an all-to-all between
@@ -35,10 +36,10 @@ __global__ void __launch_bounds__(512) dl_exec_rows_kernel(const dl_klist<Item, 
 // searched and nothing divided.  The grid is as wide as the longest item; a workgroup beyond its item's last
 // row leaves at once (the host takes this path only while few workgroups are wasted that way).  Consecutive
 // workgroups walk along one item, so the chip-wide stream of addresses stays sequential.
-template <class Item, int NMAX, int POL>
+template <class Item, int NMAX, int POL, bool ON_GRID>
 __global__ void __launch_bounds__(512) dl_exec_rows2d_kernel(const dl_klist<Item, NMAX> p)
 {
-    dl_rows_body<POL>(p.item[blockIdx.y], blockIdx.x, p.wpg_log2, p.split_log2);
+    dl_rows_body<POL, ON_GRID>(p.item[blockIdx.y], blockIdx.x, p.wpg_log2, p.split_log2);
 }
 
 // Entry i of a table that the host wrote into device memory through the BAR just before the launch.  A line
@@ -63,7 +64,7 @@ __device__ __forceinline__ const Item *dl_pushed_entry(const Item *items, uint32
 // Row path over a table of equally sized items in device memory (long lists: thousands of token
 // rows, hundreds of cache blocks): workgroup b works on item b / tiles_per_item, which every
 // workgroup of that item finds in the scalar cache.  PUSHED: see dl_pushed_entry.
-template <class Item, int POL, bool PUSHED = false>
+template <class Item, int POL, bool PUSHED, bool ON_GRID>
 __global__ void __launch_bounds__(512) dl_exec_urows_kernel(const Item *__restrict__ items, uint32_t n,
                                                             uint32_t tiles_per_item, uint32_t wpg_log2,
                                                             uint32_t split_log2, const dl_pushed ps)
@@ -73,14 +74,14 @@ __global__ void __launch_bounds__(512) dl_exec_urows_kernel(const Item *__restri
     if constexpr (PUSHED) {
         const Item *it = dl_pushed_entry(items, d, ps);
         if (it)
-            dl_rows_body<POL>(*it, blockIdx.x - d * tiles_per_item, wpg_log2, split_log2);
+            dl_rows_body<POL, ON_GRID>(*it, blockIdx.x - d * tiles_per_item, wpg_log2, split_log2);
         else if (threadIdx.x == 0)
             dl_pushed_report_lost(ps);  // nothing copied by this workgroup; the host hears of it
     } else
-        dl_rows_body<POL>(items[d], blockIdx.x - d * tiles_per_item, wpg_log2, split_log2);
+        dl_rows_body<POL, ON_GRID>(items[d], blockIdx.x - d * tiles_per_item, wpg_log2, split_log2);
 }
 
-// General path: any alignment and tile size, one workgroup per tile.
+// General path: any tile size, one workgroup per tile.
 template <class Item, int NMAX, int POL>
 __global__ void __launch_bounds__(512) dl_exec_list_kernel(const dl_klist<Item, NMAX> p)
 {
@@ -96,8 +97,8 @@ __global__ void __launch_bounds__(512) dl_exec_list_strided_kernel(const dl_klis
 }
 
 template <class Item, int POL, bool PUSHED = false>
-__global__ void __launch_bounds__(512) dl_exec_table_kernel(const Item *__restrict__ items, uint32_t n,
-                                                            uint32_t tile_bytes, uint32_t split, const dl_pushed ps)
+__global__ void __launch_bounds__(512) dl_exec_table_kernel(const Item *__restrict__ items, uint32_t n, uint32_t split,
+                                                            const dl_pushed ps)
 {
     const uint32_t b = blockIdx.x;
     if (b >= n) return;
@@ -108,10 +109,10 @@ __global__ void __launch_bounds__(512) dl_exec_table_kernel(const Item *__restri
             return;
         }
         const Item it = *pushed;
-        dl_run_item<POL>(it, 0, tile_bytes, split);
+        dl_run_entry<POL>(it, split);
     } else {
         const Item it = items[b];
-        dl_run_item<POL>(it, 0, tile_bytes, split);
+        dl_run_entry<POL>(it, split);
     }
 }
 
@@ -317,10 +318,12 @@ __global__ void __launch_bounds__(512) dl_armed_list_kernel(const dl_klist<Item,
             const uint32_t grid = gridDim.x;
             if (total <= grid)
                 dl_run_rows<DL_POL_COHERENT>(p, blockIdx.x);
+            else if (p.split_log2 != 0)  // (a forced shape: the several-rows form knows one sub-group only)
+                for (uint32_t b = blockIdx.x; b < total; b += grid) dl_run_rows<DL_POL_COHERENT>(p, b);
             else if (total <= 2u * grid)
-                dl_run_rows_coherent<2>(p, blockIdx.x, grid, total);
+                dl_run_rows_coherent<2>(p, blockIdx.x, grid, total, a.go);
             else
-                for (uint32_t b = blockIdx.x; b < total; b += 4u * grid) dl_run_rows_coherent<4>(p, b, grid, total);
+                for (uint32_t b = blockIdx.x; b < total; b += 4u * grid) dl_run_rows_coherent<4>(p, b, grid, total, a.go);
         } else {
             for (uint32_t b = blockIdx.x; b < total; b += gridDim.x) {
                 if constexpr (ROWS)
@@ -339,7 +342,6 @@ struct dl_standby_rec {
     uint64_t ticket_front;
     uint64_t activation;  // which arming of this pool slot the record is for (the executor's doorbell value)
     uint64_t *done;       // the request's completion words (host-coherent): one per tile up to DL_DONE_WORDS tiles, else one
-    uint64_t rows;        // 1: every address and byte count is a multiple of 16 (the row path's precondition)
     uint64_t arrivals;    // written as 0; requests of more than DL_DONE_WORDS tiles count their workgroups in here
     // The ticket's slot has two sets of arrival counters that its requests use in turn, each clearing the set it
     // does not use (see dl_arm).  A request served here counts nothing there, but it keeps that chain: this is
@@ -383,17 +385,10 @@ __global__ void __launch_bounds__(DL_STANDBY_THREADS) dl_standby_kernel(dl_stand
         for (uint32_t g = 0; rec.arrive_clear && g <= DL_ARM_GROUPS; ++g)
             __hip_atomic_store((uint32_t *)((char *)rec.arrive_clear + g * DL_ARM_STRIDE), 0u, __ATOMIC_RELAXED,
                                __HIP_MEMORY_SCOPE_AGENT);
-    if (rec.plain) {
-        if (rec.rows)
-            dl_run_rows<DL_POL_COHERENT>(rec.copies, blockIdx.x);
-        else
-            dl_run_tile<DL_POL_COHERENT>(rec.copies, blockIdx.x);
-    } else {
-        if (rec.rows)
-            dl_run_rows<DL_POL_COHERENT>(rec.list, blockIdx.x);
-        else
-            dl_run_tile<DL_POL_COHERENT>(rec.list, blockIdx.x);
-    }
+    if (rec.plain)
+        dl_run_rows<DL_POL_COHERENT>(rec.copies, blockIdx.x);
+    else
+        dl_run_rows<DL_POL_COHERENT>(rec.list, blockIdx.x);
     // the copy stored at system scope: once the memory counters have drained, the bytes are where everybody sees them
     dl_drain_stores();
     __syncthreads();
@@ -433,9 +428,8 @@ __device__ __forceinline__ Item dl_pushed_entry_per_lane(const Item *items, uint
 // PUSHED: the table was written through the BAR when the request was armed; the workgroup's first entry is
 // fetched before the wait.
 template <class Item, bool PUSHED = false>
-__global__ void __launch_bounds__(512) dl_armed_table_kernel(const Item *__restrict__ items, uint32_t n,
-                                                             uint32_t tile_bytes, uint32_t split, const dl_pushed ps,
-                                                             const dl_arm a)
+__global__ void __launch_bounds__(512) dl_armed_table_kernel(const Item *__restrict__ items, uint32_t n, uint32_t split,
+                                                             const dl_pushed ps, const dl_arm a)
 {
     if constexpr (PUSHED) {
         Item it{};
@@ -446,7 +440,7 @@ __global__ void __launch_bounds__(512) dl_armed_table_kernel(const Item *__restr
         if (go == DL_GO_RUN) {
             for (uint32_t b = blockIdx.x; b < n; b += gridDim.x) {
                 if (b != blockIdx.x) it = dl_pushed_entry_per_lane(items, b, ps, &sealed);
-                dl_run_item<DL_POL_COHERENT>(it, 0, tile_bytes, split);
+                dl_run_entry<DL_POL_COHERENT>(it, split);
             }
         }
         dl_arm_finish(a, go);
@@ -455,7 +449,7 @@ __global__ void __launch_bounds__(512) dl_armed_table_kernel(const Item *__restr
         if (go == DL_GO_RUN) {
             for (uint32_t b = blockIdx.x; b < n; b += gridDim.x) {
                 const Item it = items[b];
-                dl_run_item<DL_POL_COHERENT>(it, 0, tile_bytes, split);
+                dl_run_entry<DL_POL_COHERENT>(it, split);
             }
         }
         dl_arm_finish(a, go);
@@ -518,23 +512,30 @@ inline void with_policy(int policy, F f)
     }
 }
 
+// ... and with whether every item lies on the grid (see dl_rows_body) as one too.
+template <class F>
+inline void with_policy_and_grid(int policy, bool on_grid, F f)
+{
+    with_policy(policy, [&](auto pol) {
+        if (on_grid)
+            f(pol, std::true_type{});
+        else
+            f(pol, std::false_type{});
+    });
+}
+
+// The item's first destination stands on a DL_CUT boundary and its length is a multiple of 16.
+template <class Item>
+inline bool item_on_grid(const Item &it)
+{
+    return dl_item_shift(it) == 0 && (it.bytes & 15u) == 0;
+}
+
 inline uint32_t log2u(uint32_t v)
 {
     uint32_t l = 0;
     while ((2u << l) <= v) ++l;
     return l;
-}
-
-// Every address and the byte count of the item are multiples of 16.
-inline bool item_aligned16(const dl_plain_item &it)
-{
-    return (((uint64_t)it.src | (uint64_t)it.dst | it.bytes) & 15u) == 0;
-}
-inline bool item_aligned16(const dl_fused_item &it)
-{
-    uint64_t m = (uint64_t)it.src | it.bytes;
-    for (uint32_t j = 0; j < it.k; ++j) m |= (uint64_t)it.dst[j];
-    return (m & 15u) == 0;
 }
 
 // Row path layout of a fused item's destinations: sub-group g of `split` owns
@@ -601,6 +602,8 @@ int launch_klist(const Item *items, size_t n, const uint64_t *tile_end, const dl
         p.item[i] = items[i];
     }
     for (size_t i = n; i < (size_t)NMAX; ++i) p.tile_end[i] = 0xFFFFFFFFu;  // the device compares without looking at n
+    bool on_grid = true;
+    for (size_t i = 0; i < n; ++i) on_grid = on_grid && item_on_grid(items[i]);
     if (sh.rows)
         for (size_t i = 0; i < n; ++i) slots_by_subgroup(p.item[i], sh.split);
     const uint32_t grid = (uint32_t)tile_end[n - 1];
@@ -619,13 +622,13 @@ int launch_klist(const Item *items, size_t n, const uint64_t *tile_end, const dl
         else
             hipLaunchKernelGGL((dl_armed_list_kernel<Item, NMAX, false>), dim3(g), dim3(sh.block_threads), 0, stream, p, a);
     } else if (sh.rows && sh.rows2d_width) {
-        with_policy(sh.policy, [&](auto pol) {
-            hipLaunchKernelGGL((dl_exec_rows2d_kernel<Item, NMAX, decltype(pol)::value>),
+        with_policy_and_grid(sh.policy, on_grid, [&](auto pol, auto og) {
+            hipLaunchKernelGGL((dl_exec_rows2d_kernel<Item, NMAX, decltype(pol)::value, decltype(og)::value>),
                                dim3(sh.rows2d_width, (uint32_t)n), dim3(sh.block_threads), 0, stream, p);
         });
     } else if (sh.rows) {
-        with_policy(sh.policy, [&](auto pol) {
-            hipLaunchKernelGGL((dl_exec_rows_kernel<Item, NMAX, decltype(pol)::value>), dim3(grid),
+        with_policy_and_grid(sh.policy, on_grid, [&](auto pol, auto og) {
+            hipLaunchKernelGGL((dl_exec_rows_kernel<Item, NMAX, decltype(pol)::value, decltype(og)::value>), dim3(grid),
                                dim3(sh.block_threads), 0, stream, p);
         });
     } else if (sh.max_blocks && grid > sh.max_blocks) {
@@ -750,7 +753,7 @@ int stage_slot(size_t s, uint64_t bytes, hipStream_t stream)
     return launch_klist<dl_plain_item, NMAX_SMALL>(&stage, 1, &stage_tiles, ssh, stream, nullptr);
 }
 
-// Long list of equally sized, 16-byte aligned items that moves enough bytes to pay for staging
+// Long list of equally sized items that moves enough bytes to pay for staging
 // its table: the items themselves (not cut into tiles) go to device memory and the row kernel
 // above works on them.  Returns false if the list does not qualify.  (Lists that still fit the
 // kernel arguments, such as the 64 chunks of a uniform all-to-all, were 5-25 % slower this way than
@@ -773,14 +776,20 @@ bool launch_uniform_rows(const Item *items, size_t n, const dl_launch_shape &sh,
     const uint64_t bytes = items[0].bytes;
     uint32_t kmax = 1;
     for (size_t i = 0; i < n; ++i) {
-        if (items[i].bytes != bytes || !item_aligned16(items[i])) return false;
+        if (items[i].bytes != bytes) return false;
         if (item_k(items[i]) > kmax) kmax = item_k(items[i]);
     }
     // a table that needs staging must move enough bytes to pay for it; one written through the BAR needs none
     const bool pushable = g_ring.push && c.table_push && n * sizeof(Item) <= PUSH_PAYLOAD_BYTES;
     if (!pushable && bytes * n < UNIFORM_ROWS_MIN_BYTES) return false;
     const uint32_t tile = 16u * threads / split;  // one 1 KiB row per wavefront of a sub-group
-    const uint64_t tpi = (bytes + tile - 1) / tile;
+    uint64_t tpi = 0;  // of the item that lies worst on its grid; the others leave a workgroup without work
+    bool on_grid = true;
+    for (size_t i = 0; i < n; ++i) {
+        const uint64_t t = dl_item_tiles(items[i], tile);
+        if (t > tpi) tpi = t;
+        on_grid = on_grid && item_on_grid(items[i]);
+    }
     if (tpi * n >= (1ull << 30)) return false;
 
     char *pushed = push_acquire(n * sizeof(Item), stream, rc);
@@ -814,14 +823,14 @@ bool launch_uniform_rows(const Item *items, size_t n, const dl_launch_shape &sh,
         dslot = (const Item *)(g_ring.dev + s * RING_SLOT_BYTES);
     }
     const dl_pushed ps = dl_push_kernel_args(stamp);
-    with_policy(sh.policy, [&](auto pol) {
+    with_policy_and_grid(sh.policy, on_grid, [&](auto pol, auto og) {
         if (pushed)
-            hipLaunchKernelGGL((dl_exec_urows_kernel<Item, decltype(pol)::value, true>), dim3((uint32_t)(tpi * n)),
-                               dim3(threads), 0, stream, dslot, (uint32_t)n, (uint32_t)tpi,
+            hipLaunchKernelGGL((dl_exec_urows_kernel<Item, decltype(pol)::value, true, decltype(og)::value>),
+                               dim3((uint32_t)(tpi * n)), dim3(threads), 0, stream, dslot, (uint32_t)n, (uint32_t)tpi,
                                log2u(threads / 64u / split), log2u(split), ps);
         else
-            hipLaunchKernelGGL((dl_exec_urows_kernel<Item, decltype(pol)::value, false>), dim3((uint32_t)(tpi * n)),
-                               dim3(threads), 0, stream, dslot, (uint32_t)n, (uint32_t)tpi,
+            hipLaunchKernelGGL((dl_exec_urows_kernel<Item, decltype(pol)::value, false, decltype(og)::value>),
+                               dim3((uint32_t)(tpi * n)), dim3(threads), 0, stream, dslot, (uint32_t)n, (uint32_t)tpi,
                                log2u(threads / 64u / split), log2u(split), ps);
     });
     hipError_t e = hipGetLastError();
@@ -849,9 +858,9 @@ int launch_table(const Item *items, size_t n, dl_launch_shape sh, hipStream_t st
         if (launch_uniform_rows(items, n, sh, stream, &rc)) return rc;
     }
     const size_t cap = RING_SLOT_BYTES / sizeof(Item);
-    auto entries = [&](uint32_t tile) {
+    auto entries = [&](uint32_t tile) {  // one per tile of the first destination's grid, like everywhere
         uint64_t m = 0;
-        for (size_t i = 0; i < n; ++i) m += (items[i].bytes + tile - 1) / tile;
+        for (size_t i = 0; i < n; ++i) m += dl_item_tiles(items[i], tile);
         return m;
     };
     // Entries are what a long list pays for (a table in the pinned ring: every workgroup fetches its
@@ -911,7 +920,8 @@ int launch_table(const Item *items, size_t n, dl_launch_shape sh, hipStream_t st
             }
             Item it = items[i];
             advance(it, off);
-            it.bytes = left < sh.tile_bytes ? left : sh.tile_bytes;
+            const uint64_t room = sh.tile_bytes - dl_item_shift(it);  // up to the next tile boundary of the grid
+            it.bytes = left < room ? left : room;
             slot[m++] = it;  // write only: the slot may be device memory behind the BAR
             off += it.bytes;
         }
@@ -940,10 +950,10 @@ int launch_table(const Item *items, size_t n, dl_launch_shape sh, hipStream_t st
             g_dl.armed_words = a.own_word ? g : 1u;
             if (pushed)
                 hipLaunchKernelGGL((dl_armed_table_kernel<Item, true>), dim3(g), dim3(sh.block_threads), 0, stream, slot,
-                                   (uint32_t)m, sh.tile_bytes, sh.split, ps, a);
+                                   (uint32_t)m, sh.split, ps, a);
             else
                 hipLaunchKernelGGL((dl_armed_table_kernel<Item, false>), dim3(g), dim3(sh.block_threads), 0, stream, slot,
-                                   (uint32_t)m, sh.tile_bytes, sh.split, ps, a);
+                                   (uint32_t)m, sh.split, ps, a);
             // whoever wants this memory next must not wait for a request that nobody has triggered
             // (arm->nowait: a chained request's copy kernel does not wait itself, but its gate does)
             if (!arm->nowait) {
@@ -956,12 +966,10 @@ int launch_table(const Item *items, size_t n, dl_launch_shape sh, hipStream_t st
             with_policy(sh.policy, [&](auto pol) {
                 if (pushed)
                     hipLaunchKernelGGL((dl_exec_table_kernel<Item, decltype(pol)::value, true>), dim3((uint32_t)m),
-                                       dim3(sh.block_threads), 0, stream, slot, (uint32_t)m, sh.tile_bytes, sh.split,
-                                       ps);
+                                       dim3(sh.block_threads), 0, stream, slot, (uint32_t)m, sh.split, ps);
                 else
                     hipLaunchKernelGGL((dl_exec_table_kernel<Item, decltype(pol)::value, false>), dim3((uint32_t)m),
-                                       dim3(sh.block_threads), 0, stream, slot, (uint32_t)m, sh.tile_bytes, sh.split,
-                                       ps);
+                                       dim3(sh.block_threads), 0, stream, slot, (uint32_t)m, sh.split, ps);
             });
         }
         DL_HIP(hipGetLastError());
@@ -1032,8 +1040,8 @@ int exec_list(const Item *items, size_t n, hipStream_t stream, const dl_arm *arm
             sh.tile_bytes *= 2;  // keep the grid inside the launch limit
         }
         // row path: a short list (found by a few scalar compares; bisecting a long one per wavefront
-        // measured slower than the general path), aligned items, and a tile that is exactly one
-        // 1 KiB row per wavefront of a sub-group
+        // measured slower than the general path) and a tile that is exactly one 1 KiB row per
+        // wavefront of a sub-group
         sh.rows = n <= (size_t)NMAX_SMALL && sh.tile_bytes == 16u * (sh.block_threads / sh.split) &&
                   !(sh.max_blocks && !arm);
         // ... or, one-shot, a longer list whose items are about equally long: item by item on a
@@ -1049,7 +1057,6 @@ int exec_list(const Item *items, size_t n, hipStream_t stream, const dl_arm *arm
                 sh.rows2d_width = (uint32_t)widest;
             }
         }
-        for (size_t i = 0; i < n && sh.rows; ++i) sh.rows = item_aligned16(items[i]);
         *launched = true;
         if (n <= (size_t)NMAX_SMALL) return launch_klist<Item, NMAX_SMALL>(items, n, tile_end, sh, stream, arm);
         return launch_klist<Item, NBIG>(items, n, tile_end, sh, stream, arm);
@@ -1120,7 +1127,7 @@ int dl_exec_swap(const dl_swap_item *items, size_t n, hipStream_t stream, const 
 }
 
 template <class Item, int NMAX, class Get>
-uint64_t standby_list(dl_klist<Item, NMAX> &l, size_t n, uint32_t max_tiles, uint64_t *rows, Get get)
+uint64_t standby_list(dl_klist<Item, NMAX> &l, size_t n, uint32_t max_tiles, Get get)
 {
     uint64_t acc = 0;
     for (size_t i = 0; i < (size_t)NMAX; ++i) {
@@ -1129,7 +1136,6 @@ uint64_t standby_list(dl_klist<Item, NMAX> &l, size_t n, uint32_t max_tiles, uin
             acc += dl_item_tiles(it, DL_STANDBY_TILE);
             if (acc > max_tiles) return 0;  // one tile per workgroup, one pass
             l.item[i] = it;
-            if (!item_aligned16(it)) *rows = 0;
         }
         l.tile_end[i] = i < n ? (uint32_t)acc : 0xFFFFFFFFu;
     }
@@ -1150,16 +1156,15 @@ uint32_t dl_standby_fill(void *rec_mem, const dl_plan_item *items, size_t n, uin
     const dl_fused_item *it = reinterpret_cast<const dl_fused_item *>(items);
     static dl_standby_rec r;  // 2 KiB: not on the stack of every call
     uint64_t acc, used;
-    r.rows = 1;
     if (n <= 8) {
         r.plain = 0;
-        acc = standby_list(r.list, n, max_tiles, &r.rows, [&](size_t i) { return it[i]; });
+        acc = standby_list(r.list, n, max_tiles, [&](size_t i) { return it[i]; });
         used = offsetof(dl_standby_rec, list) + sizeof r.list;
     } else {
         for (size_t i = 0; i < n; ++i)
             if (it[i].k != 1) return 0;
         r.plain = 1;
-        acc = standby_list(r.copies, n, max_tiles, &r.rows,
+        acc = standby_list(r.copies, n, max_tiles,
                            [&](size_t i) { return dl_plain_item{it[i].src, it[i].dst[0], it[i].bytes}; });
         used = offsetof(dl_standby_rec, copies) + sizeof r.copies;
     }
@@ -1187,29 +1192,31 @@ int dl_standby_launch(void *rec_mem, const dl_arm *a, hipStream_t stream)
     return DL_OK;
 }
 
-int dl_launch_fused_rows_table(const dl_fused_item *dev_items, uint32_t n, uint64_t item_bytes, hipStream_t stream)
+int dl_launch_fused_rows_table(const dl_fused_item *dev_items, uint32_t n, uint64_t item_bytes, uint32_t max_shift,
+                               hipStream_t stream)
 {
     // the table's destinations are laid out for DL_TABLE_ROWS_SPLIT sub-groups (see slots_by_subgroup)
     const uint32_t split = DL_TABLE_ROWS_SPLIT, threads = DL_TABLE_ROWS_THREADS, tile = 16u * threads / split;
-    const uint64_t tpi = (item_bytes + tile - 1) / tile;
-    if (n == 0 || tpi * n >= (1ull << 30)) return DL_ERR_INVALID;
+    const uint64_t tpi = (item_bytes + max_shift + tile - 1) / tile;
+    if (n == 0 || max_shift >= DL_CUT || tpi * n >= (1ull << 30)) return DL_ERR_INVALID;
     const dl_launch_shape sh = dl_choose_shape((uint64_t)n * item_bytes, item_bytes, 8);
-    with_policy(sh.policy, [&](auto pol) {
-        hipLaunchKernelGGL((dl_exec_urows_kernel<dl_fused_item, decltype(pol)::value>), dim3((uint32_t)(tpi * n)),
-                           dim3(threads), 0, stream, dev_items, n, (uint32_t)tpi, log2u(threads / 64u / split),
-                           log2u(split), dl_push_kernel_args(0));
+    // (rows of the token dispatch: row length and buffers are multiples of 16, so no shift means "on the grid")
+    with_policy_and_grid(sh.policy, max_shift == 0 && (item_bytes & 15u) == 0, [&](auto pol, auto og) {
+        hipLaunchKernelGGL((dl_exec_urows_kernel<dl_fused_item, decltype(pol)::value, false, decltype(og)::value>),
+                           dim3((uint32_t)(tpi * n)), dim3(threads), 0, stream, dev_items, n, (uint32_t)tpi,
+                           log2u(threads / 64u / split), log2u(split), dl_push_kernel_args(0));
     });
     DL_HIP(hipGetLastError());
     return DL_OK;
 }
 
-int dl_launch_plain_table(const dl_plain_item *dev_items, uint32_t m, uint32_t tile_bytes, uint64_t moved, hipStream_t stream)
+int dl_launch_plain_table(const dl_plain_item *dev_items, uint32_t m, uint32_t entry_bytes, uint64_t moved, hipStream_t stream)
 {
     if (m == 0) return DL_OK;
-    const dl_launch_shape sh = dl_choose_shape(moved / 2, tile_bytes, 1);  // for the cache policy
+    const dl_launch_shape sh = dl_choose_shape(moved / 2, entry_bytes, 1);  // for the cache policy
     with_policy(sh.policy, [&](auto pol) {
         hipLaunchKernelGGL((dl_exec_table_kernel<dl_plain_item, decltype(pol)::value, false>), dim3(m), dim3(256), 0,
-                           stream, dev_items, m, tile_bytes, 1u, dl_push_kernel_args(0));
+                           stream, dev_items, m, 1u, dl_push_kernel_args(0));
     });
     DL_HIP(hipGetLastError());
     return DL_OK;

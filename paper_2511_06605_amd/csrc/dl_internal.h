@@ -147,12 +147,15 @@ char *dl_push_acquire(size_t bytes, hipStream_t stream, int *rc);
 int dl_push_commit(hipStream_t stream);
 
 // dl_exec.hip: the row kernel over a table of n equally sized read-once/write-k items that is already in
-// device memory, destinations laid out for DL_TABLE_ROWS_SPLIT sub-groups (see slots_by_subgroup).
-int dl_launch_fused_rows_table(const dl_fused_item *dev_items, uint32_t n, uint64_t item_bytes, hipStream_t stream);
+// device memory, destinations laid out for DL_TABLE_ROWS_SPLIT sub-groups (see slots_by_subgroup).  max_shift: no
+// item's first destination lies further than this behind a DL_CUT boundary (0: they all stand on one); every item
+// gets the workgroups that the worst position allowed by it needs.
+int dl_launch_fused_rows_table(const dl_fused_item *dev_items, uint32_t n, uint64_t item_bytes, uint32_t max_shift,
+                               hipStream_t stream);
 
-// dl_exec.hip: the table kernel over m one-tile plain copies that are already in device memory (entry b is
-// workgroup b's), with the cache policy that suits `moved` bytes read + written.
-int dl_launch_plain_table(const dl_plain_item *dev_items, uint32_t m, uint32_t tile_bytes, uint64_t moved, hipStream_t stream);
+// dl_exec.hip: the table kernel over m plain copies of at most entry_bytes (< 2^32) each that are already in device
+// memory (entry b is workgroup b's), with the cache policy that suits `moved` bytes read + written.
+int dl_launch_plain_table(const dl_plain_item *dev_items, uint32_t m, uint32_t entry_bytes, uint64_t moved, hipStream_t stream);
 
 // dl_static.hip: the address of this device's copy of the static table (dl_batch_copy_static).
 int dl_static_init(int device);

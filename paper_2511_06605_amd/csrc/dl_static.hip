@@ -64,10 +64,11 @@ extern "C" int dl_batch_copy_static(const dl_copy_desc *desc, size_t n, void *st
         if (desc[i].bytes > biggest) biggest = desc[i].bytes;
     }
     if (total == 0) return DL_OK;
-    auto entries = [&](uint64_t tile) {
+    auto entries = [&](uint64_t tile) {  // a copy is cut on the grid of its destination, like everywhere (see dl_work.h)
         uint64_t m = 0;
         for (size_t i = 0; i < n; ++i)
-            if (desc[i].bytes && desc[i].src != desc[i].dst) m += (desc[i].bytes + tile - 1) / tile;
+            if (desc[i].bytes && desc[i].src != desc[i].dst)
+                m += dl_item_tiles(dl_plain_item{(const char *)desc[i].src, (char *)desc[i].dst, desc[i].bytes}, (uint32_t)tile);
         return m;
     };
     // as for the ordinary long list: one entry per copy up to 64 KiB, 64 KiB tiles above that, coarser while
@@ -95,9 +96,10 @@ extern "C" int dl_batch_copy_static(const dl_copy_desc *desc, size_t n, void *st
     };
     for (size_t i = 0; i < n; ++i) {
         if (desc[i].bytes == 0 || desc[i].src == desc[i].dst) continue;
-        for (uint64_t off = 0; off < desc[i].bytes; off += tile) {
+        uint64_t piece = tile - ((uint64_t)desc[i].dst & (DL_CUT - 1u));  // the first one ends on the grid
+        for (uint64_t off = 0; off < desc[i].bytes; off += piece, piece = tile) {
             const uint64_t left = desc[i].bytes - off;
-            c.item[c.n++] = dl_plain_item{(const char *)desc[i].src + off, (char *)desc[i].dst + off, left < tile ? left : tile};
+            c.item[c.n++] = dl_plain_item{(const char *)desc[i].src + off, (char *)desc[i].dst + off, left < piece ? left : piece};
             ++m;
             if (c.n == 64) {
                 const int rc = flush();

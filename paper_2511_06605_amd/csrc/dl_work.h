@@ -48,55 +48,39 @@ struct dl_fused_item {
     char *dst[DL_FAN];
 };
 
-// How one item is moved.  The widest element size E in {16, 4, 1} for which the
-// source and every destination agree modulo E; `head` bytes bring the source
-// (and so every destination) to an E boundary, `body` counts E-byte elements,
-// `tail` bytes remain.  Tiles cut the body only; tile 0 also moves head and tail.
-struct dl_geom {
-    uint32_t esize;  // 16, 4 or 1
-    uint32_t head;   // < esize
-    uint32_t tail;   // < esize
-    uint64_t body;   // elements
-};
+// How an item is cut into tiles.  Tiles lie on a grid of DL_CUT bytes of the item's first destination: with
+// shift = that address modulo DL_CUT, tile t of a tile size T (a multiple of DL_CUT) covers the item's bytes
+// [t T - shift, (t + 1) T - shift), clipped to [0, bytes).  So every tile but an item's first begins on a
+// DL_CUT boundary of the first destination, whatever the addresses are, and no two workgroups write into the
+// same 128 bytes of it (partly written lines that two compute units share cost a third of the all-gather rate);
+// the other destinations and the source may lie anywhere relative to that grid (16-byte accesses need no
+// alignment on this hardware).
+constexpr uint32_t DL_CUT = 128;
 
-DL_HD dl_geom dl_make_geom(uint64_t src, uint64_t diff_or, uint64_t bytes)
+DL_HD uint32_t dl_item_shift(const dl_plain_item &it)
 {
-    // diff_or = OR over destinations of (src XOR dst): its low bits are zero
-    // exactly where all addresses agree.
-    dl_geom g;
-    g.esize = ((diff_or & 15) == 0) ? 16u : ((diff_or & 3) == 0) ? 4u : 1u;
-    uint64_t head = (0 - src) & (g.esize - 1);
-    if (head > bytes) head = bytes;
-    g.head = (uint32_t)head;
-    g.body = (bytes - head) / g.esize;
-    g.tail = (uint32_t)(bytes - head - g.body * g.esize);
-    return g;
+    return (uint32_t)((uint64_t)it.dst & (DL_CUT - 1u));
 }
 
-// Number of tiles of an item (at least 1 for a non-empty item, so that head and
-// tail bytes always have an owner).
-DL_HD uint64_t dl_geom_tiles(const dl_geom &g, uint32_t tile_bytes)
+DL_HD uint32_t dl_item_shift(const dl_fused_item &it)
 {
-    uint64_t per_tile = tile_bytes / g.esize;
-    uint64_t t = (g.body + per_tile - 1) / per_tile;
-    return t ? t : 1;
+    return (uint32_t)((uint64_t)it.dst[0] & (DL_CUT - 1u));
 }
 
-DL_HD uint64_t dl_item_diff(const dl_plain_item &it)
-{
-    return (uint64_t)it.src ^ (uint64_t)it.dst;
-}
-
-DL_HD uint64_t dl_item_diff(const dl_fused_item &it)
-{
-    uint64_t d = 0;
-    for (uint32_t j = 0; j < it.k && j < (uint32_t)DL_FAN; ++j) d |= (uint64_t)it.src ^ (uint64_t)it.dst[j];
-    return d;
-}
-
+// Number of tiles of an item (0 for an empty one).
 template <class Item>
 DL_HD uint64_t dl_item_tiles(const Item &it, uint32_t tile_bytes)
 {
     if (it.bytes == 0) return 0;
-    return dl_geom_tiles(dl_make_geom((uint64_t)it.src, dl_item_diff(it), it.bytes), tile_bytes);
+    const uint64_t span = it.bytes + dl_item_shift(it);
+    return span / tile_bytes + (span % tile_bytes ? 1u : 0u);
+}
+
+// Bytes [*lo, *hi) of an item that tile `tile` covers (*lo >= *hi: none).
+DL_HD void dl_tile_range(uint32_t shift, uint64_t bytes, uint64_t tile, uint32_t tile_bytes, uint64_t *lo, uint64_t *hi)
+{
+    const uint64_t begin = tile * tile_bytes;  // on the grid; the item starts `shift` bytes into tile 0
+    *lo = begin > shift ? begin - shift : 0;
+    const uint64_t end = begin + tile_bytes - shift;
+    *hi = end < bytes ? end : bytes;
 }

@@ -428,6 +428,28 @@ def test_armed_on_callers_stream_after_its_producer(ref, armed):
         assert np.array_equal(o.cpu().numpy(), want)
 
 
+@pytest.mark.parametrize("k", [3, 4, 7])
+def test_forced_shape_with_sub_groups_and_several_passes(ref, armed, k):
+    """A forced tile and workgroup size under which a fan-out of 3 or 4 is shared out over two sub-groups of
+    the workgroup, in a request long enough for several passes of the waiting grid: every destination is written."""
+    base = dl.dl_get_config()
+    saved = {f[0]: getattr(base, f[0]) for f in base._fields_}
+    dl.dl_set_config(tile_bytes=2048, block_threads=256)
+    try:
+        n = 1 * MiB + 48
+        src = inputs.payload(np.random.default_rng(k), n)
+        d_src = DevBuf(n, fill=src)
+        d_dst = [DevBuf(n) for _ in range(k)]
+        sync()
+        dl.dl_broadcast(d_src.ptr(), [b.ptr() for b in d_dst], n)
+        fire()
+    finally:
+        dl.dl_set_config(**saved)
+    for j, b in enumerate(d_dst):
+        assert np.array_equal(b.host(), src), f"destination {j}"
+        assert b.guards_intact()
+
+
 def test_phase_stamps_are_ordered_and_clock_relates_to_host(ref, armed):
     import time
     rate, host_ns_at_tick0 = dl.dl_trace_clock()

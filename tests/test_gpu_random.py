@@ -54,15 +54,18 @@ def size(rng, top):
 
 
 def shifts(rng, n):
-    """Per-buffer misalignment: mostly none; else all alike, or agreeing modulo 4, or arbitrary."""
-    kind = rng.choice(["none", "none", "same", "mod4", "any"])
+    """Per-buffer misalignment (DevBuf allows up to 127 bytes): mostly none; else all alike, or multiples of 4 or
+    of 16 (off the 128-byte grid that tiles are cut on, whole vectors), or arbitrary."""
+    kind = rng.choice(["none", "none", "same", "mod4", "mod16", "any"])
     if kind == "none":
         return [0] * n
     if kind == "same":
-        return [int(rng.integers(1, 16))] * n
+        return [int(rng.integers(1, 128))] * n
     if kind == "mod4":
-        return [4 * int(rng.integers(0, 4)) for _ in range(n)]
-    return [int(rng.integers(0, 16)) for _ in range(n)]
+        return [4 * int(rng.integers(0, 32)) for _ in range(n)]
+    if kind == "mod16":
+        return [16 * int(rng.integers(0, 8)) for _ in range(n)]
+    return [int(rng.integers(0, 128)) for _ in range(n)]
 
 
 def finish(mode, ticket_before):

@@ -275,19 +275,30 @@ def test_hazard_validator_fanout_and_touching():
 
 
 def test_tile_count():
-    """Tiles cut the body of whole elements; head and tail bytes ride on tile 0."""
-    a = 1 << 20  # an opaque 16-byte aligned address
+    """Tiles lie on the grid of the first destination: an item whose first destination stands s bytes behind a
+    128-byte boundary takes ceil((bytes + s) / tile) tiles, whatever the source and the other destinations are."""
+    a = 1 << 20  # an opaque address on every grid
     it = lambda s, d, n: dict(src=s, bytes=n, dst=list(d))
     T = 4096
     assert dl.dl_plan_tiles([it(a, [a + (1 << 16)], 4096)], T) == 1
-    assert dl.dl_plan_tiles([it(a, [a + (1 << 16)], 4097)], T) == 1        # 256 vectors + 1 tail byte
+    assert dl.dl_plan_tiles([it(a, [a + (1 << 16)], 4097)], T) == 2        # one byte in a tile of its own
     assert dl.dl_plan_tiles([it(a, [a + (1 << 16)], 4096 + 16)], T) == 2
-    assert dl.dl_plan_tiles([it(a, [a + (1 << 16)], 5)], T) == 1           # tail only
+    assert dl.dl_plan_tiles([it(a, [a + (1 << 16)], 5)], T) == 1
     assert dl.dl_plan_tiles([it(a, [a + (1 << 16)], 0)], T) == 0
-    assert dl.dl_plan_tiles([it(a + 3, [a + (1 << 16) + 3], 13 + 4096 + 16)], T) == 2  # 13 head bytes
-    # addresses that agree only modulo 4, then not at all: narrower elements, same byte tile
-    assert dl.dl_plan_tiles([it(a, [a + (1 << 16) + 4], 3 * 4096)], T) == 3
-    assert dl.dl_plan_tiles([it(a, [a + (1 << 16) + 1], 3 * 4096 + 1)], T) == 4
+    # the first destination decides: 3 bytes behind a boundary, the first tile holds 4093 bytes
+    assert dl.dl_plan_tiles([it(a + 3, [a + (1 << 16) + 3], 4093)], T) == 1
+    assert dl.dl_plan_tiles([it(a + 3, [a + (1 << 16) + 3], 4094)], T) == 2
+    assert dl.dl_plan_tiles([it(a, [a + (1 << 16) + 127], 1)], T) == 1
+    assert dl.dl_plan_tiles([it(a, [a + (1 << 16) + 127], 3 * 4096 - 127)], T) == 3
+    assert dl.dl_plan_tiles([it(a, [a + (1 << 16) + 127], 3 * 4096 - 126)], T) == 4
+    # the grid repeats every 128 bytes, not every tile: 128 bytes behind a tile boundary is on the grid
+    assert dl.dl_plan_tiles([it(a, [a + (1 << 16) + 128], 4096)], T) == 1
+    # neither the source nor the later destinations matter
+    assert dl.dl_plan_tiles([it(a + 77, [a + (1 << 16), a + (1 << 17) + 5], 3 * 4096)], T) == 3
+    assert dl.dl_plan_tiles([it(a, [a + (1 << 16) + 4], 3 * 4096)], T) == 4
+    # items add up; a tile size that is not a multiple of 128 is refused
+    assert dl.dl_plan_tiles([it(a, [a + (1 << 16)], 4097), it(a, [a + (1 << 17) + 1], 4096)], T) == 4
+    assert dl.dl_plan_tiles([it(a, [a + (1 << 16)], 4096)], 100) == 0
     # all-gather at 64 MiB per rank, fused, 16 KiB tiles
     B = 64 << 20
     ins = [a + r * B for r in range(8)]
@@ -489,7 +500,7 @@ def test_mode_table_applied_to_the_lowered_collectives():
     of each threshold (W = 8), the uniform all-to-all, the 2 MiB -> 7 broadcast, the 64 x 16 KiB batch."""
     W = 8
     a = np.zeros(1, dtype=np.uint8)
-    base = addr(a)
+    base = addr(a) & ~127  # opaque addresses on the 128-byte grid that tiles are cut on
 
     def ag_mode(B, ahead):
         ins = [base + (1 << 32) * (1 + j) for j in range(W)]
