@@ -121,6 +121,25 @@ __device__ __forceinline__ void dl_st16(char *p, dl_u32x4 v)
         *q = v;
 }
 
+// 16 bytes from an address that is not a multiple of 4, as the five aligned 4-byte words that hold them, shifted
+// into place.  (A 16-byte load from such an address is legal but takes the memory pipeline about twice as long as
+// one from a multiple of 4, which showed where every row is loaded by several wavefronts: the all-gather.)  Up to
+// 3 bytes in front of p and behind p + 16 are read with them and dropped; they lie in 4-byte words that also hold
+// bytes of the source.  `odd` = p modulo 4, from 1 to 3.  Not meant for the system-scope policy, whose loads each
+// wait for their own round trip.
+template <int POL>
+__device__ __forceinline__ dl_u32x4 dl_ld16_shifted(const char *p, uint32_t odd)
+{
+    const dl_u32x4 w = dl_ld16<POL>(p - odd);
+    const uint32_t w4 = dl_ld<POL>(dl_global<uint32_t>(p - odd + 16));
+    dl_u32x4 v;
+    v.x = __builtin_amdgcn_alignbyte(w.y, w.x, odd);
+    v.y = __builtin_amdgcn_alignbyte(w.z, w.y, odd);
+    v.z = __builtin_amdgcn_alignbyte(w.w, w.z, odd);
+    v.w = __builtin_amdgcn_alignbyte(w4, w.w, odd);
+    return v;
+}
+
 // One byte from src + i to the same offset of the first k destinations.
 template <int FAN, int POL>
 __device__ __forceinline__ void dl_copy_byte(const char *src, char *const (&dsts)[FAN], uint32_t k, uint64_t i)
@@ -164,6 +183,40 @@ __device__ __forceinline__ void dl_ld_many(dl_u32x4 (&v)[N], const char *const (
     }
 }
 
+// n 16-byte vectors from s to d[0..K), by nthr threads.  SHIFTED: s is not a multiple of 4 (see dl_ld16_shifted).
+template <int K, int POL, bool SHIFTED>
+__device__ __forceinline__ void dl_copy_vec16_loop(const char *__restrict__ s, char *const (&d)[K], uint32_t n, uint32_t tid,
+                                                   uint32_t nthr, uint32_t odd)
+{
+    uint32_t i = tid;
+    const uint32_t step = nthr * DL_UNROLL;
+    for (; i + (DL_UNROLL - 1) * nthr < n; i += step) {
+        dl_u32x4 v[DL_UNROLL];
+        const char *from[DL_UNROLL];
+#pragma unroll
+        for (int u = 0; u < DL_UNROLL; ++u) from[u] = s + 16ull * (i + u * nthr);
+        if constexpr (SHIFTED) {
+#pragma unroll
+            for (int u = 0; u < DL_UNROLL; ++u) v[u] = dl_ld16_shifted<POL>(from[u], odd);
+        } else {
+            dl_ld_many<POL, DL_UNROLL>(v, from);
+        }
+#pragma unroll
+        for (int u = 0; u < DL_UNROLL; ++u)
+#pragma unroll
+            for (int j = 0; j < K; ++j) dl_st16<POL>(d[j] + 16ull * (i + u * nthr), v[u]);
+    }
+    for (; i < n; i += nthr) {
+        dl_u32x4 v;
+        if constexpr (SHIFTED)
+            v = dl_ld16_shifted<POL>(s + 16ull * i, odd);
+        else
+            v = dl_ld16<POL>(s + 16ull * i);
+#pragma unroll
+        for (int j = 0; j < K; ++j) dl_st16<POL>(d[j] + 16ull * i, v);
+    }
+}
+
 // n 16-byte vectors from s to the same offsets of the first K of the destinations, by nthr threads.
 template <int K, int FAN, int POL>
 __device__ __forceinline__ void dl_copy_vec16(const char *__restrict__ s, char *const (&dsts)[FAN], uint64_t byte_off,
@@ -174,25 +227,15 @@ __device__ __forceinline__ void dl_copy_vec16(const char *__restrict__ s, char *
     char *d[K];
 #pragma unroll
     for (int j = 0; j < K; ++j) d[j] = dsts[j] + byte_off;
-
-    uint32_t i = tid;
-    const uint32_t step = nthr * DL_UNROLL;
-    for (; i + (DL_UNROLL - 1) * nthr < n; i += step) {
-        dl_u32x4 v[DL_UNROLL];
-        const char *from[DL_UNROLL];
-#pragma unroll
-        for (int u = 0; u < DL_UNROLL; ++u) from[u] = s + 16ull * (i + u * nthr);
-        dl_ld_many<POL, DL_UNROLL>(v, from);
-#pragma unroll
-        for (int u = 0; u < DL_UNROLL; ++u)
-#pragma unroll
-            for (int j = 0; j < K; ++j) dl_st16<POL>(d[j] + 16ull * (i + u * nthr), v[u]);
+    if constexpr (POL != DL_POL_COHERENT) {
+        // every load address is the same modulo 4
+        const uint32_t odd = __builtin_amdgcn_readfirstlane((uint32_t)(uint64_t)s & 3u);
+        if (odd) {
+            dl_copy_vec16_loop<K, POL, true>(s, d, n, tid, nthr, odd);
+            return;
+        }
     }
-    for (; i < n; i += nthr) {
-        const dl_u32x4 v = dl_ld16<POL>(s + 16ull * i);
-#pragma unroll
-        for (int j = 0; j < K; ++j) dl_st16<POL>(d[j] + 16ull * i, v);
-    }
+    dl_copy_vec16_loop<K, POL, false>(s, d, n, tid, nthr, 0u);
 }
 
 // Move bytes [lo, hi) of the copy (src -> dsts[0..k)), all threads of the workgroup taking part: up to 15 bytes
@@ -494,6 +537,11 @@ __device__ __forceinline__ void dl_rows_body(const Item &it, uint32_t tile, uint
     const uint64_t bytes = it.bytes;
     const bool ragged = ON_GRID ? false : dl_item_ragged(it);
     const uint64_t byte = ((row << 10) - (ON_GRID ? 0u : dl_item_shift(it))) + (lane << 4);
+    // every lane's source address is the same modulo 4: not zero -> dl_ld16_shifted (not at system scope, and not
+    // for swaps, which load both sides)
+    uint32_t odd = 0;
+    if constexpr (POL != DL_POL_COHERENT)
+        odd = __builtin_amdgcn_readfirstlane(((uint32_t)(uint64_t)src - dl_item_shift(it)) & 3u);
     uint64_t lo = 0, hi = 0;
     if constexpr (std::is_same<Item, dl_swap_item>::value) {
         char *pa = const_cast<char *>(src);
@@ -526,7 +574,10 @@ __device__ __forceinline__ void dl_rows_body(const Item &it, uint32_t tile, uint
                 return;
             }
         }
-        dl_st16<POL>(dst + byte, dl_ld16<POL>(src + byte));
+        if (odd)
+            dl_st16<POL>(dst + byte, dl_ld16_shifted<POL>(src + byte, odd));
+        else
+            dl_st16<POL>(dst + byte, dl_ld16<POL>(src + byte));
     } else {
         const uint32_t slots = (uint32_t)DL_FAN >> sl;
         const uint32_t base = (wave >> wl) * slots;
@@ -549,7 +600,11 @@ __device__ __forceinline__ void dl_rows_body(const Item &it, uint32_t tile, uint
                 return;
             }
         }
-        const dl_u32x4 v = dl_ld16<POL>(src + byte);
+        dl_u32x4 v;
+        if (odd)
+            v = dl_ld16_shifted<POL>(src + byte, odd);
+        else
+            v = dl_ld16<POL>(src + byte);
         dl_st16<POL>(d0 + byte, v);
         if (!d1) return;
         dl_st16<POL>(d1 + byte, v);
