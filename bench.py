@@ -35,7 +35,7 @@ HBM_PEAK_GBS = 8000.0
 # for a plain copy of known size.  Valid only for the kernel sources whose digest is given; with
 # any other sources the figure is reported as null until the counters are taken again.
 KERNEL_SOURCES = ["dl_work.h", "dl_device.h", "dl_exec.hip"]
-MEASURED_TRAFFIC = {"sources_sha256": "e1610e33587dd5ee4c8934b3dab5b4288083bf5c9783345b808710bafdeed8f8", "bytes_per_rank": 64 * MiB, "bytes_per_launch": 4831892063}
+MEASURED_TRAFFIC = {"sources_sha256": "7941b4c46542cb9c77d48d48e8ec826ed1786a5c6b182c45104fe0531c7810d1", "bytes_per_rank": 64 * MiB, "bytes_per_launch": 4831894846}
 
 
 def kernel_sources_digest() -> str:
@@ -387,6 +387,30 @@ def other_operations(dl, benchaid, inputs, torch, stream, ag_reqs, ag_bufs, ag_s
     row["memcpy_async_per_copy_host_us"] = lat_stats(benchaid.time_host(req, stream, benchaid.WAIT_STREAM, 5, 50))
     armed_cases.append((row, benchaid.copy_list_request(dlist, benchaid.OP_BATCH), arena))
     res["batch_b2b"] = row
+
+    # requests that do not stand on any grid: an all-gather of 16 MiB - 32 bytes per rank (so that every rank's share
+    # of a receive buffer begins off the 128-byte lines) with the send and receive buffers moved by a few bytes, and
+    # 64 copies of 4 MiB - 32 bytes; GB/s of algorithmic read + write traffic
+    rows = []
+    n = 16 * MiB - 32
+    s_in = [torch.empty(n + 256, dtype=torch.uint8, device="cuda").random_(0, 256) for _ in range(W)]
+    s_out = [torch.empty(W * n + 256, dtype=torch.uint8, device="cuda") for _ in range(W)]
+    for so, do in ((0, 0), (4, 0), (1, 0), (0, 1), (5, 2), (0, 16)):
+        req = benchaid.allgather_request([t[so:] for t in s_in], [t[do:] for t in s_out], n)
+        row = {"op": "allgather", "bytes_per_rank": n, "send_shift": so, "recv_shift": do}
+        row.update(timed(req, (W + W * W) * n, False, calls=20))
+        rows.append(row)
+    del s_in, s_out
+    n = 4 * MiB - 32
+    c_in = [torch.empty(n + 256, dtype=torch.uint8, device="cuda").random_(0, 256) for _ in range(64)]
+    c_out = [torch.empty(n + 256, dtype=torch.uint8, device="cuda") for _ in range(64)]
+    for so, do in ((0, 0), (1, 0), (0, 1), (7, 2)):
+        req = benchaid.copy_list_request([(x[so:], y[do:], n) for x, y in zip(c_in, c_out)], benchaid.OP_BATCH)
+        row = {"op": "batch_copy", "copies": 64, "copy_bytes": n, "src_shift": so, "dst_shift": do}
+        row.update(timed(req, 2 * 64 * n, False, calls=20))
+        rows.append(row)
+    del c_in, c_out
+    res["off_grid"] = rows
 
     # the latency-bound cases again in prelaunch mode (doorbell -> completion word) and in signal mode
     # (call -> completion word, no stream synchronisation); before the sections below create further streams:

@@ -1,12 +1,13 @@
 // Internal: the device-side copy loop (the "copy" phase of Sec. III-B2 executed
 // by compute units) used by both the one-shot and the armed kernels.
 //
-// One tile = a contiguous run of the item's body, read once with 16-byte
-// vector loads (lane l of a wavefront reads bytes 16*l .. 16*l+15 of each
-// 1 KiB row, so every wavefront access is one fully coalesced row) and written
-// from registers to each of the k destinations (the fused broadcast of
-// Sec. IV-B, with k up to 8 instead of 2).  Several loads are issued before the
-// first store so each lane keeps UNROLL requests in flight.
+// One tile = a contiguous run of an item's bytes on the grid of its first
+// destination (see dl_work.h), read once with 16-byte vector loads (lane l of a
+// wavefront reads bytes 16*l .. 16*l+15 of each 1 KiB row, so every wavefront
+// access is one fully coalesced row) and written from registers to each of the
+// k destinations (the fused broadcast of Sec. IV-B, with k up to 8 instead of
+// 2).  Several loads are issued before the first store so each lane keeps
+// UNROLL requests in flight.  No address needs any alignment.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -523,9 +524,9 @@ __device__ __forceinline__ bool dl_item_ragged(const Item &it)
 // the destinations in its sub-group's slots.  At this granularity (a wavefront lives for one load and one or two
 // stores) the per-wavefront instruction count and the dependent scalar loads in front of the vector load decide
 // the rate.  `tile` is the tile's index within the item.
-// ON_GRID: the host has seen that every item's first destination stands on a DL_CUT boundary and that every
-// length is a multiple of 16.  Nothing of the above is computed then; the dozen scalar instructions that it
-// takes cost the all-gather of 4 .. 64 MiB per rank 1-2.5 % of its rate.
+// ON_GRID: the host has seen that every item's first destination stands on a DL_CUT boundary, that every
+// length is a multiple of 16 and every source a multiple of 4.  Nothing of the above is computed then; the dozen
+// scalar instructions that it takes cost the all-gather of 4 .. 64 MiB per rank 1-2.5 % of its rate.
 template <int POL, bool ON_GRID = false, class Item>
 __device__ __forceinline__ void dl_rows_body(const Item &it, uint32_t tile, uint32_t wl, uint32_t sl)
 {
@@ -536,12 +537,13 @@ __device__ __forceinline__ void dl_rows_body(const Item &it, uint32_t tile, uint
     const char *src = it.src;
     const uint64_t bytes = it.bytes;
     const bool ragged = ON_GRID ? false : dl_item_ragged(it);
-    const uint64_t byte = ((row << 10) - (ON_GRID ? 0u : dl_item_shift(it))) + (lane << 4);
+    const uint32_t shift = ON_GRID ? 0u : dl_item_shift(it);
+    const uint64_t byte = ((row << 10) - shift) + (lane << 4);
     // every lane's source address is the same modulo 4: not zero -> dl_ld16_shifted (not at system scope, and not
     // for swaps, which load both sides)
     uint32_t odd = 0;
-    if constexpr (POL != DL_POL_COHERENT)
-        odd = __builtin_amdgcn_readfirstlane(((uint32_t)(uint64_t)src - dl_item_shift(it)) & 3u);
+    if constexpr (POL != DL_POL_COHERENT && !ON_GRID)
+        odd = __builtin_amdgcn_readfirstlane(((uint32_t)(uint64_t)src - shift) & 3u);
     uint64_t lo = 0, hi = 0;
     if constexpr (std::is_same<Item, dl_swap_item>::value) {
         char *pa = const_cast<char *>(src);

@@ -524,11 +524,11 @@ inline void with_policy_and_grid(int policy, bool on_grid, F f)
     });
 }
 
-// The item's first destination stands on a DL_CUT boundary and its length is a multiple of 16.
+// The item's first destination stands on a DL_CUT boundary, its length is a multiple of 16 and its source one of 4.
 template <class Item>
 inline bool item_on_grid(const Item &it)
 {
-    return dl_item_shift(it) == 0 && (it.bytes & 15u) == 0;
+    return dl_item_shift(it) == 0 && (it.bytes & 15u) == 0 && ((uint64_t)it.src & 3u) == 0;
 }
 
 inline uint32_t log2u(uint32_t v)
