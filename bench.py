@@ -395,6 +395,8 @@ def other_operations(dl, benchaid, inputs, torch, stream, ag_reqs, ag_bufs, ag_s
     n = 16 * MiB - 32
     s_in = [torch.empty(n + 256, dtype=torch.uint8, device="cuda").random_(0, 256) for _ in range(W)]
     s_out = [torch.empty(W * n + 256, dtype=torch.uint8, device="cuda") for _ in range(W)]
+    # (fresh buffers, and the device has idled while they were filled: 40 untimed calls first, or the first rows read 8 % low)
+    benchaid.time_device(benchaid.allgather_request(s_in, s_out, n), stream, warmup=40, calls=1)
     for so, do in ((0, 0), (4, 0), (1, 0), (0, 1), (5, 2), (0, 16)):
         req = benchaid.allgather_request([t[so:] for t in s_in], [t[do:] for t in s_out], n)
         row = {"op": "allgather", "bytes_per_rank": n, "send_shift": so, "recv_shift": do}
