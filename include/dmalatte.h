@@ -495,8 +495,8 @@ int dl_token_dispatch(const void *const *in, void *const *out, int W, const uint
  * `stream`, ordered behind whatever produced the mask there.  Always executed
  * as in DL_MODE_ONESHOT.  The host does not learn how many rows each rank
  * receives: out[j] must have room for what the mask sends it (at most all
- * tokens).  Limits: exactly 8 ranks, row_bytes a multiple of 16, buffers
- * 16-byte aligned (DL_ERR_INVALID otherwise); at most
+ * tokens).  Rows and buffers may have any length and alignment.  Limits:
+ * exactly 8 ranks (DL_ERR_INVALID otherwise); at most
  * DL_DISPATCH_DEVICE_MAX_TOKENS tokens in all (one slot of the library's table
  * memory holds their copy list; more: DL_ERR_CAPACITY, nothing is enqueued).
  */

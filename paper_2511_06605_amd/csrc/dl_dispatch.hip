@@ -169,12 +169,22 @@ __global__ void __launch_bounds__(BUILD_THREADS) dl_dispatch_build_kernel(const 
 }
 
 // How far behind a DL_CUT boundary the first destination of a row can lie: rows stand whole multiples of
-// row_bytes into the receive buffers, and all of these are multiples of 16.
+// row_bytes into the receive buffers, so every such address is a multiple of the largest power of two that
+// divides row_bytes and all of the buffers' addresses.
 uint32_t worst_shift(void *const *out, int W, size_t row_bytes)
 {
     uint64_t m = row_bytes;
     for (int i = 0; i < W; ++i) m |= (uint64_t)out[i];
-    return (m & (DL_CUT - 1u)) ? DL_CUT - 16u : 0u;
+    m &= DL_CUT - 1u;
+    return m ? DL_CUT - (uint32_t)(m & (0 - m)) : 0u;
+}
+
+// Every row lies as the on-grid instance of the row kernel wants it (see dl_rows_body).
+bool rows_on_grid(const void *const *in, void *const *out, int W, size_t row_bytes)
+{
+    uint64_t m = row_bytes & 3u;
+    for (int i = 0; i < W; ++i) m |= (uint64_t)in[i] & 3u;
+    return m == 0 && (row_bytes & 15u) == 0 && worst_shift(out, W, row_bytes) == 0;
 }
 
 }  // namespace
@@ -186,11 +196,10 @@ int dl_dispatch_on_device(const void *const *in, void *const *out, int W, const 
     const dl_config &c = g_dl.cfg;
     if (W != DISPATCH_W || !in || !out || !tokens || !dest) return DL_OK;
     if (c.tile_bytes || c.block_threads || c.max_blocks || (c.fan_split != 0 && c.fan_split != DL_TABLE_ROWS_SPLIT)) return DL_OK;
-    if (row_bytes == 0 || (row_bytes & 15u)) return DL_OK;
+    if (row_bytes == 0) return DL_OK;
     uint64_t total = 0;
     for (int i = 0; i < W; ++i) {
         total += tokens[i];
-        if (((uint64_t)in[i] | (uint64_t)out[i]) & 15u) return DL_OK;
         if ((tokens[i] && !in[i]) || !out[i]) return DL_OK;  // the host lowering reports what is wrong
     }
     // worth two small launches only for many tokens; mask, block counts and item table share one ring slot
@@ -267,7 +276,8 @@ int dl_dispatch_on_device(const void *const *in, void *const *out, int W, const 
         rc = dl_push_commit(stream);
         if (rc != DL_OK) return rc;
     }
-    rc = dl_launch_fused_rows_table(items, (uint32_t)total, row_bytes, worst_shift(out, W, row_bytes), stream);
+    rc = dl_launch_fused_rows_table(items, (uint32_t)total, row_bytes, worst_shift(out, W, row_bytes),
+                                    rows_on_grid(in, out, W, row_bytes), stream);
     if (rc != DL_OK) return rc;
     return dl_ring_release(slot, stream);
 }
@@ -282,14 +292,12 @@ extern "C" int dl_token_dispatch_device(const void *const *in, void *const *out,
     if (!g_dl.inited) return DL_ERR_STATE;
     if (dl_device_error_pending()) return DL_ERR_LOST;
     if (W != DISPATCH_W || !in || !out || !tokens) return DL_ERR_INVALID;
-    if (row_bytes & 15u) return DL_ERR_INVALID;
     uint64_t total = 0;
     for (int i = 0; i < W; ++i) total += tokens[i];
     if (total == 0 || row_bytes == 0) return DL_OK;
     if (!dest_device || ((uint64_t)dest_device & 7u)) return DL_ERR_INVALID;
     for (int i = 0; i < W; ++i) {
         if ((tokens[i] && !in[i]) || !out[i]) return DL_ERR_INVALID;
-        if (((uint64_t)in[i] | (uint64_t)out[i]) & 15u) return DL_ERR_INVALID;
     }
     if (total > DL_DISPATCH_DEVICE_MAX_TOKENS) return DL_ERR_CAPACITY;
     const uint64_t blocks = (total + BUILD_THREADS - 1) / BUILD_THREADS;
@@ -323,7 +331,8 @@ extern "C" int dl_token_dispatch_device(const void *const *in, void *const *out,
     hipLaunchKernelGGL((dl_dispatch_build_kernel<false, true>), dim3((uint32_t)blocks), dim3(BUILD_THREADS), 0, hs,
                        dest_device, (const uint32_t *)counts, a, items, dl_push_kernel_args(0));
     DL_HIP(hipGetLastError());
-    rc = dl_launch_fused_rows_table(items, (uint32_t)total, row_bytes, worst_shift(out, W, row_bytes), hs);
+    rc = dl_launch_fused_rows_table(items, (uint32_t)total, row_bytes, worst_shift(out, W, row_bytes),
+                                    rows_on_grid(in, out, W, row_bytes), hs);
     if (rc != DL_OK) return rc;
     t_dl_last.mode = DL_MODE_ONESHOT;
     return dl_ring_release(slot, hs);

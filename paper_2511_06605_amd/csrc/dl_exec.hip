@@ -1193,15 +1193,14 @@ int dl_standby_launch(void *rec_mem, const dl_arm *a, hipStream_t stream)
 }
 
 int dl_launch_fused_rows_table(const dl_fused_item *dev_items, uint32_t n, uint64_t item_bytes, uint32_t max_shift,
-                               hipStream_t stream)
+                               bool on_grid, hipStream_t stream)
 {
     // the table's destinations are laid out for DL_TABLE_ROWS_SPLIT sub-groups (see slots_by_subgroup)
     const uint32_t split = DL_TABLE_ROWS_SPLIT, threads = DL_TABLE_ROWS_THREADS, tile = 16u * threads / split;
     const uint64_t tpi = (item_bytes + max_shift + tile - 1) / tile;
     if (n == 0 || max_shift >= DL_CUT || tpi * n >= (1ull << 30)) return DL_ERR_INVALID;
     const dl_launch_shape sh = dl_choose_shape((uint64_t)n * item_bytes, item_bytes, 8);
-    // (rows of the token dispatch: row length and buffers are multiples of 16, so no shift means "on the grid")
-    with_policy_and_grid(sh.policy, max_shift == 0 && (item_bytes & 15u) == 0, [&](auto pol, auto og) {
+    with_policy_and_grid(sh.policy, on_grid && max_shift == 0, [&](auto pol, auto og) {
         hipLaunchKernelGGL((dl_exec_urows_kernel<dl_fused_item, decltype(pol)::value, false, decltype(og)::value>),
                            dim3((uint32_t)(tpi * n)), dim3(threads), 0, stream, dev_items, n, (uint32_t)tpi,
                            log2u(threads / 64u / split), log2u(split), dl_push_kernel_args(0));

@@ -149,9 +149,10 @@ int dl_push_commit(hipStream_t stream);
 // dl_exec.hip: the row kernel over a table of n equally sized read-once/write-k items that is already in
 // device memory, destinations laid out for DL_TABLE_ROWS_SPLIT sub-groups (see slots_by_subgroup).  max_shift: no
 // item's first destination lies further than this behind a DL_CUT boundary (0: they all stand on one); every item
-// gets the workgroups that the worst position allowed by it needs.
+// gets the workgroups that the worst position allowed by it needs.  on_grid: every item lies as the on-grid
+// instance of the row kernel wants it (see dl_rows_body).
 int dl_launch_fused_rows_table(const dl_fused_item *dev_items, uint32_t n, uint64_t item_bytes, uint32_t max_shift,
-                               hipStream_t stream);
+                               bool on_grid, hipStream_t stream);
 
 // dl_exec.hip: the table kernel over m plain copies of at most entry_bytes (< 2^32) each that are already in device
 // memory (entry b is workgroup b's), with the cache policy that suits `moved` bytes read + written.

@@ -24,15 +24,16 @@ def library():
     dl.dl_shutdown()
 
 
-def run(ref, counts, row, seed, top_k=8, mask_value=1, drop=None, kind="u8", check_host_entry=False):
+def run(ref, counts, row, seed, top_k=8, mask_value=1, drop=None, kind="u8", check_host_entry=False, shifts=None):
     import torch
     ins = inputs.token_rows(W, counts, row, seed=seed, kind=kind)
     dest = inputs.moe_token_destinations(W, counts, seed=seed + 1, n_experts=256, top_k=top_k) * np.uint8(mask_value)
     if drop:
         dest[::drop] = 0
     want = ref.token_dispatch(ins, row, dest)
-    d_in = [DevBuf(a.size, fill=a) for a in ins]
-    d_out = [DevBuf(w.size) for w in want]
+    shifts = shifts or [0] * (2 * W)
+    d_in = [DevBuf(a.size, fill=a, shift=shifts[i]) for i, a in enumerate(ins)]
+    d_out = [DevBuf(w.size, shift=shifts[W + j]) for j, w in enumerate(want)]
     d_mask = torch.from_numpy(np.ascontiguousarray(dest)).cuda()
     tok = [counts] * W if np.isscalar(counts) else list(counts)
     sync()
@@ -68,6 +69,19 @@ def test_moe_hidden_7168_bf16_top8(ref, T):
 ])
 def test_edges(ref, counts, row, top_k, mask_value, drop):
     run(ref, counts, row, seed=sum(counts) + row, top_k=top_k, mask_value=mask_value, drop=drop)
+
+
+@pytest.mark.parametrize("counts,row,top_k,shifts", [
+    ([40] * 8, 1000, 3, None),                                   # rows of whole 8 bytes: every second one off the 16
+    ([100] * 8, 14336 + 2, 8, None),                             # the task's row and one bf16 element more
+    ([64] * 8, 777, 2, None),                                    # an odd row length
+    ([90] * 8, 4096, 4, [0, 1, 2, 3, 16, 32, 64, 127] * 2),      # whole rows, buffers anywhere
+    ([33, 0, 257, 5, 64, 1, 300, 12], 3001, 5, [7, 0, 100, 16, 1, 4, 8, 2, 0, 127, 3, 64, 16, 5, 9, 48]),
+])
+def test_rows_and_buffers_of_any_length_and_alignment(ref, counts, row, top_k, shifts):
+    """Neither the row length nor any buffer address has to be a multiple of anything; the same through the entry point
+    with the mask on the host, which lowers on the device from 512 tokens."""
+    run(ref, counts, row, seed=row + sum(counts), top_k=top_k, shifts=shifts, check_host_entry=True)
 
 
 def test_mask_produced_on_the_stream_just_before(ref):
@@ -111,8 +125,7 @@ def test_limits_and_malformed_requests():
         return dl.DL_OK
 
     assert status(ins=[d.ptr()] * 4, outs=[d.ptr()] * 4, tokens=[2] * 4) == dl.DL_ERR_INVALID   # eight ranks only
-    assert status(row_bytes=24) == dl.DL_ERR_INVALID                                            # rows of whole 16 bytes
-    assert status(ins=[d.ptr(4)] * W) == dl.DL_ERR_INVALID                                      # 16-byte aligned buffers
+    assert status(row_bytes=24) == dl.DL_OK and status(ins=[d.ptr(4)] * W) == dl.DL_OK          # any row length, any address (the mask is empty: nothing moves)
     assert status(dest_device=mask.data_ptr() + 4) == dl.DL_ERR_INVALID                         # 8-byte aligned mask
     assert status(dest_device=None) == dl.DL_ERR_INVALID
     assert status(tokens=[most // W] * (W - 1) + [most // W + 1]) == dl.DL_ERR_CAPACITY         # one token too many
