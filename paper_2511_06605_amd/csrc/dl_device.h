@@ -489,21 +489,26 @@ __device__ __forceinline__ uint32_t dl_find_item(const dl_klist<Item, NMAX> &p, 
 __device__ __forceinline__ const char *dl_item_dst(const dl_plain_item &it, uint32_t) { return it.dst; }
 __device__ __forceinline__ const char *dl_item_dst(const dl_fused_item &it, uint32_t j) { return it.dst[j]; }
 
-// What a lane of the row path owns of an item of `bytes` bytes when its 16 bytes begin at offset `byte` (which
-// has wrapped below zero in front of the item): 0 nothing, 1 all 16 bytes, 2 only bytes [*lo, *hi) (the item
-// begins or ends inside).  ragged: the item's first destination or its length is not a multiple of 16; without
-// that there is no case 2 and one compare decides.
-__device__ __forceinline__ int dl_lane_part(uint64_t byte, uint64_t bytes, bool ragged, uint64_t *lo, uint64_t *hi)
+// The bytes of an item that no lane of the row path moves inside a whole vector: up to 15 in front of the first
+// destination's first 16-byte boundary and up to 15 behind its last one (or the whole of an item that lies inside
+// one vector).  Every wavefront calls this for its row with uniform arguments; if the item begins in that row,
+// lanes 0..14 move the leading bytes, if it ends there, lanes 16..30 move the trailing ones, a byte each, so all of
+// them are in flight together.  each(i) moves byte i of the item.
+template <class Each>
+__device__ __forceinline__ void dl_row_edges(uint32_t shift, uint64_t bytes, uint64_t row, uint32_t lane, Each each)
 {
-    if (!ragged) return byte < bytes ? 1 : 0;
-    const int64_t o = (int64_t)byte;
-    const int64_t l = o < 0 ? 0 : o;
-    const int64_t h = o + 16 < (int64_t)bytes ? o + 16 : (int64_t)bytes;
-    if (l >= h) return 0;
-    if (h - l == 16) return 1;
-    *lo = (uint64_t)l;
-    *hi = (uint64_t)h;
-    return 2;
+    // positions on the grid: the item occupies [shift, end)
+    const uint64_t end = shift + bytes;
+    const uint64_t first_whole = ((uint64_t)shift + 15u) & ~(uint64_t)15u;  // where the first vector inside the item would begin
+    const uint64_t last_part = end & ~(uint64_t)15u;                        // where a trailing partial vector begins
+    if (row == 0 && (shift & 15u)) {
+        const uint64_t n = first_whole < end ? first_whole - shift : bytes;
+        if (lane < n) each((uint64_t)lane);
+    }
+    if ((end & 15u) && last_part >= first_whole && (last_part >> 10) == row) {
+        const uint32_t n = (uint32_t)end & 15u;
+        if (lane >= 16u && lane - 16u < n) each(last_part - shift + (lane - 16u));
+    }
 }
 
 template <class Item>
@@ -512,12 +517,20 @@ __device__ __forceinline__ bool dl_item_ragged(const Item &it)
     return __builtin_amdgcn_readfirstlane((dl_item_shift(it) | (uint32_t)it.bytes) & 15u) != 0;
 }
 
+// A lane of the row path whose 16 bytes begin at offset `byte` of an item of `bytes` bytes (an offset in front of
+// the item has wrapped below zero) has a whole vector inside the item.  ragged: see dl_item_ragged; without it
+// one compare decides.
+__device__ __forceinline__ bool dl_lane_whole(uint64_t byte, uint64_t bytes, bool ragged)
+{
+    return byte < bytes && (!ragged || bytes - byte >= 16u);
+}
+
 // Row path: the hot loop of large requests, kept to a few dozen instructions and two scalar round trips per
 // wavefront.  Rows are the 1 KiB rows of the grid of the item's first destination (see dl_tile_range; a tile
 // is (1 << wpg_log2) rows), and lane l of a row moves the 16 bytes at row * 1024 + 16 l - shift of the item:
-// one 16-byte load, then one store per destination.  No address needs any alignment.  The lanes under which
-// an item begins or ends in mid-vector (two per item at most, none if its first destination and its length are
-// multiples of 16) move their bytes one by one.
+// one 16-byte load, then one store per destination.  No address needs any alignment.  Where an item begins or
+// ends in mid-vector (its first destination or its length is not a multiple of 16: one scalar test), the
+// wavefront of that row moves those bytes one per lane (dl_row_edges).
 // The destinations of a fused item are stored by sub-group (established on the host): sub-group g owns slots
 // g * (DL_FAN >> split_log2) onwards, filled from the front, the rest null; slot 0 is the first destination.
 // Wavefront w of the workgroup belongs to sub-group w >> wpg_log2 and moves row w & (rows - 1) of the tile, to
@@ -544,20 +557,11 @@ __device__ __forceinline__ void dl_rows_body(const Item &it, uint32_t tile, uint
     uint32_t odd = 0;
     if constexpr (POL != DL_POL_COHERENT && !ON_GRID)
         odd = __builtin_amdgcn_readfirstlane(((uint32_t)(uint64_t)src - shift) & 3u);
-    uint64_t lo = 0, hi = 0;
     if constexpr (std::is_same<Item, dl_swap_item>::value) {
         char *pa = const_cast<char *>(src);
         char *pb = it.dst;
-        if (!ragged) {  // (a uniform branch in front of the common case, which stays as short as it was)
-            if (byte >= bytes) return;
-        } else {
-            const int part = dl_lane_part(byte, bytes, true, &lo, &hi);
-            if (part == 0) return;
-            if (part == 2) {
-                for (uint64_t i = lo; i < hi; ++i) dl_swap_byte<POL>(pa, pb, i);
-                return;
-            }
-        }
+        if (ragged) dl_row_edges(shift, bytes, row, lane, [&](uint64_t i) { dl_swap_byte<POL>(pa, pb, i); });
+        if (!dl_lane_whole(byte, bytes, ragged)) return;
         dl_u32x4 xy[2];
         const char *const from[2] = {pa + byte, pb + byte};
         dl_ld_many<POL, 2>(xy, from);
@@ -565,17 +569,11 @@ __device__ __forceinline__ void dl_rows_body(const Item &it, uint32_t tile, uint
         dl_st16<POL>(pb + byte, xy[0]);
     } else if constexpr (std::is_same<Item, dl_plain_item>::value) {
         char *dst = it.dst;
-        if (!ragged) {
-            if (byte >= bytes) return;
-        } else {
-            const int part = dl_lane_part(byte, bytes, true, &lo, &hi);
-            if (part == 0) return;
-            if (part == 2) {
-                char *const d[1] = {dst};
-                for (uint64_t i = lo; i < hi; ++i) dl_copy_byte<1, POL>(src, d, 1u, i);
-                return;
-            }
-        }
+        if (ragged)
+            dl_row_edges(shift, bytes, row, lane, [&](uint64_t i) {
+                dl_st<POL>(dl_global<uint8_t>(dst) + i, dl_ld<POL>(dl_global<uint8_t>(src) + i));
+            });
+        if (!dl_lane_whole(byte, bytes, ragged)) return;
         if (odd)
             dl_st16<POL>(dst + byte, dl_ld16_shifted<POL>(src + byte, odd));
         else
@@ -585,23 +583,17 @@ __device__ __forceinline__ void dl_rows_body(const Item &it, uint32_t tile, uint
         const uint32_t base = (wave >> wl) * slots;
         char *d0 = it.dst[base];
         char *d1 = slots > 1 ? it.dst[base + 1] : nullptr;
-        if (!ragged) {
-            if (byte >= bytes || !d0) return;
-        } else {
-            const int part = d0 ? dl_lane_part(byte, bytes, true, &lo, &hi) : 0;
-            if (part == 0) return;
-            if (part == 2) {
-                for (uint64_t i = lo; i < hi; ++i) {
-                    const uint8_t v = dl_ld<POL>(dl_global<uint8_t>(src) + i);
-                    for (uint32_t q = 0; q < slots; ++q) {
-                        char *dq = it.dst[base + q];
-                        if (!dq) break;
-                        dl_st<POL>(dl_global<uint8_t>(dq) + i, v);
-                    }
+        if (!d0) return;
+        if (ragged)
+            dl_row_edges(shift, bytes, row, lane, [&](uint64_t i) {
+                const uint8_t v = dl_ld<POL>(dl_global<uint8_t>(src) + i);
+                for (uint32_t q = 0; q < slots; ++q) {
+                    char *dq = it.dst[base + q];
+                    if (!dq) break;
+                    dl_st<POL>(dl_global<uint8_t>(dq) + i, v);
                 }
-                return;
-            }
-        }
+            });
+        if (!dl_lane_whole(byte, bytes, ragged)) return;
         dl_u32x4 v;
         if (odd)
             v = dl_ld16_shifted<POL>(src + byte, odd);
@@ -649,24 +641,37 @@ __device__ __forceinline__ void dl_run_rows_coherent(const dl_klist<Item, NMAX> 
     const char *const safe = p.item[d0].bytes >= 16u ? p.item[d0].src : (const char *)spare;
     uint32_t d[R];
     uint64_t byte[R];
-    int part[R];
+    bool whole[R];
     const char *from[R];
-    uint64_t lo = 0, hi = 0;
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const uint32_t b = b0 + (uint32_t)r * stride;
-        d[r] = d0;
+        d[r] = p.n;
         byte[r] = 0;
-        part[r] = 0;
+        whole[r] = false;
         from[r] = safe;
         if (b < total && b >= b0) {  // (b >= b0: no wrap-around)
             d[r] = dl_find_item(p, b, &first);
             if (d[r] < p.n) {
                 const Item &it = p.item[d[r]];
                 const uint64_t row = ((uint64_t)(b - first) << wl) + (wave & ((1u << wl) - 1u));
-                byte[r] = ((row << 10) - dl_item_shift(it)) + (lane << 4);
-                part[r] = dl_lane_part(byte[r], it.bytes, dl_item_ragged(it), &lo, &hi);
-                if (part[r] == 1) from[r] = it.src + byte[r];
+                const uint32_t shift = dl_item_shift(it);
+                byte[r] = ((row << 10) - shift) + (lane << 4);
+                whole[r] = dl_lane_whole(byte[r], it.bytes, dl_item_ragged(it));
+                if (whole[r]) from[r] = it.src + byte[r];
+                if (dl_item_ragged(it))  // the bytes in front of and behind the item's whole vectors
+                    dl_row_edges(shift, it.bytes, row, lane, [&](uint64_t i) {
+                        const uint8_t x = dl_ld<DL_POL_COHERENT>(dl_global<uint8_t>(it.src) + i);
+                        if constexpr (std::is_same<Item, dl_plain_item>::value) {
+                            dl_st<DL_POL_COHERENT>(dl_global<uint8_t>(it.dst) + i, x);
+                        } else {
+                            for (uint32_t q = 0; q < (uint32_t)DL_FAN; ++q) {
+                                char *dq = it.dst[q];  // filled from the front, the rest null
+                                if (!dq) break;
+                                dl_st<DL_POL_COHERENT>(dl_global<uint8_t>(dq) + i, x);
+                            }
+                        }
+                    });
             }
         }
     }
@@ -674,24 +679,8 @@ __device__ __forceinline__ void dl_run_rows_coherent(const dl_klist<Item, NMAX> 
     dl_ld_many<DL_POL_COHERENT, R>(v, from);
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-        if (part[r] == 0) continue;
+        if (!whole[r]) continue;
         const Item &it = p.item[d[r]];
-        if (part[r] == 2) {
-            (void)dl_lane_part(byte[r], it.bytes, true, &lo, &hi);
-            for (uint64_t i = lo; i < hi; ++i) {
-                const uint8_t x = dl_ld<DL_POL_COHERENT>(dl_global<uint8_t>(it.src) + i);
-                if constexpr (std::is_same<Item, dl_plain_item>::value) {
-                    dl_st<DL_POL_COHERENT>(dl_global<uint8_t>(it.dst) + i, x);
-                } else {
-                    for (uint32_t q = 0; q < (uint32_t)DL_FAN; ++q) {
-                        char *dq = it.dst[q];  // filled from the front, the rest null
-                        if (!dq) break;
-                        dl_st<DL_POL_COHERENT>(dl_global<uint8_t>(dq) + i, x);
-                    }
-                }
-            }
-            continue;
-        }
         if constexpr (std::is_same<Item, dl_plain_item>::value) {
             dl_st16<DL_POL_COHERENT>(it.dst + byte[r], v[r]);
         } else {
