@@ -11,8 +11,9 @@
  *    by the caller.  The library never allocates, frees or keeps them.
  *  - Pointer arrays, descriptor arrays and chunk_bytes are HOST arrays.  They
  *    are fully consumed before the call returns.
- *  - Any byte count and any alignment gives the result memcpy would give;
- *    buffers whose addresses agree modulo 16 take the 16-byte vector path.
+ *  - Any byte count and any alignment gives the result memcpy would give, and
+ *    all of them move as 16-byte vectors (work is cut on the 128-byte lines
+ *    of each copy's first destination; sources may stand anywhere).
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *  - Calls only enqueue work.  In one-shot mode the result is complete when
  *    the stream reaches the end of the enqueued kernel.  In prelaunch mode the
@@ -431,7 +432,7 @@ typedef struct dl_config {
     uint32_t max_blocks;         /* cap on the one-shot grid; workgroups then stride over the tiles; 0 = one workgroup per tile */
     uint32_t fan_split;          /* sub-groups of a workgroup that share out the destinations of a fused copy: 1, 2 or 4; 0 = choose */
     uint32_t infer_broadcast;    /* 1: dl_batch_copy merges copies that share source and size into read-once/write-k copies; default 1 */
-    uint32_t device_lowering;    /* 1: dl_token_dispatch with 512 tokens or more (W = 8, aligned rows, one-shot mode, validation off) sends only the mask to the device, which derives the copies itself; default 1 */
+    uint32_t device_lowering;    /* 1: dl_token_dispatch with 512 tokens or more (W = 8, one-shot mode, validation off) sends only the mask to the device, which derives the copies itself; default 1 */
     uint32_t table_push;         /* 1: the table of a long list (more copies than fit the kernel arguments) is written by the host straight into device memory, through the BAR, when the device exposes one that covers its memory and the table is short enough; 0: always through pinned host memory; default 1 */
     uint64_t write_through_max_bytes; /* requests moving at most this many bytes (read + written) use write-through stores; default 144 MiB */
     uint64_t stream_plain_min_bytes;  /* lists of plain 1:1 copies (all-to-all, batches) moving at least this many bytes use streaming loads/stores: nothing of such a request fits the on-die caches, and keeping it out of them measured 3-6 % faster; default 512 MiB; UINT64_MAX = never */
