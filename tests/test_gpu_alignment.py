@@ -78,12 +78,10 @@ def arena_for(ncase, ranges_per_case, seed):
     return rng.integers(0, 256, size=ncase * ranges_per_case * SLOT, dtype=np.uint8)
 
 
-@pytest.mark.parametrize("mode", list(MODES))
-@pytest.mark.parametrize("per_call", [1, 8, 40, 500])
+@pytest.mark.parametrize("mode,per_call", [(m, n) for n in (1, 8, 40, 500) for m in MODES if n > 1 or m == "oneshot"])
 def test_plain_copies_at_every_shift(ref, mode, per_call):
-    """per_call copies per request: 1 and 8 take the row path, 40 the longer argument list, 500 a table."""
-    if mode != "oneshot" and per_call == 1:
-        pytest.skip("one copy per request is covered one-shot; the other modes take the lists")
+    """per_call copies per request: 1 (one-shot only) and 8 take the row path, 40 the longer argument list, 500 a
+    table."""
     cs = cases(4096, [0, 1, 5, 16, 77, 128])
     if per_call == 1:
         cs = cs[::7]
