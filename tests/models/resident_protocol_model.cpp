@@ -229,7 +229,7 @@ int run(bool reset_late, uint32_t requests, uint32_t blocks, uint32_t seed, bool
     for (auto &r : h.ready) r = 0;
     d.go = 0, d.arrive = 0;
     std::memset(out, 0, sizeof out);
-    const limits lim{quit_at_end ? (1ull << 40) : 400000ull, 4000000ull};
+    const limits lim{quit_at_end ? (1ull << 40) : 2000000ull, 8000000ull};
     std::vector<std::thread> th;
     th.emplace_back(leader, std::ref(h), std::ref(d), lim, reset_late, seed * 7919u + 1u);
     for (uint32_t b = 1; b < blocks; ++b) th.emplace_back(worker, std::ref(d), b, lim, seed * 7919u + 1u + b);
