@@ -395,8 +395,8 @@ def other_operations(dl, benchaid, inputs, torch, stream, ag_reqs, ag_bufs, ag_s
     n = 16 * MiB - 32
     s_in = [torch.empty(n + 256, dtype=torch.uint8, device="cuda").random_(0, 256) for _ in range(W)]
     s_out = [torch.empty(W * n + 256, dtype=torch.uint8, device="cuda") for _ in range(W)]
-    # (fresh buffers, and the device has idled while they were filled: 40 untimed calls first, or the first rows read 8 % low)
-    benchaid.time_device(benchaid.allgather_request(s_in, s_out, n), stream, warmup=40, calls=1)
+    # (fresh buffers, and the device has idled while they were filled: 150 untimed calls, 30 ms, first, or the first rows read 8 % low)
+    benchaid.time_device(benchaid.allgather_request(s_in, s_out, n), stream, warmup=150, calls=1)
     for so, do in ((0, 0), (4, 0), (1, 0), (0, 1), (5, 2), (0, 16)):
         req = benchaid.allgather_request([t[so:] for t in s_in], [t[do:] for t in s_out], n)
         row = {"op": "allgather", "bytes_per_rank": n, "send_shift": so, "recv_shift": do}
@@ -617,6 +617,33 @@ def armed_case(args, dl, benchaid, inputs, torch, stream) -> int:
     return 0
 
 
+def off_grid_case(args, dl, benchaid, torch, stream) -> int:
+    """Only requests that stand on no grid: all-gathers of 16 MiB - 32 bytes per rank (every rank's share of a receive
+    buffer off the 128-byte lines) with send / receive buffers moved by 0, 4, 1 bytes, and 64 copies of 4 MiB - 32
+    bytes with the source or the destination moved by one byte; --steps launches each: for kernel traces."""
+    n = 16 * MiB - 32
+    s_in = [torch.empty(n + 256, dtype=torch.uint8, device="cuda").random_(0, 256) for _ in range(W)]
+    s_out = [torch.empty(W * n + 256, dtype=torch.uint8, device="cuda") for _ in range(W)]
+    m = 4 * MiB - 32
+    c_in = [torch.empty(m + 256, dtype=torch.uint8, device="cuda").random_(0, 256) for _ in range(64)]
+    c_out = [torch.empty(m + 256, dtype=torch.uint8, device="cuda") for _ in range(64)]
+    reqs = [("allgather send+%d recv+%d" % (so, do),
+             benchaid.allgather_request([t[so:] for t in s_in], [t[do:] for t in s_out], n))
+            for so, do in ((0, 0), (4, 0), (1, 0), (0, 1), (0, 16))]
+    reqs += [("batch_copy src+%d dst+%d" % (so, do),
+              benchaid.copy_list_request([(x[so:], y[do:], m) for x, y in zip(c_in, c_out)], benchaid.OP_BATCH))
+             for so, do in ((0, 0), (1, 0), (0, 1))]
+    rows = []
+    benchaid.time_device(reqs[0][1], stream, warmup=150, calls=1)   # 30 ms of work: clocks up, buffers touched
+    for name, req in reqs:
+        us = benchaid.time_device(req, stream, warmup=max(args.warmup, 20), calls=args.steps)
+        rows.append({"request": name, "device_us": us})
+    dl.dl_shutdown()
+    print(json.dumps({"case": "off_grid", "launches_per_request": max(args.warmup, 20) + args.steps,
+                      "allgather_bytes_per_rank": n, "copy_bytes": m, "rows": rows}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -627,12 +654,13 @@ def main() -> int:
     ap.add_argument("--no-detail", action="store_true", help="skip per-size latency and comparison legs")
     ap.add_argument("--detail-file", default=os.path.join(ROOT, "gpurun_out", "bench_detail.json"),
                     help="where the per-size latency and comparison rows go (the printed line stays short)")
-    ap.add_argument("--case", choices=["sweep", "pmc", "token_dispatch", "alltoall", "armed"], default="sweep",
+    ap.add_argument("--case", choices=["sweep", "pmc", "token_dispatch", "alltoall", "armed", "off_grid"], default="sweep",
                     help="pmc: only --steps launches of the largest all-gather and of a plain 1 GiB copy "
                          "(the calibration kernel), for hardware-counter runs; token_dispatch: only the "
                          "token-granular MoE dispatch, for kernel traces; armed: all-gathers of 4 KiB .. 4 MiB per "
                          "rank armed, triggered and waited for (prelaunch), then in signal and standby mode, for "
-                         "kernel traces of the waiting kernels")
+                         "kernel traces of the waiting kernels; off_grid: only all-gathers and copies whose buffers and "
+                         "lengths stand on no grid, for kernel traces")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this library runs on one GPU (W virtual ranks share its HBM); --gpus must be 1",
@@ -672,6 +700,8 @@ def main() -> int:
         return alltoall_case(args, dl, benchaid, inputs, torch, stream)
     if args.case == "armed":
         return armed_case(args, dl, benchaid, inputs, torch, stream)
+    if args.case == "off_grid":
+        return off_grid_case(args, dl, benchaid, torch, stream)
 
     sizes = [B for B in (4 * KiB << i for i in range(15)) if B <= args.max_bytes]
     reqs, keep, check = {}, [], None
