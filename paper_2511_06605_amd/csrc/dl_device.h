@@ -141,6 +141,29 @@ __device__ __forceinline__ dl_u32x4 dl_ld16_shifted(const char *p, uint32_t odd)
     return v;
 }
 
+// The same for a lane of the row path, where lane l + 1 loads the 16 bytes that follow lane l's: the fifth word is
+// the next lane's first one, taken across lanes (a DPP move that shifts the wavefront by one lane) instead of from
+// memory.  own_fifth: this lane has no such neighbour (lane 63, or the next lane loads nothing) and fetches the word
+// itself, in flight together with the other four.  Every lane of the row that loads calls this together.
+// (All-gather of 64 MiB per rank from sources one byte off: unaligned 16-byte loads 4.2 TB/s, five words per lane
+// 4.7, this 5.6; aligned sources 6.0.)
+template <int POL>
+__device__ __forceinline__ dl_u32x4 dl_ld16_shifted_row(const char *p, uint32_t odd, bool own_fifth)
+{
+    const dl_u32x4 w = dl_ld16<POL>(p - odd);
+    uint32_t mine = 0;
+    if (own_fifth) mine = dl_ld<POL>(dl_global<uint32_t>(p - odd + 16));
+    constexpr int WAVE_SHL1 = 0x130;  // lane l receives lane l + 1's value; lane 63 keeps the first operand
+    uint32_t w4 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w.x, WAVE_SHL1, 0xf, 0xf, false);
+    if (own_fifth) w4 = mine;
+    dl_u32x4 v;
+    v.x = __builtin_amdgcn_alignbyte(w.y, w.x, odd);
+    v.y = __builtin_amdgcn_alignbyte(w.z, w.y, odd);
+    v.z = __builtin_amdgcn_alignbyte(w.w, w.z, odd);
+    v.w = __builtin_amdgcn_alignbyte(w4, w.w, odd);
+    return v;
+}
+
 // One byte from src + i to the same offset of the first k destinations.
 template <int FAN, int POL>
 __device__ __forceinline__ void dl_copy_byte(const char *src, char *const (&dsts)[FAN], uint32_t k, uint64_t i)
@@ -517,12 +540,26 @@ __device__ __forceinline__ bool dl_item_ragged(const Item &it)
     return __builtin_amdgcn_readfirstlane((dl_item_shift(it) | (uint32_t)it.bytes) & 15u) != 0;
 }
 
-// A lane of the row path whose 16 bytes begin at offset `byte` of an item of `bytes` bytes (an offset in front of
-// the item has wrapped below zero) has a whole vector inside the item.  ragged: see dl_item_ragged; without it
-// one compare decides.
-__device__ __forceinline__ bool dl_lane_whole(uint64_t byte, uint64_t bytes, bool ragged)
+// How a row lies in its item, for the lanes' question "are my 16 bytes wholly inside?".  The answer costs vector
+// compares only where it has to: in an item that is not ragged (see dl_item_ragged) one compare per lane decides; in a
+// ragged one every lane of a row between the item's first and last row is inside, and only those two rows look
+// closely (and have bytes to move singly, see dl_row_edges).
+enum : uint32_t { DL_ROW_PLAIN = 0, DL_ROW_INNER = 1, DL_ROW_EDGE = 2, DL_ROW_NONE = 3 };
+
+__device__ __forceinline__ uint32_t dl_row_kind(bool ragged, uint32_t shift, uint64_t bytes, uint64_t row)
 {
-    return byte < bytes && (!ragged || bytes - byte >= 16u);
+    if (!ragged) return DL_ROW_PLAIN;
+    const uint64_t last = (shift + bytes - 1u) >> 10;  // (bytes >= 1: empty items have no tiles)
+    return row > last ? DL_ROW_NONE : (row == 0 || row == last) ? DL_ROW_EDGE : DL_ROW_INNER;
+}
+
+// A lane whose 16 bytes begin at offset `byte` of an item of `bytes` bytes (an offset in front of the item has
+// wrapped below zero) has a whole vector inside the item.  kind: the row's, uniform.
+__device__ __forceinline__ bool dl_lane_whole(uint64_t byte, uint64_t bytes, uint32_t kind)
+{
+    if (kind == DL_ROW_INNER) return true;
+    if (kind == DL_ROW_PLAIN) return byte < bytes;
+    return kind == DL_ROW_EDGE && byte < bytes && bytes - byte >= 16u;
 }
 
 // Row path: the hot loop of large requests, kept to a few dozen instructions and two scalar round trips per
@@ -551,6 +588,7 @@ __device__ __forceinline__ void dl_rows_body(const Item &it, uint32_t tile, uint
     const uint64_t bytes = it.bytes;
     const bool ragged = ON_GRID ? false : dl_item_ragged(it);
     const uint32_t shift = ON_GRID ? 0u : dl_item_shift(it);
+    const uint32_t kind = ON_GRID ? (uint32_t)DL_ROW_PLAIN : dl_row_kind(ragged, shift, bytes, row);
     const uint64_t byte = ((row << 10) - shift) + (lane << 4);
     // every lane's source address is the same modulo 4: not zero -> dl_ld16_shifted (not at system scope, and not
     // for swaps, which load both sides)
@@ -560,8 +598,8 @@ __device__ __forceinline__ void dl_rows_body(const Item &it, uint32_t tile, uint
     if constexpr (std::is_same<Item, dl_swap_item>::value) {
         char *pa = const_cast<char *>(src);
         char *pb = it.dst;
-        if (ragged) dl_row_edges(shift, bytes, row, lane, [&](uint64_t i) { dl_swap_byte<POL>(pa, pb, i); });
-        if (!dl_lane_whole(byte, bytes, ragged)) return;
+        if (kind == DL_ROW_EDGE) dl_row_edges(shift, bytes, row, lane, [&](uint64_t i) { dl_swap_byte<POL>(pa, pb, i); });
+        if (!dl_lane_whole(byte, bytes, kind)) return;
         dl_u32x4 xy[2];
         const char *const from[2] = {pa + byte, pb + byte};
         dl_ld_many<POL, 2>(xy, from);
@@ -569,13 +607,13 @@ __device__ __forceinline__ void dl_rows_body(const Item &it, uint32_t tile, uint
         dl_st16<POL>(pb + byte, xy[0]);
     } else if constexpr (std::is_same<Item, dl_plain_item>::value) {
         char *dst = it.dst;
-        if (ragged)
+        if (kind == DL_ROW_EDGE)
             dl_row_edges(shift, bytes, row, lane, [&](uint64_t i) {
                 dl_st<POL>(dl_global<uint8_t>(dst) + i, dl_ld<POL>(dl_global<uint8_t>(src) + i));
             });
-        if (!dl_lane_whole(byte, bytes, ragged)) return;
+        if (!dl_lane_whole(byte, bytes, kind)) return;
         if (odd)
-            dl_st16<POL>(dst + byte, dl_ld16_shifted<POL>(src + byte, odd));
+            dl_st16<POL>(dst + byte, dl_ld16_shifted_row<POL>(src + byte, odd, lane == 63u || !dl_lane_whole(byte + 16u, bytes, kind)));
         else
             dl_st16<POL>(dst + byte, dl_ld16<POL>(src + byte));
     } else {
@@ -584,7 +622,7 @@ __device__ __forceinline__ void dl_rows_body(const Item &it, uint32_t tile, uint
         char *d0 = it.dst[base];
         char *d1 = slots > 1 ? it.dst[base + 1] : nullptr;
         if (!d0) return;
-        if (ragged)
+        if (kind == DL_ROW_EDGE)
             dl_row_edges(shift, bytes, row, lane, [&](uint64_t i) {
                 const uint8_t v = dl_ld<POL>(dl_global<uint8_t>(src) + i);
                 for (uint32_t q = 0; q < slots; ++q) {
@@ -593,10 +631,10 @@ __device__ __forceinline__ void dl_rows_body(const Item &it, uint32_t tile, uint
                     dl_st<POL>(dl_global<uint8_t>(dq) + i, v);
                 }
             });
-        if (!dl_lane_whole(byte, bytes, ragged)) return;
+        if (!dl_lane_whole(byte, bytes, kind)) return;
         dl_u32x4 v;
         if (odd)
-            v = dl_ld16_shifted<POL>(src + byte, odd);
+            v = dl_ld16_shifted_row<POL>(src + byte, odd, lane == 63u || !dl_lane_whole(byte + 16u, bytes, kind));
         else
             v = dl_ld16<POL>(src + byte);
         dl_st16<POL>(d0 + byte, v);
@@ -657,9 +695,10 @@ __device__ __forceinline__ void dl_run_rows_coherent(const dl_klist<Item, NMAX> 
                 const uint64_t row = ((uint64_t)(b - first) << wl) + (wave & ((1u << wl) - 1u));
                 const uint32_t shift = dl_item_shift(it);
                 byte[r] = ((row << 10) - shift) + (lane << 4);
-                whole[r] = dl_lane_whole(byte[r], it.bytes, dl_item_ragged(it));
+                const uint32_t kind = dl_row_kind(dl_item_ragged(it), shift, it.bytes, row);
+                whole[r] = dl_lane_whole(byte[r], it.bytes, kind);
                 if (whole[r]) from[r] = it.src + byte[r];
-                if (dl_item_ragged(it))  // the bytes in front of and behind the item's whole vectors
+                if (kind == DL_ROW_EDGE)  // the bytes in front of and behind the item's whole vectors
                     dl_row_edges(shift, it.bytes, row, lane, [&](uint64_t i) {
                         const uint8_t x = dl_ld<DL_POL_COHERENT>(dl_global<uint8_t>(it.src) + i);
                         if constexpr (std::is_same<Item, dl_plain_item>::value) {
