@@ -62,23 +62,22 @@ __device__ __forceinline__ const Item *dl_pushed_entry(const Item *items, uint32
 }
 
 // Row path over a table of equally sized items in device memory (long lists: thousands of token
-// rows, hundreds of cache blocks): workgroup b works on item b / tiles_per_item, which every
-// workgroup of that item finds in the scalar cache.  PUSHED: see dl_pushed_entry.
+// rows, hundreds of cache blocks) on a two-dimensional grid: blockIdx.y is the item (at most DL_UROWS_MAX_ITEMS,
+// the grid's limit in that dimension), which every workgroup of that item finds in the scalar cache, blockIdx.x
+// the tile within it; nothing is divided.  PUSHED: see dl_pushed_entry.
 template <class Item, int POL, bool PUSHED, bool ON_GRID>
-__global__ void __launch_bounds__(512) dl_exec_urows_kernel(const Item *__restrict__ items, uint32_t n,
-                                                            uint32_t tiles_per_item, uint32_t wpg_log2,
+__global__ void __launch_bounds__(512) dl_exec_urows_kernel(const Item *__restrict__ items, uint32_t wpg_log2,
                                                             uint32_t split_log2, const dl_pushed ps)
 {
-    const uint32_t d = blockIdx.x / tiles_per_item;
-    if (d >= n) return;
+    const uint32_t d = blockIdx.y;
     if constexpr (PUSHED) {
         const Item *it = dl_pushed_entry(items, d, ps);
         if (it)
-            dl_rows_body<POL, ON_GRID>(*it, blockIdx.x - d * tiles_per_item, wpg_log2, split_log2);
+            dl_rows_body<POL, ON_GRID>(*it, blockIdx.x, wpg_log2, split_log2);
         else if (threadIdx.x == 0)
             dl_pushed_report_lost(ps);  // nothing copied by this workgroup; the host hears of it
     } else
-        dl_rows_body<POL, ON_GRID>(items[d], blockIdx.x - d * tiles_per_item, wpg_log2, split_log2);
+        dl_rows_body<POL, ON_GRID>(items[d], blockIdx.x, wpg_log2, split_log2);
 }
 
 // General path: any tile size, one workgroup per tile.
@@ -466,6 +465,7 @@ template <> struct list_cap<dl_plain_item> { static constexpr int big = 64; };
 template <> struct list_cap<dl_swap_item> { static constexpr int big = 64; };
 template <> struct list_cap<dl_fused_item> { static constexpr int big = 32; };
 
+constexpr uint32_t DL_UROWS_MAX_ITEMS = 65535;    // a grid's second dimension goes no further
 constexpr uint64_t TABLE_ENTRIES_TARGET = 8192;  // table kernels: aim for at most this many one-tile entries
 constexpr uint64_t UNIFORM_ROWS_MIN_BYTES = 4ull << 20;  // source bytes from which a uniform long list takes the row kernel
 constexpr size_t TABLE_STAGE_MIN = 512;          // tables at least this long are staged in device memory first
@@ -790,7 +790,7 @@ bool launch_uniform_rows(const Item *items, size_t n, const dl_launch_shape &sh,
         if (t > tpi) tpi = t;
         on_grid = on_grid && item_on_grid(items[i]);
     }
-    if (tpi * n >= (1ull << 30)) return false;
+    if (tpi * n >= (1ull << 30) || tpi >= (1ull << 31) || n > DL_UROWS_MAX_ITEMS) return false;
 
     char *pushed = push_acquire(n * sizeof(Item), stream, rc);
     if (*rc != DL_OK) return true;
@@ -826,11 +826,11 @@ bool launch_uniform_rows(const Item *items, size_t n, const dl_launch_shape &sh,
     with_policy_and_grid(sh.policy, on_grid, [&](auto pol, auto og) {
         if (pushed)
             hipLaunchKernelGGL((dl_exec_urows_kernel<Item, decltype(pol)::value, true, decltype(og)::value>),
-                               dim3((uint32_t)(tpi * n)), dim3(threads), 0, stream, dslot, (uint32_t)n, (uint32_t)tpi,
+                               dim3((uint32_t)tpi, (uint32_t)n), dim3(threads), 0, stream, dslot,
                                log2u(threads / 64u / split), log2u(split), ps);
         else
             hipLaunchKernelGGL((dl_exec_urows_kernel<Item, decltype(pol)::value, false, decltype(og)::value>),
-                               dim3((uint32_t)(tpi * n)), dim3(threads), 0, stream, dslot, (uint32_t)n, (uint32_t)tpi,
+                               dim3((uint32_t)tpi, (uint32_t)n), dim3(threads), 0, stream, dslot,
                                log2u(threads / 64u / split), log2u(split), ps);
     });
     hipError_t e = hipGetLastError();
@@ -1198,12 +1198,12 @@ int dl_launch_fused_rows_table(const dl_fused_item *dev_items, uint32_t n, uint6
     // the table's destinations are laid out for DL_TABLE_ROWS_SPLIT sub-groups (see slots_by_subgroup)
     const uint32_t split = DL_TABLE_ROWS_SPLIT, threads = DL_TABLE_ROWS_THREADS, tile = 16u * threads / split;
     const uint64_t tpi = (item_bytes + max_shift + tile - 1) / tile;
-    if (n == 0 || max_shift >= DL_CUT || tpi * n >= (1ull << 30)) return DL_ERR_INVALID;
+    if (n == 0 || n > DL_UROWS_MAX_ITEMS || max_shift >= DL_CUT || tpi * n >= (1ull << 30)) return DL_ERR_INVALID;
     const dl_launch_shape sh = dl_choose_shape((uint64_t)n * item_bytes, item_bytes, 8);
     with_policy_and_grid(sh.policy, on_grid && max_shift == 0, [&](auto pol, auto og) {
         hipLaunchKernelGGL((dl_exec_urows_kernel<dl_fused_item, decltype(pol)::value, false, decltype(og)::value>),
-                           dim3((uint32_t)(tpi * n)), dim3(threads), 0, stream, dev_items, n, (uint32_t)tpi,
-                           log2u(threads / 64u / split), log2u(split), dl_push_kernel_args(0));
+                           dim3((uint32_t)tpi, n), dim3(threads), 0, stream, dev_items, log2u(threads / 64u / split),
+                           log2u(split), dl_push_kernel_args(0));
     });
     DL_HIP(hipGetLastError());
     return DL_OK;
