@@ -468,6 +468,7 @@ template <> struct list_cap<dl_fused_item> { static constexpr int big = 32; };
 constexpr uint32_t DL_UROWS_MAX_ITEMS = 65535;    // a grid's second dimension goes no further
 constexpr uint64_t TABLE_ENTRIES_TARGET = 8192;  // table kernels: aim for at most this many one-tile entries
 constexpr uint64_t UNIFORM_ROWS_MIN_BYTES = 4ull << 20;  // source bytes from which a uniform long list takes the row kernel
+constexpr uint64_t UNIFORM_ROWS_STAGE_BYTES = 768ull << 20;  // bytes moved (read + written) from which its table is staged even where it could be pushed
 constexpr size_t TABLE_STAGE_MIN = 512;          // tables at least this long are staged in device memory first
 constexpr size_t RING_SLOTS = 4;
 constexpr size_t RING_SLOT_BYTES = DL_RING_SLOT_BYTES;
@@ -779,8 +780,12 @@ bool launch_uniform_rows(const Item *items, size_t n, const dl_launch_shape &sh,
         if (items[i].bytes != bytes) return false;
         if (item_k(items[i]) > kmax) kmax = item_k(items[i]);
     }
-    // a table that needs staging must move enough bytes to pay for it; one written through the BAR needs none
-    const bool pushable = g_ring.push && c.table_push && n * sizeof(Item) <= PUSH_PAYLOAD_BYTES;
+    // a table that needs staging must move enough bytes to pay for it; one written through the BAR needs none.
+    // But every workgroup that reads a pushed table looks for the stamp and fetches its entry past the caches, two
+    // round trips that cost a large request 12 % of its kernel time, against 4 us for the staging kernel and the
+    // gap behind it: from UNIFORM_ROWS_STAGE_BYTES moved, the table is staged (256 copies of 4 MiB: 368 -> 345 us).
+    const bool pushable = g_ring.push && c.table_push && n * sizeof(Item) <= PUSH_PAYLOAD_BYTES &&
+                          bytes * n * (1u + kmax) < UNIFORM_ROWS_STAGE_BYTES;
     if (!pushable && bytes * n < UNIFORM_ROWS_MIN_BYTES) return false;
     const uint32_t tile = 16u * threads / split;  // one 1 KiB row per wavefront of a sub-group
     uint64_t tpi = 0;  // of the item that lies worst on its grid; the others leave a workgroup without work
@@ -792,7 +797,7 @@ bool launch_uniform_rows(const Item *items, size_t n, const dl_launch_shape &sh,
     }
     if (tpi * n >= (1ull << 30) || tpi >= (1ull << 31) || n > DL_UROWS_MAX_ITEMS) return false;
 
-    char *pushed = push_acquire(n * sizeof(Item), stream, rc);
+    char *pushed = pushable ? push_acquire(n * sizeof(Item), stream, rc) : nullptr;
     if (*rc != DL_OK) return true;
     size_t s = 0;
     *rc = DL_ERR_HIP;
