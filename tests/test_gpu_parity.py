@@ -506,10 +506,12 @@ def test_batch_copy_with_and_without_broadcast_inference(ref, cfg, infer):
     assert np.array_equal(extra_dst.host(), extra_src.host()) and extra_dst.guards_intact()
 
 
-@pytest.mark.parametrize("n,nb", [(9, 8 * MiB), (64, 1 * MiB), (65, 1 * MiB), (200, 512 * KiB), (70, 100 * KiB)])
+@pytest.mark.parametrize("n,nb", [(9, 8 * MiB), (64, 1 * MiB), (65, 1 * MiB), (200, 512 * KiB), (70, 100 * KiB),
+                                  (100, 4 * MiB)])
 def test_long_lists_of_equal_large_copies(ref, n, nb):
-    """Lists of equal, aligned, large copies: up to 64 of them travel in the kernel arguments (general path),
-    longer lists take the row kernel over a table staged in device memory; every byte of the arena is compared."""
+    """Lists of equal, aligned, large copies: up to 64 of them travel in the kernel arguments, longer lists take the
+    row kernel over a table in device memory (written there by the host, or, when the request moves 768 MiB or more
+    as the last case does, staged by a kernel in front); every byte of the arena is compared."""
     run_batch(ref, n, nb, 2 * n * nb + 64 * MiB, seed=n, align=4096)
 
 
