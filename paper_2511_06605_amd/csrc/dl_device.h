@@ -590,7 +590,7 @@ __device__ __forceinline__ void dl_rows_body(const Item &it, uint32_t tile, uint
     const uint32_t shift = ON_GRID ? 0u : dl_item_shift(it);
     const uint32_t kind = ON_GRID ? (uint32_t)DL_ROW_PLAIN : dl_row_kind(ragged, shift, bytes, row);
     const uint64_t byte = ((row << 10) - shift) + (lane << 4);
-    // every lane's source address is the same modulo 4: not zero -> dl_ld16_shifted (not at system scope, and not
+    // every lane's source address is the same modulo 4: not zero -> dl_ld16_shifted_row (not at system scope, and not
     // for swaps, which load both sides)
     uint32_t odd = 0;
     if constexpr (POL != DL_POL_COHERENT && !ON_GRID)
